@@ -1,0 +1,270 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+Each test names what fixes the expected value: the ring identity
+e^T(AB) = (e^T A)B, brute force over all single-bit flips, closed forms,
+numpy's int64/float64 matmul and sums as a textbook routine, linearity of the
+check in an injected delta, and library conversions for the roundings.
+"""
+import numpy as np
+import pytest
+import torch
+
+import abft_inputs as gen
+import oracle as orc
+
+pytestmark = []
+
+
+def _int_case(M, N, K, trans_b, seed):
+    A, B = gen.gen_operands("i8", M, N, K, seed, seed + 1, trans_b=trans_b)
+    return A[0], B[0]
+
+
+# ---------------------------------------------------------------- P4: numpy cross-check
+@pytest.mark.parametrize("M,N,K,trans_b", [(5, 7, 3, True), (5, 7, 3, False), (33, 17, 65, True),
+                                           (64, 48, 32, False), (197, 96, 128, True)])
+def test_gemm_i8_matches_numpy_int64(M, N, K, trans_b):
+    A, B = _int_case(M, N, K, trans_b, 11)
+    Bl = B.T if trans_b else B                      # logical K x N
+    want = A.astype(np.int64) @ Bl.astype(np.int64)
+    got = orc.gemm(A, B, trans_b)
+    assert got.dtype == np.int64 and np.array_equal(got, want)
+    a, b = orc.encode(A, B, trans_b)
+    assert np.array_equal(a, A.astype(np.int64).sum(axis=0))
+    assert np.array_equal(b, Bl.astype(np.int64).sum(axis=1))
+    cc, rc, s = orc.predict(A, B, a, b, trans_b)
+    assert np.array_equal(cc, a @ Bl.astype(np.int64))
+    assert np.array_equal(rc, A.astype(np.int64) @ b)
+    assert s == int(a @ b)
+    co, ro, so = orc.observe(want)
+    assert np.array_equal(co, want.sum(axis=0)) and np.array_equal(ro, want.sum(axis=1)) and so == want.sum()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("trans_b", [True, False])
+def test_gemm_fp_matches_numpy_float64(dtype, trans_b):
+    M, N, K = 37, 29, 83
+    A, B = gen.gen_operands(dtype, M, N, K, 5, 6, trans_b=trans_b)
+    Ad, Bd = orc.decode(A[0], dtype), orc.decode(B[0], dtype)
+    Bl = Bd.T if trans_b else Bd
+    want = Ad @ Bl
+    got = orc.gemm(Ad, Bd, trans_b)
+    assert np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
+    a, b = orc.encode(Ad, Bd, trans_b)
+    np.testing.assert_allclose(a, Ad.sum(axis=0), rtol=0, atol=1e-12 * M)
+    np.testing.assert_allclose(b, Bl.sum(axis=1), rtol=0, atol=1e-12 * N)
+    cc, rc, s = orc.predict(Ad, Bd, a, b, trans_b)
+    np.testing.assert_allclose(cc, a @ Bl, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(rc, Ad @ b, rtol=1e-12, atol=1e-12)
+    assert abs(s - a @ b) <= 1e-12 * max(1.0, abs(s))
+
+
+# ---------------------------------------------------------------- P1 + P6: integer identity
+@pytest.mark.parametrize("M,N,K,trans_b", [(1, 1, 1, True), (3, 4, 5, False), (16, 16, 16, True),
+                                           (197, 768, 768, True), (70, 130, 257, False)])
+def test_integer_identity_exact_and_in_ring(M, N, K, trans_b):
+    A, B = _int_case(M, N, K, trans_b, 1000 + M)
+    P = orc.protected_gemm(A, B, "i8", trans_b)
+    cc_obs, rc_obs, s_obs = orc.observe(P.C_ref)
+    assert np.array_equal(cc_obs, P.cc_pred) and np.array_equal(rc_obs, P.rc_pred)
+    assert s_obs == P.s_pred == P.cc_pred.sum() == P.rc_pred.sum()
+    rf, cf, E, status, _, _ = orc.check(P, P.C_stored)
+    assert not rf.any() and not cf.any() and E == [] and status == orc.CLEAN
+
+
+def test_integer_identity_holds_through_wraparound():
+    # all operands -128: C = K * 2^14; column sums M*K*2^14 exceed 2^32 but the
+    # ring identity (and the exact one in int64) still hold.
+    M, N, K = 36928, 2, 4096
+    A = np.full((M, K), -128, dtype=np.int8)
+    B = np.full((N, K), -128, dtype=np.int8)
+    P = orc.protected_gemm(A, B, "i8", True)
+    assert np.all(P.C_ref == 2 ** 26)
+    assert P.cc_pred[0] == M * 2 ** 26 and P.cc_pred[0] >= 2 ** 32
+    assert np.all(P.a == -128 * M) and np.all(P.b == -128 * N)
+    rf, cf, E, status, cc_obs, _ = orc.check(P, P.C_stored)
+    assert status == orc.CLEAN and not rf.any() and not cf.any()
+    # a wrapped 32-bit sum of the stored int32 values equals the wrapped prediction
+    wrapped = int(P.C_stored.astype(np.int64)[:, 0].sum() % 2 ** 32)
+    assert wrapped == int(P.cc_pred[0] % 2 ** 32)
+
+
+# ---------------------------------------------------------------- P3: closed forms
+def test_closed_forms():
+    M, N, K = 6, 9, 4
+    one = np.ones((M, K), dtype=np.int8)
+    Bt = np.ones((N, K), dtype=np.int8)
+    P = orc.protected_gemm(one, Bt, "i8", True)
+    assert np.all(P.C_ref == K) and np.all(P.cc_pred == M * K) and np.all(P.rc_pred == N * K)
+    assert P.s_pred == M * N * K
+    # B = identity: C = A, cc = e^T A, rc = A e  (both storage orders of B)
+    A = gen.gen_int8((7, 5), 3)
+    I = np.eye(5, dtype=np.int8)
+    for tb in (True, False):
+        P = orc.protected_gemm(A, I, "i8", tb)
+        assert np.array_equal(P.C_ref, A.astype(np.int64))
+        assert np.array_equal(P.cc_pred, A.astype(np.int64).sum(0))
+        assert np.array_equal(P.rc_pred, A.astype(np.int64).sum(1))
+    # a single non-zero of A at (2, 3) selects row 3 of logical B into row 2 of C
+    A1 = np.zeros((4, 6), dtype=np.int8)
+    A1[2, 3] = 5
+    Bk = gen.gen_int8((6, 8), 4)              # stored K x N
+    P = orc.protected_gemm(A1, Bk, "i8", False)
+    want = np.zeros((4, 8), dtype=np.int64)
+    want[2] = 5 * Bk[3].astype(np.int64)
+    assert np.array_equal(P.C_ref, want)
+    # transposed storage of the same logical B gives the same product
+    P2 = orc.protected_gemm(A1, np.ascontiguousarray(Bk.T), "i8", True)
+    assert np.array_equal(P2.C_ref, want)
+
+
+def test_softmax_times_ones_closed_form():
+    # rows of attn sum to ~1, V = 1  =>  every output ~1, rc ~ N, cc ~ M
+    M, N, K = 19, 8, 19
+    attn = gen.gen_softmax_bits((M, K), 77, "bf16")
+    V = gen.f32_to_bf16_bits(np.ones((K, N), dtype=np.float32))
+    P = orc.protected_gemm(attn, V, "bf16", False)
+    assert np.max(np.abs(P.C_ref - 1.0)) < 0.02
+    assert np.max(np.abs(P.rc_pred - N)) < 0.02 * N and np.max(np.abs(P.cc_pred - M)) < 0.02 * M
+
+
+# ---------------------------------------------------------------- P2: brute force over every flip
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (3, 4, 5), (5, 7, 3)])
+def test_every_single_bit_flip_is_flagged_and_localised(M, N, K):
+    A, B = _int_case(M, N, K, True, 42)
+    P = orc.protected_gemm(A, B, "i8", True)
+    for i in range(M):
+        for j in range(N):
+            for bit in range(32):
+                X = orc.flip(P.C_stored, i, j, bit)
+                rf, cf, E, status, cc_obs, rc_obs = orc.check(P, X)
+                exact_c, ring_c = orc.flags_int(cc_obs, P.cc_pred)
+                assert np.array_equal(exact_c, ring_c)          # same for single flips
+                assert status == orc.LOCALISED and E == [(i, j)]
+                assert rf.sum() == 1 and cf.sum() == 1
+                fixed = orc.correct(X, P.C_stored, E)
+                assert np.array_equal(fixed, P.C_stored)
+
+
+def test_flip_semantics():
+    X = np.array([[5, -7]], dtype=np.int32)
+    assert orc.flip(X, 0, 0, 1)[0, 0] == 7
+    assert orc.flip(X, 0, 0, 31)[0, 0] == 5 - 2 ** 31
+    assert orc.flip(X, 0, 1, 31)[0, 1] == -7 + 2 ** 31
+    h = np.array([[0x3E00]], dtype=np.uint16)                    # fp16 1.5
+    assert orc.decode(h, "f16")[0, 0] == 1.5
+    y = orc.decode(orc.flip(h, 0, 0, 14), "f16")[0, 0]            # exponent all ones, mantissa != 0
+    assert np.isnan(y)
+    assert orc.decode(orc.flip(h, 0, 0, 9), "f16")[0, 0] == 1.0   # top mantissa bit cleared
+    bb = np.array([[0x3FC0]], dtype=np.uint16)                    # bf16 1.5
+    assert orc.decode(bb, "bf16")[0, 0] == 1.5
+    assert orc.decode(orc.flip(bb, 0, 0, 7), "bf16")[0, 0] == 0.75  # lowest exponent bit cleared
+
+
+def test_two_bit31_flips_in_one_column_escape_the_ring_check_only():
+    # documented limit of mod-2^32 checksums: outside the single-error model
+    A, B = _int_case(4, 3, 8, True, 9)
+    P = orc.protected_gemm(A, B, "i8", True)
+    X = orc.flip(orc.flip(P.C_stored, 0, 1, 31), 2, 1, 31)
+    cc_obs, _, _ = orc.observe(orc.decode_stored(X, "i8"))
+    exact, ring = orc.flags_int(cc_obs, P.cc_pred)
+    d = int(cc_obs[1] - P.cc_pred[1])
+    assert d % 2 ** 32 == 0 and exact[1] == (d != 0) and not ring[1]
+
+
+# ---------------------------------------------------------------- P5: fp discrepancy equals the delta
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_fp_discrepancy_equals_injected_delta(dtype):
+    M, N, K = 24, 40, 64
+    A, B = gen.gen_operands(dtype, M, N, K, 21, 22, trans_b=True)
+    P = orc.protected_gemm(A[0], B[0], dtype, True)
+    # un-rounded product: identity holds to fp64 rounding
+    cc0, rc0, s0 = orc.observe(P.C_ref)
+    scale = np.max(np.abs(P.C_ref)) * max(M, N)
+    assert np.max(np.abs(cc0 - P.cc_pred)) < 1e-12 * scale
+    assert np.max(np.abs(rc0 - P.rc_pred)) < 1e-12 * scale
+    assert abs(s0 - P.s_pred) < 1e-11 * scale
+    # add delta to one element of the un-rounded product
+    i, j, delta = 5, 17, 0.375
+    X = P.C_ref.copy()
+    X[i, j] += delta
+    cc1, rc1, _ = orc.observe(X)
+    dc, dr = cc1 - P.cc_pred, rc1 - P.rc_pred
+    assert abs(dc[j] - delta) < 1e-10 and abs(dr[i] - delta) < 1e-10
+    dc[j] = 0
+    dr[i] = 0
+    assert np.max(np.abs(dc)) < 1e-10 and np.max(np.abs(dr)) < 1e-10
+
+
+def test_fp_flags_threshold_nan_and_localisation():
+    dtype = "f16"
+    M, N, K = 16, 24, 32
+    A, B = gen.gen_operands(dtype, M, N, K, 31, 32, trans_b=True)
+    P = orc.protected_gemm(A[0], B[0], dtype, True)
+    want_tau = 1e-3 * K * np.max(np.abs(orc.decode(A[0], dtype))) * np.max(np.abs(orc.decode(B[0], dtype)))
+    assert P.tau == pytest.approx(want_tau, rel=1e-15)
+    rf, cf, E, status, _, _ = orc.check(P, P.C_stored)
+    assert status == orc.CLEAN
+    # exponent flip -> large delta or NaN/Inf: flagged in exactly one row and one column
+    for bit in (14, 13):
+        X = orc.flip(P.C_stored, 3, 7, bit)
+        rf, cf, E, status, _, _ = orc.check(P, X)
+        assert status == orc.LOCALISED and E == [(3, 7)]
+    # flags_fp: boundary is inclusive, NaN and Inf flag
+    obs = np.array([1.0, 1.5, np.nan, np.inf, -np.inf, 0.0])
+    pred = np.array([0.5, 0.0, 0.0, 0.0, 0.0, 0.0])
+    assert list(orc.flags_fp(obs, pred, 0.5)) == [False, True, True, True, True, False]
+
+
+def test_one_sided_flags_mean_checksum_suspect():
+    assert orc.localise(np.array([0, 1, 0], bool), np.array([0, 0], bool)) == ([], orc.CHECKSUM_SUSPECT)
+    assert orc.localise(np.array([0, 0], bool), np.array([1, 0], bool)) == ([], orc.CHECKSUM_SUSPECT)
+    E, st = orc.localise(np.array([0, 1, 1], bool), np.array([1, 0, 1], bool))
+    assert st == orc.LOCALISED and E == [(1, 0), (1, 2), (2, 0), (2, 2)]
+
+
+# ---------------------------------------------------------------- roundings against library conversions
+def test_round_to_bf16_matches_torch_and_ties_to_even():
+    g = np.random.default_rng(3)
+    x32 = (g.standard_normal(20000) * np.exp(g.uniform(-30, 30, 20000))).astype(np.float32)
+    got = orc.encode_bits(orc.round_to_format(x32.astype(np.float64), "bf16"), "bf16")
+    want = torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # hand-made ties: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even (1.0)
+    assert orc.round_to_format(np.array([1 + 2.0 ** -8]), "bf16")[0] == 1.0
+    assert orc.round_to_format(np.array([1 + 3 * 2.0 ** -8]), "bf16")[0] == 1 + 2.0 ** -6
+    assert orc.round_to_format(np.array([1 + 2.0 ** -8 + 2.0 ** -40]), "bf16")[0] == 1 + 2.0 ** -7
+    assert np.isinf(orc.round_to_format(np.array([3.4e38]), "bf16")[0])
+    # generator's fp32 -> bf16 agrees with torch too (input preparation)
+    assert np.array_equal(gen.f32_to_bf16_bits(x32), want)
+
+
+def test_round_to_f16_matches_numpy_from_double():
+    g = np.random.default_rng(4)
+    x = g.standard_normal(20000) * np.exp(g.uniform(-20, 12, 20000))
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16)
+    got = orc.round_to_format(x, "f16")
+    assert np.array_equal(got, want.astype(np.float64))
+    assert np.array_equal(orc.encode_bits(got, "f16"), want.view(np.uint16))
+    assert np.isinf(orc.round_to_format(np.array([65520.0]), "f16")[0])
+    assert orc.round_to_format(np.array([65519.9]), "f16")[0] == 65504.0
+    assert orc.round_to_format(np.array([2.0 ** -25]), "f16")[0] == 0.0        # tie to even (0)
+    assert orc.round_to_format(np.array([2.0 ** -25 * 1.01]), "f16")[0] == 2.0 ** -24
+
+
+def test_store_int_range_guard_and_values():
+    C = np.array([[2 ** 31 - 1, -(2 ** 31) + 1]], dtype=np.int64)
+    assert orc.store(C, "i8").dtype == np.int32
+    with pytest.raises(AssertionError):
+        orc.store(np.array([[2 ** 31]], dtype=np.int64), "i8")
+
+
+# ---------------------------------------------------------------- P7: what work is counted
+def test_operation_count_overhead_matches_papers_claim():
+    # extra work of the method: encode MK + KN adds, predicted 2K(M+N), observed 2MN
+    def ratio(M, N, K):
+        return (2 * K * (M + N) + 2 * M * N + M * K + K * N) / (2 * M * N * K)
+    assert ratio(12608, 3072, 768) == pytest.approx(0.0019, abs=1e-4)   # "< 0.2 %" (abstract)
+    for (M, N, K) in [(6304, 2304, 768), (6304, 768, 768), (6304, 3072, 768), (6304, 768, 3072)]:
+        assert 0.001 < ratio(M, N, K) < 0.0036
