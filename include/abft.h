@@ -1,0 +1,184 @@
+/*
+ * libabft -- checksum-protected GEMM for AMD MI355X (gfx950).
+ *
+ * For C = A * B the library computes, next to C, the column checksum
+ * cc = (e^T A) B (length N) and the row checksum rc = A (B e) (length M),
+ * compares them with the sums e^T C and C e of the produced output, flags the
+ * rows and columns that disagree and repairs flagged elements by recomputing
+ * the tile that holds them.
+ *
+ * Where the operations are defined in the paper (ALBERTA, arXiv 2310.03841):
+ *   checksums of a GEMM layer ............ Sec. III-B.1, paragraph "Checksums"
+ *   equality check for fixed point,
+ *   tolerance check for floating point ... Sec. III-B.1, item (2) and "Eps Generation"
+ *   integer overflow of the sums ......... Sec. III-B.1, item (1)
+ *   weight checksum computed offline ..... Sec. III-B.1, "Checksums", remark (2)
+ *   output checksum in the GEMM epilogue . Sec. IV-C (memory-overhead paragraph), Sec. V "Optimizations" (2)
+ *   correction by replay ................. Sec. III-B.3
+ *   single-bit-flip fault model .......... Sec. II-A "Formulation to Quantify Resilience", Sec. III-A
+ * The row/column-vector form (instead of the paper's single scalar per sample)
+ * is the classic ABFT scheme the paper cites as its origin (Sec. I, Sec. II-B);
+ * the paper's scalar is the sum of either vector.
+ *
+ * Conventions
+ *   - All matrix pointers are DEVICE pointers.  Matrices are row-major.
+ *   - A is M x K with leading dimension lda (elements).
+ *   - B is given as N x K (transB = 1: a Linear layer's weight, or K of Q K^T)
+ *     or as K x N (transB = 0: V of attn V); ldb is the leading dimension of
+ *     the stored array.
+ *   - C is M x N with leading dimension ldc.  ABFT_I8: A, B int8, C int32.
+ *     ABFT_BF16 / ABFT_F16: A, B, C in that type, fp32 accumulation, C rounded
+ *     to nearest-even from the fp32 accumulator.
+ *   - batch > 1: item b uses A + b*strideA etc. (strides in elements); every
+ *     item has its own checksums and flags.
+ *   - Base pointers, leading dimensions and batch strides must be multiples of
+ *     16 bytes (else ABFT_EALIGN).  The buffers must hold rows*ld elements per
+ *     item: the library may read (never use) the pad between K and lda.
+ *   - The caller owns A, B, C, the flag / count buffers and the stream.  The
+ *     context owns its workspace (checksum vectors, encoded stripes, lists).
+ *   - abft_gemm / abft_verify / abft_correct / abft_inject / abft_encode_b only
+ *     enqueue work on `stream` (a hipStream_t passed as void*): they allocate
+ *     nothing, copy nothing to the host and never synchronise.  Results are
+ *     valid once the stream has reached that point.
+ *   - One context must be used from one stream at a time.
+ *   - Return value: ABFT_OK or a negative error code.  A detected fault is NOT
+ *     an error: it is reported through the flag vectors and counts.
+ */
+#ifndef ABFT_H
+#define ABFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct abft_ctx abft_ctx;
+
+typedef enum { ABFT_I8 = 0, ABFT_BF16 = 1, ABFT_F16 = 2 } abft_dtype;
+
+/* mode = one base value, optionally OR-ed with flag bits */
+enum {
+    ABFT_OFF            = 0,    /* plain GEMM: same kernel with every checksum path compiled out */
+    ABFT_DETECT         = 1,    /* encode, predicted + observed checksums, compare, flags */
+    ABFT_DETECT_CORRECT = 2,    /* DETECT, then the steps of abft_correct */
+    ABFT_MODE_MASK      = 0xF,
+    ABFT_B_CHECKSUM_CACHED = 0x10 /* reuse the encoding of B left in the context by abft_encode_b
+                                     (or by the previous abft_gemm with the same B and shape):
+                                     the paper's offline weight checksum */
+};
+
+enum {
+    ABFT_OK         =  0,
+    ABFT_EINVAL     = -1,   /* null pointer, unknown dtype/mode, index out of range */
+    ABFT_EALIGN     = -2,   /* pointer, leading dimension or stride not a multiple of 16 bytes */
+    ABFT_ESHAPE     = -3,   /* non-positive size, ld < row length, or K so large that an int32
+                               dot product of int8 values could overflow (K >= 2^17) */
+    ABFT_EWORKSPACE = -4,   /* shape exceeds what the context was created for */
+    ABFT_EHIP       = -5,   /* a HIP runtime call failed (see abft_last_hip_error) */
+    ABFT_ESTATE     = -6    /* call needs state that is not there (e.g. cached B encoding) */
+};
+
+/* status values written to counts[2] */
+enum {
+    ABFT_CLEAN            = 0,
+    ABFT_LOCALISED        = 1,  /* flags on both sides: candidates = flagged rows x flagged cols */
+    ABFT_CHECKSUM_SUSPECT = 2,  /* flags on one side only: not explainable by a corrupted element of C */
+    ABFT_TOO_MANY         = 3   /* more flagged tiles than abft_correct repairs; replay the GEMM */
+};
+
+typedef struct {
+    int64_t M, N, K;
+    int64_t batch;                    /* >= 1 */
+    int64_t lda, ldb, ldc;            /* elements */
+    int64_t strideA, strideB, strideC;/* elements between batch items (ignored if batch == 1) */
+    int32_t transB;                   /* 1: B stored N x K;  0: B stored K x N */
+    int32_t reserved;
+} abft_shape;
+
+typedef struct {
+    int64_t max_rows;   /* largest batch*M over all calls */
+    int64_t max_cols;   /* largest batch*N */
+    int64_t max_depth;  /* largest batch*(K rounded up to 128) */
+    int64_t max_batch;
+    int32_t device;     /* HIP device ordinal */
+    int32_t reserved;
+} abft_config;
+
+/* Caller-provided DEVICE buffers that receive the verdict of a call. */
+typedef struct {
+    uint8_t  *row_flag;   /* [batch*M], 1 = row checksum mismatch */
+    uint8_t  *col_flag;   /* [batch*N], 1 = column checksum mismatch */
+    uint32_t *counts;     /* [8]: 0 = number of flagged rows, 1 = flagged columns, 2 = status,
+                                  3 = tiles recomputed by the last correction,
+                                  4 = status before that correction, 5..7 reserved */
+    float     tau;        /* floating point only: > 0 overrides the tolerance
+                             1e-3 * K * max|A| * max|B| (per batch item); 0 = use that default */
+} abft_result;
+
+/* Workspace vectors that tests and reports may read back (device pointers into the context). */
+typedef enum {
+    ABFT_WS_A_SUM   = 0,  /* a = e^T A   [batch][K]   int32 / float */
+    ABFT_WS_B_SUM   = 1,  /* b = B e     [batch][K] */
+    ABFT_WS_CC_PRED = 2,  /* (e^T A) B   [batch][N] */
+    ABFT_WS_RC_PRED = 3,  /* A (B e)     [batch][M] */
+    ABFT_WS_CC_OBS  = 4,  /* e^T C from the GEMM epilogue (accumulators, before rounding) [batch][N] */
+    ABFT_WS_RC_OBS  = 5,  /* C e   from the GEMM epilogue [batch][M] */
+    ABFT_WS_CC_VOBS = 6,  /* e^T C re-summed from stored C by abft_verify [batch][N] */
+    ABFT_WS_RC_VOBS = 7,  /* C e   re-summed from stored C by abft_verify [batch][M] */
+    ABFT_WS_TAU     = 8,  /* tolerance in use [batch] float (floating point only) */
+    ABFT_WS_S_PRED  = 9,  /* scalar a.b [batch] (the paper's own scalar check value) */
+    ABFT_WS_MAXABS  = 10  /* max|A|, max|B| [batch][2] float (floating point only) */
+} abft_ws_id;
+
+/* where a flip lands */
+enum { ABFT_INJECT_STORED_C = 0, ABFT_INJECT_ACCUMULATOR = 1 };
+
+/* Allocates the context and its device workspace on cfg->device (the only call that allocates). */
+int abft_create(abft_ctx **out, const abft_config *cfg);
+int abft_destroy(abft_ctx *ctx);
+
+/* Offline weight checksum (Sec. III-B.1 "Checksums", remark (2)): encodes B once; later
+ * abft_gemm calls with ABFT_B_CHECKSUM_CACHED and the same shape skip that step. */
+int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_shape *s, void *stream);
+
+/* Steps 1-6: encode, GEMM with the checksum stripe, observed sums in the epilogue, compare.
+ * mode ABFT_OFF ignores `r` (may be NULL).  Flags and counts are overwritten. */
+int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
+              const abft_shape *s, const abft_result *r, void *stream);
+
+/* Re-sums the stored C and compares with the predictions the last abft_gemm of this shape left
+ * in the context (Sec. III-B.1: sum of layer activations vs. checksum product).  Overwrites
+ * flags and counts. */
+int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape *s,
+                const abft_result *r, void *stream);
+
+/* Replay at tile granularity (Sec. III-B.3): recomputes every 32x32 tile of C that holds a
+ * (flagged row, flagged column) pair from A and B, re-sums the touched rows and columns and
+ * updates flags and counts.  A and B must be unchanged since abft_gemm. */
+int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
+                 const abft_shape *s, const abft_result *r, void *stream);
+
+/* Test hook for the single-bit-flip fault model.  ABFT_INJECT_STORED_C inverts bit `bit`
+ * (0..31 for int32 C, 0..15 for bf16/f16 C) of C[batch_idx][row][col] on the stream.
+ * ABFT_INJECT_ACCUMULATOR arms a one-shot flip of bit 0..31 of the int32/fp32 accumulator of
+ * that element, applied inside the next abft_gemm before its epilogue (C may be NULL). */
+int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s, int64_t batch_idx,
+                int64_t row, int64_t col, int bit, int where, void *stream);
+
+/* Device pointer and element count of a workspace vector for the given shape (layout [batch][len]). */
+int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, void **ptr, int64_t *count);
+
+/* Tile the GEMM kernel uses for this problem (rows, cols of C per workgroup). */
+int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *tile_n);
+
+const char *abft_strerror(int code);
+/* hipError_t value of the last failing HIP call on this context (0 if none). */
+int abft_last_hip_error(const abft_ctx *ctx);
+int abft_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABFT_H */

@@ -1,0 +1,362 @@
+// C-ABI of libabft: context, argument validation, workspace carving, launch order.
+// Every hot call only enqueues kernels on the caller's stream.
+#include <hip/hip_runtime.h>
+#include <new>
+#include <string.h>
+
+#include "../../include/abft.h"
+#include "abft_internal.h"
+
+using namespace abft;
+
+struct abft_ctx {
+    abft_config cfg;
+    // device pools (32-bit words unless noted)
+    uint32_t *pool_depth;   // 4 * max_depth words: a_acc, b_acc, a_sum, b_sum
+    uint8_t  *pool_stripe;  // 2 * NTERM * max_depth * 2 bytes
+    uint32_t *pool_batch;   // per-batch scalars
+    uint32_t *pool_rows;    // rc_part (NTERM), rc_pred
+    uint32_t *pool_cols;    // cc_part (NTERM), cc_pred
+    uint32_t *pool_obs;     // cc_obs | rc_obs   (zeroed as one region)
+    uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
+    int32_t  *fix_tiles;
+    uint32_t *small;        // fix_count[4], cmp_ticket[4]
+    InjectArm arm;
+    int last_hip;
+    // what the context currently holds
+    bool b_valid, pred_valid;
+    int b_dt, pred_dt;
+    abft_shape b_shape, pred_shape;
+};
+
+static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + 2 * NTERM /*w_a,w_b*/ + 1 /*ticket*/ +
+                               NTERM * NTERM /*s_part*/ + 1 /*s_pred*/;
+
+static int fail_hip(abft_ctx *c, hipError_t e)
+{
+    if (c) c->last_hip = (int)e;
+    return ABFT_EHIP;
+}
+
+static int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+
+extern "C" int abft_version(void) { return 100; }
+
+extern "C" const char *abft_strerror(int code)
+{
+    switch (code) {
+    case ABFT_OK: return "ok";
+    case ABFT_EINVAL: return "invalid argument";
+    case ABFT_EALIGN: return "pointer, leading dimension or stride not a multiple of 16 bytes";
+    case ABFT_ESHAPE: return "bad shape";
+    case ABFT_EWORKSPACE: return "shape exceeds the context's workspace";
+    case ABFT_EHIP: return "HIP runtime error";
+    case ABFT_ESTATE: return "required state missing in the context";
+    default: return "unknown error";
+    }
+}
+
+extern "C" int abft_last_hip_error(const abft_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
+{
+    if (!out || !cfg) return ABFT_EINVAL;
+    *out = nullptr;
+    if (cfg->max_rows < 1 || cfg->max_cols < 1 || cfg->max_depth < 1 || cfg->max_batch < 1) return ABFT_ESHAPE;
+    abft_ctx *c = new (std::nothrow) abft_ctx;
+    if (!c) return ABFT_EINVAL;
+    memset(c, 0, sizeof(*c));
+    c->cfg = *cfg;
+    c->cfg.max_depth = round_up(cfg->max_depth, SLAB_BYTES) + (int64_t)SLAB_BYTES * cfg->max_batch;
+    c->arm.batch = -1;
+    hipError_t e = hipSetDevice(cfg->device);
+    if (e != hipSuccess) { int r = fail_hip(c, e); delete c; return r; }
+    const size_t D = (size_t)c->cfg.max_depth, R = (size_t)cfg->max_rows, Cn = (size_t)cfg->max_cols,
+                 Bt = (size_t)cfg->max_batch;
+    struct { void **p; size_t bytes; } req[] = {
+        {(void **)&c->pool_depth, 4 * D * 4},
+        {(void **)&c->pool_stripe, 2 * NTERM * D * 2},
+        {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
+        {(void **)&c->pool_rows, (NTERM + 1) * R * 4},
+        {(void **)&c->pool_cols, (NTERM + 1) * Cn * 4},
+        {(void **)&c->pool_obs, (R + Cn) * 4},
+        {(void **)&c->pool_vobs, (R + Cn) * 4},
+        {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
+        {(void **)&c->small, 8 * 4},
+    };
+    for (auto &q : req) {
+        e = hipMalloc(q.p, q.bytes);
+        if (e == hipSuccess) e = hipMemset(*q.p, 0, q.bytes);
+        if (e != hipSuccess) {
+            int r = fail_hip(c, e);
+            abft_destroy(c);
+            return r;
+        }
+    }
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) { int r = fail_hip(c, e); abft_destroy(c); return r; }
+    *out = c;
+    return ABFT_OK;
+}
+
+extern "C" int abft_destroy(abft_ctx *c)
+{
+    if (!c) return ABFT_EINVAL;
+    void *ptrs[] = {c->pool_depth, c->pool_stripe, c->pool_batch, c->pool_rows, c->pool_cols,
+                    c->pool_obs, c->pool_vobs, c->fix_tiles, c->small};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete c;
+    return ABFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// need: 1 = A, 2 = B, 4 = C
+static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need, Shape *o)
+{
+    if (!c || !s) return ABFT_EINVAL;
+    if (dt != ABFT_I8 && dt != ABFT_BF16 && dt != ABFT_F16) return ABFT_EINVAL;
+    if (s->M < 1 || s->N < 1 || s->K < 1 || s->batch < 1) return ABFT_ESHAPE;
+    if (s->M > (1 << 30) || s->N > (1 << 30) || s->K > (1 << 30) || s->batch > 65535) return ABFT_ESHAPE;
+    if (s->transB != 0 && s->transB != 1) return ABFT_EINVAL;
+    const int es = elem_size(dt), os = out_size(dt);
+    if (dt == ABFT_I8 && s->K >= (1 << 17)) return ABFT_ESHAPE;       // K * 2^14 must stay below 2^31
+    if ((need & 1) && s->lda < s->K) return ABFT_ESHAPE;
+    if ((need & 2) && s->ldb < (s->transB ? s->K : s->N)) return ABFT_ESHAPE;
+    if ((need & 4) && s->ldc < s->N) return ABFT_ESHAPE;
+    if ((need & 1) && (s->lda * es) % 16) return ABFT_EALIGN;
+    if ((need & 2) && (s->ldb * es) % 16) return ABFT_EALIGN;
+    if ((need & 4) && (s->ldc * os) % 16) return ABFT_EALIGN;
+    if (s->batch > 1) {
+        if ((need & 1) && (s->strideA < 0 || (s->strideA * es) % 16)) return ABFT_EALIGN;
+        if ((need & 2) && (s->strideB < 0 || (s->strideB * es) % 16)) return ABFT_EALIGN;
+        if ((need & 4) && (s->strideC < s->M * s->ldc || (s->strideC * os) % 16)) return ABFT_EALIGN;
+    }
+    const int64_t Kp = round_up(s->K, SLAB_BYTES / es);
+    if (s->batch * s->M > c->cfg.max_rows || s->batch * s->N > c->cfg.max_cols ||
+        s->batch * Kp > c->cfg.max_depth || s->batch > c->cfg.max_batch)
+        return ABFT_EWORKSPACE;
+    o->M = (int)s->M; o->N = (int)s->N; o->K = (int)s->K; o->batch = (int)s->batch; o->transB = s->transB;
+    o->lda = s->lda; o->ldb = s->ldb; o->ldc = s->ldc;
+    o->sA = s->batch > 1 ? s->strideA : 0;
+    o->sB = s->batch > 1 ? s->strideB : 0;
+    o->sC = s->batch > 1 ? s->strideC : 0;
+    o->Kp = (int)Kp;
+    return ABFT_OK;
+}
+
+static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
+{
+    const size_t bK = (size_t)s.batch * s.K, bM = (size_t)s.batch * s.M, bN = (size_t)s.batch * s.N;
+    const size_t D = (size_t)c->cfg.max_depth, R = (size_t)c->cfg.max_rows, Cn = (size_t)c->cfg.max_cols,
+                 Bt = (size_t)c->cfg.max_batch;
+    (void)bK;
+    w->a_acc = c->pool_depth;
+    w->b_acc = c->pool_depth + D;
+    w->a_sum = c->pool_depth + 2 * D;
+    w->b_sum = c->pool_depth + 3 * D;
+    w->stripe_a = c->pool_stripe;
+    w->stripe_b = c->pool_stripe + NTERM * D * 2;
+    uint32_t *pb = c->pool_batch;
+    w->max_acc = pb;                          pb += 2 * Bt;
+    w->maxabs = (float *)pb;                  pb += 2 * Bt;
+    w->tau = (float *)pb;                     pb += Bt;
+    w->w_a = (float *)pb;                     pb += NTERM * Bt;
+    w->w_b = (float *)pb;                     pb += NTERM * Bt;
+    w->enc_ticket = pb;                       pb += Bt;
+    w->s_part = pb;                           pb += NTERM * NTERM * Bt;
+    w->s_pred = pb;
+    w->rc_part = c->pool_rows;
+    w->rc_pred = c->pool_rows + NTERM * R;
+    w->cc_part = c->pool_cols;
+    w->cc_pred = c->pool_cols + NTERM * Cn;
+    w->cc_obs = c->pool_obs;
+    w->rc_obs = c->pool_obs + bN;
+    w->cc_vobs = c->pool_vobs;
+    w->rc_vobs = c->pool_vobs + bN;
+    w->fix_tiles = c->fix_tiles;
+    w->fix_count = c->small;
+    w->cmp_ticket = c->small + 4;
+    (void)dt; (void)bM;
+}
+
+static bool same_b(const abft_shape &x, const abft_shape &y)
+{
+    return x.N == y.N && x.K == y.K && x.batch == y.batch && x.transB == y.transB && x.ldb == y.ldb &&
+           (x.batch == 1 || x.strideB == y.strideB);
+}
+static bool same_out(const abft_shape &x, const abft_shape &y)
+{
+    return x.M == y.M && x.N == y.N && x.batch == y.batch;
+}
+
+static int check_verdict(const abft_result *r, Verdict *v)
+{
+    if (!r || !r->row_flag || !r->col_flag || !r->counts) return ABFT_EINVAL;
+    if (!(r->tau >= 0.f)) return ABFT_EINVAL;
+    v->row_flag = r->row_flag; v->col_flag = r->col_flag; v->counts = r->counts; v->tau_override = r->tau;
+    return ABFT_OK;
+}
+
+#define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail_hip(ctx, e_); } while (0)
+
+extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_shape *s, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 2, &sh);
+    if (rc) return rc;
+    if (!B) return ABFT_EINVAL;
+    if (!aligned16(B)) return ABFT_EALIGN;
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    ctx->b_valid = false;
+    HIP_TRY(launch_encode(dtype, nullptr, B, false, true, sh, w, 0.f, nullptr, 0, (hipStream_t)stream));
+    ctx->b_valid = true;
+    ctx->b_dt = dtype;
+    ctx->b_shape = *s;
+    return ABFT_OK;
+}
+
+extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
+                         const abft_shape *s, const abft_result *r, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 7, &sh);
+    if (rc) return rc;
+    if (!A || !B || !C) return ABFT_EINVAL;
+    if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return ABFT_EALIGN;
+    const int base = mode & ABFT_MODE_MASK;
+    if (base != ABFT_OFF && base != ABFT_DETECT && base != ABFT_DETECT_CORRECT) return ABFT_EINVAL;
+    if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED)) return ABFT_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    InjectArm arm = ctx->arm;
+    if (arm.batch >= 0 && (arm.batch >= sh.batch || arm.row >= sh.M || arm.col >= sh.N)) return ABFT_EINVAL;
+
+    if (base == ABFT_OFF) {
+        ctx->arm.batch = -1;
+        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, st));
+        return ABFT_OK;
+    }
+    Verdict v;
+    rc = check_verdict(r, &v);
+    if (rc) return rc;
+    const bool cached = (mode & ABFT_B_CHECKSUM_CACHED) != 0;
+    if (cached && !(ctx->b_valid && ctx->b_dt == (int)dtype && same_b(ctx->b_shape, *s))) return ABFT_ESTATE;
+    ctx->pred_valid = false;
+    if (!cached) ctx->b_valid = false;
+    ctx->arm.batch = -1;
+    HIP_TRY(launch_encode(dtype, A, B, true, !cached, sh, w, v.tau_override, w.cc_obs,
+                          (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
+    HIP_TRY(launch_compare(dtype, sh, w, false, v, st));
+    ctx->b_valid = true;
+    ctx->b_dt = dtype;
+    ctx->b_shape = *s;
+    ctx->pred_valid = true;
+    ctx->pred_dt = dtype;
+    ctx->pred_shape = *s;
+    if (base == ABFT_DETECT_CORRECT) HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, st));
+    return ABFT_OK;
+}
+
+extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape *s,
+                           const abft_result *r, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 4, &sh);
+    if (rc) return rc;
+    if (!C) return ABFT_EINVAL;
+    if (!aligned16(C)) return ABFT_EALIGN;
+    Verdict v;
+    rc = check_verdict(r, &v);
+    if (rc) return rc;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    hipStream_t st = (hipStream_t)stream;
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    HIP_TRY(launch_zero(w.cc_vobs, (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
+    HIP_TRY(launch_compare(dtype, sh, w, true, v, st));
+    return ABFT_OK;
+}
+
+extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
+                            const abft_shape *s, const abft_result *r, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 7, &sh);
+    if (rc) return rc;
+    if (!A || !B || !C) return ABFT_EINVAL;
+    if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return ABFT_EALIGN;
+    Verdict v;
+    rc = check_verdict(r, &v);
+    if (rc) return rc;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+extern "C" int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s, int64_t batch_idx,
+                           int64_t row, int64_t col, int bit, int where, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, where == ABFT_INJECT_STORED_C ? 4 : 0, &sh);
+    if (rc) return rc;
+    if (batch_idx < 0 || batch_idx >= sh.batch || row < 0 || row >= sh.M || col < 0 || col >= sh.N)
+        return ABFT_EINVAL;
+    if (where == ABFT_INJECT_ACCUMULATOR) {
+        if (bit < 0 || bit > 31) return ABFT_EINVAL;
+        ctx->arm.batch = (int)batch_idx; ctx->arm.row = (int)row; ctx->arm.col = (int)col; ctx->arm.bit = bit;
+        return ABFT_OK;
+    }
+    if (where != ABFT_INJECT_STORED_C) return ABFT_EINVAL;
+    if (!C) return ABFT_EINVAL;
+    if (bit < 0 || bit >= 8 * out_size(dtype)) return ABFT_EINVAL;
+    HIP_TRY(launch_flip(C, dtype, sh, batch_idx, row, col, bit, (hipStream_t)stream));
+    return ABFT_OK;
+}
+
+extern "C" int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, void **ptr, int64_t *count)
+{
+    if (!ptr || !count || !s) return ABFT_EINVAL;
+    Shape sh;
+    // dtype does not change the carving except through Kp; take the widest (1-byte elements)
+    int rc = check_shape(ctx, ABFT_I8, s, 0, &sh);
+    if (rc == ABFT_ESHAPE && s->K >= (1 << 17)) rc = check_shape(ctx, ABFT_BF16, s, 0, &sh);
+    if (rc) return rc;
+    Workspace w;
+    carve(ctx, 0, sh, &w);
+    const int64_t b = sh.batch;
+    switch (which) {
+    case ABFT_WS_A_SUM:   *ptr = w.a_sum;   *count = b * sh.K; break;
+    case ABFT_WS_B_SUM:   *ptr = w.b_sum;   *count = b * sh.K; break;
+    case ABFT_WS_CC_PRED: *ptr = w.cc_pred; *count = b * sh.N; break;
+    case ABFT_WS_RC_PRED: *ptr = w.rc_pred; *count = b * sh.M; break;
+    case ABFT_WS_CC_OBS:  *ptr = w.cc_obs;  *count = b * sh.N; break;
+    case ABFT_WS_RC_OBS:  *ptr = w.rc_obs;  *count = b * sh.M; break;
+    case ABFT_WS_CC_VOBS: *ptr = w.cc_vobs; *count = b * sh.N; break;
+    case ABFT_WS_RC_VOBS: *ptr = w.rc_vobs; *count = b * sh.M; break;
+    case ABFT_WS_TAU:     *ptr = w.tau;     *count = b; break;
+    case ABFT_WS_S_PRED:  *ptr = w.s_pred;  *count = b; break;
+    case ABFT_WS_MAXABS:  *ptr = w.maxabs;  *count = 2 * b; break;
+    default: return ABFT_EINVAL;
+    }
+    return ABFT_OK;
+}
+
+extern "C" int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *tile_n)
+{
+    if (!s || !tile_m || !tile_n) return ABFT_EINVAL;
+    if (dtype != ABFT_I8 && dtype != ABFT_BF16 && dtype != ABFT_F16) return ABFT_EINVAL;
+    Shape sh;
+    memset(&sh, 0, sizeof(sh));
+    sh.M = (int)s->M; sh.N = (int)s->N; sh.K = (int)s->K; sh.batch = (int)s->batch; sh.transB = s->transB;
+    gemm_tile_shape(dtype, sh, tile_m, tile_n);
+    return ABFT_OK;
+}

@@ -1,0 +1,817 @@
+// Kernels around the protected GEMM: encode (input-side checksums and their
+// stripe encoding), compare (flags), verify (re-sum stored C), correct
+// (localise, recompute tiles, re-check) and the bit-flip test hook.
+//
+// Paper references: the two input-side vectors and the comparison with the
+// output sums are the checksum scheme of Sec. III-B.1 ("Checksums"); equality
+// for integers and a tolerance for floating point follow item (2) there; the
+// tile recompute is the replay correction of Sec. III-B.3 at tile granularity;
+// the flip is the fault model of Sec. II-A / III-A.
+#include "abft_device.h"
+
+namespace abft {
+
+// ======================================================================== zero
+__global__ void zero_kernel(uint32_t *p, size_t n)
+{
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t step = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += step) p[i] = 0u;
+}
+
+hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st)
+{
+    if (nwords == 0) return hipSuccess;
+    size_t blocks = (nwords + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, nwords);
+    return hipGetLastError();
+}
+
+// ====================================================================== encode
+// One side (A or B) of the encode step.  The stored array has `rows` rows of
+// `cols` elements.  reduce_rows = 1: out[col] = sum over rows (A: e^T A; B
+// stored N x K: B e).  reduce_rows = 0: out[row] = sum over cols (B stored
+// K x N: B e).
+struct EncSide {
+    const uint8_t *X;
+    long ld, stride;      // elements
+    int rows, cols;
+    int reduce_rows;
+    int cw_log2;          // 16-byte chunk columns per block window (power of two <= 64)
+    int rpb;              // rows per block
+    int nwin, nrb;
+    uint32_t *acc;        // [batch][K] atomic accumulators
+    uint32_t *sum;        // [batch][K] final sums
+    uint8_t *stripe;      // [batch][NTERM][Kp]
+    float *w;             // [batch][NTERM]
+    int active;
+};
+
+struct EncArgs {
+    EncSide side[2];
+    int K, Kp;
+    uint32_t *max_acc;    // [batch][2]
+    float *maxabs;        // [batch][2]
+    float *tau;           // [batch]
+    uint32_t *ticket;     // [batch]
+    float tau_override;
+    uint32_t *zero_ptr;
+    size_t zero_words;
+};
+
+// Split an int32 sum into four signed base-256 digits: v = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3 (mod 2^32).
+__device__ __forceinline__ void split_digits(int v, int8_t d[NTERM])
+{
+#pragma unroll
+    for (int t = 0; t < NTERM; ++t) {
+        int8_t lo = (int8_t)(v & 0xFF);
+        d[t] = lo;
+        v = (int)(((int64_t)v - (int64_t)lo) >> 8);
+    }
+}
+
+template <int DT>
+__device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /*[4] LDS*/)
+{
+    using T = Traits<DT>;
+    const EncSide &sd = e.side[sidx];
+    const int tid = threadIdx.x;
+    const int K = e.K, Kp = e.Kp;
+    uint32_t *acc = sd.acc + (long)bz * K;
+    uint32_t *sum = sd.sum + (long)bz * K;
+    uint8_t *stripe = sd.stripe + (long)bz * NTERM * Kp * T::ES;
+
+    float amax = 0.f;
+    for (int k = tid; k < K; k += 256) {
+        uint32_t w = atomicExch(acc + k, 0u);      // take the total and leave the accumulator clean
+        sum[k] = w;
+        if (!T::IS_INT) amax = fmaxf(amax, fabsf(__uint_as_float(w)));
+    }
+    float scale = 1.f, inv = 1.f;
+    if (DT == DT_F16) {
+        // power-of-two pre-scale so the largest |sum| sits in [2^13, 2^14): well inside fp16 range
+        amax = wave_max(amax);
+        __syncthreads();
+        if ((tid & 63) == 0) red[tid >> 6] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        int sh = 0;
+        if (amax > 0.f && amax <= 3.0e38f) {
+            int ex;
+            frexpf(amax, &ex);
+            sh = 14 - ex;
+            sh = sh > 100 ? 100 : (sh < -100 ? -100 : sh);
+        }
+        scale = ldexpf(1.f, sh);
+        inv = ldexpf(1.f, -sh);
+    }
+    for (int k = tid; k < Kp; k += 256) {
+        if (DT == DT_I8) {
+            int8_t d[NTERM] = {0, 0, 0, 0};
+            if (k < K) split_digits((int)sum[k], d);
+#pragma unroll
+            for (int t = 0; t < NTERM; ++t) ((int8_t *)stripe)[(long)t * Kp + k] = d[t];
+        } else {
+            uint16_t h[NTERM] = {0, 0, 0, 0};
+            if (k < K) {
+                float v = __uint_as_float(sum[k]);
+                if (DT == DT_BF16) {
+                    uint32_t t0 = f32_to_bf16_bits(v);
+                    float r1 = v - bf16_bits_to_f32(t0);
+                    uint32_t t1 = f32_to_bf16_bits(r1);
+                    float r2 = r1 - bf16_bits_to_f32(t1);
+                    uint32_t t2 = f32_to_bf16_bits(r2);
+                    h[0] = (uint16_t)t0; h[1] = (uint16_t)t1; h[2] = (uint16_t)t2;
+                } else {
+                    float x = v * scale;
+                    uint32_t t0 = f32_to_f16_bits(x);
+                    float r1 = (x - f16_bits_to_f32(t0)) * 2048.f;
+                    uint32_t t1 = f32_to_f16_bits(r1);
+                    float r2 = (r1 - f16_bits_to_f32(t1)) * 2048.f;
+                    uint32_t t2 = f32_to_f16_bits(r2);
+                    h[0] = (uint16_t)t0; h[1] = (uint16_t)t1; h[2] = (uint16_t)t2;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NTERM; ++t) ((uint16_t *)stripe)[(long)t * Kp + k] = h[t];
+        }
+    }
+    if (!T::IS_INT && tid == 0) {
+        float *w = sd.w + (long)bz * NTERM;
+        if (DT == DT_BF16) { w[0] = 1.f; w[1] = 1.f; w[2] = 1.f; w[3] = 0.f; }
+        else { w[0] = inv; w[1] = inv * (1.f / 2048.f); w[2] = inv * (1.f / 4194304.f); w[3] = 0.f; }
+        uint32_t mb = atomicExch(e.max_acc + (long)bz * 2 + sidx, 0u);
+        e.maxabs[(long)bz * 2 + sidx] = __uint_as_float(mb);
+    }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    __shared__ acc_t red[256 * CE];
+    __shared__ float fred[4];
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x;
+    // every block takes a share of the words that must start at zero
+    {
+        size_t nb = (size_t)gridDim.x * gridDim.y * gridDim.z;
+        size_t bid = blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z);
+        for (size_t i = bid * 256 + tid; i < e.zero_words; i += nb * 256) e.zero_ptr[i] = 0u;
+    }
+    const int sidx = blockIdx.y, bz = blockIdx.z;
+    const EncSide &sd = e.side[sidx];
+    if (!sd.active || (int)blockIdx.x >= sd.nwin * sd.nrb) return;
+
+    const int win = blockIdx.x % sd.nwin, rb = blockIdx.x / sd.nwin;
+    const int CW = 1 << sd.cw_log2, RL = 256 >> sd.cw_log2;
+    const int cx = tid & (CW - 1), ry = tid >> sd.cw_log2;
+    const int col0 = (win * CW + cx) * CE;
+    const bool colok = col0 < sd.cols;
+    const int nvalid = sd.cols - col0;                       // elements of this chunk inside the row
+    const uint8_t *Xb = sd.X + (long)bz * sd.stride * ES;
+    const int rbeg = rb * sd.rpb;
+    const int rend = min(rbeg + sd.rpb, sd.rows);
+    const int iters = (sd.rpb + RL - 1) / RL;
+
+    acc_t colacc[CE];
+#pragma unroll
+    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
+    float mx = 0.f;
+
+    for (int it = 0; it < iters; ++it) {
+        const int r = rbeg + ry + it * RL;
+        const bool ok = colok && r < rend;
+        i32x4 v = {0, 0, 0, 0};
+        if (ok) {
+            v = *reinterpret_cast<const i32x4 *>(Xb + ((long)r * sd.ld + col0) * ES);
+            if (nvalid < CE) v = mask_chunk(v, nvalid * ES);
+        }
+        acc_t s = T::zero();
+#pragma unroll
+        for (int q = 0; q < CE; ++q) {
+            acc_t x = T::elem(v, q);
+            if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
+            colacc[q] = add_t(colacc[q], x);
+            s = add_t(s, x);
+        }
+        if (!sd.reduce_rows) {
+            for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+            if (cx == 0 && r < rend) atomic_add_word(sd.acc + (long)bz * e.K + r, s);
+        }
+    }
+    if (sd.reduce_rows) {
+#pragma unroll
+        for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
+        __syncthreads();
+        if (ry == 0 && colok) {
+#pragma unroll
+            for (int q = 0; q < CE; ++q) {
+                acc_t t = red[cx * CE + q];
+                for (int y = 1; y < RL; ++y) t = add_t(t, red[(y * CW + cx) * CE + q]);
+                if (q < nvalid) atomic_add_word(sd.acc + (long)bz * e.K + col0 + q, t);
+            }
+        }
+    }
+    if (!T::IS_INT) {
+        mx = wave_max(mx);
+        if ((tid & 63) == 0) atomicMax(e.max_acc + (long)bz * 2 + sidx, __float_as_uint(mx));
+    }
+    // last block of this batch item finalises both sides
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        unsigned expected = 0;
+        for (int q = 0; q < 2; ++q)
+            if (e.side[q].active) expected += (unsigned)(e.side[q].nwin * e.side[q].nrb);
+        unsigned t = atomicAdd(e.ticket + bz, 1u);
+        is_last = (t == expected - 1);
+        if (is_last) atomicExch(e.ticket + bz, 0u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    for (int q = 0; q < 2; ++q)
+        if (e.side[q].active) encode_finalize<DT>(e, q, bz, fred);
+    if (!T::IS_INT && e.side[0].active) {
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            float ma = e.maxabs[(long)bz * 2 + 0], mb = e.maxabs[(long)bz * 2 + 1];
+            e.tau[bz] = e.tau_override > 0.f ? e.tau_override : (1e-3f * (float)e.K) * ma * mb;
+        }
+    }
+}
+
+static void plan_side(EncSide &sd, int chunk_elems)
+{
+    int chunks = (sd.cols + chunk_elems - 1) / chunk_elems;
+    int lg = 0;
+    while ((1 << lg) < chunks && lg < 6) ++lg;
+    if (lg < 3) lg = 3;
+    sd.cw_log2 = lg;
+    int CW = 1 << lg, RL = 256 / CW;
+    sd.nwin = (chunks + CW - 1) / CW;
+    int rpb = RL * 16;                 // 16 chunk loads per thread
+    if (rpb > sd.rows) rpb = ((sd.rows + RL - 1) / RL) * RL;
+    sd.rpb = rpb;
+    sd.nrb = (sd.rows + rpb - 1) / rpb;
+}
+
+hipError_t launch_encode(int dt, const void *A, const void *B, bool do_a, bool do_b, const Shape &s,
+                         const Workspace &w, float tau_override, uint32_t *zero_ptr, size_t zero_words,
+                         hipStream_t st)
+{
+    EncArgs e;
+    const int ce = 16 / elem_size(dt);
+    EncSide &a = e.side[0];
+    a.X = (const uint8_t *)A; a.ld = s.lda; a.stride = s.sA; a.rows = s.M; a.cols = s.K;
+    a.reduce_rows = 1; a.acc = w.a_acc; a.sum = w.a_sum; a.stripe = w.stripe_a; a.w = w.w_a;
+    a.active = do_a ? 1 : 0;
+    plan_side(a, ce);
+    EncSide &b = e.side[1];
+    b.X = (const uint8_t *)B; b.ld = s.ldb; b.stride = s.sB;
+    if (s.transB) { b.rows = s.N; b.cols = s.K; b.reduce_rows = 1; }
+    else          { b.rows = s.K; b.cols = s.N; b.reduce_rows = 0; }
+    b.acc = w.b_acc; b.sum = w.b_sum; b.stripe = w.stripe_b; b.w = w.w_b;
+    b.active = do_b ? 1 : 0;
+    plan_side(b, ce);
+    e.K = s.K; e.Kp = s.Kp;
+    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.tau = w.tau; e.ticket = w.enc_ticket;
+    e.tau_override = tau_override;
+    e.zero_ptr = zero_ptr; e.zero_words = zero_words;
+    int na = do_a ? a.nwin * a.nrb : 0, nb = do_b ? b.nwin * b.nrb : 0;
+    dim3 grid((unsigned)(na > nb ? na : nb), 2, (unsigned)s.batch);
+    switch (dt) {
+    case DT_I8:   hipLaunchKernelGGL(encode_kernel<DT_I8>, grid, dim3(256), 0, st, e); break;
+    case DT_BF16: hipLaunchKernelGGL(encode_kernel<DT_BF16>, grid, dim3(256), 0, st, e); break;
+    case DT_F16:  hipLaunchKernelGGL(encode_kernel<DT_F16>, grid, dim3(256), 0, st, e); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ===================================================================== compare
+struct CmpArgs {
+    const uint32_t *cc_part, *rc_part, *s_part;
+    uint32_t *cc_pred, *rc_pred, *s_pred;
+    const uint32_t *cc_obs, *rc_obs;
+    const float *w_a, *w_b, *tau;
+    uint8_t *row_flag, *col_flag;
+    uint32_t *counts;
+    uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
+    int M, N, batch;
+    int recombine;        // 1: build predictions from the stripe outputs; 0: reuse stored predictions
+};
+
+template <bool IS_INT>
+__device__ __forceinline__ uint32_t recombine_terms(const uint32_t *part, long stride, const float *w)
+{
+    if (IS_INT) {
+        uint32_t v = 0;
+#pragma unroll
+        for (int t = 0; t < NTERM; ++t) v += part[t * stride] << (8 * t);
+        return v;
+    }
+    float v = 0.f;
+#pragma unroll
+    for (int t = NTERM - 1; t >= 0; --t) v += __uint_as_float(part[t * stride]) * w[t];   // small terms first
+    return __float_as_uint(v);
+}
+
+template <bool IS_INT>
+__device__ __forceinline__ bool mismatch(uint32_t obs, uint32_t pred, float tol)
+{
+    if (IS_INT) return obs != pred;                          // equality in Z/2^32
+    float d = fabsf(__uint_as_float(obs) - __uint_as_float(pred));
+    return !(d <= tol);                                      // NaN and Inf always flag
+}
+
+__device__ __forceinline__ uint32_t status_of(uint32_t nr, uint32_t nc)
+{
+    if (nr == 0 && nc == 0) return 0u;      // clean
+    if (nr == 0 || nc == 0) return 2u;      // checksum suspect
+    return 1u;                              // localised
+}
+
+template <bool IS_INT>
+__global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
+{
+    __shared__ int is_last;
+    const int bz = blockIdx.z, tid = threadIdx.x;
+    const int idx = blockIdx.x * 256 + tid;
+    const int M = a.M, N = a.N;
+    const float tol = IS_INT ? 0.f : a.tau[bz];
+    bool frow = false, fcol = false;
+    if (idx < M) {
+        uint32_t pred;
+        if (a.recombine) {
+            pred = recombine_terms<IS_INT>(a.rc_part + (long)bz * NTERM * M + idx, M, a.w_b + (long)bz * NTERM);
+            a.rc_pred[(long)bz * M + idx] = pred;
+        } else pred = a.rc_pred[(long)bz * M + idx];
+        frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], pred, tol);
+        a.row_flag[(long)bz * M + idx] = frow ? 1 : 0;
+    } else if (idx < M + N) {
+        const int j = idx - M;
+        uint32_t pred;
+        if (a.recombine) {
+            pred = recombine_terms<IS_INT>(a.cc_part + (long)bz * NTERM * N + j, N, a.w_a + (long)bz * NTERM);
+            a.cc_pred[(long)bz * N + j] = pred;
+        } else pred = a.cc_pred[(long)bz * N + j];
+        fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], pred, tol);
+        a.col_flag[(long)bz * N + j] = fcol ? 1 : 0;
+    }
+    if (a.recombine && blockIdx.x == 0 && tid == 0) {
+        // scalar a.b from the stripe corner (the paper's own single-number check value)
+        const uint32_t *sp = a.s_part + (long)bz * NTERM * NTERM;
+        if (IS_INT) {
+            uint32_t v = 0;
+            for (int t = 0; t < NTERM; ++t)
+                for (int u = 0; u < NTERM; ++u)
+                    if (8 * (t + u) < 32) v += sp[t * NTERM + u] << (8 * (t + u));
+            a.s_pred[bz] = v;
+        } else {
+            float v = 0.f;
+            for (int t = NTERM - 1; t >= 0; --t)
+                for (int u = NTERM - 1; u >= 0; --u)
+                    v += __uint_as_float(sp[t * NTERM + u]) * a.w_a[(long)bz * NTERM + t] * a.w_b[(long)bz * NTERM + u];
+            a.s_pred[bz] = __float_as_uint(v);
+        }
+    }
+    const unsigned nr = __syncthreads_count(frow);
+    const unsigned nc = __syncthreads_count(fcol);
+    if (tid == 0) {
+        if (nr) atomicAdd(a.ticket + 1, nr);
+        if (nc) atomicAdd(a.ticket + 2, nc);
+        __threadfence();
+        unsigned total = gridDim.x * gridDim.z;
+        unsigned t = atomicAdd(a.ticket, 1u);
+        is_last = (t == total - 1);
+    }
+    __syncthreads();
+    if (is_last && tid == 0) {
+        __threadfence();
+        uint32_t r = atomicExch(a.ticket + 1, 0u), c = atomicExch(a.ticket + 2, 0u);
+        atomicExch(a.ticket, 0u);
+        a.counts[0] = r;
+        a.counts[1] = c;
+        a.counts[2] = status_of(r, c);
+        a.counts[3] = 0u;
+        a.counts[4] = status_of(r, c);
+    }
+}
+
+hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, bool use_vobs, const Verdict &v,
+                          hipStream_t st)
+{
+    CmpArgs a;
+    a.cc_part = w.cc_part; a.rc_part = w.rc_part; a.s_part = w.s_part;
+    a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred; a.s_pred = w.s_pred;
+    a.cc_obs = use_vobs ? w.cc_vobs : w.cc_obs;
+    a.rc_obs = use_vobs ? w.rc_vobs : w.rc_obs;
+    a.w_a = w.w_a; a.w_b = w.w_b; a.tau = w.tau;
+    a.row_flag = v.row_flag; a.col_flag = v.col_flag; a.counts = v.counts;
+    a.ticket = w.cmp_ticket;
+    a.M = s.M; a.N = s.N; a.batch = s.batch;
+    a.recombine = use_vobs ? 0 : 1;
+    dim3 grid((unsigned)((s.M + s.N + 255) / 256), 1, (unsigned)s.batch);
+    if (dt == DT_I8) hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, a);
+    else             hipLaunchKernelGGL(compare_kernel<false>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ====================================================================== verify
+// Column and row sums of the stored C (streaming reduction, HBM-bound).
+struct VerArgs {
+    const uint8_t *C;
+    long ldc, sC;
+    int M, N;
+    int cw_log2, rpb, nwin, nrb;
+    uint32_t *cc_vobs, *rc_vobs;
+};
+
+// value q of a 16-byte chunk of stored C
+template <int DT> __device__ __forceinline__ typename Traits<DT>::acc_t out_elem(const i32x4 &v, int q)
+{
+    if (DT == DT_I8) return from_word<typename Traits<DT>::acc_t>((uint32_t)v[q]);
+    uint32_t w = (uint32_t)v[q >> 1];
+    uint32_t h = (q & 1) ? (w >> 16) : (w & 0xFFFFu);
+    if (DT == DT_BF16) return from_word<typename Traits<DT>::acc_t>(h << 16);
+    return from_word<typename Traits<DT>::acc_t>(__float_as_uint(f16_bits_to_f32(h)));
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void verify_kernel(VerArgs a)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int OS = T::OS, CE = 16 / OS;
+    __shared__ acc_t red[256 * CE];
+    const int tid = threadIdx.x, bz = blockIdx.z;
+    const int win = blockIdx.x % a.nwin, rb = blockIdx.x / a.nwin;
+    const int CW = 1 << a.cw_log2, RL = 256 >> a.cw_log2;
+    const int cx = tid & (CW - 1), ry = tid >> a.cw_log2;
+    const int col0 = (win * CW + cx) * CE;
+    const bool colok = col0 < a.N;
+    const int nvalid = a.N - col0;
+    const uint8_t *Cb = a.C + (long)bz * a.sC * OS;
+    const int rbeg = rb * a.rpb, rend = min(rbeg + a.rpb, a.M);
+    const int iters = (a.rpb + RL - 1) / RL;
+    acc_t colacc[CE];
+#pragma unroll
+    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
+    for (int it = 0; it < iters; ++it) {
+        const int r = rbeg + ry + it * RL;
+        const bool ok = colok && r < rend;
+        acc_t s = T::zero();
+        if (ok) {
+            i32x4 v = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
+#pragma unroll
+            for (int q = 0; q < CE; ++q) {
+                if (q < nvalid) {
+                    acc_t x = out_elem<DT>(v, q);
+                    colacc[q] = add_t(colacc[q], x);
+                    s = add_t(s, x);
+                }
+            }
+        }
+        for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+        if (cx == 0 && r < rend) atomic_add_word(a.rc_vobs + (long)bz * a.M + r, s);
+    }
+#pragma unroll
+    for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
+    __syncthreads();
+    if (ry == 0 && colok) {
+#pragma unroll
+        for (int q = 0; q < CE; ++q) {
+            acc_t t = red[cx * CE + q];
+            for (int y = 1; y < RL; ++y) t = add_t(t, red[(y * CW + cx) * CE + q]);
+            if (q < nvalid) atomic_add_word(a.cc_vobs + (long)bz * a.N + col0 + q, t);
+        }
+    }
+}
+
+hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st)
+{
+    VerArgs a;
+    a.C = (const uint8_t *)C; a.ldc = s.ldc; a.sC = s.sC; a.M = s.M; a.N = s.N;
+    a.cc_vobs = w.cc_vobs; a.rc_vobs = w.rc_vobs;
+    const int ce = 16 / out_size(dt);
+    int chunks = (s.N + ce - 1) / ce;
+    int lg = 0;
+    while ((1 << lg) < chunks && lg < 6) ++lg;
+    if (lg < 3) lg = 3;
+    a.cw_log2 = lg;
+    int CW = 1 << lg, RL = 256 / CW;
+    a.nwin = (chunks + CW - 1) / CW;
+    int rpb = RL * 16;
+    if (rpb > s.M) rpb = ((s.M + RL - 1) / RL) * RL;
+    a.rpb = rpb;
+    a.nrb = (s.M + rpb - 1) / rpb;
+    dim3 grid((unsigned)(a.nwin * a.nrb), 1, (unsigned)s.batch);
+    switch (dt) {
+    case DT_I8:   hipLaunchKernelGGL(verify_kernel<DT_I8>, grid, dim3(256), 0, st, a); break;
+    case DT_BF16: hipLaunchKernelGGL(verify_kernel<DT_BF16>, grid, dim3(256), 0, st, a); break;
+    case DT_F16:  hipLaunchKernelGGL(verify_kernel<DT_F16>, grid, dim3(256), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ===================================================================== correct
+// Step 1: list flagged rows / columns per batch item, map their cross product to CT x CT tiles.
+struct LocArgs {
+    const uint8_t *row_flag, *col_flag;
+    int M, N;
+    int32_t *fix_tiles;
+    uint32_t *fix_count;
+};
+
+__global__ __launch_bounds__(256) void locate_kernel(LocArgs a)
+{
+    __shared__ int rows[MAX_LIST], cols[MAX_LIST];
+    __shared__ int nr, nc;
+    const int bz = blockIdx.x, tid = threadIdx.x;
+    if (tid == 0) { nr = 0; nc = 0; }
+    __syncthreads();
+    for (int i = tid; i < a.M; i += 256)
+        if (a.row_flag[(long)bz * a.M + i]) {
+            int p = atomicAdd(&nr, 1);
+            if (p < MAX_LIST) rows[p] = i / CT;
+        }
+    for (int j = tid; j < a.N; j += 256)
+        if (a.col_flag[(long)bz * a.N + j]) {
+            int p = atomicAdd(&nc, 1);
+            if (p < MAX_LIST) cols[p] = j / CT;
+        }
+    __syncthreads();
+    if (tid != 0) return;
+    if (nr == 0 || nc == 0) return;                     // clean, or one-sided: nothing to recompute
+    bool overflow = nr > MAX_LIST || nc > MAX_LIST;
+    int r = nr > MAX_LIST ? MAX_LIST : nr, c = nc > MAX_LIST ? MAX_LIST : nc;
+    // unique tile rows / tile cols (lists are short under the single-error model)
+    int ur = 0, uc = 0;
+    for (int i = 0; i < r; ++i) {
+        bool dup = false;
+        for (int q = 0; q < ur; ++q) dup |= (rows[q] == rows[i]);
+        if (!dup) rows[ur++] = rows[i];
+    }
+    for (int j = 0; j < c; ++j) {
+        bool dup = false;
+        for (int q = 0; q < uc; ++q) dup |= (cols[q] == cols[j]);
+        if (!dup) cols[uc++] = cols[j];
+    }
+    for (int i = 0; i < ur; ++i)
+        for (int j = 0; j < uc; ++j) {
+            unsigned p = atomicAdd(a.fix_count, 1u);
+            if (p < (unsigned)MAX_FIX_TILES) {
+                a.fix_tiles[3 * p + 0] = bz;
+                a.fix_tiles[3 * p + 1] = rows[i];
+                a.fix_tiles[3 * p + 2] = cols[j];
+            } else overflow = true;
+        }
+    if (overflow) atomicExch(a.fix_count + 1, 1u);
+}
+
+// Step 2: one wave recomputes one CT x CT tile of C over the whole K, with the same MFMA
+// instruction and the same ascending-k order as the GEMM kernel.
+struct FixArgs {
+    const uint8_t *A, *B;
+    uint8_t *C;
+    int M, N, K, transB;
+    long lda, ldb, ldc, sA, sB, sC;
+    const int32_t *fix_tiles;
+    const uint32_t *fix_count;
+};
+
+template <int DT>
+__global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
+{
+    using T = Traits<DT>;
+    typedef typename T::accv_t accv_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    unsigned n = a.fix_count[0];
+    if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
+    if (blockIdx.x >= n) return;
+    const int bz = a.fix_tiles[3 * blockIdx.x], tr = a.fix_tiles[3 * blockIdx.x + 1],
+              tc = a.fix_tiles[3 * blockIdx.x + 2];
+    const int lane = threadIdx.x, l32 = lane & 31, lh = lane >> 5;
+    const int row = tr * CT + l32, col = tc * CT + l32;
+    const uint8_t *Ab = a.A + (long)bz * a.sA * ES, *Bb = a.B + (long)bz * a.sB * ES;
+    const int K = a.K;
+    accv_t acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = T::zero();
+    const int steps = (K + 2 * CE - 1) / (2 * CE);
+    for (int ks = 0; ks < steps; ++ks) {
+        const int kb = ks * 2 * CE + lh * CE;
+        i32x4 av = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
+        if (row < a.M && kb < K) {
+            av = *reinterpret_cast<const i32x4 *>(Ab + ((long)row * a.lda + kb) * ES);
+            if (kb + CE > K) av = mask_chunk(av, (K - kb) * ES);
+        }
+        if (col < a.N && kb < K) {
+            if (a.transB) {
+                bv = *reinterpret_cast<const i32x4 *>(Bb + ((long)col * a.ldb + kb) * ES);
+                if (kb + CE > K) bv = mask_chunk(bv, (K - kb) * ES);
+            } else {
+                // B stored K x N: gather one column element per k
+                uint32_t wds[4] = {0, 0, 0, 0};
+#pragma unroll
+                for (int q = 0; q < CE; ++q) {
+                    int k = kb + q;
+                    if (k < K) {
+                        if (ES == 2) {
+                            uint32_t h = *reinterpret_cast<const uint16_t *>(Bb + ((long)k * a.ldb + col) * 2);
+                            wds[q >> 1] |= h << (16 * (q & 1));
+                        } else {
+                            uint32_t h = *(Bb + ((long)k * a.ldb + col));
+                            wds[q >> 2] |= h << (8 * (q & 3));
+                        }
+                    }
+                }
+                bv[0] = (int)wds[0]; bv[1] = (int)wds[1]; bv[2] = (int)wds[2]; bv[3] = (int)wds[3];
+            }
+        }
+        acc = T::mfma(av, bv, acc);
+    }
+    uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int gr = tr * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
+        if (gr < a.M && col < a.N) T::store_c(Cb, (long)gr * a.ldc + col, acc[i]);
+    }
+}
+
+// Step 3: re-sum the rows and columns a recomputed tile touches, re-flag them.
+struct RecheckArgs {
+    const uint8_t *C;
+    int M, N;
+    long ldc, sC;
+    const int32_t *fix_tiles;
+    const uint32_t *fix_count;
+    const uint32_t *cc_pred, *rc_pred;
+    const float *tau;
+    uint8_t *row_flag, *col_flag;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void recheck_kernel(RecheckArgs a)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    __shared__ acc_t red[256];
+    unsigned n = a.fix_count[0];
+    if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
+    if (blockIdx.x >= n) return;
+    const int bz = a.fix_tiles[3 * blockIdx.x], tr = a.fix_tiles[3 * blockIdx.x + 1],
+              tc = a.fix_tiles[3 * blockIdx.x + 2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
+    const float tol = T::IS_INT ? 0.f : a.tau[bz];
+    // rows: each wave takes 8 of the 32 rows
+    for (int rr = wave; rr < CT; rr += 4) {
+        const int row = tr * CT + rr;
+        acc_t s = T::zero();
+        if (row < a.M)
+            for (int j = lane; j < a.N; j += 64) s = add_t(s, T::load_c(Cb, (long)row * a.ldc + j));
+        s = wave_sum(s);
+        if (lane == 0 && row < a.M) {
+            bool f = mismatch<T::IS_INT>(as_word(s), a.rc_pred[(long)bz * a.M + row], tol);
+            a.row_flag[(long)bz * a.M + row] = f ? 1 : 0;
+        }
+    }
+    // columns: thread (cl, rl) sums every 8th row of column cl
+    const int cl = tid & 31, rl = tid >> 5;
+    const int col = tc * CT + cl;
+    acc_t s = T::zero();
+    if (col < a.N)
+        for (int i = rl; i < a.M; i += 8) s = add_t(s, T::load_c(Cb, (long)i * a.ldc + col));
+    red[tid] = s;
+    __syncthreads();
+    if (rl == 0 && col < a.N) {
+        for (int y = 1; y < 8; ++y) s = add_t(s, red[y * 32 + cl]);
+        bool f = mismatch<T::IS_INT>(as_word(s), a.cc_pred[(long)bz * a.N + col], tol);
+        a.col_flag[(long)bz * a.N + col] = f ? 1 : 0;
+    }
+}
+
+// Step 4: recount flags, set status.
+struct CountArgs {
+    const uint8_t *row_flag, *col_flag;
+    long nrows, ncols;            // batch*M, batch*N
+    uint32_t *counts;
+    uint32_t *ticket;             // [3], self-cleaning
+    uint32_t *fix_count;
+};
+
+__global__ __launch_bounds__(256) void recount_kernel(CountArgs a)
+{
+    __shared__ int is_last;
+    const int tid = threadIdx.x;
+    long step = (long)gridDim.x * 256;
+    int r = 0, c = 0;
+    for (long i = (long)blockIdx.x * 256 + tid; i < a.nrows; i += step) r += a.row_flag[i] ? 1 : 0;
+    for (long i = (long)blockIdx.x * 256 + tid; i < a.ncols; i += step) c += a.col_flag[i] ? 1 : 0;
+    r = wave_sum(r);
+    c = wave_sum(c);
+    if ((tid & 63) == 0) {
+        if (r) atomicAdd(a.ticket + 1, (unsigned)r);
+        if (c) atomicAdd(a.ticket + 2, (unsigned)c);
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        unsigned t = atomicAdd(a.ticket, 1u);
+        is_last = (t == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (is_last && tid == 0) {
+        __threadfence();
+        uint32_t nr = atomicExch(a.ticket + 1, 0u), nc = atomicExch(a.ticket + 2, 0u);
+        atomicExch(a.ticket, 0u);
+        uint32_t tiles = a.fix_count[0], over = a.fix_count[1];
+        uint32_t before = a.counts[2];
+        a.counts[0] = nr;
+        a.counts[1] = nc;
+        a.counts[2] = over ? 3u : status_of(nr, nc);
+        a.counts[3] = tiles > (uint32_t)MAX_FIX_TILES ? (uint32_t)MAX_FIX_TILES : tiles;
+        a.counts[4] = before;
+    }
+}
+
+hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
+                          const Workspace &w, const Verdict &v, hipStream_t st)
+{
+    hipError_t e = launch_zero(w.fix_count, 2, st);
+    if (e != hipSuccess) return e;
+    LocArgs l;
+    l.row_flag = v.row_flag; l.col_flag = v.col_flag; l.M = s.M; l.N = s.N;
+    l.fix_tiles = w.fix_tiles; l.fix_count = w.fix_count;
+    hipLaunchKernelGGL(locate_kernel, dim3((unsigned)s.batch), dim3(256), 0, st, l);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+
+    FixArgs f;
+    f.A = (const uint8_t *)A; f.B = (const uint8_t *)B; f.C = (uint8_t *)C;
+    f.M = s.M; f.N = s.N; f.K = s.K; f.transB = s.transB;
+    f.lda = s.lda; f.ldb = s.ldb; f.ldc = s.ldc; f.sA = s.sA; f.sB = s.sB; f.sC = s.sC;
+    f.fix_tiles = w.fix_tiles; f.fix_count = w.fix_count;
+    RecheckArgs r;
+    r.C = (const uint8_t *)C; r.M = s.M; r.N = s.N; r.ldc = s.ldc; r.sC = s.sC;
+    r.fix_tiles = w.fix_tiles; r.fix_count = w.fix_count;
+    r.cc_pred = w.cc_pred; r.rc_pred = w.rc_pred; r.tau = w.tau;
+    r.row_flag = v.row_flag; r.col_flag = v.col_flag;
+    switch (dt) {
+    case DT_I8:
+        hipLaunchKernelGGL(recompute_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
+        hipLaunchKernelGGL(recheck_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
+        break;
+    case DT_BF16:
+        hipLaunchKernelGGL(recompute_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
+        hipLaunchKernelGGL(recheck_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
+        break;
+    case DT_F16:
+        hipLaunchKernelGGL(recompute_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
+        hipLaunchKernelGGL(recheck_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
+        break;
+    default: return hipErrorInvalidValue;
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    CountArgs c;
+    c.row_flag = v.row_flag; c.col_flag = v.col_flag;
+    c.nrows = (long)s.batch * s.M; c.ncols = (long)s.batch * s.N;
+    c.counts = v.counts; c.ticket = w.cmp_ticket; c.fix_count = w.fix_count;
+    long total = c.nrows > c.ncols ? c.nrows : c.ncols;
+    unsigned blocks = (unsigned)((total + 256 * 16 - 1) / (256 * 16));
+    if (blocks < 1) blocks = 1;
+    if (blocks > 512) blocks = 512;
+    hipLaunchKernelGGL(recount_kernel, dim3(blocks), dim3(256), 0, st, c);
+    return hipGetLastError();
+}
+
+// ====================================================================== inject
+__global__ void flip_kernel(uint8_t *C, long idx, int os, int bit)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    if (os == 4) {
+        uint32_t *p = reinterpret_cast<uint32_t *>(C) + idx;
+        *p ^= (1u << bit);
+    } else {
+        uint16_t *p = reinterpret_cast<uint16_t *>(C) + idx;
+        *p = (uint16_t)(*p ^ (uint16_t)(1u << bit));
+    }
+}
+
+hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,
+                       hipStream_t st)
+{
+    long idx = batch_idx * s.sC + row * s.ldc + col;
+    hipLaunchKernelGGL(flip_kernel, dim3(1), dim3(64), 0, st, (uint8_t *)C, idx, out_size(dt), bit);
+    return hipGetLastError();
+}
+
+}  // namespace abft

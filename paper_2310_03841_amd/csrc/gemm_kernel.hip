@@ -1,0 +1,357 @@
+// Protected GEMM kernel for gfx950: C = A * B with the encoded checksum stripe
+// carried as extra operand rows (of A) and columns (of B), and the observed
+// row / column sums of C taken from the accumulators in the epilogue.
+//
+// Method: classic row/column ABFT as cited by the paper (Sec. I, Sec. II-B),
+// with the paper's epilogue fusion of the output checksum (Sec. IV-C memory
+// paragraph; Sec. V "Optimizations" (2)).
+//
+// Logical problem seen by the kernel (PROT = true):
+//     rows    0 .. M-1        of A           | rows M .. M+NTERM-1  = stripe_a (terms of e^T A)
+//     columns 0 .. N-1        of B           | cols N .. N+NTERM-1  = stripe_b (terms of B e)
+// so the output has an extra NTERM rows (-> cc_part: terms of (e^T A) B), an
+// extra NTERM columns (-> rc_part: terms of A (B e)) and a corner (-> s_part:
+// terms of the scalar a.b).  Only the M x N block is written to C and summed
+// into cc_obs / rc_obs.
+//
+// Tiling: one workgroup of 4 waves computes a BM x BN tile; each wave owns a
+// (BM/2) x (BN/2) sub-tile as 32x32 MFMA blocks.  K advances in slabs of 128
+// bytes per row, double-buffered in LDS.  LDS rows are 128 bytes, stored as
+// eight 16-byte chunks with chunk index XOR (row & 7) so that both the
+// row-contiguous writes and the MFMA operand reads are bank-conflict free.
+#include "abft_device.h"
+
+namespace abft {
+
+struct GemmArgs {
+    const uint8_t *A, *B;
+    uint8_t *C;
+    const uint8_t *SA, *SB;                       // [batch][NTERM][Kp] operand elements
+    uint32_t *cc_part, *rc_part, *s_part;         // raw stripe outputs
+    uint32_t *cc_obs, *rc_obs;                    // observed sums (atomics)
+    int M, N, K, Kp;
+    long lda, ldb, ldc, sA, sB, sC;               // elements
+    int tiles_m, tiles_n;
+    int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
+};
+
+template <int DT, int BM, int BN, bool PROT, bool TRANSB>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    typedef typename T::accv_t accv_t;
+    constexpr int ES = T::ES;
+    constexpr int CE = 16 / ES;                  // elements per 16-byte chunk
+    constexpr int KE = SLAB_BYTES / ES;          // elements of K per slab
+    constexpr int TM = BM / 2, TN = BN / 2;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int PA = BM / 32, PB = BN / 32;    // chunks per thread per slab
+    constexpr int BUF = (BM + BN) * SLAB_BYTES;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int bz = blockIdx.z;
+
+    const int tm_idx = blockIdx.x % g.tiles_m;
+    const int tn_idx = blockIdx.x / g.tiles_m;
+    const int m0 = tm_idx * BM, n0 = tn_idx * BN;
+    const int M = g.M, N = g.N, K = g.K;
+    const int Mx = PROT ? M + NTERM : M;
+    const int Nx = PROT ? N + NTERM : N;
+
+    const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
+    const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
+    const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
+    const uint8_t *SBb = PROT ? g.SB + (long)bz * NTERM * g.Kp * ES : nullptr;
+
+    // ---- per-thread row sources: chunk column c of rows r0 + 32 p
+    const int c = tid & 7, r0 = tid >> 3;
+    const uint8_t *asrc[PA];
+    const uint8_t *bsrc[PB];
+    bool btail[PB];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        int r = m0 + r0 + 32 * p;
+        asrc[p] = r < M ? Ab + (long)r * g.lda * ES
+                        : ((PROT && r < Mx) ? SAb + (long)(r - M) * g.Kp * ES : nullptr);
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        int r = n0 + r0 + 32 * p;
+        btail[p] = r >= N;
+        const uint8_t *stripe = (PROT && r >= N && r < Nx) ? SBb + (long)(r - N) * g.Kp * ES : nullptr;
+        if (TRANSB) bsrc[p] = r < N ? Bb + (long)r * g.ldb * ES : stripe;
+        else        bsrc[p] = stripe;
+    }
+    const bool tile_has_btail = (n0 + BN > N);
+
+    // ---- accumulators
+    accv_t acc[MI][NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mi][ni][i] = T::zero();
+    bool mact[MI], nact[NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) mact[mi] = (m0 + wm * TM + mi * 32) < Mx;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) nact[ni] = (n0 + wn * TN + ni * 32) < Nx;
+
+    i32x4 areg[PA], breg[PB];
+    const int nslab = (K + KE - 1) / KE;
+    const bool ragged_k = (K % KE) != 0;
+
+    auto load_rowmajor = [&](const uint8_t *const *src, i32x4 *regs, int P, int k0, bool tail) {
+        const int kb = k0 + c * CE;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            i32x4 v = {0, 0, 0, 0};
+            if (src[p] != nullptr && (!tail || kb < K)) {
+                v = *reinterpret_cast<const i32x4 *>(src[p] + (long)kb * ES);
+                if (tail && kb + CE > K) v = mask_chunk(v, (K - kb) * ES);
+            }
+            regs[p] = v;
+        }
+    };
+    auto store_rowmajor = [&](uint8_t *dst, const i32x4 *regs, int P, const bool *only) {
+        const int sw = (c ^ (r0 & 7)) * 16;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if (only == nullptr || only[p])
+                *reinterpret_cast<i32x4 *>(dst + (r0 + 32 * p) * SLAB_BYTES + sw) = regs[p];
+        }
+    };
+    // B stored K x N: chunks run along n; they are transposed while written to LDS.
+    constexpr int NCH = BN / CE;
+    i32x4 bnn[PB];
+    auto load_b_nn = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            int q = tid + 256 * p;
+            int nch = q % NCH, kk = q / NCH;
+            int k = k0 + kk, nst = n0 + nch * CE;
+            i32x4 v = {0, 0, 0, 0};
+            if (k < K && nst < N) v = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * g.ldb + nst) * ES);
+            bnn[p] = v;
+        }
+    };
+    auto store_b_nn = [&](uint8_t *dst) {
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            int q = tid + 256 * p;
+            int nch = q % NCH, kk = q / NCH;
+            int kc = kk / CE, ke = kk % CE;
+#pragma unroll
+            for (int e = 0; e < CE; ++e) {
+                int nl = nch * CE + e;
+                if (n0 + nl < N) {
+                    uint8_t *d = dst + nl * SLAB_BYTES + ((kc ^ (nl & 7)) * 16) + ke * ES;
+                    if (ES == 2) {
+                        uint32_t w = (uint32_t)bnn[p][e >> 1];
+                        *reinterpret_cast<uint16_t *>(d) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+                    } else {
+                        uint32_t w = (uint32_t)bnn[p][e >> 2];
+                        *d = (uint8_t)(w >> (8 * (e & 3)));
+                    }
+                }
+            }
+        }
+    };
+
+    auto load_slab = [&](int s) {
+        const int k0 = s * KE;
+        const bool tail = ragged_k && (s == nslab - 1);
+        load_rowmajor(asrc, areg, PA, k0, tail);
+        if (TRANSB) {
+            load_rowmajor(bsrc, breg, PB, k0, tail);
+        } else {
+            load_b_nn(k0);
+            if (tile_has_btail) load_rowmajor(bsrc, breg, PB, k0, tail);
+        }
+    };
+    auto store_slab = [&](int buf) {
+        uint8_t *sA = smem + buf * BUF;
+        uint8_t *sB = sA + BM * SLAB_BYTES;
+        store_rowmajor(sA, areg, PA, nullptr);
+        if (TRANSB) {
+            store_rowmajor(sB, breg, PB, nullptr);
+        } else {
+            store_b_nn(sB);
+            if (tile_has_btail) store_rowmajor(sB, breg, PB, btail);
+        }
+    };
+    auto compute = [&](int buf) {
+        const uint8_t *sA = smem + buf * BUF;
+        const uint8_t *sB = sA + BM * SLAB_BYTES;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
+            i32x4 af[MI], bf[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                af[mi] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + mi * 32 + l32) * SLAB_BYTES + sw);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                bf[ni] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + ni * 32 + l32) * SLAB_BYTES + sw);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    if (mact[mi] && nact[ni]) acc[mi][ni] = T::mfma(af[mi], bf[ni], acc[mi][ni]);
+        }
+    };
+
+    // ---- main loop: global -> registers -> LDS, two LDS buffers, one barrier per slab
+    load_slab(0);
+    store_slab(0);
+    __syncthreads();
+    for (int s = 0; s < nslab; ++s) {
+        if (s + 1 < nslab) load_slab(s + 1);
+        compute(s & 1);
+        if (s + 1 < nslab) store_slab((s + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue
+    acc_t *rs_part = reinterpret_cast<acc_t *>(smem);          // [2][BM] by wave column
+    acc_t *cs_part = rs_part + 2 * BM;                         // [2][BN] by wave row
+    uint8_t *Cb = g.C + (long)bz * g.sC * T::OS;
+    const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
+                          g.inj_col >= n0 && g.inj_col < n0 + BN;
+
+    acc_t colsum[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) colsum[ni] = T::zero();
+
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        acc_t rowsum[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) rowsum[i] = T::zero();
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int gc = n0 + wn * TN + ni * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int gr = m0 + wm * TM + mi * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
+                acc_t v = acc[mi][ni][i];
+                if (inj_here && gr == g.inj_row && gc == g.inj_col)
+                    v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
+                if (gr < M && gc < N) {
+                    T::store_c(Cb, (long)gr * g.ldc + gc, v);
+                    if (PROT) {
+                        colsum[ni] = add_t(colsum[ni], v);
+                        rowsum[i] = add_t(rowsum[i], v);
+                    }
+                } else if (PROT) {
+                    if (gr >= M && gr < Mx) {
+                        if (gc < N)
+                            g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
+                        else if (gc < Nx)
+                            g.s_part[(long)bz * NTERM * NTERM + (gr - M) * NTERM + (gc - N)] = as_word(v);
+                    } else if (gr < M && gc >= N && gc < Nx) {
+                        g.rc_part[((long)bz * NTERM + (gc - N)) * M + gr] = as_word(v);
+                    }
+                }
+            }
+        }
+        if (PROT) {
+            // row sums: reduce over the 32 lanes that hold one row's columns
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                acc_t t = half_wave_sum(rowsum[i]);
+                if (l32 == 0) rs_part[wn * BM + wm * TM + mi * 32 + 8 * (i >> 2) + 4 * lh + (i & 3)] = t;
+            }
+        }
+    }
+    if (PROT) {
+        // column sums: the two half-waves hold different rows of the same columns
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            acc_t t = add_t(colsum[ni], __shfl_xor(colsum[ni], 32));
+            if (lh == 0) cs_part[wm * BN + wn * TN + ni * 32 + l32] = t;
+        }
+        __syncthreads();
+        for (int t = tid; t < BM + BN; t += 256) {
+            if (t < BM) {
+                int gr = m0 + t;
+                if (gr < M) atomic_add_word(g.rc_obs + (long)bz * M + gr, add_t(rs_part[t], rs_part[BM + t]));
+            } else {
+                int gc = n0 + (t - BM);
+                if (gc < N)
+                    atomic_add_word(g.cc_obs + (long)bz * N + gc, add_t(cs_part[t - BM], cs_part[BN + t - BM]));
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+template <int DT, int BM, int BN, bool PROT, bool TRANSB>
+static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
+{
+    constexpr int smem = 2 * (BM + BN) * SLAB_BYTES;
+    auto kern = gemm_kernel<DT, BM, BN, PROT, TRANSB>;
+    static bool attr_done = false;
+    if (!attr_done && smem > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
+    return hipGetLastError();
+}
+
+template <int DT, int BM, int BN>
+static hipError_t launch_cfg(bool protect, bool transB, GemmArgs &g, int batch, hipStream_t st)
+{
+    const int Mx = protect ? g.M + NTERM : g.M, Nx = protect ? g.N + NTERM : g.N;
+    g.tiles_m = (Mx + BM - 1) / BM;
+    g.tiles_n = (Nx + BN - 1) / BN;
+    if (protect) return transB ? launch_one<DT, BM, BN, true, true>(g, batch, st)
+                               : launch_one<DT, BM, BN, true, false>(g, batch, st);
+    return transB ? launch_one<DT, BM, BN, false, true>(g, batch, st)
+                  : launch_one<DT, BM, BN, false, false>(g, batch, st);
+}
+
+void gemm_tile_shape(int, const Shape &, int *tm, int *tn)
+{
+    *tm = 128;
+    *tn = 128;
+}
+
+hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
+                       const Workspace &w, const InjectArm &arm, hipStream_t st)
+{
+    GemmArgs g;
+    g.A = (const uint8_t *)A;
+    g.B = (const uint8_t *)B;
+    g.C = (uint8_t *)C;
+    g.SA = w.stripe_a;
+    g.SB = w.stripe_b;
+    g.cc_part = w.cc_part;
+    g.rc_part = w.rc_part;
+    g.s_part = w.s_part;
+    g.cc_obs = w.cc_obs;
+    g.rc_obs = w.rc_obs;
+    g.M = s.M; g.N = s.N; g.K = s.K; g.Kp = s.Kp;
+    g.lda = s.lda; g.ldb = s.ldb; g.ldc = s.ldc;
+    g.sA = s.sA; g.sB = s.sB; g.sC = s.sC;
+    g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
+    const bool tb = s.transB != 0;
+    switch (dt) {
+    case DT_I8:   return launch_cfg<DT_I8, 128, 128>(protect, tb, g, s.batch, st);
+    case DT_BF16: return launch_cfg<DT_BF16, 128, 128>(protect, tb, g, s.batch, st);
+    case DT_F16:  return launch_cfg<DT_F16, 128, 128>(protect, tb, g, s.batch, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace abft

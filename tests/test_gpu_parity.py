@@ -1,0 +1,263 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by
+element on the same seeded inputs.
+
+Bars: integer C, checksums (in Z/2^32), flags and counts bit-exact; bf16/fp16 C within 1e-2 of
+max|C_ref| (and within one rounding of the storage type element-wise); fp32 checksums within a
+small fraction of the tolerance tau = 1e-3 K max|A| max|B|; flags equal except for flips whose
+|delta| lies within a factor two of tau."""
+import numpy as np
+import pytest
+import torch
+
+import abft_inputs as gen
+import oracle as orc
+import paper_2310_03841_amd as ab
+from gpu_util import Run
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = ab.abft_create(max_rows=16384, max_cols=16384, max_depth=16384, max_batch=16)
+    yield c
+    ab.abft_destroy(c)
+
+
+def ring(x):
+    return np.mod(np.asarray(x, dtype=np.int64), 2 ** 32).astype(np.uint32)
+
+
+def oracle_items(dtype, A, B, trans_b):
+    return [orc.protected_gemm(A[b], B[b], dtype, trans_b) for b in range(A.shape[0])]
+
+
+def check_clean(run: Run, P, fused=True):
+    """C, checksums, flags and counts of a clean protected GEMM against the oracle items P."""
+    C = run.C()
+    rf, cf = run.flags()
+    cnt = run.cnt()
+    a = run.ws(ab.ABFT_WS_A_SUM)
+    b = run.ws(ab.ABFT_WS_B_SUM)
+    ccp, rcp = run.ws(ab.ABFT_WS_CC_PRED), run.ws(ab.ABFT_WS_RC_PRED)
+    cco, rco = run.ws(ab.ABFT_WS_CC_OBS), run.ws(ab.ABFT_WS_RC_OBS)
+    sp = run.ws(ab.ABFT_WS_S_PRED)
+    for bi, p in enumerate(P):
+        if run.dtype == "i8":
+            assert np.array_equal(C[bi], p.C_stored), f"C differs (batch {bi})"
+            assert np.array_equal(a[bi].view(np.uint32), ring(p.a))
+            assert np.array_equal(b[bi].view(np.uint32), ring(p.b))
+            assert np.array_equal(ccp[bi].view(np.uint32), ring(p.cc_pred))
+            assert np.array_equal(rcp[bi].view(np.uint32), ring(p.rc_pred))
+            assert np.array_equal(cco[bi].view(np.uint32), ring(p.cc_pred))     # identity: obs == pred
+            assert np.array_equal(rco[bi].view(np.uint32), ring(p.rc_pred))
+            assert sp[bi, 0].view(np.uint32) == ring(p.s_pred)
+        else:
+            Cg = orc.decode(C[bi], run.dtype)
+            scale = np.max(np.abs(p.C_ref))
+            assert np.max(np.abs(Cg - p.C_ref)) <= 1e-2 * scale
+            ulp = 2.0 ** -8 if run.dtype == "bf16" else 2.0 ** -11
+            assert np.all(np.abs(Cg - p.C_ref) <= ulp * np.abs(p.C_ref) + 2e-6 * scale + 1e-7)
+            tol = 1e-2 * p.tau
+            K = run.K
+            assert np.max(np.abs(a[bi] - p.a)) <= 1e-5 * run.M * p.max_a
+            assert np.max(np.abs(b[bi] - p.b)) <= 1e-5 * run.N * p.max_b
+            assert np.max(np.abs(ccp[bi] - p.cc_pred)) <= tol * max(1.0, np.sqrt(run.M))
+            assert np.max(np.abs(rcp[bi] - p.rc_pred)) <= tol * max(1.0, np.sqrt(run.N))
+            cc0, rc0, _ = orc.observe(p.C_ref)
+            assert np.max(np.abs(cco[bi] - cc0)) <= tol * max(1.0, np.sqrt(run.M))
+            assert np.max(np.abs(rco[bi] - rc0)) <= tol * max(1.0, np.sqrt(run.N))
+            assert abs(sp[bi, 0] - p.s_pred) <= 1e-4 * K * run.M * run.N * p.max_a * p.max_b
+            tau_g = run.ws(ab.ABFT_WS_TAU)[bi, 0]
+            assert tau_g == pytest.approx(p.tau, rel=1e-5)
+    assert not rf.any() and not cf.any()
+    assert cnt[0] == 0 and cnt[1] == 0 and cnt[2] == ab.ABFT_CLEAN
+
+
+SHAPES = [
+    # (M, N, K, batch, trans_b)
+    (197, 768, 768, 1, True),      # ViT-B projection at batch 1 (the small configuration)
+    (300, 200, 264, 1, True),      # several tiles, ragged M/N, ragged K slab
+    (257, 130, 72, 2, True),
+    (128, 128, 128, 1, True),      # tile-exact: stripe needs an extra tile row and column
+    (1, 1, 1, 1, True),
+    (197, 197, 64, 3, True),       # per-head Q K^T
+    (197, 64, 197, 3, False),      # per-head attn V (B stored K x N)
+    (150, 200, 136, 2, False),
+]
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", SHAPES)
+def test_clean_gemm_matches_oracle(ctx, dtype, M, N, K, batch, trans_b):
+    a_kind = "softmax" if (not trans_b and dtype != "i8") else "act"
+    A, B = gen.gen_operands(dtype, M, N, K, 101 + M, 202 + N, trans_b=trans_b, batch=batch,
+                            a_kind=a_kind, b_kind="weight" if batch == 1 else "act")
+    print(f"case dtype={dtype} M={M} N={N} K={K} batch={batch} trans_b={trans_b}", flush=True)
+    run = Run(ctx, dtype, A, B, trans_b)
+    P = oracle_items(dtype, A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT)
+    check_clean(run, P)
+    C_prot = run.C().copy()
+    # unprotected mode: the same C, bit for bit
+    run.dC.fill_(0)
+    run.gemm(ab.ABFT_OFF)
+    assert np.array_equal(run.C(), C_prot)
+    # pad columns of C (between N and ldc) are never written
+    if run.ldc != run.N:
+        run.dC.fill_(0x1111)
+        run.gemm(ab.ABFT_DETECT)
+        pad = run.dC.cpu().numpy()[:, :, run.N:]
+        assert np.all(pad == 0x1111)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+def test_cached_b_checksum(ctx, dtype):
+    M, N, K = 200, 136, 320
+    A, B = gen.gen_operands(dtype, M, N, K, 7, 8, trans_b=True)
+    A2, _ = gen.gen_operands(dtype, M, N, K, 9, 8, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
+    assert ab.abft_encode_b(ctx, run.dB, run.code, run.shape) == ab.ABFT_OK
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)
+    check_clean(run, oracle_items(dtype, A, B, True))
+    run2 = Run(ctx, dtype, A2, B, True)
+    run2.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)     # B encoding left by the previous call
+    check_clean(run2, oracle_items(dtype, A2, B, True))
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 768, 768, 1, True), (130, 70, 100, 2, False)])
+def test_stored_flip_verify_correct(ctx, dtype, M, N, K, batch, trans_b):
+    A, B = gen.gen_operands(dtype, M, N, K, 31, 32, trans_b=trans_b, batch=batch)
+    run = Run(ctx, dtype, A, B, trans_b)
+    P = oracle_items(dtype, A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT)
+    C_clean = run.C().copy()
+    run.verify()
+    rf, cf = run.flags()
+    assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+    flips = gen.gen_flips(40, M, N, dtype, 555, batch=batch)
+    n_border = 0
+    for (bi, i, j, bit) in flips:
+        bi, i, j, bit = int(bi), int(i), int(j), int(bit)
+        print(f"flip dtype={dtype} b={bi} i={i} j={j} bit={bit}", flush=True)
+        run.inject(bi, i, j, bit)
+        run.verify()
+        rf, cf = run.flags()
+        cnt = run.cnt()
+        X = orc.flip(P[bi].C_stored, i, j, bit)
+        orf, ocf, E, status, _, _ = orc.check(P[bi], X)
+        if dtype == "i8":
+            assert np.array_equal(run.C()[bi], X)
+        else:
+            with np.errstate(all="ignore"):
+                delta = abs(orc.decode(X, dtype)[i, j] - orc.decode(P[bi].C_stored, dtype)[i, j])
+            if P[bi].tau / 2 <= delta <= 2 * P[bi].tau:
+                n_border += 1
+                run.dC.copy_(torch.from_numpy(_with_ld(C_clean, run)).to("cuda"))
+                continue
+        want_rf = np.zeros((batch, M), bool)
+        want_cf = np.zeros((batch, N), bool)
+        want_rf[bi], want_cf[bi] = orf, ocf
+        assert np.array_equal(rf, want_rf) and np.array_equal(cf, want_cf)
+        assert cnt[0] == orf.sum() and cnt[1] == ocf.sum() and cnt[2] == status
+        if dtype == "i8":
+            assert status == orc.LOCALISED and E == [(i, j)]
+        run.correct()
+        rf, cf = run.flags()
+        cnt = run.cnt()
+        if status == orc.LOCALISED:
+            assert cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+        assert np.array_equal(run.C(), C_clean), "C not restored"
+        if status == orc.LOCALISED:
+            assert not rf.any() and not cf.any() and cnt[2] == ab.ABFT_CLEAN
+        if status == orc.CLEAN:                     # flip below tolerance: undetected, restore by hand
+            run.dC.copy_(torch.from_numpy(_with_ld(C_clean, run)).to("cuda"))
+    assert n_border <= 8
+
+
+def _with_ld(C, run):
+    full = np.zeros((run.batch, run.M, run.ldc), dtype=np.int32 if run.dtype == "i8" else np.int16)
+    full[:, :, :run.N] = C.view(full.dtype)
+    return full
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+def test_accumulator_flip_is_caught_by_the_fused_check(ctx, dtype):
+    M, N, K = 197, 200, 256
+    A, B = gen.gen_operands(dtype, M, N, K, 41, 42, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
+    run.gemm(ab.ABFT_DETECT)
+    C_clean = run.C().copy()
+    for (i, j, bit) in [(0, 0, 30), (196, 199, 27), (130, 129, 29 if dtype != "i8" else 0)]:
+        print(f"acc flip dtype={dtype} i={i} j={j} bit={bit}", flush=True)
+        run.inject(0, i, j, bit, ab.ABFT_INJECT_ACCUMULATOR)
+        run.gemm(ab.ABFT_DETECT)
+        rf, cf = run.flags()
+        cnt = run.cnt()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]
+        assert cnt[0] == 1 and cnt[1] == 1 and cnt[2] == ab.ABFT_LOCALISED
+        assert not np.array_equal(run.C(), C_clean)
+        run.correct()
+        assert np.array_equal(run.C(), C_clean)
+        rf, cf = run.flags()
+        assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+        # one-shot: the next GEMM is clean again
+        run.gemm(ab.ABFT_DETECT)
+        assert run.cnt()[2] == ab.ABFT_CLEAN and np.array_equal(run.C(), C_clean)
+    # DETECT_CORRECT does both in one call
+    run.inject(0, 5, 7, 30, ab.ABFT_INJECT_ACCUMULATOR)
+    run.gemm(ab.ABFT_DETECT_CORRECT)
+    cnt = run.cnt()
+    assert np.array_equal(run.C(), C_clean) and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+
+
+def test_corrupted_checksum_is_one_sided(ctx):
+    # a fault in a predicted checksum entry (not in C) flags one side only: "checksum suspect"
+    M, N, K = 64, 96, 128
+    A, B = gen.gen_operands("i8", M, N, K, 51, 52, trans_b=True)
+    run = Run(ctx, "i8", A, B, True)
+    run.gemm(ab.ABFT_DETECT)
+    ptr, n = ab.abft_workspace(ctx, ab.ABFT_WS_RC_PRED, run.shape)
+    from gpu_util import _DevView
+    t = torch.as_tensor(_DevView(ptr, n, "<i4"), device="cuda")
+    t[10] += 1
+    torch.cuda.synchronize()
+    C_before = run.C().copy()
+    run.verify()
+    rf, cf = run.flags()
+    assert rf.sum() == 1 and rf[0, 10] and not cf.any() and run.cnt()[2] == ab.ABFT_CHECKSUM_SUSPECT
+    run.correct()                                   # nothing to recompute
+    assert run.cnt()[3] == 0 and np.array_equal(run.C(), C_before)
+
+
+def test_argument_errors(ctx):
+    A, B = gen.gen_operands("bf16", 64, 64, 64, 1, 2, trans_b=True)
+    run = Run(ctx, "bf16", A, B, True)
+    s = run.shape
+    r = run.result()
+    assert ab.abft_gemm(ctx, None, run.dB, run.dC, run.code, ab.ABFT_DETECT, s, r) == ab.ABFT_EINVAL
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, 9, ab.ABFT_DETECT, s, r) == ab.ABFT_EINVAL
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, 7, s, r) == ab.ABFT_EINVAL
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, s, None) == ab.ABFT_EINVAL
+    bad = ab.make_shape(64, 64, 64, lda=68)
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, bad, r) == ab.ABFT_EALIGN
+    bad = ab.make_shape(64, 64, 64, lda=32)
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, bad, r) == ab.ABFT_ESHAPE
+    assert ab.abft_gemm(ctx, run.dA.data_ptr() + 2, run.dB, run.dC, run.code, ab.ABFT_DETECT, s, r) == ab.ABFT_EALIGN
+    big = ab.make_shape(100000, 64, 64)
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, big, r) == ab.ABFT_EWORKSPACE
+    k17 = ab.make_shape(64, 64, 1 << 17)
+    assert ab.abft_gemm(ctx, run.dA, run.dB, run.dC, ab.ABFT_I8, ab.ABFT_DETECT, k17, r) == ab.ABFT_ESHAPE
+    fresh = ab.abft_create(1024, 1024, 1024, 1)
+    try:
+        assert ab.abft_verify(fresh, run.dC, run.code, s, r) == ab.ABFT_ESTATE
+        assert ab.abft_gemm(fresh, run.dA, run.dB, run.dC, run.code,
+                            ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED, s, r) == ab.ABFT_ESTATE
+    finally:
+        ab.abft_destroy(fresh)
+    assert ab.abft_inject(ctx, run.dC, run.code, s, 0, 64, 0, 3) == ab.ABFT_EINVAL
+    assert ab.abft_inject(ctx, run.dC, run.code, s, 0, 0, 0, 16) == ab.ABFT_EINVAL
+    # nothing above may have disturbed the device
+    run.gemm(ab.ABFT_DETECT)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
