@@ -173,6 +173,13 @@ int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, void **ptr, in
 /* Tile the GEMM kernel uses for this problem (rows, cols of C per workgroup). */
 int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *tile_n);
 
+/* Kernel timing for reports (not a hot call: creates HIP events).  Between begin and end every
+ * abft_gemm records events on the caller's stream around its kernels; up to max_calls calls are
+ * kept.  abft_profile_end waits for the recorded events and returns average milliseconds per call:
+ * ms[0] encode kernel, ms[1] GEMM kernel, ms[2] compare kernel, ms[3] first event to last. */
+int abft_profile_begin(abft_ctx *ctx, int max_calls);
+int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls);
+
 const char *abft_strerror(int code);
 /* hipError_t value of the last failing HIP call on this context (0 if none). */
 int abft_last_hip_error(const abft_ctx *ctx);

@@ -23,7 +23,7 @@ __all__ = [
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
     "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_verify", "abft_correct",
     "abft_inject", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
-    "abft_version", "make_shape", "make_result", "DTYPE_CODE",
+    "abft_version", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
 
 ABFT_I8, ABFT_BF16, ABFT_F16 = 0, 1, 2
@@ -81,6 +81,9 @@ _SIGS = {
                                       ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64)]),
     "abft_tile_shape": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(abft_shape), ctypes.POINTER(ctypes.c_int),
                                        ctypes.POINTER(ctypes.c_int)]),
+    "abft_profile_begin": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
+    "abft_profile_end": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
+                                        ctypes.POINTER(ctypes.c_int)]),
     "abft_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "abft_last_hip_error": (ctypes.c_int, [ctypes.c_void_p]),
     "abft_version": (ctypes.c_int, []),
@@ -208,6 +211,20 @@ def abft_workspace(ctx, which: int, shape: abft_shape):
     if rc != ABFT_OK:
         raise AbftError(rc, "abft_workspace")
     return p.value, n.value
+
+
+def abft_profile_begin(ctx, max_calls: int) -> int:
+    return int(lib().abft_profile_begin(ctx, int(max_calls)))
+
+
+def abft_profile_end(ctx):
+    """(average ms per call [encode, gemm, compare, total], number of calls recorded)."""
+    ms = (ctypes.c_double * 4)()
+    n = ctypes.c_int()
+    rc = lib().abft_profile_end(ctx, ms, ctypes.byref(n))
+    if rc != ABFT_OK:
+        raise AbftError(rc, "abft_profile_end")
+    return [float(x) for x in ms], n.value
 
 
 def abft_tile_shape(dtype: int, shape: abft_shape):

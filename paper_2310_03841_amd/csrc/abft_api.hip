@@ -27,6 +27,9 @@ struct abft_ctx {
     bool b_valid, pred_valid;
     int b_dt, pred_dt;
     abft_shape b_shape, pred_shape;
+    // optional kernel timing (abft_profile_begin / _end)
+    hipEvent_t *prof_ev;    // 4 events per recorded call
+    int prof_cap, prof_n;
 };
 
 static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + 2 * NTERM /*w_a,w_b*/ + 1 /*ticket*/ +
@@ -99,9 +102,12 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     return ABFT_OK;
 }
 
+static void prof_free(abft_ctx *c);
+
 extern "C" int abft_destroy(abft_ctx *c)
 {
     if (!c) return ABFT_EINVAL;
+    prof_free(c);
     void *ptrs[] = {c->pool_depth, c->pool_stripe, c->pool_batch, c->pool_rows, c->pool_cols,
                     c->pool_obs, c->pool_vobs, c->fix_tiles, c->small};
     for (void *p : ptrs)
@@ -238,7 +244,10 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
 
     if (base == ABFT_OFF) {
         ctx->arm.batch = -1;
+        hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
+        if (ev) { HIP_TRY(hipEventRecord(ev[0], st)); HIP_TRY(hipEventRecord(ev[1], st)); }
         HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, st));
+        if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
         return ABFT_OK;
     }
     Verdict v;
@@ -249,10 +258,15 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_valid = false;
     if (!cached) ctx->b_valid = false;
     ctx->arm.batch = -1;
+    hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
+    if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     HIP_TRY(launch_encode(dtype, A, B, true, !cached, sh, w, v.tau_override, w.cc_obs,
                           (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    if (ev) HIP_TRY(hipEventRecord(ev[1], st));
     HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
+    if (ev) HIP_TRY(hipEventRecord(ev[2], st));
     HIP_TRY(launch_compare(dtype, sh, w, false, v, st));
+    if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
     ctx->b_valid = true;
     ctx->b_dt = dtype;
     ctx->b_shape = *s;
@@ -347,6 +361,58 @@ extern "C" int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, voi
     case ABFT_WS_MAXABS:  *ptr = w.maxabs;  *count = 2 * b; break;
     default: return ABFT_EINVAL;
     }
+    return ABFT_OK;
+}
+
+static void prof_free(abft_ctx *c)
+{
+    if (c->prof_ev) {
+        for (int i = 0; i < 4 * c->prof_cap; ++i)
+            if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+        delete[] c->prof_ev;
+    }
+    c->prof_ev = nullptr;
+    c->prof_cap = c->prof_n = 0;
+}
+
+extern "C" int abft_profile_begin(abft_ctx *ctx, int max_calls)
+{
+    if (!ctx || max_calls < 1 || max_calls > 100000) return ABFT_EINVAL;
+    prof_free(ctx);
+    ctx->prof_ev = new (std::nothrow) hipEvent_t[4 * (size_t)max_calls];
+    if (!ctx->prof_ev) return ABFT_EINVAL;
+    memset(ctx->prof_ev, 0, sizeof(hipEvent_t) * 4 * (size_t)max_calls);
+    ctx->prof_cap = max_calls;
+    for (int i = 0; i < 4 * max_calls; ++i) {
+        hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+        if (e != hipSuccess) { prof_free(ctx); return fail_hip(ctx, e); }
+    }
+    return ABFT_OK;
+}
+
+extern "C" int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls)
+{
+    if (!ctx || !ms || !calls) return ABFT_EINVAL;
+    if (!ctx->prof_ev) return ABFT_ESTATE;
+    double sum[4] = {0, 0, 0, 0};
+    const int n = ctx->prof_n;
+    for (int i = 0; i < n; ++i) {
+        hipEvent_t *ev = ctx->prof_ev + 4 * i;
+        hipError_t e = hipEventSynchronize(ev[3]);
+        if (e != hipSuccess) { prof_free(ctx); return fail_hip(ctx, e); }
+        float t;
+        for (int q = 0; q < 3; ++q) {
+            e = hipEventElapsedTime(&t, ev[q], ev[q + 1]);
+            if (e != hipSuccess) { prof_free(ctx); return fail_hip(ctx, e); }
+            sum[q] += t;
+        }
+        e = hipEventElapsedTime(&t, ev[0], ev[3]);
+        if (e != hipSuccess) { prof_free(ctx); return fail_hip(ctx, e); }
+        sum[3] += t;
+    }
+    for (int q = 0; q < 4; ++q) ms[q] = n ? sum[q] / n : 0.0;
+    *calls = n;
+    prof_free(ctx);
     return ABFT_OK;
 }
 
