@@ -1,0 +1,24 @@
+// Kernel arguments shared by the GEMM kernels of libabft.
+#pragma once
+#include <stdint.h>
+
+namespace abft {
+
+struct GemmArgs {
+    const uint8_t *A, *B;
+    uint8_t *C;
+    const uint8_t *SA, *SB;                       // [batch][NTERM][Kp] operand elements
+    uint32_t *cc_part, *rc_part, *s_part;         // raw stripe outputs
+    uint32_t *cc_obs, *rc_obs;                    // observed sums (atomics)
+    int M, N, K, Kp;
+    long lda, ldb, ldc, sA, sB, sC;               // elements
+    int tiles_m, tiles_n;
+    int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
+};
+
+// Fast path (gemm_fast.hip): B stored N x K, K a whole number of 128-byte slabs.
+bool gemm_fast_eligible(int dt, int M, int N, int K, bool transB, long lda, long ldb);
+hipError_t launch_gemm_fast(int dt, bool protect, GemmArgs &g, int batch, hipStream_t st);
+void gemm_fast_tile(int *tm, int *tn);
+
+}  // namespace abft

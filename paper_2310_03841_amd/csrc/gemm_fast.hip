@@ -1,0 +1,211 @@
+// Fast path of the protected GEMM for gfx950: B stored N x K (both operands K-contiguous) and
+// K a whole number of 128-byte slabs.  Same mathematics and the same epilogue as gemm_kernel;
+// what differs is the data movement:
+//   * global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4): no VGPR staging.  One
+//     wave instruction fills 8 LDS rows of 128 bytes; the XOR swizzle of the LDS layout is
+//     applied by choosing which global 16-byte chunk each lane fetches.
+//   * 256 x 256 tiles, 4 waves of 128 x 128 (sixteen 32x32 MFMA blocks per wave), two LDS
+//     buffers of 64 KB, one barrier per slab.
+//   * workgroup -> tile mapping keeps the workgroups that share an XCD (and its L2) on a
+//     compact group of tiles.
+// Rows of the tile beyond the (stripe-augmented) problem are fetched from a valid row instead
+// of being zero-filled: a row of A only influences the same row of C, which is discarded.
+#include "abft_device.h"
+#include "gemm_args.h"
+#include "gemm_epilogue.h"
+
+namespace abft {
+
+typedef const __attribute__((address_space(1))) void *gas_ptr;
+typedef __attribute__((address_space(3))) void *las_ptr;
+
+template <int DT, int BM, int BN, bool PROT>
+__global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
+{
+    using T = Traits<DT>;
+    typedef typename T::accv_t accv_t;
+    constexpr int ES = T::ES;
+    constexpr int KE = SLAB_BYTES / ES;
+    constexpr int TM = BM / 2, TN = BN / 2;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int GA = BM / 32, GB = BN / 32;     // 8-row load groups per wave per slab
+    constexpr int BUF = (BM + BN) * SLAB_BYTES;
+    constexpr int GROUP_M = 8;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int bz = blockIdx.z;
+
+    // ---- workgroup -> tile: consecutive ids of one XCD walk GROUP_M tile rows, then the next column
+    int tm_idx, tn_idx;
+    {
+        const int nb = gridDim.x, bid = blockIdx.x;
+        const int q = nb >> 3, r = nb & 7, xcd = bid & 7;
+        const int L = xcd * q + (xcd < r ? xcd : r) + (bid >> 3);
+        const int per_group = GROUP_M * g.tiles_n;
+        const int grp = L / per_group, in_grp = L % per_group;
+        const int first_m = grp * GROUP_M;
+        const int gsz = (g.tiles_m - first_m) < GROUP_M ? (g.tiles_m - first_m) : GROUP_M;
+        tm_idx = first_m + in_grp % gsz;
+        tn_idx = in_grp / gsz;
+    }
+    const int m0 = tm_idx * BM, n0 = tn_idx * BN;
+    const int M = g.M, N = g.N, K = g.K;
+    const int Mx = PROT ? M + NTERM : M;
+    const int Nx = PROT ? N + NTERM : N;
+
+    const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
+    const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
+    const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
+    const uint8_t *SBb = PROT ? g.SB + (long)bz * NTERM * g.Kp * ES : nullptr;
+
+    // ---- per-lane global sources.  Load group p of this wave covers tile rows
+    // (4 p + wave) * 8 .. + 8; lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches
+    // the chunk (l & 7) ^ (l >> 3) so that LDS slot = chunk ^ (row & 7).
+    const int lrow = lane >> 3;
+    const int lchunk = (lane & 7) ^ lrow;
+    // Interior tiles: the rows of consecutive load groups are 32 apart in one matrix, so a lane
+    // needs one base pointer and a uniform stride.  Edge tiles (stripe rows, rows past the end)
+    // pick the source row by row.
+    const bool a_interior = (m0 + BM <= M), b_interior = (n0 + BN <= N);
+    const uint8_t *a_lane = Ab + (long)(m0 + wave * 8 + lrow) * g.lda * ES + lchunk * 16;
+    const uint8_t *b_lane = Bb + (long)(n0 + wave * 8 + lrow) * g.ldb * ES + lchunk * 16;
+    const long a_pstride = 32 * g.lda * ES, b_pstride = 32 * g.ldb * ES;
+    auto a_src = [&](int p) -> const uint8_t * {
+        const int r = m0 + (4 * p + wave) * 8 + lrow;
+        const uint8_t *s = r < M ? Ab + (long)r * g.lda * ES
+                                 : ((PROT && r < Mx) ? SAb + (long)(r - M) * g.Kp * ES : Ab);
+        return s + lchunk * 16;
+    };
+    auto b_src = [&](int p) -> const uint8_t * {
+        const int r = n0 + (4 * p + wave) * 8 + lrow;
+        const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES
+                                 : ((PROT && r < Nx) ? SBb + (long)(r - N) * g.Kp * ES : Bb);
+        return s + lchunk * 16;
+    };
+    const int a_rows = Mx - m0, b_rows = Nx - n0;      // rows of this tile that matter
+
+    // The accumulators are never zero-filled: the first MFMA of every block takes a literal
+    // zero as its addend.  Every block is always computed, also where the tile hangs over the
+    // edge of the problem: a conditional MFMA would force the accumulators out of the AGPRs.
+    accv_t acc[MI][NI];
+    accv_t zerov;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zerov[i] = T::zero();
+
+    // One loop serves interior and edge tiles (two instances of the MFMA loop that meet in
+    // front of the epilogue would push the accumulators through VGPR copies); only the source
+    // address of a load depends, wave-uniformly, on where the tile lies.
+    auto issue_loads = [&](int s, int buf) {
+        const long koff = (long)s * SLAB_BYTES;
+        uint8_t *sA = smem + buf * BUF;
+        uint8_t *sB = sA + BM * SLAB_BYTES;
+#pragma unroll
+        for (int p = 0; p < GA; ++p) {
+            const int rb = (4 * p + wave) * 8;
+            if (a_interior) {
+                __builtin_amdgcn_global_load_lds((gas_ptr)(a_lane + p * a_pstride + koff),
+                                                 (las_ptr)(sA + rb * SLAB_BYTES), 16, 0, 0);
+            } else if (rb < a_rows) {
+                __builtin_amdgcn_global_load_lds((gas_ptr)(a_src(p) + koff), (las_ptr)(sA + rb * SLAB_BYTES), 16, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < GB; ++p) {
+            const int rb = (4 * p + wave) * 8;
+            if (b_interior) {
+                __builtin_amdgcn_global_load_lds((gas_ptr)(b_lane + p * b_pstride + koff),
+                                                 (las_ptr)(sB + rb * SLAB_BYTES), 16, 0, 0);
+            } else if (rb < b_rows) {
+                __builtin_amdgcn_global_load_lds((gas_ptr)(b_src(p) + koff), (las_ptr)(sB + rb * SLAB_BYTES), 16, 0, 0);
+            }
+        }
+    };
+    auto compute = [&](auto first_c, int buf) {
+        constexpr bool FIRST = decltype(first_c)::value;
+        const uint8_t *sA = smem + buf * BUF;
+        const uint8_t *sB = sA + BM * SLAB_BYTES;
+#pragma unroll
+        for (int s4 = 0; s4 < 4; ++s4) {
+            const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
+            i32x4 af[MI], bf[NI];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+                af[mi] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + mi * 32 + l32) * SLAB_BYTES + sw);
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+                bf[ni] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + ni * 32 + l32) * SLAB_BYTES + sw);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+                    acc[mi][ni] = T::mfma(af[mi], bf[ni], (FIRST && s4 == 0) ? zerov : acc[mi][ni]);
+        }
+    };
+    {
+        const int nslab = K / KE;
+        issue_loads(0, 0);
+        __syncthreads();
+        if (nslab > 1) issue_loads(1, 1);
+        compute(std::true_type{}, 0);
+        for (int s = 1; s < nslab; ++s) {
+            __syncthreads();             // slab s has landed for every wave; buffer (s+1)&1 is free
+            if (s + 1 < nslab) issue_loads(s + 1, (s + 1) & 1);
+            compute(std::false_type{}, s & 1);
+        }
+    }
+    __syncthreads();
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
+}
+
+// ------------------------------------------------------------------------------------------
+template <int DT, int BM, int BN, bool PROT>
+static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
+{
+    constexpr int smem = 2 * (BM + BN) * SLAB_BYTES;
+    auto kern = gemm_fast_kernel<DT, BM, BN, PROT>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const int Mx = PROT ? g.M + NTERM : g.M, Nx = PROT ? g.N + NTERM : g.N;
+    g.tiles_m = (Mx + BM - 1) / BM;
+    g.tiles_n = (Nx + BN - 1) / BN;
+    dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
+    return hipGetLastError();
+}
+
+bool gemm_fast_eligible(int dt, int M, int N, int K, bool transB, long lda, long ldb)
+{
+    const int ke = SLAB_BYTES / elem_size(dt);
+    (void)lda; (void)ldb;
+    return transB && (K % ke) == 0 && M >= 512 && N >= 512;
+}
+
+void gemm_fast_tile(int *tm, int *tn) { *tm = 256; *tn = 256; }
+
+hipError_t launch_gemm_fast(int dt, bool protect, GemmArgs &g, int batch, hipStream_t st)
+{
+    switch (dt) {
+    case DT_I8:
+        return protect ? launch_fast_one<DT_I8, 256, 256, true>(g, batch, st)
+                       : launch_fast_one<DT_I8, 256, 256, false>(g, batch, st);
+    case DT_BF16:
+        return protect ? launch_fast_one<DT_BF16, 256, 256, true>(g, batch, st)
+                       : launch_fast_one<DT_BF16, 256, 256, false>(g, batch, st);
+    case DT_F16:
+        return protect ? launch_fast_one<DT_F16, 256, 256, true>(g, batch, st)
+                       : launch_fast_one<DT_F16, 256, 256, false>(g, batch, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace abft

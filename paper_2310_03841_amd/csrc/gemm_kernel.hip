@@ -20,20 +20,11 @@
 // eight 16-byte chunks with chunk index XOR (row & 7) so that both the
 // row-contiguous writes and the MFMA operand reads are bank-conflict free.
 #include "abft_device.h"
+#include "gemm_args.h"
+#include "gemm_epilogue.h"
 
 namespace abft {
 
-struct GemmArgs {
-    const uint8_t *A, *B;
-    uint8_t *C;
-    const uint8_t *SA, *SB;                       // [batch][NTERM][Kp] operand elements
-    uint32_t *cc_part, *rc_part, *s_part;         // raw stripe outputs
-    uint32_t *cc_obs, *rc_obs;                    // observed sums (atomics)
-    int M, N, K, Kp;
-    long lda, ldb, ldc, sA, sB, sC;               // elements
-    int tiles_m, tiles_n;
-    int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
-};
 
 template <int DT, int BM, int BN, bool PROT, bool TRANSB>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
@@ -51,7 +42,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const int bz = blockIdx.z;
@@ -219,76 +211,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     }
 
     // ---- epilogue
-    acc_t *rs_part = reinterpret_cast<acc_t *>(smem);          // [2][BM] by wave column
-    acc_t *cs_part = rs_part + 2 * BM;                         // [2][BN] by wave row
-    uint8_t *Cb = g.C + (long)bz * g.sC * T::OS;
-    const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
-                          g.inj_col >= n0 && g.inj_col < n0 + BN;
-
-    acc_t colsum[NI];
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) colsum[ni] = T::zero();
-
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        acc_t rowsum[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) rowsum[i] = T::zero();
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            const int gc = n0 + wn * TN + ni * 32 + l32;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int gr = m0 + wm * TM + mi * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-                acc_t v = acc[mi][ni][i];
-                if (inj_here && gr == g.inj_row && gc == g.inj_col)
-                    v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
-                if (gr < M && gc < N) {
-                    T::store_c(Cb, (long)gr * g.ldc + gc, v);
-                    if (PROT) {
-                        colsum[ni] = add_t(colsum[ni], v);
-                        rowsum[i] = add_t(rowsum[i], v);
-                    }
-                } else if (PROT) {
-                    if (gr >= M && gr < Mx) {
-                        if (gc < N)
-                            g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
-                        else if (gc < Nx)
-                            g.s_part[(long)bz * NTERM * NTERM + (gr - M) * NTERM + (gc - N)] = as_word(v);
-                    } else if (gr < M && gc >= N && gc < Nx) {
-                        g.rc_part[((long)bz * NTERM + (gc - N)) * M + gr] = as_word(v);
-                    }
-                }
-            }
-        }
-        if (PROT) {
-            // row sums: reduce over the 32 lanes that hold one row's columns
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                acc_t t = half_wave_sum(rowsum[i]);
-                if (l32 == 0) rs_part[wn * BM + wm * TM + mi * 32 + 8 * (i >> 2) + 4 * lh + (i & 3)] = t;
-            }
-        }
-    }
-    if (PROT) {
-        // column sums: the two half-waves hold different rows of the same columns
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            acc_t t = add_t(colsum[ni], __shfl_xor(colsum[ni], 32));
-            if (lh == 0) cs_part[wm * BN + wn * TN + ni * 32 + l32] = t;
-        }
-        __syncthreads();
-        for (int t = tid; t < BM + BN; t += 256) {
-            if (t < BM) {
-                int gr = m0 + t;
-                if (gr < M) atomic_add_word(g.rc_obs + (long)bz * M + gr, add_t(rs_part[t], rs_part[BM + t]));
-            } else {
-                int gc = n0 + (t - BM);
-                if (gc < N)
-                    atomic_add_word(g.cc_obs + (long)bz * N + gc, add_t(cs_part[t - BM], cs_part[BN + t - BM]));
-            }
-        }
-    }
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -321,8 +244,12 @@ static hipError_t launch_cfg(bool protect, bool transB, GemmArgs &g, int batch, 
                   : launch_one<DT, BM, BN, false, false>(g, batch, st);
 }
 
-void gemm_tile_shape(int, const Shape &, int *tm, int *tn)
+void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 {
+    if (gemm_fast_eligible(dt, s.M, s.N, s.K, s.transB != 0, s.lda, s.ldb)) {
+        gemm_fast_tile(tm, tn);
+        return;
+    }
     *tm = 128;
     *tn = 128;
 }
@@ -346,6 +273,7 @@ hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void 
     g.sA = s.sA; g.sB = s.sB; g.sC = s.sC;
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
     const bool tb = s.transB != 0;
+    if (gemm_fast_eligible(dt, s.M, s.N, s.K, tb, s.lda, s.ldb)) return launch_gemm_fast(dt, protect, g, s.batch, st);
     switch (dt) {
     case DT_I8:   return launch_cfg<DT_I8, 128, 128>(protect, tb, g, s.batch, st);
     case DT_BF16: return launch_cfg<DT_BF16, 128, 128>(protect, tb, g, s.batch, st);

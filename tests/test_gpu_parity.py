@@ -84,6 +84,9 @@ SHAPES = [
     (197, 197, 64, 3, True),       # per-head Q K^T
     (197, 64, 197, 3, False),      # per-head attn V (B stored K x N)
     (150, 200, 136, 2, False),
+    (777, 600, 192, 1, True),      # 256x256-tile path for 16-bit types (K a multiple of 64)
+    (520, 1030, 256, 2, True),     # 256x256-tile path for all types, ragged both ways, batched
+    (512, 512, 128, 1, True),      # tile-exact on the 256x256 path
 ]
 
 
@@ -126,7 +129,8 @@ def test_cached_b_checksum(ctx, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
-@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 768, 768, 1, True), (130, 70, 100, 2, False)])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 768, 768, 1, True), (130, 70, 100, 2, False),
+                                                  (600, 520, 256, 1, True)])
 def test_stored_flip_verify_correct(ctx, dtype, M, N, K, batch, trans_b):
     A, B = gen.gen_operands(dtype, M, N, K, 31, 32, trans_b=trans_b, batch=batch)
     run = Run(ctx, dtype, A, B, trans_b)
@@ -173,7 +177,7 @@ def test_stored_flip_verify_correct(ctx, dtype, M, N, K, batch, trans_b):
         else:                                       # flip below tolerance: undetected, restore by hand
             assert status == orc.CLEAN and dtype != "i8" and cnt[3] == 0
             run.dC.copy_(torch.from_numpy(_with_ld(C_clean, run)).to("cuda"))
-    assert n_border <= 8
+    assert n_border <= len(flips) // 2
 
 
 def _with_ld(C, run):
