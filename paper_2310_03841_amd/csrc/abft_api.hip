@@ -12,7 +12,7 @@ using namespace abft;
 struct abft_ctx {
     abft_config cfg;
     // device pools (32-bit words unless noted)
-    uint32_t *pool_depth;   // 4 * max_depth words: a_acc, b_acc, a_sum, b_sum
+    uint32_t *pool_depth;   // (2 * ENC_ACC_COPIES + 2) * max_depth words: a_acc, b_acc copies, a_sum, b_sum
     uint8_t  *pool_stripe;  // 2 * NTERM * max_depth * 2 bytes
     uint32_t *pool_batch;   // per-batch scalars
     uint32_t *pool_rows;    // rc_part (NTERM), rc_pred
@@ -77,7 +77,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     const size_t D = (size_t)c->cfg.max_depth, R = (size_t)cfg->max_rows, Cn = (size_t)cfg->max_cols,
                  Bt = (size_t)cfg->max_batch;
     struct { void **p; size_t bytes; } req[] = {
-        {(void **)&c->pool_depth, 4 * D * 4},
+        {(void **)&c->pool_depth, (2 * ENC_ACC_COPIES + 2) * D * 4},
         {(void **)&c->pool_stripe, 2 * NTERM * D * 2},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_rows, (NTERM + 1) * R * 4},
@@ -160,9 +160,10 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
                  Bt = (size_t)c->cfg.max_batch;
     (void)bK;
     w->a_acc = c->pool_depth;
-    w->b_acc = c->pool_depth + D;
-    w->a_sum = c->pool_depth + 2 * D;
-    w->b_sum = c->pool_depth + 3 * D;
+    w->b_acc = c->pool_depth + ENC_ACC_COPIES * D;
+    w->acc_stride = (long)D;
+    w->a_sum = c->pool_depth + 2 * ENC_ACC_COPIES * D;
+    w->b_sum = c->pool_depth + (2 * ENC_ACC_COPIES + 1) * D;
     w->stripe_a = c->pool_stripe;
     w->stripe_b = c->pool_stripe + NTERM * D * 2;
     uint32_t *pb = c->pool_batch;

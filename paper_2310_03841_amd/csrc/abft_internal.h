@@ -16,6 +16,8 @@ constexpr int SLAB_BYTES = 128;
 constexpr int CT = 32;
 // Most tiles one abft_correct call repairs.
 constexpr int MAX_FIX_TILES = 256;
+// Copies of the encode accumulators (spreads same-cache-line atomics).
+constexpr int ENC_ACC_COPIES = 8;
 // Most flagged rows (columns) per batch item that localisation lists.
 constexpr int MAX_LIST = 64;
 
@@ -29,7 +31,8 @@ __host__ __device__ inline int out_size(int dt) { return dt == DT_I8 ? 4 : 2; }
 // DT_I8 and float otherwise, so every element is one 32-bit word.
 struct Workspace {
     // encode
-    uint32_t *a_acc, *b_acc;        // [batch][K]   atomic accumulators, self-cleaning
+    uint32_t *a_acc, *b_acc;        // [ENC_ACC_COPIES][batch][K] atomic accumulators, self-cleaning
+    long acc_stride;                // words between accumulator copies
     uint32_t *a_sum, *b_sum;        // [batch][K]   final a = e^T A, b = B e
     uint32_t *max_acc;              // [batch][2]   atomic max of |A|, |B| (float bits), self-cleaning
     float    *maxabs;               // [batch][2]

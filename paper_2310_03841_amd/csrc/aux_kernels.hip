@@ -41,7 +41,8 @@ struct EncSide {
     int cw_log2;          // 16-byte chunk columns per block window (power of two <= 64)
     int rpb;              // rows per block
     int nwin, nrb;
-    uint32_t *acc;        // [batch][K] atomic accumulators
+    uint32_t *acc;        // [ENC_COPIES][batch][K] atomic accumulators (copy stride acc_stride words)
+    long acc_stride;
     uint32_t *sum;        // [batch][K] final sums
     uint8_t *stripe;      // [batch][NTERM][Kp]
     float *w;             // [batch][NTERM]
@@ -59,6 +60,11 @@ struct EncArgs {
     uint32_t *zero_ptr;
     size_t zero_words;
 };
+
+constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread
+// Atomics on one cache line are served one after the other (tens of nanoseconds each), so the
+// row blocks of the encode pass spread their column sums over this many accumulator copies.
+constexpr int ENC_COPIES = ENC_ACC_COPIES;
 
 // Split an int32 sum into four signed base-256 digits: v = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3 (mod 2^32).
 __device__ __forceinline__ void split_digits(int v, int8_t d[NTERM])
@@ -84,7 +90,14 @@ __device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /
 
     float amax = 0.f;
     for (int k = tid; k < K; k += 256) {
-        uint32_t w = atomicExch(acc + k, 0u);      // take the total and leave the accumulator clean
+        // take the totals and leave the accumulators clean for the next call
+        uint32_t part[ENC_COPIES];
+#pragma unroll
+        for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomicExch(acc + c * sd.acc_stride + k, 0u);
+        typename T::acc_t t = from_word<typename T::acc_t>(part[0]);
+#pragma unroll
+        for (int c = 1; c < ENC_COPIES; ++c) t = add_t(t, from_word<typename T::acc_t>(part[c]));
+        const uint32_t w = as_word(t);
         sum[k] = w;
         if (!T::IS_INT) amax = fmaxf(amax, fabsf(__uint_as_float(w)));
     }
@@ -176,7 +189,7 @@ __global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
     const uint8_t *Xb = sd.X + (long)bz * sd.stride * ES;
     const int rbeg = rb * sd.rpb;
     const int rend = min(rbeg + sd.rpb, sd.rows);
-    const int iters = (sd.rpb + RL - 1) / RL;
+    const int iters = (sd.rpb + RL * ENC_UNROLL - 1) / (RL * ENC_UNROLL);
 
     acc_t colacc[CE];
 #pragma unroll
@@ -184,45 +197,61 @@ __global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
     float mx = 0.f;
 
     for (int it = 0; it < iters; ++it) {
-        const int r = rbeg + ry + it * RL;
-        const bool ok = colok && r < rend;
-        i32x4 v = {0, 0, 0, 0};
-        if (ok) {
-            v = *reinterpret_cast<const i32x4 *>(Xb + ((long)r * sd.ld + col0) * ES);
-            if (nvalid < CE) v = mask_chunk(v, nvalid * ES);
-        }
-        acc_t s = T::zero();
+        // issue a batch of independent loads first: the pass is bound by memory latency otherwise
+        i32x4 v[ENC_UNROLL];
 #pragma unroll
-        for (int q = 0; q < CE; ++q) {
-            acc_t x = T::elem(v, q);
-            if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
-            colacc[q] = add_t(colacc[q], x);
-            s = add_t(s, x);
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            v[u] = i32x4{0, 0, 0, 0};
+            if (colok && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Xb + ((long)r * sd.ld + col0) * ES);
         }
-        if (!sd.reduce_rows) {
-            for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
-            if (cx == 0 && r < rend) atomic_add_word(sd.acc + (long)bz * e.K + r, s);
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            i32x4 w = v[u];
+            if (nvalid < CE) w = mask_chunk(w, nvalid > 0 ? nvalid * ES : 0);
+            acc_t s = T::zero();
+#pragma unroll
+            for (int q = 0; q < CE; ++q) {
+                acc_t x = T::elem(w, q);
+                if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
+                colacc[q] = add_t(colacc[q], x);
+                s = add_t(s, x);
+            }
+            if (!sd.reduce_rows) {
+                for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+                if (cx == 0 && r < rend) atomic_add_word(sd.acc + (long)bz * e.K + r, s);
+            }
         }
     }
     if (sd.reduce_rows) {
 #pragma unroll
         for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
         __syncthreads();
-        if (ry == 0 && colok) {
-#pragma unroll
-            for (int q = 0; q < CE; ++q) {
-                acc_t t = red[cx * CE + q];
-                for (int y = 1; y < RL; ++y) t = add_t(t, red[(y * CW + cx) * CE + q]);
-                if (q < nvalid) atomic_add_word(sd.acc + (long)bz * e.K + col0 + q, t);
+        // one atomic per column, consecutive lanes on consecutive addresses: atomics that hit
+        // the same cache line are served one after the other, so their number is what counts
+        for (int c = tid; c < CW * CE; c += 256) {
+            const int col = win * CW * CE + c;
+            if (col < sd.cols) {
+                acc_t t = red[c];
+                for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
+                atomic_add_word(sd.acc + (rb % ENC_COPIES) * sd.acc_stride + (long)bz * e.K + col, t);
             }
         }
     }
     if (!T::IS_INT) {
         mx = wave_max(mx);
-        if ((tid & 63) == 0) atomicMax(e.max_acc + (long)bz * 2 + sidx, __float_as_uint(mx));
+        __syncthreads();
+        if ((tid & 63) == 0) fred[tid >> 6] = mx;
+        __syncthreads();
+        if (tid == 0)
+            atomicMax(e.max_acc + (long)bz * 2 + sidx,
+                      __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
     }
-    // last block of this batch item finalises both sides
-    __threadfence();
+    // last block of this batch item finalises both sides.  Everything other workgroups must
+    // see was written with device-scope atomic read-modify-writes, which are performed at the
+    // device's coherence point; the barrier waits for this workgroup's outstanding ones before
+    // the ticket is taken.  (A device-wide fence here costs tens of microseconds per launch.)
     __syncthreads();
     if (tid == 0) {
         unsigned expected = 0;
@@ -234,11 +263,9 @@ __global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
     for (int q = 0; q < 2; ++q)
         if (e.side[q].active) encode_finalize<DT>(e, q, bz, fred);
     if (!T::IS_INT && e.side[0].active) {
-        __threadfence();
         __syncthreads();
         if (tid == 0) {
             float ma = e.maxabs[(long)bz * 2 + 0], mb = e.maxabs[(long)bz * 2 + 1];
@@ -249,15 +276,22 @@ __global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
 
 static void plan_side(EncSide &sd, int chunk_elems)
 {
-    int chunks = (sd.cols + chunk_elems - 1) / chunk_elems;
-    int lg = 0;
-    while ((1 << lg) < chunks && lg < 6) ++lg;
-    if (lg < 3) lg = 3;
-    sd.cw_log2 = lg;
-    int CW = 1 << lg, RL = 256 / CW;
+    const int chunks = (sd.cols + chunk_elems - 1) / chunk_elems;
+    // window width (power of two, 8..64 chunk columns): least padding, then widest
+    int best_lg = 3;
+    long best_waste = -1;
+    for (int lg = 3; lg <= 6; ++lg) {
+        const int CW = 1 << lg;
+        const long waste = (long)((chunks + CW - 1) / CW) * CW - chunks;
+        if (best_waste < 0 || waste <= best_waste) { best_waste = waste; best_lg = lg; }
+    }
+    sd.cw_log2 = best_lg;
+    const int CW = 1 << best_lg, RL = 256 / CW;
     sd.nwin = (chunks + CW - 1) / CW;
-    int rpb = RL * 16;                 // 16 chunk loads per thread
-    if (rpb > sd.rows) rpb = ((sd.rows + RL - 1) / RL) * RL;
+    // rows per block: one batch of ENC_UNROLL loads per thread, more when the matrix is tall
+    // enough that the grid would otherwise exceed a few thousand blocks
+    int rpb = RL * ENC_UNROLL;
+    while ((long)sd.nwin * ((sd.rows + rpb - 1) / rpb) > 640) rpb *= 2;
     sd.rpb = rpb;
     sd.nrb = (sd.rows + rpb - 1) / rpb;
 }
@@ -270,14 +304,14 @@ hipError_t launch_encode(int dt, const void *A, const void *B, bool do_a, bool d
     const int ce = 16 / elem_size(dt);
     EncSide &a = e.side[0];
     a.X = (const uint8_t *)A; a.ld = s.lda; a.stride = s.sA; a.rows = s.M; a.cols = s.K;
-    a.reduce_rows = 1; a.acc = w.a_acc; a.sum = w.a_sum; a.stripe = w.stripe_a; a.w = w.w_a;
+    a.reduce_rows = 1; a.acc = w.a_acc; a.acc_stride = w.acc_stride; a.sum = w.a_sum; a.stripe = w.stripe_a; a.w = w.w_a;
     a.active = do_a ? 1 : 0;
     plan_side(a, ce);
     EncSide &b = e.side[1];
     b.X = (const uint8_t *)B; b.ld = s.ldb; b.stride = s.sB;
     if (s.transB) { b.rows = s.N; b.cols = s.K; b.reduce_rows = 1; }
     else          { b.rows = s.K; b.cols = s.N; b.reduce_rows = 0; }
-    b.acc = w.b_acc; b.sum = w.b_sum; b.stripe = w.stripe_b; b.w = w.w_b;
+    b.acc = w.b_acc; b.acc_stride = w.acc_stride; b.sum = w.b_sum; b.stripe = w.stripe_b; b.w = w.w_b;
     b.active = do_b ? 1 : 0;
     plan_side(b, ce);
     e.K = s.K; e.Kp = s.Kp;
@@ -387,14 +421,12 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     if (tid == 0) {
         if (nr) atomicAdd(a.ticket + 1, nr);
         if (nc) atomicAdd(a.ticket + 2, nc);
-        __threadfence();
         unsigned total = gridDim.x * gridDim.z;
         unsigned t = atomicAdd(a.ticket, 1u);
         is_last = (t == total - 1);
     }
     __syncthreads();
     if (is_last && tid == 0) {
-        __threadfence();
         uint32_t r = atomicExch(a.ticket + 1, 0u), c = atomicExch(a.ticket + 2, 0u);
         atomicExch(a.ticket, 0u);
         a.counts[0] = r;
@@ -460,37 +492,45 @@ __global__ __launch_bounds__(256) void verify_kernel(VerArgs a)
     const int nvalid = a.N - col0;
     const uint8_t *Cb = a.C + (long)bz * a.sC * OS;
     const int rbeg = rb * a.rpb, rend = min(rbeg + a.rpb, a.M);
-    const int iters = (a.rpb + RL - 1) / RL;
+    const int iters = (a.rpb + RL * ENC_UNROLL - 1) / (RL * ENC_UNROLL);
     acc_t colacc[CE];
 #pragma unroll
     for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
     for (int it = 0; it < iters; ++it) {
-        const int r = rbeg + ry + it * RL;
-        const bool ok = colok && r < rend;
-        acc_t s = T::zero();
-        if (ok) {
-            i32x4 v = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
+        i32x4 v[ENC_UNROLL];
 #pragma unroll
-            for (int q = 0; q < CE; ++q) {
-                if (q < nvalid) {
-                    acc_t x = out_elem<DT>(v, q);
-                    colacc[q] = add_t(colacc[q], x);
-                    s = add_t(s, x);
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            v[u] = i32x4{0, 0, 0, 0};
+            if (colok && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
+        }
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            acc_t s = T::zero();
+            if (colok && r < rend) {
+#pragma unroll
+                for (int q = 0; q < CE; ++q) {
+                    if (q < nvalid) {
+                        acc_t x = out_elem<DT>(v[u], q);
+                        colacc[q] = add_t(colacc[q], x);
+                        s = add_t(s, x);
+                    }
                 }
             }
+            for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+            if (cx == 0 && r < rend) atomic_add_word(a.rc_vobs + (long)bz * a.M + r, s);
         }
-        for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
-        if (cx == 0 && r < rend) atomic_add_word(a.rc_vobs + (long)bz * a.M + r, s);
     }
 #pragma unroll
     for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
     __syncthreads();
-    if (ry == 0 && colok) {
-#pragma unroll
-        for (int q = 0; q < CE; ++q) {
-            acc_t t = red[cx * CE + q];
-            for (int y = 1; y < RL; ++y) t = add_t(t, red[(y * CW + cx) * CE + q]);
-            if (q < nvalid) atomic_add_word(a.cc_vobs + (long)bz * a.N + col0 + q, t);
+    for (int c = tid; c < CW * CE; c += 256) {
+        const int col = win * CW * CE + c;
+        if (col < a.N) {
+            acc_t t = red[c];
+            for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
+            atomic_add_word(a.cc_vobs + (long)bz * a.N + col, t);
         }
     }
 }
@@ -500,18 +540,10 @@ hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Works
     VerArgs a;
     a.C = (const uint8_t *)C; a.ldc = s.ldc; a.sC = s.sC; a.M = s.M; a.N = s.N;
     a.cc_vobs = w.cc_vobs; a.rc_vobs = w.rc_vobs;
-    const int ce = 16 / out_size(dt);
-    int chunks = (s.N + ce - 1) / ce;
-    int lg = 0;
-    while ((1 << lg) < chunks && lg < 6) ++lg;
-    if (lg < 3) lg = 3;
-    a.cw_log2 = lg;
-    int CW = 1 << lg, RL = 256 / CW;
-    a.nwin = (chunks + CW - 1) / CW;
-    int rpb = RL * 16;
-    if (rpb > s.M) rpb = ((s.M + RL - 1) / RL) * RL;
-    a.rpb = rpb;
-    a.nrb = (s.M + rpb - 1) / rpb;
+    EncSide plan;
+    plan.rows = s.M; plan.cols = s.N;
+    plan_side(plan, 16 / out_size(dt));
+    a.cw_log2 = plan.cw_log2; a.nwin = plan.nwin; a.rpb = plan.rpb; a.nrb = plan.nrb;
     dim3 grid((unsigned)(a.nwin * a.nrb), 1, (unsigned)s.batch);
     switch (dt) {
     case DT_I8:   hipLaunchKernelGGL(verify_kernel<DT_I8>, grid, dim3(256), 0, st, a); break;
@@ -637,13 +669,13 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
                 bv[0] = (int)wds[0]; bv[1] = (int)wds[1]; bv[2] = (int)wds[2]; bv[3] = (int)wds[3];
             }
         }
-        acc = T::mfma(av, bv, acc);
+        acc = T::mfma(bv, av, acc);      // B first: lane = row of C, registers = columns
     }
     uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int gr = tr * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
-        if (gr < a.M && col < a.N) T::store_c(Cb, (long)gr * a.ldc + col, acc[i]);
+        const int gc = tc * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
+        if (row < a.M && gc < a.N) T::store_c(Cb, (long)row * a.ldc + gc, acc[i]);
     }
 }
 
@@ -723,7 +755,6 @@ __global__ __launch_bounds__(256) void recount_kernel(CountArgs a)
         if (r) atomicAdd(a.ticket + 1, (unsigned)r);
         if (c) atomicAdd(a.ticket + 2, (unsigned)c);
     }
-    __threadfence();
     __syncthreads();
     if (tid == 0) {
         unsigned t = atomicAdd(a.ticket, 1u);
@@ -731,7 +762,6 @@ __global__ __launch_bounds__(256) void recount_kernel(CountArgs a)
     }
     __syncthreads();
     if (is_last && tid == 0) {
-        __threadfence();
         uint32_t nr = atomicExch(a.ticket + 1, 0u), nc = atomicExch(a.ticket + 2, 0u);
         atomicExch(a.ticket, 0u);
         uint32_t tiles = a.fix_count[0], over = a.fix_count[1];

@@ -3,12 +3,21 @@
 // to cc_obs / rc_obs.  Paper: output checksum fused with the GEMM epilogue (Sec. IV-C memory
 // paragraph, Sec. V "Optimizations" (2)).
 //
-// Accumulator layout of one 32x32 MFMA block: lane l holds column (l & 31) and, in register i,
-// row 8*(i>>2) + 4*(l>>5) + (i&3).  Column sums are therefore in-lane adds plus one exchange
-// between the two half-waves; row sums need a reduction over the 32 lanes of a half-wave.
-//
+// The kernels issue their MFMAs with the B fragment as first operand, so one 32x32 block of
+// accumulators is laid out "row per lane": lane l holds row (l & 31) of the block and, in
+// register i, column 8*(i>>2) + 4*(l>>5) + (i&3) -- four consecutive columns per register
+// quad.  Consequences:
+//   * C goes out through LDS: each lane packs four converted values into one LDS write, the
+//     wave reads the staged rows back 16 bytes per lane and stores whole 256/512-byte row
+//     segments to global memory.
+//   * row sums are in-lane adds plus one exchange between the half-waves;
+//   * column sums need a reduction over the 32 lanes (rows): partial sums are transposed
+//     through LDS instead of a 5-step cross-lane butterfly per value.
 // Every loop over accumulator registers is expanded at compile time (static_for): the
 // accumulators must be addressed with constant indices to stay in registers.
+//
+// LDS use: each wave owns EPI_WAVE_BYTES at smem + wave * EPI_WAVE_BYTES, then the block-wide
+// partial-sum arrays follow.  The caller must have passed a barrier after its last LDS read.
 #pragma once
 #include <type_traits>
 
@@ -25,6 +34,24 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
     }
 }
 
+// bytes of wave-private LDS the epilogue needs for a wave tile that is TN columns wide
+__host__ __device__ constexpr int epi_wave_bytes(int TN) { return 32 * (TN * 4 + 16); }
+__host__ __device__ constexpr int epi_total_bytes(int BM, int BN)
+{
+    return 4 * epi_wave_bytes(BN / 2) + (2 * BM + 2 * BN) * 4;
+}
+
+// pack converted outputs
+template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b);
+template <> __device__ __forceinline__ uint32_t pack2<DT_BF16>(float a, float b)
+{
+    return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+}
+template <> __device__ __forceinline__ uint32_t pack2<DT_F16>(float a, float b)
+{
+    return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
+}
+
 template <int DT, int BM, int BN, bool PROT>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                                               typename Traits<DT>::accv_t (&acc)[BM / 64][BN / 64],
@@ -34,6 +61,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     typedef typename T::acc_t acc_t;
     constexpr int TM = BM / 2, TN = BN / 2;
     constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int OS = T::OS;
+    constexpr int WAVE_BYTES = epi_wave_bytes(TN);
+    constexpr int CROW = TN * OS + 16;              // staged C row (bytes), padded
+    constexpr int SROW = TN * 4 + 16;               // staged partial-sum row (bytes), padded
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
@@ -42,51 +73,84 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     const int Mx = PROT ? M + NTERM : M;
     const int Nx = PROT ? N + NTERM : N;
 
-    acc_t *rs_part = reinterpret_cast<acc_t *>(smem);          // [2][BM] by wave column
-    acc_t *cs_part = rs_part + 2 * BM;                         // [2][BN] by wave row
-    uint8_t *Cb = g.C + (long)bz * g.sC * T::OS;
+    uint8_t *wbuf = smem + wave * WAVE_BYTES;                              // wave-private staging
+    acc_t *rs_part = reinterpret_cast<acc_t *>(smem + 4 * WAVE_BYTES);     // [2][BM] by wave column
+    acc_t *cs_part = rs_part + 2 * BM;                                     // [2][BN] by wave row
+    uint8_t *Cb = g.C + (long)bz * g.sC * OS;
     const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
                           g.inj_col >= n0 && g.inj_col < n0 + BN;
+    const int wr0 = m0 + wm * TM, wc0 = n0 + wn * TN;                      // first row / column of the wave tile
+    const bool wave_inside = (wr0 + TM <= M) && (wc0 + TN <= N) && !inj_here;
 
-    acc_t colsum[NI];
+    // column partial sums of this lane's row group: colp[ni][i] (PROT only)
+    acc_t colp[NI][16];
+    if (PROT) {
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) colsum[ni] = T::zero();
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) colp[ni][i] = T::zero();
+    }
 
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
-        acc_t rowsum[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) rowsum[i] = T::zero();
-        const int br = m0 + wm * TM + mi * 32;                 // first row of this block
-        static_for<0, NI>([&](auto ni_c) {
-            constexpr int ni = decltype(ni_c)::value;
-            const int bc = n0 + wn * TN + ni * 32;             // first column of this block
-            const int gc = bc + l32;
-            // wave-uniform classification of the 32x32 block
-            const bool inside = (br + 32 <= M) && (bc + 32 <= N) && !inj_here;
-            if (inside) {
-                static_for<0, 16>([&](auto i_c) {
-                    constexpr int i = decltype(i_c)::value;
-                    const int gr = br + 8 * (i >> 2) + 4 * lh + (i & 3);
-                    const acc_t v = acc[mi][ni][i];
-                    T::store_c(Cb, (long)gr * g.ldc + gc, v);
+        const int gr = wr0 + mi * 32 + l32;                                // this lane's row
+        acc_t rowsum = T::zero();
+        if (wave_inside) {
+            // ---- stage 32 rows of converted C in LDS, four columns per write
+            static_for<0, NI>([&](auto ni_c) {
+                constexpr int ni = decltype(ni_c)::value;
+                static_for<0, 4>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    const acc_t v0 = acc[mi][ni][4 * q], v1 = acc[mi][ni][4 * q + 1],
+                                v2 = acc[mi][ni][4 * q + 2], v3 = acc[mi][ni][4 * q + 3];
                     if (PROT) {
-                        colsum[ni] = add_t(colsum[ni], v);
-                        rowsum[i] = add_t(rowsum[i], v);
+                        rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
+                        colp[ni][4 * q] = add_t(colp[ni][4 * q], v0);
+                        colp[ni][4 * q + 1] = add_t(colp[ni][4 * q + 1], v1);
+                        colp[ni][4 * q + 2] = add_t(colp[ni][4 * q + 2], v2);
+                        colp[ni][4 * q + 3] = add_t(colp[ni][4 * q + 3], v3);
+                    }
+                    uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
+                    if constexpr (DT == DT_I8) {
+                        *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
+                    } else {
+                        uint2 w;
+                        w.x = pack2<DT>((float)v0, (float)v1);
+                        w.y = pack2<DT>((float)v2, (float)v3);
+                        *reinterpret_cast<uint2 *>(d) = w;
                     }
                 });
-            } else if (br < Mx && bc < Nx) {
+            });
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // ---- read rows back, 16 bytes per lane, and store whole row segments
+            constexpr int LPR = TN * OS / 16;                              // lanes per row
+            constexpr int RPI = 64 / LPR;                                  // rows per instruction
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int r = it * RPI + lane / LPR, cch = lane % LPR;
+                const i32x4 v = *reinterpret_cast<const i32x4 *>(wbuf + r * CROW + cch * 16);
+                *reinterpret_cast<i32x4 *>(Cb + ((long)(wr0 + mi * 32 + r) * g.ldc + wc0) * OS + cch * 16) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else if (wr0 + mi * 32 < Mx && wc0 < Nx) {
+            // ---- edge of the problem, stripe outputs, armed flip: element by element
+            static_for<0, NI>([&](auto ni_c) {
+                constexpr int ni = decltype(ni_c)::value;
                 static_for<0, 16>([&](auto i_c) {
                     constexpr int i = decltype(i_c)::value;
-                    const int gr = br + 8 * (i >> 2) + 4 * lh + (i & 3);
+                    const int gc = wc0 + ni * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
                     acc_t v = acc[mi][ni][i];
                     if (inj_here && gr == g.inj_row && gc == g.inj_col)
                         v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
                     if (gr < M && gc < N) {
                         T::store_c(Cb, (long)gr * g.ldc + gc, v);
                         if (PROT) {
-                            colsum[ni] = add_t(colsum[ni], v);
-                            rowsum[i] = add_t(rowsum[i], v);
+                            rowsum = add_t(rowsum, v);
+                            colp[ni][i] = add_t(colp[ni][i], v);
                         }
                     } else if (PROT) {
                         if (gr >= M && gr < Mx) {
@@ -99,23 +163,42 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                         }
                     }
                 });
-            }
-        });
-        if (PROT) {
-            // row sums: reduce over the 32 lanes that hold one row's columns
-            static_for<0, 16>([&](auto i_c) {
-                constexpr int i = decltype(i_c)::value;
-                acc_t t = half_wave_sum(rowsum[i]);
-                if (l32 == 0) rs_part[wn * BM + wm * TM + mi * 32 + 8 * (i >> 2) + 4 * lh + (i & 3)] = t;
             });
         }
+        if (PROT) {
+            // row sums: the two half-waves hold different columns of the same rows
+            const acc_t t = add_t(rowsum, __shfl_xor(rowsum, 32));
+            if (lh == 0) rs_part[wn * BM + wm * TM + mi * 32 + l32] = t;
+        }
     });
+
     if (PROT) {
-        // column sums: the two half-waves hold different rows of the same columns
+        // ---- column sums: transpose the per-lane partials through LDS.
+        // staged as S[l32][column of the wave tile] (fp32 / int32), then every lane adds up
+        // the 32 rows of two columns.
+        static_for<0, NI>([&](auto ni_c) {
+            constexpr int ni = decltype(ni_c)::value;
+            static_for<0, 4>([&](auto q_c) {
+                constexpr int q = decltype(q_c)::value;
+                uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
+                *reinterpret_cast<i32x4 *>(d) =
+                    i32x4{(int)as_word(colp[ni][4 * q]), (int)as_word(colp[ni][4 * q + 1]),
+                          (int)as_word(colp[ni][4 * q + 2]), (int)as_word(colp[ni][4 * q + 3])};
+            });
+        });
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int c0 = 2 * lane; c0 < TN; c0 += 128) {
+            acc_t s0 = T::zero(), s1 = T::zero();
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) {
-            acc_t t = add_t(colsum[ni], __shfl_xor(colsum[ni], 32));
-            if (lh == 0) cs_part[wm * BN + wn * TN + ni * 32 + l32] = t;
+            for (int r = 0; r < 32; ++r) {
+                const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + c0 * 4);
+                s0 = add_t(s0, from_word<acc_t>(w.x));
+                s1 = add_t(s1, from_word<acc_t>(w.y));
+            }
+            cs_part[wm * BN + wn * TN + c0] = s0;
+            cs_part[wm * BN + wn * TN + c0 + 1] = s1;
         }
         __syncthreads();
         for (int t = tid; t < BM + BN; t += 256) {

@@ -6,6 +6,7 @@
 //     applied by choosing which global 16-byte chunk each lane fetches.
 //   * 256 x 256 tiles, 4 waves of 128 x 128 (sixteen 32x32 MFMA blocks per wave), two LDS
 //     buffers of 64 KB, one barrier per slab.
+//   * MFMAs take the B fragment first, so a lane owns a row of C (see gemm_epilogue.h).
 //   * workgroup -> tile mapping keeps the workgroups that share an XCD (and its L2) on a
 //     compact group of tiles.
 // Rows of the tile beyond the (stripe-augmented) problem are fetched from a valid row instead
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = T::mfma(af[mi], bf[ni], (FIRST && s4 == 0) ? zerov : acc[mi][ni]);
+                    acc[mi][ni] = T::mfma(bf[ni], af[mi], (FIRST && s4 == 0) ? zerov : acc[mi][ni]);
         }
     };
     {

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    if (mact[mi] && nact[ni]) acc[mi][ni] = T::mfma(af[mi], bf[ni], acc[mi][ni]);
+                    if (mact[mi] && nact[ni]) acc[mi][ni] = T::mfma(bf[ni], af[mi], acc[mi][ni]);
         }
     };
 
