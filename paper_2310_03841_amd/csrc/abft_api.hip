@@ -13,9 +13,9 @@ struct abft_ctx {
     abft_config cfg;
     // device pools (32-bit words unless noted)
     uint32_t *pool_depth;   // (2 * ENC_ACC_COPIES + 2) * max_depth words: a_acc, b_acc copies, a_sum, b_sum
-    uint8_t  *pool_stripe;  // 2 * NTERM * max_depth * 2 bytes
+    uint8_t  *pool_stripe;  // NTERM * max_depth * 2 bytes
     uint32_t *pool_batch;   // per-batch scalars
-    uint32_t *pool_rows;    // rc_part (NTERM), rc_pred
+    uint32_t *pool_rows;    // rc_pred
     uint32_t *pool_cols;    // cc_part (NTERM), cc_pred
     uint32_t *pool_obs;     // cc_obs | rc_obs   (zeroed as one region)
     uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
@@ -32,8 +32,7 @@ struct abft_ctx {
     int prof_cap, prof_n;
 };
 
-static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + 2 * NTERM /*w_a,w_b*/ + 1 /*ticket*/ +
-                               NTERM * NTERM /*s_part*/ + 1 /*s_pred*/;
+static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + NTERM /*w_a*/ + 1 /*ticket*/ + 1 /*s_pred*/;
 
 static int fail_hip(abft_ctx *c, hipError_t e)
 {
@@ -78,9 +77,9 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
                  Bt = (size_t)cfg->max_batch;
     struct { void **p; size_t bytes; } req[] = {
         {(void **)&c->pool_depth, (2 * ENC_ACC_COPIES + 2) * D * 4},
-        {(void **)&c->pool_stripe, 2 * NTERM * D * 2},
+        {(void **)&c->pool_stripe, NTERM * D * 2},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
-        {(void **)&c->pool_rows, (NTERM + 1) * R * 4},
+        {(void **)&c->pool_rows, R * 4},
         {(void **)&c->pool_cols, (NTERM + 1) * Cn * 4},
         {(void **)&c->pool_obs, (R + Cn) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
@@ -129,6 +128,7 @@ static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need,
     if (s->transB != 0 && s->transB != 1) return ABFT_EINVAL;
     const int es = elem_size(dt), os = out_size(dt);
     if (dt == ABFT_I8 && s->K >= (1 << 17)) return ABFT_ESHAPE;       // K * 2^14 must stay below 2^31
+    if ((need & 1) && s->K > encode_a_max_k(dt)) return ABFT_ESHAPE;  // rows longer than the encode pass covers
     if ((need & 1) && s->lda < s->K) return ABFT_ESHAPE;
     if ((need & 2) && s->ldb < (s->transB ? s->K : s->N)) return ABFT_ESHAPE;
     if ((need & 4) && s->ldc < s->N) return ABFT_ESHAPE;
@@ -165,18 +165,14 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->a_sum = c->pool_depth + 2 * ENC_ACC_COPIES * D;
     w->b_sum = c->pool_depth + (2 * ENC_ACC_COPIES + 1) * D;
     w->stripe_a = c->pool_stripe;
-    w->stripe_b = c->pool_stripe + NTERM * D * 2;
     uint32_t *pb = c->pool_batch;
     w->max_acc = pb;                          pb += 2 * Bt;
     w->maxabs = (float *)pb;                  pb += 2 * Bt;
     w->tau = (float *)pb;                     pb += Bt;
     w->w_a = (float *)pb;                     pb += NTERM * Bt;
-    w->w_b = (float *)pb;                     pb += NTERM * Bt;
     w->enc_ticket = pb;                       pb += Bt;
-    w->s_part = pb;                           pb += NTERM * NTERM * Bt;
     w->s_pred = pb;
-    w->rc_part = c->pool_rows;
-    w->rc_pred = c->pool_rows + NTERM * R;
+    w->rc_pred = c->pool_rows;
     w->cc_part = c->pool_cols;
     w->cc_pred = c->pool_cols + NTERM * Cn;
     w->cc_obs = c->pool_obs;
@@ -219,7 +215,7 @@ extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, con
     Workspace w;
     carve(ctx, dtype, sh, &w);
     ctx->b_valid = false;
-    HIP_TRY(launch_encode(dtype, nullptr, B, false, true, sh, w, 0.f, nullptr, 0, (hipStream_t)stream));
+    HIP_TRY(launch_encode_b(dtype, B, sh, w, (hipStream_t)stream));
     ctx->b_valid = true;
     ctx->b_dt = dtype;
     ctx->b_shape = *s;
@@ -261,8 +257,9 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->arm.batch = -1;
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
-    HIP_TRY(launch_encode(dtype, A, B, true, !cached, sh, w, v.tau_override, w.cc_obs,
-                          (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, st));
+    HIP_TRY(launch_encode_a(dtype, A, sh, w, v.tau_override, w.cc_obs,
+                            (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
     HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));

@@ -6,7 +6,7 @@
 
 namespace abft {
 
-// Number of rows (columns) of the encoded checksum stripe appended to A (B).
+// Number of rows of the encoded checksum stripe appended to A.
 // int8: four signed base-256 digits of the int32 sum; bf16/f16: three terms of
 // the fp32 sum (high, middle, low) and one zero row.
 constexpr int NTERM = 4;
@@ -37,13 +37,12 @@ struct Workspace {
     uint32_t *max_acc;              // [batch][2]   atomic max of |A|, |B| (float bits), self-cleaning
     float    *maxabs;               // [batch][2]
     float    *tau;                  // [batch]
-    float    *w_a, *w_b;            // [batch][NTERM] weights that recombine the stripe terms (fp)
-    uint8_t  *stripe_a, *stripe_b;  // [batch][NTERM][Kp] in the operand type
+    float    *w_a;                  // [batch][NTERM] weights that recombine the stripe terms (fp)
+    uint8_t  *stripe_a;             // [batch][NTERM][Kp] terms of a in the operand type
     uint32_t *enc_ticket;           // [batch]
-    // predicted (raw stripe outputs, then recombined)
-    uint32_t *cc_part, *rc_part;    // [batch][NTERM][N], [batch][NTERM][M]
-    uint32_t *s_part;               // [batch][NTERM*NTERM]
-    uint32_t *cc_pred, *rc_pred;    // [batch][N], [batch][M]
+    // predicted
+    uint32_t *cc_part;              // [batch][NTERM][N] raw stripe outputs of the GEMM
+    uint32_t *cc_pred, *rc_pred;    // [batch][N] recombined, [batch][M] from the A pass
     uint32_t *s_pred;               // [batch]
     // observed
     uint32_t *cc_obs, *rc_obs;      // epilogue sums (atomics)
@@ -70,9 +69,10 @@ struct Verdict {                    // caller buffers
 
 // ---- launchers (each enqueues on `st`, returns the hipError_t of the launch) ----
 hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st);
-hipError_t launch_encode(int dt, const void *A, const void *B, bool do_a, bool do_b, const Shape &s,
-                         const Workspace &w, float tau_override, uint32_t *zero_ptr, size_t zero_words,
-                         hipStream_t st);
+hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspace &w, hipStream_t st);
+hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspace &w, float tau_override,
+                           uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
+int encode_a_max_k(int dt);
 hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
                        const Workspace &w, const InjectArm &arm, hipStream_t st);
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, bool use_vobs, const Verdict &v,

@@ -29,41 +29,16 @@ hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st)
 }
 
 // ====================================================================== encode
-// One side (A or B) of the encode step.  The stored array has `rows` rows of
-// `cols` elements.  reduce_rows = 1: out[col] = sum over rows (A: e^T A; B
-// stored N x K: B e).  reduce_rows = 0: out[row] = sum over cols (B stored
-// K x N: B e).
-struct EncSide {
-    const uint8_t *X;
-    long ld, stride;      // elements
-    int rows, cols;
-    int reduce_rows;
-    int cw_log2;          // 16-byte chunk columns per block window (power of two <= 64)
-    int rpb;              // rows per block
-    int nwin, nrb;
-    uint32_t *acc;        // [ENC_COPIES][batch][K] atomic accumulators (copy stride acc_stride words)
-    long acc_stride;
-    uint32_t *sum;        // [batch][K] final sums
-    uint8_t *stripe;      // [batch][NTERM][Kp]
-    float *w;             // [batch][NTERM]
-    int active;
-};
-
-struct EncArgs {
-    EncSide side[2];
-    int K, Kp;
-    uint32_t *max_acc;    // [batch][2]
-    float *maxabs;        // [batch][2]
-    float *tau;           // [batch]
-    uint32_t *ticket;     // [batch]
-    float tau_override;
-    uint32_t *zero_ptr;
-    size_t zero_words;
-};
-
-constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread
+// Input-side checksum vectors (Sec. III-B.1 "Checksums"): a = e^T A (the input summed over its
+// rows) and b = B e (the weight reduced over its output dimension), both of length K, plus
+// what only a pass over the operands can give: max|A|, max|B| for the tolerance, and the row
+// checksum prediction rc_pred = A b.  That last product is a matrix-vector product, bound by
+// the read of A, so it rides on the same streaming pass instead of occupying MFMA tiles.
+// The pass over B comes first (b must be complete before A b); for a weight it is done once,
+// offline (remark (2) of the same paragraph).
+constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread (B pass)
 // Atomics on one cache line are served one after the other (tens of nanoseconds each), so the
-// row blocks of the encode pass spread their column sums over this many accumulator copies.
+// row blocks of a pass spread their column sums over several accumulator copies.
 constexpr int ENC_COPIES = ENC_ACC_COPIES;
 
 // Split an int32 sum into four signed base-256 digits: v = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3 (mod 2^32).
@@ -77,27 +52,279 @@ __device__ __forceinline__ void split_digits(int v, int8_t d[NTERM])
     }
 }
 
+// Sum the accumulator copies of column k, leave them clean for the next call.
+template <typename acc_t>
+__device__ __forceinline__ acc_t take_copies(uint32_t *acc, long stride, int k)
+{
+    uint32_t part[ENC_COPIES];
+#pragma unroll
+    for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomicExch(acc + c * stride + k, 0u);
+    acc_t t = from_word<acc_t>(part[0]);
+#pragma unroll
+    for (int c = 1; c < ENC_COPIES; ++c) t = add_t(t, from_word<acc_t>(part[c]));
+    return t;
+}
+
+// ---------------------------------------------------------------- B pass: b = B e, max|B|
+// The stored array has `rows` rows of `cols` elements.  reduce_rows = 1 (B stored N x K):
+// b[col] = sum over rows.  reduce_rows = 0 (B stored K x N): b[row] = sum over cols.
+struct EncBArgs {
+    const uint8_t *X;
+    long ld, stride;      // elements
+    int rows, cols, K;
+    int reduce_rows;
+    int cw_log2;          // 16-byte chunk columns per block window (power of two <= 64)
+    int rpb;              // rows per block
+    int nwin, nrb;
+    uint32_t *acc;        // [ENC_COPIES][batch][K] atomic accumulators
+    long acc_stride;
+    uint32_t *sum;        // [batch][K]
+    uint32_t *max_acc;    // [batch][2]
+    float *maxabs;        // [batch][2]
+    uint32_t *ticket;     // [batch]
+};
+
 template <int DT>
-__device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /*[4] LDS*/)
+__global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
 {
     using T = Traits<DT>;
-    const EncSide &sd = e.side[sidx];
-    const int tid = threadIdx.x;
-    const int K = e.K, Kp = e.Kp;
-    uint32_t *acc = sd.acc + (long)bz * K;
-    uint32_t *sum = sd.sum + (long)bz * K;
-    uint8_t *stripe = sd.stripe + (long)bz * NTERM * Kp * T::ES;
+    typedef typename T::acc_t acc_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    __shared__ acc_t red[256 * CE];
+    __shared__ float fred[4];
+    __shared__ int is_last;
 
+    const int tid = threadIdx.x, bz = blockIdx.z;
+    const int win = blockIdx.x % e.nwin, rb = blockIdx.x / e.nwin;
+    const int CW = 1 << e.cw_log2, RL = 256 >> e.cw_log2;
+    const int cx = tid & (CW - 1), ry = tid >> e.cw_log2;
+    const int col0 = (win * CW + cx) * CE;
+    const bool colok = col0 < e.cols;
+    const int nvalid = e.cols - col0;                        // elements of this chunk inside the row
+    const uint8_t *Xb = e.X + (long)bz * e.stride * ES;
+    const int rbeg = rb * e.rpb;
+    const int rend = min(rbeg + e.rpb, e.rows);
+    const int iters = (e.rpb + RL * ENC_UNROLL - 1) / (RL * ENC_UNROLL);
+
+    acc_t colacc[CE];
+#pragma unroll
+    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
+    float mx = 0.f;
+
+    for (int it = 0; it < iters; ++it) {
+        // a batch of independent loads first: the pass is bound by memory latency otherwise
+        i32x4 v[ENC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            v[u] = i32x4{0, 0, 0, 0};
+            if (colok && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Xb + ((long)r * e.ld + col0) * ES);
+        }
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
+            i32x4 w = v[u];
+            if (nvalid < CE) w = mask_chunk(w, nvalid > 0 ? nvalid * ES : 0);
+            acc_t s = T::zero();
+#pragma unroll
+            for (int q = 0; q < CE; ++q) {
+                acc_t x = T::elem(w, q);
+                if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
+                colacc[q] = add_t(colacc[q], x);
+                s = add_t(s, x);
+            }
+            if (!e.reduce_rows) {
+                for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+                if (cx == 0 && r < rend) atomic_add_word(e.acc + (long)bz * e.K + r, s);
+            }
+        }
+    }
+    if (e.reduce_rows) {
+#pragma unroll
+        for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
+        __syncthreads();
+        // one atomic per column, consecutive lanes on consecutive addresses
+        for (int c = tid; c < CW * CE; c += 256) {
+            const int col = win * CW * CE + c;
+            if (col < e.cols) {
+                acc_t t = red[c];
+                for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
+                atomic_add_word(e.acc + (rb % ENC_COPIES) * e.acc_stride + (long)bz * e.K + col, t);
+            }
+        }
+    }
+    if (!T::IS_INT) {
+        mx = wave_max(mx);
+        __syncthreads();
+        if ((tid & 63) == 0) fred[tid >> 6] = mx;
+        __syncthreads();
+        if (tid == 0)
+            atomicMax(e.max_acc + (long)bz * 2 + 1,
+                      __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
+    }
+    // Last block of this batch item finalises.  Everything other workgroups must see was
+    // written with device-scope atomic read-modify-writes, which are performed at the device's
+    // coherence point; the barrier waits for this workgroup's outstanding ones before the
+    // ticket is taken.  (A device-wide fence here costs tens of microseconds per launch.)
+    __syncthreads();
+    if (tid == 0) {
+        unsigned t = atomicAdd(e.ticket + bz, 1u);
+        is_last = (t == (unsigned)(e.nwin * e.nrb) - 1);
+        if (is_last) atomicExch(e.ticket + bz, 0u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    for (int k = tid; k < e.K; k += 256)
+        e.sum[(long)bz * e.K + k] = as_word(take_copies<acc_t>(e.acc + (long)bz * e.K, e.acc_stride, k));
+    if (!T::IS_INT && tid == 0)
+        e.maxabs[(long)bz * 2 + 1] = __uint_as_float(atomicExch(e.max_acc + (long)bz * 2 + 1, 0u));
+}
+
+// ---------------------------------------------------------------- A pass: a = e^T A, A b, max|A|, stripe
+// A block owns whole rows: CW lanes of 16-byte chunks cover a row in NW windows, 256 / CW rows
+// at a time, so the dot product of a row with b completes inside the block (no atomics, no
+// zeroing for rc_pred).  Column sums go to the accumulator copies; the last block of a batch
+// item turns them into a, its stripe encoding, and the tolerance.
+struct EncAArgs {
+    const uint8_t *A;
+    long lda, sA;
+    int M, K, Kp;
+    int cw_log2, nwin, rpb, nrb;
+    uint32_t *a_acc;
+    long acc_stride;
+    uint32_t *a_sum;
+    const uint32_t *b_sum;
+    uint32_t *rc_pred;
+    uint8_t *stripe;      // [batch][NTERM][Kp] operand elements
+    float *w_a;           // [batch][NTERM]
+    uint32_t *max_acc;
+    float *maxabs, *tau;
+    uint32_t *ticket;
+    float tau_override;
+    uint32_t *zero_ptr;
+    size_t zero_words;
+};
+
+__device__ __forceinline__ int mul_t(int x, int y) { return (int)((uint32_t)x * (uint32_t)y); }
+__device__ __forceinline__ float mul_t(float x, float y) { return x * y; }
+
+template <int DT, int NW>
+__global__ __launch_bounds__(256) void encode_a_kernel(EncAArgs e)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    constexpr int UR = NW >= 8 ? 1 : 8 / NW;              // rows in flight per thread
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    __shared__ float fred[4];
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, bz = blockIdx.z, rb = blockIdx.x;
+    const int K = e.K, M = e.M;
+    // every block takes a share of the words that must start at zero for the GEMM epilogue
+    {
+        size_t nb = (size_t)gridDim.x * gridDim.z;
+        size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
+        for (size_t i = bid * 256 + tid; i < e.zero_words; i += nb * 256) e.zero_ptr[i] = 0u;
+    }
+    const int CW = 1 << e.cw_log2, RL = 256 >> e.cw_log2;
+    const int cx = tid & (CW - 1), ry = tid >> e.cw_log2;
+    const int span = e.nwin * CW * CE;                      // columns covered by the windows (>= K)
+    acc_t *bl = reinterpret_cast<acc_t *>(lds);             // b staged, zero beyond K
+    acc_t *red = bl + span;                                 // [RL][CW * CE]
+    for (int k = tid; k < span; k += 256)
+        bl[k] = k < K ? from_word<acc_t>(e.b_sum[(long)bz * K + k]) : T::zero();
+    __syncthreads();
+
+    const uint8_t *Ab = e.A + (long)bz * e.sA * ES;
+    const int rbeg = rb * e.rpb, rend = min(rbeg + e.rpb, M);
+    const int iters = (e.rpb + RL * UR - 1) / (RL * UR);
+
+    acc_t colacc[NW][CE];
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int q = 0; q < CE; ++q) colacc[w][q] = T::zero();
+    float mx = 0.f;
+
+    for (int it = 0; it < iters; ++it) {
+        i32x4 v[UR][NW];
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            const int r = rbeg + ry + (it * UR + u) * RL;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const int col0 = (w * CW + cx) * CE;
+                v[u][w] = i32x4{0, 0, 0, 0};
+                if (w < e.nwin && col0 < K && r < rend)
+                    v[u][w] = *reinterpret_cast<const i32x4 *>(Ab + ((long)r * e.lda + col0) * ES);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UR; ++u) {
+            const int r = rbeg + ry + (it * UR + u) * RL;
+            acc_t dot = T::zero();
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                if (w < e.nwin) {
+                    const int col0 = (w * CW + cx) * CE;
+                    i32x4 x4 = v[u][w];
+                    if (K - col0 < CE) x4 = mask_chunk(x4, K - col0 > 0 ? (K - col0) * ES : 0);
+#pragma unroll
+                    for (int q = 0; q < CE; ++q) {
+                        const acc_t x = T::elem(x4, q);
+                        if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
+                        colacc[w][q] = add_t(colacc[w][q], x);
+                        dot = add_t(dot, mul_t(x, bl[col0 + q]));
+                    }
+                }
+            }
+            for (int o = 1; o < CW; o <<= 1) dot = add_t(dot, __shfl_xor(dot, o));
+            if (cx == 0 && r < rend) e.rc_pred[(long)bz * M + r] = as_word(dot);
+        }
+    }
+    // column sums: reduce over the row lanes in LDS, then one coalesced atomic per column
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        if (w < e.nwin) {
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[w][q];
+            __syncthreads();
+            for (int c = tid; c < CW * CE; c += 256) {
+                const int col = w * CW * CE + c;
+                if (col < K) {
+                    acc_t t = red[c];
+                    for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
+                    atomic_add_word(e.a_acc + (rb % ENC_COPIES) * e.acc_stride + (long)bz * K + col, t);
+                }
+            }
+        }
+    }
+    if (!T::IS_INT) {
+        mx = wave_max(mx);
+        __syncthreads();
+        if ((tid & 63) == 0) fred[tid >> 6] = mx;
+        __syncthreads();
+        if (tid == 0)
+            atomicMax(e.max_acc + (long)bz * 2, __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
+    }
+    // last block of this batch item finalises (same ordering argument as in the B pass)
+    __syncthreads();
+    if (tid == 0) {
+        unsigned t = atomicAdd(e.ticket + bz, 1u);
+        is_last = (t == gridDim.x - 1);
+        if (is_last) atomicExch(e.ticket + bz, 0u);
+    }
+    __syncthreads();
+    if (!is_last) return;
+
+    const int Kp = e.Kp;
+    uint32_t *sum = e.a_sum + (long)bz * K;
+    uint8_t *stripe = e.stripe + (long)bz * NTERM * Kp * ES;
     float amax = 0.f;
     for (int k = tid; k < K; k += 256) {
-        // take the totals and leave the accumulators clean for the next call
-        uint32_t part[ENC_COPIES];
-#pragma unroll
-        for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomicExch(acc + c * sd.acc_stride + k, 0u);
-        typename T::acc_t t = from_word<typename T::acc_t>(part[0]);
-#pragma unroll
-        for (int c = 1; c < ENC_COPIES; ++c) t = add_t(t, from_word<typename T::acc_t>(part[c]));
-        const uint32_t w = as_word(t);
+        const uint32_t w = as_word(take_copies<acc_t>(e.a_acc + (long)bz * K, e.acc_stride, k));
         sum[k] = w;
         if (!T::IS_INT) amax = fmaxf(amax, fabsf(__uint_as_float(w)));
     }
@@ -106,9 +333,9 @@ __device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /
         // power-of-two pre-scale so the largest |sum| sits in [2^13, 2^14): well inside fp16 range
         amax = wave_max(amax);
         __syncthreads();
-        if ((tid & 63) == 0) red[tid >> 6] = amax;
+        if ((tid & 63) == 0) fred[tid >> 6] = amax;
         __syncthreads();
-        amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        amax = fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]));
         int sh = 0;
         if (amax > 0.f && amax <= 3.0e38f) {
             int ex;
@@ -130,6 +357,7 @@ __device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /
             if (k < K) {
                 float v = __uint_as_float(sum[k]);
                 if (DT == DT_BF16) {
+                    // three bf16 terms carry the 24 significant bits of the fp32 sum
                     uint32_t t0 = f32_to_bf16_bits(v);
                     float r1 = v - bf16_bits_to_f32(t0);
                     uint32_t t1 = f32_to_bf16_bits(r1);
@@ -137,6 +365,7 @@ __device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /
                     uint32_t t2 = f32_to_bf16_bits(r2);
                     h[0] = (uint16_t)t0; h[1] = (uint16_t)t1; h[2] = (uint16_t)t2;
                 } else {
+                    // fp16 terms: each remainder is rescaled by 2^11 to stay in the normal range
                     float x = v * scale;
                     uint32_t t0 = f32_to_f16_bits(x);
                     float r1 = (x - f16_bits_to_f32(t0)) * 2048.f;
@@ -151,132 +380,23 @@ __device__ void encode_finalize(const EncArgs &e, int sidx, int bz, float *red /
         }
     }
     if (!T::IS_INT && tid == 0) {
-        float *w = sd.w + (long)bz * NTERM;
+        float *w = e.w_a + (long)bz * NTERM;
         if (DT == DT_BF16) { w[0] = 1.f; w[1] = 1.f; w[2] = 1.f; w[3] = 0.f; }
         else { w[0] = inv; w[1] = inv * (1.f / 2048.f); w[2] = inv * (1.f / 4194304.f); w[3] = 0.f; }
-        uint32_t mb = atomicExch(e.max_acc + (long)bz * 2 + sidx, 0u);
-        e.maxabs[(long)bz * 2 + sidx] = __uint_as_float(mb);
+        const float ma = __uint_as_float(atomicExch(e.max_acc + (long)bz * 2, 0u));
+        e.maxabs[(long)bz * 2] = ma;
+        const float mb = e.maxabs[(long)bz * 2 + 1];
+        e.tau[bz] = e.tau_override > 0.f ? e.tau_override : (1e-3f * (float)K) * ma * mb;
     }
 }
 
-template <int DT>
-__global__ __launch_bounds__(256) void encode_kernel(EncArgs e)
+struct EncPlan { int cw_log2, nwin, rpb, nrb; };
+
+// windowed streaming pass over a rows x cols array (B pass, verify)
+static EncPlan plan_window(int rows, int cols, int chunk_elems)
 {
-    using T = Traits<DT>;
-    typedef typename T::acc_t acc_t;
-    constexpr int ES = T::ES, CE = 16 / ES;
-    __shared__ acc_t red[256 * CE];
-    __shared__ float fred[4];
-    __shared__ int is_last;
-
-    const int tid = threadIdx.x;
-    // every block takes a share of the words that must start at zero
-    {
-        size_t nb = (size_t)gridDim.x * gridDim.y * gridDim.z;
-        size_t bid = blockIdx.x + (size_t)gridDim.x * (blockIdx.y + (size_t)gridDim.y * blockIdx.z);
-        for (size_t i = bid * 256 + tid; i < e.zero_words; i += nb * 256) e.zero_ptr[i] = 0u;
-    }
-    const int sidx = blockIdx.y, bz = blockIdx.z;
-    const EncSide &sd = e.side[sidx];
-    if (!sd.active || (int)blockIdx.x >= sd.nwin * sd.nrb) return;
-
-    const int win = blockIdx.x % sd.nwin, rb = blockIdx.x / sd.nwin;
-    const int CW = 1 << sd.cw_log2, RL = 256 >> sd.cw_log2;
-    const int cx = tid & (CW - 1), ry = tid >> sd.cw_log2;
-    const int col0 = (win * CW + cx) * CE;
-    const bool colok = col0 < sd.cols;
-    const int nvalid = sd.cols - col0;                       // elements of this chunk inside the row
-    const uint8_t *Xb = sd.X + (long)bz * sd.stride * ES;
-    const int rbeg = rb * sd.rpb;
-    const int rend = min(rbeg + sd.rpb, sd.rows);
-    const int iters = (sd.rpb + RL * ENC_UNROLL - 1) / (RL * ENC_UNROLL);
-
-    acc_t colacc[CE];
-#pragma unroll
-    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
-    float mx = 0.f;
-
-    for (int it = 0; it < iters; ++it) {
-        // issue a batch of independent loads first: the pass is bound by memory latency otherwise
-        i32x4 v[ENC_UNROLL];
-#pragma unroll
-        for (int u = 0; u < ENC_UNROLL; ++u) {
-            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
-            v[u] = i32x4{0, 0, 0, 0};
-            if (colok && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Xb + ((long)r * sd.ld + col0) * ES);
-        }
-#pragma unroll
-        for (int u = 0; u < ENC_UNROLL; ++u) {
-            const int r = rbeg + ry + (it * ENC_UNROLL + u) * RL;
-            i32x4 w = v[u];
-            if (nvalid < CE) w = mask_chunk(w, nvalid > 0 ? nvalid * ES : 0);
-            acc_t s = T::zero();
-#pragma unroll
-            for (int q = 0; q < CE; ++q) {
-                acc_t x = T::elem(w, q);
-                if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
-                colacc[q] = add_t(colacc[q], x);
-                s = add_t(s, x);
-            }
-            if (!sd.reduce_rows) {
-                for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
-                if (cx == 0 && r < rend) atomic_add_word(sd.acc + (long)bz * e.K + r, s);
-            }
-        }
-    }
-    if (sd.reduce_rows) {
-#pragma unroll
-        for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[q];
-        __syncthreads();
-        // one atomic per column, consecutive lanes on consecutive addresses: atomics that hit
-        // the same cache line are served one after the other, so their number is what counts
-        for (int c = tid; c < CW * CE; c += 256) {
-            const int col = win * CW * CE + c;
-            if (col < sd.cols) {
-                acc_t t = red[c];
-                for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
-                atomic_add_word(sd.acc + (rb % ENC_COPIES) * sd.acc_stride + (long)bz * e.K + col, t);
-            }
-        }
-    }
-    if (!T::IS_INT) {
-        mx = wave_max(mx);
-        __syncthreads();
-        if ((tid & 63) == 0) fred[tid >> 6] = mx;
-        __syncthreads();
-        if (tid == 0)
-            atomicMax(e.max_acc + (long)bz * 2 + sidx,
-                      __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
-    }
-    // last block of this batch item finalises both sides.  Everything other workgroups must
-    // see was written with device-scope atomic read-modify-writes, which are performed at the
-    // device's coherence point; the barrier waits for this workgroup's outstanding ones before
-    // the ticket is taken.  (A device-wide fence here costs tens of microseconds per launch.)
-    __syncthreads();
-    if (tid == 0) {
-        unsigned expected = 0;
-        for (int q = 0; q < 2; ++q)
-            if (e.side[q].active) expected += (unsigned)(e.side[q].nwin * e.side[q].nrb);
-        unsigned t = atomicAdd(e.ticket + bz, 1u);
-        is_last = (t == expected - 1);
-        if (is_last) atomicExch(e.ticket + bz, 0u);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    for (int q = 0; q < 2; ++q)
-        if (e.side[q].active) encode_finalize<DT>(e, q, bz, fred);
-    if (!T::IS_INT && e.side[0].active) {
-        __syncthreads();
-        if (tid == 0) {
-            float ma = e.maxabs[(long)bz * 2 + 0], mb = e.maxabs[(long)bz * 2 + 1];
-            e.tau[bz] = e.tau_override > 0.f ? e.tau_override : (1e-3f * (float)e.K) * ma * mb;
-        }
-    }
-}
-
-static void plan_side(EncSide &sd, int chunk_elems)
-{
-    const int chunks = (sd.cols + chunk_elems - 1) / chunk_elems;
+    EncPlan p;
+    const int chunks = (cols + chunk_elems - 1) / chunk_elems;
     // window width (power of two, 8..64 chunk columns): least padding, then widest
     int best_lg = 3;
     long best_waste = -1;
@@ -285,61 +405,108 @@ static void plan_side(EncSide &sd, int chunk_elems)
         const long waste = (long)((chunks + CW - 1) / CW) * CW - chunks;
         if (best_waste < 0 || waste <= best_waste) { best_waste = waste; best_lg = lg; }
     }
-    sd.cw_log2 = best_lg;
+    p.cw_log2 = best_lg;
     const int CW = 1 << best_lg, RL = 256 / CW;
-    sd.nwin = (chunks + CW - 1) / CW;
-    // rows per block: one batch of ENC_UNROLL loads per thread, more when the matrix is tall
-    // enough that the grid would otherwise exceed a few thousand blocks
+    p.nwin = (chunks + CW - 1) / CW;
+    // rows per block: one batch of ENC_UNROLL loads per thread, more when the matrix is tall:
+    // fewer blocks mean fewer atomics on the same cache lines
     int rpb = RL * ENC_UNROLL;
-    while ((long)sd.nwin * ((sd.rows + rpb - 1) / rpb) > 640) rpb *= 2;
-    sd.rpb = rpb;
-    sd.nrb = (sd.rows + rpb - 1) / rpb;
+    while ((long)p.nwin * ((rows + rpb - 1) / rpb) > 640) rpb *= 2;
+    p.rpb = rpb;
+    p.nrb = (rows + rpb - 1) / rpb;
+    return p;
 }
 
-hipError_t launch_encode(int dt, const void *A, const void *B, bool do_a, bool do_b, const Shape &s,
-                         const Workspace &w, float tau_override, uint32_t *zero_ptr, size_t zero_words,
-                         hipStream_t st)
+hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspace &w, hipStream_t st)
 {
-    EncArgs e;
-    const int ce = 16 / elem_size(dt);
-    EncSide &a = e.side[0];
-    a.X = (const uint8_t *)A; a.ld = s.lda; a.stride = s.sA; a.rows = s.M; a.cols = s.K;
-    a.reduce_rows = 1; a.acc = w.a_acc; a.acc_stride = w.acc_stride; a.sum = w.a_sum; a.stripe = w.stripe_a; a.w = w.w_a;
-    a.active = do_a ? 1 : 0;
-    plan_side(a, ce);
-    EncSide &b = e.side[1];
-    b.X = (const uint8_t *)B; b.ld = s.ldb; b.stride = s.sB;
-    if (s.transB) { b.rows = s.N; b.cols = s.K; b.reduce_rows = 1; }
-    else          { b.rows = s.K; b.cols = s.N; b.reduce_rows = 0; }
-    b.acc = w.b_acc; b.acc_stride = w.acc_stride; b.sum = w.b_sum; b.stripe = w.stripe_b; b.w = w.w_b;
-    b.active = do_b ? 1 : 0;
-    plan_side(b, ce);
-    e.K = s.K; e.Kp = s.Kp;
-    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.tau = w.tau; e.ticket = w.enc_ticket;
-    e.tau_override = tau_override;
-    e.zero_ptr = zero_ptr; e.zero_words = zero_words;
-    int na = do_a ? a.nwin * a.nrb : 0, nb = do_b ? b.nwin * b.nrb : 0;
-    dim3 grid((unsigned)(na > nb ? na : nb), 2, (unsigned)s.batch);
+    EncBArgs e;
+    e.X = (const uint8_t *)B; e.ld = s.ldb; e.stride = s.sB; e.K = s.K;
+    if (s.transB) { e.rows = s.N; e.cols = s.K; e.reduce_rows = 1; }
+    else          { e.rows = s.K; e.cols = s.N; e.reduce_rows = 0; }
+    EncPlan p = plan_window(e.rows, e.cols, 16 / elem_size(dt));
+    e.cw_log2 = p.cw_log2; e.nwin = p.nwin; e.rpb = p.rpb; e.nrb = p.nrb;
+    e.acc = w.b_acc; e.acc_stride = w.acc_stride; e.sum = w.b_sum;
+    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.ticket = w.enc_ticket;
+    dim3 grid((unsigned)(e.nwin * e.nrb), 1, (unsigned)s.batch);
     switch (dt) {
-    case DT_I8:   hipLaunchKernelGGL(encode_kernel<DT_I8>, grid, dim3(256), 0, st, e); break;
-    case DT_BF16: hipLaunchKernelGGL(encode_kernel<DT_BF16>, grid, dim3(256), 0, st, e); break;
-    case DT_F16:  hipLaunchKernelGGL(encode_kernel<DT_F16>, grid, dim3(256), 0, st, e); break;
+    case DT_I8:   hipLaunchKernelGGL(encode_b_kernel<DT_I8>, grid, dim3(256), 0, st, e); break;
+    case DT_BF16: hipLaunchKernelGGL(encode_b_kernel<DT_BF16>, grid, dim3(256), 0, st, e); break;
+    case DT_F16:  hipLaunchKernelGGL(encode_b_kernel<DT_F16>, grid, dim3(256), 0, st, e); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
+// Largest K the A pass handles (8 windows of 64 chunks of 16 bytes, 4 windows for int8).
+int encode_a_max_k(int dt) { return dt == DT_I8 ? 4 * 64 * 16 : 8 * 64 * 8; }
+
+template <int DT>
+static hipError_t launch_encode_a_t(EncAArgs &e, int batch, hipStream_t st)
+{
+    constexpr int CE = 16 / Traits<DT>::ES;
+    const int CW = 1 << e.cw_log2;
+    const size_t smem = ((size_t)e.nwin * CW * CE + 256 * CE) * 4;
+    dim3 grid((unsigned)e.nrb, 1, (unsigned)batch);
+    if (e.nwin <= 1)      hipLaunchKernelGGL((encode_a_kernel<DT, 1>), grid, dim3(256), smem, st, e);
+    else if (e.nwin <= 2) hipLaunchKernelGGL((encode_a_kernel<DT, 2>), grid, dim3(256), smem, st, e);
+    else if (e.nwin <= 4) hipLaunchKernelGGL((encode_a_kernel<DT, 4>), grid, dim3(256), smem, st, e);
+    else if (DT != DT_I8 && e.nwin <= 8) hipLaunchKernelGGL((encode_a_kernel<DT, (DT == DT_I8 ? 4 : 8)>), grid, dim3(256), smem, st, e);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspace &w, float tau_override,
+                           uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
+{
+    EncAArgs e;
+    const int ce = 16 / elem_size(dt);
+    const int chunks = (s.K + ce - 1) / ce;
+    const int nw_max = dt == DT_I8 ? 4 : 8;
+    // window width: least padding among (CW, nwin) with nwin <= nw_max, then widest
+    int best_lg = -1;
+    long best_waste = -1;
+    for (int lg = 3; lg <= 6; ++lg) {
+        const int CW = 1 << lg, nwin = (chunks + CW - 1) / CW;
+        if (nwin > nw_max) continue;
+        const long waste = (long)nwin * CW - chunks;
+        if (best_waste < 0 || waste <= best_waste) { best_waste = waste; best_lg = lg; }
+    }
+    if (best_lg < 0) return hipErrorInvalidValue;
+    e.cw_log2 = best_lg;
+    const int CW = 1 << best_lg, RL = 256 / CW;
+    e.nwin = (chunks + CW - 1) / CW;
+    int nwt = 1;
+    while (nwt < e.nwin) nwt *= 2;
+    const int UR = nwt >= 8 ? 1 : 8 / nwt;
+    int rpb = RL * UR;
+    while ((s.M + rpb - 1) / rpb > 512) rpb *= 2;
+    e.rpb = rpb;
+    e.nrb = (s.M + rpb - 1) / rpb;
+    e.A = (const uint8_t *)A; e.lda = s.lda; e.sA = s.sA; e.M = s.M; e.K = s.K; e.Kp = s.Kp;
+    e.a_acc = w.a_acc; e.acc_stride = w.acc_stride; e.a_sum = w.a_sum; e.b_sum = w.b_sum;
+    e.rc_pred = w.rc_pred; e.stripe = w.stripe_a; e.w_a = w.w_a;
+    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.tau = w.tau; e.ticket = w.enc_ticket;
+    e.tau_override = tau_override; e.zero_ptr = zero_ptr; e.zero_words = zero_words;
+    switch (dt) {
+    case DT_I8:   return launch_encode_a_t<DT_I8>(e, s.batch, st);
+    case DT_BF16: return launch_encode_a_t<DT_BF16>(e, s.batch, st);
+    case DT_F16:  return launch_encode_a_t<DT_F16>(e, s.batch, st);
+    }
+    return hipErrorInvalidValue;
+}
+
 // ===================================================================== compare
 struct CmpArgs {
-    const uint32_t *cc_part, *rc_part, *s_part;
-    uint32_t *cc_pred, *rc_pred, *s_pred;
+    const uint32_t *cc_part, *a_sum, *b_sum;
+    uint32_t *cc_pred, *s_pred;
+    const uint32_t *rc_pred;
     const uint32_t *cc_obs, *rc_obs;
-    const float *w_a, *w_b, *tau;
+    const float *w_a, *tau;
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
-    int M, N, batch;
-    int recombine;        // 1: build predictions from the stripe outputs; 0: reuse stored predictions
+    int M, N, K, batch;
+    int recombine;        // 1: build the column predictions from the stripe outputs; 0: reuse stored ones
 };
 
 template <bool IS_INT>
@@ -376,17 +543,15 @@ template <bool IS_INT>
 __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
 {
     __shared__ int is_last;
+    __shared__ uint32_t sred[4];
     const int bz = blockIdx.z, tid = threadIdx.x;
     const int idx = blockIdx.x * 256 + tid;
     const int M = a.M, N = a.N;
     const float tol = IS_INT ? 0.f : a.tau[bz];
     bool frow = false, fcol = false;
     if (idx < M) {
-        uint32_t pred;
-        if (a.recombine) {
-            pred = recombine_terms<IS_INT>(a.rc_part + (long)bz * NTERM * M + idx, M, a.w_b + (long)bz * NTERM);
-            a.rc_pred[(long)bz * M + idx] = pred;
-        } else pred = a.rc_pred[(long)bz * M + idx];
+        // row check: prediction A (B e) was taken by the encode pass over A
+        const uint32_t pred = a.rc_pred[(long)bz * M + idx];
         frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], pred, tol);
         a.row_flag[(long)bz * M + idx] = frow ? 1 : 0;
     } else if (idx < M + N) {
@@ -399,21 +564,25 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], pred, tol);
         a.col_flag[(long)bz * N + j] = fcol ? 1 : 0;
     }
-    if (a.recombine && blockIdx.x == 0 && tid == 0) {
-        // scalar a.b from the stripe corner (the paper's own single-number check value)
-        const uint32_t *sp = a.s_part + (long)bz * NTERM * NTERM;
+    if (a.recombine && blockIdx.x == 0) {
+        // scalar a.b (the paper's own single-number check value), straight from the two sums
+        const uint32_t *av = a.a_sum + (long)bz * a.K, *bv = a.b_sum + (long)bz * a.K;
         if (IS_INT) {
             uint32_t v = 0;
-            for (int t = 0; t < NTERM; ++t)
-                for (int u = 0; u < NTERM; ++u)
-                    if (8 * (t + u) < 32) v += sp[t * NTERM + u] << (8 * (t + u));
-            a.s_pred[bz] = v;
+            for (int k = tid; k < a.K; k += 256) v += av[k] * bv[k];
+            v = (uint32_t)wave_sum((int)v);
+            if ((tid & 63) == 0) sred[tid >> 6] = v;
+            __syncthreads();
+            if (tid == 0) a.s_pred[bz] = sred[0] + sred[1] + sred[2] + sred[3];
         } else {
             float v = 0.f;
-            for (int t = NTERM - 1; t >= 0; --t)
-                for (int u = NTERM - 1; u >= 0; --u)
-                    v += __uint_as_float(sp[t * NTERM + u]) * a.w_a[(long)bz * NTERM + t] * a.w_b[(long)bz * NTERM + u];
-            a.s_pred[bz] = __float_as_uint(v);
+            for (int k = tid; k < a.K; k += 256) v += __uint_as_float(av[k]) * __uint_as_float(bv[k]);
+            v = wave_sum(v);
+            if ((tid & 63) == 0) sred[tid >> 6] = __float_as_uint(v);
+            __syncthreads();
+            if (tid == 0)
+                a.s_pred[bz] = __float_as_uint((__uint_as_float(sred[0]) + __uint_as_float(sred[1])) +
+                                               (__uint_as_float(sred[2]) + __uint_as_float(sred[3])));
         }
     }
     const unsigned nr = __syncthreads_count(frow);
@@ -441,14 +610,14 @@ hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, bool use_v
                           hipStream_t st)
 {
     CmpArgs a;
-    a.cc_part = w.cc_part; a.rc_part = w.rc_part; a.s_part = w.s_part;
+    a.cc_part = w.cc_part; a.a_sum = w.a_sum; a.b_sum = w.b_sum;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred; a.s_pred = w.s_pred;
     a.cc_obs = use_vobs ? w.cc_vobs : w.cc_obs;
     a.rc_obs = use_vobs ? w.rc_vobs : w.rc_obs;
-    a.w_a = w.w_a; a.w_b = w.w_b; a.tau = w.tau;
+    a.w_a = w.w_a; a.tau = w.tau;
     a.row_flag = v.row_flag; a.col_flag = v.col_flag; a.counts = v.counts;
     a.ticket = w.cmp_ticket;
-    a.M = s.M; a.N = s.N; a.batch = s.batch;
+    a.M = s.M; a.N = s.N; a.K = s.K; a.batch = s.batch;
     a.recombine = use_vobs ? 0 : 1;
     dim3 grid((unsigned)((s.M + s.N + 255) / 256), 1, (unsigned)s.batch);
     if (dt == DT_I8) hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, a);
@@ -540,9 +709,7 @@ hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Works
     VerArgs a;
     a.C = (const uint8_t *)C; a.ldc = s.ldc; a.sC = s.sC; a.M = s.M; a.N = s.N;
     a.cc_vobs = w.cc_vobs; a.rc_vobs = w.rc_vobs;
-    EncSide plan;
-    plan.rows = s.M; plan.cols = s.N;
-    plan_side(plan, 16 / out_size(dt));
+    EncPlan plan = plan_window(s.M, s.N, 16 / out_size(dt));
     a.cw_log2 = plan.cw_log2; a.nwin = plan.nwin; a.rpb = plan.rpb; a.nrb = plan.nrb;
     dim3 grid((unsigned)(a.nwin * a.nrb), 1, (unsigned)s.batch);
     switch (dt) {

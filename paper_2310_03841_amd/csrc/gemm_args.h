@@ -7,8 +7,8 @@ namespace abft {
 struct GemmArgs {
     const uint8_t *A, *B;
     uint8_t *C;
-    const uint8_t *SA, *SB;                       // [batch][NTERM][Kp] operand elements
-    uint32_t *cc_part, *rc_part, *s_part;         // raw stripe outputs
+    const uint8_t *SA;                            // A-side stripe [batch][NTERM][Kp] operand elements
+    uint32_t *cc_part;                            // raw stripe outputs: terms of (e^T A) B, [batch][NTERM][N]
     uint32_t *cc_obs, *rc_obs;                    // observed sums (atomics)
     int M, N, K, Kp;
     long lda, ldb, ldc, sA, sB, sC;               // elements

@@ -64,14 +64,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     constexpr int OS = T::OS;
     constexpr int WAVE_BYTES = epi_wave_bytes(TN);
     constexpr int CROW = TN * OS + 16;              // staged C row (bytes), padded
-    constexpr int SROW = TN * 4 + 16;               // staged partial-sum row (bytes), padded
+    constexpr int SROW = TN * 4 + 16;               // staged 32-bit row (bytes), padded
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const int M = g.M, N = g.N;
-    const int Mx = PROT ? M + NTERM : M;
-    const int Nx = PROT ? N + NTERM : N;
+    const int Mx = PROT ? M + NTERM : M;             // rows M .. Mx-1 are the A-side stripe
 
     uint8_t *wbuf = smem + wave * WAVE_BYTES;                              // wave-private staging
     acc_t *rs_part = reinterpret_cast<acc_t *>(smem + 4 * WAVE_BYTES);     // [2][BM] by wave column
@@ -80,7 +79,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
                           g.inj_col >= n0 && g.inj_col < n0 + BN;
     const int wr0 = m0 + wm * TM, wc0 = n0 + wn * TN;                      // first row / column of the wave tile
-    const bool wave_inside = (wr0 + TM <= M) && (wc0 + TN <= N) && !inj_here;
+    // staged path: every column of the wave tile is a column of C; rows may run past M
+    const bool staged = (wc0 + TN <= N) && !inj_here;
+
+    auto wave_sync = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
 
     // column partial sums of this lane's row group: colp[ni][i] (PROT only)
     acc_t colp[NI][16];
@@ -93,51 +99,89 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
 
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
-        const int gr = wr0 + mi * 32 + l32;                                // this lane's row
+        const int br = wr0 + mi * 32;                                      // first row of this 32-row group
+        const int gr = br + l32;                                           // this lane's row
         acc_t rowsum = T::zero();
-        if (wave_inside) {
-            // ---- stage 32 rows of converted C in LDS, four columns per write
-            static_for<0, NI>([&](auto ni_c) {
-                constexpr int ni = decltype(ni_c)::value;
-                static_for<0, 4>([&](auto q_c) {
-                    constexpr int q = decltype(q_c)::value;
-                    const acc_t v0 = acc[mi][ni][4 * q], v1 = acc[mi][ni][4 * q + 1],
-                                v2 = acc[mi][ni][4 * q + 2], v3 = acc[mi][ni][4 * q + 3];
-                    if (PROT) {
-                        rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
-                        colp[ni][4 * q] = add_t(colp[ni][4 * q], v0);
-                        colp[ni][4 * q + 1] = add_t(colp[ni][4 * q + 1], v1);
-                        colp[ni][4 * q + 2] = add_t(colp[ni][4 * q + 2], v2);
-                        colp[ni][4 * q + 3] = add_t(colp[ni][4 * q + 3], v3);
-                    }
-                    uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
-                    if constexpr (DT == DT_I8) {
-                        *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
-                    } else {
-                        uint2 w;
-                        w.x = pack2<DT>((float)v0, (float)v1);
-                        w.y = pack2<DT>((float)v2, (float)v3);
-                        *reinterpret_cast<uint2 *>(d) = w;
-                    }
+        if (staged) {
+            const int rows_in = M - br < 0 ? 0 : (M - br > 32 ? 32 : M - br);   // rows of C in the group
+            if (rows_in > 0) {
+                // ---- stage 32 rows of converted C in LDS, four columns per write
+                const bool lane_ok = l32 < rows_in;
+                auto stage = [&](auto masked_c) {
+                constexpr bool MASKED = decltype(masked_c)::value;
+                static_for<0, NI>([&](auto ni_c) {
+                    constexpr int ni = decltype(ni_c)::value;
+                    static_for<0, 4>([&](auto q_c) {
+                        constexpr int q = decltype(q_c)::value;
+                        const acc_t v0 = acc[mi][ni][4 * q], v1 = acc[mi][ni][4 * q + 1],
+                                    v2 = acc[mi][ni][4 * q + 2], v3 = acc[mi][ni][4 * q + 3];
+                        if (PROT) {
+                            rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
+                            if (!MASKED || lane_ok) {                       // rows past M stay out of the column sums
+                                colp[ni][4 * q] = add_t(colp[ni][4 * q], v0);
+                                colp[ni][4 * q + 1] = add_t(colp[ni][4 * q + 1], v1);
+                                colp[ni][4 * q + 2] = add_t(colp[ni][4 * q + 2], v2);
+                                colp[ni][4 * q + 3] = add_t(colp[ni][4 * q + 3], v3);
+                            }
+                        }
+                        uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
+                        if constexpr (DT == DT_I8) {
+                            *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
+                        } else {
+                            uint2 w;
+                            w.x = pack2<DT>((float)v0, (float)v1);
+                            w.y = pack2<DT>((float)v2, (float)v3);
+                            *reinterpret_cast<uint2 *>(d) = w;
+                        }
+                    });
                 });
-            });
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            // ---- read rows back, 16 bytes per lane, and store whole row segments
-            constexpr int LPR = TN * OS / 16;                              // lanes per row
-            constexpr int RPI = 64 / LPR;                                  // rows per instruction
+                };
+                if (rows_in == 32) stage(std::false_type{});
+                else stage(std::true_type{});
+                wave_sync();
+                // ---- read rows back, 16 bytes per lane, and store whole row segments
+                constexpr int LPR = TN * OS / 16;                          // lanes per row
+                constexpr int RPI = 64 / LPR;                              // rows per instruction
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int r = it * RPI + lane / LPR, cch = lane % LPR;
-                const i32x4 v = *reinterpret_cast<const i32x4 *>(wbuf + r * CROW + cch * 16);
-                *reinterpret_cast<i32x4 *>(Cb + ((long)(wr0 + mi * 32 + r) * g.ldc + wc0) * OS + cch * 16) = v;
+                for (int it = 0; it < 32 / RPI; ++it) {
+                    const int r = it * RPI + lane / LPR, cch = lane % LPR;
+                    if (r < rows_in) {
+                        const i32x4 v = *reinterpret_cast<const i32x4 *>(wbuf + r * CROW + cch * 16);
+                        *reinterpret_cast<i32x4 *>(Cb + ((long)(br + r) * g.ldc + wc0) * OS + cch * 16) = v;
+                    }
+                }
+                wave_sync();
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        } else if (wr0 + mi * 32 < Mx && wc0 < Nx) {
-            // ---- edge of the problem, stripe outputs, armed flip: element by element
+            if (PROT && br < Mx && br + 32 > M) {
+                // ---- the group holds rows of the A-side stripe: their accumulators are the
+                // terms of (e^T A) B.  Stage the group as 32-bit words, emit those rows.
+                static_for<0, NI>([&](auto ni_c) {
+                    constexpr int ni = decltype(ni_c)::value;
+                    static_for<0, 4>([&](auto q_c) {
+                        constexpr int q = decltype(q_c)::value;
+                        uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
+                        *reinterpret_cast<i32x4 *>(d) =
+                            i32x4{(int)as_word(acc[mi][ni][4 * q]), (int)as_word(acc[mi][ni][4 * q + 1]),
+                                  (int)as_word(acc[mi][ni][4 * q + 2]), (int)as_word(acc[mi][ni][4 * q + 3])};
+                    });
+                });
+                wave_sync();
+#pragma unroll
+                for (int t = 0; t < NTERM; ++t) {
+                    const int r = M + t - br;
+                    if (r >= 0 && r < 32) {
+                        for (int c0 = 2 * lane; c0 < TN; c0 += 128) {
+                            const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + c0 * 4);
+                            uint32_t *dst = g.cc_part + ((long)bz * NTERM + t) * N + wc0 + c0;
+                            dst[0] = w.x;
+                            dst[1] = w.y;
+                        }
+                    }
+                }
+                wave_sync();
+            }
+        } else if (br < Mx && wc0 < N) {
+            // ---- ragged columns or armed flip: element by element
             static_for<0, NI>([&](auto ni_c) {
                 constexpr int ni = decltype(ni_c)::value;
                 static_for<0, 16>([&](auto i_c) {
@@ -146,20 +190,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                     acc_t v = acc[mi][ni][i];
                     if (inj_here && gr == g.inj_row && gc == g.inj_col)
                         v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
-                    if (gr < M && gc < N) {
-                        T::store_c(Cb, (long)gr * g.ldc + gc, v);
-                        if (PROT) {
-                            rowsum = add_t(rowsum, v);
-                            colp[ni][i] = add_t(colp[ni][i], v);
-                        }
-                    } else if (PROT) {
-                        if (gr >= M && gr < Mx) {
-                            if (gc < N)
-                                g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
-                            else if (gc < Nx)
-                                g.s_part[(long)bz * NTERM * NTERM + (gr - M) * NTERM + (gc - N)] = as_word(v);
-                        } else if (gr < M && gc >= N && gc < Nx) {
-                            g.rc_part[((long)bz * NTERM + (gc - N)) * M + gr] = as_word(v);
+                    if (gc < N) {
+                        if (gr < M) {
+                            T::store_c(Cb, (long)gr * g.ldc + gc, v);
+                            if (PROT) {
+                                rowsum = add_t(rowsum, v);
+                                colp[ni][i] = add_t(colp[ni][i], v);
+                            }
+                        } else if (PROT && gr < Mx) {
+                            g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
                         }
                     }
                 });

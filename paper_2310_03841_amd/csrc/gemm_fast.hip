@@ -57,12 +57,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     const int m0 = tm_idx * BM, n0 = tn_idx * BN;
     const int M = g.M, N = g.N, K = g.K;
     const int Mx = PROT ? M + NTERM : M;
-    const int Nx = PROT ? N + NTERM : N;
 
     const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
     const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
-    const uint8_t *SBb = PROT ? g.SB + (long)bz * NTERM * g.Kp * ES : nullptr;
 
     // ---- per-lane global sources.  Load group p of this wave covers tile rows
     // (4 p + wave) * 8 .. + 8; lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches
@@ -84,11 +82,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     };
     auto b_src = [&](int p) -> const uint8_t * {
         const int r = n0 + (4 * p + wave) * 8 + lrow;
-        const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES
-                                 : ((PROT && r < Nx) ? SBb + (long)(r - N) * g.Kp * ES : Bb);
+        const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES : Bb;
         return s + lchunk * 16;
     };
-    const int a_rows = Mx - m0, b_rows = Nx - n0;      // rows of this tile that matter
+    const int a_rows = Mx - m0, b_rows = N - n0;      // rows of this tile that matter
 
     // The accumulators are never zero-filled: the first MFMA of every block takes a literal
     // zero as its addend.  Every block is always computed, also where the tile hangs over the
@@ -176,9 +173,9 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const int Mx = PROT ? g.M + NTERM : g.M, Nx = PROT ? g.N + NTERM : g.N;
+    const int Mx = PROT ? g.M + NTERM : g.M;
     g.tiles_m = (Mx + BM - 1) / BM;
-    g.tiles_n = (Nx + BN - 1) / BN;
+    g.tiles_n = (g.N + BN - 1) / BN;
     dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
     return hipGetLastError();

@@ -6,13 +6,11 @@
 // with the paper's epilogue fusion of the output checksum (Sec. IV-C memory
 // paragraph; Sec. V "Optimizations" (2)).
 //
-// Logical problem seen by the kernel (PROT = true):
-//     rows    0 .. M-1        of A           | rows M .. M+NTERM-1  = stripe_a (terms of e^T A)
-//     columns 0 .. N-1        of B           | cols N .. N+NTERM-1  = stripe_b (terms of B e)
-// so the output has an extra NTERM rows (-> cc_part: terms of (e^T A) B), an
-// extra NTERM columns (-> rc_part: terms of A (B e)) and a corner (-> s_part:
-// terms of the scalar a.b).  Only the M x N block is written to C and summed
-// into cc_obs / rc_obs.
+// Logical problem seen by the kernel (PROT = true): rows 0 .. M-1 of A, then rows
+// M .. M+NTERM-1 = stripe_a (the terms of e^T A), so the output has NTERM extra
+// rows (-> cc_part: terms of (e^T A) B).  Only the M x N block is written to C and
+// summed into cc_obs / rc_obs.  The row checksum A (B e) is a matrix-vector product
+// and is taken by the encode pass that streams A anyway, not here.
 //
 // Tiling: one workgroup of 4 waves computes a BM x BN tile; each wave owns a
 // (BM/2) x (BN/2) sub-tile as 32x32 MFMA blocks.  K advances in slabs of 128
@@ -53,12 +51,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     const int m0 = tm_idx * BM, n0 = tn_idx * BN;
     const int M = g.M, N = g.N, K = g.K;
     const int Mx = PROT ? M + NTERM : M;
-    const int Nx = PROT ? N + NTERM : N;
 
     const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
     const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
-    const uint8_t *SBb = PROT ? g.SB + (long)bz * NTERM * g.Kp * ES : nullptr;
 
     // ---- per-thread row sources: chunk column c of rows r0 + 32 p
     const int c = tid & 7, r0 = tid >> 3;
@@ -74,10 +70,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         int r = n0 + r0 + 32 * p;
-        btail[p] = r >= N;
-        const uint8_t *stripe = (PROT && r >= N && r < Nx) ? SBb + (long)(r - N) * g.Kp * ES : nullptr;
-        if (TRANSB) bsrc[p] = r < N ? Bb + (long)r * g.ldb * ES : stripe;
-        else        bsrc[p] = stripe;
+        btail[p] = r >= N;                           // rows of the B tile past N are zero-filled
+        bsrc[p] = (TRANSB && r < N) ? Bb + (long)r * g.ldb * ES : nullptr;
     }
     const bool tile_has_btail = (n0 + BN > N);
 
@@ -93,7 +87,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) mact[mi] = (m0 + wm * TM + mi * 32) < Mx;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) nact[ni] = (n0 + wn * TN + ni * 32) < Nx;
+    for (int ni = 0; ni < NI; ++ni) nact[ni] = (n0 + wn * TN + ni * 32) < N;
 
     i32x4 areg[PA], breg[PB];
     const int nslab = (K + KE - 1) / KE;
@@ -235,9 +229,9 @@ static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
 template <int DT, int BM, int BN>
 static hipError_t launch_cfg(bool protect, bool transB, GemmArgs &g, int batch, hipStream_t st)
 {
-    const int Mx = protect ? g.M + NTERM : g.M, Nx = protect ? g.N + NTERM : g.N;
+    const int Mx = protect ? g.M + NTERM : g.M;
     g.tiles_m = (Mx + BM - 1) / BM;
-    g.tiles_n = (Nx + BN - 1) / BN;
+    g.tiles_n = (g.N + BN - 1) / BN;
     if (protect) return transB ? launch_one<DT, BM, BN, true, true>(g, batch, st)
                                : launch_one<DT, BM, BN, true, false>(g, batch, st);
     return transB ? launch_one<DT, BM, BN, false, true>(g, batch, st)
@@ -262,10 +256,7 @@ hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void 
     g.B = (const uint8_t *)B;
     g.C = (uint8_t *)C;
     g.SA = w.stripe_a;
-    g.SB = w.stripe_b;
     g.cc_part = w.cc_part;
-    g.rc_part = w.rc_part;
-    g.s_part = w.s_part;
     g.cc_obs = w.cc_obs;
     g.rc_obs = w.rc_obs;
     g.M = s.M; g.N = s.N; g.K = s.K; g.Kp = s.Kp;
