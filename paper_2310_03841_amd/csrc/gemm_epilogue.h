@@ -41,6 +41,22 @@ __host__ __device__ constexpr int epi_total_bytes(int BM, int BN)
     return 4 * epi_wave_bytes(BN / 2) + (2 * BM + 2 * BN) * 4;
 }
 
+// Read one accumulator element where it lives (an AGPR) at the point of use.  Without this the
+// register allocator moves the whole accumulator set into VGPRs at the top of the epilogue and
+// spills part of it.
+__device__ __forceinline__ float acc_read(float v)
+{
+    float r;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+    return r;
+}
+__device__ __forceinline__ int acc_read(int v)
+{
+    int r;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(v));
+    return r;
+}
+
 // pack converted outputs
 template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b);
 template <> __device__ __forceinline__ uint32_t pack2<DT_BF16>(float a, float b)
@@ -88,15 +104,6 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    // column partial sums of this lane's row group: colp[ni][i] (PROT only)
-    acc_t colp[NI][16];
-    if (PROT) {
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) colp[ni][i] = T::zero();
-    }
-
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
         const int br = wr0 + mi * 32;                                      // first row of this 32-row group
@@ -106,24 +113,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
             const int rows_in = M - br < 0 ? 0 : (M - br > 32 ? 32 : M - br);   // rows of C in the group
             if (rows_in > 0) {
                 // ---- stage 32 rows of converted C in LDS, four columns per write
-                const bool lane_ok = l32 < rows_in;
-                auto stage = [&](auto masked_c) {
-                constexpr bool MASKED = decltype(masked_c)::value;
                 static_for<0, NI>([&](auto ni_c) {
                     constexpr int ni = decltype(ni_c)::value;
                     static_for<0, 4>([&](auto q_c) {
                         constexpr int q = decltype(q_c)::value;
-                        const acc_t v0 = acc[mi][ni][4 * q], v1 = acc[mi][ni][4 * q + 1],
-                                    v2 = acc[mi][ni][4 * q + 2], v3 = acc[mi][ni][4 * q + 3];
-                        if (PROT) {
-                            rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
-                            if (!MASKED || lane_ok) {                       // rows past M stay out of the column sums
-                                colp[ni][4 * q] = add_t(colp[ni][4 * q], v0);
-                                colp[ni][4 * q + 1] = add_t(colp[ni][4 * q + 1], v1);
-                                colp[ni][4 * q + 2] = add_t(colp[ni][4 * q + 2], v2);
-                                colp[ni][4 * q + 3] = add_t(colp[ni][4 * q + 3], v3);
-                            }
-                        }
+                        const acc_t v0 = acc_read(acc[mi][ni][4 * q]), v1 = acc_read(acc[mi][ni][4 * q + 1]),
+                                    v2 = acc_read(acc[mi][ni][4 * q + 2]), v3 = acc_read(acc[mi][ni][4 * q + 3]);
+                        if (PROT) rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
                         uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
                         if constexpr (DT == DT_I8) {
                             *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
@@ -134,10 +130,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                             *reinterpret_cast<uint2 *>(d) = w;
                         }
                     });
+                    // keep the scheduler from hoisting every accumulator read to the top: that
+                    // would need hundreds of live registers and spill
+                    __builtin_amdgcn_sched_barrier(0);
                 });
-                };
-                if (rows_in == 32) stage(std::false_type{});
-                else stage(std::true_type{});
                 wave_sync();
                 // ---- read rows back, 16 bytes per lane, and store whole row segments
                 constexpr int LPR = TN * OS / 16;                          // lanes per row
@@ -161,8 +157,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                         constexpr int q = decltype(q_c)::value;
                         uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
                         *reinterpret_cast<i32x4 *>(d) =
-                            i32x4{(int)as_word(acc[mi][ni][4 * q]), (int)as_word(acc[mi][ni][4 * q + 1]),
-                                  (int)as_word(acc[mi][ni][4 * q + 2]), (int)as_word(acc[mi][ni][4 * q + 3])};
+                            i32x4{(int)as_word(acc_read(acc[mi][ni][4 * q])), (int)as_word(acc_read(acc[mi][ni][4 * q + 1])),
+                                  (int)as_word(acc_read(acc[mi][ni][4 * q + 2])), (int)as_word(acc_read(acc[mi][ni][4 * q + 3]))};
                     });
                 });
                 wave_sync();
@@ -187,16 +183,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 static_for<0, 16>([&](auto i_c) {
                     constexpr int i = decltype(i_c)::value;
                     const int gc = wc0 + ni * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-                    acc_t v = acc[mi][ni][i];
+                    acc_t v = acc_read(acc[mi][ni][i]);
                     if (inj_here && gr == g.inj_row && gc == g.inj_col)
                         v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
                     if (gc < N) {
                         if (gr < M) {
                             T::store_c(Cb, (long)gr * g.ldc + gc, v);
-                            if (PROT) {
-                                rowsum = add_t(rowsum, v);
-                                colp[ni][i] = add_t(colp[ni][i], v);
-                            }
+                            if (PROT) rowsum = add_t(rowsum, v);
                         } else if (PROT && gr < Mx) {
                             g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
                         }
@@ -212,17 +205,44 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     });
 
     if (PROT) {
-        // ---- column sums: transpose the per-lane partials through LDS.
-        // staged as S[l32][column of the wave tile] (fp32 / int32), then every lane adds up
-        // the 32 rows of two columns.
+        // ---- column sums: a second walk over the accumulators, one block column at a time (16
+        // live partial sums instead of 16 * NI), each lane adding up its rows of the MI row
+        // groups; the per-lane partials are transposed through LDS: staged as
+        // S[l32][column of the wave tile] (fp32 / int32), then every lane adds up the 32 rows
+        // of two columns.  Rows past M and the column where a flip is armed are handled here
+        // too, so the sums cover exactly what was stored.
         static_for<0, NI>([&](auto ni_c) {
             constexpr int ni = decltype(ni_c)::value;
+            acc_t cp[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cp[i] = T::zero();
+            static_for<0, MI>([&](auto mi_c) {
+                constexpr int mi = decltype(mi_c)::value;
+                const int br = wr0 + mi * 32;
+                if (br + 32 <= M && !inj_here) {                 // whole group inside, no flip: plain adds
+                    static_for<0, 16>([&](auto i_c) {
+                        constexpr int i = decltype(i_c)::value;
+                        cp[i] = add_t(cp[i], acc_read(acc[mi][ni][i]));
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                } else if (br < M) {
+                    const int gr = br + l32;
+                    static_for<0, 16>([&](auto i_c) {
+                        constexpr int i = decltype(i_c)::value;
+                        const int gc = wc0 + ni * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
+                        acc_t v = acc_read(acc[mi][ni][i]);
+                        if (inj_here && gr == g.inj_row && gc == g.inj_col)
+                            v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
+                        if (gr < M) cp[i] = add_t(cp[i], v);
+                    });
+                }
+            });
             static_for<0, 4>([&](auto q_c) {
                 constexpr int q = decltype(q_c)::value;
                 uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
                 *reinterpret_cast<i32x4 *>(d) =
-                    i32x4{(int)as_word(colp[ni][4 * q]), (int)as_word(colp[ni][4 * q + 1]),
-                          (int)as_word(colp[ni][4 * q + 2]), (int)as_word(colp[ni][4 * q + 3])};
+                    i32x4{(int)as_word(cp[4 * q]), (int)as_word(cp[4 * q + 1]),
+                          (int)as_word(cp[4 * q + 2]), (int)as_word(cp[4 * q + 3])};
             });
         });
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
