@@ -58,14 +58,21 @@ __device__ __forceinline__ int acc_read(int v)
 }
 
 // pack converted outputs
+// Two fp32 values -> two storage-type values in one word, round to nearest even (the packed
+// conversion instructions of gfx950).
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 template <int DT> __device__ __forceinline__ uint32_t pack2(float a, float b);
 template <> __device__ __forceinline__ uint32_t pack2<DT_BF16>(float a, float b)
 {
-    return f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 template <> __device__ __forceinline__ uint32_t pack2<DT_F16>(float a, float b)
 {
-    return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
 }
 
 template <int DT, int BM, int BN, bool PROT>

@@ -74,13 +74,13 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     const uint8_t *a_lane = Ab + (long)(m0 + wave * 8 + lrow) * g.lda * ES + lchunk * 16;
     const uint8_t *b_lane = Bb + (long)(n0 + wave * 8 + lrow) * g.ldb * ES + lchunk * 16;
     const long a_pstride = 32 * g.lda * ES, b_pstride = 32 * g.ldb * ES;
-    auto a_src = [&](int p) -> const uint8_t * {
+    auto a_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
         const int r = m0 + (4 * p + wave) * 8 + lrow;
         const uint8_t *s = r < M ? Ab + (long)r * g.lda * ES
                                  : ((PROT && r < Mx) ? SAb + (long)(r - M) * g.Kp * ES : Ab);
         return s + lchunk * 16;
     };
-    auto b_src = [&](int p) -> const uint8_t * {
+    auto b_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
         const int r = n0 + (4 * p + wave) * 8 + lrow;
         const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES : Bb;
         return s + lchunk * 16;
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     // One loop serves interior and edge tiles (two instances of the MFMA loop that meet in
     // front of the epilogue would push the accumulators through VGPR copies); only the source
     // address of a load depends, wave-uniformly, on where the tile lies.
-    auto issue_loads = [&](int s, int buf) {
+    auto issue_loads = [&](int s, int buf) __attribute__((always_inline)) {
         const long koff = (long)s * SLAB_BYTES;
         uint8_t *sA = smem + buf * BUF;
         uint8_t *sB = sA + BM * SLAB_BYTES;
@@ -123,38 +123,59 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
             }
         }
     };
-    auto compute = [&](auto first_c, int buf) {
-        constexpr bool FIRST = decltype(first_c)::value;
+    // ---- main loop, software-pipelined by hand.  A slab is four MFMA steps of 32 bytes of K.
+    // The fragments of step t+1 are read from LDS while the MFMAs of step t run (two register
+    // sets); the reads are issued in the first half of a step so that the second half covers
+    // their latency.  The barrier sits between steps 2 and 3: by then every wave has read its
+    // step-3 fragments, so nobody reads this slab's buffer any more and the loads of slab s+2
+    // can be issued into it at once, while step 3 runs and prefetches step 0 of slab s+1.
+    i32x4 fa[2][MI], fb[2][NI];
+    auto ldfr = [&](int buf, int s4, int set) __attribute__((always_inline)) {
         const uint8_t *sA = smem + buf * BUF;
         const uint8_t *sB = sA + BM * SLAB_BYTES;
+        const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
 #pragma unroll
-        for (int s4 = 0; s4 < 4; ++s4) {
-            const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
-            i32x4 af[MI], bf[NI];
+        for (int mi = 0; mi < MI; ++mi)
+            fa[set][mi] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + mi * 32 + l32) * SLAB_BYTES + sw);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                af[mi] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + mi * 32 + l32) * SLAB_BYTES + sw);
+        for (int ni = 0; ni < NI; ++ni)
+            fb[set][ni] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + ni * 32 + l32) * SLAB_BYTES + sw);
+    };
+    auto mfmas = [&](auto first_c, int set) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_c)::value;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
-                bf[ni] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + ni * 32 + l32) * SLAB_BYTES + sw);
+                acc[mi][ni] = T::mfma(fb[set][ni], fa[set][mi], FIRST ? zerov : acc[mi][ni]);
+    };
+    auto interleave = [&]() __attribute__((always_inline)) {
+        // scheduling directive: (MFMA, LDS read) x (MI + NI), then the remaining MFMAs
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = T::mfma(bf[ni], af[mi], (FIRST && s4 == 0) ? zerov : acc[mi][ni]);
+        for (int j = 0; j < MI + NI; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
     };
     {
         const int nslab = K / KE;
         issue_loads(0, 0);
-        __syncthreads();
         if (nslab > 1) issue_loads(1, 1);
-        compute(std::true_type{}, 0);
-        for (int s = 1; s < nslab; ++s) {
-            __syncthreads();             // slab s has landed for every wave; buffer (s+1)&1 is free
-            if (s + 1 < nslab) issue_loads(s + 1, (s + 1) & 1);
-            compute(std::false_type{}, s & 1);
-        }
+        __syncthreads();
+        ldfr(0, 0, 0);
+        auto slab = [&](auto first_c, int s) __attribute__((always_inline)) {
+            const int buf = s & 1;
+            ldfr(buf, 1, 1); mfmas(first_c, 0); interleave();
+            ldfr(buf, 2, 0); mfmas(std::false_type{}, 1); interleave();
+            ldfr(buf, 3, 1); mfmas(std::false_type{}, 0); interleave();
+            __syncthreads();
+            if (s + 2 < nslab) issue_loads(s + 2, buf);
+            if (s + 1 < nslab) ldfr(buf ^ 1, 0, 0);
+            mfmas(std::false_type{}, 1); interleave();
+        };
+        slab(std::true_type{}, 0);
+        for (int s = 1; s < nslab; ++s) slab(std::false_type{}, s);
     }
     __syncthreads();
     gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
