@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per GEMM-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # same counters on a plain copy kernel (see profiles/); None until measured for this kernel version.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = int((61531.4 / 0.5 + 76887.0) * 1024)   # profiles/gemm_fast_bf16_fc1_b64_hbm_traffic.txt
 
 
 def log(*a):
@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target seconds of oracle work")
     ap.add_argument("--flips", type=int, default=64, help="stored-C flips for the correction timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -92,6 +95,15 @@ def main():
         assert n == steps
         return ms
 
+    if args.calibrate_copy:
+        src = torch.ones(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src * 1.0 if False else src)      # plain copy kernel: reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- the timed region of the contract: W warm-up steps, then exactly K steps
     ms_prot = timed(ab.ABFT_DETECT, args.steps, args.warmup)
     cnt = run.cnt()
@@ -126,15 +138,33 @@ def main():
     ms_verify = t_verify(50)
     c_bytes = M * N * 2
     flips = gen.gen_flips(args.flips, M, N, dtype, gen.seed_for(1, 9))
-    detected = localised = restored = 0
+    tau_dev = float(run.ws(ab.ABFT_WS_TAU)[0, 0])
     C_clean = run.dC.clone()
+    C_host = run.C()[0]
+
+    def bf16_val(bits):
+        return float((np.array([bits], dtype=np.uint32) << 16).view(np.float32)[0])
+
+    # strata of the campaign: S0 all flips; S1 |delta| > tau or non-finite (what the check is
+    # specified to catch); S2 |delta| > 1e-2 * max|C| (flip breaks the 1e-2 acceptance band)
+    cmax = float(np.max(np.abs((C_host.astype(np.uint32) << 16).view(np.float32))))
+    strata = {"S0": [0, 0], "S1": [0, 0], "S2": [0, 0]}          # [injected, detected]
+    detected = localised = restored = 0
     t_corr = 0.0
     for (_, i, j, bit) in flips:
         i, j, bit = int(i), int(j), int(bit)
+        old = bf16_val(int(C_host[i, j]))
+        new = bf16_val(int(C_host[i, j]) ^ (1 << bit))
+        delta = abs(new - old) if np.isfinite(new) else float("inf")
         run.inject(0, i, j, bit)
         run.verify()
         rf, cf = run.flags()
-        if rf.any() or cf.any():
+        hit = bool(rf.any() or cf.any())
+        for name, cond in (("S0", True), ("S1", delta > tau_dev), ("S2", delta > 1e-2 * cmax)):
+            if cond:
+                strata[name][0] += 1
+                strata[name][1] += int(hit)
+        if hit:
             detected += 1
             if rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]:
                 localised += 1
@@ -167,7 +197,7 @@ def main():
                    "tile": list(ab.abft_tile_shape(run.code, run.shape))},
         "roofline": {"bound": "mfma", "achieved": flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[dtype],
                      "unit": "TFLOP/s", "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
-                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel": "gemm_kernel<bf16, protected>",
+                     "traffic": MEASURED_TRAFFIC_BYTES, "kernel": "gemm_fast_kernel<bf16, 256, 256, protected>",
                      "kernel_ms": gemm_ms},
         "protection": {
             "unprotected_ms": ms_off, "unprotected_tflops": flops / (ms_off * 1e-3) / 1e12,
@@ -182,8 +212,11 @@ def main():
             "flips": {"injected": len(flips), "detected": detected, "localised": localised,
                       "restored": restored, "us_per_correction": us_correct,
                       "correction_pct_of_step": 100.0 * us_correct * 1e-3 / ms_prot,
-                      "note": "stored-C flips, exponent/mantissa 50/50; flips with |delta| below tau are "
-                              "undetectable by construction"},
+                      "tau": tau_dev, "max_abs_C": cmax,
+                      "strata_injected_detected": strata,
+                      "note": "stored-C single-bit flips, exponent/mantissa 50/50, each applied alone; "
+                              "S1 = |delta| > tau or non-finite (the gating stratum), S2 = |delta| > "
+                              "1e-2 max|C|; flips with |delta| <= tau are undetectable by construction"},
         },
     }
 
@@ -194,7 +227,6 @@ def main():
         orc.protected_gemm(A[0][:rows], B[0], dtype, True)
         dt = time.perf_counter() - t0
         rows = int(min(M, max(rows, rows * args.cpu_seconds / max(dt, 1e-3))))
-        rows = min(rows, 4096)
         t0 = time.perf_counter()
         P = orc.protected_gemm(A[0][:rows], B[0], dtype, True)
         orc.check(P, P.C_stored)
