@@ -52,16 +52,20 @@ __device__ __forceinline__ void split_digits(int v, int8_t d[NTERM])
     }
 }
 
-// Sum the accumulator copies of column k, leave them clean for the next call.
+// Sum the accumulator copies of column k, leave them clean for the next call.  The reads go
+// through the coherence point (device-scope atomic loads, all in flight at once); the zeros are
+// ordinary stores, visible to the next kernel.
 template <typename acc_t>
 __device__ __forceinline__ acc_t take_copies(uint32_t *acc, long stride, int k)
 {
     uint32_t part[ENC_COPIES];
 #pragma unroll
-    for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomicExch(acc + c * stride + k, 0u);
+    for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomic_read_word(acc + c * stride + k);
     acc_t t = from_word<acc_t>(part[0]);
 #pragma unroll
     for (int c = 1; c < ENC_COPIES; ++c) t = add_t(t, from_word<acc_t>(part[c]));
+#pragma unroll
+    for (int c = 0; c < ENC_COPIES; ++c) acc[c * stride + k] = 0u;
     return t;
 }
 

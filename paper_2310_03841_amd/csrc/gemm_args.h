@@ -13,6 +13,7 @@ struct GemmArgs {
     int M, N, K, Kp;
     long lda, ldb, ldc, sA, sB, sC;               // elements
     int tiles_m, tiles_n;
+    int n_big, tiles_m_big, tiles_m_small;        // fast path: 256-row tiles first, then 128-row tiles
     int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
 };
 

@@ -145,14 +145,18 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 // ---- read rows back, 16 bytes per lane, and store whole row segments
                 constexpr int LPR = TN * OS / 16;                          // lanes per row
                 constexpr int RPI = 64 / LPR;                              // rows per instruction
+                // (all LDS reads first, then the stores: one LDS latency instead of one per row)
+                constexpr int NIT = 32 / RPI;
+                const int r0 = lane / LPR, cch = lane % LPR;
+                i32x4 rowv[NIT];
 #pragma unroll
-                for (int it = 0; it < 32 / RPI; ++it) {
-                    const int r = it * RPI + lane / LPR, cch = lane % LPR;
-                    if (r < rows_in) {
-                        const i32x4 v = *reinterpret_cast<const i32x4 *>(wbuf + r * CROW + cch * 16);
-                        *reinterpret_cast<i32x4 *>(Cb + ((long)(br + r) * g.ldc + wc0) * OS + cch * 16) = v;
-                    }
-                }
+                for (int it = 0; it < NIT; ++it)
+                    rowv[it] = *reinterpret_cast<const i32x4 *>(wbuf + (it * RPI + r0) * CROW + cch * 16);
+                uint8_t *crow = Cb + ((long)(br + r0) * g.ldc + wc0) * OS + cch * 16;
+                const long cstep = (long)RPI * g.ldc * OS;
+#pragma unroll
+                for (int it = 0; it < NIT; ++it)
+                    if (it * RPI + r0 < rows_in) *reinterpret_cast<i32x4 *>(crow + it * cstep) = rowv[it];
                 wave_sync();
             }
             if (PROT && br < Mx && br + 32 > M) {

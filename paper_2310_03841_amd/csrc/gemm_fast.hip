@@ -5,7 +5,7 @@
 //     wave instruction fills 8 LDS rows of 128 bytes; the XOR swizzle of the LDS layout is
 //     applied by choosing which global 16-byte chunk each lane fetches.
 //   * 256 x 256 tiles, 4 waves of 128 x 128 (sixteen 32x32 MFMA blocks per wave), two LDS
-//     buffers of 64 KB, one barrier per slab.
+//     buffers of 64 KB, one barrier per slab; 128 x 256 tiles fill the last, partial round.
 //   * MFMAs take the B fragment first, so a lane owns a row of C (see gemm_epilogue.h).
 //   * workgroup -> tile mapping keeps the workgroups that share an XCD (and its L2) on a
 //     compact group of tiles.
@@ -20,8 +20,9 @@ namespace abft {
 typedef const __attribute__((address_space(1))) void *gas_ptr;
 typedef __attribute__((address_space(3))) void *las_ptr;
 
+// One BM x BN tile with origin (m0, n0) of batch item bz.
 template <int DT, int BM, int BN, bool PROT>
-__global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
+__device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int m0, int n0, int bz)
 {
     using T = Traits<DT>;
     typedef typename T::accv_t accv_t;
@@ -31,30 +32,11 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     constexpr int MI = TM / 32, NI = TN / 32;
     constexpr int GA = BM / 32, GB = BN / 32;     // 8-row load groups per wave per slab
     constexpr int BUF = (BM + BN) * SLAB_BYTES;
-    constexpr int GROUP_M = 8;
-
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int bz = blockIdx.z;
-
-    // ---- workgroup -> tile: consecutive ids of one XCD walk GROUP_M tile rows, then the next column
-    int tm_idx, tn_idx;
-    {
-        const int nb = gridDim.x, bid = blockIdx.x;
-        const int q = nb >> 3, r = nb & 7, xcd = bid & 7;
-        const int L = xcd * q + (xcd < r ? xcd : r) + (bid >> 3);
-        const int per_group = GROUP_M * g.tiles_n;
-        const int grp = L / per_group, in_grp = L % per_group;
-        const int first_m = grp * GROUP_M;
-        const int gsz = (g.tiles_m - first_m) < GROUP_M ? (g.tiles_m - first_m) : GROUP_M;
-        tm_idx = first_m + in_grp % gsz;
-        tn_idx = in_grp / gsz;
-    }
-    const int m0 = tm_idx * BM, n0 = tn_idx * BN;
     const int M = g.M, N = g.N, K = g.K;
     const int Mx = PROT ? M + NTERM : M;
 
@@ -181,12 +163,49 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
 }
 
+// Workgroup -> tile inside a region of tiles_m x tiles_n tiles: consecutive ids of one XCD
+// (workgroups are dealt to the 8 XCDs round-robin) walk GROUP_M tile rows, then the next column,
+// so the workgroups that share an L2 work on a compact group of tiles.
+__device__ __forceinline__ void map_tile(int bid, int nb, int tiles_m, int tiles_n, int *tm, int *tn)
+{
+    constexpr int GROUP_M = 8;
+    const int q = nb >> 3, r = nb & 7, xcd = bid & 7;
+    const int L = xcd * q + (xcd < r ? xcd : r) + (bid >> 3);
+    const int per_group = GROUP_M * tiles_n;
+    const int grp = L / per_group, in_grp = L % per_group;
+    const int first_m = grp * GROUP_M;
+    const int gsz = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    *tm = first_m + in_grp % gsz;
+    *tn = in_grp / gsz;
+}
+
+// The grid mixes two tile shapes against wave quantisation: 256 x 256 tiles cover the first
+// big_rows rows in whole rounds of the machine, 128 x 256 tiles cover the rest, are dispatched
+// after them and take half as long, so the last round is short.  (600 big tiles on 256 CUs
+// would be three rounds for 2.34 rounds of work.)
+template <int DT, bool PROT>
+__global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int bid = blockIdx.x, bz = blockIdx.z;
+    int tm, tn;
+    if (bid < g.n_big) {
+        map_tile(bid, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
+        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz);
+    } else {
+        map_tile(bid - g.n_big, (int)gridDim.x - g.n_big, g.tiles_m_small, g.tiles_n, &tm, &tn);
+        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
-template <int DT, int BM, int BN, bool PROT>
+static int g_num_cu = 0;
+
+template <int DT, bool PROT>
 static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
 {
-    constexpr int smem = 2 * (BM + BN) * SLAB_BYTES;
-    auto kern = gemm_fast_kernel<DT, BM, BN, PROT>;
+    constexpr int smem = 2 * (256 + 256) * SLAB_BYTES;
+    auto kern = gemm_fast_kernel<DT, PROT>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -194,10 +213,30 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
+    if (g_num_cu == 0) {
+        int dev = 0, n = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        g_num_cu = n > 0 ? n : 256;
+    }
     const int Mx = PROT ? g.M + NTERM : g.M;
-    g.tiles_m = (Mx + BM - 1) / BM;
-    g.tiles_n = (g.N + BN - 1) / BN;
-    dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
+    g.tiles_n = (g.N + 255) / 256;
+    const int rows_all_big = (Mx + 255) / 256;
+    const long total_big = (long)rows_all_big * g.tiles_n * batch;
+    int big_rows = rows_all_big;
+    if (total_big % g_num_cu != 0) {
+        // whole rounds of big tiles, the remainder of the rows in half-height tiles
+        const long rounds = total_big / g_num_cu;
+        big_rows = (int)((rounds * g_num_cu) / ((long)g.tiles_n * batch));
+        if (big_rows > rows_all_big) big_rows = rows_all_big;
+    }
+    g.tiles_m_big = big_rows;
+    g.n_big = big_rows * g.tiles_n;
+    const int rest = Mx - big_rows * 256;
+    g.tiles_m_small = rest > 0 ? (rest + 127) / 128 : 0;
+    g.tiles_m = g.tiles_m_big + g.tiles_m_small;
+    dim3 grid((unsigned)(g.n_big + g.tiles_m_small * g.tiles_n), 1, (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
     return hipGetLastError();
 }
@@ -215,14 +254,11 @@ hipError_t launch_gemm_fast(int dt, bool protect, GemmArgs &g, int batch, hipStr
 {
     switch (dt) {
     case DT_I8:
-        return protect ? launch_fast_one<DT_I8, 256, 256, true>(g, batch, st)
-                       : launch_fast_one<DT_I8, 256, 256, false>(g, batch, st);
+        return protect ? launch_fast_one<DT_I8, true>(g, batch, st) : launch_fast_one<DT_I8, false>(g, batch, st);
     case DT_BF16:
-        return protect ? launch_fast_one<DT_BF16, 256, 256, true>(g, batch, st)
-                       : launch_fast_one<DT_BF16, 256, 256, false>(g, batch, st);
+        return protect ? launch_fast_one<DT_BF16, true>(g, batch, st) : launch_fast_one<DT_BF16, false>(g, batch, st);
     case DT_F16:
-        return protect ? launch_fast_one<DT_F16, 256, 256, true>(g, batch, st)
-                       : launch_fast_one<DT_F16, 256, 256, false>(g, batch, st);
+        return protect ? launch_fast_one<DT_F16, true>(g, batch, st) : launch_fast_one<DT_F16, false>(g, batch, st);
     }
     return hipErrorInvalidValue;
 }
