@@ -81,7 +81,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_rows, R * 4},
         {(void **)&c->pool_cols, (NTERM + 1) * Cn * 4},
-        {(void **)&c->pool_obs, (R + Cn) * 4},
+        {(void **)&c->pool_obs, (R + Cn + (R + Cn) / 128 + 4 * Bt + 16) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
         {(void **)&c->small, 8 * 4},
@@ -175,8 +175,17 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->rc_pred = c->pool_rows;
     w->cc_part = c->pool_cols;
     w->cc_pred = c->pool_cols + NTERM * Cn;
+    // one region that must be zero before the GEMM: cc_obs | rc_obs | tile tickets | launch ticket
     w->cc_obs = c->pool_obs;
     w->rc_obs = c->pool_obs + bN;
+    {
+        const size_t trows = (size_t)s.batch * ((size_t)(s.M + NTERM + 127) / 128);   // bound for any tile height
+        const size_t tcols = (size_t)s.batch * ((size_t)(s.N + 127) / 128);
+        w->row_ticket = w->rc_obs + bM;
+        w->col_ticket = w->row_ticket + trows;
+        w->fin = w->col_ticket + tcols;
+        w->zero_words = bN + bM + trows + tcols + 4;
+    }
     w->cc_vobs = c->pool_vobs;
     w->rc_vobs = c->pool_vobs + bN;
     w->fix_tiles = c->fix_tiles;
@@ -243,7 +252,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         ctx->arm.batch = -1;
         hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
         if (ev) { HIP_TRY(hipEventRecord(ev[0], st)); HIP_TRY(hipEventRecord(ev[1], st)); }
-        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, st));
+        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, nullptr, st));
         if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
         return ABFT_OK;
     }
@@ -258,12 +267,10 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, st));
-    HIP_TRY(launch_encode_a(dtype, A, sh, w, v.tau_override, w.cc_obs,
-                            (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    HIP_TRY(launch_encode_a(dtype, A, sh, w, v.tau_override, w.cc_obs, w.zero_words, st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
+    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, &v, st));      // compare + flags fused in its tail
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
-    HIP_TRY(launch_compare(dtype, sh, w, false, v, st));
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
     ctx->b_valid = true;
     ctx->b_dt = dtype;
@@ -292,7 +299,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     carve(ctx, dtype, sh, &w);
     HIP_TRY(launch_zero(w.cc_vobs, (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
-    HIP_TRY(launch_compare(dtype, sh, w, true, v, st));
+    HIP_TRY(launch_compare(dtype, sh, w, v, st));
     return ABFT_OK;
 }
 

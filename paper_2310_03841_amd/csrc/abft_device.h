@@ -131,6 +131,12 @@ __device__ __forceinline__ uint32_t atomic_read_word(uint32_t *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Store that other workgroups of the same launch will read: goes to the coherence point.
+__device__ __forceinline__ void publish_word(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---------------------------------------------------------------- wave-level reductions (DPP)
 template <int CTRL> __device__ __forceinline__ int dpp_mov(int v)
 {

@@ -46,6 +46,8 @@ struct Workspace {
     uint32_t *s_pred;               // [batch]
     // observed
     uint32_t *cc_obs, *rc_obs;      // epilogue sums (atomics)
+    uint32_t *row_ticket, *col_ticket, *fin;   // fused compare: per tile row / tile column / launch
+    size_t zero_words;              // words from cc_obs on that must be zero before the GEMM
     uint32_t *cc_vobs, *rc_vobs;    // re-summed from stored C
     // correction
     int32_t  *fix_tiles;            // [MAX_FIX_TILES][3] (batch, tile row, tile col)
@@ -73,10 +75,10 @@ hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspac
 hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspace &w, float tau_override,
                            uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
 int encode_a_max_k(int dt);
+// v != nullptr: flags and counts are produced by the last-arriving workgroups of the GEMM itself
 hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
-                       const Workspace &w, const InjectArm &arm, hipStream_t st);
-hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, bool use_vobs, const Verdict &v,
-                          hipStream_t st);
+                       const Workspace &w, const InjectArm &arm, const Verdict *v, hipStream_t st);
+hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st);
 hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st);
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
                           const Workspace &w, const Verdict &v, hipStream_t st);

@@ -204,6 +204,7 @@ struct EncAArgs {
     uint32_t *max_acc;
     float *maxabs, *tau;
     uint32_t *ticket;
+    uint32_t *s_pred;     // [batch] scalar a . b (the paper's own single-number check value)
     float tau_override;
     uint32_t *zero_ptr;
     size_t zero_words;
@@ -331,6 +332,21 @@ __global__ __launch_bounds__(256) void encode_a_kernel(EncAArgs e)
         const uint32_t w = as_word(take_copies<acc_t>(e.a_acc + (long)bz * K, e.acc_stride, k));
         sum[k] = w;
         if (!T::IS_INT) amax = fmaxf(amax, fabsf(__uint_as_float(w)));
+    }
+    {
+        // scalar a . b, straight from the two sums (b is still staged in LDS)
+        acc_t v = T::zero();
+        for (int k = tid; k < K; k += 256) v = add_t(v, mul_t(from_word<acc_t>(sum[k]), bl[k]));
+        v = wave_sum(v);
+        __syncthreads();
+        if ((tid & 63) == 0) fred[tid >> 6] = __uint_as_float(as_word(v));
+        __syncthreads();
+        if (tid == 0) {
+            acc_t t = add_t(add_t(from_word<acc_t>(__float_as_uint(fred[0])), from_word<acc_t>(__float_as_uint(fred[1]))),
+                            add_t(from_word<acc_t>(__float_as_uint(fred[2])), from_word<acc_t>(__float_as_uint(fred[3]))));
+            e.s_pred[bz] = as_word(t);
+        }
+        __syncthreads();
     }
     float scale = 1.f, inv = 1.f;
     if (DT == DT_F16) {
@@ -491,6 +507,7 @@ hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspac
     e.rc_pred = w.rc_pred; e.stripe = w.stripe_a; e.w_a = w.w_a;
     e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.tau = w.tau; e.ticket = w.enc_ticket;
     e.tau_override = tau_override; e.zero_ptr = zero_ptr; e.zero_words = zero_words;
+    e.s_pred = w.s_pred;
     switch (dt) {
     case DT_I8:   return launch_encode_a_t<DT_I8>(e, s.batch, st);
     case DT_BF16: return launch_encode_a_t<DT_BF16>(e, s.batch, st);
@@ -500,33 +517,18 @@ hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspac
 }
 
 // ===================================================================== compare
+// Flags from observed sums against the predictions the last abft_gemm left in the context
+// (Sec. III-B.1 item (2): equality for fixed point, tolerance for floating point).  Used by
+// abft_verify; abft_gemm does the same comparison in the tail of the GEMM kernel.
 struct CmpArgs {
-    const uint32_t *cc_part, *a_sum, *b_sum;
-    uint32_t *cc_pred, *s_pred;
-    const uint32_t *rc_pred;
+    const uint32_t *cc_pred, *rc_pred;
     const uint32_t *cc_obs, *rc_obs;
-    const float *w_a, *tau;
+    const float *tau;
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
-    int M, N, K, batch;
-    int recombine;        // 1: build the column predictions from the stripe outputs; 0: reuse stored ones
+    int M, N, batch;
 };
-
-template <bool IS_INT>
-__device__ __forceinline__ uint32_t recombine_terms(const uint32_t *part, long stride, const float *w)
-{
-    if (IS_INT) {
-        uint32_t v = 0;
-#pragma unroll
-        for (int t = 0; t < NTERM; ++t) v += part[t * stride] << (8 * t);
-        return v;
-    }
-    float v = 0.f;
-#pragma unroll
-    for (int t = NTERM - 1; t >= 0; --t) v += __uint_as_float(part[t * stride]) * w[t];   // small terms first
-    return __float_as_uint(v);
-}
 
 template <bool IS_INT>
 __device__ __forceinline__ bool mismatch(uint32_t obs, uint32_t pred, float tol)
@@ -547,47 +549,18 @@ template <bool IS_INT>
 __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
 {
     __shared__ int is_last;
-    __shared__ uint32_t sred[4];
     const int bz = blockIdx.z, tid = threadIdx.x;
     const int idx = blockIdx.x * 256 + tid;
     const int M = a.M, N = a.N;
     const float tol = IS_INT ? 0.f : a.tau[bz];
     bool frow = false, fcol = false;
     if (idx < M) {
-        // row check: prediction A (B e) was taken by the encode pass over A
-        const uint32_t pred = a.rc_pred[(long)bz * M + idx];
-        frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], pred, tol);
+        frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], a.rc_pred[(long)bz * M + idx], tol);
         a.row_flag[(long)bz * M + idx] = frow ? 1 : 0;
     } else if (idx < M + N) {
         const int j = idx - M;
-        uint32_t pred;
-        if (a.recombine) {
-            pred = recombine_terms<IS_INT>(a.cc_part + (long)bz * NTERM * N + j, N, a.w_a + (long)bz * NTERM);
-            a.cc_pred[(long)bz * N + j] = pred;
-        } else pred = a.cc_pred[(long)bz * N + j];
-        fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], pred, tol);
+        fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], a.cc_pred[(long)bz * N + j], tol);
         a.col_flag[(long)bz * N + j] = fcol ? 1 : 0;
-    }
-    if (a.recombine && blockIdx.x == 0) {
-        // scalar a.b (the paper's own single-number check value), straight from the two sums
-        const uint32_t *av = a.a_sum + (long)bz * a.K, *bv = a.b_sum + (long)bz * a.K;
-        if (IS_INT) {
-            uint32_t v = 0;
-            for (int k = tid; k < a.K; k += 256) v += av[k] * bv[k];
-            v = (uint32_t)wave_sum((int)v);
-            if ((tid & 63) == 0) sred[tid >> 6] = v;
-            __syncthreads();
-            if (tid == 0) a.s_pred[bz] = sred[0] + sred[1] + sred[2] + sred[3];
-        } else {
-            float v = 0.f;
-            for (int k = tid; k < a.K; k += 256) v += __uint_as_float(av[k]) * __uint_as_float(bv[k]);
-            v = wave_sum(v);
-            if ((tid & 63) == 0) sred[tid >> 6] = __float_as_uint(v);
-            __syncthreads();
-            if (tid == 0)
-                a.s_pred[bz] = __float_as_uint((__uint_as_float(sred[0]) + __uint_as_float(sred[1])) +
-                                               (__uint_as_float(sred[2]) + __uint_as_float(sred[3])));
-        }
     }
     const unsigned nr = __syncthreads_count(frow);
     const unsigned nc = __syncthreads_count(fcol);
@@ -610,19 +583,15 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     }
 }
 
-hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, bool use_vobs, const Verdict &v,
-                          hipStream_t st)
+hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st)
 {
     CmpArgs a;
-    a.cc_part = w.cc_part; a.a_sum = w.a_sum; a.b_sum = w.b_sum;
-    a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred; a.s_pred = w.s_pred;
-    a.cc_obs = use_vobs ? w.cc_vobs : w.cc_obs;
-    a.rc_obs = use_vobs ? w.rc_vobs : w.rc_obs;
-    a.w_a = w.w_a; a.tau = w.tau;
+    a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
+    a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
+    a.tau = w.tau;
     a.row_flag = v.row_flag; a.col_flag = v.col_flag; a.counts = v.counts;
     a.ticket = w.cmp_ticket;
-    a.M = s.M; a.N = s.N; a.K = s.K; a.batch = s.batch;
-    a.recombine = use_vobs ? 0 : 1;
+    a.M = s.M; a.N = s.N; a.batch = s.batch;
     dim3 grid((unsigned)((s.M + s.N + 255) / 256), 1, (unsigned)s.batch);
     if (dt == DT_I8) hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, a);
     else             hipLaunchKernelGGL(compare_kernel<false>, grid, dim3(256), 0, st, a);

@@ -38,7 +38,14 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 __host__ __device__ constexpr int epi_wave_bytes(int TN) { return 32 * (TN * 4 + 16); }
 __host__ __device__ constexpr int epi_total_bytes(int BM, int BN)
 {
-    return 4 * epi_wave_bytes(BN / 2) + (2 * BM + 2 * BN) * 4;
+    return 4 * epi_wave_bytes(BN / 2) + (2 * BM + 2 * BN) * 4 + 16;
+}
+
+template <bool IS_INT> __device__ __forceinline__ bool epi_mismatch(uint32_t obs, uint32_t pred, float tol)
+{
+    if (IS_INT) return obs != pred;                          // equality in Z/2^32
+    const float d = fabsf(__uint_as_float(obs) - __uint_as_float(pred));
+    return !(d <= tol);                                      // NaN and Inf always flag
 }
 
 // Read one accumulator element where it lives (an AGPR) at the point of use.  Without this the
@@ -78,7 +85,7 @@ template <> __device__ __forceinline__ uint32_t pack2<DT_F16>(float a, float b)
 template <int DT, int BM, int BN, bool PROT>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                                               typename Traits<DT>::accv_t (&acc)[BM / 64][BN / 64],
-                                              uint8_t *smem, int m0, int n0, int bz)
+                                              uint8_t *smem, int m0, int n0, int bz, int tile_row_id)
 {
     using T = Traits<DT>;
     typedef typename T::acc_t acc_t;
@@ -180,8 +187,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                         for (int c0 = 2 * lane; c0 < TN; c0 += 128) {
                             const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + c0 * 4);
                             uint32_t *dst = g.cc_part + ((long)bz * NTERM + t) * N + wc0 + c0;
-                            dst[0] = w.x;
-                            dst[1] = w.y;
+                            publish_word(dst, w.x);          // read by the workgroup that compares this column
+                            publish_word(dst + 1, w.y);
                         }
                     }
                 }
@@ -202,7 +209,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                             T::store_c(Cb, (long)gr * g.ldc + gc, v);
                             if (PROT) rowsum = add_t(rowsum, v);
                         } else if (PROT && gr < Mx) {
-                            g.cc_part[((long)bz * NTERM + (gr - M)) * N + gc] = as_word(v);
+                            publish_word(g.cc_part + ((long)bz * NTERM + (gr - M)) * N + gc, as_word(v));
                         }
                     }
                 });
@@ -279,6 +286,87 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 int gc = n0 + (t - BM);
                 if (gc < N)
                     atomic_add_word(g.cc_obs + (long)bz * N + gc, add_t(cs_part[t - BM], cs_part[BN + t - BM]));
+            }
+        }
+        if (g.fuse_compare) {
+            // ---- compare and flag without another launch (Sec. III-B.1 item (2)).  The workgroup
+            // that completes a tile row compares that row's sums, the one that completes a tile
+            // column recombines the stripe terms and compares that column's sums; the last
+            // workgroup of the launch publishes counts and status.  Everything the comparing
+            // workgroup reads from others was written with device-scope atomics (performed at
+            // the coherence point); the barrier waits for this workgroup's outstanding ones
+            // before it takes its tickets.
+            static_assert(BM <= 256 && BN <= 256, "one row / column per thread in the fused compare");
+            int *flag_s = reinterpret_cast<int *>(cs_part + 2 * BN);       // [3] after the partial sums
+            __syncthreads();
+            if (tid == 0) {
+                const unsigned tr = atomicAdd(g.row_ticket + (long)bz * g.tiles_m + tile_row_id, 1u);
+                const unsigned tc = atomicAdd(g.col_ticket + (long)bz * g.tiles_n + n0 / BN, 1u);
+                flag_s[0] = (tr == (unsigned)g.tiles_n - 1);
+                flag_s[1] = (tc == (unsigned)g.tiles_m - 1);
+            }
+            __syncthreads();
+            const bool last_row = flag_s[0], last_col = flag_s[1];
+            const float tol = T::IS_INT ? 0.f : g.tau[bz];
+            unsigned nr = 0, nc = 0;
+            if (last_row) {
+                bool f = false;
+                for (int t = tid; t < BM; t += 256) {
+                    const int gr = m0 + t;
+                    if (gr < M) {
+                        const uint32_t obs = atomic_read_word(g.rc_obs + (long)bz * M + gr);
+                        f = epi_mismatch<T::IS_INT>(obs, g.rc_pred[(long)bz * M + gr], tol);
+                        g.row_flag[(long)bz * M + gr] = f ? 1 : 0;
+                    }
+                }
+                nr = __syncthreads_count(f);
+            }
+            if (last_col) {
+                bool f = false;
+                for (int t = tid; t < BN; t += 256) {
+                    const int gc = n0 + t;
+                    if (gc < N) {
+                        uint32_t term[NTERM];
+#pragma unroll
+                        for (int q = 0; q < NTERM; ++q)
+                            term[q] = atomic_read_word(g.cc_part + ((long)bz * NTERM + q) * N + gc);
+                        uint32_t pred;
+                        if (T::IS_INT) {
+                            pred = 0;
+#pragma unroll
+                            for (int q = 0; q < NTERM; ++q) pred += term[q] << (8 * q);
+                        } else {
+                            float v = 0.f;
+#pragma unroll
+                            for (int q = NTERM - 1; q >= 0; --q)          // small terms first
+                                v += __uint_as_float(term[q]) * g.w_a[(long)bz * NTERM + q];
+                            pred = __float_as_uint(v);
+                        }
+                        g.cc_pred[(long)bz * N + gc] = pred;
+                        const uint32_t obs = atomic_read_word(g.cc_obs + (long)bz * N + gc);
+                        f = epi_mismatch<T::IS_INT>(obs, pred, tol);
+                        g.col_flag[(long)bz * N + gc] = f ? 1 : 0;
+                    }
+                }
+                nc = __syncthreads_count(f);
+            }
+            if (tid == 0) {
+                if (nr) atomicAdd(g.fin + 1, nr);
+                if (nc) atomicAdd(g.fin + 2, nc);
+            }
+            __syncthreads();                         // orders this workgroup's count atomics before its final ticket
+            if (tid == 0) {
+                const unsigned total = gridDim.x * gridDim.z;
+                if (atomicAdd(g.fin, 1u) == total - 1) {
+                    const uint32_t r = atomicExch(g.fin + 1, 0u), c = atomicExch(g.fin + 2, 0u);
+                    atomicExch(g.fin, 0u);
+                    const uint32_t st = (r == 0 && c == 0) ? 0u : ((r == 0 || c == 0) ? 2u : 1u);
+                    g.counts[0] = r;
+                    g.counts[1] = c;
+                    g.counts[2] = st;
+                    g.counts[3] = 0u;
+                    g.counts[4] = st;
+                }
             }
         }
     }

@@ -22,7 +22,7 @@ typedef __attribute__((address_space(3))) void *las_ptr;
 
 // One BM x BN tile with origin (m0, n0) of batch item bz.
 template <int DT, int BM, int BN, bool PROT>
-__device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int m0, int n0, int bz)
+__device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int m0, int n0, int bz, int tile_row_id)
 {
     using T = Traits<DT>;
     typedef typename T::accv_t accv_t;
@@ -160,7 +160,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         for (int s = 1; s < nslab; ++s) slab(std::false_type{}, s);
     }
     __syncthreads();
-    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, tile_row_id);
 }
 
 // Workgroup -> tile inside a region of tiles_m x tiles_n tiles: consecutive ids of one XCD
@@ -191,10 +191,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     int tm, tn;
     if (bid < g.n_big) {
         map_tile(bid, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz);
+        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tm);
     } else {
         map_tile(bid - g.n_big, (int)gridDim.x - g.n_big, g.tiles_m_small, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz);
+        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, g.tiles_m_big + tm);
     }
 }
 

@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     }
 
     // ---- epilogue
-    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz);
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, tm_idx);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -249,7 +249,7 @@ void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 }
 
 hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
-                       const Workspace &w, const InjectArm &arm, hipStream_t st)
+                       const Workspace &w, const InjectArm &arm, const Verdict *v, hipStream_t st)
 {
     GemmArgs g;
     g.A = (const uint8_t *)A;
@@ -263,6 +263,11 @@ hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void 
     g.lda = s.lda; g.ldb = s.ldb; g.ldc = s.ldc;
     g.sA = s.sA; g.sB = s.sB; g.sC = s.sC;
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
+    g.fuse_compare = (protect && v != nullptr) ? 1 : 0;
+    g.rc_pred = w.rc_pred; g.cc_pred = w.cc_pred; g.w_a = w.w_a; g.tau = w.tau;
+    g.row_flag = v ? v->row_flag : nullptr; g.col_flag = v ? v->col_flag : nullptr;
+    g.counts = v ? v->counts : nullptr;
+    g.row_ticket = w.row_ticket; g.col_ticket = w.col_ticket; g.fin = w.fin;
     const bool tb = s.transB != 0;
     if (gemm_fast_eligible(dt, s.M, s.N, s.K, tb, s.lda, s.ldb)) return launch_gemm_fast(dt, protect, g, s.batch, st);
     switch (dt) {
