@@ -24,6 +24,13 @@ def ctx():
     ab.abft_destroy(c)
 
 
+@pytest.fixture(scope="module")
+def ctx_big():
+    c = ab.abft_create(max_rows=12608, max_cols=3072, max_depth=3072, max_batch=1)
+    yield c
+    ab.abft_destroy(c)
+
+
 def ring(x):
     return np.mod(np.asarray(x, dtype=np.int64), 2 ** 32).astype(np.uint32)
 
@@ -271,3 +278,84 @@ def test_argument_errors(ctx):
     # nothing above may have disturbed the device
     run.gemm(ab.ABFT_DETECT)
     assert run.cnt()[2] == ab.ABFT_CLEAN
+
+
+def test_full_size_bench_workload_sampled(ctx_big):
+    """The benchmark workload at full size (ViT-B fc1, batch 64, bf16), in the launch configuration
+    bench.py times.  The oracle recomputes a seeded sample of full rows of C one by one, all four
+    checksum vectors exactly (O(MK + KN + K(M+N)) work), and the flags must be clean."""
+    dtype = "bf16"
+    g = gen.CONFIGS[1]["gemms"][0]
+    M, N, K = g["M"], g["N"], g["K"]
+    A, B = gen.gen_operands(dtype, M, N, K, gen.seed_for(1, 0), gen.seed_for(1, 1), trans_b=True)
+    run = Run(ctx_big, dtype, A, B, True)
+    run.gemm(ab.ABFT_DETECT)
+    rf, cf = run.flags()
+    cnt = run.cnt()
+    assert not rf.any() and not cf.any() and cnt[2] == ab.ABFT_CLEAN
+    Ad, Bd = orc.decode(A[0], dtype), orc.decode(B[0], dtype)
+    a, b = orc.encode(Ad, Bd, True)
+    cc, rc, s = orc.predict(Ad, Bd, a, b, True)
+    ma, mb = np.max(np.abs(Ad)), np.max(np.abs(Bd))
+    tau = orc.tau(K, ma, mb)
+    assert run.ws(ab.ABFT_WS_TAU)[0, 0] == pytest.approx(tau, rel=1e-5)
+    tol = 1e-2 * tau
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_A_SUM)[0] - a)) <= 1e-5 * M * ma
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_B_SUM)[0] - b)) <= 1e-5 * N * mb
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_CC_PRED)[0] - cc)) <= tol * np.sqrt(M)
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_RC_PRED)[0] - rc)) <= tol * np.sqrt(N)
+    # observed sums equal the predictions up to fp32 noise (the identity, at full size)
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_CC_OBS)[0] - cc)) <= tol * np.sqrt(M)
+    assert np.max(np.abs(run.ws(ab.ABFT_WS_RC_OBS)[0] - rc)) <= tol * np.sqrt(N)
+    assert abs(run.ws(ab.ABFT_WS_S_PRED)[0, 0] - s) <= 1e-4 * K * M * N * ma * mb
+    # sampled rows: every tile row region incl. the 128-row tiles at the bottom and the last row
+    rng = np.random.default_rng(gen.seed_for(1, 7))
+    rows = np.unique(np.concatenate([rng.integers(0, M, 24), [0, 255, 256, 10751, 10752, 10880, M - 1]]))
+    C = run.C()[0]
+    ref = orc.gemm(np.ascontiguousarray(Ad[rows]), Bd, True)
+    got = orc.decode(C[rows], dtype)
+    scale = np.max(np.abs(ref))
+    assert np.max(np.abs(got - ref)) <= 1e-2 * scale
+    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 2e-6 * scale + 1e-7)
+    assert np.mean(C[rows] != orc.store(ref, dtype)) < 5e-3
+    # a stored flip at full size: verify localises it, correct restores the bits
+    C_before = run.dC.clone()
+    i, j, bit = 11000, 2999, 14
+    run.inject(0, i, j, bit)
+    run.verify()
+    rf, cf = run.flags()
+    assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j] and run.cnt()[2] == ab.ABFT_LOCALISED
+    run.correct()
+    assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
+
+
+def test_full_size_int8_fc2_sampled(ctx_big):
+    """ViT-B fc2 at batch 32 in int8 (the injection-campaign GEMM): exact checksums in Z/2^32 at
+    full size, sampled rows bit-exact, a handful of seeded flips detected, localised, repaired."""
+    g = gen.CONFIGS[4]["gemms"][0]
+    M, N, K = g["M"], g["N"], g["K"]
+    A, B = gen.gen_operands("i8", M, N, K, gen.seed_for(4, 0), gen.seed_for(4, 1), trans_b=True)
+    run = Run(ctx_big, "i8", A, B, True)
+    run.gemm(ab.ABFT_DETECT)
+    rf, cf = run.flags()
+    assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+    a, b = orc.encode(A[0], B[0], True)
+    cc, rc, s = orc.predict(A[0], B[0], a, b, True)
+    for which, want in ((ab.ABFT_WS_A_SUM, a), (ab.ABFT_WS_B_SUM, b), (ab.ABFT_WS_CC_PRED, cc),
+                        (ab.ABFT_WS_RC_PRED, rc), (ab.ABFT_WS_CC_OBS, cc), (ab.ABFT_WS_RC_OBS, rc)):
+        assert np.array_equal(run.ws(which)[0].view(np.uint32), ring(want)), which
+    assert run.ws(ab.ABFT_WS_S_PRED)[0, 0].view(np.uint32) == ring(s)
+    rng = np.random.default_rng(gen.seed_for(4, 7))
+    rows = np.unique(np.concatenate([rng.integers(0, M, 16), [0, 6143, 6144, M - 1]]))
+    ref = orc.gemm(np.ascontiguousarray(A[0][rows]), B[0], True)
+    C = run.C()[0]
+    assert np.array_equal(C[rows], ref.astype(np.int32))
+    C_before = run.dC.clone()
+    for (_, i, j, bit) in gen.gen_flips(12, M, N, "i8", gen.seed_for(4, 9)):
+        i, j, bit = int(i), int(j), int(bit)
+        run.inject(0, i, j, bit)
+        run.verify()
+        rf, cf = run.flags()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]
+        run.correct()
+        assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN
