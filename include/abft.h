@@ -73,8 +73,8 @@ enum {
     ABFT_OK         =  0,
     ABFT_EINVAL     = -1,   /* null pointer, unknown dtype/mode, index out of range */
     ABFT_EALIGN     = -2,   /* pointer, leading dimension or stride not a multiple of 16 bytes */
-    ABFT_ESHAPE     = -3,   /* non-positive size, ld < row length, or K so large that an int32
-                               dot product of int8 values could overflow (K >= 2^17) */
+    ABFT_ESHAPE     = -3,   /* non-positive size, ld < row length, or K beyond what the encode pass
+                               covers (K > 4096; int8 additionally needs K * 2^14 < 2^31) */
     ABFT_EWORKSPACE = -4,   /* shape exceeds what the context was created for */
     ABFT_EHIP       = -5,   /* a HIP runtime call failed (see abft_last_hip_error) */
     ABFT_ESTATE     = -6    /* call needs state that is not there (e.g. cached B encoding) */
@@ -155,8 +155,11 @@ int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape
                 const abft_result *r, void *stream);
 
 /* Replay at tile granularity (Sec. III-B.3): recomputes every 32x32 tile of C that holds a
- * (flagged row, flagged column) pair from A and B, re-sums the touched rows and columns and
- * updates flags and counts.  A and B must be unchanged since abft_gemm. */
+ * (flagged row, flagged column) pair from A and B (same MFMA and k order as abft_gemm, so the
+ * repaired elements are bit-identical to an undisturbed run), then re-sums the stored C as
+ * abft_verify does and rewrites flags and counts (counts[3] = tiles recomputed, counts[4] =
+ * status before).  At most 256 tiles per call; beyond that status = ABFT_TOO_MANY and the
+ * caller replays the GEMM.  A and B must be unchanged since abft_gemm. */
 int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
                  const abft_shape *s, const abft_result *r, void *stream);
 

@@ -299,7 +299,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     carve(ctx, dtype, sh, &w);
     HIP_TRY(launch_zero(w.cc_vobs, (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
-    HIP_TRY(launch_compare(dtype, sh, w, v, st));
+    HIP_TRY(launch_compare(dtype, sh, w, v, false, st));
     return ABFT_OK;
 }
 

@@ -78,7 +78,8 @@ int encode_a_max_k(int dt);
 // v != nullptr: flags and counts are produced by the last-arriving workgroups of the GEMM itself
 hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
                        const Workspace &w, const InjectArm &arm, const Verdict *v, hipStream_t st);
-hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st);
+hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
+                          hipStream_t st);
 hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st);
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
                           const Workspace &w, const Verdict &v, hipStream_t st);

@@ -527,6 +527,7 @@ struct CmpArgs {
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
+    const uint32_t *fix_count;   // non-null after a correction: [0] tiles listed, [1] overflow
     int M, N, batch;
 };
 
@@ -575,17 +576,27 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     if (is_last && tid == 0) {
         uint32_t r = atomicExch(a.ticket + 1, 0u), c = atomicExch(a.ticket + 2, 0u);
         atomicExch(a.ticket, 0u);
+        const uint32_t before = a.counts[2];
         a.counts[0] = r;
         a.counts[1] = c;
-        a.counts[2] = status_of(r, c);
-        a.counts[3] = 0u;
-        a.counts[4] = status_of(r, c);
+        if (a.fix_count) {
+            const uint32_t tiles = a.fix_count[0];
+            a.counts[2] = a.fix_count[1] ? 3u : status_of(r, c);
+            a.counts[3] = tiles > (uint32_t)MAX_FIX_TILES ? (uint32_t)MAX_FIX_TILES : tiles;
+            a.counts[4] = before;
+        } else {
+            a.counts[2] = status_of(r, c);
+            a.counts[3] = 0u;
+            a.counts[4] = status_of(r, c);
+        }
     }
 }
 
-hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st)
+hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
+                          hipStream_t st)
 {
     CmpArgs a;
+    a.fix_count = after_fix ? w.fix_count : nullptr;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
     a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
     a.tau = w.tau;
@@ -779,14 +790,20 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = T::zero();
     const int steps = (K + 2 * CE - 1) / (2 * CE);
-    for (int ks = 0; ks < steps; ++ks) {
+    constexpr int UB = 8;                       // k-steps whose operands are in flight together
+    auto load_a = [&](int ks) __attribute__((always_inline)) -> i32x4 {
         const int kb = ks * 2 * CE + lh * CE;
-        i32x4 av = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
-        if (row < a.M && kb < K) {
+        i32x4 av = {0, 0, 0, 0};
+        if (ks < steps && row < a.M && kb < K) {
             av = *reinterpret_cast<const i32x4 *>(Ab + ((long)row * a.lda + kb) * ES);
             if (kb + CE > K) av = mask_chunk(av, (K - kb) * ES);
         }
-        if (col < a.N && kb < K) {
+        return av;
+    };
+    auto load_b = [&](int ks) __attribute__((always_inline)) -> i32x4 {
+        const int kb = ks * 2 * CE + lh * CE;
+        i32x4 bv = {0, 0, 0, 0};
+        if (ks < steps && col < a.N && kb < K) {
             if (a.transB) {
                 bv = *reinterpret_cast<const i32x4 *>(Bb + ((long)col * a.ldb + kb) * ES);
                 if (kb + CE > K) bv = mask_chunk(bv, (K - kb) * ES);
@@ -809,108 +826,21 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
                 bv[0] = (int)wds[0]; bv[1] = (int)wds[1]; bv[2] = (int)wds[2]; bv[3] = (int)wds[3];
             }
         }
-        acc = T::mfma(bv, av, acc);      // B first: lane = row of C, registers = columns
+        return bv;
+    };
+    for (int ks0 = 0; ks0 < steps; ks0 += UB) {
+        i32x4 av[UB], bv[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) { av[u] = load_a(ks0 + u); bv[u] = load_b(ks0 + u); }
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+            if (ks0 + u < steps) acc = T::mfma(bv[u], av[u], acc);   // B first: lane = row of C, registers = columns
     }
     uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int gc = tc * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
         if (row < a.M && gc < a.N) T::store_c(Cb, (long)row * a.ldc + gc, acc[i]);
-    }
-}
-
-// Step 3: re-sum the rows and columns a recomputed tile touches, re-flag them.
-struct RecheckArgs {
-    const uint8_t *C;
-    int M, N;
-    long ldc, sC;
-    const int32_t *fix_tiles;
-    const uint32_t *fix_count;
-    const uint32_t *cc_pred, *rc_pred;
-    const float *tau;
-    uint8_t *row_flag, *col_flag;
-};
-
-template <int DT>
-__global__ __launch_bounds__(256) void recheck_kernel(RecheckArgs a)
-{
-    using T = Traits<DT>;
-    typedef typename T::acc_t acc_t;
-    __shared__ acc_t red[256];
-    unsigned n = a.fix_count[0];
-    if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
-    if (blockIdx.x >= n) return;
-    const int bz = a.fix_tiles[3 * blockIdx.x], tr = a.fix_tiles[3 * blockIdx.x + 1],
-              tc = a.fix_tiles[3 * blockIdx.x + 2];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
-    const float tol = T::IS_INT ? 0.f : a.tau[bz];
-    // rows: each wave takes 8 of the 32 rows
-    for (int rr = wave; rr < CT; rr += 4) {
-        const int row = tr * CT + rr;
-        acc_t s = T::zero();
-        if (row < a.M)
-            for (int j = lane; j < a.N; j += 64) s = add_t(s, T::load_c(Cb, (long)row * a.ldc + j));
-        s = wave_sum(s);
-        if (lane == 0 && row < a.M) {
-            bool f = mismatch<T::IS_INT>(as_word(s), a.rc_pred[(long)bz * a.M + row], tol);
-            a.row_flag[(long)bz * a.M + row] = f ? 1 : 0;
-        }
-    }
-    // columns: thread (cl, rl) sums every 8th row of column cl
-    const int cl = tid & 31, rl = tid >> 5;
-    const int col = tc * CT + cl;
-    acc_t s = T::zero();
-    if (col < a.N)
-        for (int i = rl; i < a.M; i += 8) s = add_t(s, T::load_c(Cb, (long)i * a.ldc + col));
-    red[tid] = s;
-    __syncthreads();
-    if (rl == 0 && col < a.N) {
-        for (int y = 1; y < 8; ++y) s = add_t(s, red[y * 32 + cl]);
-        bool f = mismatch<T::IS_INT>(as_word(s), a.cc_pred[(long)bz * a.N + col], tol);
-        a.col_flag[(long)bz * a.N + col] = f ? 1 : 0;
-    }
-}
-
-// Step 4: recount flags, set status.
-struct CountArgs {
-    const uint8_t *row_flag, *col_flag;
-    long nrows, ncols;            // batch*M, batch*N
-    uint32_t *counts;
-    uint32_t *ticket;             // [3], self-cleaning
-    uint32_t *fix_count;
-};
-
-__global__ __launch_bounds__(256) void recount_kernel(CountArgs a)
-{
-    __shared__ int is_last;
-    const int tid = threadIdx.x;
-    long step = (long)gridDim.x * 256;
-    int r = 0, c = 0;
-    for (long i = (long)blockIdx.x * 256 + tid; i < a.nrows; i += step) r += a.row_flag[i] ? 1 : 0;
-    for (long i = (long)blockIdx.x * 256 + tid; i < a.ncols; i += step) c += a.col_flag[i] ? 1 : 0;
-    r = wave_sum(r);
-    c = wave_sum(c);
-    if ((tid & 63) == 0) {
-        if (r) atomicAdd(a.ticket + 1, (unsigned)r);
-        if (c) atomicAdd(a.ticket + 2, (unsigned)c);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        unsigned t = atomicAdd(a.ticket, 1u);
-        is_last = (t == gridDim.x - 1);
-    }
-    __syncthreads();
-    if (is_last && tid == 0) {
-        uint32_t nr = atomicExch(a.ticket + 1, 0u), nc = atomicExch(a.ticket + 2, 0u);
-        atomicExch(a.ticket, 0u);
-        uint32_t tiles = a.fix_count[0], over = a.fix_count[1];
-        uint32_t before = a.counts[2];
-        a.counts[0] = nr;
-        a.counts[1] = nc;
-        a.counts[2] = over ? 3u : status_of(nr, nc);
-        a.counts[3] = tiles > (uint32_t)MAX_FIX_TILES ? (uint32_t)MAX_FIX_TILES : tiles;
-        a.counts[4] = before;
     }
 }
 
@@ -930,37 +860,18 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     f.M = s.M; f.N = s.N; f.K = s.K; f.transB = s.transB;
     f.lda = s.lda; f.ldb = s.ldb; f.ldc = s.ldc; f.sA = s.sA; f.sB = s.sB; f.sC = s.sC;
     f.fix_tiles = w.fix_tiles; f.fix_count = w.fix_count;
-    RecheckArgs r;
-    r.C = (const uint8_t *)C; r.M = s.M; r.N = s.N; r.ldc = s.ldc; r.sC = s.sC;
-    r.fix_tiles = w.fix_tiles; r.fix_count = w.fix_count;
-    r.cc_pred = w.cc_pred; r.rc_pred = w.rc_pred; r.tau = w.tau;
-    r.row_flag = v.row_flag; r.col_flag = v.col_flag;
     switch (dt) {
-    case DT_I8:
-        hipLaunchKernelGGL(recompute_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
-        hipLaunchKernelGGL(recheck_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
-        break;
-    case DT_BF16:
-        hipLaunchKernelGGL(recompute_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
-        hipLaunchKernelGGL(recheck_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
-        break;
-    case DT_F16:
-        hipLaunchKernelGGL(recompute_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f);
-        hipLaunchKernelGGL(recheck_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(256), 0, st, r);
-        break;
+    case DT_I8:   hipLaunchKernelGGL(recompute_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
+    case DT_BF16: hipLaunchKernelGGL(recompute_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
+    case DT_F16:  hipLaunchKernelGGL(recompute_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
     default: return hipErrorInvalidValue;
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    CountArgs c;
-    c.row_flag = v.row_flag; c.col_flag = v.col_flag;
-    c.nrows = (long)s.batch * s.M; c.ncols = (long)s.batch * s.N;
-    c.counts = v.counts; c.ticket = w.cmp_ticket; c.fix_count = w.fix_count;
-    long total = c.nrows > c.ncols ? c.nrows : c.ncols;
-    unsigned blocks = (unsigned)((total + 256 * 16 - 1) / (256 * 16));
-    if (blocks < 1) blocks = 1;
-    if (blocks > 512) blocks = 512;
-    hipLaunchKernelGGL(recount_kernel, dim3(blocks), dim3(256), 0, st, c);
-    return hipGetLastError();
+    // re-check: the stored C is re-summed as a whole (a streaming pass at HBM speed is cheaper
+    // than strided column walks over the touched tiles) and compared with the predictions
+    if ((e = launch_zero(w.cc_vobs, (size_t)s.batch * ((size_t)s.M + s.N), st)) != hipSuccess) return e;
+    if ((e = launch_verify_sums(dt, C, s, w, st)) != hipSuccess) return e;
+    return launch_compare(dt, s, w, v, true, st);
 }
 
 // ====================================================================== inject
