@@ -12,12 +12,10 @@ using namespace abft;
 struct abft_ctx {
     abft_config cfg;
     // device pools (32-bit words unless noted)
-    uint32_t *pool_depth;   // (2 * ENC_ACC_COPIES + 2) * max_depth words: a_acc, b_acc copies, a_sum, b_sum
-    uint8_t  *pool_stripe;  // NTERM * max_depth * 2 bytes
+    uint32_t *pool_depth;   // (ENC_ACC_COPIES + 1) * max_depth words: b_acc copies, b_sum
     uint32_t *pool_batch;   // per-batch scalars
-    uint32_t *pool_rows;    // rc_pred
-    uint32_t *pool_cols;    // cc_part (NTERM), cc_pred
-    uint32_t *pool_obs;     // cc_obs | rc_obs   (zeroed as one region)
+    uint32_t *pool_cols;    // cc_pred
+    uint32_t *pool_obs;     // cc_obs | rc_obs | rc_pred | a_sum | a_max (zeroed as one region)
     uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
     int32_t  *fix_tiles;
     uint32_t *small;        // fix_count[4], cmp_ticket[4]
@@ -32,7 +30,7 @@ struct abft_ctx {
     int prof_cap, prof_n;
 };
 
-static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + NTERM /*w_a*/ + 1 /*ticket*/ + 1 /*s_pred*/;
+static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + 1 /*ticket*/ + 1 /*s_pred*/;
 
 static int fail_hip(abft_ctx *c, hipError_t e)
 {
@@ -76,12 +74,10 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     const size_t D = (size_t)c->cfg.max_depth, R = (size_t)cfg->max_rows, Cn = (size_t)cfg->max_cols,
                  Bt = (size_t)cfg->max_batch;
     struct { void **p; size_t bytes; } req[] = {
-        {(void **)&c->pool_depth, (2 * ENC_ACC_COPIES + 2) * D * 4},
-        {(void **)&c->pool_stripe, NTERM * D * 2},
+        {(void **)&c->pool_depth, (ENC_ACC_COPIES + 1) * D * 4},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
-        {(void **)&c->pool_rows, R * 4},
-        {(void **)&c->pool_cols, (NTERM + 1) * Cn * 4},
-        {(void **)&c->pool_obs, (R + Cn + (R + Cn) / 128 + 4 * Bt + 16) * 4},
+        {(void **)&c->pool_cols, Cn * 4},
+        {(void **)&c->pool_obs, (Cn + 2 * R + D + Bt) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
         {(void **)&c->small, 8 * 4},
@@ -107,8 +103,7 @@ extern "C" int abft_destroy(abft_ctx *c)
 {
     if (!c) return ABFT_EINVAL;
     prof_free(c);
-    void *ptrs[] = {c->pool_depth, c->pool_stripe, c->pool_batch, c->pool_rows, c->pool_cols,
-                    c->pool_obs, c->pool_vobs, c->fix_tiles, c->small};
+    void *ptrs[] = {c->pool_depth, c->pool_batch, c->pool_cols, c->pool_obs, c->pool_vobs, c->fix_tiles, c->small};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete c;
@@ -128,7 +123,7 @@ static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need,
     if (s->transB != 0 && s->transB != 1) return ABFT_EINVAL;
     const int es = elem_size(dt), os = out_size(dt);
     if (dt == ABFT_I8 && s->K >= (1 << 17)) return ABFT_ESHAPE;       // K * 2^14 must stay below 2^31
-    if ((need & 1) && s->K > encode_a_max_k(dt)) return ABFT_ESHAPE;  // rows longer than the encode pass covers
+    if ((need & 1) && s->K > protect_max_k(dt)) return ABFT_ESHAPE;   // deeper than the protected GEMM covers
     if ((need & 1) && s->lda < s->K) return ABFT_ESHAPE;
     if ((need & 2) && s->ldb < (s->transB ? s->K : s->N)) return ABFT_ESHAPE;
     if ((need & 4) && s->ldc < s->N) return ABFT_ESHAPE;
@@ -156,42 +151,30 @@ static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need,
 static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
 {
     const size_t bK = (size_t)s.batch * s.K, bM = (size_t)s.batch * s.M, bN = (size_t)s.batch * s.N;
-    const size_t D = (size_t)c->cfg.max_depth, R = (size_t)c->cfg.max_rows, Cn = (size_t)c->cfg.max_cols,
-                 Bt = (size_t)c->cfg.max_batch;
-    (void)bK;
-    w->a_acc = c->pool_depth;
-    w->b_acc = c->pool_depth + ENC_ACC_COPIES * D;
+    const size_t D = (size_t)c->cfg.max_depth, Bt = (size_t)c->cfg.max_batch;
+    w->b_acc = c->pool_depth;
     w->acc_stride = (long)D;
-    w->a_sum = c->pool_depth + 2 * ENC_ACC_COPIES * D;
-    w->b_sum = c->pool_depth + (2 * ENC_ACC_COPIES + 1) * D;
-    w->stripe_a = c->pool_stripe;
+    w->b_sum = c->pool_depth + ENC_ACC_COPIES * D;
     uint32_t *pb = c->pool_batch;
     w->max_acc = pb;                          pb += 2 * Bt;
     w->maxabs = (float *)pb;                  pb += 2 * Bt;
     w->tau = (float *)pb;                     pb += Bt;
-    w->w_a = (float *)pb;                     pb += NTERM * Bt;
     w->enc_ticket = pb;                       pb += Bt;
     w->s_pred = pb;
-    w->rc_pred = c->pool_rows;
-    w->cc_part = c->pool_cols;
-    w->cc_pred = c->pool_cols + NTERM * Cn;
-    // one region that must be zero before the GEMM: cc_obs | rc_obs | tile tickets | launch ticket
+    w->cc_pred = c->pool_cols;
+    // one region that must be zero before the protected GEMM
     w->cc_obs = c->pool_obs;
-    w->rc_obs = c->pool_obs + bN;
-    {
-        const size_t trows = (size_t)s.batch * ((size_t)(s.M + NTERM + 127) / 128);   // bound for any tile height
-        const size_t tcols = (size_t)s.batch * ((size_t)(s.N + 127) / 128);
-        w->row_ticket = w->rc_obs + bM;
-        w->col_ticket = w->row_ticket + trows;
-        w->fin = w->col_ticket + tcols;
-        w->zero_words = bN + bM + trows + tcols + 4;
-    }
+    w->rc_obs = w->cc_obs + bN;
+    w->rc_pred = w->rc_obs + bM;
+    w->a_sum = w->rc_pred + bM;
+    w->a_max = w->a_sum + bK;
+    w->zero_words = bN + 2 * bM + bK + (size_t)s.batch;
     w->cc_vobs = c->pool_vobs;
     w->rc_vobs = c->pool_vobs + bN;
     w->fix_tiles = c->fix_tiles;
     w->fix_count = c->small;
     w->cmp_ticket = c->small + 4;
-    (void)dt; (void)bM;
+    (void)dt;
 }
 
 static bool same_b(const abft_shape &x, const abft_shape &y)
@@ -224,7 +207,7 @@ extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, con
     Workspace w;
     carve(ctx, dtype, sh, &w);
     ctx->b_valid = false;
-    HIP_TRY(launch_encode_b(dtype, B, sh, w, (hipStream_t)stream));
+    HIP_TRY(launch_encode_b(dtype, B, sh, w, nullptr, 0, (hipStream_t)stream));
     ctx->b_valid = true;
     ctx->b_dt = dtype;
     ctx->b_shape = *s;
@@ -252,7 +235,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         ctx->arm.batch = -1;
         hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
         if (ev) { HIP_TRY(hipEventRecord(ev[0], st)); HIP_TRY(hipEventRecord(ev[1], st)); }
-        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, nullptr, st));
+        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, st));
         if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
         return ABFT_OK;
     }
@@ -266,11 +249,13 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->arm.batch = -1;
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
-    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, st));
-    HIP_TRY(launch_encode_a(dtype, A, sh, w, v.tau_override, w.cc_obs, w.zero_words, st));
+    // pass over B (it also clears what the GEMM accumulates into), GEMM, finish
+    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, w.zero_words, st));
+    else HIP_TRY(launch_zero(w.cc_obs, w.zero_words, st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, &v, st));      // compare + flags fused in its tail
+    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
+    HIP_TRY(launch_finish(dtype, B, sh, w, v, st));
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
     ctx->b_valid = true;
     ctx->b_dt = dtype;

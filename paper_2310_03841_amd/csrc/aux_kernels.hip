@@ -1,6 +1,6 @@
-// Kernels around the protected GEMM: encode (input-side checksums and their
-// stripe encoding), compare (flags), verify (re-sum stored C), correct
-// (localise, recompute tiles, re-check) and the bit-flip test hook.
+// Kernels around the protected GEMM: the pass over B (its checksum vector), finish (column
+// prediction from the sums the GEMM collected, compare, flags), verify (re-sum stored C),
+// correct (localise, recompute tiles, re-check) and the bit-flip test hook.
 //
 // Paper references: the two input-side vectors and the comparison with the
 // output sums are the checksum scheme of Sec. III-B.1 ("Checksums"); equality
@@ -31,26 +31,14 @@ hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st)
 // ====================================================================== encode
 // Input-side checksum vectors (Sec. III-B.1 "Checksums"): a = e^T A (the input summed over its
 // rows) and b = B e (the weight reduced over its output dimension), both of length K, plus
-// what only a pass over the operands can give: max|A|, max|B| for the tolerance, and the row
-// checksum prediction rc_pred = A b.  That last product is a matrix-vector product, bound by
-// the read of A, so it rides on the same streaming pass instead of occupying MFMA tiles.
-// The pass over B comes first (b must be complete before A b); for a weight it is done once,
-// offline (remark (2) of the same paragraph).
+// max|A|, max|B| for the tolerance and the row checksum prediction rc_pred = A b.  Everything
+// that reads A is done by the GEMM kernel on the slabs it holds in LDS (gemm_apass.h); what is
+// left here is the pass over B, which must be complete before that (A b needs all of b).  For a
+// weight it is done once, offline (remark (2) of the same paragraph).
 constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread (B pass)
 // Atomics on one cache line are served one after the other (tens of nanoseconds each), so the
 // row blocks of a pass spread their column sums over several accumulator copies.
 constexpr int ENC_COPIES = ENC_ACC_COPIES;
-
-// Split an int32 sum into four signed base-256 digits: v = d0 + 2^8 d1 + 2^16 d2 + 2^24 d3 (mod 2^32).
-__device__ __forceinline__ void split_digits(int v, int8_t d[NTERM])
-{
-#pragma unroll
-    for (int t = 0; t < NTERM; ++t) {
-        int8_t lo = (int8_t)(v & 0xFF);
-        d[t] = lo;
-        v = (int)(((int64_t)v - (int64_t)lo) >> 8);
-    }
-}
 
 // Sum the accumulator copies of column k, leave them clean for the next call.  The reads go
 // through the coherence point (device-scope atomic loads, all in flight at once); the zeros are
@@ -86,6 +74,8 @@ struct EncBArgs {
     uint32_t *max_acc;    // [batch][2]
     float *maxabs;        // [batch][2]
     uint32_t *ticket;     // [batch]
+    uint32_t *zero_ptr;   // region every block helps to clear (the next kernel's atomics start at zero)
+    size_t zero_words;
 };
 
 template <int DT>
@@ -99,6 +89,11 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
     __shared__ int is_last;
 
     const int tid = threadIdx.x, bz = blockIdx.z;
+    {
+        const size_t nb = (size_t)gridDim.x * gridDim.z;
+        const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
+        for (size_t i = bid * 256 + tid; i < e.zero_words; i += nb * 256) e.zero_ptr[i] = 0u;
+    }
     const int win = blockIdx.x % e.nwin, rb = blockIdx.x / e.nwin;
     const int CW = 1 << e.cw_log2, RL = 256 >> e.cw_log2;
     const int cx = tid & (CW - 1), ry = tid >> e.cw_log2;
@@ -184,231 +179,8 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
         e.maxabs[(long)bz * 2 + 1] = __uint_as_float(atomicExch(e.max_acc + (long)bz * 2 + 1, 0u));
 }
 
-// ---------------------------------------------------------------- A pass: a = e^T A, A b, max|A|, stripe
-// A block owns whole rows: CW lanes of 16-byte chunks cover a row in NW windows, 256 / CW rows
-// at a time, so the dot product of a row with b completes inside the block (no atomics, no
-// zeroing for rc_pred).  Column sums go to the accumulator copies; the last block of a batch
-// item turns them into a, its stripe encoding, and the tolerance.
-struct EncAArgs {
-    const uint8_t *A;
-    long lda, sA;
-    int M, K, Kp;
-    int cw_log2, nwin, rpb, nrb;
-    uint32_t *a_acc;
-    long acc_stride;
-    uint32_t *a_sum;
-    const uint32_t *b_sum;
-    uint32_t *rc_pred;
-    uint8_t *stripe;      // [batch][NTERM][Kp] operand elements
-    float *w_a;           // [batch][NTERM]
-    uint32_t *max_acc;
-    float *maxabs, *tau;
-    uint32_t *ticket;
-    uint32_t *s_pred;     // [batch] scalar a . b (the paper's own single-number check value)
-    float tau_override;
-    uint32_t *zero_ptr;
-    size_t zero_words;
-};
-
 __device__ __forceinline__ int mul_t(int x, int y) { return (int)((uint32_t)x * (uint32_t)y); }
 __device__ __forceinline__ float mul_t(float x, float y) { return x * y; }
-
-template <int DT, int NW>
-__global__ __launch_bounds__(256) void encode_a_kernel(EncAArgs e)
-{
-    using T = Traits<DT>;
-    typedef typename T::acc_t acc_t;
-    constexpr int ES = T::ES, CE = 16 / ES;
-    constexpr int UR = NW >= 8 ? 1 : 8 / NW;              // rows in flight per thread
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    __shared__ float fred[4];
-    __shared__ int is_last;
-
-    const int tid = threadIdx.x, bz = blockIdx.z, rb = blockIdx.x;
-    const int K = e.K, M = e.M;
-    // every block takes a share of the words that must start at zero for the GEMM epilogue
-    {
-        size_t nb = (size_t)gridDim.x * gridDim.z;
-        size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
-        for (size_t i = bid * 256 + tid; i < e.zero_words; i += nb * 256) e.zero_ptr[i] = 0u;
-    }
-    const int CW = 1 << e.cw_log2, RL = 256 >> e.cw_log2;
-    const int cx = tid & (CW - 1), ry = tid >> e.cw_log2;
-    const int span = e.nwin * CW * CE;                      // columns covered by the windows (>= K)
-    acc_t *bl = reinterpret_cast<acc_t *>(lds);             // b staged, zero beyond K
-    acc_t *red = bl + span;                                 // [RL][CW * CE]
-    for (int k = tid; k < span; k += 256)
-        bl[k] = k < K ? from_word<acc_t>(e.b_sum[(long)bz * K + k]) : T::zero();
-    __syncthreads();
-
-    const uint8_t *Ab = e.A + (long)bz * e.sA * ES;
-    const int rbeg = rb * e.rpb, rend = min(rbeg + e.rpb, M);
-    const int iters = (e.rpb + RL * UR - 1) / (RL * UR);
-
-    acc_t colacc[NW][CE];
-#pragma unroll
-    for (int w = 0; w < NW; ++w)
-#pragma unroll
-        for (int q = 0; q < CE; ++q) colacc[w][q] = T::zero();
-    float mx = 0.f;
-
-    for (int it = 0; it < iters; ++it) {
-        i32x4 v[UR][NW];
-#pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            const int r = rbeg + ry + (it * UR + u) * RL;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const int col0 = (w * CW + cx) * CE;
-                v[u][w] = i32x4{0, 0, 0, 0};
-                if (w < e.nwin && col0 < K && r < rend)
-                    v[u][w] = *reinterpret_cast<const i32x4 *>(Ab + ((long)r * e.lda + col0) * ES);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < UR; ++u) {
-            const int r = rbeg + ry + (it * UR + u) * RL;
-            acc_t dot = T::zero();
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                if (w < e.nwin) {
-                    const int col0 = (w * CW + cx) * CE;
-                    i32x4 x4 = v[u][w];
-                    if (K - col0 < CE) x4 = mask_chunk(x4, K - col0 > 0 ? (K - col0) * ES : 0);
-#pragma unroll
-                    for (int q = 0; q < CE; ++q) {
-                        const acc_t x = T::elem(x4, q);
-                        if (!T::IS_INT) mx = fmaxf(mx, fabsf((float)x));
-                        colacc[w][q] = add_t(colacc[w][q], x);
-                        dot = add_t(dot, mul_t(x, bl[col0 + q]));
-                    }
-                }
-            }
-            for (int o = 1; o < CW; o <<= 1) dot = add_t(dot, __shfl_xor(dot, o));
-            if (cx == 0 && r < rend) e.rc_pred[(long)bz * M + r] = as_word(dot);
-        }
-    }
-    // column sums: reduce over the row lanes in LDS, then one coalesced atomic per column
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        if (w < e.nwin) {
-            __syncthreads();
-#pragma unroll
-            for (int q = 0; q < CE; ++q) red[(ry * CW + cx) * CE + q] = colacc[w][q];
-            __syncthreads();
-            for (int c = tid; c < CW * CE; c += 256) {
-                const int col = w * CW * CE + c;
-                if (col < K) {
-                    acc_t t = red[c];
-                    for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
-                    atomic_add_word(e.a_acc + (rb % ENC_COPIES) * e.acc_stride + (long)bz * K + col, t);
-                }
-            }
-        }
-    }
-    if (!T::IS_INT) {
-        mx = wave_max(mx);
-        __syncthreads();
-        if ((tid & 63) == 0) fred[tid >> 6] = mx;
-        __syncthreads();
-        if (tid == 0)
-            atomicMax(e.max_acc + (long)bz * 2, __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
-    }
-    // last block of this batch item finalises (same ordering argument as in the B pass)
-    __syncthreads();
-    if (tid == 0) {
-        unsigned t = atomicAdd(e.ticket + bz, 1u);
-        is_last = (t == gridDim.x - 1);
-        if (is_last) atomicExch(e.ticket + bz, 0u);
-    }
-    __syncthreads();
-    if (!is_last) return;
-
-    const int Kp = e.Kp;
-    uint32_t *sum = e.a_sum + (long)bz * K;
-    uint8_t *stripe = e.stripe + (long)bz * NTERM * Kp * ES;
-    float amax = 0.f;
-    for (int k = tid; k < K; k += 256) {
-        const uint32_t w = as_word(take_copies<acc_t>(e.a_acc + (long)bz * K, e.acc_stride, k));
-        sum[k] = w;
-        if (!T::IS_INT) amax = fmaxf(amax, fabsf(__uint_as_float(w)));
-    }
-    {
-        // scalar a . b, straight from the two sums (b is still staged in LDS)
-        acc_t v = T::zero();
-        for (int k = tid; k < K; k += 256) v = add_t(v, mul_t(from_word<acc_t>(sum[k]), bl[k]));
-        v = wave_sum(v);
-        __syncthreads();
-        if ((tid & 63) == 0) fred[tid >> 6] = __uint_as_float(as_word(v));
-        __syncthreads();
-        if (tid == 0) {
-            acc_t t = add_t(add_t(from_word<acc_t>(__float_as_uint(fred[0])), from_word<acc_t>(__float_as_uint(fred[1]))),
-                            add_t(from_word<acc_t>(__float_as_uint(fred[2])), from_word<acc_t>(__float_as_uint(fred[3]))));
-            e.s_pred[bz] = as_word(t);
-        }
-        __syncthreads();
-    }
-    float scale = 1.f, inv = 1.f;
-    if (DT == DT_F16) {
-        // power-of-two pre-scale so the largest |sum| sits in [2^13, 2^14): well inside fp16 range
-        amax = wave_max(amax);
-        __syncthreads();
-        if ((tid & 63) == 0) fred[tid >> 6] = amax;
-        __syncthreads();
-        amax = fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]));
-        int sh = 0;
-        if (amax > 0.f && amax <= 3.0e38f) {
-            int ex;
-            frexpf(amax, &ex);
-            sh = 14 - ex;
-            sh = sh > 100 ? 100 : (sh < -100 ? -100 : sh);
-        }
-        scale = ldexpf(1.f, sh);
-        inv = ldexpf(1.f, -sh);
-    }
-    for (int k = tid; k < Kp; k += 256) {
-        if (DT == DT_I8) {
-            int8_t d[NTERM] = {0, 0, 0, 0};
-            if (k < K) split_digits((int)sum[k], d);
-#pragma unroll
-            for (int t = 0; t < NTERM; ++t) ((int8_t *)stripe)[(long)t * Kp + k] = d[t];
-        } else {
-            uint16_t h[NTERM] = {0, 0, 0, 0};
-            if (k < K) {
-                float v = __uint_as_float(sum[k]);
-                if (DT == DT_BF16) {
-                    // three bf16 terms carry the 24 significant bits of the fp32 sum
-                    uint32_t t0 = f32_to_bf16_bits(v);
-                    float r1 = v - bf16_bits_to_f32(t0);
-                    uint32_t t1 = f32_to_bf16_bits(r1);
-                    float r2 = r1 - bf16_bits_to_f32(t1);
-                    uint32_t t2 = f32_to_bf16_bits(r2);
-                    h[0] = (uint16_t)t0; h[1] = (uint16_t)t1; h[2] = (uint16_t)t2;
-                } else {
-                    // fp16 terms: each remainder is rescaled by 2^11 to stay in the normal range
-                    float x = v * scale;
-                    uint32_t t0 = f32_to_f16_bits(x);
-                    float r1 = (x - f16_bits_to_f32(t0)) * 2048.f;
-                    uint32_t t1 = f32_to_f16_bits(r1);
-                    float r2 = (r1 - f16_bits_to_f32(t1)) * 2048.f;
-                    uint32_t t2 = f32_to_f16_bits(r2);
-                    h[0] = (uint16_t)t0; h[1] = (uint16_t)t1; h[2] = (uint16_t)t2;
-                }
-            }
-#pragma unroll
-            for (int t = 0; t < NTERM; ++t) ((uint16_t *)stripe)[(long)t * Kp + k] = h[t];
-        }
-    }
-    if (!T::IS_INT && tid == 0) {
-        float *w = e.w_a + (long)bz * NTERM;
-        if (DT == DT_BF16) { w[0] = 1.f; w[1] = 1.f; w[2] = 1.f; w[3] = 0.f; }
-        else { w[0] = inv; w[1] = inv * (1.f / 2048.f); w[2] = inv * (1.f / 4194304.f); w[3] = 0.f; }
-        const float ma = __uint_as_float(atomicExch(e.max_acc + (long)bz * 2, 0u));
-        e.maxabs[(long)bz * 2] = ma;
-        const float mb = e.maxabs[(long)bz * 2 + 1];
-        e.tau[bz] = e.tau_override > 0.f ? e.tau_override : (1e-3f * (float)K) * ma * mb;
-    }
-}
 
 struct EncPlan { int cw_log2, nwin, rpb, nrb; };
 
@@ -437,7 +209,8 @@ static EncPlan plan_window(int rows, int cols, int chunk_elems)
     return p;
 }
 
-hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspace &w, hipStream_t st)
+hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspace &w, uint32_t *zero_ptr,
+                           size_t zero_words, hipStream_t st)
 {
     EncBArgs e;
     e.X = (const uint8_t *)B; e.ld = s.ldb; e.stride = s.sB; e.K = s.K;
@@ -447,6 +220,7 @@ hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspac
     e.cw_log2 = p.cw_log2; e.nwin = p.nwin; e.rpb = p.rpb; e.nrb = p.nrb;
     e.acc = w.b_acc; e.acc_stride = w.acc_stride; e.sum = w.b_sum;
     e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.ticket = w.enc_ticket;
+    e.zero_ptr = zero_ptr; e.zero_words = zero_ptr ? zero_words : 0;
     dim3 grid((unsigned)(e.nwin * e.nrb), 1, (unsigned)s.batch);
     switch (dt) {
     case DT_I8:   hipLaunchKernelGGL(encode_b_kernel<DT_I8>, grid, dim3(256), 0, st, e); break;
@@ -457,69 +231,14 @@ hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspac
     return hipGetLastError();
 }
 
-// Largest K the A pass handles (8 windows of 64 chunks of 16 bytes, 4 windows for int8).
-int encode_a_max_k(int dt) { return dt == DT_I8 ? 4 * 64 * 16 : 8 * 64 * 8; }
-
-template <int DT>
-static hipError_t launch_encode_a_t(EncAArgs &e, int batch, hipStream_t st)
-{
-    constexpr int CE = 16 / Traits<DT>::ES;
-    const int CW = 1 << e.cw_log2;
-    const size_t smem = ((size_t)e.nwin * CW * CE + 256 * CE) * 4;
-    dim3 grid((unsigned)e.nrb, 1, (unsigned)batch);
-    if (e.nwin <= 1)      hipLaunchKernelGGL((encode_a_kernel<DT, 1>), grid, dim3(256), smem, st, e);
-    else if (e.nwin <= 2) hipLaunchKernelGGL((encode_a_kernel<DT, 2>), grid, dim3(256), smem, st, e);
-    else if (e.nwin <= 4) hipLaunchKernelGGL((encode_a_kernel<DT, 4>), grid, dim3(256), smem, st, e);
-    else if (DT != DT_I8 && e.nwin <= 8) hipLaunchKernelGGL((encode_a_kernel<DT, (DT == DT_I8 ? 4 : 8)>), grid, dim3(256), smem, st, e);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
-}
-
-hipError_t launch_encode_a(int dt, const void *A, const Shape &s, const Workspace &w, float tau_override,
-                           uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
-{
-    EncAArgs e;
-    const int ce = 16 / elem_size(dt);
-    const int chunks = (s.K + ce - 1) / ce;
-    const int nw_max = dt == DT_I8 ? 4 : 8;
-    // window width: least padding among (CW, nwin) with nwin <= nw_max, then widest
-    int best_lg = -1;
-    long best_waste = -1;
-    for (int lg = 3; lg <= 6; ++lg) {
-        const int CW = 1 << lg, nwin = (chunks + CW - 1) / CW;
-        if (nwin > nw_max) continue;
-        const long waste = (long)nwin * CW - chunks;
-        if (best_waste < 0 || waste <= best_waste) { best_waste = waste; best_lg = lg; }
-    }
-    if (best_lg < 0) return hipErrorInvalidValue;
-    e.cw_log2 = best_lg;
-    const int CW = 1 << best_lg, RL = 256 / CW;
-    e.nwin = (chunks + CW - 1) / CW;
-    int nwt = 1;
-    while (nwt < e.nwin) nwt *= 2;
-    const int UR = nwt >= 8 ? 1 : 8 / nwt;
-    int rpb = RL * UR;
-    while ((s.M + rpb - 1) / rpb > 512) rpb *= 2;
-    e.rpb = rpb;
-    e.nrb = (s.M + rpb - 1) / rpb;
-    e.A = (const uint8_t *)A; e.lda = s.lda; e.sA = s.sA; e.M = s.M; e.K = s.K; e.Kp = s.Kp;
-    e.a_acc = w.a_acc; e.acc_stride = w.acc_stride; e.a_sum = w.a_sum; e.b_sum = w.b_sum;
-    e.rc_pred = w.rc_pred; e.stripe = w.stripe_a; e.w_a = w.w_a;
-    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.tau = w.tau; e.ticket = w.enc_ticket;
-    e.tau_override = tau_override; e.zero_ptr = zero_ptr; e.zero_words = zero_words;
-    e.s_pred = w.s_pred;
-    switch (dt) {
-    case DT_I8:   return launch_encode_a_t<DT_I8>(e, s.batch, st);
-    case DT_BF16: return launch_encode_a_t<DT_BF16>(e, s.batch, st);
-    case DT_F16:  return launch_encode_a_t<DT_F16>(e, s.batch, st);
-    }
-    return hipErrorInvalidValue;
-}
+// Largest K of a protected GEMM: the column sums of A's slabs wait in LDS (4 bytes per column
+// of K) next to the operand buffers until the epilogue.
+int protect_max_k(int dt) { (void)dt; return 4096; }
 
 // ===================================================================== compare
 // Flags from observed sums against the predictions the last abft_gemm left in the context
 // (Sec. III-B.1 item (2): equality for fixed point, tolerance for floating point).  Used by
-// abft_verify; abft_gemm does the same comparison in the tail of the GEMM kernel.
+// abft_verify and abft_correct; abft_gemm compares in its finish kernel.
 struct CmpArgs {
     const uint32_t *cc_pred, *rc_pred;
     const uint32_t *cc_obs, *rc_obs;
@@ -606,6 +325,205 @@ hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verd
     dim3 grid((unsigned)((s.M + s.N + 255) / 256), 1, (unsigned)s.batch);
     if (dt == DT_I8) hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, a);
     else             hipLaunchKernelGGL(compare_kernel<false>, grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ====================================================================== finish
+// Runs after the protected GEMM, when its atomics have completed a = e^T A, rc_pred = A b,
+// max|A| and the observed sums.  Column blocks form the column checksum prediction
+// cc_pred = a B (Sec. III-B.1: the product of the input-side checksum with the weight), a
+// matrix-vector product bound by one read of B, and compare it with cc_obs; row blocks compare
+// rc_pred with rc_obs; the last block to finish writes the counts and the status.
+struct FinArgs {
+    const uint8_t *B;
+    long ldb, sB;
+    int transB;
+    int M, N, K;
+    const uint32_t *a_sum, *b_sum, *rc_pred, *cc_obs, *rc_obs, *a_max;
+    uint32_t *cc_pred, *s_pred;
+    float *maxabs, *tau;
+    float tau_override;
+    uint8_t *row_flag, *col_flag;
+    uint32_t *counts;
+    uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
+    int col_blocks;       // blocks [0, col_blocks) take columns, the rest rows
+};
+
+constexpr int FIN_ROWS_B = 16;     // rows of a B stored N x K per column block (4 per wave)
+constexpr int FIN_KY = 8;          // k lanes of a column block over a B stored K x N
+
+template <int DT>
+__global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    __shared__ acc_t wred[4];
+    __shared__ int is_last;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bz = blockIdx.z;
+    const int M = f.M, N = f.N, K = f.K;
+
+    float tol = 0.f;
+    if (!T::IS_INT) {
+        const float ma = __uint_as_float(f.a_max[bz]), mb = f.maxabs[(long)bz * 2 + 1];
+        tol = f.tau_override > 0.f ? f.tau_override : (1e-3f * (float)K) * ma * mb;
+        if (blockIdx.x == 0 && tid == 0) {
+            f.maxabs[(long)bz * 2] = ma;
+            f.tau[bz] = tol;
+        }
+    }
+
+    bool frow = false, fcol = false, fcol2 = false;
+    if ((int)blockIdx.x < f.col_blocks) {
+        // ---- a staged in LDS, zero beyond K up to a whole chunk
+        acc_t *al = reinterpret_cast<acc_t *>(lds);
+        const int Kc = (K + CE - 1) / CE * CE;
+        for (int k = tid; k < Kc; k += 256) al[k] = k < K ? from_word<acc_t>(f.a_sum[(long)bz * K + k]) : T::zero();
+        __syncthreads();
+        const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
+        if (blockIdx.x == 0) {
+            // scalar a . b (the single-number check value of Sec. III-B.1)
+            acc_t v = T::zero();
+            for (int k = tid; k < K; k += 256) v = add_t(v, mul_t(al[k], from_word<acc_t>(f.b_sum[(long)bz * K + k])));
+            v = wave_sum(v);
+            if (lane == 0) wred[wave] = v;
+            __syncthreads();
+            if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
+        }
+        if (f.transB) {
+            // B stored N x K: a wave takes four rows of B at a time, lanes run along K
+            const int nch = Kc / CE;
+            const int nb = blockIdx.x * FIN_ROWS_B + wave * 4;
+            acc_t dot[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
+            for (int ch = lane; ch < nch; ch += 64) {
+                i32x4 v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    v[j] = i32x4{0, 0, 0, 0};
+                    if (nb + j < N) v[j] = *reinterpret_cast<const i32x4 *>(Bb + ((long)(nb + j) * f.ldb + ch * CE) * ES);
+                }
+                const int left = K - ch * CE;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    i32x4 w = v[j];
+                    if (left < CE) w = mask_chunk(w, left * ES);
+#pragma unroll
+                    for (int q = 0; q < CE; ++q) dot[j] = add_t(dot[j], mul_t(T::elem(w, q), al[ch * CE + q]));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const acc_t t = wave_sum(dot[j]);
+                if (lane == j && nb + j < N) {
+                    const long o = (long)bz * N + nb + j;
+                    f.cc_pred[o] = as_word(t);
+                    fcol = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                    f.col_flag[o] = fcol ? 1 : 0;
+                }
+            }
+        } else {
+            // B stored K x N: 32 chunk columns per block, FIN_KY lanes run along K
+            acc_t *red = al + Kc;                                   // [FIN_KY][32 * CE]
+            const int cx = tid & 31, ky = tid >> 5;
+            const int nst = (blockIdx.x * 32 + cx) * CE;
+            const int left = N - nst;
+            acc_t colp[CE];
+#pragma unroll
+            for (int q = 0; q < CE; ++q) colp[q] = T::zero();
+            for (int k0 = ky; k0 < K; k0 += 4 * FIN_KY) {
+                i32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = k0 + u * FIN_KY;
+                    v[u] = i32x4{0, 0, 0, 0};
+                    if (k < K && left > 0) v[u] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * f.ldb + nst) * ES);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int k = k0 + u * FIN_KY;
+                    if (k < K) {
+                        const acc_t ak = al[k];
+#pragma unroll
+                        for (int q = 0; q < CE; ++q) colp[q] = add_t(colp[q], mul_t(T::elem(v[u], q), ak));
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < CE; ++q) red[ky * 32 * CE + cx * CE + q] = colp[q];
+            __syncthreads();
+            // at most two columns per thread (int8: 512 columns per block)
+            for (int c = tid; c < 32 * CE; c += 256) {
+                const int n = blockIdx.x * 32 * CE + c;
+                if (n < N) {
+                    acc_t t = red[c];
+#pragma unroll
+                    for (int y = 1; y < FIN_KY; ++y) t = add_t(t, red[y * 32 * CE + c]);
+                    const long o = (long)bz * N + n;
+                    f.cc_pred[o] = as_word(t);
+                    const bool fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                    f.col_flag[o] = fl ? 1 : 0;
+                    if (c < 256) fcol = fl;
+                    else fcol2 = fl;
+                }
+            }
+        }
+    } else {
+        const int r = ((int)blockIdx.x - f.col_blocks) * 256 + tid;
+        if (r < M) {
+            const long o = (long)bz * M + r;
+            frow = mismatch<T::IS_INT>(f.rc_obs[o], f.rc_pred[o], tol);
+            f.row_flag[o] = frow ? 1 : 0;
+        }
+    }
+    const unsigned nr = __syncthreads_count(frow);
+    const unsigned nc = __syncthreads_count(fcol) + __syncthreads_count(fcol2);
+    if (tid == 0) {
+        if (nr) atomicAdd(f.ticket + 1, nr);
+        if (nc) atomicAdd(f.ticket + 2, nc);
+    }
+    // the counts of this block are at the coherence point before its ticket is (atomics only,
+    // ordered by the barrier's wait for outstanding memory operations)
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned total = gridDim.x * gridDim.z;
+        const unsigned t = atomicAdd(f.ticket, 1u);
+        is_last = (t == total - 1);
+    }
+    __syncthreads();
+    if (is_last && tid == 0) {
+        const uint32_t r = atomicExch(f.ticket + 1, 0u), c = atomicExch(f.ticket + 2, 0u);
+        atomicExch(f.ticket, 0u);
+        f.counts[0] = r;
+        f.counts[1] = c;
+        f.counts[2] = status_of(r, c);
+        f.counts[3] = 0u;
+        f.counts[4] = status_of(r, c);
+    }
+}
+
+hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
+                         hipStream_t st)
+{
+    FinArgs f;
+    f.B = (const uint8_t *)B; f.ldb = s.ldb; f.sB = s.sB; f.transB = s.transB;
+    f.M = s.M; f.N = s.N; f.K = s.K;
+    f.a_sum = w.a_sum; f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;
+    f.a_max = w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
+    f.tau_override = v.tau_override;
+    f.row_flag = v.row_flag; f.col_flag = v.col_flag; f.counts = v.counts; f.ticket = w.cmp_ticket;
+    const int ce = 16 / elem_size(dt);
+    f.col_blocks = s.transB ? (s.N + FIN_ROWS_B - 1) / FIN_ROWS_B : (s.N + 32 * ce - 1) / (32 * ce);
+    const int row_blocks = (s.M + 255) / 256;
+    const int kc = (s.K + ce - 1) / ce * ce;
+    const size_t smem = ((size_t)kc + (s.transB ? 0 : (size_t)FIN_KY * 32 * ce)) * 4;
+    dim3 grid((unsigned)(f.col_blocks + row_blocks), 1, (unsigned)s.batch);
+    switch (dt) {
+    case DT_I8:   hipLaunchKernelGGL(finish_kernel<DT_I8>, grid, dim3(256), smem, st, f); break;
+    case DT_BF16: hipLaunchKernelGGL(finish_kernel<DT_BF16>, grid, dim3(256), smem, st, f); break;
+    case DT_F16:  hipLaunchKernelGGL(finish_kernel<DT_F16>, grid, dim3(256), smem, st, f); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -1,0 +1,94 @@
+// Input-side checksums of A taken from the operand slabs the GEMM already holds in LDS.
+//
+// The checksum scheme (Sec. III-B.1 "Checksums") needs two reductions of A: the column sums
+// a = e^T A (which give the column checksum prediction (e^T A) B) and the matrix-vector product
+// A (B e) (the row checksum prediction).  Both read every element of A exactly once, and every
+// element of A passes through LDS on its way to the matrix cores anyway: of the workgroups that
+// share a tile row, the one in tile column (s mod tiles_n) reduces slab s while it is resident.
+// So A is read from memory once, by the GEMM, and the separate encode pass over A disappears.
+//
+// LDS slab layout (both GEMM kernels): row r is 128 bytes = eight 16-byte chunks, chunk c stored
+// in slot c ^ (r & 7).  Thread t reduces chunk c = t & 7 of rows (t >> 3) + 32 p.
+#pragma once
+#include "abft_device.h"
+#include "gemm_args.h"
+
+namespace abft {
+
+// Sum over each aligned group of 8 lanes; every lane of the group ends with the total.
+template <typename T> __device__ __forceinline__ T row8_sum(T v)
+{
+    v = add_t(v, dpp_get<0xB1>(v));    // lane ^ 1
+    v = add_t(v, dpp_get<0x4E>(v));    // lane ^ 2
+    v = add_t(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
+    return v;
+}
+
+// Per-thread state of the A pass that lives across the slabs of one tile.
+template <int DT> struct APassState {
+    typename Traits<DT>::acc_t rdot;   // dot of row (t >> 3) + 32 (t & 7) with b, over the owned slabs
+    float amax;                        // max |A| seen (floating point only)
+};
+
+// Words of LDS the pass needs for a tile: column sums of the owned slabs, then BM row values.
+__host__ __device__ inline int apass_owned_slabs(int nslab, int tiles_n) { return (nslab + tiles_n - 1) / tiles_n; }
+__host__ __device__ inline size_t apass_lds_bytes(int dt, int bm, int nslab, int tiles_n)
+{
+    return ((size_t)apass_owned_slabs(nslab, tiles_n) * (SLAB_BYTES / elem_size(dt)) + bm) * 4;
+}
+
+// Reduce one resident slab of A.  sA: the slab in LDS (BM rows).  bk: b + first column of the
+// slab (global), kvalid: columns of the slab inside K, rows_valid: rows of the tile inside M
+// (rows beyond may hold anything finite or not: they are ignored).  col_lds: KE words of this
+// slab's column sums (LDS atomics: the four waves add to the same words).
+template <int DT, int BM>
+__device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *bk, int kvalid, int rows_valid,
+                                       uint32_t *col_lds, APassState<DT> &st, bool mul24_ok)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int CE = 16 / T::ES;
+    constexpr int P = BM / 32;
+    const int tid = threadIdx.x;
+    const int c = tid & 7, rg = tid >> 3;
+    const uint8_t *src = sA + rg * SLAB_BYTES + ((c ^ (rg & 7)) * 16);
+
+    acc_t bv[CE], cs[CE];
+#pragma unroll
+    for (int q = 0; q < CE; ++q) {
+        bv[q] = (c * CE + q < kvalid) ? from_word<acc_t>(bk[c * CE + q]) : T::zero();
+        cs[q] = T::zero();
+    }
+    i32x4 v[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) v[p] = *reinterpret_cast<const i32x4 *>(src + p * 32 * SLAB_BYTES);
+    acc_t mine = T::zero();
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        i32x4 x4 = v[p];
+        if (rg + 32 * p >= rows_valid) x4 = i32x4{0, 0, 0, 0};
+        acc_t dot = T::zero();
+#pragma unroll
+        for (int q = 0; q < CE; ++q) {
+            const acc_t x = T::elem(x4, q);
+            cs[q] = add_t(cs[q], x);
+            if constexpr (T::IS_INT) {
+                dot = mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot)
+                               : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot);
+            } else {
+                dot = __builtin_fmaf((float)x, (float)bv[q], (float)dot);
+                st.amax = fmaxf(st.amax, fabsf((float)x));
+            }
+        }
+        dot = row8_sum(dot);
+        if (c == p) mine = dot;
+    }
+    st.rdot = add_t(st.rdot, mine);
+#pragma unroll
+    for (int q = 0; q < CE; ++q) {
+        if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(col_lds) + c * CE + q, (int)cs[q]);
+        else atomicAdd(reinterpret_cast<float *>(col_lds) + c * CE + q, (float)cs[q]);
+    }
+}
+
+}  // namespace abft

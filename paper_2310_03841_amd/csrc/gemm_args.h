@@ -7,22 +7,18 @@ namespace abft {
 struct GemmArgs {
     const uint8_t *A, *B;
     uint8_t *C;
-    const uint8_t *SA;                            // A-side stripe [batch][NTERM][Kp] operand elements
-    uint32_t *cc_part;                            // raw stripe outputs: terms of (e^T A) B, [batch][NTERM][N]
-    uint32_t *cc_obs, *rc_obs;                    // observed sums (atomics)
-    int M, N, K, Kp;
+    int M, N, K;
     long lda, ldb, ldc, sA, sB, sC;               // elements
     int tiles_m, tiles_n;
     int n_big, tiles_m_big, tiles_m_small;        // fast path: 256-row tiles first, then 128-row tiles
     int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
-    // compare fused into the tail of the GEMM (fuse_compare != 0)
-    int fuse_compare;
-    const uint32_t *rc_pred;                      // [batch][M] from the A pass
-    uint32_t *cc_pred;                            // [batch][N] recombined here
-    const float *w_a, *tau;
-    uint8_t *row_flag, *col_flag;
-    uint32_t *counts;
-    uint32_t *row_ticket, *col_ticket, *fin;      // zeroed before the launch; fin[3]: ticket, rows, cols
+    // protected launches: all of these are accumulated with atomics and start at zero
+    uint32_t *cc_obs, *rc_obs;                    // observed sums of C        [batch][N], [batch][M]
+    uint32_t *rc_pred;                            // A (B e)                    [batch][M]
+    uint32_t *a_sum;                              // e^T A                      [batch][K]
+    uint32_t *a_max;                              // max|A| as float bits       [batch]
+    const uint32_t *b_sum;                        // B e, complete before the launch [batch][K]
+    int mul24_ok;                                 // int8: |b| < 2^23, 24-bit multiplies are exact
 };
 
 // Fast path (gemm_fast.hip): B stored N x K, K a whole number of 128-byte slabs.

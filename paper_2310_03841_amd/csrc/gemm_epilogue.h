@@ -1,7 +1,7 @@
-// Epilogue shared by the GEMM kernels: store C, emit the stripe outputs, take the observed
-// row / column sums of the M x N block from the accumulators (before rounding) and add them
-// to cc_obs / rc_obs.  Paper: output checksum fused with the GEMM epilogue (Sec. IV-C memory
-// paragraph, Sec. V "Optimizations" (2)).
+// Epilogue shared by the GEMM kernels: store C, take the observed row / column sums of the
+// M x N block from the accumulators (before rounding) and add them to cc_obs / rc_obs, and
+// hand over what the pass over A's slabs collected (gemm_apass.h).  Paper: output checksum
+// fused with the GEMM epilogue (Sec. IV-C memory paragraph, Sec. V "Optimizations" (2)).
 //
 // The kernels issue their MFMAs with the B fragment as first operand, so one 32x32 block of
 // accumulators is laid out "row per lane": lane l holds row (l & 31) of the block and, in
@@ -16,6 +16,12 @@
 // Every loop over accumulator registers is expanded at compile time (static_for): the
 // accumulators must be addressed with constant indices to stay in registers.
 //
+// Two paths per group of 32 rows of a wave tile.  The common one (every row and column of the
+// group inside C, no flip armed) works from registers as described.  The other one (edges of
+// the problem, armed flip) stages the raw 32-bit accumulators in LDS and walks them with an
+// ordinary loop, so that it costs little code: straight-line code that is rarely executed still
+// has to be fetched past.
+//
 // LDS use: each wave owns EPI_WAVE_BYTES at smem + wave * EPI_WAVE_BYTES, then the block-wide
 // partial-sum arrays follow.  The caller must have passed a barrier after its last LDS read.
 #pragma once
@@ -23,6 +29,7 @@
 
 #include "abft_device.h"
 #include "gemm_args.h"
+#include "gemm_apass.h"
 
 namespace abft {
 
@@ -38,14 +45,7 @@ template <int I, int N, typename F> __device__ __forceinline__ void static_for(F
 __host__ __device__ constexpr int epi_wave_bytes(int TN) { return 32 * (TN * 4 + 16); }
 __host__ __device__ constexpr int epi_total_bytes(int BM, int BN)
 {
-    return 4 * epi_wave_bytes(BN / 2) + (2 * BM + 2 * BN) * 4 + 16;
-}
-
-template <bool IS_INT> __device__ __forceinline__ bool epi_mismatch(uint32_t obs, uint32_t pred, float tol)
-{
-    if (IS_INT) return obs != pred;                          // equality in Z/2^32
-    const float d = fabsf(__uint_as_float(obs) - __uint_as_float(pred));
-    return !(d <= tol);                                      // NaN and Inf always flag
+    return 4 * epi_wave_bytes(BN / 2) + (3 * BM + 2 * BN) * 4 + 16;
 }
 
 // Read one accumulator element where it lives (an AGPR) at the point of use.  Without this the
@@ -82,16 +82,26 @@ template <> __device__ __forceinline__ uint32_t pack2<DT_F16>(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
 }
 
+// What a protected tile hands to the epilogue besides its accumulators.
+template <int DT> struct EpiProt {
+    APassState<DT> st;        // row dots and max|A| of the owned slabs
+    const uint32_t *col_lds;  // column sums of the owned slabs, KE words each (LDS)
+    int owned;                // number of owned slabs: slab j is slab tn + j * tiles_n of K
+    int tn, tiles_n;
+};
+
 template <int DT, int BM, int BN, bool PROT>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                                               typename Traits<DT>::accv_t (&acc)[BM / 64][BN / 64],
-                                              uint8_t *smem, int m0, int n0, int bz, int tile_row_id)
+                                              uint8_t *smem, int m0, int n0, int bz, const EpiProt<DT> &ep)
 {
     using T = Traits<DT>;
     typedef typename T::acc_t acc_t;
     constexpr int TM = BM / 2, TN = BN / 2;
     constexpr int MI = TM / 32, NI = TN / 32;
     constexpr int OS = T::OS;
+    constexpr int KE = SLAB_BYTES / T::ES;
+    constexpr int CPL = TN / 64;                    // columns per lane when a wave walks a row
     constexpr int WAVE_BYTES = epi_wave_bytes(TN);
     constexpr int CROW = TN * OS + 16;              // staged C row (bytes), padded
     constexpr int SROW = TN * 4 + 16;               // staged 32-bit row (bytes), padded
@@ -100,274 +110,187 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const int M = g.M, N = g.N;
-    const int Mx = PROT ? M + NTERM : M;             // rows M .. Mx-1 are the A-side stripe
 
     uint8_t *wbuf = smem + wave * WAVE_BYTES;                              // wave-private staging
     acc_t *rs_part = reinterpret_cast<acc_t *>(smem + 4 * WAVE_BYTES);     // [2][BM] by wave column
     acc_t *cs_part = rs_part + 2 * BM;                                     // [2][BN] by wave row
+    acc_t *rp = cs_part + 2 * BN;                                          // [BM] row dots of the A pass
+    float *amax4 = reinterpret_cast<float *>(rp + BM);                     // [4]
     uint8_t *Cb = g.C + (long)bz * g.sC * OS;
     const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
                           g.inj_col >= n0 && g.inj_col < n0 + BN;
     const int wr0 = m0 + wm * TM, wc0 = n0 + wn * TN;                      // first row / column of the wave tile
-    // staged path: every column of the wave tile is a column of C; rows may run past M
-    const bool staged = (wc0 + TN <= N) && !inj_here;
+    const bool cols_full = (wc0 + TN <= N) && !inj_here;
 
-    auto wave_sync = [&]() {
+    auto wave_sync = [&]() __attribute__((always_inline)) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
+    // column partials: of the groups that went the register way (block column ni, register i:
+    // this lane's rows) and of the groups that were walked row by row (columns CPL*lane ..)
+    acc_t cp[PROT ? NI : 1][16];
+    acc_t colacc[CPL];
+    if (PROT) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) cp[ni][i] = T::zero();
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) colacc[j] = T::zero();
+    }
+
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
         const int br = wr0 + mi * 32;                                      // first row of this 32-row group
-        const int gr = br + l32;                                           // this lane's row
-        acc_t rowsum = T::zero();
-        if (staged) {
-            const int rows_in = M - br < 0 ? 0 : (M - br > 32 ? 32 : M - br);   // rows of C in the group
-            if (rows_in > 0) {
-                // ---- stage 32 rows of converted C in LDS, four columns per write
-                static_for<0, NI>([&](auto ni_c) {
-                    constexpr int ni = decltype(ni_c)::value;
-                    static_for<0, 4>([&](auto q_c) {
-                        constexpr int q = decltype(q_c)::value;
-                        const acc_t v0 = acc_read(acc[mi][ni][4 * q]), v1 = acc_read(acc[mi][ni][4 * q + 1]),
-                                    v2 = acc_read(acc[mi][ni][4 * q + 2]), v3 = acc_read(acc[mi][ni][4 * q + 3]);
-                        if (PROT) rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
-                        uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
-                        if constexpr (DT == DT_I8) {
-                            *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
-                        } else {
-                            uint2 w;
-                            w.x = pack2<DT>((float)v0, (float)v1);
-                            w.y = pack2<DT>((float)v2, (float)v3);
-                            *reinterpret_cast<uint2 *>(d) = w;
-                        }
-                    });
-                    // keep the scheduler from hoisting every accumulator read to the top: that
-                    // would need hundreds of live registers and spill
-                    __builtin_amdgcn_sched_barrier(0);
-                });
-                wave_sync();
-                // ---- read rows back, 16 bytes per lane, and store whole row segments
-                constexpr int LPR = TN * OS / 16;                          // lanes per row
-                constexpr int RPI = 64 / LPR;                              // rows per instruction
-                // (all LDS reads first, then the stores: one LDS latency instead of one per row)
-                constexpr int NIT = 32 / RPI;
-                const int r0 = lane / LPR, cch = lane % LPR;
-                i32x4 rowv[NIT];
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-                    rowv[it] = *reinterpret_cast<const i32x4 *>(wbuf + (it * RPI + r0) * CROW + cch * 16);
-                uint8_t *crow = Cb + ((long)(br + r0) * g.ldc + wc0) * OS + cch * 16;
-                const long cstep = (long)RPI * g.ldc * OS;
-#pragma unroll
-                for (int it = 0; it < NIT; ++it)
-                    if (it * RPI + r0 < rows_in) *reinterpret_cast<i32x4 *>(crow + it * cstep) = rowv[it];
-                wave_sync();
-            }
-            if (PROT && br < Mx && br + 32 > M) {
-                // ---- the group holds rows of the A-side stripe: their accumulators are the
-                // terms of (e^T A) B.  Stage the group as 32-bit words, emit those rows.
-                static_for<0, NI>([&](auto ni_c) {
-                    constexpr int ni = decltype(ni_c)::value;
-                    static_for<0, 4>([&](auto q_c) {
-                        constexpr int q = decltype(q_c)::value;
-                        uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
-                        *reinterpret_cast<i32x4 *>(d) =
-                            i32x4{(int)as_word(acc_read(acc[mi][ni][4 * q])), (int)as_word(acc_read(acc[mi][ni][4 * q + 1])),
-                                  (int)as_word(acc_read(acc[mi][ni][4 * q + 2])), (int)as_word(acc_read(acc[mi][ni][4 * q + 3]))};
-                    });
-                });
-                wave_sync();
-#pragma unroll
-                for (int t = 0; t < NTERM; ++t) {
-                    const int r = M + t - br;
-                    if (r >= 0 && r < 32) {
-                        for (int c0 = 2 * lane; c0 < TN; c0 += 128) {
-                            const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + c0 * 4);
-                            uint32_t *dst = g.cc_part + ((long)bz * NTERM + t) * N + wc0 + c0;
-                            publish_word(dst, w.x);          // read by the workgroup that compares this column
-                            publish_word(dst + 1, w.y);
-                        }
-                    }
-                }
-                wave_sync();
-            }
-        } else if (br < Mx && wc0 < N) {
-            // ---- ragged columns or armed flip: element by element
+        if (cols_full && br + 32 <= M) {
+            // ---- register path: one read of every accumulator serves the sums and the store
+            acc_t rowsum = T::zero();
             static_for<0, NI>([&](auto ni_c) {
                 constexpr int ni = decltype(ni_c)::value;
-                static_for<0, 16>([&](auto i_c) {
-                    constexpr int i = decltype(i_c)::value;
-                    const int gc = wc0 + ni * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-                    acc_t v = acc_read(acc[mi][ni][i]);
-                    if (inj_here && gr == g.inj_row && gc == g.inj_col)
-                        v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
-                    if (gc < N) {
-                        if (gr < M) {
-                            T::store_c(Cb, (long)gr * g.ldc + gc, v);
-                            if (PROT) rowsum = add_t(rowsum, v);
-                        } else if (PROT && gr < Mx) {
-                            publish_word(g.cc_part + ((long)bz * NTERM + (gr - M)) * N + gc, as_word(v));
-                        }
+                static_for<0, 4>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    const acc_t v0 = acc_read(acc[mi][ni][4 * q]), v1 = acc_read(acc[mi][ni][4 * q + 1]),
+                                v2 = acc_read(acc[mi][ni][4 * q + 2]), v3 = acc_read(acc[mi][ni][4 * q + 3]);
+                    if (PROT) {
+                        cp[PROT ? ni : 0][4 * q] = add_t(cp[PROT ? ni : 0][4 * q], v0);
+                        cp[PROT ? ni : 0][4 * q + 1] = add_t(cp[PROT ? ni : 0][4 * q + 1], v1);
+                        cp[PROT ? ni : 0][4 * q + 2] = add_t(cp[PROT ? ni : 0][4 * q + 2], v2);
+                        cp[PROT ? ni : 0][4 * q + 3] = add_t(cp[PROT ? ni : 0][4 * q + 3], v3);
+                        rowsum = add_t(rowsum, add_t(add_t(v0, v1), add_t(v2, v3)));
+                    }
+                    uint8_t *d = wbuf + l32 * CROW + (ni * 32 + 8 * q + 4 * lh) * OS;
+                    if constexpr (DT == DT_I8) {
+                        *reinterpret_cast<i32x4 *>(d) = i32x4{(int)v0, (int)v1, (int)v2, (int)v3};
+                    } else {
+                        uint2 w;
+                        w.x = pack2<DT>((float)v0, (float)v1);
+                        w.y = pack2<DT>((float)v2, (float)v3);
+                        *reinterpret_cast<uint2 *>(d) = w;
                     }
                 });
+                __builtin_amdgcn_sched_barrier(0);      // keeps the accumulator reads from all moving to the top
             });
-        }
-        if (PROT) {
-            // row sums: the two half-waves hold different columns of the same rows
-            const acc_t t = add_t(rowsum, __shfl_xor(rowsum, 32));
-            if (lh == 0) rs_part[wn * BM + wm * TM + mi * 32 + l32] = t;
+            if (PROT) {
+                const acc_t t = add_t(rowsum, __shfl_xor(rowsum, 32));     // the half-waves hold different columns
+                if (lh == 0) rs_part[wn * BM + wm * TM + mi * 32 + l32] = t;
+            }
+            wave_sync();
+            // read rows back, 16 bytes per lane, and store whole row segments
+            constexpr int LPR = TN * OS / 16;                              // lanes per row
+            constexpr int RPI = 64 / LPR;                                  // rows per instruction
+            constexpr int NIT = 32 / RPI;
+            const int r0 = lane / LPR, cch = lane % LPR;
+            i32x4 rowv[NIT];
+#pragma unroll
+            for (int it = 0; it < NIT; ++it)
+                rowv[it] = *reinterpret_cast<const i32x4 *>(wbuf + (it * RPI + r0) * CROW + cch * 16);
+            uint8_t *crow = Cb + ((long)(br + r0) * g.ldc + wc0) * OS + cch * 16;
+            const long cstep = (long)RPI * g.ldc * OS;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) *reinterpret_cast<i32x4 *>(crow + it * cstep) = rowv[it];
+            wave_sync();
+        } else if (br < M && wc0 < N) {
+            // ---- edge path: raw accumulators to LDS, then a plain loop over rows
+            static_for<0, NI>([&](auto ni_c) {
+                constexpr int ni = decltype(ni_c)::value;
+                static_for<0, 4>([&](auto q_c) {
+                    constexpr int q = decltype(q_c)::value;
+                    uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
+                    *reinterpret_cast<i32x4 *>(d) =
+                        i32x4{(int)as_word(acc_read(acc[mi][ni][4 * q])), (int)as_word(acc_read(acc[mi][ni][4 * q + 1])),
+                              (int)as_word(acc_read(acc[mi][ni][4 * q + 2])), (int)as_word(acc_read(acc[mi][ni][4 * q + 3]))};
+                });
+            });
+            wave_sync();
+            if (inj_here && g.inj_row >= br && g.inj_row < br + 32 && g.inj_col >= wc0 && g.inj_col < wc0 + TN) {
+                // the armed flip: one bit of one accumulator, before rounding and before the sums
+                if (lane == 0)
+                    *reinterpret_cast<uint32_t *>(wbuf + (g.inj_row - br) * SROW + (g.inj_col - wc0) * 4) ^= (1u << g.inj_bit);
+                wave_sync();
+            }
+            const int nrow = M - br < 32 ? M - br : 32;
+            acc_t myrow = T::zero();
+            for (int r = 0; r < nrow; ++r) {
+                acc_t rs = T::zero();
+#pragma unroll
+                for (int j = 0; j < CPL; ++j) {
+                    const int col = CPL * lane + j, gc = wc0 + col;
+                    if (gc < N) {
+                        const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + col * 4));
+                        T::store_c(Cb, (long)(br + r) * g.ldc + gc, v);
+                        if (PROT) { colacc[j] = add_t(colacc[j], v); rs = add_t(rs, v); }
+                    }
+                }
+                if (PROT) {
+                    rs = wave_sum(rs);
+                    if (lane == r) myrow = rs;
+                }
+            }
+            if (PROT && lane < 32) {
+                rs_part[wn * BM + wm * TM + mi * 32 + lane] = myrow;
+            }
+            wave_sync();
+        } else if (PROT) {
+            if (lane < 32) rs_part[wn * BM + wm * TM + mi * 32 + lane] = T::zero();
         }
     });
 
     if (PROT) {
-        // ---- column sums: a second walk over the accumulators, one block column at a time (16
-        // live partial sums instead of 16 * NI), each lane adding up its rows of the MI row
-        // groups; the per-lane partials are transposed through LDS: staged as
-        // S[l32][column of the wave tile] (fp32 / int32), then every lane adds up the 32 rows
-        // of two columns.  Rows past M and the column where a flip is armed are handled here
-        // too, so the sums cover exactly what was stored.
+        // ---- column sums of the register-path groups: transpose the lanes' partials through LDS
         static_for<0, NI>([&](auto ni_c) {
             constexpr int ni = decltype(ni_c)::value;
-            acc_t cp[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) cp[i] = T::zero();
-            static_for<0, MI>([&](auto mi_c) {
-                constexpr int mi = decltype(mi_c)::value;
-                const int br = wr0 + mi * 32;
-                if (br + 32 <= M && !inj_here) {                 // whole group inside, no flip: plain adds
-                    static_for<0, 16>([&](auto i_c) {
-                        constexpr int i = decltype(i_c)::value;
-                        cp[i] = add_t(cp[i], acc_read(acc[mi][ni][i]));
-                    });
-                    __builtin_amdgcn_sched_barrier(0);
-                } else if (br < M) {
-                    const int gr = br + l32;
-                    static_for<0, 16>([&](auto i_c) {
-                        constexpr int i = decltype(i_c)::value;
-                        const int gc = wc0 + ni * 32 + 8 * (i >> 2) + 4 * lh + (i & 3);
-                        acc_t v = acc_read(acc[mi][ni][i]);
-                        if (inj_here && gr == g.inj_row && gc == g.inj_col)
-                            v = from_word<acc_t>(as_word(v) ^ (1u << g.inj_bit));
-                        if (gr < M) cp[i] = add_t(cp[i], v);
-                    });
-                }
-            });
             static_for<0, 4>([&](auto q_c) {
                 constexpr int q = decltype(q_c)::value;
                 uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
                 *reinterpret_cast<i32x4 *>(d) =
-                    i32x4{(int)as_word(cp[4 * q]), (int)as_word(cp[4 * q + 1]),
-                          (int)as_word(cp[4 * q + 2]), (int)as_word(cp[4 * q + 3])};
+                    i32x4{(int)as_word(cp[PROT ? ni : 0][4 * q]), (int)as_word(cp[PROT ? ni : 0][4 * q + 1]),
+                          (int)as_word(cp[PROT ? ni : 0][4 * q + 2]), (int)as_word(cp[PROT ? ni : 0][4 * q + 3])};
             });
         });
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        for (int c0 = 2 * lane; c0 < TN; c0 += 128) {
-            acc_t s0 = T::zero(), s1 = T::zero();
+        wave_sync();
 #pragma unroll
-            for (int r = 0; r < 32; ++r) {
-                const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + c0 * 4);
-                s0 = add_t(s0, from_word<acc_t>(w.x));
-                s1 = add_t(s1, from_word<acc_t>(w.y));
+        for (int r = 0; r < 32; ++r) {
+#pragma unroll
+            for (int j = 0; j < CPL; ++j)
+                colacc[j] = add_t(colacc[j], from_word<acc_t>(*reinterpret_cast<const uint32_t *>(
+                                                 wbuf + r * SROW + (CPL * lane + j) * 4)));
+        }
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) cs_part[wm * BN + wn * TN + CPL * lane + j] = colacc[j];
+        // ---- what the pass over A's slabs left in registers
+        {
+            constexpr int P = BM / 32;
+            const int c = tid & 7, rg = tid >> 3;
+            if (c < P) rp[rg + 32 * c] = ep.st.rdot;
+            if (!T::IS_INT) {
+                const float m = wave_max(ep.st.amax);
+                if (lane == 0) amax4[wave] = m;
             }
-            cs_part[wm * BN + wn * TN + c0] = s0;
-            cs_part[wm * BN + wn * TN + c0 + 1] = s1;
         }
         __syncthreads();
         for (int t = tid; t < BM + BN; t += 256) {
             if (t < BM) {
-                int gr = m0 + t;
-                if (gr < M) atomic_add_word(g.rc_obs + (long)bz * M + gr, add_t(rs_part[t], rs_part[BM + t]));
+                const int gr = m0 + t;
+                if (gr < M) {
+                    atomic_add_word(g.rc_obs + (long)bz * M + gr, add_t(rs_part[t], rs_part[BM + t]));
+                    atomic_add_word(g.rc_pred + (long)bz * M + gr, rp[t]);
+                }
             } else {
-                int gc = n0 + (t - BM);
+                const int gc = n0 + (t - BM);
                 if (gc < N)
                     atomic_add_word(g.cc_obs + (long)bz * N + gc, add_t(cs_part[t - BM], cs_part[BN + t - BM]));
             }
         }
-        if (g.fuse_compare) {
-            // ---- compare and flag without another launch (Sec. III-B.1 item (2)).  The workgroup
-            // that completes a tile row compares that row's sums, the one that completes a tile
-            // column recombines the stripe terms and compares that column's sums; the last
-            // workgroup of the launch publishes counts and status.  Everything the comparing
-            // workgroup reads from others was written with device-scope atomics (performed at
-            // the coherence point); the barrier waits for this workgroup's outstanding ones
-            // before it takes its tickets.
-            static_assert(BM <= 256 && BN <= 256, "one row / column per thread in the fused compare");
-            int *flag_s = reinterpret_cast<int *>(cs_part + 2 * BN);       // [3] after the partial sums
-            __syncthreads();
-            if (tid == 0) {
-                const unsigned tr = atomicAdd(g.row_ticket + (long)bz * g.tiles_m + tile_row_id, 1u);
-                const unsigned tc = atomicAdd(g.col_ticket + (long)bz * g.tiles_n + n0 / BN, 1u);
-                flag_s[0] = (tr == (unsigned)g.tiles_n - 1);
-                flag_s[1] = (tc == (unsigned)g.tiles_m - 1);
-            }
-            __syncthreads();
-            const bool last_row = flag_s[0], last_col = flag_s[1];
-            const float tol = T::IS_INT ? 0.f : g.tau[bz];
-            unsigned nr = 0, nc = 0;
-            if (last_row) {
-                bool f = false;
-                for (int t = tid; t < BM; t += 256) {
-                    const int gr = m0 + t;
-                    if (gr < M) {
-                        const uint32_t obs = atomic_read_word(g.rc_obs + (long)bz * M + gr);
-                        f = epi_mismatch<T::IS_INT>(obs, g.rc_pred[(long)bz * M + gr], tol);
-                        g.row_flag[(long)bz * M + gr] = f ? 1 : 0;
-                    }
-                }
-                nr = __syncthreads_count(f);
-            }
-            if (last_col) {
-                bool f = false;
-                for (int t = tid; t < BN; t += 256) {
-                    const int gc = n0 + t;
-                    if (gc < N) {
-                        uint32_t term[NTERM];
-#pragma unroll
-                        for (int q = 0; q < NTERM; ++q)
-                            term[q] = atomic_read_word(g.cc_part + ((long)bz * NTERM + q) * N + gc);
-                        uint32_t pred;
-                        if (T::IS_INT) {
-                            pred = 0;
-#pragma unroll
-                            for (int q = 0; q < NTERM; ++q) pred += term[q] << (8 * q);
-                        } else {
-                            float v = 0.f;
-#pragma unroll
-                            for (int q = NTERM - 1; q >= 0; --q)          // small terms first
-                                v += __uint_as_float(term[q]) * g.w_a[(long)bz * NTERM + q];
-                            pred = __float_as_uint(v);
-                        }
-                        g.cc_pred[(long)bz * N + gc] = pred;
-                        const uint32_t obs = atomic_read_word(g.cc_obs + (long)bz * N + gc);
-                        f = epi_mismatch<T::IS_INT>(obs, pred, tol);
-                        g.col_flag[(long)bz * N + gc] = f ? 1 : 0;
-                    }
-                }
-                nc = __syncthreads_count(f);
-            }
-            if (tid == 0) {
-                if (nr) atomicAdd(g.fin + 1, nr);
-                if (nc) atomicAdd(g.fin + 2, nc);
-            }
-            __syncthreads();                         // orders this workgroup's count atomics before its final ticket
-            if (tid == 0) {
-                const unsigned total = gridDim.x * gridDim.z;
-                if (atomicAdd(g.fin, 1u) == total - 1) {
-                    const uint32_t r = atomicExch(g.fin + 1, 0u), c = atomicExch(g.fin + 2, 0u);
-                    atomicExch(g.fin, 0u);
-                    const uint32_t st = (r == 0 && c == 0) ? 0u : ((r == 0 || c == 0) ? 2u : 1u);
-                    g.counts[0] = r;
-                    g.counts[1] = c;
-                    g.counts[2] = st;
-                    g.counts[3] = 0u;
-                    g.counts[4] = st;
-                }
-            }
+        // column sums of A over this tile's rows, for the slabs this workgroup reduced
+        for (int t = tid; t < ep.owned * KE; t += 256) {
+            const int k = ((t / KE) * ep.tiles_n + ep.tn) * KE + (t % KE);
+            if (k < g.K) atomic_add_word(g.a_sum + (long)bz * g.K + k, from_word<acc_t>(ep.col_lds[t]));
+        }
+        if (!T::IS_INT && tid == 0) {
+            const float m = fmaxf(fmaxf(amax4[0], amax4[1]), fmaxf(amax4[2], amax4[3]));
+            if (m > 0.f) atomicMax(g.a_max + bz, __float_as_uint(m));
         }
     }
 }

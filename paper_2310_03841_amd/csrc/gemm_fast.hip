@@ -22,7 +22,7 @@ typedef __attribute__((address_space(3))) void *las_ptr;
 
 // One BM x BN tile with origin (m0, n0) of batch item bz.
 template <int DT, int BM, int BN, bool PROT>
-__device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int m0, int n0, int bz, int tile_row_id)
+__device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int m0, int n0, int bz, int tn)
 {
     using T = Traits<DT>;
     typedef typename T::accv_t accv_t;
@@ -38,11 +38,9 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
     const int M = g.M, N = g.N, K = g.K;
-    const int Mx = PROT ? M + NTERM : M;
 
     const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
-    const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
 
     // ---- per-lane global sources.  Load group p of this wave covers tile rows
     // (4 p + wave) * 8 .. + 8; lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches
@@ -50,16 +48,15 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     const int lrow = lane >> 3;
     const int lchunk = (lane & 7) ^ lrow;
     // Interior tiles: the rows of consecutive load groups are 32 apart in one matrix, so a lane
-    // needs one base pointer and a uniform stride.  Edge tiles (stripe rows, rows past the end)
-    // pick the source row by row.
+    // needs one base pointer and a uniform stride.  Edge tiles (rows past the end) pick the
+    // source row by row.
     const bool a_interior = (m0 + BM <= M), b_interior = (n0 + BN <= N);
     const uint8_t *a_lane = Ab + (long)(m0 + wave * 8 + lrow) * g.lda * ES + lchunk * 16;
     const uint8_t *b_lane = Bb + (long)(n0 + wave * 8 + lrow) * g.ldb * ES + lchunk * 16;
     const long a_pstride = 32 * g.lda * ES, b_pstride = 32 * g.ldb * ES;
     auto a_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
         const int r = m0 + (4 * p + wave) * 8 + lrow;
-        const uint8_t *s = r < M ? Ab + (long)r * g.lda * ES
-                                 : ((PROT && r < Mx) ? SAb + (long)(r - M) * g.Kp * ES : Ab);
+        const uint8_t *s = r < M ? Ab + (long)r * g.lda * ES : Ab;
         return s + lchunk * 16;
     };
     auto b_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
@@ -67,7 +64,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES : Bb;
         return s + lchunk * 16;
     };
-    const int a_rows = Mx - m0, b_rows = N - n0;      // rows of this tile that matter
+    const int a_rows = M - m0, b_rows = N - n0;       // rows of this tile that matter
 
     // The accumulators are never zero-filled: the first MFMA of every block takes a literal
     // zero as its addend.  Every block is always computed, also where the tile hangs over the
@@ -140,14 +137,32 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
     };
+    // Protected tiles reduce the slabs of A they own (slab s belongs to tile column s mod
+    // tiles_n) while those are resident: see gemm_apass.h.
+    constexpr int AUX_OFF = 2 * (256 + 256) * SLAB_BYTES;           // behind the buffers of the largest tile
+    uint32_t *col_lds = reinterpret_cast<uint32_t *>(smem + AUX_OFF);
+    EpiProt<DT> ep;
+    ep.st.rdot = T::zero(); ep.st.amax = 0.f;
+    ep.col_lds = col_lds; ep.tn = tn; ep.tiles_n = g.tiles_n; ep.owned = 0;
     {
         const int nslab = K / KE;
         issue_loads(0, 0);
         if (nslab > 1) issue_loads(1, 1);
+        int next_own = tn;
+        if (PROT) {
+            const int owned = tn < nslab ? (nslab - tn + g.tiles_n - 1) / g.tiles_n : 0;
+            for (int t = tid; t < owned * KE; t += 256) col_lds[t] = 0u;
+        }
         __syncthreads();
         ldfr(0, 0, 0);
         auto slab = [&](auto first_c, int s) __attribute__((always_inline)) {
             const int buf = s & 1;
+            if (PROT && s == next_own) {
+                a_pass<DT, BM>(smem + buf * BUF, g.b_sum + (long)bz * K + s * KE, KE, a_rows,
+                               col_lds + ep.owned * KE, ep.st, g.mul24_ok != 0);
+                next_own += g.tiles_n;
+                ep.owned += 1;
+            }
             ldfr(buf, 1, 1); mfmas(first_c, 0); interleave();
             ldfr(buf, 2, 0); mfmas(std::false_type{}, 1); interleave();
             ldfr(buf, 3, 1); mfmas(std::false_type{}, 0); interleave();
@@ -160,7 +175,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         for (int s = 1; s < nslab; ++s) slab(std::false_type{}, s);
     }
     __syncthreads();
-    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, tile_row_id);
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, ep);
 }
 
 // Workgroup -> tile inside a region of tiles_m x tiles_n tiles: consecutive ids of one XCD
@@ -191,10 +206,10 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
     int tm, tn;
     if (bid < g.n_big) {
         map_tile(bid, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tm);
+        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tn);
     } else {
         map_tile(bid - g.n_big, (int)gridDim.x - g.n_big, g.tiles_m_small, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, g.tiles_m_big + tm);
+        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, tn);
     }
 }
 
@@ -204,12 +219,13 @@ static int g_num_cu = 0;
 template <int DT, bool PROT>
 static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
 {
-    constexpr int smem = 2 * (256 + 256) * SLAB_BYTES;
+    constexpr int smem_main = 2 * (256 + 256) * SLAB_BYTES;
+    constexpr int smem_max = smem_main + (PROT ? 4096 * 4 + 2 * SLAB_BYTES * 4 : 0);
     auto kern = gemm_fast_kernel<DT, PROT>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -220,9 +236,8 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
         if (e != hipSuccess) return e;
         g_num_cu = n > 0 ? n : 256;
     }
-    const int Mx = PROT ? g.M + NTERM : g.M;
     g.tiles_n = (g.N + 255) / 256;
-    const int rows_all_big = (Mx + 255) / 256;
+    const int rows_all_big = (g.M + 255) / 256;
     const long total_big = (long)rows_all_big * g.tiles_n * batch;
     int big_rows = rows_all_big;
     if (total_big % g_num_cu != 0) {
@@ -233,10 +248,16 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
     }
     g.tiles_m_big = big_rows;
     g.n_big = big_rows * g.tiles_n;
-    const int rest = Mx - big_rows * 256;
+    const int rest = g.M - big_rows * 256;
     g.tiles_m_small = rest > 0 ? (rest + 127) / 128 : 0;
     g.tiles_m = g.tiles_m_big + g.tiles_m_small;
     dim3 grid((unsigned)(g.n_big + g.tiles_m_small * g.tiles_n), 1, (unsigned)batch);
+    size_t smem = smem_main;
+    if (PROT) {
+        const int ke = SLAB_BYTES / Traits<DT>::ES;
+        smem += (size_t)apass_owned_slabs(g.K / ke, g.tiles_n) * ke * 4;
+        if (smem > (size_t)smem_max) return hipErrorInvalidValue;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
     return hipGetLastError();
 }

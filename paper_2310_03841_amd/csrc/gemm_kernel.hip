@@ -1,22 +1,17 @@
-// Protected GEMM kernel for gfx950: C = A * B with the encoded checksum stripe
-// carried as extra operand rows (of A) and columns (of B), and the observed
-// row / column sums of C taken from the accumulators in the epilogue.
+// Protected GEMM kernel for gfx950, general shapes: C = A * B with the observed row / column
+// sums of C taken from the accumulators in the epilogue and the input-side checksums of A
+// taken from the operand slabs while they are resident in LDS.
 //
-// Method: classic row/column ABFT as cited by the paper (Sec. I, Sec. II-B),
-// with the paper's epilogue fusion of the output checksum (Sec. IV-C memory
-// paragraph; Sec. V "Optimizations" (2)).
-//
-// Logical problem seen by the kernel (PROT = true): rows 0 .. M-1 of A, then rows
-// M .. M+NTERM-1 = stripe_a (the terms of e^T A), so the output has NTERM extra
-// rows (-> cc_part: terms of (e^T A) B).  Only the M x N block is written to C and
-// summed into cc_obs / rc_obs.  The row checksum A (B e) is a matrix-vector product
-// and is taken by the encode pass that streams A anyway, not here.
+// Method: classic row/column ABFT as cited by the paper (Sec. I, Sec. II-B), with the paper's
+// epilogue fusion of the output checksum (Sec. IV-C memory paragraph; Sec. V "Optimizations"
+// (2)).
 //
 // Tiling: one workgroup of 4 waves computes a BM x BN tile; each wave owns a
 // (BM/2) x (BN/2) sub-tile as 32x32 MFMA blocks.  K advances in slabs of 128
 // bytes per row, double-buffered in LDS.  LDS rows are 128 bytes, stored as
 // eight 16-byte chunks with chunk index XOR (row & 7) so that both the
 // row-contiguous writes and the MFMA operand reads are bank-conflict free.
+// Rows of A past M and the tail of a ragged K are zero-filled in LDS.
 #include "abft_device.h"
 #include "gemm_args.h"
 #include "gemm_epilogue.h"
@@ -50,11 +45,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     const int tn_idx = blockIdx.x / g.tiles_m;
     const int m0 = tm_idx * BM, n0 = tn_idx * BN;
     const int M = g.M, N = g.N, K = g.K;
-    const int Mx = PROT ? M + NTERM : M;
 
     const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
-    const uint8_t *SAb = PROT ? g.SA + (long)bz * NTERM * g.Kp * ES : nullptr;
 
     // ---- per-thread row sources: chunk column c of rows r0 + 32 p
     const int c = tid & 7, r0 = tid >> 3;
@@ -64,8 +57,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
         int r = m0 + r0 + 32 * p;
-        asrc[p] = r < M ? Ab + (long)r * g.lda * ES
-                        : ((PROT && r < Mx) ? SAb + (long)(r - M) * g.Kp * ES : nullptr);
+        asrc[p] = r < M ? Ab + (long)r * g.lda * ES : nullptr;     // rows past M are zero-filled
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
@@ -85,7 +77,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
             for (int i = 0; i < 16; ++i) acc[mi][ni][i] = T::zero();
     bool mact[MI], nact[NI];
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) mact[mi] = (m0 + wm * TM + mi * 32) < Mx;
+    for (int mi = 0; mi < MI; ++mi) mact[mi] = (m0 + wm * TM + mi * 32) < M;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) nact[ni] = (n0 + wn * TN + ni * 32) < N;
 
@@ -193,33 +185,59 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
         }
     };
 
+    // Protected tiles reduce the slabs of A they own (slab s belongs to tile column s mod
+    // tiles_n) while those are resident: see gemm_apass.h.
+    uint32_t *col_lds = reinterpret_cast<uint32_t *>(smem + 2 * BUF);
+    EpiProt<DT> ep;
+    ep.st.rdot = T::zero(); ep.st.amax = 0.f;
+    ep.col_lds = col_lds; ep.tn = tn_idx; ep.tiles_n = g.tiles_n; ep.owned = 0;
+    int next_own = tn_idx;
+    if (PROT) {
+        const int owned = tn_idx < nslab ? (nslab - tn_idx + g.tiles_n - 1) / g.tiles_n : 0;
+        for (int t = tid; t < owned * KE; t += 256) col_lds[t] = 0u;
+    }
+
     // ---- main loop: global -> registers -> LDS, two LDS buffers, one barrier per slab
     load_slab(0);
     store_slab(0);
     __syncthreads();
     for (int s = 0; s < nslab; ++s) {
         if (s + 1 < nslab) load_slab(s + 1);
+        if (PROT && s == next_own) {
+            const int kv = K - s * KE;
+            a_pass<DT, BM>(smem + (s & 1) * BUF, g.b_sum + (long)bz * K + s * KE, kv < KE ? kv : KE, BM,
+                           col_lds + ep.owned * KE, ep.st, g.mul24_ok != 0);
+            next_own += g.tiles_n;
+            ep.owned += 1;
+        }
         compute(s & 1);
         if (s + 1 < nslab) store_slab((s + 1) & 1);
         __syncthreads();
     }
 
     // ---- epilogue
-    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, tm_idx);
+    gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, ep);
 }
 
 // ------------------------------------------------------------------------------------------
 template <int DT, int BM, int BN, bool PROT, bool TRANSB>
 static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
 {
-    constexpr int smem = 2 * (BM + BN) * SLAB_BYTES;
+    constexpr int smem_main = 2 * (BM + BN) * SLAB_BYTES;
+    constexpr int smem_max = smem_main + (PROT ? (4096 + SLAB_BYTES) * 4 : 0);
     auto kern = gemm_kernel<DT, BM, BN, PROT, TRANSB>;
     static bool attr_done = false;
-    if (!attr_done && smem > 48 * 1024) {
+    if (!attr_done && smem_max > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
         if (e != hipSuccess) return e;
         attr_done = true;
+    }
+    size_t smem = smem_main;
+    if (PROT) {
+        const int ke = SLAB_BYTES / Traits<DT>::ES;
+        smem += (size_t)apass_owned_slabs((g.K + ke - 1) / ke, g.tiles_n) * ke * 4;
+        if (smem > (size_t)smem_max) return hipErrorInvalidValue;
     }
     dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
@@ -229,8 +247,7 @@ static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
 template <int DT, int BM, int BN>
 static hipError_t launch_cfg(bool protect, bool transB, GemmArgs &g, int batch, hipStream_t st)
 {
-    const int Mx = protect ? g.M + NTERM : g.M;
-    g.tiles_m = (Mx + BM - 1) / BM;
+    g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     if (protect) return transB ? launch_one<DT, BM, BN, true, true>(g, batch, st)
                                : launch_one<DT, BM, BN, true, false>(g, batch, st);
@@ -249,25 +266,20 @@ void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 }
 
 hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
-                       const Workspace &w, const InjectArm &arm, const Verdict *v, hipStream_t st)
+                       const Workspace &w, const InjectArm &arm, hipStream_t st)
 {
     GemmArgs g;
     g.A = (const uint8_t *)A;
     g.B = (const uint8_t *)B;
     g.C = (uint8_t *)C;
-    g.SA = w.stripe_a;
-    g.cc_part = w.cc_part;
-    g.cc_obs = w.cc_obs;
-    g.rc_obs = w.rc_obs;
-    g.M = s.M; g.N = s.N; g.K = s.K; g.Kp = s.Kp;
+    g.M = s.M; g.N = s.N; g.K = s.K;
     g.lda = s.lda; g.ldb = s.ldb; g.ldc = s.ldc;
     g.sA = s.sA; g.sB = s.sB; g.sC = s.sC;
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
-    g.fuse_compare = (protect && v != nullptr) ? 1 : 0;
-    g.rc_pred = w.rc_pred; g.cc_pred = w.cc_pred; g.w_a = w.w_a; g.tau = w.tau;
-    g.row_flag = v ? v->row_flag : nullptr; g.col_flag = v ? v->col_flag : nullptr;
-    g.counts = v ? v->counts : nullptr;
-    g.row_ticket = w.row_ticket; g.col_ticket = w.col_ticket; g.fin = w.fin;
+    g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred;
+    g.a_sum = w.a_sum; g.a_max = w.a_max; g.b_sum = w.b_sum;
+    g.mul24_ok = s.N < 65536 ? 1 : 0;            // |b| <= 128 N
+    g.tiles_m = g.tiles_n = g.n_big = g.tiles_m_big = g.tiles_m_small = 0;
     const bool tb = s.transB != 0;
     if (gemm_fast_eligible(dt, s.M, s.N, s.K, tb, s.lda, s.ldb)) return launch_gemm_fast(dt, protect, g, s.batch, st);
     switch (dt) {
