@@ -30,19 +30,20 @@ template <int DT> struct APassState {
     float amax;                        // max |A| seen (floating point only)
 };
 
-// Words of LDS the pass needs for a tile: column sums of the owned slabs, then BM row values.
+// LDS the pass needs for a tile besides the operand buffers: for every owned slab KE words of
+// column sums and KE words of b (staged once, at the start of the tile, zero beyond K).
 __host__ __device__ inline int apass_owned_slabs(int nslab, int tiles_n) { return (nslab + tiles_n - 1) / tiles_n; }
-__host__ __device__ inline size_t apass_lds_bytes(int dt, int bm, int nslab, int tiles_n)
+__host__ __device__ inline size_t apass_lds_bytes(int dt, int nslab, int tiles_n)
 {
-    return ((size_t)apass_owned_slabs(nslab, tiles_n) * (SLAB_BYTES / elem_size(dt)) + bm) * 4;
+    return (size_t)apass_owned_slabs(nslab, tiles_n) * (SLAB_BYTES / elem_size(dt)) * 8;
 }
 
-// Reduce one resident slab of A.  sA: the slab in LDS (BM rows).  bk: b + first column of the
-// slab (global), kvalid: columns of the slab inside K, rows_valid: rows of the tile inside M
-// (rows beyond may hold anything finite or not: they are ignored).  col_lds: KE words of this
-// slab's column sums (LDS atomics: the four waves add to the same words).
+// Reduce one resident slab of A.  sA: the slab in LDS (BM rows).  b_lds: the KE values of b
+// that belong to the slab (LDS).  rows_valid: rows of the tile inside M (rows beyond may hold
+// anything, finite or not: they are ignored).  col_lds: KE words of this slab's column sums
+// (LDS atomics: the four waves add to the same words).
 template <int DT, int BM>
-__device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *bk, int kvalid, int rows_valid,
+__device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds, int rows_valid,
                                        uint32_t *col_lds, APassState<DT> &st, bool mul24_ok)
 {
     using T = Traits<DT>;
@@ -55,10 +56,13 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *bk, in
 
     acc_t bv[CE], cs[CE];
 #pragma unroll
-    for (int q = 0; q < CE; ++q) {
-        bv[q] = (c * CE + q < kvalid) ? from_word<acc_t>(bk[c * CE + q]) : T::zero();
-        cs[q] = T::zero();
+    for (int q4 = 0; q4 < CE / 4; ++q4) {
+        const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + c * CE + 4 * q4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bv[4 * q4 + e] = from_word<acc_t>((uint32_t)w[e]);
     }
+#pragma unroll
+    for (int q = 0; q < CE; ++q) cs[q] = T::zero();
     i32x4 v[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) v[p] = *reinterpret_cast<const i32x4 *>(src + p * 32 * SLAB_BYTES);
@@ -84,10 +88,23 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *bk, in
         if (c == p) mine = dot;
     }
     st.rdot = add_t(st.rdot, mine);
+    // Column sums: first over the eight row groups of the wave (lanes with equal c), then one
+    // LDS atomic per column and wave.  (LDS atomics in which several lanes of one instruction
+    // hit the same word are served one lane at a time.)
 #pragma unroll
     for (int q = 0; q < CE; ++q) {
-        if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(col_lds) + c * CE + q, (int)cs[q]);
-        else atomicAdd(reinterpret_cast<float *>(col_lds) + c * CE + q, (float)cs[q]);
+        acc_t t = cs[q];
+        t = add_t(t, dpp_get<0x128>(t));      // row_ror:8 inside 16 lanes: lane ^ 8
+        t = add_t(t, __shfl_xor(t, 16));
+        t = add_t(t, __shfl_xor(t, 32));
+        cs[q] = t;
+    }
+    if ((tid & 63) < 8) {
+#pragma unroll
+        for (int q = 0; q < CE; ++q) {
+            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(col_lds) + c * CE + q, (int)cs[q]);
+            else atomicAdd(reinterpret_cast<float *>(col_lds) + c * CE + q, (float)cs[q]);
+        }
     }
 }
 

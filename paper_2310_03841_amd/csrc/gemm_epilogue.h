@@ -189,7 +189,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
             uint8_t *crow = Cb + ((long)(br + r0) * g.ldc + wc0) * OS + cch * 16;
             const long cstep = (long)RPI * g.ldc * OS;
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) *reinterpret_cast<i32x4 *>(crow + it * cstep) = rowv[it];
+            for (int it = 0; it < NIT; ++it)
+                __builtin_nontemporal_store(rowv[it], reinterpret_cast<i32x4 *>(crow + it * cstep));
             wave_sync();
         } else if (br < M && wc0 < N) {
             // ---- edge path: raw accumulators to LDS, then a plain loop over rows
@@ -252,10 +253,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
         wave_sync();
 #pragma unroll
         for (int r = 0; r < 32; ++r) {
+            if constexpr (CPL == 2) {
+                const uint2 w = *reinterpret_cast<const uint2 *>(wbuf + r * SROW + lane * 8);
+                colacc[0] = add_t(colacc[0], from_word<acc_t>(w.x));
+                colacc[1] = add_t(colacc[1], from_word<acc_t>(w.y));
+            } else {
 #pragma unroll
-            for (int j = 0; j < CPL; ++j)
-                colacc[j] = add_t(colacc[j], from_word<acc_t>(*reinterpret_cast<const uint32_t *>(
-                                                 wbuf + r * SROW + (CPL * lane + j) * 4)));
+                for (int j = 0; j < CPL; ++j)
+                    colacc[j] = add_t(colacc[j], from_word<acc_t>(*reinterpret_cast<const uint32_t *>(
+                                                     wbuf + r * SROW + (CPL * lane + j) * 4)));
+            }
         }
 #pragma unroll
         for (int j = 0; j < CPL; ++j) cs_part[wm * BN + wn * TN + CPL * lane + j] = colacc[j];
@@ -269,7 +276,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 if (lane == 0) amax4[wave] = m;
             }
         }
-        __syncthreads();
+        // Barrier over LDS traffic only: the partial sums meet in LDS, and a full barrier would
+        // also wait until every store of C issued above has been acknowledged.
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         for (int t = tid; t < BM + BN; t += 256) {
             if (t < BM) {
                 const int gr = m0 + t;

@@ -42,29 +42,30 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
 
-    // ---- per-lane global sources.  Load group p of this wave covers tile rows
-    // (4 p + wave) * 8 .. + 8; lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches
-    // the chunk (l & 7) ^ (l >> 3) so that LDS slot = chunk ^ (row & 7).
+    // ---- global sources.  Load group p of this wave covers tile rows (4 p + wave) * 8 .. + 8;
+    // lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches the chunk (l & 7) ^ (l >> 3)
+    // so that LDS slot = chunk ^ (row & 7).  An address is a wave-uniform base (tile origin plus
+    // the slab's offset along K) plus a per-lane 32-bit offset that never changes, so issuing a
+    // load inside the main loop costs no vector arithmetic and no branch.  Rows of the tile past
+    // the end of the matrix fetch the last valid row instead.
     const int lrow = lane >> 3;
     const int lchunk = (lane & 7) ^ lrow;
-    // Interior tiles: the rows of consecutive load groups are 32 apart in one matrix, so a lane
-    // needs one base pointer and a uniform stride.  Edge tiles (rows past the end) pick the
-    // source row by row.
-    const bool a_interior = (m0 + BM <= M), b_interior = (n0 + BN <= N);
-    const uint8_t *a_lane = Ab + (long)(m0 + wave * 8 + lrow) * g.lda * ES + lchunk * 16;
-    const uint8_t *b_lane = Bb + (long)(n0 + wave * 8 + lrow) * g.ldb * ES + lchunk * 16;
-    const long a_pstride = 32 * g.lda * ES, b_pstride = 32 * g.ldb * ES;
-    auto a_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
-        const int r = m0 + (4 * p + wave) * 8 + lrow;
-        const uint8_t *s = r < M ? Ab + (long)r * g.lda * ES : Ab;
-        return s + lchunk * 16;
-    };
-    auto b_src = [&](int p) __attribute__((always_inline)) -> const uint8_t * {
-        const int r = n0 + (4 * p + wave) * 8 + lrow;
-        const uint8_t *s = r < N ? Bb + (long)r * g.ldb * ES : Bb;
-        return s + lchunk * 16;
-    };
-    const int a_rows = M - m0, b_rows = N - n0;       // rows of this tile that matter
+    const uint8_t *a_base = Ab + (long)m0 * g.lda * ES;
+    const uint8_t *b_base = Bb + (long)n0 * g.ldb * ES;
+    uint32_t a_off[GA], b_off[GB];
+#pragma unroll
+    for (int p = 0; p < GA; ++p) {
+        int r = (4 * p + wave) * 8 + lrow;
+        r = r < M - m0 ? r : M - m0 - 1;
+        a_off[p] = (uint32_t)r * (uint32_t)(g.lda * ES) + lchunk * 16;
+    }
+#pragma unroll
+    for (int p = 0; p < GB; ++p) {
+        int r = (4 * p + wave) * 8 + lrow;
+        r = r < N - n0 ? r : N - n0 - 1;
+        b_off[p] = (uint32_t)r * (uint32_t)(g.ldb * ES) + lchunk * 16;
+    }
+    const int a_rows = M - m0;                        // rows of this tile inside A
 
     // The accumulators are never zero-filled: the first MFMA of every block takes a literal
     // zero as its addend.  Every block is always computed, also where the tile hangs over the
@@ -74,40 +75,26 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
 #pragma unroll
     for (int i = 0; i < 16; ++i) zerov[i] = T::zero();
 
-    // One loop serves interior and edge tiles (two instances of the MFMA loop that meet in
-    // front of the epilogue would push the accumulators through VGPR copies); only the source
-    // address of a load depends, wave-uniformly, on where the tile lies.
     auto issue_loads = [&](int s, int buf) __attribute__((always_inline)) {
-        const long koff = (long)s * SLAB_BYTES;
+        const uint8_t *ak = a_base + (long)s * SLAB_BYTES;
+        const uint8_t *bk = b_base + (long)s * SLAB_BYTES;
         uint8_t *sA = smem + buf * BUF;
         uint8_t *sB = sA + BM * SLAB_BYTES;
 #pragma unroll
-        for (int p = 0; p < GA; ++p) {
-            const int rb = (4 * p + wave) * 8;
-            if (a_interior) {
-                __builtin_amdgcn_global_load_lds((gas_ptr)(a_lane + p * a_pstride + koff),
-                                                 (las_ptr)(sA + rb * SLAB_BYTES), 16, 0, 0);
-            } else if (rb < a_rows) {
-                __builtin_amdgcn_global_load_lds((gas_ptr)(a_src(p) + koff), (las_ptr)(sA + rb * SLAB_BYTES), 16, 0, 0);
-            }
-        }
+        for (int p = 0; p < GA; ++p)
+            __builtin_amdgcn_global_load_lds((gas_ptr)(ak + a_off[p]), (las_ptr)(sA + (4 * p + wave) * 8 * SLAB_BYTES), 16, 0, 0);
 #pragma unroll
-        for (int p = 0; p < GB; ++p) {
-            const int rb = (4 * p + wave) * 8;
-            if (b_interior) {
-                __builtin_amdgcn_global_load_lds((gas_ptr)(b_lane + p * b_pstride + koff),
-                                                 (las_ptr)(sB + rb * SLAB_BYTES), 16, 0, 0);
-            } else if (rb < b_rows) {
-                __builtin_amdgcn_global_load_lds((gas_ptr)(b_src(p) + koff), (las_ptr)(sB + rb * SLAB_BYTES), 16, 0, 0);
-            }
-        }
+        for (int p = 0; p < GB; ++p)
+            __builtin_amdgcn_global_load_lds((gas_ptr)(bk + b_off[p]), (las_ptr)(sB + (4 * p + wave) * 8 * SLAB_BYTES), 16, 0, 0);
     };
     // ---- main loop, software-pipelined by hand.  A slab is four MFMA steps of 32 bytes of K.
     // The fragments of step t+1 are read from LDS while the MFMAs of step t run (two register
     // sets); the reads are issued in the first half of a step so that the second half covers
     // their latency.  The barrier sits between steps 2 and 3: by then every wave has read its
     // step-3 fragments, so nobody reads this slab's buffer any more and the loads of slab s+2
-    // can be issued into it at once, while step 3 runs and prefetches step 0 of slab s+1.
+    // are issued into it at once, spread between the MFMAs of step 3, which also prefetches
+    // step 0 of slab s+1.  The loop is peeled (first slab: literal-zero addend; last two slabs:
+    // nothing left to load) so that no branch separates loads and MFMAs.
     i32x4 fa[2][MI], fb[2][NI];
     auto ldfr = [&](int buf, int s4, int set) __attribute__((always_inline)) {
         const uint8_t *sA = smem + buf * BUF;
@@ -137,6 +124,39 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         }
         __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
     };
+    // Step 3 of a slab that still has loads to issue, in explicit program order: after every
+    // MFMA (register set 1) one fragment read of the next slab's step 0 (into set 0) while
+    // there are any, and this MFMA's share of the GA + GB direct-to-LDS loads of slab s + 2.
+    // The scheduling fences keep that order; left alone, the compiler issues all loads in one
+    // burst behind the barrier and the matrix pipe waits for them.
+    auto step3_loads = [&](int s2, int buf) __attribute__((always_inline)) {
+        constexpr int NMF = MI * NI, NLD = GA + GB;
+        const uint8_t *ak = a_base + (long)s2 * SLAB_BYTES;
+        const uint8_t *bk = b_base + (long)s2 * SLAB_BYTES;
+        uint8_t *dA = smem + buf * BUF;
+        uint8_t *dB = dA + BM * SLAB_BYTES;
+        const uint8_t *sA = smem + (buf ^ 1) * BUF;
+        const uint8_t *sB = sA + BM * SLAB_BYTES;
+        const int sw = (lh ^ (lane & 7)) * 16;
+        static_for<0, NMF>([&](auto j_c) {
+            constexpr int j = decltype(j_c)::value;
+            constexpr int mi = j / NI, ni = j % NI;
+            acc[mi][ni] = T::mfma(fb[1][ni], fa[1][mi], acc[mi][ni]);
+            if constexpr (j < MI)
+                fa[0][j] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + j * 32 + l32) * SLAB_BYTES + sw);
+            else if constexpr (j < MI + NI)
+                fb[0][j - MI] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + (j - MI) * 32 + l32) * SLAB_BYTES + sw);
+            constexpr int l0 = j * NLD / NMF, l1 = (j + 1) * NLD / NMF;
+            static_for<l0, l1>([&](auto l_c) {
+                constexpr int l = decltype(l_c)::value;
+                if constexpr (l < GA)
+                    __builtin_amdgcn_global_load_lds((gas_ptr)(ak + a_off[l]), (las_ptr)(dA + (4 * l + wave) * 8 * SLAB_BYTES), 16, 0, 0);
+                else
+                    __builtin_amdgcn_global_load_lds((gas_ptr)(bk + b_off[l - GA]), (las_ptr)(dB + (4 * (l - GA) + wave) * 8 * SLAB_BYTES), 16, 0, 0);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
     // Protected tiles reduce the slabs of A they own (slab s belongs to tile column s mod
     // tiles_n) while those are resident: see gemm_apass.h.
     constexpr int AUX_OFF = 2 * (256 + 256) * SLAB_BYTES;           // behind the buffers of the largest tile
@@ -145,34 +165,52 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
     ep.col_lds = col_lds; ep.tn = tn; ep.tiles_n = g.tiles_n; ep.owned = 0;
     {
-        const int nslab = K / KE;
-        issue_loads(0, 0);
-        if (nslab > 1) issue_loads(1, 1);
+        const int nslab = K / KE;                      // at least 3 (gemm_fast_eligible)
         int next_own = tn;
+        const int owned = (PROT && tn < nslab) ? (nslab - tn + g.tiles_n - 1) / g.tiles_n : 0;
+        uint32_t *b_lds = col_lds + owned * KE;
         if (PROT) {
-            const int owned = tn < nslab ? (nslab - tn + g.tiles_n - 1) / g.tiles_n : 0;
+            // the values of b the owned slabs need, straight into LDS (one slab per wave and turn),
+            // and zeros for the column sums; both are in place behind the first barrier
+            for (int j = wave; j < owned; j += 4) {
+                const uint32_t *src = g.b_sum + (long)bz * K + (long)(tn + j * g.tiles_n) * KE + lane;
+#pragma unroll
+                for (int h = 0; h < KE / 64; ++h)
+                    __builtin_amdgcn_global_load_lds((gas_ptr)(src + 64 * h), (las_ptr)(b_lds + j * KE + 64 * h), 4, 0, 0);
+            }
             for (int t = tid; t < owned * KE; t += 256) col_lds[t] = 0u;
         }
+        issue_loads(0, 0);
+        issue_loads(1, 1);
         __syncthreads();
         ldfr(0, 0, 0);
-        auto slab = [&](auto first_c, int s) __attribute__((always_inline)) {
+        auto slab = [&](auto first_c, auto loads_c, int s) __attribute__((always_inline)) {
+            constexpr bool LOADS = decltype(loads_c)::value;
             const int buf = s & 1;
             if (PROT && s == next_own) {
-                a_pass<DT, BM>(smem + buf * BUF, g.b_sum + (long)bz * K + s * KE, KE, a_rows,
-                               col_lds + ep.owned * KE, ep.st, g.mul24_ok != 0);
+                a_pass<DT, BM>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                               g.mul24_ok != 0);
                 next_own += g.tiles_n;
                 ep.owned += 1;
             }
+            __builtin_amdgcn_sched_barrier(0);
             ldfr(buf, 1, 1); mfmas(first_c, 0); interleave();
+            __builtin_amdgcn_sched_barrier(0);
             ldfr(buf, 2, 0); mfmas(std::false_type{}, 1); interleave();
+            __builtin_amdgcn_sched_barrier(0);
             ldfr(buf, 3, 1); mfmas(std::false_type{}, 0); interleave();
             __syncthreads();
-            if (s + 2 < nslab) issue_loads(s + 2, buf);
-            if (s + 1 < nslab) ldfr(buf ^ 1, 0, 0);
-            mfmas(std::false_type{}, 1); interleave();
+            if constexpr (LOADS) {
+                step3_loads(s + 2, buf);
+            } else {
+                ldfr(buf ^ 1, 0, 0);                   // after the last slab: read and never used
+                mfmas(std::false_type{}, 1); interleave();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         };
-        slab(std::true_type{}, 0);
-        for (int s = 1; s < nslab; ++s) slab(std::false_type{}, s);
+        slab(std::true_type{}, std::true_type{}, 0);
+        for (int s = 1; s < nslab - 2; ++s) slab(std::false_type{}, std::true_type{}, s);
+        for (int s = nslab - 2; s < nslab; ++s) slab(std::false_type{}, std::false_type{}, s);
     }
     __syncthreads();
     gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, ep);
@@ -220,7 +258,7 @@ template <int DT, bool PROT>
 static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
 {
     constexpr int smem_main = 2 * (256 + 256) * SLAB_BYTES;
-    constexpr int smem_max = smem_main + (PROT ? 4096 * 4 + 2 * SLAB_BYTES * 4 : 0);
+    constexpr int smem_max = 160 * 1024;
     auto kern = gemm_fast_kernel<DT, PROT>;
     static bool attr_done = false;
     if (!attr_done) {
@@ -255,7 +293,7 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
     size_t smem = smem_main;
     if (PROT) {
         const int ke = SLAB_BYTES / Traits<DT>::ES;
-        smem += (size_t)apass_owned_slabs(g.K / ke, g.tiles_n) * ke * 4;
+        smem += apass_lds_bytes(DT, g.K / ke, g.tiles_n);
         if (smem > (size_t)smem_max) return hipErrorInvalidValue;
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
@@ -265,8 +303,10 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
 bool gemm_fast_eligible(int dt, int M, int N, int K, bool transB, long lda, long ldb)
 {
     const int ke = SLAB_BYTES / elem_size(dt);
-    (void)lda; (void)ldb;
-    return transB && (K % ke) == 0 && M >= 512 && N >= 512;
+    // whole slabs, at least three of them (the main loop is peeled), and 32-bit row offsets
+    // inside a tile
+    return transB && (K % ke) == 0 && K >= 3 * ke && M >= 512 && N >= 512 &&
+           lda * elem_size(dt) < (1L << 23) && ldb * elem_size(dt) < (1L << 23);
 }
 
 void gemm_fast_tile(int *tm, int *tn) { *tm = 256; *tn = 256; }

@@ -192,9 +192,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
     ep.col_lds = col_lds; ep.tn = tn_idx; ep.tiles_n = g.tiles_n; ep.owned = 0;
     int next_own = tn_idx;
+    const int owned = (PROT && tn_idx < nslab) ? (nslab - tn_idx + g.tiles_n - 1) / g.tiles_n : 0;
+    uint32_t *b_lds = col_lds + owned * KE;
     if (PROT) {
-        const int owned = tn_idx < nslab ? (nslab - tn_idx + g.tiles_n - 1) / g.tiles_n : 0;
-        for (int t = tid; t < owned * KE; t += 256) col_lds[t] = 0u;
+        // zeros for the column sums and the values of b the owned slabs need (zero beyond K);
+        // both are in place behind the first barrier
+        for (int t = tid; t < owned * KE; t += 256) {
+            const int kk = (tn_idx + (t / KE) * g.tiles_n) * KE + (t % KE);
+            col_lds[t] = 0u;
+            b_lds[t] = kk < K ? g.b_sum[(long)bz * K + kk] : 0u;
+        }
     }
 
     // ---- main loop: global -> registers -> LDS, two LDS buffers, one barrier per slab
@@ -204,9 +211,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     for (int s = 0; s < nslab; ++s) {
         if (s + 1 < nslab) load_slab(s + 1);
         if (PROT && s == next_own) {
-            const int kv = K - s * KE;
-            a_pass<DT, BM>(smem + (s & 1) * BUF, g.b_sum + (long)bz * K + s * KE, kv < KE ? kv : KE, BM,
-                           col_lds + ep.owned * KE, ep.st, g.mul24_ok != 0);
+            a_pass<DT, BM>(smem + (s & 1) * BUF, b_lds + ep.owned * KE, BM, col_lds + ep.owned * KE, ep.st,
+                           g.mul24_ok != 0);
             next_own += g.tiles_n;
             ep.owned += 1;
         }
@@ -224,7 +230,7 @@ template <int DT, int BM, int BN, bool PROT, bool TRANSB>
 static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
 {
     constexpr int smem_main = 2 * (BM + BN) * SLAB_BYTES;
-    constexpr int smem_max = smem_main + (PROT ? (4096 + SLAB_BYTES) * 4 : 0);
+    constexpr int smem_max = smem_main + (PROT ? (4096 + SLAB_BYTES) * 8 : 0);
     auto kern = gemm_kernel<DT, BM, BN, PROT, TRANSB>;
     static bool attr_done = false;
     if (!attr_done && smem_max > 48 * 1024) {
@@ -236,7 +242,7 @@ static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
     size_t smem = smem_main;
     if (PROT) {
         const int ke = SLAB_BYTES / Traits<DT>::ES;
-        smem += (size_t)apass_owned_slabs((g.K + ke - 1) / ke, g.tiles_n) * ke * 4;
+        smem += apass_lds_bytes(DT, (g.K + ke - 1) / ke, g.tiles_n);
         if (smem > (size_t)smem_max) return hipErrorInvalidValue;
     }
     dim3 grid((unsigned)(g.tiles_m * g.tiles_n), 1, (unsigned)batch);
