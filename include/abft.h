@@ -35,7 +35,7 @@
  *     16 bytes (else ABFT_EALIGN).  The buffers must hold rows*ld elements per
  *     item: the library may read (never use) the pad between K and lda.
  *   - The caller owns A, B, C, the flag / count buffers and the stream.  The
- *     context owns its workspace (checksum vectors, encoded stripes, lists).
+ *     context owns its workspace (checksum vectors, tile lists).
  *   - abft_gemm / abft_verify / abft_correct / abft_inject / abft_encode_b only
  *     enqueue work on `stream` (a hipStream_t passed as void*): they allocate
  *     nothing, copy nothing to the host and never synchronise.  Results are
@@ -73,8 +73,8 @@ enum {
     ABFT_OK         =  0,
     ABFT_EINVAL     = -1,   /* null pointer, unknown dtype/mode, index out of range */
     ABFT_EALIGN     = -2,   /* pointer, leading dimension or stride not a multiple of 16 bytes */
-    ABFT_ESHAPE     = -3,   /* non-positive size, ld < row length, or K beyond what the encode pass
-                               covers (K > 4096; int8 additionally needs K * 2^14 < 2^31) */
+    ABFT_ESHAPE     = -3,   /* non-positive size, ld < row length, or K beyond what the protected
+                               GEMM covers (K > 4096; int8 additionally needs K * 2^14 < 2^31) */
     ABFT_EWORKSPACE = -4,   /* shape exceeds what the context was created for */
     ABFT_EHIP       = -5,   /* a HIP runtime call failed (see abft_last_hip_error) */
     ABFT_ESTATE     = -6    /* call needs state that is not there (e.g. cached B encoding) */
@@ -143,7 +143,14 @@ int abft_destroy(abft_ctx *ctx);
  * abft_gemm calls with ABFT_B_CHECKSUM_CACHED and the same shape skip that step. */
 int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_shape *s, void *stream);
 
-/* Steps 1-6: encode, GEMM with the checksum stripe, observed sums in the epilogue, compare.
+/* The protected GEMM (Sec. III-B.1 "Checksums"; epilogue fusion of Sec. V "Optimizations" (2)).
+ * Enqueues: the pass over B that gives b = B e and max|B| (skipped with
+ * ABFT_B_CHECKSUM_CACHED); the GEMM, which besides C produces, from the operand slabs of A it
+ * holds on chip, a = e^T A, the row prediction A b and max|A|, and from its accumulators
+ * (before rounding) the observed sums e^T C and C e; the finish kernel, which forms the
+ * column prediction a B from one read of B, compares both pairs (equality for ABFT_I8,
+ * |difference| <= tau otherwise; NaN or Inf always flag) and writes flags, counts and status.
+ * A and B must stay unchanged until the finish kernel has run.
  * mode ABFT_OFF ignores `r` (may be NULL).  Flags and counts are overwritten. */
 int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
               const abft_shape *s, const abft_result *r, void *stream);
@@ -179,7 +186,8 @@ int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *til
 /* Kernel timing for reports (not a hot call: creates HIP events).  Between begin and end every
  * abft_gemm records events on the caller's stream around its kernels; up to max_calls calls are
  * kept.  abft_profile_end waits for the recorded events and returns average milliseconds per call:
- * ms[0] encode kernel, ms[1] GEMM kernel, ms[2] compare kernel, ms[3] first event to last. */
+ * ms[0] pass over B (or the clearing kernel that replaces it), ms[1] GEMM kernel, ms[2] finish
+ * kernel, ms[3] first event to last. */
 int abft_profile_begin(abft_ctx *ctx, int max_calls);
 int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls);
 

@@ -360,9 +360,13 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     constexpr int ES = T::ES, CE = 16 / ES;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     __shared__ acc_t wred[4];
+    __shared__ unsigned wcnt[4][2];
     __shared__ int is_last;
+    (void)is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bz = blockIdx.z;
     const int M = f.M, N = f.N, K = f.K;
+    const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
+    const uint32_t *asum = f.a_sum + (long)bz * K;
 
     float tol = 0.f;
     if (!T::IS_INT) {
@@ -376,40 +380,41 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
 
     bool frow = false, fcol = false, fcol2 = false;
     if ((int)blockIdx.x < f.col_blocks) {
-        // ---- a staged in LDS, zero beyond K up to a whole chunk
-        acc_t *al = reinterpret_cast<acc_t *>(lds);
-        const int Kc = (K + CE - 1) / CE * CE;
-        for (int k = tid; k < Kc; k += 256) al[k] = k < K ? from_word<acc_t>(f.a_sum[(long)bz * K + k]) : T::zero();
-        __syncthreads();
-        const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
-        if (blockIdx.x == 0) {
-            // scalar a . b (the single-number check value of Sec. III-B.1)
-            acc_t v = T::zero();
-            for (int k = tid; k < K; k += 256) v = add_t(v, mul_t(al[k], from_word<acc_t>(f.b_sum[(long)bz * K + k])));
-            v = wave_sum(v);
-            if (lane == 0) wred[wave] = v;
-            __syncthreads();
-            if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
-        }
         if (f.transB) {
-            // B stored N x K: a wave takes four rows of B at a time, lanes run along K
-            const int nch = Kc / CE;
+            // B stored N x K: a wave takes four rows of B at a time, lanes run along K.  The
+            // matching values of a come straight from memory, in flight together with B.
+            const int nch = (K + CE - 1) / CE;
             const int nb = blockIdx.x * FIN_ROWS_B + wave * 4;
             acc_t dot[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
             for (int ch = lane; ch < nch; ch += 64) {
-                i32x4 v[4];
+                i32x4 v[4], aw[CE / 4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     v[j] = i32x4{0, 0, 0, 0};
                     if (nb + j < N) v[j] = *reinterpret_cast<const i32x4 *>(Bb + ((long)(nb + j) * f.ldb + ch * CE) * ES);
                 }
-                const int left = K - ch * CE;
+                const int left = K - ch * CE;                       // >= 1
+                if (left >= CE) {
+#pragma unroll
+                    for (int q4 = 0; q4 < CE / 4; ++q4) {
+                        // dword-aligned 16-byte reads (the batch offset need not be a multiple of four words)
+                        const uint32_t *ap = asum + ch * CE + 4 * q4;
+                        aw[q4] = i32x4{(int)ap[0], (int)ap[1], (int)ap[2], (int)ap[3]};
+                    }
+                } else {
+#pragma unroll
+                    for (int q4 = 0; q4 < CE / 4; ++q4)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            aw[q4][e] = (4 * q4 + e < left) ? (int)asum[ch * CE + 4 * q4 + e] : 0;
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     i32x4 w = v[j];
                     if (left < CE) w = mask_chunk(w, left * ES);
 #pragma unroll
-                    for (int q = 0; q < CE; ++q) dot[j] = add_t(dot[j], mul_t(T::elem(w, q), al[ch * CE + q]));
+                    for (int q = 0; q < CE; ++q)
+                        dot[j] = add_t(dot[j], mul_t(T::elem(w, q), from_word<acc_t>((uint32_t)aw[q >> 2][q & 3])));
                 }
             }
 #pragma unroll
@@ -423,8 +428,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                 }
             }
         } else {
-            // B stored K x N: 32 chunk columns per block, FIN_KY lanes run along K
-            acc_t *red = al + Kc;                                   // [FIN_KY][32 * CE]
+            // B stored K x N: a staged in LDS; 32 chunk columns per block, FIN_KY lanes run along K
+            acc_t *al = reinterpret_cast<acc_t *>(lds);
+            for (int k = tid; k < K; k += 256) al[k] = from_word<acc_t>(asum[k]);
+            __syncthreads();
+            acc_t *red = al + (K + 3) / 4 * 4;                      // [FIN_KY][32 * CE]
             const int cx = tid & 31, ky = tid >> 5;
             const int nst = (blockIdx.x * 32 + cx) * CE;
             const int left = N - nst;
@@ -475,30 +483,47 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
             frow = mismatch<T::IS_INT>(f.rc_obs[o], f.rc_pred[o], tol);
             f.row_flag[o] = frow ? 1 : 0;
         }
+        if ((int)blockIdx.x == f.col_blocks) {
+            // scalar a . b (the single-number check value of Sec. III-B.1), by the first row block
+            acc_t v = T::zero();
+            for (int k = tid; k < K; k += 256)
+                v = add_t(v, mul_t(from_word<acc_t>(asum[k]), from_word<acc_t>(f.b_sum[(long)bz * K + k])));
+            v = wave_sum(v);
+            if (lane == 0) wred[wave] = v;
+        }
     }
-    const unsigned nr = __syncthreads_count(frow);
-    const unsigned nc = __syncthreads_count(fcol) + __syncthreads_count(fcol2);
-    if (tid == 0) {
-        if (nr) atomicAdd(f.ticket + 1, nr);
-        if (nc) atomicAdd(f.ticket + 2, nc);
+    // flagged rows / columns of this block
+    {
+        const unsigned nr = __popcll(__ballot(frow));
+        const unsigned nc = __popcll(__ballot(fcol)) + __popcll(__ballot(fcol2));
+        if (lane == 0) { wcnt[wave][0] = nr; wcnt[wave][1] = nc; }
     }
-    // the counts of this block are at the coherence point before its ticket is (atomics only,
-    // ordered by the barrier's wait for outstanding memory operations)
     __syncthreads();
     if (tid == 0) {
+        if ((int)blockIdx.x == f.col_blocks)
+            f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
+        const unsigned nr = wcnt[0][0] + wcnt[1][0] + wcnt[2][0] + wcnt[3][0];
+        const unsigned nc = wcnt[0][1] + wcnt[1][1] + wcnt[2][1] + wcnt[3][1];
+        if (nr | nc) {
+            // rare: the counts must be at the coherence point before this block's ticket is, so
+            // fetch their old values and wait for them
+            unsigned o1 = 0, o2 = 0;
+            if (nr) o1 = atomicAdd(f.ticket + 1, nr);
+            if (nc) o2 = atomicAdd(f.ticket + 2, nc);
+            asm volatile("s_waitcnt vmcnt(0)" :: "v"(o1), "v"(o2) : "memory");
+        }
         const unsigned total = gridDim.x * gridDim.z;
         const unsigned t = atomicAdd(f.ticket, 1u);
         is_last = (t == total - 1);
-    }
-    __syncthreads();
-    if (is_last && tid == 0) {
-        const uint32_t r = atomicExch(f.ticket + 1, 0u), c = atomicExch(f.ticket + 2, 0u);
-        atomicExch(f.ticket, 0u);
-        f.counts[0] = r;
-        f.counts[1] = c;
-        f.counts[2] = status_of(r, c);
-        f.counts[3] = 0u;
-        f.counts[4] = status_of(r, c);
+        if (is_last) {
+            const uint32_t r = atomicExch(f.ticket + 1, 0u), c = atomicExch(f.ticket + 2, 0u);
+            atomicExch(f.ticket, 0u);
+            f.counts[0] = r;
+            f.counts[1] = c;
+            f.counts[2] = status_of(r, c);
+            f.counts[3] = 0u;
+            f.counts[4] = status_of(r, c);
+        }
     }
 }
 
@@ -515,8 +540,7 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     const int ce = 16 / elem_size(dt);
     f.col_blocks = s.transB ? (s.N + FIN_ROWS_B - 1) / FIN_ROWS_B : (s.N + 32 * ce - 1) / (32 * ce);
     const int row_blocks = (s.M + 255) / 256;
-    const int kc = (s.K + ce - 1) / ce * ce;
-    const size_t smem = ((size_t)kc + (s.transB ? 0 : (size_t)FIN_KY * 32 * ce)) * 4;
+    const size_t smem = s.transB ? 0 : ((size_t)(s.K + 3) / 4 * 4 + (size_t)FIN_KY * 32 * ce) * 4;
     dim3 grid((unsigned)(f.col_blocks + row_blocks), 1, (unsigned)s.batch);
     switch (dt) {
     case DT_I8:   hipLaunchKernelGGL(finish_kernel<DT_I8>, grid, dim3(256), smem, st, f); break;

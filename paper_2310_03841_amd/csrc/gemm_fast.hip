@@ -1,16 +1,19 @@
 // Fast path of the protected GEMM for gfx950: B stored N x K (both operands K-contiguous) and
-// K a whole number of 128-byte slabs.  Same mathematics and the same epilogue as gemm_kernel;
-// what differs is the data movement:
+// K a whole number (at least three) of 128-byte slabs.  Same mathematics, the same pass over
+// A's slabs and the same epilogue as gemm_kernel; what differs is the data movement:
 //   * global -> LDS with direct-to-LDS loads (global_load_lds_dwordx4): no VGPR staging.  One
 //     wave instruction fills 8 LDS rows of 128 bytes; the XOR swizzle of the LDS layout is
 //     applied by choosing which global 16-byte chunk each lane fetches.
 //   * 256 x 256 tiles, 4 waves of 128 x 128 (sixteen 32x32 MFMA blocks per wave), two LDS
 //     buffers of 64 KB, one barrier per slab; 128 x 256 tiles fill the last, partial round.
+//   * the loads of the next-but-one slab are issued one by one between the MFMAs of a slab's
+//     last step, without branches.
 //   * MFMAs take the B fragment first, so a lane owns a row of C (see gemm_epilogue.h).
 //   * workgroup -> tile mapping keeps the workgroups that share an XCD (and its L2) on a
 //     compact group of tiles.
-// Rows of the tile beyond the (stripe-augmented) problem are fetched from a valid row instead
-// of being zero-filled: a row of A only influences the same row of C, which is discarded.
+// Rows of the tile beyond the problem are fetched from a valid row instead of being
+// zero-filled: a row of A only influences the same row of C, which is discarded, and the pass
+// over A's slabs ignores them.
 #include "abft_device.h"
 #include "gemm_args.h"
 #include "gemm_epilogue.h"
@@ -182,7 +185,12 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         }
         issue_loads(0, 0);
         issue_loads(1, 1);
-        __syncthreads();
+        // Start as soon as slab 0 is in place: loads complete in order, so "at most the GA + GB
+        // loads of slab 1 outstanding" means everything issued before them has landed.  (The
+        // barrier inside slab 0 waits for the rest.)
+        if constexpr (GA + GB == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else if constexpr (GA + GB == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else __syncthreads();
         ldfr(0, 0, 0);
         auto slab = [&](auto first_c, auto loads_c, int s) __attribute__((always_inline)) {
             constexpr bool LOADS = decltype(loads_c)::value;

@@ -89,7 +89,7 @@ SHAPES = [
     (197, 768, 768, 1, True),      # ViT-B projection at batch 1 (the small configuration)
     (300, 200, 264, 1, True),      # several tiles, ragged M/N, ragged K slab
     (257, 130, 72, 2, True),
-    (128, 128, 128, 1, True),      # tile-exact: stripe needs an extra tile row and column
+    (128, 128, 128, 1, True),      # tile-exact
     (1, 1, 1, 1, True),
     (197, 197, 64, 3, True),       # per-head Q K^T
     (197, 64, 197, 3, False),      # per-head attn V (B stored K x N)
