@@ -139,47 +139,59 @@ def main():
     ms_verify = t_verify(50)
     c_bytes = M * N * 2
     flips = gen.gen_flips(args.flips, M, N, dtype, gen.seed_for(1, 9))
-    tau_dev = float(run.ws(ab.ABFT_WS_TAU)[0, 0])
-    C_clean = run.dC.clone()
-    C_host = run.C()[0]
 
     def bf16_val(bits):
         return float((np.array([bits], dtype=np.uint32) << 16).view(np.float32)[0])
 
-    # strata of the campaign: S0 all flips; S1 |delta| > tau or non-finite (what the check is
-    # specified to catch); S2 |delta| > 1e-2 * max|C| (flip breaks the 1e-2 acceptance band)
-    cmax = float(np.max(np.abs((C_host.astype(np.uint32) << 16).view(np.float32))))
-    strata = {"S0": [0, 0], "S1": [0, 0], "S2": [0, 0]}          # [injected, detected]
-    borderline = 0                                               # tau / 2 < |delta| <= 2 tau
-    detected = localised = restored = 0
-    t_corr = 0.0
-    for (_, i, j, bit) in flips:
-        i, j, bit = int(i), int(j), int(bit)
-        old = bf16_val(int(C_host[i, j]))
-        new = bf16_val(int(C_host[i, j]) ^ (1 << bit))
-        delta = abs(new - old) if np.isfinite(new) else float("inf")
-        run.inject(0, i, j, bit)
-        run.verify()
-        rf, cf = run.flags()
-        hit = bool(rf.any() or cf.any())
-        borderline += int(0.5 * tau_dev < delta <= 2.0 * tau_dev)
-        for name, cond in (("S0", True), ("S1", delta > tau_dev), ("S2", delta > 1e-2 * cmax)):
-            if cond:
-                strata[name][0] += 1
-                strata[name][1] += int(hit)
-        if hit:
-            detected += 1
-            if rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]:
-                localised += 1
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            ab.abft_correct(ctx, run.dA, run.dB, run.dC, run.code, run.shape, res)
-            torch.cuda.synchronize()
-            t_corr += time.perf_counter() - t0
-            if torch.equal(run.dC, C_clean):
-                restored += 1
-        run.dC.copy_(C_clean)
-    us_correct = (t_corr / max(detected, 1)) * 1e6
+    def campaign(mode, tol_factor):
+        """stored-C flips, each applied alone: inject, verify, correct, check restored.
+        Strata: S0 all flips; S1 |delta| > the check's tolerance or non-finite (what the check
+        is specified to catch); S2 |delta| > 1e-2 * max|C| (flip breaks the 1e-2 acceptance band)."""
+        step(mode)
+        tau_dev = float(run.ws(ab.ABFT_WS_TAU)[0, 0])
+        tol = tol_factor * tau_dev
+        C_clean = run.dC.clone()
+        C_host = run.C()[0]
+        cmax = float(np.max(np.abs((C_host.astype(np.uint32) << 16).view(np.float32))))
+        strata = {"S0": [0, 0], "S1": [0, 0], "S2": [0, 0]}          # [injected, detected]
+        borderline = 0                                               # tol / 2 < |delta| <= 2 tol
+        detected = localised = restored = 0
+        t_corr = 0.0
+        for (_, i, j, bit) in flips:
+            i, j, bit = int(i), int(j), int(bit)
+            old = bf16_val(int(C_host[i, j]))
+            new = bf16_val(int(C_host[i, j]) ^ (1 << bit))
+            delta = abs(new - old) if np.isfinite(new) else float("inf")
+            run.inject(0, i, j, bit)
+            run.verify()
+            rf, cf = run.flags()
+            hit = bool(rf.any() or cf.any())
+            borderline += int(0.5 * tol < delta <= 2.0 * tol)
+            for name, cond in (("S0", True), ("S1", delta > tol), ("S2", delta > 1e-2 * cmax)):
+                if cond:
+                    strata[name][0] += 1
+                    strata[name][1] += int(hit)
+            if hit:
+                detected += 1
+                if rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]:
+                    localised += 1
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ab.abft_correct(ctx, run.dA, run.dB, run.dC, run.code, run.shape, res)
+                torch.cuda.synchronize()
+                t_corr += time.perf_counter() - t0
+                if torch.equal(run.dC, C_clean):
+                    restored += 1
+            run.dC.copy_(C_clean)
+        us = (t_corr / max(detected, 1)) * 1e6
+        return {"injected": len(flips), "detected": detected, "localised": localised, "restored": restored,
+                "us_per_correction": us, "correction_pct_of_step": 100.0 * us * 1e-3 / ms_prot,
+                "tolerance": tol, "tau": tau_dev, "max_abs_C": cmax,
+                "strata_injected_detected": strata, "borderline_within_2x_tolerance": borderline}
+
+    camp = campaign(ab.ABFT_DETECT, 1.0)
+    camp_sto = campaign(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS, 1e-2)
+    ms_sto = timed(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS, args.steps, 5)
 
     out = {
         "metric": "protected GEMM TFLOP/s (useful 2MNK only; every ABFT kernel in the timed region)",
@@ -212,14 +224,13 @@ def main():
             "frac_of_peak_whole_step": flops / (ms_prot * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
             "false_positive_flags_clean": int(cnt[0] + cnt[1]),
             "verify_ms": ms_verify, "verify_GBps": c_bytes / (ms_verify * 1e-3) / 1e9,
-            "flips": {"injected": len(flips), "detected": detected, "localised": localised,
-                      "restored": restored, "us_per_correction": us_correct,
-                      "correction_pct_of_step": 100.0 * us_correct * 1e-3 / ms_prot,
-                      "tau": tau_dev, "max_abs_C": cmax,
-                      "strata_injected_detected": strata, "borderline_within_2x_tau": borderline,
-                      "note": "stored-C single-bit flips, exponent/mantissa 50/50, each applied alone; "
-                              "S1 = |delta| > tau or non-finite (the gating stratum), S2 = |delta| > "
-                              "1e-2 max|C|; flips with |delta| <= tau are undetectable by construction"},
+            "flips": dict(camp, note="stored-C single-bit flips, exponent/mantissa 50/50, each applied alone; "
+                          "S1 = |delta| > tolerance or non-finite (the gating stratum), S2 = |delta| > "
+                          "1e-2 max|C|; flips with |delta| <= tolerance are undetectable by construction"),
+            "stored_sums_mode": dict(camp_sto, ms_per_step=ms_sto,
+                                     note="same flips with ABFT_STORED_SUMS: verify also compares the re-summed "
+                                          "stored C with the epilogue's sums of the rounded values, tolerance "
+                                          "1e-2 tau"),
         },
     }
 

@@ -64,6 +64,14 @@ enum {
     ABFT_DETECT         = 1,    /* encode, predicted + observed checksums, compare, flags */
     ABFT_DETECT_CORRECT = 2,    /* DETECT, then the steps of abft_correct */
     ABFT_MODE_MASK      = 0xF,
+    ABFT_STORED_SUMS    = 0x20, /* floating point: the GEMM epilogue also sums the values of C as
+                                   they are stored (after rounding); abft_verify / abft_correct then
+                                   flag, besides |stored sums - prediction| > tau, any row or column
+                                   whose re-summed stored C differs from those sums by more than
+                                   1e-2 tau (only the order of fp32 summation separates the two, so a
+                                   flip in stored C shows far below tau).  Ignored for ABFT_I8, where
+                                   the stored values are the accumulators, and not kept with
+                                   ABFT_DETECT_CORRECT (a correction replaces summed values). */
     ABFT_B_CHECKSUM_CACHED = 0x10 /* reuse the encoding of B left in the context by abft_encode_b
                                      (or by the previous abft_gemm with the same B and shape):
                                      the paper's offline weight checksum */
@@ -129,7 +137,9 @@ typedef enum {
     ABFT_WS_RC_VOBS = 7,  /* C e   re-summed from stored C by abft_verify [batch][M] */
     ABFT_WS_TAU     = 8,  /* tolerance in use [batch] float (floating point only) */
     ABFT_WS_S_PRED  = 9,  /* scalar a.b [batch] (the paper's own scalar check value) */
-    ABFT_WS_MAXABS  = 10  /* max|A|, max|B| [batch][2] float (floating point only) */
+    ABFT_WS_MAXABS  = 10, /* max|A|, max|B| [batch][2] float (floating point only) */
+    ABFT_WS_CC_STO  = 11, /* e^T C of the values as stored, from the GEMM epilogue (ABFT_STORED_SUMS) [batch][N] */
+    ABFT_WS_RC_STO  = 12  /* C e   of the values as stored [batch][M] */
 } abft_ws_id;
 
 /* where a flip lands */

@@ -331,3 +331,26 @@ def check(P: Protected, X_stored: np.ndarray):
         row_flag = flags_fp(rc_obs, P.rc_pred, P.tau)
     E, status = localise(row_flag, col_flag)
     return row_flag, col_flag, E, status, cc_obs, rc_obs
+
+
+STO_TOL_FACTOR = 1e-2
+
+
+def check_stored(P: Protected, X_stored: np.ndarray):
+    """The tightened storage check (floating point): flag a row / column of a stored output when
+    its sum differs from the prediction by more than tau (as `check` does) OR from the sum of the
+    clean stored output P.C_stored by more than STO_TOL_FACTOR * tau.  Both of the latter are
+    sums of rounded values, exact here (fp64), so the difference is the corruption itself;
+    the factor leaves room for the fp32 summation order of an implementation.
+    (Sec. III-B.1: the sum of the layer's activations is the checked quantity; which reference
+    it is compared with is this build's reading, see the list of readings.)
+
+    Returns (row_flag, col_flag, E, status)."""
+    assert P.dtype != "i8"
+    row_flag, col_flag, _, _, cc_obs, rc_obs = check(P, X_stored)
+    cc_sto, rc_sto, _ = observe(decode_stored(P.C_stored, P.dtype))
+    col_flag = col_flag | flags_fp(cc_obs, cc_sto, STO_TOL_FACTOR * P.tau)
+    row_flag = row_flag | flags_fp(rc_obs, rc_sto, STO_TOL_FACTOR * P.tau)
+    E, status = localise(row_flag, col_flag)
+    return row_flag, col_flag, E, status
+

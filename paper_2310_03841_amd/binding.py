@@ -15,11 +15,11 @@ _LIB_PATH = os.path.join(_HERE, "libabft.so")
 
 __all__ = [
     "ABFT_I8", "ABFT_BF16", "ABFT_F16", "ABFT_OFF", "ABFT_DETECT", "ABFT_DETECT_CORRECT",
-    "ABFT_B_CHECKSUM_CACHED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
+    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
     "ABFT_EHIP", "ABFT_ESTATE", "ABFT_CLEAN", "ABFT_LOCALISED", "ABFT_CHECKSUM_SUSPECT", "ABFT_TOO_MANY",
     "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR",
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
-    "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS",
+    "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS", "ABFT_WS_CC_STO", "ABFT_WS_RC_STO",
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
     "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_verify", "abft_correct",
     "abft_inject", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
@@ -30,11 +30,13 @@ ABFT_I8, ABFT_BF16, ABFT_F16 = 0, 1, 2
 DTYPE_CODE = {"i8": ABFT_I8, "bf16": ABFT_BF16, "f16": ABFT_F16}
 ABFT_OFF, ABFT_DETECT, ABFT_DETECT_CORRECT = 0, 1, 2
 ABFT_B_CHECKSUM_CACHED = 0x10
+ABFT_STORED_SUMS = 0x20
 ABFT_OK, ABFT_EINVAL, ABFT_EALIGN, ABFT_ESHAPE, ABFT_EWORKSPACE, ABFT_EHIP, ABFT_ESTATE = 0, -1, -2, -3, -4, -5, -6
 ABFT_CLEAN, ABFT_LOCALISED, ABFT_CHECKSUM_SUSPECT, ABFT_TOO_MANY = 0, 1, 2, 3
 ABFT_INJECT_STORED_C, ABFT_INJECT_ACCUMULATOR = 0, 1
 (ABFT_WS_A_SUM, ABFT_WS_B_SUM, ABFT_WS_CC_PRED, ABFT_WS_RC_PRED, ABFT_WS_CC_OBS, ABFT_WS_RC_OBS,
- ABFT_WS_CC_VOBS, ABFT_WS_RC_VOBS, ABFT_WS_TAU, ABFT_WS_S_PRED, ABFT_WS_MAXABS) = range(11)
+ ABFT_WS_CC_VOBS, ABFT_WS_RC_VOBS, ABFT_WS_TAU, ABFT_WS_S_PRED, ABFT_WS_MAXABS,
+ ABFT_WS_CC_STO, ABFT_WS_RC_STO) = range(13)
 
 
 class abft_shape(ctypes.Structure):

@@ -22,7 +22,7 @@ struct abft_ctx {
     InjectArm arm;
     int last_hip;
     // what the context currently holds
-    bool b_valid, pred_valid;
+    bool b_valid, pred_valid, sto_valid;
     int b_dt, pred_dt;
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
@@ -77,7 +77,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
         {(void **)&c->pool_depth, (ENC_ACC_COPIES + 1) * D * 4},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_cols, Cn * 4},
-        {(void **)&c->pool_obs, (Cn + 2 * R + D + Bt) * 4},
+        {(void **)&c->pool_obs, (2 * Cn + 3 * R + D + Bt) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
         {(void **)&c->small, 8 * 4},
@@ -168,7 +168,9 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->rc_pred = w->rc_obs + bM;
     w->a_sum = w->rc_pred + bM;
     w->a_max = w->a_sum + bK;
-    w->zero_words = bN + 2 * bM + bK + (size_t)s.batch;
+    w->cc_sto = w->a_max + s.batch;
+    w->rc_sto = w->cc_sto + bN;
+    w->zero_words = 2 * bN + 3 * bM + bK + (size_t)s.batch;
     w->cc_vobs = c->pool_vobs;
     w->rc_vobs = c->pool_vobs + bN;
     w->fix_tiles = c->fix_tiles;
@@ -224,7 +226,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return ABFT_EALIGN;
     const int base = mode & ABFT_MODE_MASK;
     if (base != ABFT_OFF && base != ABFT_DETECT && base != ABFT_DETECT_CORRECT) return ABFT_EINVAL;
-    if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED)) return ABFT_EINVAL;
+    if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED | ABFT_STORED_SUMS)) return ABFT_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     Workspace w;
     carve(ctx, dtype, sh, &w);
@@ -235,7 +237,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         ctx->arm.batch = -1;
         hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
         if (ev) { HIP_TRY(hipEventRecord(ev[0], st)); HIP_TRY(hipEventRecord(ev[1], st)); }
-        HIP_TRY(launch_gemm(dtype, false, A, B, C, sh, w, arm, st));
+        HIP_TRY(launch_gemm(dtype, false, false, A, B, C, sh, w, arm, st));
         if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
         return ABFT_OK;
     }
@@ -253,7 +255,9 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, w.zero_words, st));
     else HIP_TRY(launch_zero(w.cc_obs, w.zero_words, st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-    HIP_TRY(launch_gemm(dtype, true, A, B, C, sh, w, arm, st));
+    const bool stored = (mode & ABFT_STORED_SUMS) != 0;
+    ctx->sto_valid = false;
+    HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
     HIP_TRY(launch_finish(dtype, B, sh, w, v, st));
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
@@ -263,7 +267,9 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_valid = true;
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
-    if (base == ABFT_DETECT_CORRECT) HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, st));
+    // a correction inside this call replaces values the stored-side sums already contain
+    ctx->sto_valid = stored && base == ABFT_DETECT;
+    if (base == ABFT_DETECT_CORRECT) HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, st));
     return ABFT_OK;
 }
 
@@ -284,7 +290,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     carve(ctx, dtype, sh, &w);
     HIP_TRY(launch_zero(w.cc_vobs, (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
-    HIP_TRY(launch_compare(dtype, sh, w, v, false, st));
+    HIP_TRY(launch_compare(dtype, sh, w, v, false, ctx->sto_valid, st));
     return ABFT_OK;
 }
 
@@ -302,7 +308,7 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, (hipStream_t)stream));
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, (hipStream_t)stream));
     return ABFT_OK;
 }
 
@@ -349,6 +355,8 @@ extern "C" int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, voi
     case ABFT_WS_TAU:     *ptr = w.tau;     *count = b; break;
     case ABFT_WS_S_PRED:  *ptr = w.s_pred;  *count = b; break;
     case ABFT_WS_MAXABS:  *ptr = w.maxabs;  *count = 2 * b; break;
+    case ABFT_WS_CC_STO:  *ptr = w.cc_sto;  *count = b * sh.N; break;
+    case ABFT_WS_RC_STO:  *ptr = w.rc_sto;  *count = b * sh.M; break;
     default: return ABFT_EINVAL;
     }
     return ABFT_OK;

@@ -14,6 +14,9 @@ constexpr int CT = 32;
 constexpr int MAX_FIX_TILES = 256;
 // Copies of the encode accumulators (spreads same-cache-line atomics).
 constexpr int ENC_ACC_COPIES = 8;
+// Tolerance of the stored-side comparison relative to tau: both sides are fp32 sums of the same
+// rounded values, so only the order of summation separates them.
+constexpr float STO_TOL_FACTOR = 1e-2f;
 // Most flagged rows (columns) per batch item that localisation lists.
 constexpr int MAX_LIST = 64;
 
@@ -39,10 +42,12 @@ struct Workspace {
     uint32_t *s_pred;               // [batch]
     // one region that must be zero before the protected GEMM, filled by its atomics:
     //   cc_obs [batch][N] | rc_obs [batch][M] | rc_pred [batch][M] | a_sum [batch][K] | a_max [batch]
+    //   | cc_sto [batch][N] | rc_sto [batch][M]
     uint32_t *cc_obs, *rc_obs;      // observed sums of C (epilogue)
     uint32_t *rc_pred;              // A (B e), from the operand slabs of A in LDS
     uint32_t *a_sum;                // a = e^T A, from the same slabs
     uint32_t *a_max;                // max|A| (float bits)
+    uint32_t *cc_sto, *rc_sto;      // sums of C as stored (floating point, on request)
     size_t zero_words;              // words from cc_obs on
     uint32_t *cc_vobs, *rc_vobs;    // re-summed from stored C
     // correction
@@ -74,15 +79,18 @@ hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspac
 int protect_max_k(int dt);
 // protect: A-side checksums and observed sums are produced by the kernel (atomics into the
 // zeroed region of the workspace); launch_finish turns them into flags.
-hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
-                       const Workspace &w, const InjectArm &arm, hipStream_t st);
+// stored_sums: also accumulate the row / column sums of the rounded values that are stored
+hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, const void *B, void *C,
+                       const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st);
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
                          hipStream_t st);
+// with_sto: a row / column also flags when the re-summed stored C differs from the stored-side
+// sums of the GEMM by more than STO_TOL_FACTOR * tau
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          hipStream_t st);
+                          bool with_sto, hipStream_t st);
 hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st);
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, hipStream_t st);
+                          const Workspace &w, const Verdict &v, bool with_sto, hipStream_t st);
 hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,
                        hipStream_t st);
 void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn);

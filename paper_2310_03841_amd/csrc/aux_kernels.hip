@@ -247,6 +247,7 @@ struct CmpArgs {
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
     const uint32_t *fix_count;   // non-null after a correction: [0] tiles listed, [1] overflow
+    const uint32_t *cc_sto, *rc_sto;   // non-null: stored-side sums of the GEMM (floating point)
     int M, N, batch;
 };
 
@@ -276,10 +277,14 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     bool frow = false, fcol = false;
     if (idx < M) {
         frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], a.rc_pred[(long)bz * M + idx], tol);
+        if (!IS_INT && a.rc_sto)
+            frow = frow || mismatch<false>(a.rc_obs[(long)bz * M + idx], a.rc_sto[(long)bz * M + idx], STO_TOL_FACTOR * tol);
         a.row_flag[(long)bz * M + idx] = frow ? 1 : 0;
     } else if (idx < M + N) {
         const int j = idx - M;
         fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], a.cc_pred[(long)bz * N + j], tol);
+        if (!IS_INT && a.cc_sto)
+            fcol = fcol || mismatch<false>(a.cc_obs[(long)bz * N + j], a.cc_sto[(long)bz * N + j], STO_TOL_FACTOR * tol);
         a.col_flag[(long)bz * N + j] = fcol ? 1 : 0;
     }
     const unsigned nr = __syncthreads_count(frow);
@@ -312,9 +317,11 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
 }
 
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          hipStream_t st)
+                          bool with_sto, hipStream_t st)
 {
     CmpArgs a;
+    a.cc_sto = (with_sto && dt != DT_I8) ? w.cc_sto : nullptr;
+    a.rc_sto = a.cc_sto ? w.rc_sto : nullptr;
     a.fix_count = after_fix ? w.fix_count : nullptr;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
     a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
@@ -787,7 +794,7 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
 }
 
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, hipStream_t st)
+                          const Workspace &w, const Verdict &v, bool with_sto, hipStream_t st)
 {
     hipError_t e = launch_zero(w.fix_count, 2, st);
     if (e != hipSuccess) return e;
@@ -813,7 +820,7 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     // than strided column walks over the touched tiles) and compared with the predictions
     if ((e = launch_zero(w.cc_vobs, (size_t)s.batch * ((size_t)s.M + s.N), st)) != hipSuccess) return e;
     if ((e = launch_verify_sums(dt, C, s, w, st)) != hipSuccess) return e;
-    return launch_compare(dt, s, w, v, true, st);
+    return launch_compare(dt, s, w, v, true, with_sto, st);
 }
 
 // ====================================================================== inject

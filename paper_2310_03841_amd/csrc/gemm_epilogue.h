@@ -82,6 +82,14 @@ template <> __device__ __forceinline__ uint32_t pack2<DT_F16>(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
 }
 
+// The value an accumulator becomes in memory, back as a float (round to nearest even).
+template <int DT> __device__ __forceinline__ float stored_value(float v)
+{
+    const uint32_t w = pack2<DT>(v, 0.f) & 0xFFFFu;
+    if constexpr (DT == DT_BF16) return __uint_as_float(w << 16);
+    else return f16_bits_to_f32(w);
+}
+
 // What a protected tile hands to the epilogue besides its accumulators.
 template <int DT> struct EpiProt {
     APassState<DT> st;        // row dots and max|A| of the owned slabs
@@ -132,6 +140,16 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     // this lane's rows) and of the groups that were walked row by row (columns CPL*lane ..)
     acc_t cp[PROT ? NI : 1][16];
     acc_t colacc[CPL];
+    // sums of the values as stored (after rounding), on request and for floating point only:
+    // edge groups add to these while they walk their rows, register-path groups in a second
+    // pass over the accumulators further down
+    const bool sto = PROT && !T::IS_INT && g.cc_sto != nullptr;
+    float colacc_s[CPL], rowsto[MI];
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) colacc_s[j] = 0.f;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) rowsto[mi] = 0.f;
+    bool reg_path[MI];
     if (PROT) {
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni)
@@ -144,6 +162,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     static_for<0, MI>([&](auto mi_c) {
         constexpr int mi = decltype(mi_c)::value;
         const int br = wr0 + mi * 32;                                      // first row of this 32-row group
+        reg_path[mi] = cols_full && br + 32 <= M;
         if (cols_full && br + 32 <= M) {
             // ---- register path: one read of every accumulator serves the sums and the store
             acc_t rowsum = T::zero();
@@ -213,8 +232,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
             }
             const int nrow = M - br < 32 ? M - br : 32;
             acc_t myrow = T::zero();
+            float myrow_s = 0.f;
             for (int r = 0; r < nrow; ++r) {
                 acc_t rs = T::zero();
+                float rs_s = 0.f;
 #pragma unroll
                 for (int j = 0; j < CPL; ++j) {
                     const int col = CPL * lane + j, gc = wc0 + col;
@@ -222,15 +243,27 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                         const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + col * 4));
                         T::store_c(Cb, (long)(br + r) * g.ldc + gc, v);
                         if (PROT) { colacc[j] = add_t(colacc[j], v); rs = add_t(rs, v); }
+                        if constexpr (PROT && !T::IS_INT) {
+                            if (sto) {
+                                const float sv = stored_value<DT>((float)v);
+                                colacc_s[j] += sv;
+                                rs_s += sv;
+                            }
+                        }
                     }
                 }
                 if (PROT) {
                     rs = wave_sum(rs);
                     if (lane == r) myrow = rs;
+                    if (!T::IS_INT && sto) {
+                        rs_s = wave_sum(rs_s);
+                        if (lane == r) myrow_s = rs_s;
+                    }
                 }
             }
             if (PROT && lane < 32) {
                 rs_part[wn * BM + wm * TM + mi * 32 + lane] = myrow;
+                if (!T::IS_INT && sto) rowsto[mi] = myrow_s;           // lanes 0..31: row mi * 32 + lane
             }
             wave_sync();
         } else if (PROT) {
@@ -266,6 +299,73 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
         }
 #pragma unroll
         for (int j = 0; j < CPL; ++j) cs_part[wm * BN + wn * TN + CPL * lane + j] = colacc[j];
+        if constexpr (!T::IS_INT) {
+            if (sto) {
+                // ---- stored-side sums of the register-path groups: second pass over the
+                // accumulators, each value rounded as the store above rounded it
+#pragma unroll
+                for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) cp[PROT ? ni : 0][i] = T::zero();
+                static_for<0, MI>([&](auto mi_c) {
+                    constexpr int mi = decltype(mi_c)::value;
+                    if (reg_path[mi]) {
+                        float rsum = 0.f;
+                        static_for<0, NI>([&](auto ni_c) {
+                            constexpr int ni = decltype(ni_c)::value;
+                            static_for<0, 8>([&](auto h_c) {
+                                constexpr int h = decltype(h_c)::value;
+                                const uint32_t w = pack2<DT>((float)acc_read(acc[mi][ni][2 * h]),
+                                                             (float)acc_read(acc[mi][ni][2 * h + 1]));
+                                float s0, s1;
+                                if constexpr (DT == DT_BF16) {
+                                    s0 = __uint_as_float(w << 16);
+                                    s1 = __uint_as_float(w & 0xFFFF0000u);
+                                } else {
+                                    s0 = f16_bits_to_f32(w & 0xFFFFu);
+                                    s1 = f16_bits_to_f32(w >> 16);
+                                }
+                                cp[PROT ? ni : 0][2 * h] = add_t(cp[PROT ? ni : 0][2 * h], (acc_t)s0);
+                                cp[PROT ? ni : 0][2 * h + 1] = add_t(cp[PROT ? ni : 0][2 * h + 1], (acc_t)s1);
+                                rsum += s0 + s1;
+                            });
+                            __builtin_amdgcn_sched_barrier(0);
+                        });
+                        rsum += __shfl_xor(rsum, 32);
+                        rowsto[mi] = rsum;                              // lanes 0..31: row mi * 32 + lane
+                    }
+                });
+                wave_sync();
+                static_for<0, NI>([&](auto ni_c) {
+                    constexpr int ni = decltype(ni_c)::value;
+                    static_for<0, 4>([&](auto q_c) {
+                        constexpr int q = decltype(q_c)::value;
+                        uint8_t *d = wbuf + l32 * SROW + (ni * 32 + 8 * q + 4 * lh) * 4;
+                        *reinterpret_cast<i32x4 *>(d) =
+                            i32x4{(int)as_word(cp[PROT ? ni : 0][4 * q]), (int)as_word(cp[PROT ? ni : 0][4 * q + 1]),
+                                  (int)as_word(cp[PROT ? ni : 0][4 * q + 2]), (int)as_word(cp[PROT ? ni : 0][4 * q + 3])};
+                    });
+                });
+                wave_sync();
+                for (int r = 0; r < 32; ++r)
+#pragma unroll
+                    for (int j = 0; j < CPL; ++j)
+                        colacc_s[j] += __uint_as_float(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + (CPL * lane + j) * 4));
+                // one atomic per row / column of the wave tile (two waves share each)
+                if (lane < 32) {
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) {
+                        const int gr = wr0 + mi * 32 + lane;
+                        if (gr < M) unsafeAtomicAdd(reinterpret_cast<float *>(g.rc_sto) + (long)bz * M + gr, rowsto[mi]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < CPL; ++j) {
+                    const int gc = wc0 + CPL * lane + j;
+                    if (gc < N) unsafeAtomicAdd(reinterpret_cast<float *>(g.cc_sto) + (long)bz * N + gc, colacc_s[j]);
+                }
+            }
+        }
         // ---- what the pass over A's slabs left in registers
         {
             constexpr int P = BM / 32;

@@ -271,8 +271,8 @@ void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
     *tn = 128;
 }
 
-hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void *C, const Shape &s,
-                       const Workspace &w, const InjectArm &arm, hipStream_t st)
+hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, const void *B, void *C,
+                       const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st)
 {
     GemmArgs g;
     g.A = (const uint8_t *)A;
@@ -284,6 +284,8 @@ hipError_t launch_gemm(int dt, bool protect, const void *A, const void *B, void 
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
     g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred;
     g.a_sum = w.a_sum; g.a_max = w.a_max; g.b_sum = w.b_sum;
+    g.cc_sto = (protect && stored_sums && dt != DT_I8) ? w.cc_sto : nullptr;
+    g.rc_sto = g.cc_sto ? w.rc_sto : nullptr;
     g.mul24_ok = s.N < 65536 ? 1 : 0;            // |b| <= 128 N
     g.tiles_m = g.tiles_n = g.n_big = g.tiles_m_big = g.tiles_m_small = 0;
     const bool tb = s.transB != 0;

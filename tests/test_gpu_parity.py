@@ -190,6 +190,67 @@ def test_stored_flip_verify_correct(ctx, dtype, M, N, K, batch, trans_b):
     assert n_border <= len(flips) // 2
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(600, 520, 256, 1, True), (197, 768, 768, 1, True),
+                                                  (130, 70, 100, 2, False)])
+def test_tightened_storage_check(ctx, dtype, M, N, K, batch, trans_b):
+    """ABFT_STORED_SUMS: the epilogue's sums of the rounded values equal the oracle's sums of the
+    stored clean C; verify then flags stored flips down to 1e-2 tau, as the oracle's check_stored."""
+    A, B = gen.gen_operands(dtype, M, N, K, 61, 62, trans_b=trans_b, batch=batch)
+    run = Run(ctx, dtype, A, B, trans_b)
+    P = oracle_items(dtype, A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    C_clean = run.C().copy()
+    cc_sto, rc_sto = run.ws(ab.ABFT_WS_CC_STO), run.ws(ab.ABFT_WS_RC_STO)
+    for bi in range(batch):
+        # the oracle's stored C and the device's may differ in a few last-place roundings: sum the device's
+        X = orc.decode_stored(C_clean[bi], dtype)
+        cc, rc, _ = orc.observe(X)
+        tol = 1e-2 * orc.STO_TOL_FACTOR * P[bi].tau
+        assert np.max(np.abs(cc_sto[bi] - cc)) <= tol * np.sqrt(M)
+        assert np.max(np.abs(rc_sto[bi] - rc)) <= tol * np.sqrt(N)
+    run.verify()
+    rf, cf = run.flags()
+    assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+    flips = gen.gen_flips(40, M, N, dtype, 777, batch=batch)
+    n_border = n_tight_only = 0
+    for (bi, i, j, bit) in flips:
+        bi, i, j, bit = int(bi), int(i), int(j), int(bit)
+        print(f"flip dtype={dtype} b={bi} i={i} j={j} bit={bit}", flush=True)
+        Xc = P[bi].C_stored
+        X = orc.flip(Xc, i, j, bit)
+        with np.errstate(all="ignore"):
+            delta = abs(orc.decode(X, dtype)[i, j] - orc.decode(Xc, dtype)[i, j])
+        orf, ocf, E, status = orc.check_stored(P[bi], X)
+        t_sto = orc.STO_TOL_FACTOR * P[bi].tau
+        if t_sto / 2 <= delta <= 2 * t_sto or P[bi].tau / 2 <= delta <= 2 * P[bi].tau:
+            n_border += 1
+            continue
+        run.inject(bi, i, j, bit)
+        run.verify()
+        rf, cf = run.flags()
+        cnt = run.cnt()
+        big = status == orc.LOCALISED
+        want_rf = np.zeros((batch, M), bool)
+        want_cf = np.zeros((batch, N), bool)
+        want_rf[bi], want_cf[bi] = orf, ocf
+        if big:
+            assert E == [(i, j)]
+            n_tight_only += int(delta <= P[bi].tau / 2)
+        assert np.array_equal(rf, want_rf) and np.array_equal(cf, want_cf), (bit, delta, t_sto)
+        assert cnt[0] == orf.sum() and cnt[1] == ocf.sum() and cnt[2] == status
+        run.correct()
+        if big:
+            cnt = run.cnt()
+            assert cnt[3] == 1 and cnt[2] == ab.ABFT_CLEAN
+            assert np.array_equal(run.C(), C_clean), "C not restored"
+        else:
+            run.dC.copy_(torch.from_numpy(_with_ld(C_clean, run)).to("cuda"))
+    assert n_border <= len(flips) // 2 and n_tight_only > 0
+
+
 def _with_ld(C, run):
     full = np.zeros((run.batch, run.M, run.ldc), dtype=np.int32 if run.dtype == "i8" else np.int16)
     full[:, :, :run.N] = C.view(full.dtype)

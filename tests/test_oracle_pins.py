@@ -268,3 +268,36 @@ def test_operation_count_overhead_matches_papers_claim():
     assert ratio(12608, 3072, 768) == pytest.approx(0.0019, abs=1e-4)   # "< 0.2 %" (abstract)
     for (M, N, K) in [(6304, 2304, 768), (6304, 768, 768), (6304, 3072, 768), (6304, 768, 3072)]:
         assert 0.001 < ratio(M, N, K) < 0.0036
+
+
+def test_tightened_storage_check_flags_exactly_the_flips_above_its_tolerance():
+    """check_stored: a flip of stored C shows in its row and column sum with its full size delta
+    (linearity, as in P5), so it must be flagged iff |delta| > 1e-2 tau (or non-finite), also
+    where the plain check (tolerance tau) stays silent; the clean output never flags."""
+    dtype = "bf16"
+    M, N, K = 40, 48, 64
+    A, B = gen.gen_operands(dtype, M, N, K, 41, 42, trans_b=True)
+    P = orc.protected_gemm(A[0], B[0], dtype, True)
+    rf, cf, E, status = orc.check_stored(P, P.C_stored)
+    assert status == orc.CLEAN and not rf.any() and not cf.any()
+    clean = orc.decode(P.C_stored, dtype)
+    seen_small = seen_mid = 0
+    for bit in range(15):
+        for (i, j) in ((0, 0), (17, 5), (39, 47)):
+            X = orc.flip(P.C_stored, i, j, bit)
+            with np.errstate(all="ignore"):
+                delta = abs(orc.decode(X, dtype)[i, j] - clean[i, j])
+            rf, cf, E, status = orc.check_stored(P, X)
+            rf0, cf0, _, status0, _, _ = orc.check(P, X)
+            big = not (delta <= orc.STO_TOL_FACTOR * P.tau)
+            if big:
+                assert status == orc.LOCALISED and E == [(i, j)], (bit, i, j, delta)
+            else:
+                assert status == orc.CLEAN
+                seen_small += 1
+            if big and delta <= P.tau * 0.5:
+                assert status0 == orc.CLEAN          # the plain check cannot see it
+                seen_mid += 1
+            assert (rf | rf0 == rf).all() and (cf | cf0 == cf).all()   # never weaker than the plain check
+    assert seen_small > 0 and seen_mid > 0
+
