@@ -15,7 +15,11 @@ struct abft_ctx {
     uint32_t *pool_depth;   // (ENC_ACC_COPIES + 1) * max_depth words: b_acc copies, b_sum
     uint32_t *pool_batch;   // per-batch scalars
     uint32_t *pool_cols;    // cc_pred
-    uint32_t *pool_obs;     // cc_obs | rc_obs | rc_pred | a_sum | a_max (zeroed as one region)
+    uint32_t *pool_obs;     // two regions of cc_obs | rc_obs | rc_pred | a_sum | a_max | cc_sto | rc_sto:
+                            // protected GEMMs alternate between them; each must be clean before use
+    size_t region_words;    // words per region
+    int cur;                // region of the last protected GEMM
+    size_t dirty[2];        // leading words of each region that may be non-zero
     uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
     int32_t  *fix_tiles;
     uint32_t *small;        // fix_count[4], cmp_ticket[4]
@@ -77,7 +81,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
         {(void **)&c->pool_depth, (ENC_ACC_COPIES + 1) * D * 4},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_cols, Cn * 4},
-        {(void **)&c->pool_obs, (2 * Cn + 3 * R + D + Bt) * 4},
+        {(void **)&c->pool_obs, 2 * (2 * Cn + 3 * R + D + Bt) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
         {(void **)&c->small, 8 * 4},
@@ -93,6 +97,9 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     }
     e = hipDeviceSynchronize();
     if (e != hipSuccess) { int r = fail_hip(c, e); abft_destroy(c); return r; }
+    c->region_words = 2 * Cn + 3 * R + D + Bt;
+    c->cur = 0;
+    c->dirty[0] = c->dirty[1] = 0;
     *out = c;
     return ABFT_OK;
 }
@@ -162,8 +169,8 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->enc_ticket = pb;                       pb += Bt;
     w->s_pred = pb;
     w->cc_pred = c->pool_cols;
-    // one region that must be zero before the protected GEMM
-    w->cc_obs = c->pool_obs;
+    // the region the protected GEMM accumulates into (must be zero before it)
+    w->cc_obs = c->pool_obs + (size_t)c->cur * c->region_words;
     w->rc_obs = w->cc_obs + bN;
     w->rc_pred = w->rc_obs + bM;
     w->a_sum = w->rc_pred + bM;
@@ -251,15 +258,27 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->arm.batch = -1;
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
-    // pass over B (it also clears what the GEMM accumulates into), GEMM, finish
-    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, w.zero_words, st));
-    else HIP_TRY(launch_zero(w.cc_obs, w.zero_words, st));
+    // This call accumulates into the region the previous protected call did not use.  It is
+    // clean unless a call failed half way; the region of the previous call is cleared by this
+    // call's finish kernel.  So a call with a cached B checksum is two kernels: GEMM, finish.
+    const int prev = ctx->cur;
+    ctx->cur ^= 1;
+    carve(ctx, dtype, sh, &w);
+    uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
+    const size_t stale = ctx->dirty[ctx->cur];
+    ctx->dirty[ctx->cur] = ctx->region_words;            // until everything below is enqueued
+    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, stale, st));
+    else if (stale) HIP_TRY(launch_zero(w.cc_obs, stale, st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
     const bool stored = (mode & ABFT_STORED_SUMS) != 0;
     ctx->sto_valid = false;
     HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
-    HIP_TRY(launch_finish(dtype, B, sh, w, v, st));
+    const size_t prev_dirty = ctx->dirty[prev];
+    ctx->dirty[prev] = ctx->region_words;
+    HIP_TRY(launch_finish(dtype, B, sh, w, v, prev_base, prev_dirty, st));
+    ctx->dirty[prev] = 0;
+    ctx->dirty[ctx->cur] = w.zero_words;
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
     ctx->b_valid = true;
     ctx->b_dt = dtype;

@@ -82,8 +82,9 @@ int protect_max_k(int dt);
 // stored_sums: also accumulate the row / column sums of the rounded values that are stored
 hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, const void *B, void *C,
                        const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st);
+// zero_ptr / zero_words: a region every block of the kernel helps to clear (may be null / 0)
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
-                         hipStream_t st);
+                         uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
 // with_sto: a row / column also flags when the re-summed stored C differs from the stored-side
 // sums of the GEMM by more than STO_TOL_FACTOR * tau
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,

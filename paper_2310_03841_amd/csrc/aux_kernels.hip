@@ -354,6 +354,8 @@ struct FinArgs {
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
     int col_blocks;       // blocks [0, col_blocks) take columns, the rest rows
+    uint32_t *zero_ptr;   // region every block helps to clear: what the previous protected GEMM of this
+    size_t zero_words;    // context accumulated into, so that the next one finds it clean
 };
 
 constexpr int FIN_ROWS_B = 16;     // rows of a B stored N x K per column block (4 per wave)
@@ -374,6 +376,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     const int M = f.M, N = f.N, K = f.K;
     const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
     const uint32_t *asum = f.a_sum + (long)bz * K;
+    {
+        const size_t nb = (size_t)gridDim.x * gridDim.z;
+        const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
+        for (size_t i = bid * 256 + tid; i < f.zero_words; i += nb * 256) f.zero_ptr[i] = 0u;
+    }
 
     float tol = 0.f;
     if (!T::IS_INT) {
@@ -535,9 +542,10 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
 }
 
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
-                         hipStream_t st)
+                         uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
 {
     FinArgs f;
+    f.zero_ptr = zero_ptr; f.zero_words = zero_ptr ? zero_words : 0;
     f.B = (const uint8_t *)B; f.ldb = s.ldb; f.sB = s.sB; f.transB = s.transB;
     f.M = s.M; f.N = s.N; f.K = s.K;
     f.a_sum = w.a_sum; f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;

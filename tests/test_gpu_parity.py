@@ -309,6 +309,34 @@ def test_corrupted_checksum_is_one_sided(ctx):
     assert run.cnt()[3] == 0 and np.array_equal(run.C(), C_before)
 
 
+@pytest.mark.gpu
+def test_context_reuse_across_shapes_and_modes(ctx):
+    """Protected calls alternate between two accumulate regions and each call's finish kernel
+    clears the other one: whatever the order of shapes, dtypes and cached / uncached calls, a
+    clean GEMM must come out clean, with exact integer checksums."""
+    cases = [("i8", 300, 520, 256, True), ("bf16", 600, 640, 192, True), ("i8", 130, 70, 100, False),
+             ("i8", 640, 520, 384, True)]
+    runs = []
+    for k, (dtype, M, N, K, tb) in enumerate(cases):
+        A, B = gen.gen_operands(dtype, M, N, K, 71 + k, 81 + k, trans_b=tb)
+        runs.append((Run(ctx, dtype, A, B, tb), oracle_items(dtype, A, B, tb)[0], dtype))
+    order = [0, 1, 0, 0, 2, 3, 1, 3, 3, 2, 0]
+    last = None
+    for step_no, idx in enumerate(order):
+        run, P, dtype = runs[idx]
+        cached = (last == idx)                     # same B as the previous call: reuse its checksum
+        run.gemm(ab.ABFT_DETECT | (ab.ABFT_B_CHECKSUM_CACHED if cached else 0))
+        cnt = run.cnt()
+        assert cnt[2] == ab.ABFT_CLEAN and cnt[0] == 0 and cnt[1] == 0, (step_no, idx, cnt)
+        if dtype == "i8":
+            ring = lambda v: (np.asarray(v, dtype=np.int64) & 0xFFFFFFFF).astype(np.uint32)
+            for which, want in ((ab.ABFT_WS_CC_PRED, P.cc_pred), (ab.ABFT_WS_RC_PRED, P.rc_pred),
+                                (ab.ABFT_WS_CC_OBS, P.cc_pred), (ab.ABFT_WS_RC_OBS, P.rc_pred),
+                                (ab.ABFT_WS_A_SUM, P.a)):
+                assert np.array_equal(run.ws(which)[0].view(np.uint32), ring(want)), (step_no, which)
+        last = idx
+
+
 def test_argument_errors(ctx):
     A, B = gen.gen_operands("bf16", 64, 64, 64, 1, 2, trans_b=True)
     run = Run(ctx, "bf16", A, B, True)
