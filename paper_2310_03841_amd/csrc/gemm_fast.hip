@@ -14,6 +14,9 @@
 // Rows of the tile beyond the problem are fetched from a valid row instead of being
 // zero-filled: a row of A only influences the same row of C, which is discarded, and the pass
 // over A's slabs ignores them.
+#include <queue>
+#include <vector>
+
 #include "abft_device.h"
 #include "gemm_args.h"
 #include "gemm_epilogue.h"
@@ -262,6 +265,58 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
 // ------------------------------------------------------------------------------------------
 static int g_num_cu = 0;
 
+// How many tile rows get 256-row tiles (the rest of M gets 128-row tiles).  Workgroups are
+// dispatched in index order to whichever CU is free, one per CU; a 128 x 256 tile takes about
+// 0.62 of the time of a 256 x 256 tile (measured), not half: its main loop waits on the same
+// load latency per slab.  A few candidate splits are played through with those two costs and
+// the one that finishes first wins; the result is remembered per shape.
+static double play_schedule(int big_rows, int M, int tiles_n, int batch, int ncu)
+{
+    const int rest = M - big_rows * 256;
+    const long nb = (long)big_rows * tiles_n, ns = (long)(rest > 0 ? (rest + 127) / 128 : 0) * tiles_n;
+    std::priority_queue<double, std::vector<double>, std::greater<double>> cu;
+    for (int i = 0; i < ncu; ++i) cu.push(0.0);
+    double end = 0.0;
+    for (int z = 0; z < batch; ++z)
+        for (long t = 0; t < nb + ns; ++t) {
+            const double f = cu.top() + (t < nb ? 1.0 : 0.62);
+            cu.pop();
+            cu.push(f);
+            if (f > end) end = f;
+        }
+    return end;
+}
+
+static int choose_big_rows(int M, int tiles_n, int batch, int ncu)
+{
+    struct Memo { int M, tiles_n, batch, ncu, big_rows; };
+    static Memo memo[16];
+    static int memo_n = 0;
+    for (int i = 0; i < memo_n; ++i)
+        if (memo[i].M == M && memo[i].tiles_n == tiles_n && memo[i].batch == batch && memo[i].ncu == ncu)
+            return memo[i].big_rows;
+    const int rows_all_big = (M + 255) / 256;
+    const long per_row = (long)tiles_n * batch;
+    const long total_big = rows_all_big * per_row;
+    int cand[4], nc = 0;
+    cand[nc++] = rows_all_big;                                   // big tiles only
+    cand[nc++] = 0;                                              // half-height tiles only
+    long whole = (total_big / ncu) * ncu / per_row;              // whole rounds of big tiles
+    if (whole > rows_all_big) whole = rows_all_big;
+    cand[nc++] = (int)whole;
+    const long fewer = whole - (ncu + per_row - 1) / per_row;    // one round fewer
+    if (fewer > 0) cand[nc++] = (int)fewer;
+    int best = cand[0];
+    double best_t = play_schedule(cand[0], M, tiles_n, batch, ncu);
+    for (int i = 1; i < nc; ++i) {
+        const double t = play_schedule(cand[i], M, tiles_n, batch, ncu);
+        if (t < best_t - 1e-9) { best_t = t; best = cand[i]; }
+    }
+    Memo m = {M, tiles_n, batch, ncu, best};
+    memo[memo_n < 16 ? memo_n++ : (M + tiles_n) & 15] = m;
+    return best;
+}
+
 template <int DT, bool PROT>
 static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
 {
@@ -283,15 +338,7 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
         g_num_cu = n > 0 ? n : 256;
     }
     g.tiles_n = (g.N + 255) / 256;
-    const int rows_all_big = (g.M + 255) / 256;
-    const long total_big = (long)rows_all_big * g.tiles_n * batch;
-    int big_rows = rows_all_big;
-    if (total_big % g_num_cu != 0) {
-        // whole rounds of big tiles, the remainder of the rows in half-height tiles
-        const long rounds = total_big / g_num_cu;
-        big_rows = (int)((rounds * g_num_cu) / ((long)g.tiles_n * batch));
-        if (big_rows > rows_all_big) big_rows = rows_all_big;
-    }
+    const int big_rows = choose_big_rows(g.M, g.tiles_n, batch, g_num_cu);
     g.tiles_m_big = big_rows;
     g.n_big = big_rows * g.tiles_n;
     const int rest = g.M - big_rows * 256;
