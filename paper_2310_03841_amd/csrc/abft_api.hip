@@ -12,7 +12,10 @@ using namespace abft;
 struct abft_ctx {
     abft_config cfg;
     // device pools (32-bit words unless noted)
-    uint32_t *pool_depth;   // (ENC_ACC_COPIES + 1) * max_depth words: b_acc copies, b_sum
+    uint32_t *pool_depth;   // two slots of (max_depth + max_batch) words: b = B e, then max|B| per batch item
+    size_t bslot_words;     // words per slot
+    int bslot;              // slot that holds the b in use
+    bool bclean[2];         // slot is all zero
     uint32_t *pool_batch;   // per-batch scalars
     uint32_t *pool_cols;    // cc_pred
     uint32_t *pool_obs;     // two regions of cc_obs | rc_obs | rc_pred | a_sum | a_max | cc_sto | rc_sto:
@@ -34,7 +37,7 @@ struct abft_ctx {
     int prof_cap, prof_n;
 };
 
-static const int BATCH_WORDS = 2 /*max_acc*/ + 2 /*maxabs*/ + 1 /*tau*/ + 1 /*ticket*/ + 1 /*s_pred*/;
+static const int BATCH_WORDS = 2 /*maxabs*/ + 1 /*tau*/ + 1 /*s_pred*/;
 
 static int fail_hip(abft_ctx *c, hipError_t e)
 {
@@ -78,7 +81,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     const size_t D = (size_t)c->cfg.max_depth, R = (size_t)cfg->max_rows, Cn = (size_t)cfg->max_cols,
                  Bt = (size_t)cfg->max_batch;
     struct { void **p; size_t bytes; } req[] = {
-        {(void **)&c->pool_depth, (ENC_ACC_COPIES + 1) * D * 4},
+        {(void **)&c->pool_depth, 2 * (D + Bt) * 4},
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_cols, Cn * 4},
         {(void **)&c->pool_obs, 2 * (2 * Cn + 3 * R + D + Bt) * 4},
@@ -100,6 +103,9 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     c->region_words = 2 * Cn + 3 * R + D + Bt;
     c->cur = 0;
     c->dirty[0] = c->dirty[1] = 0;
+    c->bslot_words = D + Bt;
+    c->bslot = 0;
+    c->bclean[0] = c->bclean[1] = true;
     *out = c;
     return ABFT_OK;
 }
@@ -159,14 +165,11 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
 {
     const size_t bK = (size_t)s.batch * s.K, bM = (size_t)s.batch * s.M, bN = (size_t)s.batch * s.N;
     const size_t D = (size_t)c->cfg.max_depth, Bt = (size_t)c->cfg.max_batch;
-    w->b_acc = c->pool_depth;
-    w->acc_stride = (long)D;
-    w->b_sum = c->pool_depth + ENC_ACC_COPIES * D;
+    w->b_sum = c->pool_depth + (size_t)c->bslot * c->bslot_words;
+    w->b_max = w->b_sum + D;
     uint32_t *pb = c->pool_batch;
-    w->max_acc = pb;                          pb += 2 * Bt;
     w->maxabs = (float *)pb;                  pb += 2 * Bt;
     w->tau = (float *)pb;                     pb += Bt;
-    w->enc_ticket = pb;                       pb += Bt;
     w->s_pred = pb;
     w->cc_pred = c->pool_cols;
     // the region the protected GEMM accumulates into (must be zero before it)
@@ -206,6 +209,18 @@ static int check_verdict(const abft_result *r, Verdict *v)
 
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail_hip(ctx, e_); } while (0)
 
+// A pass over B accumulates into the slot that is not in use; that slot is clean unless two
+// passes follow each other without a protected GEMM in between (whose finish kernel cleans it).
+static int begin_b_pass(abft_ctx *ctx, hipStream_t st)
+{
+    const int target = ctx->bslot ^ 1;
+    if (!ctx->bclean[target])
+        HIP_TRY(launch_zero(ctx->pool_depth + (size_t)target * ctx->bslot_words, ctx->bslot_words, st));
+    ctx->bclean[target] = false;
+    ctx->bslot = target;
+    return ABFT_OK;
+}
+
 extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_shape *s, void *stream)
 {
     Shape sh;
@@ -213,9 +228,11 @@ extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, con
     if (rc) return rc;
     if (!B) return ABFT_EINVAL;
     if (!aligned16(B)) return ABFT_EALIGN;
+    ctx->b_valid = false;
+    rc = begin_b_pass(ctx, (hipStream_t)stream);
+    if (rc) return rc;
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    ctx->b_valid = false;
     HIP_TRY(launch_encode_b(dtype, B, sh, w, nullptr, 0, (hipStream_t)stream));
     ctx->b_valid = true;
     ctx->b_dt = dtype;
@@ -263,6 +280,10 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     // call's finish kernel.  So a call with a cached B checksum is two kernels: GEMM, finish.
     const int prev = ctx->cur;
     ctx->cur ^= 1;
+    if (!cached) {
+        rc = begin_b_pass(ctx, st);
+        if (rc) return rc;
+    }
     carve(ctx, dtype, sh, &w);
     uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
     const size_t stale = ctx->dirty[ctx->cur];
@@ -276,7 +297,12 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
     const size_t prev_dirty = ctx->dirty[prev];
     ctx->dirty[prev] = ctx->region_words;
-    HIP_TRY(launch_finish(dtype, B, sh, w, v, prev_base, prev_dirty, st));
+    // the finish kernel also cleans the b slot that is not in use (for the next pass over B)
+    const int other = ctx->bslot ^ 1;
+    uint32_t *other_base = ctx->pool_depth + (size_t)other * ctx->bslot_words;
+    HIP_TRY(launch_finish(dtype, B, sh, w, v, prev_base, prev_dirty, ctx->bclean[other] ? nullptr : other_base,
+                          ctx->bslot_words, st));
+    ctx->bclean[other] = true;
     ctx->dirty[prev] = 0;
     ctx->dirty[ctx->cur] = w.zero_words;
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }

@@ -12,8 +12,6 @@ constexpr int SLAB_BYTES = 128;
 constexpr int CT = 32;
 // Most tiles one abft_correct call repairs.
 constexpr int MAX_FIX_TILES = 256;
-// Copies of the encode accumulators (spreads same-cache-line atomics).
-constexpr int ENC_ACC_COPIES = 8;
 // Tolerance of the stored-side comparison relative to tau: both sides are fp32 sums of the same
 // rounded values, so only the order of summation separates them.
 constexpr float STO_TOL_FACTOR = 1e-2f;
@@ -29,12 +27,10 @@ __host__ __device__ inline int out_size(int dt) { return dt == DT_I8 ? 4 : 2; }
 // All arrays are [batch][len]; checksum values are int32 (ring Z/2^32) for
 // DT_I8 and float otherwise, so every element is one 32-bit word.
 struct Workspace {
-    // B pass
-    uint32_t *b_acc;                // [ENC_ACC_COPIES][batch][K] atomic accumulators, self-cleaning
-    long acc_stride;                // words between accumulator copies
-    uint32_t *b_sum;                // [batch][K]   b = B e
-    uint32_t *max_acc;              // [batch]      atomic max of |B| (float bits), self-cleaning
-    uint32_t *enc_ticket;           // [batch]
+    // B pass: b = B e and max|B| are accumulated with atomics into one of two slots (the
+    // context alternates; the finish kernel of a protected GEMM clears the slot not in use)
+    uint32_t *b_sum;                // [batch][K]   slot in use
+    uint32_t *b_max;                // [batch]      max|B| as float bits, same slot
     float    *maxabs;               // [batch][2]   max|A|, max|B|
     float    *tau;                  // [batch]
     // predicted
@@ -84,7 +80,8 @@ hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, co
                        const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st);
 // zero_ptr / zero_words: a region every block of the kernel helps to clear (may be null / 0)
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
-                         uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
+                         uint32_t *zero_ptr, size_t zero_words, uint32_t *zero2_ptr, size_t zero2_words,
+                         hipStream_t st);
 // with_sto: a row / column also flags when the re-summed stored C differs from the stored-side
 // sums of the GEMM by more than STO_TOL_FACTOR * tau
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,

@@ -36,27 +36,9 @@ hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st)
 // left here is the pass over B, which must be complete before that (A b needs all of b).  For a
 // weight it is done once, offline (remark (2) of the same paragraph).
 constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread (B pass)
-// Atomics on one cache line are served one after the other (tens of nanoseconds each), so the
-// row blocks of a pass spread their column sums over several accumulator copies.
-constexpr int ENC_COPIES = ENC_ACC_COPIES;
-
-// Sum the accumulator copies of column k, leave them clean for the next call.  The reads go
-// through the coherence point (device-scope atomic loads, all in flight at once); the zeros are
-// ordinary stores, visible to the next kernel.
-template <typename acc_t>
-__device__ __forceinline__ acc_t take_copies(uint32_t *acc, long stride, int k)
-{
-    uint32_t part[ENC_COPIES];
-#pragma unroll
-    for (int c = 0; c < ENC_COPIES; ++c) part[c] = atomic_read_word(acc + c * stride + k);
-    acc_t t = from_word<acc_t>(part[0]);
-#pragma unroll
-    for (int c = 1; c < ENC_COPIES; ++c) t = add_t(t, from_word<acc_t>(part[c]));
-#pragma unroll
-    for (int c = 0; c < ENC_COPIES; ++c) acc[c * stride + k] = 0u;
-    return t;
-}
-
+#ifndef ENC_BATCHES
+#define ENC_BATCHES 2
+#endif
 // ---------------------------------------------------------------- B pass: b = B e, max|B|
 // The stored array has `rows` rows of `cols` elements.  reduce_rows = 1 (B stored N x K):
 // b[col] = sum over rows.  reduce_rows = 0 (B stored K x N): b[row] = sum over cols.
@@ -68,12 +50,8 @@ struct EncBArgs {
     int cw_log2;          // 16-byte chunk columns per block window (power of two <= 64)
     int rpb;              // rows per block
     int nwin, nrb;
-    uint32_t *acc;        // [ENC_COPIES][batch][K] atomic accumulators
-    long acc_stride;
-    uint32_t *sum;        // [batch][K]
-    uint32_t *max_acc;    // [batch][2]
-    float *maxabs;        // [batch][2]
-    uint32_t *ticket;     // [batch]
+    uint32_t *sum;        // [batch][K]  accumulated with atomics: zero before the launch
+    uint32_t *max_acc;    // [batch]     max|B| as float bits, atomic max: zero before the launch
     uint32_t *zero_ptr;   // region every block helps to clear (the next kernel's atomics start at zero)
     size_t zero_words;
 };
@@ -85,8 +63,6 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
     typedef typename T::acc_t acc_t;
     constexpr int ES = T::ES, CE = 16 / ES;
     __shared__ acc_t red[256 * CE];
-    __shared__ float fred[4];
-    __shared__ int is_last;
 
     const int tid = threadIdx.x, bz = blockIdx.z;
     {
@@ -134,7 +110,7 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
             }
             if (!e.reduce_rows) {
                 for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
-                if (cx == 0 && r < rend) atomic_add_word(e.acc + (long)bz * e.K + r, s);
+                if (cx == 0 && r < rend) atomic_add_word(e.sum + (long)bz * e.K + r, s);
             }
         }
     }
@@ -148,35 +124,14 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
             if (col < e.cols) {
                 acc_t t = red[c];
                 for (int y = 1; y < RL; ++y) t = add_t(t, red[y * CW * CE + c]);
-                atomic_add_word(e.acc + (rb % ENC_COPIES) * e.acc_stride + (long)bz * e.K + col, t);
+                atomic_add_word(e.sum + (long)bz * e.K + col, t);
             }
         }
     }
     if (!T::IS_INT) {
         mx = wave_max(mx);
-        __syncthreads();
-        if ((tid & 63) == 0) fred[tid >> 6] = mx;
-        __syncthreads();
-        if (tid == 0)
-            atomicMax(e.max_acc + (long)bz * 2 + 1,
-                      __float_as_uint(fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]))));
+        if ((tid & 63) == 0 && mx > 0.f) atomicMax(e.max_acc + bz, __float_as_uint(mx));
     }
-    // Last block of this batch item finalises.  Everything other workgroups must see was
-    // written with device-scope atomic read-modify-writes, which are performed at the device's
-    // coherence point; the barrier waits for this workgroup's outstanding ones before the
-    // ticket is taken.  (A device-wide fence here costs tens of microseconds per launch.)
-    __syncthreads();
-    if (tid == 0) {
-        unsigned t = atomicAdd(e.ticket + bz, 1u);
-        is_last = (t == (unsigned)(e.nwin * e.nrb) - 1);
-        if (is_last) atomicExch(e.ticket + bz, 0u);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    for (int k = tid; k < e.K; k += 256)
-        e.sum[(long)bz * e.K + k] = as_word(take_copies<acc_t>(e.acc + (long)bz * e.K, e.acc_stride, k));
-    if (!T::IS_INT && tid == 0)
-        e.maxabs[(long)bz * 2 + 1] = __uint_as_float(atomicExch(e.max_acc + (long)bz * 2 + 1, 0u));
 }
 
 __device__ __forceinline__ int mul_t(int x, int y) { return (int)((uint32_t)x * (uint32_t)y); }
@@ -200,9 +155,10 @@ static EncPlan plan_window(int rows, int cols, int chunk_elems)
     p.cw_log2 = best_lg;
     const int CW = 1 << best_lg, RL = 256 / CW;
     p.nwin = (chunks + CW - 1) / CW;
-    // rows per block: one batch of ENC_UNROLL loads per thread, more when the matrix is tall:
-    // fewer blocks mean fewer atomics on the same cache lines
-    int rpb = RL * ENC_UNROLL;
+    // rows per block: ENC_BATCHES batches of ENC_UNROLL loads per thread, more when the matrix is
+    // tall: atomics that hit one cache line are served one after the other (tens of nanoseconds
+    // each), so fewer row blocks mean less waiting at the end of the pass
+    int rpb = RL * ENC_UNROLL * ENC_BATCHES;
     while ((long)p.nwin * ((rows + rpb - 1) / rpb) > 640) rpb *= 2;
     p.rpb = rpb;
     p.nrb = (rows + rpb - 1) / rpb;
@@ -218,8 +174,7 @@ hipError_t launch_encode_b(int dt, const void *B, const Shape &s, const Workspac
     else          { e.rows = s.K; e.cols = s.N; e.reduce_rows = 0; }
     EncPlan p = plan_window(e.rows, e.cols, 16 / elem_size(dt));
     e.cw_log2 = p.cw_log2; e.nwin = p.nwin; e.rpb = p.rpb; e.nrb = p.nrb;
-    e.acc = w.b_acc; e.acc_stride = w.acc_stride; e.sum = w.b_sum;
-    e.max_acc = w.max_acc; e.maxabs = w.maxabs; e.ticket = w.enc_ticket;
+    e.sum = w.b_sum; e.max_acc = w.b_max;
     e.zero_ptr = zero_ptr; e.zero_words = zero_ptr ? zero_words : 0;
     dim3 grid((unsigned)(e.nwin * e.nrb), 1, (unsigned)s.batch);
     switch (dt) {
@@ -356,6 +311,9 @@ struct FinArgs {
     int col_blocks;       // blocks [0, col_blocks) take columns, the rest rows
     uint32_t *zero_ptr;   // region every block helps to clear: what the previous protected GEMM of this
     size_t zero_words;    // context accumulated into, so that the next one finds it clean
+    const uint32_t *b_max;   // max|B| of the b in use, float bits [batch]
+    uint32_t *zero2_ptr;  // second region to clear: the b slot the next pass over B will accumulate into
+    size_t zero2_words;
 };
 
 constexpr int FIN_ROWS_B = 16;     // rows of a B stored N x K per column block (4 per wave)
@@ -380,14 +338,16 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
         const size_t nb = (size_t)gridDim.x * gridDim.z;
         const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
         for (size_t i = bid * 256 + tid; i < f.zero_words; i += nb * 256) f.zero_ptr[i] = 0u;
+        for (size_t i = bid * 256 + tid; i < f.zero2_words; i += nb * 256) f.zero2_ptr[i] = 0u;
     }
 
     float tol = 0.f;
     if (!T::IS_INT) {
-        const float ma = __uint_as_float(f.a_max[bz]), mb = f.maxabs[(long)bz * 2 + 1];
+        const float ma = __uint_as_float(f.a_max[bz]), mb = __uint_as_float(f.b_max[bz]);
         tol = f.tau_override > 0.f ? f.tau_override : (1e-3f * (float)K) * ma * mb;
         if (blockIdx.x == 0 && tid == 0) {
             f.maxabs[(long)bz * 2] = ma;
+            f.maxabs[(long)bz * 2 + 1] = mb;
             f.tau[bz] = tol;
         }
     }
@@ -542,9 +502,11 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
 }
 
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
-                         uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
+                         uint32_t *zero_ptr, size_t zero_words, uint32_t *zero2_ptr, size_t zero2_words,
+                         hipStream_t st)
 {
     FinArgs f;
+    f.b_max = w.b_max; f.zero2_ptr = zero2_ptr; f.zero2_words = zero2_ptr ? zero2_words : 0;
     f.zero_ptr = zero_ptr; f.zero_words = zero_ptr ? zero_words : 0;
     f.B = (const uint8_t *)B; f.ldb = s.ldb; f.sB = s.sB; f.transB = s.transB;
     f.M = s.M; f.N = s.N; f.K = s.K;
