@@ -97,6 +97,8 @@ SHAPES = [
     (777, 600, 192, 1, True),      # 256x256-tile path for 16-bit types (K a multiple of 64)
     (520, 1030, 256, 2, True),     # 256x256-tile path for all types, ragged both ways, batched
     (512, 512, 128, 1, True),      # tile-exact on the 256x256 path
+    (520, 600, 4096, 1, True),     # deepest K of a protected GEMM: 16 / 32 slabs per workgroup to reduce
+    (140, 90, 4096, 1, False),     # the same on the general kernel
 ]
 
 
