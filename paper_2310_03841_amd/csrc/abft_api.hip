@@ -25,7 +25,7 @@ struct abft_ctx {
     size_t dirty[2];        // leading words of each region that may be non-zero
     uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
     int32_t  *fix_tiles;
-    uint32_t *small;        // fix_count[4], cmp_ticket[4]
+    uint32_t *small;        // fix_count[4], cmp_ticket[4], group tickets of the finish kernel [64]
     InjectArm arm;
     int last_hip;
     // what the context currently holds
@@ -87,7 +87,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
         {(void **)&c->pool_obs, 2 * (2 * Cn + 3 * R + D + Bt) * 4},
         {(void **)&c->pool_vobs, (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
-        {(void **)&c->small, 8 * 4},
+        {(void **)&c->small, (8 + 64) * 4},
     };
     for (auto &q : req) {
         e = hipMalloc(q.p, q.bytes);

@@ -49,7 +49,7 @@ struct Workspace {
     // correction
     int32_t  *fix_tiles;            // [MAX_FIX_TILES][3] (batch, tile row, tile col)
     uint32_t *fix_count;            // [4]: 0 tiles, 1 overflow flag, 2 ticket, 3 spare
-    uint32_t *cmp_ticket;           // [3]
+    uint32_t *cmp_ticket;           // [4] ticket and counts, then [64] first-level tickets of the finish kernel
 };
 
 struct Shape {

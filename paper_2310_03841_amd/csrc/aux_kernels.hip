@@ -308,7 +308,10 @@ struct FinArgs {
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
-    int col_blocks;       // blocks [0, col_blocks) take columns, the rest rows
+    uint32_t *group_ticket;   // [FIN_MAX_BLOCKS / FIN_GROUP] first-level tickets (self-cleaning)
+    int batch;
+    int lpr;              // B stored N x K: lanes along one row of B (8, 16, 32 or 64)
+    int col_blocks;       // units [0, col_blocks) of a batch item take columns, the rest rows
     uint32_t *zero_ptr;   // region every block helps to clear: what the previous protected GEMM of this
     size_t zero_words;    // context accumulated into, so that the next one finds it clean
     const uint32_t *b_max;   // max|B| of the b in use, float bits [batch]
@@ -316,9 +319,26 @@ struct FinArgs {
     size_t zero2_words;
 };
 
-constexpr int FIN_ROWS_B = 16;     // rows of a B stored N x K per column block (4 per wave)
 constexpr int FIN_KY = 8;          // k lanes of a column block over a B stored K x N
+constexpr int FIN_MAX_BLOCKS = 1024;
+constexpr int FIN_GROUP = 16;          // blocks per first-level ticket
 
+// Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a group ends with
+// the total.
+template <typename V> __device__ __forceinline__ V seg_sum(V v, int width)
+{
+    v = add_t(v, dpp_get<0xB1>(v));    // lane ^ 1
+    v = add_t(v, dpp_get<0x4E>(v));    // lane ^ 2
+    v = add_t(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
+    if (width >= 16) v = add_t(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
+    if (width >= 32) v = add_t(v, __shfl_xor(v, 16));
+    if (width >= 64) v = add_t(v, __shfl_xor(v, 32));
+    return v;
+}
+
+// Work is cut into units: (batch item, block of columns) and (batch item, block of 256 rows).
+// A block takes units blockIdx.x, blockIdx.x + gridDim.x, ...: many small batch items (attention
+// heads) then cost few blocks, and few blocks matter because each ends on the same ticket.
 template <int DT>
 __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
 {
@@ -328,154 +348,170 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     __shared__ acc_t wred[4];
     __shared__ unsigned wcnt[4][2];
-    __shared__ int is_last;
-    (void)is_last;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bz = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int M = f.M, N = f.N, K = f.K;
-    const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
-    const uint32_t *asum = f.a_sum + (long)bz * K;
     {
-        const size_t nb = (size_t)gridDim.x * gridDim.z;
-        const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
-        for (size_t i = bid * 256 + tid; i < f.zero_words; i += nb * 256) f.zero_ptr[i] = 0u;
-        for (size_t i = bid * 256 + tid; i < f.zero2_words; i += nb * 256) f.zero2_ptr[i] = 0u;
+        const size_t nb = gridDim.x;
+        for (size_t i = (size_t)blockIdx.x * 256 + tid; i < f.zero_words; i += nb * 256) f.zero_ptr[i] = 0u;
+        for (size_t i = (size_t)blockIdx.x * 256 + tid; i < f.zero2_words; i += nb * 256) f.zero2_ptr[i] = 0u;
     }
+    const int row_blocks = (M + 255) / 256;
+    const int upi = f.col_blocks + row_blocks;                 // units per batch item
+    const int units = upi * f.batch;                           // fits: checked by the launcher
+    unsigned nr_w = 0, nc_w = 0;                               // flagged rows / columns seen by this wave
 
-    float tol = 0.f;
-    if (!T::IS_INT) {
-        const float ma = __uint_as_float(f.a_max[bz]), mb = __uint_as_float(f.b_max[bz]);
-        tol = f.tau_override > 0.f ? f.tau_override : (1e-3f * (float)K) * ma * mb;
-        if (blockIdx.x == 0 && tid == 0) {
-            f.maxabs[(long)bz * 2] = ma;
-            f.maxabs[(long)bz * 2 + 1] = mb;
-            f.tau[bz] = tol;
+    for (int u = blockIdx.x; u < units; u += gridDim.x) {
+        const int bz = u / upi, blk = u - bz * upi;
+        const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
+        const uint32_t *asum = f.a_sum + (long)bz * K;
+        float tol = 0.f;
+        if (!T::IS_INT) {
+            const float ma = __uint_as_float(f.a_max[bz]), mb = __uint_as_float(f.b_max[bz]);
+            tol = f.tau_override > 0.f ? f.tau_override : (1e-3f * (float)K) * ma * mb;
+            if (blk == 0 && tid == 0) {
+                f.maxabs[(long)bz * 2] = ma;
+                f.maxabs[(long)bz * 2 + 1] = mb;
+                f.tau[bz] = tol;
+            }
         }
-    }
-
-    bool frow = false, fcol = false, fcol2 = false;
-    if ((int)blockIdx.x < f.col_blocks) {
-        if (f.transB) {
-            // B stored N x K: a wave takes four rows of B at a time, lanes run along K.  The
-            // matching values of a come straight from memory, in flight together with B.
-            const int nch = (K + CE - 1) / CE;
-            const int nb = blockIdx.x * FIN_ROWS_B + wave * 4;
-            acc_t dot[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
-            for (int ch = lane; ch < nch; ch += 64) {
-                i32x4 v[4], aw[CE / 4];
+        if (blk < f.col_blocks) {
+            if (f.transB) {
+                // B stored N x K: lpr lanes run along a row of B (K), a wave takes 64 / lpr rows at
+                // a time, four times.  The matching values of a come straight from memory, in
+                // flight together with B.
+                const int nch = (K + CE - 1) / CE;
+                const int lpr = f.lpr, rpw = 64 / lpr;
+                const int sub = lane / lpr, lc = lane % lpr;
+                const int nb = blk * (16 * rpw) + wave * 4 * rpw + sub;     // row of pass 0; pass j: + j * rpw
+                acc_t dot[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
+                for (int ch = lc; ch < nch; ch += lpr) {
+                    i32x4 v[4], aw[CE / 4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    v[j] = i32x4{0, 0, 0, 0};
-                    if (nb + j < N) v[j] = *reinterpret_cast<const i32x4 *>(Bb + ((long)(nb + j) * f.ldb + ch * CE) * ES);
-                }
-                const int left = K - ch * CE;                       // >= 1
-                if (left >= CE) {
-#pragma unroll
-                    for (int q4 = 0; q4 < CE / 4; ++q4) {
-                        // dword-aligned 16-byte reads (the batch offset need not be a multiple of four words)
-                        const uint32_t *ap = asum + ch * CE + 4 * q4;
-                        aw[q4] = i32x4{(int)ap[0], (int)ap[1], (int)ap[2], (int)ap[3]};
+                    for (int j = 0; j < 4; ++j) {
+                        const int n = nb + j * rpw;
+                        v[j] = i32x4{0, 0, 0, 0};
+                        if (n < N) v[j] = *reinterpret_cast<const i32x4 *>(Bb + ((long)n * f.ldb + ch * CE) * ES);
                     }
+                    const int left = K - ch * CE;                       // >= 1
+                    if (left >= CE) {
+#pragma unroll
+                        for (int q4 = 0; q4 < CE / 4; ++q4) {
+                            // dword-aligned reads (the batch offset need not be a multiple of four words)
+                            const uint32_t *ap = asum + ch * CE + 4 * q4;
+                            aw[q4] = i32x4{(int)ap[0], (int)ap[1], (int)ap[2], (int)ap[3]};
+                        }
+                    } else {
+#pragma unroll
+                        for (int q4 = 0; q4 < CE / 4; ++q4)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                aw[q4][e] = (4 * q4 + e < left) ? (int)asum[ch * CE + 4 * q4 + e] : 0;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        i32x4 w = v[j];
+                        if (left < CE) w = mask_chunk(w, left * ES);
+#pragma unroll
+                        for (int q = 0; q < CE; ++q)
+                            dot[j] = add_t(dot[j], mul_t(T::elem(w, q), from_word<acc_t>((uint32_t)aw[q >> 2][q & 3])));
+                    }
+                }
+                if (lpr == 64) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) dot[j] = wave_sum(dot[j]);
                 } else {
 #pragma unroll
-                    for (int q4 = 0; q4 < CE / 4; ++q4)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            aw[q4][e] = (4 * q4 + e < left) ? (int)asum[ch * CE + 4 * q4 + e] : 0;
+                    for (int j = 0; j < 4; ++j) dot[j] = seg_sum(dot[j], lpr);
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    i32x4 w = v[j];
-                    if (left < CE) w = mask_chunk(w, left * ES);
-#pragma unroll
-                    for (int q = 0; q < CE; ++q)
-                        dot[j] = add_t(dot[j], mul_t(T::elem(w, q), from_word<acc_t>((uint32_t)aw[q >> 2][q & 3])));
+                    const acc_t t = dot[j];
+                    const int n = nb + j * rpw;
+                    bool fl = false;
+                    if (lc == 0 && n < N) {
+                        const long o = (long)bz * N + n;
+                        f.cc_pred[o] = as_word(t);
+                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                        f.col_flag[o] = fl ? 1 : 0;
+                    }
+                    nc_w += __popcll(__ballot(fl));
                 }
-            }
+            } else {
+                // B stored K x N: a staged in LDS; 32 chunk columns per unit, FIN_KY lanes run along K
+                acc_t *al = reinterpret_cast<acc_t *>(lds);
+                __syncthreads();                                        // previous unit done with al / red
+                for (int k = tid; k < K; k += 256) al[k] = from_word<acc_t>(asum[k]);
+                __syncthreads();
+                acc_t *red = al + (K + 3) / 4 * 4;                      // [FIN_KY][32 * CE]
+                const int cx = tid & 31, ky = tid >> 5;
+                const int nst = (blk * 32 + cx) * CE;
+                const int left = N - nst;
+                acc_t colp[CE];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const acc_t t = wave_sum(dot[j]);
-                if (lane == j && nb + j < N) {
-                    const long o = (long)bz * N + nb + j;
-                    f.cc_pred[o] = as_word(t);
-                    fcol = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
-                    f.col_flag[o] = fcol ? 1 : 0;
+                for (int q = 0; q < CE; ++q) colp[q] = T::zero();
+                for (int k0 = ky; k0 < K; k0 += 4 * FIN_KY) {
+                    i32x4 v[4];
+#pragma unroll
+                    for (int uu = 0; uu < 4; ++uu) {
+                        const int k = k0 + uu * FIN_KY;
+                        v[uu] = i32x4{0, 0, 0, 0};
+                        if (k < K && left > 0) v[uu] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * f.ldb + nst) * ES);
+                    }
+#pragma unroll
+                    for (int uu = 0; uu < 4; ++uu) {
+                        const int k = k0 + uu * FIN_KY;
+                        if (k < K) {
+                            const acc_t ak = al[k];
+#pragma unroll
+                            for (int q = 0; q < CE; ++q) colp[q] = add_t(colp[q], mul_t(T::elem(v[uu], q), ak));
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < CE; ++q) red[ky * 32 * CE + cx * CE + q] = colp[q];
+                __syncthreads();
+                // at most two columns per thread (int8: 512 columns per unit)
+                for (int c = tid; c < 32 * CE; c += 256) {
+                    const int n = blk * 32 * CE + c;
+                    bool fl = false;
+                    if (n < N) {
+                        acc_t t = red[c];
+#pragma unroll
+                        for (int y = 1; y < FIN_KY; ++y) t = add_t(t, red[y * 32 * CE + c]);
+                        const long o = (long)bz * N + n;
+                        f.cc_pred[o] = as_word(t);
+                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                        f.col_flag[o] = fl ? 1 : 0;
+                    }
+                    nc_w += __popcll(__ballot(fl));
                 }
             }
         } else {
-            // B stored K x N: a staged in LDS; 32 chunk columns per block, FIN_KY lanes run along K
-            acc_t *al = reinterpret_cast<acc_t *>(lds);
-            for (int k = tid; k < K; k += 256) al[k] = from_word<acc_t>(asum[k]);
-            __syncthreads();
-            acc_t *red = al + (K + 3) / 4 * 4;                      // [FIN_KY][32 * CE]
-            const int cx = tid & 31, ky = tid >> 5;
-            const int nst = (blockIdx.x * 32 + cx) * CE;
-            const int left = N - nst;
-            acc_t colp[CE];
-#pragma unroll
-            for (int q = 0; q < CE; ++q) colp[q] = T::zero();
-            for (int k0 = ky; k0 < K; k0 += 4 * FIN_KY) {
-                i32x4 v[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int k = k0 + u * FIN_KY;
-                    v[u] = i32x4{0, 0, 0, 0};
-                    if (k < K && left > 0) v[u] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * f.ldb + nst) * ES);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int k = k0 + u * FIN_KY;
-                    if (k < K) {
-                        const acc_t ak = al[k];
-#pragma unroll
-                        for (int q = 0; q < CE; ++q) colp[q] = add_t(colp[q], mul_t(T::elem(v[u], q), ak));
-                    }
-                }
+            const int r = (blk - f.col_blocks) * 256 + tid;
+            bool fl = false;
+            if (r < M) {
+                const long o = (long)bz * M + r;
+                fl = mismatch<T::IS_INT>(f.rc_obs[o], f.rc_pred[o], tol);
+                f.row_flag[o] = fl ? 1 : 0;
             }
-#pragma unroll
-            for (int q = 0; q < CE; ++q) red[ky * 32 * CE + cx * CE + q] = colp[q];
-            __syncthreads();
-            // at most two columns per thread (int8: 512 columns per block)
-            for (int c = tid; c < 32 * CE; c += 256) {
-                const int n = blockIdx.x * 32 * CE + c;
-                if (n < N) {
-                    acc_t t = red[c];
-#pragma unroll
-                    for (int y = 1; y < FIN_KY; ++y) t = add_t(t, red[y * 32 * CE + c]);
-                    const long o = (long)bz * N + n;
-                    f.cc_pred[o] = as_word(t);
-                    const bool fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
-                    f.col_flag[o] = fl ? 1 : 0;
-                    if (c < 256) fcol = fl;
-                    else fcol2 = fl;
-                }
+            nr_w += __popcll(__ballot(fl));
+            if (blk == f.col_blocks) {
+                // scalar a . b (the single-number check value of Sec. III-B.1), by the first row unit
+                acc_t v = T::zero();
+                for (int k = tid; k < K; k += 256)
+                    v = add_t(v, mul_t(from_word<acc_t>(asum[k]), from_word<acc_t>(f.b_sum[(long)bz * K + k])));
+                v = wave_sum(v);
+                __syncthreads();                                        // wred free again
+                if (lane == 0) wred[wave] = v;
+                __syncthreads();
+                if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
             }
         }
-    } else {
-        const int r = ((int)blockIdx.x - f.col_blocks) * 256 + tid;
-        if (r < M) {
-            const long o = (long)bz * M + r;
-            frow = mismatch<T::IS_INT>(f.rc_obs[o], f.rc_pred[o], tol);
-            f.row_flag[o] = frow ? 1 : 0;
-        }
-        if ((int)blockIdx.x == f.col_blocks) {
-            // scalar a . b (the single-number check value of Sec. III-B.1), by the first row block
-            acc_t v = T::zero();
-            for (int k = tid; k < K; k += 256)
-                v = add_t(v, mul_t(from_word<acc_t>(asum[k]), from_word<acc_t>(f.b_sum[(long)bz * K + k])));
-            v = wave_sum(v);
-            if (lane == 0) wred[wave] = v;
-        }
     }
-    // flagged rows / columns of this block
-    {
-        const unsigned nr = __popcll(__ballot(frow));
-        const unsigned nc = __popcll(__ballot(fcol)) + __popcll(__ballot(fcol2));
-        if (lane == 0) { wcnt[wave][0] = nr; wcnt[wave][1] = nc; }
-    }
+    // flagged rows / columns of this block, then its ticket
+    if (lane == 0) { wcnt[wave][0] = nr_w; wcnt[wave][1] = nc_w; }
     __syncthreads();
     if (tid == 0) {
-        if ((int)blockIdx.x == f.col_blocks)
-            f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
         const unsigned nr = wcnt[0][0] + wcnt[1][0] + wcnt[2][0] + wcnt[3][0];
         const unsigned nc = wcnt[0][1] + wcnt[1][1] + wcnt[2][1] + wcnt[3][1];
         if (nr | nc) {
@@ -486,10 +522,16 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
             if (nc) o2 = atomicAdd(f.ticket + 2, nc);
             asm volatile("s_waitcnt vmcnt(0)" :: "v"(o1), "v"(o2) : "memory");
         }
-        const unsigned total = gridDim.x * gridDim.z;
-        const unsigned t = atomicAdd(f.ticket, 1u);
-        is_last = (t == total - 1);
-        if (is_last) {
+        // Tickets in two levels (atomics on one word are served one after the other, ~12 ns each):
+        // the last block of a group of FIN_GROUP takes a ticket for the group.
+        const unsigned grp = blockIdx.x / FIN_GROUP, ngrp = (gridDim.x + FIN_GROUP - 1) / FIN_GROUP;
+        const unsigned gsize = min((unsigned)FIN_GROUP, gridDim.x - grp * FIN_GROUP);
+        bool last = false;
+        if (atomicAdd(f.group_ticket + grp, 1u) == gsize - 1) {
+            atomicExch(f.group_ticket + grp, 0u);
+            last = atomicAdd(f.ticket, 1u) == ngrp - 1;
+        }
+        if (last) {
             const uint32_t r = atomicExch(f.ticket + 1, 0u), c = atomicExch(f.ticket + 2, 0u);
             atomicExch(f.ticket, 0u);
             f.counts[0] = r;
@@ -514,11 +556,18 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     f.a_max = w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
     f.tau_override = v.tau_override;
     f.row_flag = v.row_flag; f.col_flag = v.col_flag; f.counts = v.counts; f.ticket = w.cmp_ticket;
+    f.group_ticket = w.cmp_ticket + 4;
     const int ce = 16 / elem_size(dt);
-    f.col_blocks = s.transB ? (s.N + FIN_ROWS_B - 1) / FIN_ROWS_B : (s.N + 32 * ce - 1) / (32 * ce);
+    const int nch = (s.K + ce - 1) / ce;
+    f.lpr = nch <= 8 ? 8 : (nch <= 16 ? 16 : (nch <= 32 ? 32 : 64));
+    f.batch = s.batch;
+    const int rows_per_unit = 16 * (64 / f.lpr);
+    f.col_blocks = s.transB ? (s.N + rows_per_unit - 1) / rows_per_unit : (s.N + 32 * ce - 1) / (32 * ce);
     const int row_blocks = (s.M + 255) / 256;
     const size_t smem = s.transB ? 0 : ((size_t)(s.K + 3) / 4 * 4 + (size_t)FIN_KY * 32 * ce) * 4;
-    dim3 grid((unsigned)(f.col_blocks + row_blocks), 1, (unsigned)s.batch);
+    const long units = (long)(f.col_blocks + row_blocks) * s.batch;
+    if (units > 0x7FFFFFFFL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(units < FIN_MAX_BLOCKS ? units : FIN_MAX_BLOCKS), 1, 1);
     switch (dt) {
     case DT_I8:   hipLaunchKernelGGL(finish_kernel<DT_I8>, grid, dim3(256), smem, st, f); break;
     case DT_BF16: hipLaunchKernelGGL(finish_kernel<DT_BF16>, grid, dim3(256), smem, st, f); break;

@@ -231,39 +231,47 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 wave_sync();
             }
             const int nrow = M - br < 32 ? M - br : 32;
-            acc_t myrow = T::zero();
-            float myrow_s = 0.f;
+            // (1) lane <-> CPL consecutive columns, walking the rows: store C, column sums
             for (int r = 0; r < nrow; ++r) {
-                acc_t rs = T::zero();
-                float rs_s = 0.f;
 #pragma unroll
                 for (int j = 0; j < CPL; ++j) {
                     const int col = CPL * lane + j, gc = wc0 + col;
                     if (gc < N) {
                         const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + col * 4));
                         T::store_c(Cb, (long)(br + r) * g.ldc + gc, v);
-                        if (PROT) { colacc[j] = add_t(colacc[j], v); rs = add_t(rs, v); }
+                        if (PROT) colacc[j] = add_t(colacc[j], v);
                         if constexpr (PROT && !T::IS_INT) {
-                            if (sto) {
-                                const float sv = stored_value<DT>((float)v);
-                                colacc_s[j] += sv;
-                                rs_s += sv;
-                            }
+                            if (sto) colacc_s[j] += stored_value<DT>((float)v);
                         }
                     }
                 }
-                if (PROT) {
-                    rs = wave_sum(rs);
-                    if (lane == r) myrow = rs;
-                    if (!T::IS_INT && sto) {
-                        rs_s = wave_sum(rs_s);
-                        if (lane == r) myrow_s = rs_s;
+            }
+            // (2) lane <-> row, the half-waves split the columns, walking the columns (each lane
+            // starts at a different one: no bank conflicts): row sums without cross-lane traffic.
+            // Rows of the group past M get a value too; nobody reads it.
+            if (PROT) {
+                constexpr int HC = TN / 2;
+                const int ncol = N - wc0 < TN ? N - wc0 : TN;
+                acc_t rs = T::zero();
+                float rs_s = 0.f;
+                for (int c = 0; c < HC; ++c) {
+                    const int col = lh * HC + ((c + l32) & (HC - 1));
+                    if (col < ncol) {
+                        const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + l32 * SROW + col * 4));
+                        rs = add_t(rs, v);
+                        if constexpr (!T::IS_INT) {
+                            if (sto) rs_s += stored_value<DT>((float)v);
+                        }
                     }
                 }
-            }
-            if (PROT && lane < 32) {
-                rs_part[wn * BM + wm * TM + mi * 32 + lane] = myrow;
-                if (!T::IS_INT && sto) rowsto[mi] = myrow_s;           // lanes 0..31: row mi * 32 + lane
+                rs = add_t(rs, __shfl_xor(rs, 32));
+                if (lane < 32) rs_part[wn * BM + wm * TM + mi * 32 + lane] = rs;
+                if constexpr (!T::IS_INT) {
+                    if (sto) {
+                        rs_s += __shfl_xor(rs_s, 32);
+                        rowsto[mi] = rs_s;                              // lanes 0..31: row mi * 32 + lane
+                    }
+                }
             }
             wave_sync();
         } else if (PROT) {
