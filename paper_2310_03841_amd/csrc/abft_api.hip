@@ -23,7 +23,10 @@ struct abft_ctx {
     size_t region_words;    // words per region
     int cur;                // region of the last protected GEMM
     size_t dirty[2];        // leading words of each region that may be non-zero
-    uint32_t *pool_vobs;    // cc_vobs | rc_vobs (zeroed as one region)
+    uint32_t *pool_vobs;    // two regions of cc_vobs | rc_vobs, used alternately like pool_obs
+    size_t vregion_words;
+    int vcur;
+    size_t vdirty[2];
     int32_t  *fix_tiles;
     uint32_t *small;        // fix_count[4], cmp_ticket[4], group tickets of the finish kernel [64]
     InjectArm arm;
@@ -85,7 +88,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
         {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
         {(void **)&c->pool_cols, Cn * 4},
         {(void **)&c->pool_obs, 2 * (2 * Cn + 3 * R + D + Bt) * 4},
-        {(void **)&c->pool_vobs, (R + Cn) * 4},
+        {(void **)&c->pool_vobs, 2 * (R + Cn) * 4},
         {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
         {(void **)&c->small, (8 + 64) * 4},
     };
@@ -103,6 +106,9 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     c->region_words = 2 * Cn + 3 * R + D + Bt;
     c->cur = 0;
     c->dirty[0] = c->dirty[1] = 0;
+    c->vregion_words = R + Cn;
+    c->vcur = 0;
+    c->vdirty[0] = c->vdirty[1] = 0;
     c->bslot_words = D + Bt;
     c->bslot = 0;
     c->bclean[0] = c->bclean[1] = true;
@@ -181,8 +187,8 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->cc_sto = w->a_max + s.batch;
     w->rc_sto = w->cc_sto + bN;
     w->zero_words = 2 * bN + 3 * bM + bK + (size_t)s.batch;
-    w->cc_vobs = c->pool_vobs;
-    w->rc_vobs = c->pool_vobs + bN;
+    w->cc_vobs = c->pool_vobs + (size_t)c->vcur * c->vregion_words;
+    w->rc_vobs = w->cc_vobs + bN;
     w->fix_tiles = c->fix_tiles;
     w->fix_count = c->small;
     w->cmp_ticket = c->small + 4;
@@ -208,6 +214,29 @@ static int check_verdict(const abft_result *r, Verdict *v)
 }
 
 #define HIP_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return fail_hip(ctx, e_); } while (0)
+
+// A re-sum of stored C accumulates into the re-summing region the previous one did not use; the
+// compare that follows clears that previous region.  Returns what the caller passes on.
+struct ResumPlan { size_t stale; uint32_t *other; size_t other_words; };
+static ResumPlan begin_resum(abft_ctx *ctx, size_t words)
+{
+    const int prev = ctx->vcur;
+    ctx->vcur ^= 1;
+    ResumPlan p;
+    p.stale = ctx->vdirty[ctx->vcur];
+    p.other = ctx->pool_vobs + (size_t)prev * ctx->vregion_words;
+    p.other_words = ctx->vdirty[prev];
+    // until the kernels are enqueued both count as dirty; end_resum settles it
+    ctx->vdirty[ctx->vcur] = ctx->vregion_words;
+    ctx->vdirty[prev] = ctx->vregion_words;
+    (void)words;
+    return p;
+}
+static void end_resum(abft_ctx *ctx, size_t words)
+{
+    ctx->vdirty[ctx->vcur] = words;
+    ctx->vdirty[ctx->vcur ^ 1] = 0;
+}
 
 // A pass over B accumulates into the slot that is not in use; that slot is clean unless two
 // passes follow each other without a protected GEMM in between (whose finish kernel cleans it).
@@ -314,7 +343,13 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_shape = *s;
     // a correction inside this call replaces values the stored-side sums already contain
     ctx->sto_valid = stored && base == ABFT_DETECT;
-    if (base == ABFT_DETECT_CORRECT) HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, st));
+    if (base == ABFT_DETECT_CORRECT) {
+        const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
+        const ResumPlan rp = begin_resum(ctx, words);
+        carve(ctx, dtype, sh, &w);
+        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, rp.stale, rp.other, rp.other_words, st));
+        end_resum(ctx, words);
+    }
     return ABFT_OK;
 }
 
@@ -331,11 +366,14 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     if (rc) return rc;
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
     hipStream_t st = (hipStream_t)stream;
+    const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
+    const ResumPlan rp = begin_resum(ctx, words);
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    HIP_TRY(launch_zero(w.cc_vobs, (size_t)sh.batch * ((size_t)sh.M + sh.N), st));
+    if (rp.stale) HIP_TRY(launch_zero(w.cc_vobs, rp.stale, st));
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
-    HIP_TRY(launch_compare(dtype, sh, w, v, false, ctx->sto_valid, st));
+    HIP_TRY(launch_compare(dtype, sh, w, v, false, ctx->sto_valid, rp.other, rp.other_words, st));
+    end_resum(ctx, words);
     return ABFT_OK;
 }
 
@@ -351,9 +389,13 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     rc = check_verdict(r, &v);
     if (rc) return rc;
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
+    const ResumPlan rp = begin_resum(ctx, words);
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, (hipStream_t)stream));
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words,
+                           (hipStream_t)stream));
+    end_resum(ctx, words);
     return ABFT_OK;
 }
 

@@ -174,6 +174,19 @@ template <typename T> __device__ __forceinline__ T wave_sum(T v)
     return add_t(v, __shfl_xor(v, 32));
 }
 
+// Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a group ends with
+// the total.
+template <typename V> __device__ __forceinline__ V seg_sum(V v, int width)
+{
+    v = add_t(v, dpp_get<0xB1>(v));    // lane ^ 1
+    v = add_t(v, dpp_get<0x4E>(v));    // lane ^ 2
+    v = add_t(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
+    if (width >= 16) v = add_t(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
+    if (width >= 32) v = add_t(v, __shfl_xor(v, 16));
+    if (width >= 64) v = add_t(v, __shfl_xor(v, 32));
+    return v;
+}
+
 __device__ __forceinline__ float wave_max(float v)
 {
     for (int o = 1; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));

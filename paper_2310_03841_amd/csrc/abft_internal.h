@@ -84,11 +84,15 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
                          hipStream_t st);
 // with_sto: a row / column also flags when the re-summed stored C differs from the stored-side
 // sums of the GEMM by more than STO_TOL_FACTOR * tau
+// zero_ptr / zero_words: a region every block of the kernel helps to clear (may be null / 0)
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          bool with_sto, hipStream_t st);
+                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
 hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st);
+// stale_words: leading words of the re-summing region in use that must be cleared first;
+// zero_ptr / zero_words: the other re-summing region, cleared by the final compare
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, bool with_sto, hipStream_t st);
+                          const Workspace &w, const Verdict &v, bool with_sto, size_t stale_words,
+                          uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
 hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,
                        hipStream_t st);
 void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn);

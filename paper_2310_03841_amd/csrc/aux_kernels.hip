@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
                 s = add_t(s, x);
             }
             if (!e.reduce_rows) {
-                for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+                s = seg_sum(s, CW);
                 if (cx == 0 && r < rend) atomic_add_word(e.sum + (long)bz * e.K + r, s);
             }
         }
@@ -203,6 +203,8 @@ struct CmpArgs {
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
     const uint32_t *fix_count;   // non-null after a correction: [0] tiles listed, [1] overflow
     const uint32_t *cc_sto, *rc_sto;   // non-null: stored-side sums of the GEMM (floating point)
+    uint32_t *zero_ptr;   // region every block helps to clear: the re-summing region not in use,
+    size_t zero_words;    // so that the next re-sum finds it clean
     int M, N, batch;
 };
 
@@ -228,6 +230,11 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     const int bz = blockIdx.z, tid = threadIdx.x;
     const int idx = blockIdx.x * 256 + tid;
     const int M = a.M, N = a.N;
+    {
+        const size_t nb = (size_t)gridDim.x * gridDim.z;
+        const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
+        for (size_t i = bid * 256 + tid; i < a.zero_words; i += nb * 256) a.zero_ptr[i] = 0u;
+    }
     const float tol = IS_INT ? 0.f : a.tau[bz];
     bool frow = false, fcol = false;
     if (idx < M) {
@@ -272,9 +279,10 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
 }
 
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          bool with_sto, hipStream_t st)
+                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
 {
     CmpArgs a;
+    a.zero_ptr = zero_ptr; a.zero_words = zero_ptr ? zero_words : 0;
     a.cc_sto = (with_sto && dt != DT_I8) ? w.cc_sto : nullptr;
     a.rc_sto = a.cc_sto ? w.rc_sto : nullptr;
     a.fix_count = after_fix ? w.fix_count : nullptr;
@@ -322,19 +330,6 @@ struct FinArgs {
 constexpr int FIN_KY = 8;          // k lanes of a column block over a B stored K x N
 constexpr int FIN_MAX_BLOCKS = 1024;
 constexpr int FIN_GROUP = 16;          // blocks per first-level ticket
-
-// Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a group ends with
-// the total.
-template <typename V> __device__ __forceinline__ V seg_sum(V v, int width)
-{
-    v = add_t(v, dpp_get<0xB1>(v));    // lane ^ 1
-    v = add_t(v, dpp_get<0x4E>(v));    // lane ^ 2
-    v = add_t(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
-    if (width >= 16) v = add_t(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
-    if (width >= 32) v = add_t(v, __shfl_xor(v, 16));
-    if (width >= 64) v = add_t(v, __shfl_xor(v, 32));
-    return v;
-}
 
 // Work is cut into units: (batch item, block of columns) and (batch item, block of 256 rows).
 // A block takes units blockIdx.x, blockIdx.x + gridDim.x, ...: many small batch items (attention
@@ -639,7 +634,7 @@ __global__ __launch_bounds__(256) void verify_kernel(VerArgs a)
                     }
                 }
             }
-            for (int o = 1; o < CW; o <<= 1) s = add_t(s, __shfl_xor(s, o));
+            s = seg_sum(s, CW);
             if (cx == 0 && r < rend) atomic_add_word(a.rc_vobs + (long)bz * a.M + r, s);
         }
     }
@@ -813,7 +808,8 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
 }
 
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, bool with_sto, hipStream_t st)
+                          const Workspace &w, const Verdict &v, bool with_sto, size_t stale_words,
+                          uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
 {
     hipError_t e = launch_zero(w.fix_count, 2, st);
     if (e != hipSuccess) return e;
@@ -837,9 +833,9 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     if ((e = hipGetLastError()) != hipSuccess) return e;
     // re-check: the stored C is re-summed as a whole (a streaming pass at HBM speed is cheaper
     // than strided column walks over the touched tiles) and compared with the predictions
-    if ((e = launch_zero(w.cc_vobs, (size_t)s.batch * ((size_t)s.M + s.N), st)) != hipSuccess) return e;
+    if (stale_words && (e = launch_zero(w.cc_vobs, stale_words, st)) != hipSuccess) return e;
     if ((e = launch_verify_sums(dt, C, s, w, st)) != hipSuccess) return e;
-    return launch_compare(dt, s, w, v, true, with_sto, st);
+    return launch_compare(dt, s, w, v, true, with_sto, zero_ptr, zero_words, st);
 }
 
 // ====================================================================== inject
