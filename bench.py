@@ -177,7 +177,7 @@ def main():
                     localised += 1
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                ab.abft_correct(ctx, run.dA, run.dB, run.dC, run.code, run.shape, res)
+                ab.abft_correct(ctx, run.dA, run.dB, run.dC, run.code, run.shape, run.result())
                 torch.cuda.synchronize()
                 t_corr += time.perf_counter() - t0
                 if torch.equal(run.dC, C_clean):
@@ -191,6 +191,27 @@ def main():
 
     camp = campaign(ab.ABFT_DETECT, 1.0)
     camp_sto = campaign(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS, 1e-2)
+    # threshold read off the clean discrepancies (the paper's Eps Generation): |mean| + z std of
+    # (re-summed stored C - prediction) over the rows and columns of this GEMM
+    step(ab.ABFT_DETECT)
+    run.verify()
+    stats = torch.zeros((1, 8), dtype=torch.float32, device="cuda")
+    rc = ab.abft_discrepancy(ctx, run.code, run.shape, ab.ABFT_DISC_STORED, stats)
+    assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+    torch.cuda.synchronize()
+    st = stats.cpu().numpy().astype(np.float64)[0]
+    n_all = st[3] + st[7]
+    mean = (st[0] + st[4]) / n_all
+    std = float(np.sqrt(max((st[1] + st[5]) / n_all - mean * mean, 0.0)))
+    z_cal = 4.5
+    tau_cal = abs(mean) + z_cal * std
+    tau_analytic = float(run.ws(ab.ABFT_WS_TAU)[0, 0])
+    run.tau = float(max(tau_cal, max(st[2], st[6]) * 1.01))       # never below the largest clean discrepancy seen
+    camp_cal = campaign(ab.ABFT_DETECT, run.tau / tau_analytic)
+    run.verify()
+    clean_under_cal = int(run.cnt()[0] + run.cnt()[1])
+    tau_used = run.tau
+    run.tau = 0.0
     ms_sto = timed(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS, args.steps, 5)
 
     out = {
@@ -227,6 +248,12 @@ def main():
             "flips": dict(camp, note="stored-C single-bit flips, exponent/mantissa 50/50, each applied alone; "
                           "S1 = |delta| > tolerance or non-finite (the gating stratum), S2 = |delta| > "
                           "1e-2 max|C|; flips with |delta| <= tolerance are undetectable by construction"),
+            "calibrated_tau": dict(camp_cal, z=z_cal, mean=mean, std=std, max_clean_abs=float(max(st[2], st[6])),
+                                   tau_calibrated=tau_used, tau_analytic=tau_analytic,
+                                   false_positive_flags_clean=clean_under_cal,
+                                   note="same flips, verify against the predictions with the tolerance read off "
+                                        "this GEMM's own clean discrepancies (stored C re-summed minus "
+                                        "prediction): |mean| + z std"),
             "stored_sums_mode": dict(camp_sto, ms_per_step=ms_sto,
                                      note="same flips with ABFT_STORED_SUMS: verify also compares the re-summed "
                                           "stored C with the epilogue's sums of the rounded values, tolerance "

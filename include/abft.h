@@ -180,6 +180,19 @@ int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape
 int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
                  const abft_shape *s, const abft_result *r, void *stream);
 
+/* Eps generation (Sec. III-B.1 "Eps Generation": the floating-point threshold of a layer is read
+ * off the distribution of its checksum discrepancy over fault-free runs, at a chosen
+ * confidence).  Writes, for every batch item of the last protected abft_gemm of this shape,
+ * statistics of d = observed - predicted: stats[b][0..3] = sum d, sum d^2, max|d|, count over
+ * the M rows, stats[b][4..7] the same over the N columns (device floats).  source
+ * ABFT_DISC_FUSED: observed = the epilogue's sums of the accumulators; ABFT_DISC_STORED:
+ * observed = the re-sum of stored C by the last abft_verify (ABFT_ESTATE without one).  The caller
+ * pools these over runs and sets abft_result.tau, e.g. |mean| + z * std.  Floating point only
+ * (ABFT_EINVAL for ABFT_I8). */
+enum { ABFT_DISC_FUSED = 0, ABFT_DISC_STORED = 1 };
+int abft_discrepancy(abft_ctx *ctx, abft_dtype dtype, const abft_shape *s, int source, float *stats,
+                     void *stream);
+
 /* Test hook for the single-bit-flip fault model.  ABFT_INJECT_STORED_C inverts bit `bit`
  * (0..31 for int32 C, 0..15 for bf16/f16 C) of C[batch_idx][row][col] on the stream.
  * ABFT_INJECT_ACCUMULATOR arms a one-shot flip of bit 0..31 of the int32/fp32 accumulator of

@@ -354,3 +354,26 @@ def check_stored(P: Protected, X_stored: np.ndarray):
     E, status = localise(row_flag, col_flag)
     return row_flag, col_flag, E, status
 
+
+def discrepancy_stats(P: Protected, X_stored: np.ndarray):
+    """Statistics of d = observed - predicted over the rows and the columns of a stored output
+    (Sec. III-B.1 "Eps Generation": the threshold is read off the fault-free distribution of the
+    checksum discrepancy).  Returns {"rows": (sum, sumsq, maxabs, count), "cols": (...)} in fp64."""
+    cc_obs, rc_obs, _ = observe(decode_stored(X_stored, P.dtype))
+    out = {}
+    for name, obs, pred in (("rows", rc_obs, P.rc_pred), ("cols", cc_obs, P.cc_pred)):
+        d = np.asarray(obs, dtype=np.float64) - np.asarray(pred, dtype=np.float64)
+        out[name] = (float(d.sum()), float((d * d).sum()), float(np.max(np.abs(d))), int(d.size))
+    return out
+
+
+def calibrated_tau(stats, z: float) -> float:
+    """Threshold at z standard deviations from pooled discrepancy statistics (normal fit, the
+    paper's default): |mean| + z * std over every (sum, sumsq, maxabs, count) tuple in `stats`."""
+    n = sum(t[3] for t in stats)
+    s = sum(t[0] for t in stats)
+    s2 = sum(t[1] for t in stats)
+    mean = s / n
+    var = max(s2 / n - mean * mean, 0.0)
+    return abs(mean) + z * var ** 0.5
+

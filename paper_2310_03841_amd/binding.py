@@ -15,14 +15,14 @@ _LIB_PATH = os.path.join(_HERE, "libabft.so")
 
 __all__ = [
     "ABFT_I8", "ABFT_BF16", "ABFT_F16", "ABFT_OFF", "ABFT_DETECT", "ABFT_DETECT_CORRECT",
-    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
+    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
     "ABFT_EHIP", "ABFT_ESTATE", "ABFT_CLEAN", "ABFT_LOCALISED", "ABFT_CHECKSUM_SUSPECT", "ABFT_TOO_MANY",
     "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR",
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
     "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS", "ABFT_WS_CC_STO", "ABFT_WS_RC_STO",
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
     "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_verify", "abft_correct",
-    "abft_inject", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
+    "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
     "abft_version", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
 
@@ -31,6 +31,7 @@ DTYPE_CODE = {"i8": ABFT_I8, "bf16": ABFT_BF16, "f16": ABFT_F16}
 ABFT_OFF, ABFT_DETECT, ABFT_DETECT_CORRECT = 0, 1, 2
 ABFT_B_CHECKSUM_CACHED = 0x10
 ABFT_STORED_SUMS = 0x20
+ABFT_DISC_FUSED, ABFT_DISC_STORED = 0, 1
 ABFT_OK, ABFT_EINVAL, ABFT_EALIGN, ABFT_ESHAPE, ABFT_EWORKSPACE, ABFT_EHIP, ABFT_ESTATE = 0, -1, -2, -3, -4, -5, -6
 ABFT_CLEAN, ABFT_LOCALISED, ABFT_CHECKSUM_SUSPECT, ABFT_TOO_MANY = 0, 1, 2, 3
 ABFT_INJECT_STORED_C, ABFT_INJECT_ACCUMULATOR = 0, 1
@@ -79,6 +80,8 @@ _SIGS = {
     "abft_inject": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_void_p]),
+    "abft_discrepancy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape), ctypes.c_int,
+                                        ctypes.c_void_p, ctypes.c_void_p]),
     "abft_workspace": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                       ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int64)]),
     "abft_tile_shape": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(abft_shape), ctypes.POINTER(ctypes.c_int),
@@ -203,6 +206,10 @@ def abft_inject(ctx, C, dtype: int, shape: abft_shape, batch_idx: int, row: int,
                 where: int = ABFT_INJECT_STORED_C, stream=None) -> int:
     return int(lib().abft_inject(ctx, _ptr(C), dtype, ctypes.byref(shape), batch_idx, row, col, bit, where,
                                  _stream(stream)))
+
+
+def abft_discrepancy(ctx, dtype: int, shape: abft_shape, source: int, stats, stream=None) -> int:
+    return int(lib().abft_discrepancy(ctx, dtype, ctypes.byref(shape), source, _ptr(stats), _stream(stream)))
 
 
 def abft_workspace(ctx, which: int, shape: abft_shape):

@@ -32,7 +32,7 @@ struct abft_ctx {
     InjectArm arm;
     int last_hip;
     // what the context currently holds
-    bool b_valid, pred_valid, sto_valid;
+    bool b_valid, pred_valid, sto_valid, vobs_valid;
     int b_dt, pred_dt;
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
@@ -300,6 +300,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     const bool cached = (mode & ABFT_B_CHECKSUM_CACHED) != 0;
     if (cached && !(ctx->b_valid && ctx->b_dt == (int)dtype && same_b(ctx->b_shape, *s))) return ABFT_ESTATE;
     ctx->pred_valid = false;
+    ctx->vobs_valid = false;
     if (!cached) ctx->b_valid = false;
     ctx->arm.batch = -1;
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
@@ -374,6 +375,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
     HIP_TRY(launch_compare(dtype, sh, w, v, false, ctx->sto_valid, rp.other, rp.other_words, st));
     end_resum(ctx, words);
+    ctx->vobs_valid = true;
     return ABFT_OK;
 }
 
@@ -396,6 +398,22 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words,
                            (hipStream_t)stream));
     end_resum(ctx, words);
+    return ABFT_OK;
+}
+
+extern "C" int abft_discrepancy(abft_ctx *ctx, abft_dtype dtype, const abft_shape *s, int source, float *stats,
+                                void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 0, &sh);
+    if (rc) return rc;
+    if (dtype == ABFT_I8) return ABFT_EINVAL;              // integers compare for equality: nothing to fit
+    if (!stats || (source != ABFT_DISC_FUSED && source != ABFT_DISC_STORED)) return ABFT_EINVAL;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    if (source == ABFT_DISC_STORED && !ctx->vobs_valid) return ABFT_ESTATE;
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    HIP_TRY(launch_discrepancy(sh, w, source == ABFT_DISC_STORED, stats, (hipStream_t)stream));
     return ABFT_OK;
 }
 

@@ -198,6 +198,7 @@ struct CmpArgs {
     const uint32_t *cc_pred, *rc_pred;
     const uint32_t *cc_obs, *rc_obs;
     const float *tau;
+    float tau_override;   // > 0: use this tolerance instead of tau[]
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
         for (size_t i = bid * 256 + tid; i < a.zero_words; i += nb * 256) a.zero_ptr[i] = 0u;
     }
-    const float tol = IS_INT ? 0.f : a.tau[bz];
+    const float tol = IS_INT ? 0.f : (a.tau_override > 0.f ? a.tau_override : a.tau[bz]);
     bool frow = false, fcol = false;
     if (idx < M) {
         frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], a.rc_pred[(long)bz * M + idx], tol);
@@ -288,7 +289,7 @@ hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verd
     a.fix_count = after_fix ? w.fix_count : nullptr;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
     a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
-    a.tau = w.tau;
+    a.tau = w.tau; a.tau_override = v.tau_override;
     a.row_flag = v.row_flag; a.col_flag = v.col_flag; a.counts = v.counts;
     a.ticket = w.cmp_ticket;
     a.M = s.M; a.N = s.N; a.batch = s.batch;
@@ -569,6 +570,58 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     case DT_F16:  hipLaunchKernelGGL(finish_kernel<DT_F16>, grid, dim3(256), smem, st, f); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+// ================================================================= discrepancy
+// Statistics of d = observed - predicted over the rows and over the columns of one GEMM: what
+// the paper's "Eps Generation" (Sec. III-B.1) fits its thresholds to.  One block per batch
+// item; out[bz] = { sum d, sum d^2, max|d|, count } for the rows, then the same for the columns.
+struct DiscArgs {
+    const uint32_t *cc_pred, *rc_pred, *cc_src, *rc_src;
+    int M, N;
+    float *out;           // [batch][8]
+};
+
+__global__ __launch_bounds__(256) void discrepancy_kernel(DiscArgs a)
+{
+    __shared__ float red[4][3];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, bz = blockIdx.x;
+    for (int side = 0; side < 2; ++side) {
+        const int n = side == 0 ? a.M : a.N;
+        const uint32_t *src = (side == 0 ? a.rc_src : a.cc_src) + (long)bz * n;
+        const uint32_t *pred = (side == 0 ? a.rc_pred : a.cc_pred) + (long)bz * n;
+        float s = 0.f, s2 = 0.f, mx = 0.f;
+        for (int i = tid; i < n; i += 256) {
+            const float dd = __uint_as_float(src[i]) - __uint_as_float(pred[i]);
+            s += dd;
+            s2 = __builtin_fmaf(dd, dd, s2);
+            mx = fmaxf(mx, fabsf(dd));
+        }
+        s = wave_sum(s);
+        s2 = wave_sum(s2);
+        mx = wave_max(mx);
+        __syncthreads();
+        if (lane == 0) { red[wave][0] = s; red[wave][1] = s2; red[wave][2] = mx; }
+        __syncthreads();
+        if (tid == 0) {
+            float *o = a.out + (long)bz * 8 + side * 4;
+            o[0] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
+            o[1] = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
+            o[2] = fmaxf(fmaxf(red[0][2], red[1][2]), fmaxf(red[2][2], red[3][2]));
+            o[3] = (float)n;
+        }
+    }
+}
+
+hipError_t launch_discrepancy(const Shape &s, const Workspace &w, bool stored, float *out, hipStream_t st)
+{
+    DiscArgs a;
+    a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
+    a.cc_src = stored ? w.cc_vobs : w.cc_obs;
+    a.rc_src = stored ? w.rc_vobs : w.rc_obs;
+    a.M = s.M; a.N = s.N; a.out = out;
+    hipLaunchKernelGGL(discrepancy_kernel, dim3((unsigned)s.batch), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

@@ -301,3 +301,39 @@ def test_tightened_storage_check_flags_exactly_the_flips_above_its_tolerance():
             assert (rf | rf0 == rf).all() and (cf | cf0 == cf).all()   # never weaker than the plain check
     assert seen_small > 0 and seen_mid > 0
 
+
+def test_discrepancy_statistics_and_calibrated_threshold_closed_forms():
+    """discrepancy_stats on a case with known discrepancies: shift the predictions of a clean
+    protected GEMM by constants c_r, c_c; then d = (clean d) + c exactly, so sum, sum of squares
+    and max follow in closed form from the unshifted statistics.  calibrated_tau on statistics
+    built from a known mean and spread returns |mean| + z * std."""
+    dtype = "f16"
+    M, N, K = 24, 40, 32
+    A, B = gen.gen_operands(dtype, M, N, K, 51, 52, trans_b=True)
+    P = orc.protected_gemm(A[0], B[0], dtype, True)
+    st0 = orc.discrepancy_stats(P, P.C_stored)
+    assert st0["rows"][3] == M and st0["cols"][3] == N
+    # clean discrepancies are the roundings of the stored values summed up: far below tau
+    assert st0["rows"][2] < P.tau and st0["cols"][2] < P.tau
+    cr, cc = 0.75, -1.25
+    import copy
+    Q = copy.copy(P)
+    Q.rc_pred = P.rc_pred - cr
+    Q.cc_pred = P.cc_pred - cc
+    st1 = orc.discrepancy_stats(Q, P.C_stored)
+    for name, c, n in (("rows", cr, M), ("cols", cc, N)):
+        s0, q0, _, _ = st0[name]
+        s1, q1, m1, n1 = st1[name]
+        assert n1 == n
+        assert s1 == pytest.approx(s0 + n * c, rel=1e-12, abs=1e-12)
+        assert q1 == pytest.approx(q0 + 2 * c * s0 + n * c * c, rel=1e-12, abs=1e-12)
+        assert abs(m1 - abs(c)) <= st0[name][2] + 1e-12
+    # a population of n values mean mu, variance v: sum = n mu, sumsq = n (v + mu^2)
+    mu, v, n = -0.02, 0.0009, 1000
+    tau = orc.calibrated_tau([(n * mu, n * (v + mu * mu), 0.2, n)], z=4.0)
+    assert tau == pytest.approx(0.02 + 4.0 * 0.03, rel=1e-12)
+    # pooling two groups equals one group with the sums added
+    t2 = orc.calibrated_tau([(1.0, 3.0, 1.0, 10), (-2.0, 5.0, 1.5, 30)], z=2.0)
+    t1 = orc.calibrated_tau([(-1.0, 8.0, 1.5, 40)], z=2.0)
+    assert t2 == pytest.approx(t1, rel=1e-15)
+
