@@ -189,7 +189,12 @@ template <typename V> __device__ __forceinline__ V seg_sum(V v, int width)
 
 __device__ __forceinline__ float wave_max(float v)
 {
-    for (int o = 1; o < 64; o <<= 1) v = fmaxf(v, __shfl_xor(v, o));
+    v = fmaxf(v, dpp_get<0xB1>(v));    // lane ^ 1
+    v = fmaxf(v, dpp_get<0x4E>(v));    // lane ^ 2
+    v = fmaxf(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
+    v = fmaxf(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
     return v;
 }
 
