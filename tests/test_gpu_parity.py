@@ -507,3 +507,87 @@ def test_full_size_int8_fc2_sampled(ctx_big):
         assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]
         run.correct()
         assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN
+
+
+@pytest.fixture(scope="module")
+def ctx_block():
+    # one transformer block of ViT-L/16 at 384^2, batch 64: 1024 per-head GEMMs of 577 x 577
+    c = ab.abft_create(max_rows=1024 * 577, max_cols=1024 * 577, max_depth=1024 * 640, max_batch=1024)
+    yield c
+    ab.abft_destroy(c)
+
+
+def _block_cases():
+    for cfg in (2, 3):
+        for gi, g in enumerate(gen.CONFIGS[cfg]["gemms"]):
+            yield pytest.param(cfg, gi, id=f"cfg{cfg + 1}-{g['name']}")
+
+
+@pytest.mark.parametrize("cfg,gi", list(_block_cases()))
+def test_transformer_block_gemms_full_size_sampled(ctx_block, cfg, gi):
+    """Every GEMM class of one ViT-B/16 block (bf16, batch 32) and one ViT-L/16 block at 384^2
+    (int8, batch 64) at full size.  The oracle gives all checksum vectors of every batch item
+    (O(MK + KN + K(M+N)) work per item) and a seeded sample of full rows of C; the flags must be
+    clean; one stored flip is localised and repaired."""
+    dtype = gen.CONFIGS[cfg]["dtype"]
+    g = gen.CONFIGS[cfg]["gemms"][gi]
+    M, N, K, batch, tb = g["M"], g["N"], g["K"], g["batch"], g["trans_b"]
+    A, B = gen.gen_operands(dtype, M, N, K, gen.seed_for(cfg, 10 + 2 * gi), gen.seed_for(cfg, 11 + 2 * gi),
+                            trans_b=tb, batch=batch, a_kind=g["a_kind"], b_kind=g["b_kind"])
+    run = Run(ctx_block, dtype, A, B, tb)
+    run.gemm(ab.ABFT_DETECT)
+    rf, cf = run.flags()
+    cnt = run.cnt()
+    assert not rf.any() and not cf.any() and cnt[0] == 0 and cnt[1] == 0 and cnt[2] == ab.ABFT_CLEAN
+    got = {w: run.ws(w) for w in (ab.ABFT_WS_A_SUM, ab.ABFT_WS_B_SUM, ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED,
+                                  ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS, ab.ABFT_WS_S_PRED)}
+    tau_g = run.ws(ab.ABFT_WS_TAU)
+    rng = np.random.default_rng(gen.seed_for(cfg, 40 + gi))
+    items = np.unique(np.concatenate([rng.integers(0, batch, 5), [0, batch - 1]]))
+    for bi in range(batch):
+        Ad = A[bi] if dtype == "i8" else orc.decode(A[bi], dtype)
+        Bd = B[bi] if dtype == "i8" else orc.decode(B[bi], dtype)
+        a, b = orc.encode(Ad, Bd, tb)
+        cc, rc, s = orc.predict(Ad, Bd, a, b, tb)
+        if dtype == "i8":
+            for w, want in ((ab.ABFT_WS_A_SUM, a), (ab.ABFT_WS_B_SUM, b), (ab.ABFT_WS_CC_PRED, cc),
+                            (ab.ABFT_WS_RC_PRED, rc), (ab.ABFT_WS_CC_OBS, cc), (ab.ABFT_WS_RC_OBS, rc)):
+                assert np.array_equal(got[w][bi].view(np.uint32), ring(want)), (bi, w)
+            assert got[ab.ABFT_WS_S_PRED][bi, 0].view(np.uint32) == ring(s)
+        else:
+            ma, mb = np.max(np.abs(Ad)), np.max(np.abs(Bd))
+            tau = orc.tau(K, ma, mb)
+            assert tau_g[bi, 0] == pytest.approx(tau, rel=1e-5)
+            tol = 1e-2 * tau
+            assert np.max(np.abs(got[ab.ABFT_WS_A_SUM][bi] - a)) <= 1e-5 * M * ma
+            assert np.max(np.abs(got[ab.ABFT_WS_B_SUM][bi] - b)) <= 1e-5 * N * mb
+            assert np.max(np.abs(got[ab.ABFT_WS_CC_PRED][bi] - cc)) <= tol * np.sqrt(M)
+            assert np.max(np.abs(got[ab.ABFT_WS_RC_PRED][bi] - rc)) <= tol * np.sqrt(N)
+            assert np.max(np.abs(got[ab.ABFT_WS_CC_OBS][bi] - cc)) <= tol * np.sqrt(M)
+            assert np.max(np.abs(got[ab.ABFT_WS_RC_OBS][bi] - rc)) <= tol * np.sqrt(N)
+            assert abs(got[ab.ABFT_WS_S_PRED][bi, 0] - s) <= 1e-4 * K * M * N * ma * mb
+        if bi in items:
+            rows = np.unique(np.concatenate([rng.integers(0, M, 6), [0, M - 1]]))
+            ref = orc.gemm(np.ascontiguousarray(Ad[rows]), Bd, tb)
+            Cg = run.dC[bi][torch.as_tensor(rows, device="cuda")][:, :N].cpu().numpy()
+            if dtype == "i8":
+                assert np.array_equal(Cg, ref.astype(np.int32)), bi
+            else:
+                Cg = Cg.view(np.uint16)
+                val = orc.decode(Cg, dtype)
+                scale = np.max(np.abs(ref))
+                assert np.max(np.abs(val - ref)) <= 1e-2 * scale
+                assert np.all(np.abs(val - ref) <= 2.0 ** -8 * np.abs(ref) + 2e-6 * scale + 1e-7)
+                assert np.mean(Cg != orc.store(ref, dtype)) < 5e-3
+    # one stored flip (a high exponent bit for bf16, so that it is far above the tolerance)
+    C_before = run.dC.clone()
+    bi, i, j = int(items[-1]), int(rng.integers(0, M)), int(rng.integers(0, N))
+    bit = int(rng.integers(0, 32)) if dtype == "i8" else 14
+    run.inject(bi, i, j, bit)
+    run.verify()
+    rf, cf = run.flags()
+    assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, i] and cf[bi, j] and run.cnt()[2] == ab.ABFT_LOCALISED
+    run.correct()
+    assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
+    del run, C_before
+    torch.cuda.empty_cache()
