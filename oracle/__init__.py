@@ -278,6 +278,28 @@ def correct(X: np.ndarray, clean: np.ndarray, E) -> np.ndarray:
     return Y
 
 
+def correct_by_checksum(X: np.ndarray, cc_obs, rc_obs, cc_pred, rc_pred):
+    """Checksum-only correction of the classic scheme the paper builds on (Sec. II-B; the paper
+    itself replays, Sec. III-B.3): integers only.  With exactly one row i and one column j
+    flagged and the same discrepancy d on both (modulo 2^32), the corrupted element is
+    X[i, j] and X[i, j] - d is its value.  Anything else is left alone.
+
+    X: int32 stored output.  Returns (Y, fixed) with fixed in {0, 1}."""
+    _, rf = flags_int(rc_obs, rc_pred)
+    _, cf = flags_int(cc_obs, cc_pred)
+    Y = np.array(X, copy=True)
+    if rf.sum() != 1 or cf.sum() != 1:
+        return Y, 0
+    i, j = int(np.flatnonzero(rf)[0]), int(np.flatnonzero(cf)[0])
+    dr = (int(rc_obs[i]) - int(rc_pred[i])) % 2 ** 32
+    dc = (int(cc_obs[j]) - int(cc_pred[j])) % 2 ** 32
+    if dr != dc:
+        return Y, 0
+    v = (int(Y[i, j]) - dr) % 2 ** 32
+    Y[i, j] = v - 2 ** 32 if v >= 2 ** 31 else v
+    return Y, 1
+
+
 # ----------------------------------------------------------------------------
 # one protected GEMM, all steps
 # ----------------------------------------------------------------------------

@@ -337,3 +337,41 @@ def test_discrepancy_statistics_and_calibrated_threshold_closed_forms():
     t1 = orc.calibrated_tau([(-1.0, 8.0, 1.5, 40)], z=2.0)
     assert t2 == pytest.approx(t1, rel=1e-15)
 
+
+
+# ---------------------------------------------------------------- checksum-only correction
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (3, 4, 5), (5, 7, 3)])
+def test_checksum_only_correction_restores_every_single_bit_flip(M, N, K):
+    """The truth it is pinned to is the clean output itself: for every element and every bit, the
+    corrected matrix must be bit-identical to the undisturbed one (a wrong sign of d, a swapped
+    row/column index or a missing wrap-around fails this)."""
+    A, B = _int_case(M, N, K, True, 43)
+    P = orc.protected_gemm(A, B, "i8", True)
+    for i in range(M):
+        for j in range(N):
+            for bit in range(32):
+                X = orc.flip(P.C_stored, i, j, bit)
+                _, _, _, _, cc_obs, rc_obs = orc.check(P, X)
+                Y, fixed = orc.correct_by_checksum(X, cc_obs, rc_obs, P.cc_pred, P.rc_pred)
+                assert fixed == 1 and np.array_equal(Y, P.C_stored) and Y.dtype == np.int32
+
+
+def test_checksum_only_correction_leaves_what_it_cannot_explain():
+    A, B = _int_case(6, 5, 16, True, 44)
+    P = orc.protected_gemm(A, B, "i8", True)
+    # two errors in different rows and columns: two flags on each side
+    X = orc.flip(orc.flip(P.C_stored, 1, 2, 5), 4, 0, 9)
+    _, _, _, _, cc_obs, rc_obs = orc.check(P, X)
+    Y, fixed = orc.correct_by_checksum(X, cc_obs, rc_obs, P.cc_pred, P.rc_pred)
+    assert fixed == 0 and np.array_equal(Y, X)
+    # one flagged row and column whose discrepancies disagree (a checksum word was hit as well)
+    X = orc.flip(P.C_stored, 3, 3, 12)
+    _, _, _, _, cc_obs, rc_obs = orc.check(P, X)
+    cc_bad = cc_obs.copy()
+    cc_bad[3] += 1
+    Y, fixed = orc.correct_by_checksum(X, cc_bad, rc_obs, P.cc_pred, P.rc_pred)
+    assert fixed == 0 and np.array_equal(Y, X)
+    # clean
+    _, _, _, _, cc_obs, rc_obs = orc.check(P, P.C_stored)
+    Y, fixed = orc.correct_by_checksum(P.C_stored, cc_obs, rc_obs, P.cc_pred, P.rc_pred)
+    assert fixed == 0 and np.array_equal(Y, P.C_stored)
