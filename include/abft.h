@@ -36,10 +36,10 @@
  *     item: the library may read (never use) the pad between K and lda.
  *   - The caller owns A, B, C, the flag / count buffers and the stream.  The
  *     context owns its workspace (checksum vectors, tile lists).
- *   - abft_gemm / abft_verify / abft_correct / abft_inject / abft_encode_b only
- *     enqueue work on `stream` (a hipStream_t passed as void*): they allocate
- *     nothing, copy nothing to the host and never synchronise.  Results are
- *     valid once the stream has reached that point.
+ *   - abft_gemm / abft_verify / abft_correct / abft_correct_checksum / abft_inject /
+ *     abft_encode_b / abft_discrepancy only enqueue work on `stream` (a hipStream_t
+ *     passed as void*): they allocate nothing, copy nothing to the host and never
+ *     synchronise.  Results are valid once the stream has reached that point.
  *   - One context must be used from one stream at a time.
  *   - Return value: ABFT_OK or a negative error code.  A detected fault is NOT
  *     an error: it is reported through the flag vectors and counts.
@@ -179,6 +179,19 @@ int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape
  * caller replays the GEMM.  A and B must be unchanged since abft_gemm. */
 int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
                  const abft_shape *s, const abft_result *r, void *stream);
+
+/* Checksum-only correction (the inline correction of the classic scheme the paper starts from,
+ * Sec. II-B; the paper itself replays, Sec. III-B.3).  ABFT_I8 only (ABFT_EINVAL otherwise: a
+ * rounded floating-point sum cannot restore the stored bits).  Uses the flags in `r` and the
+ * re-summed stored C of the last abft_verify of this shape (ABFT_ESTATE without one; the flags
+ * must be the ones that call wrote).  For every batch item with exactly one flagged row i and
+ * one flagged column j whose discrepancies d = re-summed - predicted agree modulo 2^32:
+ * C[i][j] -= d, the item's flags are cleared and its re-summed vectors updated.  Every other
+ * pattern (several flags, one-sided flags, disagreeing discrepancies) is left untouched for
+ * abft_correct.  Reads neither A nor B and does not re-read C.  counts[0..2] = flags and status
+ * that remain, counts[3] = elements repaired, counts[4] = status before. */
+int abft_correct_checksum(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s,
+                          const abft_result *r, void *stream);
 
 /* Eps generation (Sec. III-B.1 "Eps Generation": the floating-point threshold of a layer is read
  * off the distribution of its checksum discrepancy over fault-free runs, at a chosen

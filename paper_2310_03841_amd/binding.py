@@ -22,7 +22,7 @@ __all__ = [
     "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS", "ABFT_WS_CC_STO", "ABFT_WS_RC_STO",
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
     "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_verify", "abft_correct",
-    "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
+    "abft_correct_checksum", "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
     "abft_version", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
 
@@ -77,6 +77,9 @@ _SIGS = {
     "abft_correct": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_int, ctypes.POINTER(abft_shape), ctypes.POINTER(abft_result),
                                     ctypes.c_void_p]),
+    "abft_correct_checksum": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                             ctypes.POINTER(abft_shape), ctypes.POINTER(abft_result),
+                                             ctypes.c_void_p]),
     "abft_inject": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_void_p]),
@@ -200,6 +203,11 @@ def abft_verify(ctx, C, dtype: int, shape: abft_shape, result: abft_result, stre
 def abft_correct(ctx, A, B, C, dtype: int, shape: abft_shape, result: abft_result, stream=None) -> int:
     return int(lib().abft_correct(ctx, _ptr(A), _ptr(B), _ptr(C), dtype, ctypes.byref(shape),
                                   ctypes.byref(result), _stream(stream)))
+
+
+def abft_correct_checksum(ctx, C, dtype: int, shape: abft_shape, result: abft_result, stream=None) -> int:
+    return int(lib().abft_correct_checksum(ctx, _ptr(C), dtype, ctypes.byref(shape), ctypes.byref(result),
+                                           _stream(stream)))
 
 
 def abft_inject(ctx, C, dtype: int, shape: abft_shape, batch_idx: int, row: int, col: int, bit: int,

@@ -350,6 +350,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         carve(ctx, dtype, sh, &w);
         HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, rp.stale, rp.other, rp.other_words, st));
         end_resum(ctx, words);
+        ctx->vobs_valid = true;
     }
     return ABFT_OK;
 }
@@ -398,6 +399,27 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words,
                            (hipStream_t)stream));
     end_resum(ctx, words);
+    ctx->vobs_valid = true;
+    return ABFT_OK;
+}
+
+extern "C" int abft_correct_checksum(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s,
+                                     const abft_result *r, void *stream)
+{
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 4, &sh);
+    if (rc) return rc;
+    if (dtype != ABFT_I8) return ABFT_EINVAL;     // a rounded sum cannot restore the stored bits
+    if (!C) return ABFT_EINVAL;
+    if (!aligned16(C)) return ABFT_EALIGN;
+    Verdict v;
+    rc = check_verdict(r, &v);
+    if (rc) return rc;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    if (!ctx->vobs_valid) return ABFT_ESTATE;     // needs the re-summed stored C of abft_verify
+    Workspace w;
+    carve(ctx, dtype, sh, &w);
+    HIP_TRY(launch_arith_fix(C, sh, w, v, (hipStream_t)stream));
     return ABFT_OK;
 }
 

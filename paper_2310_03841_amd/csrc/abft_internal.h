@@ -93,6 +93,8 @@ hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Works
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
                           const Workspace &w, const Verdict &v, bool with_sto, size_t stale_words,
                           uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
+// integers: repairs a single flagged element per batch item from the checksums alone
+hipError_t launch_arith_fix(void *C, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st);
 // stored: the sums of the last re-sum of stored C instead of the epilogue's
 hipError_t launch_discrepancy(const Shape &s, const Workspace &w, bool stored, float *out, hipStream_t st);
 hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,

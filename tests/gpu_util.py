@@ -89,6 +89,11 @@ class Run:
         assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
         torch.cuda.synchronize()
 
+    def correct_checksum(self):
+        rc = ab.abft_correct_checksum(self.ctx, self.dC, self.code, self.shape, self.result())
+        assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+        torch.cuda.synchronize()
+
     def inject(self, b, i, j, bit, where=ab.ABFT_INJECT_STORED_C):
         rc = ab.abft_inject(self.ctx, self.dC, self.code, self.shape, b, i, j, bit, where)
         assert rc == ab.ABFT_OK, ab.abft_strerror(rc)

@@ -591,3 +591,66 @@ def test_transformer_block_gemms_full_size_sampled(ctx_block, cfg, gi):
     assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
     del run, C_before
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 768, 768, 1, True), (130, 70, 100, 3, False),
+                                                 (520, 1030, 256, 2, True)])
+def test_checksum_only_correction_int8(ctx, M, N, K, batch, trans_b):
+    """Single stored flips repaired from the checksums alone (no operand read, no recompute):
+    the result must be what the oracle's checksum-only correction gives, i.e. the clean C bit
+    for bit; patterns the scheme cannot explain are left for the tile recompute."""
+    A, B = gen.gen_operands("i8", M, N, K, 311, 312, trans_b=trans_b, batch=batch)
+    P = oracle_items("i8", A, B, trans_b)
+    run = Run(ctx, "i8", A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT)
+    # before any verify there is no re-summed C to work from
+    assert ab.abft_correct_checksum(ctx, run.dC, run.code, run.shape, run.result()) == ab.ABFT_ESTATE
+    clean = np.stack([p.C_stored for p in P])
+    assert np.array_equal(run.C(), clean)
+    for (bi, i, j, bit) in gen.gen_flips(10, M, N, "i8", 313, batch=batch):
+        bi, i, j, bit = int(bi), int(i), int(j), int(bit)
+        run.inject(bi, i, j, bit)
+        run.verify()
+        X = run.C()
+        rf, cf = run.flags()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, i] and cf[bi, j]
+        _, _, _, _, cc_obs, rc_obs = orc.check(P[bi], X[bi])
+        want, fixed = orc.correct_by_checksum(X[bi], cc_obs, rc_obs, P[bi].cc_pred, P[bi].rc_pred)
+        assert fixed == 1
+        run.correct_checksum()
+        got = run.C()
+        assert np.array_equal(got[bi], want) and np.array_equal(got, clean)
+        cnt = run.cnt()
+        assert cnt[0] == 0 and cnt[1] == 0 and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+        rf, cf = run.flags()
+        assert not rf.any() and not cf.any()
+        # the re-summed vectors were updated with the repair: they equal the predictions again
+        assert np.array_equal(run.ws(ab.ABFT_WS_CC_VOBS), run.ws(ab.ABFT_WS_CC_PRED))
+        assert np.array_equal(run.ws(ab.ABFT_WS_RC_VOBS), run.ws(ab.ABFT_WS_RC_PRED))
+        run.verify()
+        assert run.cnt()[2] == ab.ABFT_CLEAN
+    # two errors in one item (two flags on each side): untouched, left for the recompute;
+    # a single error in another item of the same call is still repaired
+    run.inject(0, 1, 2, 5)
+    run.inject(0, M - 1, N - 1, 30)
+    if batch > 1:
+        run.inject(batch - 1, 3, 4, 31)
+    run.verify()
+    X = run.C()
+    run.correct_checksum()
+    got = run.C()
+    for bi in range(batch):
+        _, _, _, _, cc_obs, rc_obs = orc.check(P[bi], X[bi])
+        want, _ = orc.correct_by_checksum(X[bi], cc_obs, rc_obs, P[bi].cc_pred, P[bi].rc_pred)
+        assert np.array_equal(got[bi], want), bi
+    assert np.array_equal(got[0], X[0]) and not np.array_equal(got[0], clean[0])
+    cnt = run.cnt()
+    assert cnt[0] == 2 and cnt[1] == 2 and cnt[2] == ab.ABFT_LOCALISED and cnt[3] == (1 if batch > 1 else 0)
+    run.correct()
+    assert np.array_equal(run.C(), clean) and run.cnt()[2] == ab.ABFT_CLEAN
+    # floating point is refused
+    Af, Bf = gen.gen_operands("bf16", 64, 64, 64, 1, 2, trans_b=True)
+    rf16 = Run(ctx, "bf16", Af, Bf, True)
+    rf16.gemm(ab.ABFT_DETECT)
+    rf16.verify()
+    assert ab.abft_correct_checksum(ctx, rf16.dC, rf16.code, rf16.shape, rf16.result()) == ab.ABFT_EINVAL
