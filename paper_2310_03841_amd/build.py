@@ -10,8 +10,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libabft.so")
-SOURCES = ["gemm_kernel.hip", "gemm_fast.hip", "aux_kernels.hip", "abft_api.hip"]
-HEADERS = ["abft_internal.h", "abft_device.h", "gemm_args.h", "gemm_epilogue.h", os.path.join("..", "..", "include", "abft.h")]
+SOURCES = ["gemm_kernel.hip", "gemm_fast.hip", "gemm_item.hip", "aux_kernels.hip", "abft_api.hip"]
+HEADERS = ["abft_internal.h", "abft_device.h", "gemm_args.h", "gemm_epilogue.h", "gemm_apass.h", os.path.join("..", "..", "include", "abft.h")]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-munsafe-fp-atomics",

@@ -305,6 +305,17 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->arm.batch = -1;
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
+    const bool stored = (mode & ABFT_STORED_SUMS) != 0;
+    if (gemm_item_eligible(dtype, sh, stored)) {
+        // Batch of small problems: one kernel does everything and writes the workspace vectors
+        // with plain stores, into the region and the b slot in use (nothing has to start at zero).
+        if (ev) HIP_TRY(hipEventRecord(ev[1], st));
+        if (!cached) ctx->bclean[ctx->bslot] = false;
+        if (ctx->dirty[ctx->cur] < w.zero_words) ctx->dirty[ctx->cur] = w.zero_words;
+        ctx->sto_valid = false;
+        HIP_TRY(launch_gemm_item(dtype, true, cached, A, B, C, sh, w, &v, arm, st));
+        if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
+    } else {
     // This call accumulates into the region the previous protected call did not use.  It is
     // clean unless a call failed half way; the region of the previous call is cleared by this
     // call's finish kernel.  So a call with a cached B checksum is two kernels: GEMM, finish.
@@ -321,7 +332,6 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, stale, st));
     else if (stale) HIP_TRY(launch_zero(w.cc_obs, stale, st));
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-    const bool stored = (mode & ABFT_STORED_SUMS) != 0;
     ctx->sto_valid = false;
     HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
@@ -336,6 +346,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->dirty[prev] = 0;
     ctx->dirty[ctx->cur] = w.zero_words;
     if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
+    }
     ctx->b_valid = true;
     ctx->b_dt = dtype;
     ctx->b_shape = *s;
@@ -343,7 +354,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
     // a correction inside this call replaces values the stored-side sums already contain
-    ctx->sto_valid = stored && base == ABFT_DETECT;
+    ctx->sto_valid = stored && base == ABFT_DETECT && !gemm_item_eligible(dtype, sh, stored);
     if (base == ABFT_DETECT_CORRECT) {
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words);

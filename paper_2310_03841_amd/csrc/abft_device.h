@@ -198,6 +198,26 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// Products of checksum values (integer: in Z/2^32).
+__device__ __forceinline__ int mul_t(int x, int y) { return (int)((uint32_t)x * (uint32_t)y); }
+__device__ __forceinline__ float mul_t(float x, float y) { return x * y; }
+
+// The check of Sec. III-B.1 item (2): equality for fixed point, tolerance for floating point.
+template <bool IS_INT>
+__device__ __forceinline__ bool mismatch(uint32_t obs, uint32_t pred, float tol)
+{
+    if (IS_INT) return obs != pred;                          // equality in Z/2^32
+    float d = fabsf(__uint_as_float(obs) - __uint_as_float(pred));
+    return !(d <= tol);                                      // NaN and Inf always flag
+}
+
+__device__ __forceinline__ uint32_t status_of(uint32_t nr, uint32_t nc)
+{
+    if (nr == 0 && nc == 0) return 0u;      // clean
+    if (nr == 0 || nc == 0) return 2u;      // checksum suspect
+    return 1u;                              // localised
+}
+
 // Keep the first nbytes (0..16) of a 16-byte chunk, zero the rest.
 __device__ __forceinline__ i32x4 mask_chunk(i32x4 v, int nbytes)
 {

@@ -134,8 +134,6 @@ __global__ __launch_bounds__(256) void encode_b_kernel(EncBArgs e)
     }
 }
 
-__device__ __forceinline__ int mul_t(int x, int y) { return (int)((uint32_t)x * (uint32_t)y); }
-__device__ __forceinline__ float mul_t(float x, float y) { return x * y; }
 
 struct EncPlan { int cw_log2, nwin, rpb, nrb; };
 
@@ -208,21 +206,6 @@ struct CmpArgs {
     size_t zero_words;    // so that the next re-sum finds it clean
     int M, N, batch;
 };
-
-template <bool IS_INT>
-__device__ __forceinline__ bool mismatch(uint32_t obs, uint32_t pred, float tol)
-{
-    if (IS_INT) return obs != pred;                          // equality in Z/2^32
-    float d = fabsf(__uint_as_float(obs) - __uint_as_float(pred));
-    return !(d <= tol);                                      // NaN and Inf always flag
-}
-
-__device__ __forceinline__ uint32_t status_of(uint32_t nr, uint32_t nc)
-{
-    if (nr == 0 && nc == 0) return 0u;      // clean
-    if (nr == 0 || nc == 0) return 2u;      // checksum suspect
-    return 1u;                              // localised
-}
 
 template <bool IS_INT>
 __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)

@@ -1,0 +1,800 @@
+// Protected GEMM for batches of small problems (the per-head attention products Q K^T and
+// attn V): one workgroup owns a whole batch item, so every checksum of the scheme
+// (Sec. III-B.1 "Checksums") is formed and checked inside that workgroup -- no atomics on
+// global memory, no separate pass over B, no finish kernel.
+//
+// Per item: B is brought into LDS once and stays (as rows n of K-contiguous 128-byte slabs, the
+// layout the MFMA fragment reads want; a B stored K x N is transposed on the way in).  b = B e
+// and max|B| are taken from that copy.  A streams through a ring of LDS buffers in blocks of 32
+// or 64 rows, filled by direct-to-LDS loads that a fifth wave issues several blocks ahead.  That
+// wave does nothing else: the memory counter of a wave counts its loads and its stores in one
+// sequence, so a wave that stores C cannot wait for a load without also waiting for its stores
+// to be acknowledged; with the roles split the four computing waves never wait on memory at
+// all.  From each resident block come a = e^T A, the row prediction A b and max|A| (gemm_apass.h), from the accumulators
+// the observed row and column sums (before rounding; Sec. IV-C memory paragraph, Sec. V
+// "Optimizations" (2)), and C leaves through a wave-private LDS stage as row-contiguous
+// segments.  When the last block is done the column prediction a B is formed from the resident
+// B, both pairs are compared (equality for int8, tolerance for floating point; Sec. III-B.1
+// item (2)), and the vectors, flags and counts are written.
+//
+// These products are bound by memory traffic (about 39 flop per byte at 197 x 197 x 64), so the
+// design goal is streaming: few dependent round trips per item, whole-line stores, and nothing
+// read twice from memory.
+#include "abft_device.h"
+#include "gemm_args.h"
+#include "gemm_apass.h"
+#include "gemm_epilogue.h"
+
+namespace abft {
+
+constexpr int ITEM_MAX_SLABS = 5;          // K * element size <= 640 bytes
+constexpr int ITEM_MAX_M = 1024;
+constexpr int ITEM_MIN_BATCH = 64;         // fewer items leave most compute units without work
+constexpr int ITEM_MAX_BLOCKS = 1024;      // workgroups; items beyond are taken in turn
+constexpr int ITEM_GROUP = 16;             // workgroups per first-level ticket
+constexpr int ITEM_STAGE_ROW = 36;         // words per staged row of a 32 x 32 block (32 + pad)
+constexpr int ITEM_STAGE_WAVE = 32 * ITEM_STAGE_ROW * 4;
+constexpr int ITEM_LDS_LIMIT = 160 * 1024;
+constexpr int ITEM_THREADS = 320;          // four computing waves and the loading wave
+constexpr int ITEM_MAX_STAGES = 8;
+
+typedef const __attribute__((address_space(1))) void *item_gas_ptr;
+typedef __attribute__((address_space(3))) void *item_las_ptr;
+
+// Workgroup barrier over LDS traffic only.  The waves meet to exchange data through LDS; a full
+// barrier would also wait until every store of C issued so far has been acknowledged (and, in
+// the loading wave, until every block in flight has landed), which is the latency this kernel
+// is built to hide.  Data that arrives in LDS by direct loads is waited for explicitly.
+__device__ __forceinline__ void item_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate).
+__device__ __forceinline__ void item_wait_vmcnt(int n)
+{
+#define ITEM_W(k) case k: asm volatile("s_waitcnt vmcnt(" #k ")" ::: "memory"); break;
+    switch (n) {
+        ITEM_W(0) ITEM_W(1) ITEM_W(2) ITEM_W(3) ITEM_W(4) ITEM_W(5) ITEM_W(6) ITEM_W(7)
+        ITEM_W(8) ITEM_W(9) ITEM_W(10) ITEM_W(11) ITEM_W(12) ITEM_W(13) ITEM_W(14) ITEM_W(15)
+        ITEM_W(16) ITEM_W(17) ITEM_W(18) ITEM_W(19) ITEM_W(20) ITEM_W(21) ITEM_W(22) ITEM_W(23)
+        ITEM_W(24) ITEM_W(25) ITEM_W(26) ITEM_W(27) ITEM_W(28) ITEM_W(29) ITEM_W(30) ITEM_W(31)
+        ITEM_W(32) ITEM_W(33) ITEM_W(34) ITEM_W(35) ITEM_W(36) ITEM_W(37) ITEM_W(38) ITEM_W(39)
+        ITEM_W(40) ITEM_W(41) ITEM_W(42) ITEM_W(43) ITEM_W(44) ITEM_W(45) ITEM_W(46) ITEM_W(47)
+        ITEM_W(48) ITEM_W(49) ITEM_W(50) ITEM_W(51) ITEM_W(52) ITEM_W(53) ITEM_W(54) ITEM_W(55)
+        ITEM_W(56) ITEM_W(57) ITEM_W(58) ITEM_W(59) ITEM_W(60) ITEM_W(61) ITEM_W(62) ITEM_W(63)
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+#undef ITEM_W
+}
+
+struct ItemArgs {
+    const uint8_t *A, *B;
+    uint8_t *C;
+    int M, N, K, batch;
+    long lda, ldb, ldc, sA, sB, sC;               // elements
+    int nslab;                                    // 128-byte slabs that cover a row of K
+    int nch;                                      // 16-byte chunks of a row that hold data
+    int ksteps;                                   // MFMA steps over K (32 bytes of K per row each)
+    int NB;                                       // blocks of 32 columns
+    int nrb;                                      // blocks of rows
+    int stages;                                   // LDS buffers of the ring A streams through (2..8)
+    int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
+    int mul24_ok;
+    int cached_b;                                 // take b and max|B| from b_sum / b_max instead of forming them
+    // protected launches: everything below is written with plain stores, item by item
+    uint32_t *cc_obs, *rc_obs, *rc_pred, *a_sum, *a_max, *b_sum, *b_max, *cc_pred, *s_pred;
+    float *maxabs, *tau;
+    float tau_override;
+    uint8_t *row_flag, *col_flag;
+    uint32_t *counts;
+    uint32_t *ticket;                             // [3]: ticket, flagged rows, flagged cols (self-cleaning)
+    uint32_t *group_ticket;                       // [ITEM_MAX_BLOCKS / ITEM_GROUP] (self-cleaning)
+};
+
+// Slabs of K a configuration takes: the column sums of A stay in registers over all row blocks
+// of an item (16 bytes of columns per slab and thread), so wide tiles leave room for few.
+__host__ __device__ constexpr int item_max_slabs(int wm, int tpw) { return wm == 2 ? ITEM_MAX_SLABS : (tpw <= 2 ? 3 : 2); }
+
+// LDS of a workgroup: B, `stages` buffers for blocks of A, the waves' output stages, vectors.
+__host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int M, int N, int K)
+{
+    const int es = elem_size(dt), ke = SLAB_BYTES / es;
+    const int nslab = (K * es + SLAB_BYTES - 1) / SLAB_BYTES;
+    const int bmr = 32 * wm, wn = 4 / wm;
+    const int Nr = (N + 31) / 32 * 32, Mr = (M + bmr - 1) / bmr * bmr;
+    size_t b = (size_t)nslab * Nr * SLAB_BYTES + (size_t)stages * nslab * bmr * SLAB_BYTES + 4 * ITEM_STAGE_WAVE;
+    b += ((size_t)2 * nslab * ke + 2 * Mr + Nr + 2 * wn * bmr + 24) * 4;
+    return b;
+}
+
+// Depth of the ring: as deep as half the LDS of a compute unit allows (two workgroups per
+// unit), else as deep as the whole allows; the loading wave waits with an immediate count, so
+// (stages - 2) blocks' worth of load instructions must stay below 64.  0: does not fit.
+__host__ inline int item_stages(int dt, int wm, int M, int N, int K)
+{
+    const int es = elem_size(dt);
+    const int nslab = (K * es + SLAB_BYTES - 1) / SLAB_BYTES;
+    const int ql = 4 * wm * nslab;
+    int smax = 2 + 63 / ql;
+    if (smax > ITEM_MAX_STAGES) smax = ITEM_MAX_STAGES;
+    const size_t fixed = item_lds_bytes(dt, wm, 0, M, N, K);
+    const size_t abuf = (size_t)nslab * 32 * wm * SLAB_BYTES;
+    const size_t budgets[2] = {(size_t)ITEM_LDS_LIMIT / 2, (size_t)ITEM_LDS_LIMIT};
+    for (int i = 0; i < 2; ++i) {
+        if (fixed >= budgets[i]) continue;
+        long st = (long)((budgets[i] - fixed) / abuf);
+        if (st > smax) st = smax;
+        if (st >= (i == 0 ? 3 : 2)) return (int)st;
+    }
+    return 0;
+}
+
+// WM x WN waves; a row block is 32 WM rows; wave (wm, wn) owns the 32-column blocks
+// wn, wn + WN, ... (TPW of them at most) of its 32 rows.
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
+__global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    typedef typename T::accv_t accv_t;
+    constexpr int ES = T::ES, OS = T::OS;
+    constexpr int CE = 16 / ES;                  // elements per 16-byte chunk
+    constexpr int KE = SLAB_BYTES / ES;          // elements of K per slab
+    constexpr int WN = 4 / WM, BMr = 32 * WM;
+    constexpr int MAXS = item_max_slabs(WM, TPW);   // slabs of K this configuration takes
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool loader = wave == 4;               // waves 0..3 compute, wave 4 streams A
+    const int wm = (wave & 3) / WN, wn = (wave & 3) % WN;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int c8 = tid & 7, rg = tid >> 3;       // loader / reducer view: chunk c8 of row rg (+ 32 p)
+    const int M = g.M, N = g.N, K = g.K;
+    const int nslab = g.nslab, NB = g.NB;
+    const int Nr = NB * 32, Mr = g.nrb * BMr;
+    const int kbytes = K * ES;
+
+    uint8_t *sB = smem;
+    uint8_t *sA0 = sB + (size_t)nslab * Nr * SLAB_BYTES;
+    const int abuf = nslab * BMr * SLAB_BYTES;
+    const int S = g.stages;
+    uint8_t *stage = sA0 + S * abuf + (wave & 3) * ITEM_STAGE_WAVE;
+    uint32_t *a_lds = reinterpret_cast<uint32_t *>(sA0 + S * abuf + 4 * ITEM_STAGE_WAVE);
+    uint32_t *b_lds = a_lds + nslab * KE;
+    uint32_t *rcobs = b_lds + nslab * KE;
+    uint32_t *rcpred = rcobs + Mr;
+    uint32_t *ccobs = rcpred + Mr;
+    uint32_t *rs_part = ccobs + Nr;              // [2][WN][BMr]
+    uint32_t *misc = rs_part + 2 * WN * BMr;     // [24]: 0..3 max|A| per wave, 4..7 max|B|, 8..11 a.b partials,
+                                                 // 16..23 flagged rows / columns per wave
+
+    auto wave_sync = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    unsigned nr_w = 0, nc_w = 0;                 // flagged rows / columns seen by this wave
+
+    // The ring starts as zeros: chunk positions beyond K are never loaded and must read as zero.
+    for (int q = tid; q < S * abuf / 16; q += ITEM_THREADS)
+        reinterpret_cast<i32x4 *>(sA0)[q] = i32x4{0, 0, 0, 0};
+    item_barrier();
+    const int QL = 4 * WM * nslab;               // load instructions per block of A
+    const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
+    const int tail_chunk = (kbytes & 15) ? g.nch - 1 : -1;      // chunk that ends inside its 16 bytes
+
+    for (int bz = blockIdx.x; bz < g.batch; bz += gridDim.x) {
+        const uint8_t *Ab = g.A + (long)bz * g.sA * ES;
+        const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
+        uint8_t *Cb = g.C + (long)bz * g.sC * OS;
+
+        // Block blk of A into its ring buffer: one wave instruction fills 8 rows of 128 bytes;
+        // lane l lands in row l >> 3, slot l & 7 and fetches chunk (l & 7) ^ (l >> 3), so that
+        // slot = chunk ^ (row & 7).  Rows past M (also whole blocks past the last one, which
+        // keep the number of loads in flight constant) fetch the last row: nothing of them is
+        // used.
+        auto issue_block = [&](int blk) __attribute__((always_inline)) {
+            uint8_t *slot = sA0 + (blk % S) * abuf;
+            for (int s2 = 0; s2 < nslab; ++s2) {
+                const int ch = s2 * 8 + lchunk;
+#pragma unroll
+                for (int g8 = 0; g8 < 4 * WM; ++g8) {
+                    int r = blk * BMr + g8 * 8 + lrow;
+                    r = r < M ? r : M - 1;
+                    const uint8_t *src = Ab + (long)r * g.lda * ES + ch * 16;
+                    uint8_t *dst = slot + s2 * BMr * SLAB_BYTES + g8 * 8 * SLAB_BYTES;
+                    if (ch < g.nch)
+                        __builtin_amdgcn_global_load_lds((item_gas_ptr)src, (item_las_ptr)dst, 16, 0, 0);
+                }
+            }
+        };
+        // the bytes of the last chunk of a row that lie beyond K are whatever the caller's
+        // buffer holds there: cleared in LDS before anybody reads the block
+        auto fix_tail = [&](int blk) __attribute__((always_inline)) {
+            if (tail_chunk >= 0 && lane < BMr) {
+                uint8_t *p = sA0 + (blk % S) * abuf + (tail_chunk >> 3) * BMr * SLAB_BYTES + lane * SLAB_BYTES +
+                             (((tail_chunk & 7) ^ (lane & 7)) * 16);
+                i32x4 v = *reinterpret_cast<i32x4 *>(p);
+                v = mask_chunk(v, kbytes - tail_chunk * 16);
+                *reinterpret_cast<i32x4 *>(p) = v;
+            }
+        };
+        if (loader) {
+            for (int b2 = 0; b2 < S - 1; ++b2) issue_block(b2);
+            item_wait_vmcnt((S - 2) * QL);                     // block 0 has arrived
+            fix_tail(0);
+        }
+
+        // ---- B of this item into LDS, every position written (pads and rows past N with zeros)
+        if (TRANSB) {
+            const int cpr = nslab * 8;                           // chunk positions per row
+            const int total = Nr * cpr;
+            if (!loader)
+            for (int q0 = tid; q0 < total; q0 += 4 * 256) {
+                i32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = q0 + 256 * u;
+                    v[u] = i32x4{0, 0, 0, 0};
+                    if (q < total) {
+                        const int n = q / cpr, ch = q - n * cpr;
+                        if (n < N && ch < g.nch) {
+                            i32x4 x = *reinterpret_cast<const i32x4 *>(Bb + (long)n * g.ldb * ES + ch * 16);
+                            if ((ch + 1) * 16 > kbytes) x = mask_chunk(x, kbytes - ch * 16);
+                            v[u] = x;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = q0 + 256 * u;
+                    if (q < total) {
+                        const int n = q / cpr, ch = q - n * cpr;
+                        *reinterpret_cast<i32x4 *>(sB + (size_t)(ch >> 3) * Nr * SLAB_BYTES + n * SLAB_BYTES +
+                                                   (((ch & 7) ^ (n & 7)) * 16)) = v[u];
+                    }
+                }
+            }
+        } else {
+            // B stored K x N: chunks run along n and are transposed element by element
+            for (int q = tid; q < nslab * Nr * 8; q += ITEM_THREADS)
+                reinterpret_cast<i32x4 *>(sB)[q] = i32x4{0, 0, 0, 0};
+            item_barrier();
+            const int cpr = (N + CE - 1) / CE;                   // chunks along n per row k
+            const int total = K * cpr;
+            if (!loader)
+            for (int q0 = tid; q0 < total; q0 += 4 * 256) {
+                i32x4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = q0 + 256 * u;
+                    v[u] = i32x4{0, 0, 0, 0};
+                    if (q < total) {
+                        const int k = q / cpr, chn = q - k * cpr;
+                        v[u] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * g.ldb + chn * CE) * ES);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = q0 + 256 * u;
+                    if (q < total) {
+                        const int k = q / cpr, chn = q - k * cpr;
+                        const int kb = k * ES;
+                        uint8_t *col = sB + (size_t)(kb >> 7) * Nr * SLAB_BYTES + (kb & 15);
+                        const int kc = (kb >> 4) & 7;
+#pragma unroll
+                        for (int e = 0; e < CE; ++e) {
+                            const int n = chn * CE + e;
+                            if (n < N) {
+                                uint8_t *d = col + n * SLAB_BYTES + ((kc ^ (n & 7)) * 16);
+                                if (ES == 2) {
+                                    const uint32_t w = (uint32_t)v[u][e >> 1];
+                                    *reinterpret_cast<uint16_t *>(d) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
+                                } else {
+                                    const uint32_t w = (uint32_t)v[u][e >> 2];
+                                    *d = (uint8_t)(w >> (8 * (e & 3)));
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (PROT && !loader) {
+            for (int k = tid; k < 2 * nslab * KE; k += 256) a_lds[k] = 0u;     // a_lds and b_lds
+            for (int n = tid; n < Nr; n += 256) ccobs[n] = 0u;
+            if (tid < 16) misc[tid] = 0u;
+        }
+        item_barrier();
+
+        // ---- b = B e and max|B| from the resident copy (or the cached encoding)
+        if (PROT) {
+            if (loader) {
+            } else if (g.cached_b) {
+                for (int k = tid; k < K; k += 256) b_lds[k] = g.b_sum[(long)bz * K + k];
+            } else {
+                float bmax = 0.f;
+                for (int s = 0; s < nslab; ++s) {
+                    acc_t cs[CE];
+#pragma unroll
+                    for (int q = 0; q < CE; ++q) cs[q] = T::zero();
+                    for (int j = 0; j < NB; ++j) {
+                        const i32x4 v = *reinterpret_cast<const i32x4 *>(
+                            sB + (size_t)s * Nr * SLAB_BYTES + (rg + 32 * j) * SLAB_BYTES + ((c8 ^ (rg & 7)) * 16));
+#pragma unroll
+                        for (int q = 0; q < CE; ++q) {
+                            const acc_t x = T::elem(v, q);
+                            cs[q] = add_t(cs[q], x);
+                            if (!T::IS_INT) bmax = fmaxf(bmax, fabsf((float)x));
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < CE; ++q) {
+                        acc_t t = cs[q];
+                        t = add_t(t, dpp_get<0x128>(t));          // lane ^ 8
+                        t = add_t(t, __shfl_xor(t, 16));
+                        t = add_t(t, __shfl_xor(t, 32));
+                        cs[q] = t;
+                    }
+                    if (lane < 8) {
+#pragma unroll
+                        for (int q = 0; q < CE; ++q) {
+                            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(b_lds) + s * KE + c8 * CE + q, (int)cs[q]);
+                            else atomicAdd(reinterpret_cast<float *>(b_lds) + s * KE + c8 * CE + q, (float)cs[q]);
+                        }
+                    }
+                }
+                if (!T::IS_INT) {
+                    bmax = wave_max(bmax);
+                    if (lane == 0) misc[4 + wave] = __float_as_uint(bmax);
+                }
+            }
+            item_barrier();
+        }
+
+        // ---- row blocks
+        float amax = 0.f;
+        acc_t csa[MAXS][CE];                     // column sums of A: chunk c8 of every slab, rows rg + 32 p
+#pragma unroll
+        for (int s2 = 0; s2 < MAXS; ++s2)
+#pragma unroll
+            for (int q = 0; q < CE; ++q) csa[s2][q] = T::zero();
+        acc_t cs[TPW][4];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cs[t][e] = T::zero();
+
+        for (int rb = 0; rb < g.nrb; ++rb) {
+            const int m0 = rb * BMr;
+            const uint8_t *sAc = sA0 + (rb % S) * abuf;
+            if (loader) {
+                // S - 1 blocks ahead; then block rb + 1 must be in place behind this barrier
+                issue_block(rb + S - 1);
+                item_wait_vmcnt((S - 2) * QL);
+                fix_tail(rb + 1);
+            } else {
+            if (PROT) {
+                // The block's share of a = e^T A (kept in registers until the item ends), of the
+                // row prediction A b and of max|A|: thread (c8, rg) reads chunk c8 of rows
+                // rg + 32 p in every slab; a row's dot product is completed over its 8 lanes.
+                acc_t dot[WM];
+#pragma unroll
+                for (int p = 0; p < WM; ++p) dot[p] = T::zero();
+#pragma unroll
+                for (int s2 = 0; s2 < MAXS; ++s2) {
+                    if (s2 < nslab) {
+                        acc_t bv[CE];
+#pragma unroll
+                        for (int q4 = 0; q4 < CE / 4; ++q4) {
+                            const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + s2 * KE + c8 * CE + 4 * q4);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) bv[4 * q4 + e] = from_word<acc_t>((uint32_t)w[e]);
+                        }
+#pragma unroll
+                        for (int p = 0; p < WM; ++p) {
+                            i32x4 x4 = *reinterpret_cast<const i32x4 *>(sAc + s2 * BMr * SLAB_BYTES +
+                                                                        (rg + 32 * p) * SLAB_BYTES + ((c8 ^ (rg & 7)) * 16));
+                            if (m0 + rg + 32 * p >= M) x4 = i32x4{0, 0, 0, 0};
+#pragma unroll
+                            for (int q = 0; q < CE; ++q) {
+                                const acc_t x = T::elem(x4, q);
+                                csa[s2][q] = add_t(csa[s2][q], x);
+                                if constexpr (T::IS_INT) {
+                                    dot[p] = g.mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot[p])
+                                                        : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot[p]);
+                                } else {
+                                    dot[p] = __builtin_fmaf((float)x, (float)bv[q], (float)dot[p]);
+                                    amax = fmaxf(amax, fabsf((float)x));
+                                }
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int p = 0; p < WM; ++p) {
+                    const acc_t d = row8_sum(dot[p]);
+                    if (c8 == p) rcpred[m0 + rg + 32 * p] = as_word(d);
+                }
+            }
+
+            accv_t acc[TPW];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[t][i] = T::zero();
+            const bool mact = (m0 + wm * 32) < M;
+            if (mact) {
+                for (int ks = 0; ks < g.ksteps; ++ks) {
+                    const int s = ks >> 2, s4 = ks & 3;
+                    const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
+                    const i32x4 af = *reinterpret_cast<const i32x4 *>(sAc + s * BMr * SLAB_BYTES +
+                                                                      (wm * 32 + l32) * SLAB_BYTES + sw);
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) {
+                        const int nb = t * WN + wn;
+                        if (nb < NB) {
+                            const i32x4 bf = *reinterpret_cast<const i32x4 *>(
+                                sB + (size_t)s * Nr * SLAB_BYTES + (nb * 32 + l32) * SLAB_BYTES + sw);
+                            acc[t] = T::mfma(bf, af, acc[t]);
+                        }
+                    }
+                }
+            }
+
+            // ---- epilogue of the row block: block by block through the wave's LDS stage.
+            // Lane l holds row l & 31 of a block and in register i column 8 (i >> 2) + 4 (l >> 5)
+            // + (i & 3); read back, lane l has four consecutive columns 4 (l & 7) .. of row
+            // 8 p + (l >> 3): eight lanes cover a 32-column row segment.
+            acc_t rsum[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
+            const int row0 = m0 + wm * 32 + (lane >> 3);             // this lane's row of pass 0; pass p: + 8 p
+            const long rowstep = 8 * g.ldc * OS;
+            uint8_t *dst_row0 = Cb + ((long)row0 * g.ldc + 4 * (lane & 7)) * OS;
+            const bool inj_blk = PROT && bz == g.inj_b && g.inj_row >= m0 && g.inj_row < m0 + BMr;
+            static_for<0, TPW>([&](auto t_c) {
+                constexpr int t = decltype(t_c)::value;
+                const int nb = t * WN + wn;
+                if (mact && nb < NB) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<i32x4 *>(stage + (l32 * ITEM_STAGE_ROW + 8 * q + 4 * lh) * 4) =
+                            i32x4{(int)as_word(acc[t][4 * q]), (int)as_word(acc[t][4 * q + 1]),
+                                  (int)as_word(acc[t][4 * q + 2]), (int)as_word(acc[t][4 * q + 3])};
+                    wave_sync();
+                    i32x4 w4[4];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p)
+                        w4[p] = *reinterpret_cast<const i32x4 *>(
+                            stage + ((8 * p + (lane >> 3)) * ITEM_STAGE_ROW + 4 * (lane & 7)) * 4);
+                    wave_sync();                                  // the stage is free for the next block
+                    const int gc = nb * 32 + 4 * (lane & 7);
+                    uint8_t *dst_blk = dst_row0 + (long)nb * 32 * OS;
+                    const bool cfull = gc + 4 <= N;
+                    if (inj_blk) {
+#pragma unroll
+                        for (int p = 0; p < 4; ++p)
+                            if (row0 + 8 * p == g.inj_row && g.inj_col >= gc && g.inj_col < gc + 4)
+                                w4[p][g.inj_col - gc] ^= (int)(1u << g.inj_bit);
+                    }
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const bool rv = row0 + 8 * p < M;          // rows past M hold a copy of the last row
+                        acc_t v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = from_word<acc_t>((uint32_t)w4[p][e]);
+                        if (PROT) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) cs[t][e] = add_t(cs[t][e], rv ? v[e] : T::zero());
+                            rsum[p] = add_t(rsum[p], add_t(add_t(v[0], v[1]), add_t(v[2], v[3])));
+                        }
+                        // Plain stores: the row segments of neighbouring blocks complete each other's
+                        // cache lines (rows of C are not line-aligned), which the L2 merges;
+                        // streaming stores sent the partial lines to memory one by one and ran
+                        // three to five times slower here.
+                        uint8_t *dst = dst_blk + p * rowstep;
+                        if constexpr (T::IS_INT) {
+                            if (rv && cfull) {
+                                *reinterpret_cast<i32x4 *>(dst) = w4[p];
+                            } else if (rv) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (gc + e < N) reinterpret_cast<int *>(dst)[e] = w4[p][e];
+                            }
+                        } else {
+                            const uint32_t lo = pack2<DT>((float)v[0], (float)v[1]);
+                            const uint32_t hi = pack2<DT>((float)v[2], (float)v[3]);
+                            if (rv && cfull) {
+                                typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+                                *reinterpret_cast<u32x2 *>(dst) = u32x2{lo, hi};
+                            } else if (rv) {
+                                uint16_t *d16 = reinterpret_cast<uint16_t *>(dst);
+                                if (gc + 0 < N) d16[0] = (uint16_t)(lo & 0xFFFFu);
+                                if (gc + 1 < N) d16[1] = (uint16_t)(lo >> 16);
+                                if (gc + 2 < N) d16[2] = (uint16_t)(hi & 0xFFFFu);
+                                if (gc + 3 < N) d16[3] = (uint16_t)(hi >> 16);
+                            }
+                        }
+                    }
+                }
+            });
+            if (PROT) {
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const acc_t r = row8_sum(rsum[p]);
+                    if ((lane & 7) == 0)
+                        rs_part[((rb & 1) * WN + wn) * BMr + wm * 32 + 8 * p + (lane >> 3)] = as_word(r);
+                }
+            }
+            }   // computing waves
+            item_barrier();
+            if (PROT && tid < BMr) {
+                acc_t t = T::zero();
+#pragma unroll
+                for (int w2 = 0; w2 < WN; ++w2)
+                    t = add_t(t, from_word<acc_t>(rs_part[((rb & 1) * WN + w2) * BMr + tid]));
+                rcobs[m0 + tid] = as_word(t);
+            }
+        }
+
+        if (loader) item_wait_vmcnt(0);                         // the blocks fetched past the end
+
+        // ---- the item's checks
+        if (PROT) {
+            if (!loader) {
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                const int nb = t * WN + wn;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc_t v = cs[t][e];
+                    v = add_t(v, dpp_get<0x128>(v));              // lane ^ 8
+                    v = add_t(v, __shfl_xor(v, 16));
+                    v = add_t(v, __shfl_xor(v, 32));
+                    if (lane < 8 && nb < NB) {
+                        uint32_t *dst = ccobs + nb * 32 + 4 * lane + e;
+                        if (WM == 1) *dst = as_word(v);
+                        else if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)v);
+                        else atomicAdd(reinterpret_cast<float *>(dst), (float)v);
+                    }
+                }
+            }
+            // a = e^T A: over the eight row groups of the wave, then over the waves
+#pragma unroll
+            for (int s2 = 0; s2 < MAXS; ++s2) {
+                if (s2 < nslab) {
+#pragma unroll
+                    for (int q = 0; q < CE; ++q) {
+                        acc_t v = csa[s2][q];
+                        v = add_t(v, dpp_get<0x128>(v));          // lane ^ 8
+                        v = add_t(v, __shfl_xor(v, 16));
+                        v = add_t(v, __shfl_xor(v, 32));
+                        if (lane < 8) {
+                            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(a_lds) + s2 * KE + c8 * CE + q, (int)v);
+                            else atomicAdd(reinterpret_cast<float *>(a_lds) + s2 * KE + c8 * CE + q, (float)v);
+                        }
+                    }
+                }
+            }
+            if (!T::IS_INT) {
+                const float m = wave_max(amax);
+                if (lane == 0) misc[wave] = __float_as_uint(m);
+            }
+            }
+            item_barrier();
+            float tol = 0.f, ma = 0.f, mb = 0.f;
+            if (!T::IS_INT) {
+                ma = fmaxf(fmaxf(__uint_as_float(misc[0]), __uint_as_float(misc[1])),
+                           fmaxf(__uint_as_float(misc[2]), __uint_as_float(misc[3])));
+                mb = g.cached_b ? __uint_as_float(g.b_max[bz])
+                                : fmaxf(fmaxf(__uint_as_float(misc[4]), __uint_as_float(misc[5])),
+                                        fmaxf(__uint_as_float(misc[6]), __uint_as_float(misc[7])));
+                tol = g.tau_override > 0.f ? g.tau_override : (1e-3f * (float)K) * ma * mb;
+            }
+            if (!loader) {
+            // columns: prediction a B from the resident B; LPC lanes share a column (four where
+            // there are at most 64 columns, so that all 256 threads take part)
+            constexpr int LPC = WM == 2 ? 4 : 1;
+            for (int n0 = 0; n0 < N; n0 += 256 / LPC) {
+                const int n = n0 + tid / LPC, part = tid % LPC;
+                bool fl = false;
+                acc_t dot = T::zero();
+                if (n < N) {
+                    for (int ch = part; ch < g.nch; ch += LPC) {
+                        const i32x4 v = *reinterpret_cast<const i32x4 *>(
+                            sB + (size_t)(ch >> 3) * Nr * SLAB_BYTES + n * SLAB_BYTES + (((ch & 7) ^ (n & 7)) * 16));
+                        const i32x4 *ap = reinterpret_cast<const i32x4 *>(a_lds + ch * CE);
+#pragma unroll
+                        for (int q4 = 0; q4 < CE / 4; ++q4) {
+                            const i32x4 aw = ap[q4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                dot = add_t(dot, mul_t(T::elem(v, 4 * q4 + e), from_word<acc_t>((uint32_t)aw[e])));
+                        }
+                    }
+                }
+                if (LPC == 4) {
+                    dot = add_t(dot, dpp_get<0xB1>(dot));         // lane ^ 1
+                    dot = add_t(dot, dpp_get<0x4E>(dot));         // lane ^ 2
+                }
+                if (n < N && part == 0) {
+                    const long o = (long)bz * N + n;
+                    const uint32_t obs = ccobs[n];
+                    g.cc_pred[o] = as_word(dot);
+                    g.cc_obs[o] = obs;
+                    fl = mismatch<T::IS_INT>(obs, as_word(dot), tol);
+                    g.col_flag[o] = fl ? 1 : 0;
+                }
+                nc_w += __popcll(__ballot(fl));
+            }
+            for (int r0 = 0; r0 < M; r0 += 256) {
+                const int r = r0 + tid;
+                bool fl = false;
+                if (r < M) {
+                    const long o = (long)bz * M + r;
+                    const uint32_t obs = rcobs[r], pred = rcpred[r];
+                    g.rc_obs[o] = obs;
+                    g.rc_pred[o] = pred;
+                    fl = mismatch<T::IS_INT>(obs, pred, tol);
+                    g.row_flag[o] = fl ? 1 : 0;
+                }
+                nr_w += __popcll(__ballot(fl));
+            }
+            acc_t sp = T::zero();
+            for (int k = tid; k < K; k += 256) {
+                const uint32_t aw = a_lds[k], bw = b_lds[k];
+                g.a_sum[(long)bz * K + k] = aw;
+                if (!g.cached_b) g.b_sum[(long)bz * K + k] = bw;
+                sp = add_t(sp, mul_t(from_word<acc_t>(aw), from_word<acc_t>(bw)));
+            }
+            sp = wave_sum(sp);
+            if (lane == 0) misc[8 + wave] = as_word(sp);
+            }
+            item_barrier();
+            if (tid == 0) {
+                g.s_pred[bz] = as_word(add_t(add_t(from_word<acc_t>(misc[8]), from_word<acc_t>(misc[9])),
+                                             add_t(from_word<acc_t>(misc[10]), from_word<acc_t>(misc[11]))));
+                if (!T::IS_INT) {
+                    g.maxabs[(long)bz * 2] = ma;
+                    g.maxabs[(long)bz * 2 + 1] = mb;
+                    g.tau[bz] = tol;
+                    g.a_max[bz] = __float_as_uint(ma);
+                    if (!g.cached_b) g.b_max[bz] = __float_as_uint(mb);
+                }
+            }
+        }
+        item_barrier();                                        // LDS is reused by the next item
+    }
+
+    if (PROT) {
+        // flagged rows / columns of this workgroup, then its ticket (in two levels: atomics on
+        // one word are served one after the other); the last workgroup writes counts and status
+        if (lane == 0 && !loader) { misc[16 + wave] = nr_w; misc[20 + wave] = nc_w; }
+        item_barrier();
+        if (tid == 0) {
+            const unsigned nr = misc[16] + misc[17] + misc[18] + misc[19];
+            const unsigned nc = misc[20] + misc[21] + misc[22] + misc[23];
+            if (nr | nc) {
+                // rare: the counts must have arrived before this workgroup's ticket does
+                unsigned o1 = 0, o2 = 0;
+                if (nr) o1 = atomicAdd(g.ticket + 1, nr);
+                if (nc) o2 = atomicAdd(g.ticket + 2, nc);
+                asm volatile("s_waitcnt vmcnt(0)" :: "v"(o1), "v"(o2) : "memory");
+            }
+            const unsigned grp = blockIdx.x / ITEM_GROUP, ngrp = (gridDim.x + ITEM_GROUP - 1) / ITEM_GROUP;
+            const unsigned gsize = min((unsigned)ITEM_GROUP, gridDim.x - grp * ITEM_GROUP);
+            bool last = false;
+            if (atomicAdd(g.group_ticket + grp, 1u) == gsize - 1) {
+                atomicExch(g.group_ticket + grp, 0u);
+                last = atomicAdd(g.ticket, 1u) == ngrp - 1;
+            }
+            if (last) {
+                const uint32_t r = atomicExch(g.ticket + 1, 0u), c = atomicExch(g.ticket + 2, 0u);
+                atomicExch(g.ticket, 0u);
+                g.counts[0] = r;
+                g.counts[1] = c;
+                g.counts[2] = status_of(r, c);
+                g.counts[3] = 0u;
+                g.counts[4] = status_of(r, c);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+static void item_config(int N, int *wm, int *tpw)
+{
+    if (N <= 64) { *wm = 2; *tpw = 1; }
+    else if (N <= 256) { *wm = 1; *tpw = 2; }
+    else { *wm = 1; *tpw = 5; }
+}
+
+bool gemm_item_eligible(int dt, const Shape &s, bool stored_sums)
+{
+    const int es = elem_size(dt);
+    if (stored_sums && dt != DT_I8) return false;          // the stored-side sums live in the tiled kernels
+    if (s.batch < ITEM_MIN_BATCH) return false;
+    if (s.N > 640 || s.M > ITEM_MAX_M) return false;
+    if ((long)s.K * es > ITEM_MAX_SLABS * SLAB_BYTES) return false;
+    int wm, tpw;
+    item_config(s.N, &wm, &tpw);
+    if (((long)s.K * es + SLAB_BYTES - 1) / SLAB_BYTES > item_max_slabs(wm, tpw)) return false;
+    return item_stages(dt, wm, s.M, s.N, s.K) >= 2;
+}
+
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
+static hipError_t launch_item_one(const ItemArgs &g, size_t smem, hipStream_t st)
+{
+    auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, ITEM_LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const unsigned blocks = (unsigned)(g.batch < ITEM_MAX_BLOCKS ? g.batch : ITEM_MAX_BLOCKS);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(ITEM_THREADS), smem, st, g);
+    return hipGetLastError();
+}
+
+template <int DT, int WM, int TPW>
+static hipError_t launch_item_cfg(bool protect, bool transB, const ItemArgs &g, size_t smem, hipStream_t st)
+{
+    if (protect) return transB ? launch_item_one<DT, WM, TPW, true, true>(g, smem, st)
+                               : launch_item_one<DT, WM, TPW, true, false>(g, smem, st);
+    return transB ? launch_item_one<DT, WM, TPW, false, true>(g, smem, st)
+                  : launch_item_one<DT, WM, TPW, false, false>(g, smem, st);
+}
+
+template <int DT>
+static hipError_t launch_item_dt(int wm, int tpw, bool protect, bool transB, const ItemArgs &g, size_t smem,
+                                 hipStream_t st)
+{
+    if (wm == 2) return launch_item_cfg<DT, 2, 1>(protect, transB, g, smem, st);
+    if (tpw == 2) return launch_item_cfg<DT, 1, 2>(protect, transB, g, smem, st);
+    return launch_item_cfg<DT, 1, 5>(protect, transB, g, smem, st);
+}
+
+hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, const void *A, const void *B, void *C,
+                            const Shape &s, const Workspace &w, const Verdict *v, const InjectArm &arm,
+                            hipStream_t st)
+{
+    if (!gemm_item_eligible(dt, s, false)) return hipErrorInvalidValue;
+    if (protect && v == nullptr) return hipErrorInvalidValue;
+    const int es = elem_size(dt);
+    int wm, tpw;
+    item_config(s.N, &wm, &tpw);
+    ItemArgs g;
+    g.A = (const uint8_t *)A; g.B = (const uint8_t *)B; g.C = (uint8_t *)C;
+    g.M = s.M; g.N = s.N; g.K = s.K; g.batch = s.batch;
+    g.lda = s.lda; g.ldb = s.ldb; g.ldc = s.ldc; g.sA = s.sA; g.sB = s.sB; g.sC = s.sC;
+    g.nslab = (s.K * es + SLAB_BYTES - 1) / SLAB_BYTES;
+    g.nch = (s.K * es + 15) / 16;
+    g.ksteps = (s.K * es + 31) / 32;
+    g.NB = (s.N + 31) / 32;
+    g.nrb = (s.M + 32 * wm - 1) / (32 * wm);
+    g.stages = item_stages(dt, wm, s.M, s.N, s.K);
+    g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
+    g.mul24_ok = s.N < 65536 ? 1 : 0;
+    g.cached_b = cached_b ? 1 : 0;
+    g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred; g.a_sum = w.a_sum; g.a_max = w.a_max;
+    g.b_sum = w.b_sum; g.b_max = w.b_max; g.cc_pred = w.cc_pred; g.s_pred = w.s_pred;
+    g.maxabs = w.maxabs; g.tau = w.tau;
+    g.tau_override = v ? v->tau_override : 0.f;
+    g.row_flag = v ? v->row_flag : nullptr; g.col_flag = v ? v->col_flag : nullptr;
+    g.counts = v ? v->counts : nullptr;
+    g.ticket = w.cmp_ticket; g.group_ticket = w.cmp_ticket + 4;
+    const size_t smem = item_lds_bytes(dt, wm, g.stages, s.M, s.N, s.K);
+    switch (dt) {
+    case DT_I8:   return launch_item_dt<DT_I8>(wm, tpw, protect, s.transB != 0, g, smem, st);
+    case DT_BF16: return launch_item_dt<DT_BF16>(wm, tpw, protect, s.transB != 0, g, smem, st);
+    case DT_F16:  return launch_item_dt<DT_F16>(wm, tpw, protect, s.transB != 0, g, smem, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace abft

@@ -263,6 +263,11 @@ static hipError_t launch_cfg(bool protect, bool transB, GemmArgs &g, int batch, 
 
 void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 {
+    if (gemm_item_eligible(dt, s, false)) {          // one workgroup per batch item
+        *tm = s.M;
+        *tn = s.N;
+        return;
+    }
     if (gemm_fast_eligible(dt, s.M, s.N, s.K, s.transB != 0, s.lda, s.ldb)) {
         gemm_fast_tile(tm, tn);
         return;
@@ -274,6 +279,8 @@ void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, const void *B, void *C,
                        const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st)
 {
+    if (!protect && gemm_item_eligible(dt, s, false))
+        return launch_gemm_item(dt, false, false, A, B, C, s, w, nullptr, arm, st);
     GemmArgs g;
     g.A = (const uint8_t *)A;
     g.B = (const uint8_t *)B;

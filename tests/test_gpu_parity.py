@@ -105,6 +105,10 @@ SHAPES = [
 @pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
 @pytest.mark.parametrize("M,N,K,batch,trans_b", SHAPES)
 def test_clean_gemm_matches_oracle(ctx, dtype, M, N, K, batch, trans_b):
+    _clean_case(ctx, dtype, M, N, K, batch, trans_b)
+
+
+def _clean_case(ctx, dtype, M, N, K, batch, trans_b):
     a_kind = "softmax" if (not trans_b and dtype != "i8") else "act"
     A, B = gen.gen_operands(dtype, M, N, K, 101 + M, 202 + N, trans_b=trans_b, batch=batch,
                             a_kind=a_kind, b_kind="weight" if batch == 1 else "act")
@@ -654,3 +658,92 @@ def test_checksum_only_correction_int8(ctx, M, N, K, batch, trans_b):
     rf16.gemm(ab.ABFT_DETECT)
     rf16.verify()
     assert ab.abft_correct_checksum(ctx, rf16.dC, rf16.code, rf16.shape, rf16.result()) == ab.ABFT_EINVAL
+
+
+# ---------------------------------------------------------------- batches of small problems
+@pytest.fixture(scope="module")
+def ctx_items():
+    c = ab.abft_create(max_rows=66 * 640, max_cols=66 * 640, max_depth=66 * 640, max_batch=66)
+    yield c
+    ab.abft_destroy(c)
+
+
+ITEM_SHAPES = [
+    # (M, N, K, batch, trans_b): from 64 items on, one workgroup takes a whole item
+    (70, 50, 40, 64, True),        # N <= 64: 2 x 2 waves, 64-row blocks
+    (70, 50, 40, 64, False),
+    (130, 64, 197, 64, False),     # attn V shape with several slabs of K
+    (100, 130, 72, 65, True),      # N <= 256: 1 x 4 waves, two column blocks per wave at most
+    (45, 200, 100, 66, False),
+    (197, 197, 64, 64, True),      # per-head Q K^T
+    (60, 300, 24, 64, True),       # N <= 640: five column blocks per wave at most
+    (33, 577, 64, 64, False),
+    (1, 1, 1, 64, True),
+]
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", ITEM_SHAPES)
+def test_item_kernel_clean_matches_oracle(ctx_items, dtype, M, N, K, batch, trans_b):
+    s = ab.make_shape(M, N, K, batch=batch, lda=K, ldb=K if trans_b else N, ldc=N, transB=trans_b)
+    assert ab.abft_tile_shape(ab.DTYPE_CODE[dtype], s) == (M, N)      # the whole item per workgroup
+    _clean_case(ctx_items, dtype, M, N, K, batch, trans_b)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(70, 50, 40, 64, False), (100, 130, 72, 65, True)])
+def test_item_kernel_flips_cached_b_and_correction(ctx_items, dtype, M, N, K, batch, trans_b):
+    ctx = ctx_items
+    A, B = gen.gen_operands(dtype, M, N, K, 61, 62, trans_b=trans_b, batch=batch, b_kind="act")
+    P = oracle_items(dtype, A, B, trans_b)
+    run = Run(ctx, dtype, A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT)
+    check_clean(run, P)
+    C_clean = run.C().copy()
+    # the encoding of B left by that call serves a second one; so does abft_encode_b's
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)
+    check_clean(run, P)
+    assert ab.abft_encode_b(ctx, run.dB, run.code, run.shape) == ab.ABFT_OK
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)
+    check_clean(run, P)
+    # armed accumulator flips: caught by the check inside the kernel, at the element
+    fp = dtype != "i8"
+    for (bi, i, j, bit) in [(0, 0, 0, 30), (batch - 1, M - 1, N - 1, 30 if fp else 27), (7, M // 2, N // 2, 30 if fp else 0)]:
+        run.inject(bi, i, j, bit, ab.ABFT_INJECT_ACCUMULATOR)
+        run.gemm(ab.ABFT_DETECT)
+        rf, cf = run.flags()
+        cnt = run.cnt()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, i] and cf[bi, j]
+        assert cnt[0] == 1 and cnt[1] == 1 and cnt[2] == ab.ABFT_LOCALISED
+        run.correct()
+        assert np.array_equal(run.C(), C_clean) and run.cnt()[2] == ab.ABFT_CLEAN
+        run.gemm(ab.ABFT_DETECT)
+        assert run.cnt()[2] == ab.ABFT_CLEAN and np.array_equal(run.C(), C_clean)
+    run.inject(3, 5, 7, 30, ab.ABFT_INJECT_ACCUMULATOR)
+    run.gemm(ab.ABFT_DETECT_CORRECT)
+    cnt = run.cnt()
+    assert np.array_equal(run.C(), C_clean) and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+    # stored flips: verify works from the vectors the kernel left
+    for (bi, i, j, bit) in gen.gen_flips(8, M, N, dtype, 63, batch=batch):
+        bi, i, j, bit = int(bi), int(i), int(j), int(bit)
+        X = orc.flip(P[bi].C_stored, i, j, bit)
+        if dtype != "i8":
+            with np.errstate(all="ignore"):
+                delta = abs(orc.decode(X, dtype)[i, j] - orc.decode(P[bi].C_stored, dtype)[i, j])
+            if not (delta > 2 * P[bi].tau):            # below or near the tolerance: covered elsewhere
+                continue
+        run.inject(bi, i, j, bit)
+        run.verify()
+        rf, cf = run.flags()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, i] and cf[bi, j] and run.cnt()[2] == ab.ABFT_LOCALISED
+        run.correct()
+        assert np.array_equal(run.C(), C_clean) and run.cnt()[2] == ab.ABFT_CLEAN
+    # a tiled-kernel call after item calls on the same context (the regions they share)
+    A1, B1 = gen.gen_operands(dtype, 300, 200, 264, 64, 65, trans_b=True)
+    r1 = Run(ctx, dtype, A1, B1, True)
+    r1.gemm(ab.ABFT_DETECT)
+    check_clean(r1, oracle_items(dtype, A1, B1, True))
+    run.gemm(ab.ABFT_DETECT)
+    check_clean(run, P)
+    r1.gemm(ab.ABFT_DETECT)
+    check_clean(r1, oracle_items(dtype, A1, B1, True))
