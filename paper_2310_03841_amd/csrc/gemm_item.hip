@@ -101,14 +101,15 @@ __host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int
 {
     const int es = elem_size(dt), ke = SLAB_BYTES / es;
     const int nslab = (K * es + SLAB_BYTES - 1) / SLAB_BYTES;
-    const int bmr = 32 * wm, wn = 4 / wm;
+    const int bmr = 32 * wm;
     const int Nr = (N + 31) / 32 * 32, Mr = (M + bmr - 1) / bmr * bmr;
     size_t b = (size_t)nslab * Nr * SLAB_BYTES + (size_t)stages * nslab * bmr * SLAB_BYTES + 4 * ITEM_STAGE_WAVE;
-    b += ((size_t)2 * nslab * ke + 2 * Mr + Nr + 2 * wn * bmr + 24) * 4;
+    b += ((size_t)2 * nslab * ke + 2 * Mr + Nr + 24) * 4;
     return b;
 }
 
-// Depth of the ring: as deep as half the LDS of a compute unit allows (two workgroups per
+// Depth of the ring (a depth of all the item's row blocks means A is resident as a whole and the
+// computing waves run through the blocks without meeting): as deep as half the LDS of a compute unit allows (two workgroups per
 // unit), else as deep as the whole allows; the loading wave waits with an immediate count, so
 // (stages - 2) blocks' worth of load instructions must stay below 64.  0: does not fit.
 __host__ inline int item_stages(int dt, int wm, int M, int N, int K)
@@ -120,10 +121,12 @@ __host__ inline int item_stages(int dt, int wm, int M, int N, int K)
     if (smax > ITEM_MAX_STAGES) smax = ITEM_MAX_STAGES;
     const size_t fixed = item_lds_bytes(dt, wm, 0, M, N, K);
     const size_t abuf = (size_t)nslab * 32 * wm * SLAB_BYTES;
+    const int nrb = (M + 32 * wm - 1) / (32 * wm);
     const size_t budgets[2] = {(size_t)ITEM_LDS_LIMIT / 2, (size_t)ITEM_LDS_LIMIT};
     for (int i = 0; i < 2; ++i) {
         if (fixed >= budgets[i]) continue;
         long st = (long)((budgets[i] - fixed) / abuf);
+        if (st >= nrb) return nrb;               // all of A resident: no ring, no barriers per block
         if (st > smax) st = smax;
         if (st >= (i == 0 ? 3 : 2)) return (int)st;
     }
@@ -132,9 +135,14 @@ __host__ inline int item_stages(int dt, int wm, int M, int N, int K)
 
 // WM x WN waves; a row block is 32 WM rows; wave (wm, wn) owns the 32-column blocks
 // wn, wn + WN, ... (TPW of them at most) of its 32 rows.
-template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
-__global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
+// RES: every row block of an item has its own LDS buffer (stages == nrb).  Then all of A is
+// fetched at the start of the item, by the four computing waves themselves, and the loading
+// wave is left out: with four waves per workgroup two workgroups share a compute unit without
+// their waves competing for the registers of one SIMD.
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES>
+__global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
 {
+    constexpr int NT = RES ? 256 : ITEM_THREADS;
     using T = Traits<DT>;
     typedef typename T::acc_t acc_t;
     typedef typename T::accv_t accv_t;
@@ -148,7 +156,7 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool loader = wave == 4;               // waves 0..3 compute, wave 4 streams A
+    const bool loader = !RES && wave == 4;       // waves 0..3 compute, wave 4 streams A
     const int wm = (wave & 3) / WN, wn = (wave & 3) % WN;
     const int l32 = lane & 31, lh = lane >> 5;
     const int c8 = tid & 7, rg = tid >> 3;       // loader / reducer view: chunk c8 of row rg (+ 32 p)
@@ -167,8 +175,7 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
     uint32_t *rcobs = b_lds + nslab * KE;
     uint32_t *rcpred = rcobs + Mr;
     uint32_t *ccobs = rcpred + Mr;
-    uint32_t *rs_part = ccobs + Nr;              // [2][WN][BMr]
-    uint32_t *misc = rs_part + 2 * WN * BMr;     // [24]: 0..3 max|A| per wave, 4..7 max|B|, 8..11 a.b partials,
+    uint32_t *misc = ccobs + Nr;                 // [24]: 0..3 max|A| per wave, 4..7 max|B|, 8..11 a.b partials,
                                                  // 16..23 flagged rows / columns per wave
 
     auto wave_sync = [&]() __attribute__((always_inline)) {
@@ -180,10 +187,11 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
     unsigned nr_w = 0, nc_w = 0;                 // flagged rows / columns seen by this wave
 
     // The ring starts as zeros: chunk positions beyond K are never loaded and must read as zero.
-    for (int q = tid; q < S * abuf / 16; q += ITEM_THREADS)
+    for (int q = tid; q < S * abuf / 16; q += NT)
         reinterpret_cast<i32x4 *>(sA0)[q] = i32x4{0, 0, 0, 0};
     item_barrier();
     const int QL = 4 * WM * nslab;               // load instructions per block of A
+    const bool resident = RES || S >= g.nrb;     // every block of the item has its own buffer
     const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;
     const int tail_chunk = (kbytes & 15) ? g.nch - 1 : -1;      // chunk that ends inside its 16 bytes
 
@@ -223,11 +231,27 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
                 *reinterpret_cast<i32x4 *>(p) = v;
             }
         };
-        if (loader) {
-            for (int b2 = 0; b2 < S - 1; ++b2) issue_block(b2);
-            item_wait_vmcnt((S - 2) * QL);                     // block 0 has arrived
-            fix_tail(0);
+        if (RES) {
+            for (int b2 = wave; b2 < g.nrb; b2 += 4) issue_block(b2);
+        } else if (loader) {
+            if (resident) {
+                for (int b2 = 0; b2 < g.nrb; ++b2) issue_block(b2);
+                item_wait_vmcnt(0);
+                for (int b2 = 0; b2 < g.nrb; ++b2) fix_tail(b2);
+            } else {
+                for (int b2 = 0; b2 < S - 1; ++b2) issue_block(b2);
+                item_wait_vmcnt((S - 2) * QL);                 // block 0 has arrived
+                fix_tail(0);
+            }
         }
+
+        if (PROT && !loader) {
+            for (int k = tid; k < 2 * nslab * KE; k += 256) a_lds[k] = 0u;     // a_lds and b_lds
+            for (int n = tid; n < Nr; n += 256) ccobs[n] = 0u;
+            for (int r = tid; r < Mr; r += 256) rcobs[r] = 0u;
+            if (tid < 16) misc[tid] = 0u;
+        }
+        float bmax = 0.f;                                        // max|B| seen by this thread
 
         // ---- B of this item into LDS, every position written (pads and rows past N with zeros)
         if (TRANSB) {
@@ -261,7 +285,7 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
             }
         } else {
             // B stored K x N: chunks run along n and are transposed element by element
-            for (int q = tid; q < nslab * Nr * 8; q += ITEM_THREADS)
+            for (int q = tid; q < nslab * Nr * 8; q += NT)
                 reinterpret_cast<i32x4 *>(sB)[q] = i32x4{0, 0, 0, 0};
             item_barrier();
             const int cpr = (N + CE - 1) / CE;                   // chunks along n per row k
@@ -286,10 +310,16 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
                         const int kb = k * ES;
                         uint8_t *col = sB + (size_t)(kb >> 7) * Nr * SLAB_BYTES + (kb & 15);
                         const int kc = (kb >> 4) & 7;
+                        acc_t part = T::zero();                  // this chunk's share of b[k] = sum over n
 #pragma unroll
                         for (int e = 0; e < CE; ++e) {
                             const int n = chn * CE + e;
                             if (n < N) {
+                                if (PROT) {
+                                    const acc_t x = T::elem(v[u], e);
+                                    part = add_t(part, x);
+                                    if (!T::IS_INT) bmax = fmaxf(bmax, fabsf((float)x));
+                                }
                                 uint8_t *d = col + n * SLAB_BYTES + ((kc ^ (n & 7)) * 16);
                                 if (ES == 2) {
                                     const uint32_t w = (uint32_t)v[u][e >> 1];
@@ -300,14 +330,18 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
                                 }
                             }
                         }
+                        // a row of the stored B is a run of consecutive lanes: few lanes per word
+                        if (PROT && !g.cached_b) {
+                            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(b_lds) + k, (int)part);
+                            else atomicAdd(reinterpret_cast<float *>(b_lds) + k, (float)part);
+                        }
                     }
                 }
             }
         }
-        if (PROT && !loader) {
-            for (int k = tid; k < 2 * nslab * KE; k += 256) a_lds[k] = 0u;     // a_lds and b_lds
-            for (int n = tid; n < Nr; n += 256) ccobs[n] = 0u;
-            if (tid < 16) misc[tid] = 0u;
+        if (RES) {
+            item_wait_vmcnt(0);                                  // this wave's blocks of A have arrived
+            for (int b2 = wave; b2 < g.nrb; b2 += 4) fix_tail(b2);
         }
         item_barrier();
 
@@ -317,7 +351,7 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
             } else if (g.cached_b) {
                 for (int k = tid; k < K; k += 256) b_lds[k] = g.b_sum[(long)bz * K + k];
             } else {
-                float bmax = 0.f;
+                if (TRANSB)
                 for (int s = 0; s < nslab; ++s) {
                     acc_t cs[CE];
 #pragma unroll
@@ -374,9 +408,11 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
             const uint8_t *sAc = sA0 + (rb % S) * abuf;
             if (loader) {
                 // S - 1 blocks ahead; then block rb + 1 must be in place behind this barrier
-                issue_block(rb + S - 1);
-                item_wait_vmcnt((S - 2) * QL);
-                fix_tail(rb + 1);
+                if (!resident) {
+                    issue_block(rb + S - 1);
+                    item_wait_vmcnt((S - 2) * QL);
+                    fix_tail(rb + 1);
+                }
             } else {
             if (PROT) {
                 // The block's share of a = e^T A (kept in registers until the item ends), of the
@@ -428,7 +464,44 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[t][i] = T::zero();
             const bool mact = (m0 + wm * 32) < M;
-            if (mact) {
+            if (mact && TPW <= 2) {
+                // narrow tiles: the fragments of step ks + 1 are read while the MFMAs of step ks
+                // run.  A column block past the last one reads the last one again (its products
+                // are never used).
+                const uint8_t *fa = sAc + (wm * 32 + l32) * SLAB_BYTES;
+                const uint8_t *fb[TPW];
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    int nb = t * WN + wn;
+                    nb = nb < NB ? nb : NB - 1;
+                    fb[t] = sB + (nb * 32 + l32) * SLAB_BYTES;
+                }
+                const int bslab = Nr * SLAB_BYTES, aslab = BMr * SLAB_BYTES;
+                i32x4 af[2], bf[2][TPW];
+                {
+                    const int sw = (lh ^ (lane & 7)) * 16;
+                    af[0] = *reinterpret_cast<const i32x4 *>(fa + sw);
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) bf[0][t] = *reinterpret_cast<const i32x4 *>(fb[t] + sw);
+                }
+                for (int ks = 0; ks < g.ksteps; ks += 2) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int k1 = ks + h + 1;                 // the step to fetch
+                        if (k1 < g.ksteps) {
+                            const int s1 = k1 >> 2, sw = ((2 * (k1 & 3) + lh) ^ (lane & 7)) * 16;
+                            af[(h + 1) & 1] = *reinterpret_cast<const i32x4 *>(fa + s1 * aslab + sw);
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t)
+                                bf[(h + 1) & 1][t] = *reinterpret_cast<const i32x4 *>(fb[t] + (size_t)s1 * bslab + sw);
+                        }
+                        if (ks + h < g.ksteps) {
+#pragma unroll
+                            for (int t = 0; t < TPW; ++t) acc[t] = T::mfma(bf[h][t], af[h], acc[t]);
+                        }
+                    }
+                }
+            } else if (mact) {
                 for (int ks = 0; ks < g.ksteps; ++ks) {
                     const int s = ks >> 2, s4 = ks & 3;
                     const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
@@ -477,8 +550,9 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
                     if (inj_blk) {
 #pragma unroll
                         for (int p = 0; p < 4; ++p)
-                            if (row0 + 8 * p == g.inj_row && g.inj_col >= gc && g.inj_col < gc + 4)
-                                w4[p][g.inj_col - gc] ^= (int)(1u << g.inj_bit);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (row0 + 8 * p == g.inj_row && g.inj_col == gc + e) w4[p][e] ^= (int)(1u << g.inj_bit);
                     }
 #pragma unroll
                     for (int p = 0; p < 4; ++p) {
@@ -524,21 +598,19 @@ __global__ __launch_bounds__(ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
             if (PROT) {
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
+                    // the waves that share these rows add their parts (distinct words per lane)
                     const acc_t r = row8_sum(rsum[p]);
-                    if ((lane & 7) == 0)
-                        rs_part[((rb & 1) * WN + wn) * BMr + wm * 32 + 8 * p + (lane >> 3)] = as_word(r);
+                    if ((lane & 7) == 0 && mact) {
+                        uint32_t *dst = rcobs + m0 + wm * 32 + 8 * p + (lane >> 3);
+                        if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)r);
+                        else atomicAdd(reinterpret_cast<float *>(dst), (float)r);
+                    }
                 }
             }
             }   // computing waves
-            item_barrier();
-            if (PROT && tid < BMr) {
-                acc_t t = T::zero();
-#pragma unroll
-                for (int w2 = 0; w2 < WN; ++w2)
-                    t = add_t(t, from_word<acc_t>(rs_part[((rb & 1) * WN + w2) * BMr + tid]));
-                rcobs[m0 + tid] = as_word(t);
-            }
+            if (!resident) item_barrier();
         }
+        item_barrier();
 
         if (loader) item_wait_vmcnt(0);                         // the blocks fetched past the end
 
@@ -722,13 +794,13 @@ bool gemm_item_eligible(int dt, const Shape &s, bool stored_sums)
     int wm, tpw;
     item_config(s.N, &wm, &tpw);
     if (((long)s.K * es + SLAB_BYTES - 1) / SLAB_BYTES > item_max_slabs(wm, tpw)) return false;
-    return item_stages(dt, wm, s.M, s.N, s.K) >= 2;
+    return item_stages(dt, wm, s.M, s.N, s.K) > 0;
 }
 
-template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
-static hipError_t launch_item_one(const ItemArgs &g, size_t smem, hipStream_t st)
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES>
+static hipError_t launch_item_res(const ItemArgs &g, size_t smem, hipStream_t st)
 {
-    auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB>;
+    auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB, RES>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -737,8 +809,17 @@ static hipError_t launch_item_one(const ItemArgs &g, size_t smem, hipStream_t st
         attr_done = true;
     }
     const unsigned blocks = (unsigned)(g.batch < ITEM_MAX_BLOCKS ? g.batch : ITEM_MAX_BLOCKS);
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(ITEM_THREADS), smem, st, g);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(RES ? 256 : ITEM_THREADS), smem, st, g);
     return hipGetLastError();
+}
+
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
+static hipError_t launch_item_one(const ItemArgs &g, size_t smem, hipStream_t st)
+{
+    if constexpr (TPW <= 2) {
+        if (g.stages >= g.nrb) return launch_item_res<DT, WM, TPW, PROT, TRANSB, true>(g, smem, st);
+    }
+    return launch_item_res<DT, WM, TPW, PROT, TRANSB, false>(g, smem, st);
 }
 
 template <int DT, int WM, int TPW>
