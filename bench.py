@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--flips", type=int, default=64, help="stored-C flips for the correction timing")
     ap.add_argument("--int-flips", type=int, default=10000,
                     help="stored-C flips of the int8 campaign (ViT-B fc2 at batch 32); 0 skips it")
+    ap.add_argument("--no-blocks", action="store_true", help="skip the per-class timing of the transformer blocks")
+    ap.add_argument("--only-blocks", action="store_true",
+                    help="kernel-profile runs of the transformer-block GEMMs: time them, print them, exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
@@ -97,6 +100,63 @@ def main():
         ms, n = ab.abft_profile_end(ctx)
         assert n == steps
         return ms
+
+    # ---- the six GEMM classes of one transformer block (ViT-B/16 bf16 batch 32; ViT-L/16 at
+    # 384^2 int8 batch 64): microseconds unprotected / protected / protected with the encoding of
+    # B cached (Linear layers only: for the attention products B is an activation)
+    def time_blocks():
+        blocks = {}
+        for cfg in (2, 3):
+            cdt = gen.CONFIGS[cfg]["dtype"]
+            rows = []
+            for gi, gg in enumerate(gen.CONFIGS[cfg]["gemms"]):
+                Mb, Nb, Kb, bb, tb = gg["M"], gg["N"], gg["K"], gg["batch"], gg["trans_b"]
+                Ab, Bb = gen.gen_operands(cdt, Mb, Nb, Kb, gen.seed_for(cfg, 10 + 2 * gi), gen.seed_for(cfg, 11 + 2 * gi),
+                                          trans_b=tb, batch=bb, a_kind=gg["a_kind"], b_kind=gg["b_kind"])
+                cb = ab.abft_create(max_rows=bb * Mb, max_cols=bb * Nb, max_depth=bb * ((Kb + 127) // 128 * 128),
+                                    max_batch=bb)
+                rb = Run(cb, cdt, Ab, Bb, tb)
+                resb = rb.result()
+
+                def tstep(mode, n=30):
+                    for it in range(n + 5):
+                        if it == 5:
+                            torch.cuda.synchronize()
+                            t0 = time.perf_counter()
+                        rcb = ab.abft_gemm(cb, rb.dA, rb.dB, rb.dC, rb.code, mode, rb.shape,
+                                           None if mode == ab.ABFT_OFF else resb)
+                        if rcb != ab.ABFT_OK:
+                            raise RuntimeError(ab.abft_strerror(rcb))
+                    torch.cuda.synchronize()
+                    return (time.perf_counter() - t0) / n * 1e6
+                us_off, us_on = tstep(ab.ABFT_OFF), tstep(ab.ABFT_DETECT)
+                assert rb.cnt()[2] == ab.ABFT_CLEAN
+                us_c = tstep(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED) if gg["b_kind"] == "weight" else None
+                es, osz = (1, 4) if cdt == "i8" else (2, 2)
+                rows.append({"gemm": gg["name"], "M": Mb, "N": Nb, "K": Kb, "batch": bb,
+                             "us_unprotected": us_off, "us_protected": us_on, "us_protected_b_cached": us_c,
+                             "gflop": 2.0 * Mb * Nb * Kb * bb / 1e9,
+                             "mbytes": bb * (Mb * Kb * es + Nb * Kb * es + Mb * Nb * osz) / 1e6,
+                             "tile": list(ab.abft_tile_shape(rb.code, rb.shape))})
+                ab.abft_destroy(cb)
+                del rb, Ab, Bb
+                torch.cuda.empty_cache()
+            t_off = sum(r["us_unprotected"] for r in rows)
+            t_on = sum(r["us_protected"] for r in rows)
+            t_c = sum(r["us_protected_b_cached"] or r["us_protected"] for r in rows)
+            blocks[f"config{cfg + 1}_{cdt}"] = {"gemms": rows, "us_unprotected": t_off, "us_protected": t_on,
+                                               "us_protected_weights_cached": t_c,
+                                               "overhead_pct": 100.0 * (t_on - t_off) / t_off,
+                                               "overhead_pct_weights_cached": 100.0 * (t_c - t_off) / t_off}
+            log(f"block config {cfg + 1} ({cdt}): " + "; ".join(
+                f"{r['gemm']} {r['us_unprotected']:.0f}->{r['us_protected']:.0f}" +
+                (f"/{r['us_protected_b_cached']:.0f}" if r['us_protected_b_cached'] else "") for r in rows) +
+                f" | total {t_off:.0f} -> {t_on:.0f} / {t_c:.0f} us")
+        return blocks
+
+    if args.only_blocks:
+        print(json.dumps({"transformer_block": time_blocks()}), flush=True)
+        return
 
     if args.calibrate_copy:
         src = torch.ones(512 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda")
@@ -276,6 +336,8 @@ def main():
         del ri, Ci
         log(f"int8 campaign: {camp_int}")
 
+    blocks = time_blocks() if (args.flips > 0 and not args.no_blocks) else None
+
     out = {
         "metric": "protected GEMM TFLOP/s (useful 2MNK only; every ABFT kernel in the timed region)",
         "value": flops / (ms_prot * 1e-3) / 1e12,
@@ -311,6 +373,7 @@ def main():
                           "S1 = |delta| > tolerance or non-finite (the gating stratum), S2 = |delta| > "
                           "1e-2 max|C|; flips with |delta| <= tolerance are undetectable by construction"),
             "int8_flips": camp_int,
+            "transformer_block": blocks,
             "calibrated_tau": None if camp_cal is None else dict(camp_cal, z=z_cal, mean=mean, std=std, max_clean_abs=float(max(st[2], st[6])),
                                    tau_calibrated=tau_used, tau_analytic=tau_analytic,
                                    false_positive_flags_clean=clean_under_cal,
