@@ -161,6 +161,10 @@ int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_sha
  * column prediction a B from one read of B, compares both pairs (equality for ABFT_I8,
  * |difference| <= tau otherwise; NaN or Inf always flag) and writes flags, counts and status.
  * A and B must stay unchanged until the finish kernel has run.
+ * A batch of at least 64 small problems (per-head attention products: N <= 640, M <= 1024, a row
+ * of K at most 640 bytes, operands of one item fitting the local memory of a compute unit; not
+ * with ABFT_STORED_SUMS) is one kernel instead: one workgroup per batch item forms b, a, both
+ * predictions and both observed sums from on-chip operands and compares them itself.
  * mode ABFT_OFF ignores `r` (may be NULL).  Flags and counts are overwritten. */
 int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
               const abft_shape *s, const abft_result *r, void *stream);
@@ -216,14 +220,15 @@ int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s, i
 /* Device pointer and element count of a workspace vector for the given shape (layout [batch][len]). */
 int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, void **ptr, int64_t *count);
 
-/* Tile the GEMM kernel uses for this problem (rows, cols of C per workgroup). */
+/* Tile the GEMM kernel uses for this problem (rows, cols of C per workgroup; M, N where a
+ * workgroup takes a whole batch item). */
 int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *tile_n);
 
 /* Kernel timing for reports (not a hot call: creates HIP events).  Between begin and end every
  * abft_gemm records events on the caller's stream around its kernels; up to max_calls calls are
  * kept.  abft_profile_end waits for the recorded events and returns average milliseconds per call:
  * ms[0] pass over B (or the clearing kernel that replaces it), ms[1] GEMM kernel, ms[2] finish
- * kernel, ms[3] first event to last. */
+ * kernel, ms[3] first event to last.  (Calls that are a single kernel report it as ms[1].) */
 int abft_profile_begin(abft_ctx *ctx, int max_calls);
 int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls);
 

@@ -269,6 +269,60 @@ extern "C" int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, con
     return ABFT_OK;
 }
 
+// The kernels of a protected GEMM, tiled path: pass over B (unless its encoding is cached), GEMM,
+// finish.  The call accumulates into the region the previous protected call did not use.  It is
+// clean unless a call failed half way; the region of the previous call is cleared by this
+// call's finish kernel.  So a call with a cached B checksum is two kernels: GEMM, finish.
+static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, const void *A, const void *B, void *C,
+                         const Shape &sh, Workspace *w, const Verdict &v, const InjectArm &arm, hipEvent_t *ev,
+                         hipStream_t st)
+{
+    const int prev = ctx->cur;
+    ctx->cur ^= 1;
+    if (!cached) {
+        int rc = begin_b_pass(ctx, st);
+        if (rc) return rc;
+    }
+    carve(ctx, dtype, sh, w);
+    uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
+    const size_t stale = ctx->dirty[ctx->cur];
+    ctx->dirty[ctx->cur] = ctx->region_words;            // until everything below is enqueued
+    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, *w, w->cc_obs, stale, st));
+    else if (stale) HIP_TRY(launch_zero(w->cc_obs, stale, st));
+    if (ev) HIP_TRY(hipEventRecord(ev[1], st));
+    ctx->sto_valid = false;
+    HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, *w, arm, st));
+    if (ev) HIP_TRY(hipEventRecord(ev[2], st));
+    const size_t prev_dirty = ctx->dirty[prev];
+    ctx->dirty[prev] = ctx->region_words;
+    // the finish kernel also cleans the b slot that is not in use (for the next pass over B)
+    const int other = ctx->bslot ^ 1;
+    uint32_t *other_base = ctx->pool_depth + (size_t)other * ctx->bslot_words;
+    HIP_TRY(launch_finish(dtype, B, sh, *w, v, prev_base, prev_dirty, ctx->bclean[other] ? nullptr : other_base,
+                          ctx->bslot_words, st));
+    ctx->bclean[other] = true;
+    ctx->dirty[prev] = 0;
+    ctx->dirty[ctx->cur] = w->zero_words;
+    if (ev) HIP_TRY(hipEventRecord(ev[3], st));
+    return ABFT_OK;
+}
+
+// A batch of small problems: one kernel does everything and writes the workspace vectors with
+// plain stores, into the region and the b slot in use (nothing has to start at zero; what it
+// leaves there counts as dirty for the tiled path).
+static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, const void *A, const void *B, void *C,
+                        const Shape &sh, const Workspace &w, const Verdict &v, const InjectArm &arm, hipEvent_t *ev,
+                        hipStream_t st)
+{
+    if (ev) HIP_TRY(hipEventRecord(ev[1], st));
+    if (!cached) ctx->bclean[ctx->bslot] = false;
+    if (ctx->dirty[ctx->cur] < w.zero_words) ctx->dirty[ctx->cur] = w.zero_words;
+    ctx->sto_valid = false;
+    HIP_TRY(launch_gemm_item(dtype, true, cached, A, B, C, sh, w, &v, arm, st));
+    if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); }
+    return ABFT_OK;
+}
+
 extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
                          const abft_shape *s, const abft_result *r, void *stream)
 {
@@ -306,47 +360,11 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     const bool stored = (mode & ABFT_STORED_SUMS) != 0;
-    if (gemm_item_eligible(dtype, sh, stored)) {
-        // Batch of small problems: one kernel does everything and writes the workspace vectors
-        // with plain stores, into the region and the b slot in use (nothing has to start at zero).
-        if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-        if (!cached) ctx->bclean[ctx->bslot] = false;
-        if (ctx->dirty[ctx->cur] < w.zero_words) ctx->dirty[ctx->cur] = w.zero_words;
-        ctx->sto_valid = false;
-        HIP_TRY(launch_gemm_item(dtype, true, cached, A, B, C, sh, w, &v, arm, st));
-        if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
-    } else {
-    // This call accumulates into the region the previous protected call did not use.  It is
-    // clean unless a call failed half way; the region of the previous call is cleared by this
-    // call's finish kernel.  So a call with a cached B checksum is two kernels: GEMM, finish.
-    const int prev = ctx->cur;
-    ctx->cur ^= 1;
-    if (!cached) {
-        rc = begin_b_pass(ctx, st);
-        if (rc) return rc;
-    }
-    carve(ctx, dtype, sh, &w);
-    uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
-    const size_t stale = ctx->dirty[ctx->cur];
-    ctx->dirty[ctx->cur] = ctx->region_words;            // until everything below is enqueued
-    if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, w, w.cc_obs, stale, st));
-    else if (stale) HIP_TRY(launch_zero(w.cc_obs, stale, st));
-    if (ev) HIP_TRY(hipEventRecord(ev[1], st));
-    ctx->sto_valid = false;
-    HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, w, arm, st));
-    if (ev) HIP_TRY(hipEventRecord(ev[2], st));
-    const size_t prev_dirty = ctx->dirty[prev];
-    ctx->dirty[prev] = ctx->region_words;
-    // the finish kernel also cleans the b slot that is not in use (for the next pass over B)
-    const int other = ctx->bslot ^ 1;
-    uint32_t *other_base = ctx->pool_depth + (size_t)other * ctx->bslot_words;
-    HIP_TRY(launch_finish(dtype, B, sh, w, v, prev_base, prev_dirty, ctx->bclean[other] ? nullptr : other_base,
-                          ctx->bslot_words, st));
-    ctx->bclean[other] = true;
-    ctx->dirty[prev] = 0;
-    ctx->dirty[ctx->cur] = w.zero_words;
-    if (ev) { HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
-    }
+    const bool item = gemm_item_eligible(dtype, sh, stored);
+    rc = item ? enqueue_item(ctx, dtype, cached, A, B, C, sh, w, v, arm, ev, st)
+              : enqueue_tiled(ctx, dtype, cached, stored, A, B, C, sh, &w, v, arm, ev, st);
+    if (rc) return rc;
+    if (ev) ctx->prof_n++;
     ctx->b_valid = true;
     ctx->b_dt = dtype;
     ctx->b_shape = *s;
@@ -354,7 +372,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
     // a correction inside this call replaces values the stored-side sums already contain
-    ctx->sto_valid = stored && base == ABFT_DETECT && !gemm_item_eligible(dtype, sh, stored);
+    ctx->sto_valid = stored && base == ABFT_DETECT && !item;
     if (base == ABFT_DETECT_CORRECT) {
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words);

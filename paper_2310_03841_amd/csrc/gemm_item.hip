@@ -256,8 +256,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
         // ---- B of this item into LDS, every position written (pads and rows past N with zeros)
         if (TRANSB) {
             const int cpr = nslab * 8;                           // chunk positions per row
-            const int total = Nr * cpr;
-            if (!loader)
+            const int total = loader ? 0 : Nr * cpr;           // the loading wave takes no part
             for (int q0 = tid; q0 < total; q0 += 4 * 256) {
                 i32x4 v[4];
 #pragma unroll
@@ -289,8 +288,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 reinterpret_cast<i32x4 *>(sB)[q] = i32x4{0, 0, 0, 0};
             item_barrier();
             const int cpr = (N + CE - 1) / CE;                   // chunks along n per row k
-            const int total = K * cpr;
-            if (!loader)
+            const int total = loader ? 0 : K * cpr;            // the loading wave takes no part
             for (int q0 = tid; q0 < total; q0 += 4 * 256) {
                 i32x4 v[4];
 #pragma unroll
@@ -348,11 +346,13 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
         // ---- b = B e and max|B| from the resident copy (or the cached encoding)
         if (PROT) {
             if (loader) {
+                // nothing to do
             } else if (g.cached_b) {
                 for (int k = tid; k < K; k += 256) b_lds[k] = g.b_sum[(long)bz * K + k];
             } else {
-                if (TRANSB)
-                for (int s = 0; s < nslab; ++s) {
+                // B stored N x K: column sums of the resident copy (stored K x N, the transposing
+                // load above has already summed its rows)
+                for (int s = 0; s < (TRANSB ? nslab : 0); ++s) {
                     acc_t cs[CE];
 #pragma unroll
                     for (int q = 0; q < CE; ++q) cs[q] = T::zero();
@@ -403,17 +403,10 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
 #pragma unroll
             for (int e = 0; e < 4; ++e) cs[t][e] = T::zero();
 
-        for (int rb = 0; rb < g.nrb; ++rb) {
+        // one row block, as the computing waves see it
+        auto compute_block = [&](int rb) __attribute__((always_inline)) {
             const int m0 = rb * BMr;
             const uint8_t *sAc = sA0 + (rb % S) * abuf;
-            if (loader) {
-                // S - 1 blocks ahead; then block rb + 1 must be in place behind this barrier
-                if (!resident) {
-                    issue_block(rb + S - 1);
-                    item_wait_vmcnt((S - 2) * QL);
-                    fix_tail(rb + 1);
-                }
-            } else {
             if (PROT) {
                 // The block's share of a = e^T A (kept in registers until the item ends), of the
                 // row prediction A b and of max|A|: thread (c8, rg) reads chunk c8 of rows
@@ -607,16 +600,25 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     }
                 }
             }
-            }   // computing waves
+        };
+        for (int rb = 0; rb < g.nrb; ++rb) {
+            if (!loader) {
+                compute_block(rb);
+            } else if (!resident) {
+                // S - 1 blocks ahead; then block rb + 1 must be in place behind this barrier
+                issue_block(rb + S - 1);
+                item_wait_vmcnt((S - 2) * QL);
+                fix_tail(rb + 1);
+            }
             if (!resident) item_barrier();
         }
         item_barrier();
 
         if (loader) item_wait_vmcnt(0);                         // the blocks fetched past the end
 
-        // ---- the item's checks
-        if (PROT) {
-            if (!loader) {
+        // ---- the item's checks (computing waves)
+        // the waves' partial column sums of C and of A meet in LDS
+        auto reduce_sums = [&]() __attribute__((always_inline)) {
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
                 const int nb = t * WN + wn;
@@ -655,18 +657,9 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 const float m = wave_max(amax);
                 if (lane == 0) misc[wave] = __float_as_uint(m);
             }
-            }
-            item_barrier();
-            float tol = 0.f, ma = 0.f, mb = 0.f;
-            if (!T::IS_INT) {
-                ma = fmaxf(fmaxf(__uint_as_float(misc[0]), __uint_as_float(misc[1])),
-                           fmaxf(__uint_as_float(misc[2]), __uint_as_float(misc[3])));
-                mb = g.cached_b ? __uint_as_float(g.b_max[bz])
-                                : fmaxf(fmaxf(__uint_as_float(misc[4]), __uint_as_float(misc[5])),
-                                        fmaxf(__uint_as_float(misc[6]), __uint_as_float(misc[7])));
-                tol = g.tau_override > 0.f ? g.tau_override : (1e-3f * (float)K) * ma * mb;
-            }
-            if (!loader) {
+        };
+        // a B from the resident B against the column sums; row sums against A b; vectors out
+        auto check_item = [&](float tol) __attribute__((always_inline)) {
             // columns: prediction a B from the resident B; LPC lanes share a column (four where
             // there are at most 64 columns, so that all 256 threads take part)
             constexpr int LPC = WM == 2 ? 4 : 1;
@@ -724,7 +717,20 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
             }
             sp = wave_sum(sp);
             if (lane == 0) misc[8 + wave] = as_word(sp);
+        };
+        if (PROT) {
+            if (!loader) reduce_sums();
+            item_barrier();
+            float tol = 0.f, ma = 0.f, mb = 0.f;
+            if (!T::IS_INT) {
+                ma = fmaxf(fmaxf(__uint_as_float(misc[0]), __uint_as_float(misc[1])),
+                           fmaxf(__uint_as_float(misc[2]), __uint_as_float(misc[3])));
+                mb = g.cached_b ? __uint_as_float(g.b_max[bz])
+                                : fmaxf(fmaxf(__uint_as_float(misc[4]), __uint_as_float(misc[5])),
+                                        fmaxf(__uint_as_float(misc[6]), __uint_as_float(misc[7])));
+                tol = g.tau_override > 0.f ? g.tau_override : (1e-3f * (float)K) * ma * mb;
             }
+            if (!loader) check_item(tol);
             item_barrier();
             if (tid == 0) {
                 g.s_pred[bz] = as_word(add_t(add_t(from_word<acc_t>(misc[8]), from_word<acc_t>(misc[9])),
