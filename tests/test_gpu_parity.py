@@ -747,3 +747,82 @@ def test_item_kernel_flips_cached_b_and_correction(ctx_items, dtype, M, N, K, ba
     check_clean(run, P)
     r1.gemm(ab.ABFT_DETECT)
     check_clean(r1, oracle_items(dtype, A1, B1, True))
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 130, 72, 3, True), (150, 70, 100, 2, False),
+                                                 (600, 520, 256, 2, True),       # 256-row tiles
+                                                 (70, 50, 40, 64, False), (100, 130, 72, 65, True)])
+def test_leading_dimensions_and_batch_strides(ctx_items, dtype, M, N, K, batch, trans_b):
+    """Operands and C embedded in larger allocations: leading dimensions wider than the rows,
+    batch strides longer than an item.  Everything outside the M x N items of C must stay as it
+    was; everything outside the operands is filled with a pattern that must never be used."""
+    ctx = ctx_items
+    es, osz = (1, 4) if dtype == "i8" else (2, 2)
+    A, B = gen.gen_operands(dtype, M, N, K, 71, 72, trans_b=trans_b, batch=batch)
+    P = oracle_items(dtype, A, B, trans_b)
+
+    def embed(arr, extra_rows, extra_cols, fill, tdt):
+        b, r, c = arr.shape
+        ld = (c + extra_cols + 16 // arr.dtype.itemsize - 1) // (16 // arr.dtype.itemsize) * (16 // arr.dtype.itemsize)
+        big = np.full((b, r + extra_rows, ld), fill, dtype=arr.dtype)
+        big[:, :r, :c] = arr
+        t = torch.from_numpy(big.view(np.int16) if arr.dtype == np.uint16 else big).to("cuda").view(tdt)
+        return t, ld, (r + extra_rows) * ld
+
+    in_t = torch.int8 if dtype == "i8" else torch.int16
+    pat = 0x55 if dtype == "i8" else 0x7F55            # bf16/f16: a large finite value (f16: NaN pattern 0x7F55)
+    dA, lda, sA = embed(A, 3, 40, pat, in_t)
+    dB, ldb, sB = embed(B, 2, 24, pat, in_t)
+    out_np = np.int32 if dtype == "i8" else np.uint16
+    Cbig = np.full((batch, M + 4, N), 0, dtype=out_np)
+    dC, ldc, sC = embed(Cbig, 0, 20, 0, torch.int32 if dtype == "i8" else torch.int16)
+    dC.fill_(0x1234)
+    shape = ab.make_shape(M, N, K, batch=batch, lda=lda, ldb=ldb, ldc=ldc, strideA=sA, strideB=sB, strideC=sC,
+                          transB=trans_b)
+    rf = torch.full((batch * M,), 7, dtype=torch.uint8, device="cuda")
+    cf = torch.full((batch * N,), 7, dtype=torch.uint8, device="cuda")
+    cnt = torch.full((8,), 99, dtype=torch.int32, device="cuda")
+    res = ab.make_result(rf, cf, cnt, 0.0)
+    code = ab.DTYPE_CODE[dtype]
+    for mode in (ab.ABFT_DETECT, ab.ABFT_OFF):
+        dC.fill_(0x1234)
+        rc = ab.abft_gemm(ctx, dA, dB, dC, code, mode, shape, None if mode == ab.ABFT_OFF else res)
+        assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+        torch.cuda.synchronize()
+        Ch = dC.cpu().numpy()
+        got = Ch[:, :M, :N]
+        for bi, p in enumerate(P):
+            if dtype == "i8":
+                assert np.array_equal(got[bi], p.C_stored), (mode, bi)
+            else:
+                val = orc.decode(got[bi].view(np.uint16), dtype)
+                scale = np.max(np.abs(p.C_ref))
+                assert np.max(np.abs(val - p.C_ref)) <= 1e-2 * scale
+                assert np.mean(got[bi].view(np.uint16) != p.C_stored) < 5e-3
+        assert np.all(Ch[:, M:, :] == 0x1234) and np.all(Ch[:, :, N:] == 0x1234), "wrote outside C"
+    c = cnt.cpu().numpy()
+    assert not rf.cpu().numpy().any() and not cf.cpu().numpy().any() and c[0] == 0 and c[1] == 0 and c[2] == ab.ABFT_CLEAN
+    from gpu_util import read_ws
+    kind = "i" if dtype == "i8" else "f"
+    ccp = read_ws(ctx, ab.ABFT_WS_CC_PRED, shape, kind).reshape(batch, -1)
+    rcp = read_ws(ctx, ab.ABFT_WS_RC_PRED, shape, kind).reshape(batch, -1)
+    for bi, p in enumerate(P):
+        if dtype == "i8":
+            assert np.array_equal(ccp[bi].view(np.uint32), ring(p.cc_pred))
+            assert np.array_equal(rcp[bi].view(np.uint32), ring(p.rc_pred))
+        else:
+            assert np.max(np.abs(ccp[bi] - p.cc_pred)) <= 1e-2 * p.tau * max(1.0, np.sqrt(M))
+            assert np.max(np.abs(rcp[bi] - p.rc_pred)) <= 1e-2 * p.tau * max(1.0, np.sqrt(N))
+    # a flip, verify and the tile recompute on the embedded C
+    C_before = dC.clone()
+    bi, i, j, bit = batch - 1, M - 1, N - 1, 30 if dtype == "i8" else 14
+    assert ab.abft_inject(ctx, dC, code, shape, bi, i, j, bit, ab.ABFT_INJECT_STORED_C) == ab.ABFT_OK
+    # (the last call above ran unprotected: the predictions of the protected one before it still stand)
+    assert ab.abft_verify(ctx, dC, code, shape, res) == ab.ABFT_OK
+    torch.cuda.synchronize()
+    f_r, f_c = rf.cpu().numpy().reshape(batch, M), cf.cpu().numpy().reshape(batch, N)
+    assert f_r.sum() == 1 and f_c.sum() == 1 and f_r[bi, i] and f_c[bi, j]
+    assert ab.abft_correct(ctx, dA, dB, dC, code, shape, res) == ab.ABFT_OK
+    torch.cuda.synchronize()
+    assert torch.equal(dC, C_before) and cnt.cpu().numpy()[2] == ab.ABFT_CLEAN
