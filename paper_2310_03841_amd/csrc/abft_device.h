@@ -150,6 +150,41 @@ template <int CTRL> __device__ __forceinline__ float dpp_get(float v)
     return __int_as_float(dpp_mov<CTRL>(__float_as_int(v)));
 }
 
+// Exchange between the rows of 16 lanes and between the halves of a wave with the row-swap
+// instructions of gfx950 (v_permlane16_swap, v_permlane32_swap: vector ALU, no trip through the
+// LDS crossbar as a lane shuffle takes).  Called with the same value twice, the two results
+// hold, lane by lane, the lane's own value and that of lane ^ 16 (lane ^ 32), in either order.
+__device__ __forceinline__ int add_xor16(int v)
+{
+    auto p = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)(p[0] + p[1]);
+}
+__device__ __forceinline__ int add_xor32(int v)
+{
+    auto p = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);
+    return (int)(p[0] + p[1]);
+}
+__device__ __forceinline__ float add_xor16(float v)
+{
+    auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
+__device__ __forceinline__ float add_xor32(float v)
+{
+    auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
+__device__ __forceinline__ float max_xor16(float v)
+{
+    auto p = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+}
+__device__ __forceinline__ float max_xor32(float v)
+{
+    auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+}
+
 // Sum over each aligned group of 16 lanes; every lane of the group ends with the total.
 template <typename T> __device__ __forceinline__ T row16_sum(T v)
 {
@@ -164,14 +199,14 @@ template <typename T> __device__ __forceinline__ T row16_sum(T v)
 template <typename T> __device__ __forceinline__ T half_wave_sum(T v)
 {
     v = row16_sum(v);
-    return add_t(v, __shfl_xor(v, 16));
+    return add_xor16(v);
 }
 
 // Sum over the whole wave; every lane ends with the total.
 template <typename T> __device__ __forceinline__ T wave_sum(T v)
 {
     v = half_wave_sum(v);
-    return add_t(v, __shfl_xor(v, 32));
+    return add_xor32(v);
 }
 
 // Sum over aligned groups of `width` lanes (8, 16, 32 or 64); every lane of a group ends with
@@ -182,8 +217,8 @@ template <typename V> __device__ __forceinline__ V seg_sum(V v, int width)
     v = add_t(v, dpp_get<0x4E>(v));    // lane ^ 2
     v = add_t(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
     if (width >= 16) v = add_t(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
-    if (width >= 32) v = add_t(v, __shfl_xor(v, 16));
-    if (width >= 64) v = add_t(v, __shfl_xor(v, 32));
+    if (width >= 32) v = add_xor16(v);
+    if (width >= 64) v = add_xor32(v);
     return v;
 }
 
@@ -193,8 +228,8 @@ __device__ __forceinline__ float wave_max(float v)
     v = fmaxf(v, dpp_get<0x4E>(v));    // lane ^ 2
     v = fmaxf(v, dpp_get<0x141>(v));   // i <-> 7 - i inside 8 lanes
     v = fmaxf(v, dpp_get<0x140>(v));   // i <-> 15 - i inside 16 lanes
-    v = fmaxf(v, __shfl_xor(v, 16));
-    v = fmaxf(v, __shfl_xor(v, 32));
+    v = max_xor16(v);
+    v = max_xor32(v);
     return v;
 }
 

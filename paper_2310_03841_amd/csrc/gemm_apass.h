@@ -95,8 +95,8 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
     for (int q = 0; q < CE; ++q) {
         acc_t t = cs[q];
         t = add_t(t, dpp_get<0x128>(t));      // row_ror:8 inside 16 lanes: lane ^ 8
-        t = add_t(t, __shfl_xor(t, 16));
-        t = add_t(t, __shfl_xor(t, 32));
+        t = add_xor16(t);
+        t = add_xor32(t);
         cs[q] = t;
     }
     if ((tid & 63) < 8) {

@@ -192,7 +192,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 __builtin_amdgcn_sched_barrier(0);      // keeps the accumulator reads from all moving to the top
             });
             if (PROT) {
-                const acc_t t = add_t(rowsum, __shfl_xor(rowsum, 32));     // the half-waves hold different columns
+                const acc_t t = add_xor32(rowsum);     // the half-waves hold different columns
                 if (lh == 0) rs_part[wn * BM + wm * TM + mi * 32 + l32] = t;
             }
             wave_sync();
@@ -264,11 +264,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                         }
                     }
                 }
-                rs = add_t(rs, __shfl_xor(rs, 32));
+                rs = add_xor32(rs);
                 if (lane < 32) rs_part[wn * BM + wm * TM + mi * 32 + lane] = rs;
                 if constexpr (!T::IS_INT) {
                     if (sto) {
-                        rs_s += __shfl_xor(rs_s, 32);
+                        rs_s = add_xor32(rs_s);
                         rowsto[mi] = rs_s;                              // lanes 0..31: row mi * 32 + lane
                     }
                 }
@@ -339,7 +339,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                             });
                             __builtin_amdgcn_sched_barrier(0);
                         });
-                        rsum += __shfl_xor(rsum, 32);
+                        rsum = add_xor32(rsum);
                         rowsto[mi] = rsum;                              // lanes 0..31: row mi * 32 + lane
                     }
                 });

@@ -370,8 +370,8 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     for (int q = 0; q < CE; ++q) {
                         acc_t t = cs[q];
                         t = add_t(t, dpp_get<0x128>(t));          // lane ^ 8
-                        t = add_t(t, __shfl_xor(t, 16));
-                        t = add_t(t, __shfl_xor(t, 32));
+                        t = add_xor16(t);
+                        t = add_xor32(t);
                         cs[q] = t;
                     }
                     if (lane < 8) {
@@ -626,8 +626,8 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 for (int e = 0; e < 4; ++e) {
                     acc_t v = cs[t][e];
                     v = add_t(v, dpp_get<0x128>(v));              // lane ^ 8
-                    v = add_t(v, __shfl_xor(v, 16));
-                    v = add_t(v, __shfl_xor(v, 32));
+                    v = add_xor16(v);
+                    v = add_xor32(v);
                     if (lane < 8 && nb < NB) {
                         uint32_t *dst = ccobs + nb * 32 + 4 * lane + e;
                         if (WM == 1) *dst = as_word(v);
@@ -644,8 +644,8 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     for (int q = 0; q < CE; ++q) {
                         acc_t v = csa[s2][q];
                         v = add_t(v, dpp_get<0x128>(v));          // lane ^ 8
-                        v = add_t(v, __shfl_xor(v, 16));
-                        v = add_t(v, __shfl_xor(v, 32));
+                        v = add_xor16(v);
+                        v = add_xor32(v);
                         if (lane < 8) {
                             if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(a_lds) + s2 * KE + c8 * CE + q, (int)v);
                             else atomicAdd(reinterpret_cast<float *>(a_lds) + s2 * KE + c8 * CE + q, (float)v);
