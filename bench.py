@@ -42,7 +42,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target seconds of oracle work")
-    ap.add_argument("--flips", type=int, default=64, help="stored-C flips for the correction timing")
+    ap.add_argument("--flips", type=int, default=1000,
+                    help="stored-C flips of the bf16 campaigns on the benchmark workload; 0 also skips "
+                         "every other extra (kernel-profile runs)")
     ap.add_argument("--int-flips", type=int, default=10000,
                     help="stored-C flips of the int8 campaign (ViT-B fc2 at batch 32); 0 skips it")
     ap.add_argument("--no-blocks", action="store_true", help="skip the per-class timing of the transformer blocks")
