@@ -826,3 +826,42 @@ def test_leading_dimensions_and_batch_strides(ctx_items, dtype, M, N, K, batch, 
     assert ab.abft_correct(ctx, dA, dB, dC, code, shape, res) == ab.ABFT_OK
     torch.cuda.synchronize()
     assert torch.equal(dC, C_before) and cnt.cpu().numpy()[2] == ab.ABFT_CLEAN
+
+
+@pytest.mark.parametrize("M,N,K", [(197, 768, 768), (600, 520, 256)])
+def test_faults_in_the_operands(ctx, M, N, K):
+    """Other injection sites (Sec. III-A: inputs and weights as well as outputs).  A flip in the
+    weight after its checksum was encoded moves a whole column of C: the row checks catch it in
+    every row whose A[i, k] is non-zero, the column check (whose prediction reads the weight as
+    it is) stays silent, and the status says that C itself is not the suspect.  A flip in A
+    before the call is outside what a GEMM's own checksums can see: they are taken from the
+    operands as given, so the call is clean and C is the product of what it was given."""
+    A, B = gen.gen_operands("i8", M, N, K, 81, 82, trans_b=True)
+    run = Run(ctx, "i8", A, B, True)
+    assert ab.abft_encode_b(ctx, run.dB, run.code, run.shape) == ab.ABFT_OK
+    j, k, bit = N // 2, K // 3, 5
+    B2 = B.copy()
+    B2[0, j, k] = np.int8(np.uint8(B2[0, j, k]) ^ np.uint8(1 << bit))
+    run.dB[0, j, k] = int(B2[0, j, k])
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)
+    a, b_clean = orc.encode(A[0], B[0], True)
+    C2 = orc.gemm(A[0], B2[0], True)
+    cc_pred, rc_pred, _ = orc.predict(A[0], B2[0], a, b_clean, True)
+    cc_obs, rc_obs, _ = orc.observe(C2)
+    _, want_rf = orc.flags_int(rc_obs, rc_pred)
+    _, want_cf = orc.flags_int(cc_obs, cc_pred)
+    rf, cf = run.flags()
+    cnt = run.cnt()
+    assert np.array_equal(run.C()[0], C2.astype(np.int32))
+    assert np.array_equal(rf[0], want_rf) and np.array_equal(cf[0], want_cf) and not want_cf.any()
+    assert cnt[0] == want_rf.sum() and cnt[1] == 0 and cnt[2] == ab.ABFT_CHECKSUM_SUSPECT
+    # re-encoding the weight as it is now makes the call consistent again (the fault is then part of the input)
+    run.gemm(ab.ABFT_DETECT)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    # a flip in A before the call
+    A2 = A.copy()
+    A2[0, M // 2, K // 2] = np.int8(np.uint8(A2[0, M // 2, K // 2]) ^ np.uint8(1 << 7))
+    run.dA[0, M // 2, K // 2] = int(A2[0, M // 2, K // 2])
+    run.gemm(ab.ABFT_DETECT)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    assert np.array_equal(run.C()[0], orc.gemm(A2[0], B2[0], True).astype(np.int32))

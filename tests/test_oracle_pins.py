@@ -375,3 +375,28 @@ def test_checksum_only_correction_leaves_what_it_cannot_explain():
     _, _, _, _, cc_obs, rc_obs = orc.check(P, P.C_stored)
     Y, fixed = orc.correct_by_checksum(P.C_stored, cc_obs, rc_obs, P.cc_pred, P.rc_pred)
     assert fixed == 0 and np.array_equal(Y, P.C_stored)
+
+
+# ---------------------------------------------------------------- a fault in the weight, after its checksum was taken
+def test_weight_fault_after_encoding_shows_on_the_row_side_only():
+    """b = B e is taken from the clean weight (the offline checksum of Sec. III-B.1, remark (2));
+    then one element B[j, k] changes by delta.  Every row i of C moves by A[i, k] * delta in
+    column j, so the row discrepancy is exactly A[i, k] * delta; the column prediction a B is
+    formed from the weight as it is now and stays consistent with C: no column is flagged."""
+    M, N, K = 9, 7, 12
+    A, B = _int_case(M, N, K, True, 77)
+    a, b_clean = orc.encode(A, B, True)
+    j, k, bit = 3, 5, 6
+    B2 = B.copy()
+    B2[j, k] = np.int8(np.uint8(B2[j, k]) ^ np.uint8(1 << bit))
+    delta = int(B2[j, k]) - int(B[j, k])
+    C2 = orc.gemm(A, B2, True)
+    cc_pred, rc_pred, _ = orc.predict(A, B2, a, b_clean, True)
+    cc_obs, rc_obs, _ = orc.observe(C2)
+    assert np.array_equal(cc_obs, cc_pred)
+    assert np.array_equal(rc_obs - rc_pred, A[:, k].astype(np.int64) * delta)
+    _, rf = orc.flags_int(rc_obs, rc_pred)
+    _, cf = orc.flags_int(cc_obs, cc_pred)
+    assert np.array_equal(rf, A[:, k] != 0) and not cf.any()
+    E, status = orc.localise(rf, cf)
+    assert E == [] and status == orc.CHECKSUM_SUSPECT
