@@ -392,11 +392,21 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
 
         // ---- row blocks
         float amax = 0.f;
-        acc_t csa[MAXS][CE];                     // column sums of A: chunk c8 of every slab, rows rg + 32 p
+        // Column sums of A: chunk c8 of every slab, rows rg + 32 p of every row block.  int8: two
+        // columns per register as 16-bit halves (a thread sees at most M / 32 <= 32 rows of a
+        // column: |sum| <= 4096); dword d of a chunk gives csa[2 d] = columns 4 d + {0, 2} and
+        // csa[2 d + 1] = columns 4 d + {1, 3}.
+        typedef short item_s16x2 __attribute__((ext_vector_type(2)));
+        typedef typename std::conditional<T::IS_INT, item_s16x2, float>::type csa_t;
+        constexpr int NCSA = T::IS_INT ? CE / 2 : CE;
+        csa_t csa[MAXS][NCSA];
 #pragma unroll
         for (int s2 = 0; s2 < MAXS; ++s2)
 #pragma unroll
-            for (int q = 0; q < CE; ++q) csa[s2][q] = T::zero();
+            for (int q = 0; q < NCSA; ++q) {
+                if constexpr (T::IS_INT) csa[s2][q] = item_s16x2{0, 0};
+                else csa[s2][q] = 0.f;
+            }
         acc_t cs[TPW][4];
 #pragma unroll
         for (int t = 0; t < TPW; ++t)
@@ -429,10 +439,19 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                             i32x4 x4 = *reinterpret_cast<const i32x4 *>(sAc + s2 * BMr * SLAB_BYTES +
                                                                         (rg + 32 * p) * SLAB_BYTES + ((c8 ^ (rg & 7)) * 16));
                             if (m0 + rg + 32 * p >= M) x4 = i32x4{0, 0, 0, 0};
+                            if constexpr (T::IS_INT) {
+#pragma unroll
+                                for (int d = 0; d < 4; ++d) {
+                                    const int wd = x4[d];
+                                    const item_s16x2 w = item_s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
+                                    csa[s2][2 * d] += (w << 8) >> 8;      // bytes 0 and 2, sign-extended
+                                    csa[s2][2 * d + 1] += w >> 8;         // bytes 1 and 3
+                                }
+                            }
 #pragma unroll
                             for (int q = 0; q < CE; ++q) {
                                 const acc_t x = T::elem(x4, q);
-                                csa[s2][q] = add_t(csa[s2][q], x);
+                                if constexpr (!T::IS_INT) csa[s2][q] = csa[s2][q] + (float)x;
                                 if constexpr (T::IS_INT) {
                                     dot[p] = g.mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot[p])
                                                         : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot[p]);
@@ -458,9 +477,11 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 for (int i = 0; i < 16; ++i) acc[t][i] = T::zero();
             const bool mact = (m0 + wm * 32) < M;
             if (mact && TPW <= 2) {
-                // narrow tiles: the fragments of step ks + 1 are read while the MFMAs of step ks
-                // run.  A column block past the last one reads the last one again (its products
-                // are never used).
+                // narrow tiles: with one or two MFMAs per step of K, the LDS latency of a step's
+                // fragments is several MFMAs long, so the reads run FD - 1 = 3 steps ahead of the
+                // MFMAs (a slab is four steps).  A column block past the last one reads the last one again (its
+                // products are never used).
+                constexpr int FD = 4;
                 const uint8_t *fa = sAc + (wm * 32 + l32) * SLAB_BYTES;
                 const uint8_t *fb[TPW];
 #pragma unroll
@@ -470,30 +491,32 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     fb[t] = sB + (nb * 32 + l32) * SLAB_BYTES;
                 }
                 const int bslab = Nr * SLAB_BYTES, aslab = BMr * SLAB_BYTES;
-                i32x4 af[2], bf[2][TPW];
-                {
-                    const int sw = (lh ^ (lane & 7)) * 16;
-                    af[0] = *reinterpret_cast<const i32x4 *>(fa + sw);
+                i32x4 af[FD], bf[FD][TPW];
+                auto frag_load = [&](int k1, auto slot_c) __attribute__((always_inline)) {
+                    constexpr int slot = decltype(slot_c)::value;
+                    const int s1 = k1 >> 2, sw = ((2 * (k1 & 3) + lh) ^ (lane & 7)) * 16;
+                    af[slot] = *reinterpret_cast<const i32x4 *>(fa + s1 * aslab + sw);
 #pragma unroll
-                    for (int t = 0; t < TPW; ++t) bf[0][t] = *reinterpret_cast<const i32x4 *>(fb[t] + sw);
+                    for (int t = 0; t < TPW; ++t)
+                        bf[slot][t] = *reinterpret_cast<const i32x4 *>(fb[t] + (size_t)s1 * bslab + sw);
+                };
+                // Whole slabs, four steps each, without conditions (the steps past K multiply the
+                // zero padding of the slab): straight-line code lets the waits count exactly.
+                static_for<0, FD - 1>([&](auto d_c) { frag_load(decltype(d_c)::value, d_c); });
+                for (int s1 = 0; s1 < nslab - 1; ++s1) {
+                    static_for<0, FD>([&](auto h_c) {
+                        constexpr int h = decltype(h_c)::value;
+                        frag_load(4 * s1 + h + FD - 1, std::integral_constant<int, (h + FD - 1) % FD>{});
+#pragma unroll
+                        for (int t = 0; t < TPW; ++t) acc[t] = T::mfma(bf[h][t], af[h], acc[t]);
+                    });
                 }
-                for (int ks = 0; ks < g.ksteps; ks += 2) {
+                frag_load(4 * (nslab - 1) + FD - 1, std::integral_constant<int, FD - 1>{});
+                static_for<0, FD>([&](auto h_c) {
+                    constexpr int h = decltype(h_c)::value;
 #pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        const int k1 = ks + h + 1;                 // the step to fetch
-                        if (k1 < g.ksteps) {
-                            const int s1 = k1 >> 2, sw = ((2 * (k1 & 3) + lh) ^ (lane & 7)) * 16;
-                            af[(h + 1) & 1] = *reinterpret_cast<const i32x4 *>(fa + s1 * aslab + sw);
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t)
-                                bf[(h + 1) & 1][t] = *reinterpret_cast<const i32x4 *>(fb[t] + (size_t)s1 * bslab + sw);
-                        }
-                        if (ks + h < g.ksteps) {
-#pragma unroll
-                            for (int t = 0; t < TPW; ++t) acc[t] = T::mfma(bf[h][t], af[h], acc[t]);
-                        }
-                    }
-                }
+                    for (int t = 0; t < TPW; ++t) acc[t] = T::mfma(bf[h][t], af[h], acc[t]);
+                });
             } else if (mact) {
                 for (int ks = 0; ks < g.ksteps; ++ks) {
                     const int s = ks >> 2, s4 = ks & 3;
@@ -642,7 +665,9 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 if (s2 < nslab) {
 #pragma unroll
                     for (int q = 0; q < CE; ++q) {
-                        acc_t v = csa[s2][q];
+                        acc_t v;
+                        if constexpr (T::IS_INT) v = (acc_t)csa[s2][2 * (q >> 2) + (q & 1)][(q >> 1) & 1];
+                        else v = (acc_t)csa[s2][q];
                         v = add_t(v, dpp_get<0x128>(v));          // lane ^ 8
                         v = add_xor16(v);
                         v = add_xor32(v);
