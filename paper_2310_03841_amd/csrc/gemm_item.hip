@@ -283,55 +283,73 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 }
             }
         } else {
-            // B stored K x N: chunks run along n and are transposed element by element
+            // B stored K x N: chunks run along n and are transposed on the way into LDS
             for (int q = tid; q < nslab * Nr * 8; q += NT)
                 reinterpret_cast<i32x4 *>(sB)[q] = i32x4{0, 0, 0, 0};
             item_barrier();
+            // A work item is KPT consecutive rows k of one chunk of columns: the KPT values of a
+            // column make one 32-bit word of the transposed copy, so every LDS write is a word.
+            constexpr int KPT = 4 / ES;
             const int cpr = (N + CE - 1) / CE;                   // chunks along n per row k
-            const int total = loader ? 0 : K * cpr;            // the loading wave takes no part
-            for (int q0 = tid; q0 < total; q0 += 4 * 256) {
-                i32x4 v[4];
+            const int total = loader ? 0 : ((K + KPT - 1) / KPT) * cpr;     // the loading wave takes no part
+            for (int q0 = tid; q0 < total; q0 += 2 * 256) {
+                i32x4 v[2][KPT];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 2; ++u) {
                     const int q = q0 + 256 * u;
-                    v[u] = i32x4{0, 0, 0, 0};
-                    if (q < total) {
-                        const int k = q / cpr, chn = q - k * cpr;
-                        v[u] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * g.ldb + chn * CE) * ES);
+                    const int kg = q / cpr, chn = q - kg * cpr;
+#pragma unroll
+                    for (int kk = 0; kk < KPT; ++kk) {
+                        const int k = kg * KPT + kk;
+                        v[u][kk] = i32x4{0, 0, 0, 0};
+                        if (q < total && k < K)
+                            v[u][kk] = *reinterpret_cast<const i32x4 *>(Bb + ((long)k * g.ldb + chn * CE) * ES);
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < 2; ++u) {
                     const int q = q0 + 256 * u;
                     if (q < total) {
-                        const int k = q / cpr, chn = q - k * cpr;
-                        const int kb = k * ES;
+                        const int kg = q / cpr, chn = q - kg * cpr;
+                        const int kb = kg * 4;                   // byte offset of the word along K
                         uint8_t *col = sB + (size_t)(kb >> 7) * Nr * SLAB_BYTES + (kb & 15);
                         const int kc = (kb >> 4) & 7;
-                        acc_t part = T::zero();                  // this chunk's share of b[k] = sum over n
+                        acc_t part[KPT];                         // shares of b[k] = sum over n
+#pragma unroll
+                        for (int kk = 0; kk < KPT; ++kk) part[kk] = T::zero();
 #pragma unroll
                         for (int e = 0; e < CE; ++e) {
                             const int n = chn * CE + e;
                             if (n < N) {
-                                if (PROT) {
-                                    const acc_t x = T::elem(v[u], e);
-                                    part = add_t(part, x);
-                                    if (!T::IS_INT) bmax = fmaxf(bmax, fabsf((float)x));
+                                uint32_t word = 0;
+#pragma unroll
+                                for (int kk = 0; kk < KPT; ++kk) {
+                                    if (PROT) {
+                                        const acc_t x = T::elem(v[u][kk], e);
+                                        part[kk] = add_t(part[kk], x);
+                                        if (!T::IS_INT) bmax = fmaxf(bmax, fabsf((float)x));
+                                    }
+                                    if (ES == 2) {
+                                        const uint32_t w = (uint32_t)v[u][kk][e >> 1];
+                                        word |= ((e & 1) ? (w >> 16) : (w & 0xFFFFu)) << (16 * kk);
+                                    } else {
+                                        const uint32_t w = (uint32_t)v[u][kk][e >> 2];
+                                        word |= ((w >> (8 * (e & 3))) & 0xFFu) << (8 * kk);
+                                    }
                                 }
-                                uint8_t *d = col + n * SLAB_BYTES + ((kc ^ (n & 7)) * 16);
-                                if (ES == 2) {
-                                    const uint32_t w = (uint32_t)v[u][e >> 1];
-                                    *reinterpret_cast<uint16_t *>(d) = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xFFFFu));
-                                } else {
-                                    const uint32_t w = (uint32_t)v[u][e >> 2];
-                                    *d = (uint8_t)(w >> (8 * (e & 3)));
-                                }
+                                *reinterpret_cast<uint32_t *>(col + n * SLAB_BYTES + ((kc ^ (n & 7)) * 16)) = word;
                             }
                         }
                         // a row of the stored B is a run of consecutive lanes: few lanes per word
                         if (PROT && !g.cached_b) {
-                            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(b_lds) + k, (int)part);
-                            else atomicAdd(reinterpret_cast<float *>(b_lds) + k, (float)part);
+#pragma unroll
+                            for (int kk = 0; kk < KPT; ++kk) {
+                                const int k = kg * KPT + kk;
+                                if (k < K) {
+                                    if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(b_lds) + k, (int)part[kk]);
+                                    else atomicAdd(reinterpret_cast<float *>(b_lds) + k, (float)part[kk]);
+                                }
+                            }
                         }
                     }
                 }
