@@ -81,6 +81,7 @@ struct ItemArgs {
     int stages;                                   // LDS buffers of the ring A streams through (2..8)
     int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
     int mul24_ok;
+    int b16_ok;                                   // int8: |b| < 2^15 (N <= 255): the row dots take 16-bit pairs
     int cached_b;                                 // take b and max|B| from b_sum / b_max instead of forming them
     // protected launches: everything below is written with plain stores, item by item
     uint32_t *cc_obs, *rc_obs, *rc_pred, *a_sum, *a_max, *b_sum, *b_max, *cc_pred, *s_pred;
@@ -462,10 +463,19 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                                 for (int d = 0; d < 4; ++d) {
                                     const int wd = x4[d];
                                     const item_s16x2 w = item_s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
-                                    csa[s2][2 * d] += (w << 8) >> 8;      // bytes 0 and 2, sign-extended
-                                    csa[s2][2 * d + 1] += w >> 8;         // bytes 1 and 3
+                                    const item_s16x2 ev = (w << 8) >> 8, od = w >> 8;   // bytes 0, 2 and 1, 3, sign-extended
+                                    csa[s2][2 * d] += ev;
+                                    csa[s2][2 * d + 1] += od;
+                                    if (g.b16_ok) {
+                                        // the same pairs against pairs of b: two products per instruction
+                                        const item_s16x2 b02 = item_s16x2{(short)bv[4 * d], (short)bv[4 * d + 2]};
+                                        const item_s16x2 b13 = item_s16x2{(short)bv[4 * d + 1], (short)bv[4 * d + 3]};
+                                        dot[p] = __builtin_amdgcn_sdot2(ev, b02, (int)dot[p], false);
+                                        dot[p] = __builtin_amdgcn_sdot2(od, b13, (int)dot[p], false);
+                                    }
                                 }
                             }
+                            if (T::IS_INT && g.b16_ok) continue;
 #pragma unroll
                             for (int q = 0; q < CE; ++q) {
                                 const acc_t x = T::elem(x4, q);
@@ -910,6 +920,7 @@ hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, const void *A, 
     g.stages = item_stages(dt, wm, s.M, s.N, s.K);
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
     g.mul24_ok = s.N < 65536 ? 1 : 0;
+    g.b16_ok = s.N <= 255 ? 1 : 0;
     g.cached_b = cached_b ? 1 : 0;
     g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred; g.a_sum = w.a_sum; g.a_max = w.a_max;
     g.b_sum = w.b_sum; g.b_max = w.b_max; g.cc_pred = w.cc_pred; g.s_pred = w.s_pred;
