@@ -729,8 +729,11 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                         for (int q4 = 0; q4 < CE / 4; ++q4) {
                             const i32x4 aw = ap[q4];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                dot = add_t(dot, mul_t(T::elem(v, 4 * q4 + e), from_word<acc_t>((uint32_t)aw[e])));
+                            for (int e = 0; e < 4; ++e) {
+                                // int8: |a| <= 128 M < 2^23 here (M <= 1024): 24-bit multiplies are exact
+                                if constexpr (T::IS_INT) dot = __mul24((int)T::elem(v, 4 * q4 + e), aw[e]) + dot;
+                                else dot = add_t(dot, mul_t(T::elem(v, 4 * q4 + e), from_word<acc_t>((uint32_t)aw[e])));
+                            }
                         }
                     }
                 }
