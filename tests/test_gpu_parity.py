@@ -865,3 +865,39 @@ def test_faults_in_the_operands(ctx, M, N, K):
     run.gemm(ab.ABFT_DETECT)
     assert run.cnt()[2] == ab.ABFT_CLEAN
     assert np.array_equal(run.C()[0], orc.gemm(A2[0], B2[0], True).astype(np.int32))
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(40, 50, 64, 1100, True), (70, 40, 100, 1030, False),
+                                                 (36, 300, 128, 1040, True)])
+def test_item_kernel_more_items_than_workgroups(dtype, M, N, K, batch, trans_b):
+    """More batch items than the kernel launches workgroups (1024): a workgroup takes several items
+    in turn, reusing its LDS, and the flagged counts of all its items meet in one ticket.
+    (K is kept at 64 or more: the re-check after a correction sums the stored, rounded C of every
+    item, and with a much smaller K the tolerance 1e-3 K max|A| max|B| comes within reach of the
+    rounding of a row of bf16 values.)"""
+    c = ab.abft_create(max_rows=batch * M, max_cols=batch * N, max_depth=batch * 128, max_batch=batch)
+    try:
+        A, B = gen.gen_operands(dtype, M, N, K, 91, 92, trans_b=trans_b, batch=batch, b_kind="act")
+        P = oracle_items(dtype, A, B, trans_b)
+        run = Run(c, dtype, A, B, trans_b)
+        assert ab.abft_tile_shape(run.code, run.shape) == (M, N)
+        run.gemm(ab.ABFT_DETECT)
+        check_clean(run, P)
+        C_clean = run.C().copy()
+        # armed flips in an item of the first turn and in one of the second turn of a workgroup
+        bit = 27 if dtype == "i8" else 30
+        for bi in (5, 1024 + 5, batch - 1):
+            run.inject(bi, M - 1, N - 1, bit, ab.ABFT_INJECT_ACCUMULATOR)
+            run.gemm(ab.ABFT_DETECT)
+            rf, cf = run.flags()
+            cnt = run.cnt()
+            assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, M - 1] and cf[bi, N - 1]
+            assert cnt[0] == 1 and cnt[1] == 1 and cnt[2] == ab.ABFT_LOCALISED
+            run.correct()
+            assert np.array_equal(run.C(), C_clean) and run.cnt()[2] == ab.ABFT_CLEAN
+        run.dC.fill_(0)
+        run.gemm(ab.ABFT_OFF)
+        assert np.array_equal(run.C(), C_clean)
+    finally:
+        ab.abft_destroy(c)
