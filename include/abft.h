@@ -162,8 +162,8 @@ int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_sha
  * |difference| <= tau otherwise; NaN or Inf always flag) and writes flags, counts and status.
  * A and B must stay unchanged until the finish kernel has run.
  * A batch of at least 64 small problems (per-head attention products: N <= 640, M <= 1024, a row
- * of K at most 640 bytes, operands of one item fitting the local memory of a compute unit; not
- * with ABFT_STORED_SUMS) is one kernel instead: one workgroup per batch item forms b, a, both
+ * of K at most 640 bytes, operands of one item fitting the local memory of a compute unit; with
+ * ABFT_STORED_SUMS only up to N = 256) is one kernel instead: one workgroup per batch item forms b, a, both
  * predictions and both observed sums from on-chip operands and compares them itself.
  * mode ABFT_OFF ignores `r` (may be NULL).  Flags and counts are overwritten. */
 int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,

@@ -310,7 +310,7 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
 // A batch of small problems: one kernel does everything and writes the workspace vectors with
 // plain stores, into the region and the b slot in use (nothing has to start at zero; what it
 // leaves there counts as dirty for the tiled path).
-static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, const void *A, const void *B, void *C,
+static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, bool stored, const void *A, const void *B, void *C,
                         const Shape &sh, const Workspace &w, const Verdict &v, const InjectArm &arm, hipEvent_t *ev,
                         hipStream_t st)
 {
@@ -318,7 +318,7 @@ static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, const void *A, co
     if (!cached) ctx->bclean[ctx->bslot] = false;
     if (ctx->dirty[ctx->cur] < w.zero_words) ctx->dirty[ctx->cur] = w.zero_words;
     ctx->sto_valid = false;
-    HIP_TRY(launch_gemm_item(dtype, true, cached, A, B, C, sh, w, &v, arm, st));
+    HIP_TRY(launch_gemm_item(dtype, true, cached, stored, A, B, C, sh, w, &v, arm, st));
     if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); }
     return ABFT_OK;
 }
@@ -361,7 +361,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     const bool stored = (mode & ABFT_STORED_SUMS) != 0;
     const bool item = gemm_item_eligible(dtype, sh, stored);
-    rc = item ? enqueue_item(ctx, dtype, cached, A, B, C, sh, w, v, arm, ev, st)
+    rc = item ? enqueue_item(ctx, dtype, cached, stored, A, B, C, sh, w, v, arm, ev, st)
               : enqueue_tiled(ctx, dtype, cached, stored, A, B, C, sh, &w, v, arm, ev, st);
     if (rc) return rc;
     if (ev) ctx->prof_n++;
@@ -372,7 +372,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
     // a correction inside this call replaces values the stored-side sums already contain
-    ctx->sto_valid = stored && base == ABFT_DETECT && !item;
+    ctx->sto_valid = stored && base == ABFT_DETECT;
     if (base == ABFT_DETECT_CORRECT) {
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words);

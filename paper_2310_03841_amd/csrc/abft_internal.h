@@ -102,7 +102,7 @@ hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row
 // Batches of small problems (attention heads): one workgroup per batch item, all checksums and
 // the comparison inside the GEMM kernel (gemm_item.hip).  v may be null when protect is false.
 bool gemm_item_eligible(int dt, const Shape &s, bool stored_sums);
-hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, const void *A, const void *B, void *C,
+hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, bool stored_sums, const void *A, const void *B, void *C,
                             const Shape &s, const Workspace &w, const Verdict *v, const InjectArm &arm,
                             hipStream_t st);
 void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn);

@@ -85,6 +85,7 @@ struct ItemArgs {
     int cached_b;                                 // take b and max|B| from b_sum / b_max instead of forming them
     // protected launches: everything below is written with plain stores, item by item
     uint32_t *cc_obs, *rc_obs, *rc_pred, *a_sum, *a_max, *b_sum, *b_max, *cc_pred, *s_pred;
+    uint32_t *cc_sto, *rc_sto;                    // sums of C as stored (after rounding), on request (floating point)
     float *maxabs, *tau;
     float tau_override;
     uint8_t *row_flag, *col_flag;
@@ -98,7 +99,7 @@ struct ItemArgs {
 __host__ __device__ constexpr int item_max_slabs(int wm, int tpw) { return wm == 2 ? ITEM_MAX_SLABS : (tpw <= 2 ? 3 : 2); }
 
 // LDS of a workgroup: B, `stages` buffers for blocks of A, the waves' output stages, vectors.
-__host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int M, int N, int K)
+__host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int M, int N, int K, bool sto)
 {
     const int es = elem_size(dt), ke = SLAB_BYTES / es;
     const int nslab = (K * es + SLAB_BYTES - 1) / SLAB_BYTES;
@@ -106,6 +107,7 @@ __host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int
     const int Nr = (N + 31) / 32 * 32, Mr = (M + bmr - 1) / bmr * bmr;
     size_t b = (size_t)nslab * Nr * SLAB_BYTES + (size_t)stages * nslab * bmr * SLAB_BYTES + 4 * ITEM_STAGE_WAVE;
     b += ((size_t)2 * nslab * ke + 2 * Mr + Nr + 24) * 4;
+    if (sto) b += ((size_t)Mr + Nr) * 4;          // stored-side sums
     return b;
 }
 
@@ -113,14 +115,14 @@ __host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int
 // computing waves run through the blocks without meeting): as deep as half the LDS of a compute unit allows (two workgroups per
 // unit), else as deep as the whole allows; the loading wave waits with an immediate count, so
 // (stages - 2) blocks' worth of load instructions must stay below 64.  0: does not fit.
-__host__ inline int item_stages(int dt, int wm, int M, int N, int K)
+__host__ inline int item_stages(int dt, int wm, int M, int N, int K, bool sto)
 {
     const int es = elem_size(dt);
     const int nslab = (K * es + SLAB_BYTES - 1) / SLAB_BYTES;
     const int ql = 4 * wm * nslab;
     int smax = 2 + 63 / ql;
     if (smax > ITEM_MAX_STAGES) smax = ITEM_MAX_STAGES;
-    const size_t fixed = item_lds_bytes(dt, wm, 0, M, N, K);
+    const size_t fixed = item_lds_bytes(dt, wm, 0, M, N, K, sto);
     const size_t abuf = (size_t)nslab * 32 * wm * SLAB_BYTES;
     const int nrb = (M + 32 * wm - 1) / (32 * wm);
     const size_t budgets[2] = {(size_t)ITEM_LDS_LIMIT / 2, (size_t)ITEM_LDS_LIMIT};
@@ -140,7 +142,8 @@ __host__ inline int item_stages(int dt, int wm, int M, int N, int K)
 // fetched at the start of the item, by the four computing waves themselves, and the loading
 // wave is left out: with four waves per workgroup two workgroups share a compute unit without
 // their waves competing for the registers of one SIMD.
-template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES>
+// STO (floating point, protected): also the row / column sums of the values as they are stored.
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES, bool STO>
 __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(ItemArgs g)
 {
     constexpr int NT = RES ? 256 : ITEM_THREADS;
@@ -176,6 +179,8 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
     uint32_t *rcobs = b_lds + nslab * KE;
     uint32_t *rcpred = rcobs + Mr;
     uint32_t *ccobs = rcpred + Mr;
+    uint32_t *rcsto = ccobs + Nr + 24;           // STO: [Mr], then ccsto [Nr]
+    uint32_t *ccsto = rcsto + Mr;
     uint32_t *misc = ccobs + Nr;                 // [24]: 0..3 max|A| per wave, 4..7 max|B|, 8..11 a.b partials,
                                                  // 16..23 flagged rows / columns per wave
 
@@ -250,6 +255,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
             for (int k = tid; k < 2 * nslab * KE; k += 256) a_lds[k] = 0u;     // a_lds and b_lds
             for (int n = tid; n < Nr; n += 256) ccobs[n] = 0u;
             for (int r = tid; r < Mr; r += 256) rcobs[r] = 0u;
+            if (STO) for (int r = tid; r < Mr + Nr; r += 256) rcsto[r] = 0u;     // rcsto and ccsto
             if (tid < 16) misc[tid] = 0u;
         }
         float bmax = 0.f;                                        // max|B| seen by this thread
@@ -427,10 +433,14 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 else csa[s2][q] = 0.f;
             }
         acc_t cs[TPW][4];
+        float cs_s[STO ? TPW : 1][4];            // column sums of the stored values
 #pragma unroll
         for (int t = 0; t < TPW; ++t)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) cs[t][e] = T::zero();
+            for (int e = 0; e < 4; ++e) {
+                cs[t][e] = T::zero();
+                cs_s[STO ? t : 0][e] = 0.f;
+            }
 
         // one row block, as the computing waves see it
         auto compute_block = [&](int rb) __attribute__((always_inline)) {
@@ -568,6 +578,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
             // + (i & 3); read back, lane l has four consecutive columns 4 (l & 7) .. of row
             // 8 p + (l >> 3): eight lanes cover a 32-column row segment.
             acc_t rsum[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
+            float rsum_s[4] = {0.f, 0.f, 0.f, 0.f};
             const int row0 = m0 + wm * 32 + (lane >> 3);             // this lane's row of pass 0; pass p: + 8 p
             const long rowstep = 8 * g.ldc * OS;
             uint8_t *dst_row0 = Cb + ((long)row0 * g.ldc + 4 * (lane & 7)) * OS;
@@ -625,6 +636,19 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                         } else {
                             const uint32_t lo = pack2<DT>((float)v[0], (float)v[1]);
                             const uint32_t hi = pack2<DT>((float)v[2], (float)v[3]);
+                            if constexpr (STO) {
+                                float sv[4];
+                                if constexpr (DT == DT_BF16) {
+                                    sv[0] = __uint_as_float(lo << 16); sv[1] = __uint_as_float(lo & 0xFFFF0000u);
+                                    sv[2] = __uint_as_float(hi << 16); sv[3] = __uint_as_float(hi & 0xFFFF0000u);
+                                } else {
+                                    sv[0] = f16_bits_to_f32(lo & 0xFFFFu); sv[1] = f16_bits_to_f32(lo >> 16);
+                                    sv[2] = f16_bits_to_f32(hi & 0xFFFFu); sv[3] = f16_bits_to_f32(hi >> 16);
+                                }
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) cs_s[t][e] += rv ? sv[e] : 0.f;
+                                rsum_s[p] += (sv[0] + sv[1]) + (sv[2] + sv[3]);
+                            }
                             if (rv && cfull) {
                                 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
                                 *reinterpret_cast<u32x2 *>(dst) = u32x2{lo, hi};
@@ -648,6 +672,10 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                         uint32_t *dst = rcobs + m0 + wm * 32 + 8 * p + (lane >> 3);
                         if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)r);
                         else atomicAdd(reinterpret_cast<float *>(dst), (float)r);
+                    }
+                    if constexpr (STO) {
+                        const float rs = row8_sum(rsum_s[p]);
+                        if ((lane & 7) == 0 && mact) atomicAdd(reinterpret_cast<float *>(rcsto) + m0 + wm * 32 + 8 * p + (lane >> 3), rs);
                     }
                 }
             }
@@ -684,6 +712,13 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                         if (WM == 1) *dst = as_word(v);
                         else if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)v);
                         else atomicAdd(reinterpret_cast<float *>(dst), (float)v);
+                    }
+                    if constexpr (STO) {
+                        float vs = cs_s[t][e];
+                        vs = add_t(vs, dpp_get<0x128>(vs));       // lane ^ 8
+                        vs = add_xor16(vs);
+                        vs = add_xor32(vs);
+                        if (lane < 8 && nb < NB) atomicAdd(reinterpret_cast<float *>(ccsto) + nb * 32 + 4 * lane + e, vs);
                     }
                 }
             }
@@ -746,6 +781,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     const uint32_t obs = ccobs[n];
                     g.cc_pred[o] = as_word(dot);
                     g.cc_obs[o] = obs;
+                    if (STO) g.cc_sto[o] = ccsto[n];
                     fl = mismatch<T::IS_INT>(obs, as_word(dot), tol);
                     g.col_flag[o] = fl ? 1 : 0;
                 }
@@ -759,6 +795,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     const uint32_t obs = rcobs[r], pred = rcpred[r];
                     g.rc_obs[o] = obs;
                     g.rc_pred[o] = pred;
+                    if (STO) g.rc_sto[o] = rcsto[r];
                     fl = mismatch<T::IS_INT>(obs, pred, tol);
                     g.row_flag[o] = fl ? 1 : 0;
                 }
@@ -849,20 +886,21 @@ static void item_config(int N, int *wm, int *tpw)
 bool gemm_item_eligible(int dt, const Shape &s, bool stored_sums)
 {
     const int es = elem_size(dt);
-    if (stored_sums && dt != DT_I8) return false;          // the stored-side sums live in the tiled kernels
+    const bool sto = stored_sums && dt != DT_I8;
     if (s.batch < ITEM_MIN_BATCH) return false;
     if (s.N > 640 || s.M > ITEM_MAX_M) return false;
     if ((long)s.K * es > ITEM_MAX_SLABS * SLAB_BYTES) return false;
     int wm, tpw;
     item_config(s.N, &wm, &tpw);
+    if (sto && tpw > 2) return false;                      // wide tiles have no registers to spare for them
     if (((long)s.K * es + SLAB_BYTES - 1) / SLAB_BYTES > item_max_slabs(wm, tpw)) return false;
-    return item_stages(dt, wm, s.M, s.N, s.K) > 0;
+    return item_stages(dt, wm, s.M, s.N, s.K, sto) > 0;
 }
 
-template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES>
-static hipError_t launch_item_res(const ItemArgs &g, size_t smem, hipStream_t st)
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES, bool STO>
+static hipError_t launch_item_sto(const ItemArgs &g, size_t smem, hipStream_t st)
 {
-    auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB, RES>;
+    auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB, RES, STO>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -873,6 +911,15 @@ static hipError_t launch_item_res(const ItemArgs &g, size_t smem, hipStream_t st
     const unsigned blocks = (unsigned)(g.batch < ITEM_MAX_BLOCKS ? g.batch : ITEM_MAX_BLOCKS);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(RES ? 256 : ITEM_THREADS), smem, st, g);
     return hipGetLastError();
+}
+
+template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES>
+static hipError_t launch_item_res(const ItemArgs &g, size_t smem, hipStream_t st)
+{
+    if constexpr (PROT && DT != DT_I8 && TPW <= 2) {
+        if (g.cc_sto) return launch_item_sto<DT, WM, TPW, PROT, TRANSB, RES, true>(g, smem, st);
+    }
+    return launch_item_sto<DT, WM, TPW, PROT, TRANSB, RES, false>(g, smem, st);
 }
 
 template <int DT, int WM, int TPW, bool PROT, bool TRANSB>
@@ -902,11 +949,12 @@ static hipError_t launch_item_dt(int wm, int tpw, bool protect, bool transB, con
     return launch_item_cfg<DT, 1, 5>(protect, transB, g, smem, st);
 }
 
-hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, const void *A, const void *B, void *C,
+hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, bool stored_sums, const void *A, const void *B, void *C,
                             const Shape &s, const Workspace &w, const Verdict *v, const InjectArm &arm,
                             hipStream_t st)
 {
-    if (!gemm_item_eligible(dt, s, false)) return hipErrorInvalidValue;
+    const bool sto = protect && stored_sums && dt != DT_I8;
+    if (!gemm_item_eligible(dt, s, sto)) return hipErrorInvalidValue;
     if (protect && v == nullptr) return hipErrorInvalidValue;
     const int es = elem_size(dt);
     int wm, tpw;
@@ -920,19 +968,20 @@ hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, const void *A, 
     g.ksteps = (s.K * es + 31) / 32;
     g.NB = (s.N + 31) / 32;
     g.nrb = (s.M + 32 * wm - 1) / (32 * wm);
-    g.stages = item_stages(dt, wm, s.M, s.N, s.K);
+    g.stages = item_stages(dt, wm, s.M, s.N, s.K, sto);
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
     g.mul24_ok = s.N < 65536 ? 1 : 0;
     g.b16_ok = s.N <= 255 ? 1 : 0;
     g.cached_b = cached_b ? 1 : 0;
     g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred; g.a_sum = w.a_sum; g.a_max = w.a_max;
     g.b_sum = w.b_sum; g.b_max = w.b_max; g.cc_pred = w.cc_pred; g.s_pred = w.s_pred;
+    g.cc_sto = sto ? w.cc_sto : nullptr; g.rc_sto = sto ? w.rc_sto : nullptr;
     g.maxabs = w.maxabs; g.tau = w.tau;
     g.tau_override = v ? v->tau_override : 0.f;
     g.row_flag = v ? v->row_flag : nullptr; g.col_flag = v ? v->col_flag : nullptr;
     g.counts = v ? v->counts : nullptr;
     g.ticket = w.cmp_ticket; g.group_ticket = w.cmp_ticket + 4;
-    const size_t smem = item_lds_bytes(dt, wm, g.stages, s.M, s.N, s.K);
+    const size_t smem = item_lds_bytes(dt, wm, g.stages, s.M, s.N, s.K, sto);
     switch (dt) {
     case DT_I8:   return launch_item_dt<DT_I8>(wm, tpw, protect, s.transB != 0, g, smem, st);
     case DT_BF16: return launch_item_dt<DT_BF16>(wm, tpw, protect, s.transB != 0, g, smem, st);

@@ -280,7 +280,7 @@ hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, co
                        const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st)
 {
     if (!protect && gemm_item_eligible(dt, s, false))
-        return launch_gemm_item(dt, false, false, A, B, C, s, w, nullptr, arm, st);
+        return launch_gemm_item(dt, false, false, false, A, B, C, s, w, nullptr, arm, st);
     GemmArgs g;
     g.A = (const uint8_t *)A;
     g.B = (const uint8_t *)B;

@@ -201,6 +201,17 @@ def test_stored_flip_verify_correct(ctx, dtype, M, N, K, batch, trans_b):
 @pytest.mark.parametrize("M,N,K,batch,trans_b", [(600, 520, 256, 1, True), (197, 768, 768, 1, True),
                                                   (130, 70, 100, 2, False)])
 def test_tightened_storage_check(ctx, dtype, M, N, K, batch, trans_b):
+    _tightened_storage_case(ctx, dtype, M, N, K, batch, trans_b)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(70, 50, 40, 64, False), (100, 130, 72, 65, True),
+                                                 (197, 197, 64, 64, True)])
+def test_tightened_storage_check_item_kernel(ctx_items, dtype, M, N, K, batch, trans_b):
+    _tightened_storage_case(ctx_items, dtype, M, N, K, batch, trans_b)
+
+
+def _tightened_storage_case(ctx, dtype, M, N, K, batch, trans_b):
     """ABFT_STORED_SUMS: the epilogue's sums of the rounded values equal the oracle's sums of the
     stored clean C; verify then flags stored flips down to 1e-2 tau, as the oracle's check_stored."""
     A, B = gen.gen_operands(dtype, M, N, K, 61, 62, trans_b=trans_b, batch=batch)
