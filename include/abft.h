@@ -40,6 +40,10 @@
  *     abft_encode_b / abft_discrepancy only enqueue work on `stream` (a hipStream_t
  *     passed as void*): they allocate nothing, copy nothing to the host and never
  *     synchronise.  Results are valid once the stream has reached that point.
+ *     They may be captured into a HIP graph (after one eager call of the same kind, which sets
+ *     kernel attributes): calls enqueued under capture clear what they accumulate into themselves,
+ *     so a replay does not depend on what ran before it; every buffer named at capture is used
+ *     by the replays.
  *   - One context must be used from one stream at a time.
  *   - Return value: ABFT_OK or a negative error code.  A detected fault is NOT
  *     an error: it is reported through the flag vectors and counts.

@@ -218,12 +218,23 @@ static int check_verdict(const abft_result *r, Verdict *v)
 // A re-sum of stored C accumulates into the re-summing region the previous one did not use; the
 // compare that follows clears that previous region.  Returns what the caller passes on.
 struct ResumPlan { size_t stale; uint32_t *other; size_t other_words; };
-static ResumPlan begin_resum(abft_ctx *ctx, size_t words)
+// While a stream is being captured into a graph, what the host knows about the regions describes
+// the moment of capture, not the moment of a replay (a replayed call finds the region it
+// accumulates into as its own previous replay left it).  Calls enqueued under capture therefore
+// clear everything they accumulate into themselves; the alternation between two regions, which
+// saves that clearing, is for calls that run once.
+static bool capturing(hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(st, &cs) == hipSuccess && cs == hipStreamCaptureStatusActive;
+}
+
+static ResumPlan begin_resum(abft_ctx *ctx, size_t words, hipStream_t st)
 {
     const int prev = ctx->vcur;
     ctx->vcur ^= 1;
     ResumPlan p;
-    p.stale = ctx->vdirty[ctx->vcur];
+    p.stale = capturing(st) ? words : ctx->vdirty[ctx->vcur];
     p.other = ctx->pool_vobs + (size_t)prev * ctx->vregion_words;
     p.other_words = ctx->vdirty[prev];
     // until the kernels are enqueued both count as dirty; end_resum settles it
@@ -243,7 +254,7 @@ static void end_resum(abft_ctx *ctx, size_t words)
 static int begin_b_pass(abft_ctx *ctx, hipStream_t st)
 {
     const int target = ctx->bslot ^ 1;
-    if (!ctx->bclean[target])
+    if (!ctx->bclean[target] || capturing(st))
         HIP_TRY(launch_zero(ctx->pool_depth + (size_t)target * ctx->bslot_words, ctx->bslot_words, st));
     ctx->bclean[target] = false;
     ctx->bslot = target;
@@ -285,7 +296,7 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
     }
     carve(ctx, dtype, sh, w);
     uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
-    const size_t stale = ctx->dirty[ctx->cur];
+    const size_t stale = capturing(st) ? w->zero_words : ctx->dirty[ctx->cur];
     ctx->dirty[ctx->cur] = ctx->region_words;            // until everything below is enqueued
     if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, *w, w->cc_obs, stale, st));
     else if (stale) HIP_TRY(launch_zero(w->cc_obs, stale, st));
@@ -375,7 +386,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->sto_valid = stored && base == ABFT_DETECT;
     if (base == ABFT_DETECT_CORRECT) {
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
-        const ResumPlan rp = begin_resum(ctx, words);
+        const ResumPlan rp = begin_resum(ctx, words, st);
         carve(ctx, dtype, sh, &w);
         HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, rp.stale, rp.other, rp.other_words, st));
         end_resum(ctx, words);
@@ -398,7 +409,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
-    const ResumPlan rp = begin_resum(ctx, words);
+    const ResumPlan rp = begin_resum(ctx, words, st);
     Workspace w;
     carve(ctx, dtype, sh, &w);
     if (rp.stale) HIP_TRY(launch_zero(w.cc_vobs, rp.stale, st));
@@ -421,12 +432,12 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     rc = check_verdict(r, &v);
     if (rc) return rc;
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    hipStream_t st = (hipStream_t)stream;
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
-    const ResumPlan rp = begin_resum(ctx, words);
+    const ResumPlan rp = begin_resum(ctx, words, st);
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words,
-                           (hipStream_t)stream));
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words, st));
     end_resum(ctx, words);
     ctx->vobs_valid = true;
     return ABFT_OK;

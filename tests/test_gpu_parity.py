@@ -912,3 +912,52 @@ def test_item_kernel_more_items_than_workgroups(dtype, M, N, K, batch, trans_b):
         assert np.array_equal(run.C(), C_clean)
     finally:
         ab.abft_destroy(c)
+
+
+@pytest.mark.parametrize("dtype,M,N,K,batch,trans_b", [("i8", 197, 768, 768, 1, True), ("bf16", 600, 520, 256, 2, True),
+                                                       ("bf16", 100, 130, 72, 65, True), ("i8", 70, 50, 40, 64, False)])
+def test_calls_can_be_captured_in_a_graph(ctx_items, dtype, M, N, K, batch, trans_b):
+    """The hot calls only enqueue kernels (no allocation, no copy, no synchronisation, no memset
+    node): a protected GEMM followed by a verify is captured once and replayed several times, with
+    eager work in between, and every replay must give the eager result -- also with a fault
+    armed by the host between replays showing up in exactly that replay's flags."""
+    ctx = ctx_items
+    A, B = gen.gen_operands(dtype, M, N, K, 95, 96, trans_b=trans_b, batch=batch, b_kind="act" if batch > 1 else "weight")
+    run = Run(ctx, dtype, A, B, trans_b)
+    res = run.result()
+    run.gemm(ab.ABFT_DETECT)                     # warm-up: kernel attributes are set on first use
+    run.verify()
+    C_eager = run.dC.clone()
+    vec_eager = [run.ws(w).copy() for w in (ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED, ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS)]
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            rc1 = ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, run.shape, res)
+            rc2 = ab.abft_verify(ctx, run.dC, run.code, run.shape, res)
+    assert rc1 == ab.ABFT_OK and rc2 == ab.ABFT_OK
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        run.dC.fill_(0)
+        run.counts.fill_(99)
+        run.row_flag.fill_(7)
+        run.col_flag.fill_(7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.dC[:, :, :N], C_eager[:, :, :N]), rep
+        rf, cf = run.flags()
+        assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN, rep
+        for w, want in zip((ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED, ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS), vec_eager):
+            got = run.ws(w)
+            if dtype == "i8":
+                assert np.array_equal(got, want), (rep, w)
+            else:       # fp32 atomics: the order of the additions is not fixed
+                assert np.allclose(got, want, rtol=0, atol=1e-3 * max(1.0, float(np.max(np.abs(want))))), (rep, w)
+        # eager work between the replays, on the same context
+        run.inject(0, 1, 2, 5 if dtype == "i8" else 14)
+        run.verify()
+        assert run.cnt()[2] == ab.ABFT_LOCALISED
+    del graph
