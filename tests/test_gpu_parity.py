@@ -961,3 +961,33 @@ def test_calls_can_be_captured_in_a_graph(ctx_items, dtype, M, N, K, batch, tran
         run.verify()
         assert run.cnt()[2] == ab.ABFT_LOCALISED
     del graph
+
+
+def _random_shapes():
+    rng = np.random.default_rng(20231003)
+    out = []
+    for _ in range(24):                     # the tiled kernels: up to a few tiles, ragged everywhere
+        M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        K = int(rng.choice([1, 7, 16, 31, 64, 100, 128, 129, 200, 256, 384, 512, 640]))
+        out.append((M, N, K, int(rng.integers(1, 4)), bool(rng.integers(0, 2))))
+    for _ in range(24):                     # the item kernel: every tile configuration, several slabs
+        N = int(rng.choice([rng.integers(1, 65), rng.integers(65, 257), rng.integers(257, 641)]))
+        M = int(rng.integers(1, 260))
+        K = int(rng.integers(1, 130 if N > 256 else (190 if N > 64 else 320)))
+        out.append((M, N, K, int(rng.integers(64, 70)), bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.fixture(scope="module")
+def ctx_random():
+    c = ab.abft_create(max_rows=70 * 700, max_cols=70 * 700, max_depth=70 * 640, max_batch=70)
+    yield c
+    ab.abft_destroy(c)
+
+
+@pytest.mark.parametrize("M,N,K,batch,trans_b", _random_shapes())
+def test_seeded_random_shapes(ctx_random, M, N, K, batch, trans_b):
+    """Seeded shapes nobody chose by hand, int8 and bf16 alternating (fp16 shares the bf16 code
+    but for the conversion): C, every checksum vector, flags, unprotected mode, C's padding."""
+    dtype = "i8" if (M + N + K) % 2 else "bf16"
+    _clean_case(ctx_random, dtype, M, N, K, batch, trans_b)
