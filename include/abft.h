@@ -44,7 +44,8 @@
  *     kernel attributes): calls enqueued under capture clear what they accumulate into themselves,
  *     so a replay does not depend on what ran before it; every buffer named at capture is used
  *     by the replays.
- *   - One context must be used from one stream at a time.
+ *   - One context must be used from one stream (and one host thread) at a time; different
+ *     contexts share nothing and may be used concurrently.
  *   - Return value: ABFT_OK or a negative error code.  A detected fault is NOT
  *     an error: it is reported through the flag vectors and counts.
  */

@@ -14,6 +14,7 @@
 // Rows of the tile beyond the problem are fetched from a valid row instead of being
 // zero-filled: a row of A only influences the same row of C, which is discarded, and the pass
 // over A's slabs ignores them.
+#include <mutex>
 #include <queue>
 #include <vector>
 
@@ -292,6 +293,8 @@ static int choose_big_rows(int M, int tiles_n, int batch, int ncu)
     struct Memo { int M, tiles_n, batch, ncu, big_rows; };
     static Memo memo[16];
     static int memo_n = 0;
+    static std::mutex memo_lock;                 // contexts may be driven from different host threads
+    std::lock_guard<std::mutex> hold(memo_lock);
     for (int i = 0; i < memo_n; ++i)
         if (memo[i].M == M && memo[i].tiles_n == tiles_n && memo[i].batch == batch && memo[i].ncu == ncu)
             return memo[i].big_rows;

@@ -991,3 +991,32 @@ def test_seeded_random_shapes(ctx_random, M, N, K, batch, trans_b):
     but for the conversion): C, every checksum vector, flags, unprotected mode, C's padding."""
     dtype = "i8" if (M + N + K) % 2 else "bf16"
     _clean_case(ctx_random, dtype, M, N, K, batch, trans_b)
+
+
+def test_two_contexts_on_two_streams():
+    """Two contexts, each on its own stream, interleaved call by call: no state is shared between
+    contexts, so each stream's results are those of its own problem."""
+    c1 = ab.abft_create(max_rows=4096, max_cols=4096, max_depth=4096, max_batch=70)
+    c2 = ab.abft_create(max_rows=70 * 256, max_cols=70 * 256, max_depth=70 * 128, max_batch=70)
+    try:
+        A1, B1 = gen.gen_operands("i8", 600, 520, 256, 101, 102, trans_b=True)
+        A2, B2 = gen.gen_operands("bf16", 100, 130, 72, 103, 104, trans_b=True, batch=65, b_kind="act")
+        r1, r2 = Run(c1, "i8", A1, B1, True), Run(c2, "bf16", A2, B2, True)
+        P1, P2 = oracle_items("i8", A1, B1, True), oracle_items("bf16", A2, B2, True)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for _ in range(5):
+            with torch.cuda.stream(s1):
+                assert ab.abft_gemm(c1, r1.dA, r1.dB, r1.dC, r1.code, ab.ABFT_DETECT, r1.shape, r1.result()) == ab.ABFT_OK
+            with torch.cuda.stream(s2):
+                assert ab.abft_gemm(c2, r2.dA, r2.dB, r2.dC, r2.code, ab.ABFT_DETECT, r2.shape, r2.result()) == ab.ABFT_OK
+            with torch.cuda.stream(s1):
+                assert ab.abft_verify(c1, r1.dC, r1.code, r1.shape, r1.result()) == ab.ABFT_OK
+            with torch.cuda.stream(s2):
+                assert ab.abft_verify(c2, r2.dC, r2.code, r2.shape, r2.result()) == ab.ABFT_OK
+        torch.cuda.synchronize()
+        check_clean(r1, P1)
+        check_clean(r2, P2)
+    finally:
+        ab.abft_destroy(c1)
+        ab.abft_destroy(c2)
