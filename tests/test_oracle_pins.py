@@ -261,11 +261,32 @@ def test_store_int_range_guard_and_values():
 
 
 # ---------------------------------------------------------------- P7: what work is counted
+def _paper_claims():
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_claims.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, vals, unit, where = [x.strip() for x in line.split("|")]
+            assert where, name                                   # every figure carries its citation
+            out[name] = [float(v) for v in vals.split()]
+    return out
+
+
 def test_operation_count_overhead_matches_papers_claim():
+    claims = _paper_claims()
     # extra work of the method: encode MK + KN adds, predicted 2K(M+N), observed 2MN
     def ratio(M, N, K):
         return (2 * K * (M + N) + 2 * M * N + M * K + K * N) / (2 * M * N * K)
-    assert ratio(12608, 3072, 768) == pytest.approx(0.0019, abs=1e-4)   # "< 0.2 %" (abstract)
+    assert ratio(12608, 3072, 768) == pytest.approx(0.0019, abs=1e-4)
+    assert 100 * ratio(12608, 3072, 768) < claims["compute_overhead_max"][0]     # "< 0.2 %" (abstract)
+    # the paper's own counts are consistent with its coverage claim
+    missed, total = claims["missed_of_mismatching"]
+    assert 100 * (1 - missed / total) > claims["coverage_min"][0]
+    # the default tolerance of this build is the paper's bound on eps times the scale of a sum
+    assert orc.tau(1, 1.0, 1.0) == pytest.approx(claims["eps_max"][0])
+    assert claims["fixed_point_coverage"][0] == 100          # what the brute-force pin above demonstrates
     for (M, N, K) in [(6304, 2304, 768), (6304, 768, 768), (6304, 3072, 768), (6304, 768, 3072)]:
         assert 0.001 < ratio(M, N, K) < 0.0036
 
