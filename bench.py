@@ -182,6 +182,20 @@ def main():
     ms_prot_i = float(np.median([r[0] for r in reps]))
     ms_off_i = float(np.median([r[1] for r in reps]))
 
+    # ---- spread of single steps (events around every step; the events themselves cost ~1 us)
+    def step_percentiles(mode, n=100):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for _ in range(5):
+            step(mode)
+        for a, b in ev:
+            a.record()
+            step(mode)
+            b.record()
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+        return {"p10_us": t[n // 10], "p50_us": t[n // 2], "p90_us": t[(9 * n) // 10]}
+    spread = {"protected": step_percentiles(ab.ABFT_DETECT), "unprotected": step_percentiles(ab.ABFT_OFF)}
+
     # ---- the same step on operands that are not in any cache: six copies of A and of C (580 MB)
     # are cycled through, more than the 256 MB of memory-side cache; the weight stays (4.7 MB)
     cold = None
@@ -397,6 +411,7 @@ def main():
             "flips": None if camp is None else dict(camp, note="stored-C single-bit flips, exponent/mantissa 50/50, each applied alone; "
                           "S1 = |delta| > tolerance or non-finite (the gating stratum), S2 = |delta| > "
                           "1e-2 max|C|; flips with |delta| <= tolerance are undetectable by construction"),
+            "single_step_spread": spread,
             "cold_cache": cold,
             "int8_flips": camp_int,
             "transformer_block": blocks,
