@@ -241,27 +241,32 @@ def main():
     c_bytes = M * N * 2
     flips = gen.gen_flips(args.flips, M, N, dtype, gen.seed_for(1, 9))
 
-    def bf16_val(bits):
-        return float((np.array([bits], dtype=np.uint32) << 16).view(np.float32)[0])
+    def fp_val(bits, dt):
+        if dt == "bf16":
+            return float((np.array([bits], dtype=np.uint32) << 16).view(np.float32)[0])
+        return float(np.array([bits], dtype=np.uint16).view(np.float16)[0])
 
-    def campaign(mode, tol_factor):
+    def campaign(mode, tol_factor, ctx=ctx, run=run, flips=flips, dtype=dtype, ms_ref=None):
         """stored-C flips, each applied alone: inject, verify, correct, check restored.
         Strata: S0 all flips; S1 |delta| > the check's tolerance or non-finite (what the check
         is specified to catch); S2 |delta| > 1e-2 * max|C| (flip breaks the 1e-2 acceptance band)."""
-        step(mode)
+        run.gemm(mode)
         tau_dev = float(run.ws(ab.ABFT_WS_TAU)[0, 0])
         tol = tol_factor * tau_dev
         C_clean = run.dC.clone()
         C_host = run.C()[0]
-        cmax = float(np.max(np.abs((C_host.astype(np.uint32) << 16).view(np.float32))))
+        if dtype == "bf16":
+            cmax = float(np.max(np.abs((C_host.astype(np.uint32) << 16).view(np.float32))))
+        else:
+            cmax = float(np.max(np.abs(C_host.view(np.float16).astype(np.float32))))
         strata = {"S0": [0, 0], "S1": [0, 0], "S2": [0, 0]}          # [injected, detected]
         borderline = 0                                               # tol / 2 < |delta| <= 2 tol
         detected = localised = restored = 0
         t_corr = 0.0
         for (_, i, j, bit) in flips:
             i, j, bit = int(i), int(j), int(bit)
-            old = bf16_val(int(C_host[i, j]))
-            new = bf16_val(int(C_host[i, j]) ^ (1 << bit))
+            old = fp_val(int(C_host[i, j]), dtype)
+            new = fp_val(int(C_host[i, j]) ^ (1 << bit), dtype)
             delta = abs(new - old) if np.isfinite(new) else float("inf")
             run.inject(0, i, j, bit)
             run.verify()
@@ -286,7 +291,7 @@ def main():
             run.dC.copy_(C_clean)
         us = (t_corr / max(detected, 1)) * 1e6
         return {"injected": len(flips), "detected": detected, "localised": localised, "restored": restored,
-                "us_per_correction": us, "correction_pct_of_step": 100.0 * us * 1e-3 / ms_prot,
+                "us_per_correction": us, "correction_pct_of_step": 100.0 * us * 1e-3 / (ms_ref or ms_prot),
                 "tolerance": tol, "tau": tau_dev, "max_abs_C": cmax,
                 "strata_injected_detected": strata, "borderline_within_2x_tolerance": borderline}
 
@@ -322,7 +327,7 @@ def main():
     # ---- int8 campaign on the injection workload (ViT-B fc2, batch 32): every flip must be
     # flagged at its row and column; even flips are repaired from the checksums alone, odd ones
     # by the tile recompute, and C must come back bit for bit
-    camp_int = None
+    camp_int = camp_f16 = camp_small = None
     if args.flips > 0 and args.int_flips > 0:
         gi = gen.CONFIGS[4]["gemms"][0]
         Mi, Ni, Ki = gi["M"], gi["N"], gi["K"]
@@ -371,9 +376,82 @@ def main():
                     "us_per_tile_recompute_repair": 1e6 * t_fix[1] / max(n_fix[1], 1),
                     "note": "bit uniform in 0..31, each flip applied alone; times include the host "
                             "synchronisation around each call"}
+        # the same GEMM in fp16 (exponent bits 10..14 or mantissa bits 0..9, half and half)
+        Af, Bf = gen.gen_operands("f16", Mi, Ni, Ki, gen.seed_for(4, 2), gen.seed_for(4, 3), trans_b=True)
+        rf16 = Run(ctx_i, "f16", Af, Bf, True)
+        fl16 = gen.gen_flips(args.flips, Mi, Ni, "f16", gen.seed_for(4, 10))
+        for _ in range(20):
+            rf16.gemm(ab.ABFT_DETECT)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(50):
+            ab.abft_gemm(ctx_i, rf16.dA, rf16.dB, rf16.dC, rf16.code, ab.ABFT_DETECT, rf16.shape, rf16.result())
+        torch.cuda.synchronize()
+        ms16 = (time.perf_counter() - t0) * 1e3 / 50
+        camp_f16 = {"workload": f"fp16 {Mi}x{Ni}x{Ki} (ViT-B fc2, batch 32)", "protected_ms": ms16,
+                    "plain": campaign(ab.ABFT_DETECT, 1.0, ctx_i, rf16, fl16, "f16", ms16),
+                    "stored_sums": campaign(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS, 1e-2, ctx_i, rf16, fl16, "f16", ms16)}
         ab.abft_destroy(ctx_i)
-        del ri, Ci
+        del ri, Ci, rf16
         log(f"int8 campaign: {camp_int}")
+        log("fp16 campaign: " + str({k: (v if not isinstance(v, dict) else {x: v[x] for x in
+            ("injected", "detected", "localised", "restored", "strata_injected_detected")}) for k, v in camp_f16.items()}))
+        # the small configuration: int8 197 x 768 x 768 (one image), launch-latency-bound
+        g0 = gen.CONFIGS[0]["gemms"][0]
+        A0, B0 = gen.gen_operands("i8", g0["M"], g0["N"], g0["K"], gen.seed_for(0, 0), gen.seed_for(0, 1), trans_b=True)
+        ctx0 = ab.abft_create(max_rows=g0["M"], max_cols=g0["N"], max_depth=g0["K"], max_batch=1)
+        r0 = Run(ctx0, "i8", A0, B0, True)
+        t_small = {}
+        for nm, md in (("unprotected_us", ab.ABFT_OFF), ("protected_us", ab.ABFT_DETECT),
+                       ("protected_b_cached_us", ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)):
+            # eager calls are bound by the host here (a call takes longer to enqueue than to run);
+            # replaying 20 captured calls as a graph shows the time on the GPU
+            for _ in range(20):
+                ab.abft_gemm(ctx0, r0.dA, r0.dB, r0.dC, r0.code, md, r0.shape, None if md == ab.ABFT_OFF else r0.result())
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(100):
+                ab.abft_gemm(ctx0, r0.dA, r0.dB, r0.dC, r0.code, md, r0.shape, None if md == ab.ABFT_OFF else r0.result())
+            torch.cuda.synchronize()
+            t_small[nm.replace("_us", "_eager_us")] = (time.perf_counter() - t0) * 1e4
+            gr = torch.cuda.CUDAGraph()
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(gr, stream=side):
+                    for _ in range(20):
+                        ab.abft_gemm(ctx0, r0.dA, r0.dB, r0.dC, r0.code, md, r0.shape,
+                                     None if md == ab.ABFT_OFF else r0.result())
+            torch.cuda.current_stream().wait_stream(side)
+            for _ in range(3):
+                gr.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                gr.replay()
+            torch.cuda.synchronize()
+            t_small[nm] = (time.perf_counter() - t0) / 200 * 1e6
+            del gr
+        r0.gemm(ab.ABFT_DETECT)
+        C0 = r0.dC.clone()
+        det0 = loc0 = rest0 = 0
+        fl0 = gen.gen_flips(gen.CONFIGS[0]["flips"], g0["M"], g0["N"], "i8", gen.seed_for(0, 9))
+        for (_, i, j, bit) in fl0:
+            i, j, bit = int(i), int(j), int(bit)
+            r0.inject(0, i, j, bit)
+            r0.verify()
+            rf, cf = r0.flags()
+            det0 += int(rf.any() or cf.any())
+            loc0 += int(rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j])
+            r0.correct()
+            if torch.equal(r0.dC, C0) and r0.cnt()[2] == ab.ABFT_CLEAN:
+                rest0 += 1
+            else:
+                r0.dC.copy_(C0)
+        camp_small = dict(t_small, workload="int8 197x768x768 (ViT-B projection, one image), C int32",
+                          injected=len(fl0), detected=det0, localised=loc0, restored=rest0)
+        ab.abft_destroy(ctx0)
+        log(f"small configuration: {camp_small}")
 
     blocks = time_blocks() if (args.flips > 0 and not args.no_blocks) else None
 
@@ -414,6 +492,8 @@ def main():
             "single_step_spread": spread,
             "cold_cache": cold,
             "int8_flips": camp_int,
+            "fp16_flips": camp_f16,
+            "small_configuration": camp_small,
             "transformer_block": blocks,
             "calibrated_tau": None if camp_cal is None else dict(camp_cal, z=z_cal, mean=mean, std=std, max_clean_abs=float(max(st[2], st[6])),
                                    tau_calibrated=tau_used, tau_analytic=tau_analytic,
