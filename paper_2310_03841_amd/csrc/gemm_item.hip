@@ -5,21 +5,23 @@
 //
 // Per item: B is brought into LDS once and stays (as rows n of K-contiguous 128-byte slabs, the
 // layout the MFMA fragment reads want; a B stored K x N is transposed on the way in).  b = B e
-// and max|B| are taken from that copy.  A streams through a ring of LDS buffers in blocks of 32
-// or 64 rows, filled by direct-to-LDS loads that a fifth wave issues several blocks ahead.  That
-// wave does nothing else: the memory counter of a wave counts its loads and its stores in one
-// sequence, so a wave that stores C cannot wait for a load without also waiting for its stores
-// to be acknowledged; with the roles split the four computing waves never wait on memory at
-// all.  From each resident block come a = e^T A, the row prediction A b and max|A| (gemm_apass.h), from the accumulators
-// the observed row and column sums (before rounding; Sec. IV-C memory paragraph, Sec. V
-// "Optimizations" (2)), and C leaves through a wave-private LDS stage as row-contiguous
+// and max|B| are taken from that copy (for a B stored K x N: from the registers of the
+// transposing load).  A streams through a ring of LDS buffers in blocks of 32 or 64 rows, filled
+// by direct-to-LDS loads that a fifth wave issues several blocks ahead.  That wave does nothing
+// else: the memory counter of a wave counts its loads and its stores in one sequence, so a wave
+// that stores C cannot wait for a load without also waiting for its stores to be acknowledged;
+// with the roles split the four computing waves never wait on memory at all.  (Where all of A
+// fits in LDS it is fetched at the start of the item and the fifth wave is left out.)  From each
+// resident block come its share of a = e^T A, the row prediction A b and max|A|, from the
+// accumulators the observed row and column sums (before rounding; Sec. IV-C memory paragraph,
+// Sec. V "Optimizations" (2)), and C leaves through a wave-private LDS stage as row-contiguous
 // segments.  When the last block is done the column prediction a B is formed from the resident
 // B, both pairs are compared (equality for int8, tolerance for floating point; Sec. III-B.1
 // item (2)), and the vectors, flags and counts are written.
 //
 // These products are bound by memory traffic (about 39 flop per byte at 197 x 197 x 64), so the
-// design goal is streaming: few dependent round trips per item, whole-line stores, and nothing
-// read twice from memory.
+// design goal is streaming: few dependent round trips per item, row segments that the L2 can
+// merge into whole lines, and nothing read twice from memory.
 #include "abft_device.h"
 #include "gemm_args.h"
 #include "gemm_apass.h"
@@ -78,7 +80,7 @@ struct ItemArgs {
     int ksteps;                                   // MFMA steps over K (32 bytes of K per row each)
     int NB;                                       // blocks of 32 columns
     int nrb;                                      // blocks of rows
-    int stages;                                   // LDS buffers of the ring A streams through (2..8)
+    int stages;                                   // LDS buffers for blocks of A: a ring of 2..8, or one per block (nrb)
     int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
     int mul24_ok;
     int b16_ok;                                   // int8: |b| < 2^15 (N <= 255): the row dots take 16-bit pairs
@@ -111,10 +113,11 @@ __host__ __device__ inline size_t item_lds_bytes(int dt, int wm, int stages, int
     return b;
 }
 
-// Depth of the ring (a depth of all the item's row blocks means A is resident as a whole and the
-// computing waves run through the blocks without meeting): as deep as half the LDS of a compute unit allows (two workgroups per
-// unit), else as deep as the whole allows; the loading wave waits with an immediate count, so
-// (stages - 2) blocks' worth of load instructions must stay below 64.  0: does not fit.
+// Depth of the ring.  A depth of all the item's row blocks means A is resident as a whole and
+// the computing waves run through the blocks without meeting.  Otherwise: as deep as half the
+// LDS of a compute unit allows (two workgroups per unit), else as deep as the whole allows; the
+// loading wave waits with an immediate count, so (stages - 2) blocks' worth of load
+// instructions must stay below 64.  0: does not fit.
 __host__ inline int item_stages(int dt, int wm, int M, int N, int K, bool sto)
 {
     const int es = elem_size(dt);
