@@ -23,7 +23,6 @@ template <int DT, int BM, int BN, bool PROT, bool TRANSB>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 {
     using T = Traits<DT>;
-    typedef typename T::acc_t acc_t;
     typedef typename T::accv_t accv_t;
     constexpr int ES = T::ES;
     constexpr int CE = 16 / ES;                  // elements per 16-byte chunk
