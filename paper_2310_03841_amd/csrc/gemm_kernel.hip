@@ -80,7 +80,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) nact[ni] = (n0 + wn * TN + ni * 32) < N;
 
-    i32x4 areg[PA], breg[PB];
+    // Two register sets: the slab after next is already on its way from memory while the next
+    // one is written to LDS (small problems are a chain of memory latencies otherwise).
+    struct SlabRegs { i32x4 a[PA], b[PB], bnn[PB]; };
+    SlabRegs R0, R1;
     const int nslab = (K + KE - 1) / KE;
     const bool ragged_k = (K % KE) != 0;
 
@@ -106,8 +109,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     };
     // B stored K x N: chunks run along n; they are transposed while written to LDS.
     constexpr int NCH = BN / CE;
-    i32x4 bnn[PB];
-    auto load_b_nn = [&](int k0) {
+    auto load_b_nn = [&](int k0, i32x4 *bnn) {
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
             int q = tid + 256 * p;
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
             bnn[p] = v;
         }
     };
-    auto store_b_nn = [&](uint8_t *dst) {
+    auto store_b_nn = [&](uint8_t *dst, const i32x4 *bnn) {
 #pragma unroll
         for (int p = 0; p < PB; ++p) {
             int q = tid + 256 * p;
@@ -141,26 +143,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
         }
     };
 
-    auto load_slab = [&](int s) {
+    auto load_slab = [&](int s, SlabRegs &R) __attribute__((always_inline)) {
+        if (s >= nslab) return;
         const int k0 = s * KE;
         const bool tail = ragged_k && (s == nslab - 1);
-        load_rowmajor(asrc, areg, PA, k0, tail);
+        load_rowmajor(asrc, R.a, PA, k0, tail);
         if (TRANSB) {
-            load_rowmajor(bsrc, breg, PB, k0, tail);
+            load_rowmajor(bsrc, R.b, PB, k0, tail);
         } else {
-            load_b_nn(k0);
-            if (tile_has_btail) load_rowmajor(bsrc, breg, PB, k0, tail);
+            load_b_nn(k0, R.bnn);
+            if (tile_has_btail) load_rowmajor(bsrc, R.b, PB, k0, tail);
         }
     };
-    auto store_slab = [&](int buf) {
-        uint8_t *sA = smem + buf * BUF;
+    auto store_slab = [&](int s, const SlabRegs &R) __attribute__((always_inline)) {
+        if (s >= nslab) return;
+        uint8_t *sA = smem + (s & 1) * BUF;
         uint8_t *sB = sA + BM * SLAB_BYTES;
-        store_rowmajor(sA, areg, PA, nullptr);
+        store_rowmajor(sA, R.a, PA, nullptr);
         if (TRANSB) {
-            store_rowmajor(sB, breg, PB, nullptr);
+            store_rowmajor(sB, R.b, PB, nullptr);
         } else {
-            store_b_nn(sB);
-            if (tile_has_btail) store_rowmajor(sB, breg, PB, btail);
+            store_b_nn(sB, R.bnn);
+            if (tile_has_btail) store_rowmajor(sB, R.b, PB, btail);
         }
     };
     auto compute = [&](int buf) {
@@ -203,12 +207,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
         }
     }
 
-    // ---- main loop: global -> registers -> LDS, two LDS buffers, one barrier per slab
-    load_slab(0);
-    store_slab(0);
-    __syncthreads();
-    for (int s = 0; s < nslab; ++s) {
-        if (s + 1 < nslab) load_slab(s + 1);
+    // ---- main loop: global -> registers -> LDS, two LDS buffers, one barrier per slab.  While
+    // slab s is multiplied, slab s + 1 goes from its register set to the other LDS buffer and the
+    // loads of slab s + 3 are issued into the set that has just been emptied (slab s + 2 is in
+    // flight in the other set).
+    auto one_slab = [&](int s, SlabRegs &Rnext, SlabRegs & /*Rafter*/) __attribute__((always_inline)) {
         if (PROT && s == next_own) {
             a_pass<DT, BM>(smem + (s & 1) * BUF, b_lds + ep.owned * KE, BM, col_lds + ep.owned * KE, ep.st,
                            g.mul24_ok != 0);
@@ -216,8 +219,18 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
             ep.owned += 1;
         }
         compute(s & 1);
-        if (s + 1 < nslab) store_slab((s + 1) & 1);
+        store_slab(s + 1, Rnext);
+        load_slab(s + 3, Rnext);
         __syncthreads();
+    };
+    load_slab(0, R0);
+    load_slab(1, R1);
+    store_slab(0, R0);
+    load_slab(2, R0);
+    __syncthreads();
+    for (int s = 0; s < nslab; s += 2) {
+        one_slab(s, R1, R0);
+        if (s + 1 < nslab) one_slab(s + 1, R0, R1);
     }
 
     // ---- epilogue
