@@ -45,8 +45,10 @@ def main():
     ap.add_argument("--flips", type=int, default=1000,
                     help="stored-C flips of the bf16 campaigns on the benchmark workload; 0 also skips "
                          "every other extra (kernel-profile runs)")
-    ap.add_argument("--int-flips", type=int, default=10000,
+    ap.add_argument("--int-flips", type=int, default=100000,
                     help="stored-C flips of the int8 campaign (ViT-B fc2 at batch 32); 0 skips it")
+    ap.add_argument("--f16-flips", type=int, default=100000,
+                    help="stored-C flips of the fp16 campaigns on the same GEMM (skipped with the int8 one)")
     ap.add_argument("--no-blocks", action="store_true", help="skip the per-class timing of the transformer blocks")
     ap.add_argument("--only-blocks", action="store_true",
                     help="kernel-profile runs of the transformer-block GEMMs: time them, print them, exit")
@@ -263,7 +265,9 @@ def main():
         borderline = 0                                               # tol / 2 < |delta| <= 2 tol
         detected = localised = restored = 0
         t_corr = t_corr_gpu = 0.0
-        for (_, i, j, bit) in flips:
+        for n, (_, i, j, bit) in enumerate(flips):
+            if n and n % 20000 == 0:
+                log(f"  campaign: {n} of {len(flips)} flips, {detected} detected")
             i, j, bit = int(i), int(j), int(bit)
             old = fp_val(int(C_host[i, j]), dtype)
             new = fp_val(int(C_host[i, j]) ^ (1 << bit), dtype)
@@ -348,6 +352,8 @@ def main():
         t_ver = 0.0
         fl = gen.gen_flips(args.int_flips, Mi, Ni, "i8", gen.seed_for(4, 9))
         for n, (_, i, j, bit) in enumerate(fl):
+            if n and n % 20000 == 0:
+                log(f"  int8 campaign: {n} of {len(fl)} flips, {det} detected")
             i, j, bit = int(i), int(j), int(bit)
             ri.inject(0, i, j, bit)
             torch.cuda.synchronize()
@@ -384,7 +390,7 @@ def main():
         # the same GEMM in fp16 (exponent bits 10..14 or mantissa bits 0..9, half and half)
         Af, Bf = gen.gen_operands("f16", Mi, Ni, Ki, gen.seed_for(4, 2), gen.seed_for(4, 3), trans_b=True)
         rf16 = Run(ctx_i, "f16", Af, Bf, True)
-        fl16 = gen.gen_flips(args.flips, Mi, Ni, "f16", gen.seed_for(4, 10))
+        fl16 = gen.gen_flips(args.f16_flips, Mi, Ni, "f16", gen.seed_for(4, 10))
         for _ in range(20):
             rf16.gemm(ab.ABFT_DETECT)
         torch.cuda.synchronize()
