@@ -33,6 +33,7 @@ struct abft_ctx {
     int last_hip;
     // what the context currently holds
     bool b_valid, pred_valid, sto_valid, vobs_valid;
+    bool list_dirty;        // the tile list's counters may be non-zero (a correction failed half way)
     int b_dt, pred_dt;
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
@@ -388,7 +389,10 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words, st);
         carve(ctx, dtype, sh, &w);
-        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, rp.stale, rp.other, rp.other_words, st));
+        const bool clear_list = ctx->list_dirty;
+        ctx->list_dirty = true;
+        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, rp.stale, rp.other, rp.other_words, st));
+        ctx->list_dirty = false;
         end_resum(ctx, words);
         ctx->vobs_valid = true;
     }
@@ -437,7 +441,10 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     const ResumPlan rp = begin_resum(ctx, words, st);
     Workspace w;
     carve(ctx, dtype, sh, &w);
-    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, rp.stale, rp.other, rp.other_words, st));
+    const bool clear_list = ctx->list_dirty;
+    ctx->list_dirty = true;
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, rp.stale, rp.other, rp.other_words, st));
+    ctx->list_dirty = false;
     end_resum(ctx, words);
     ctx->vobs_valid = true;
     return ABFT_OK;

@@ -200,7 +200,7 @@ struct CmpArgs {
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
-    const uint32_t *fix_count;   // non-null after a correction: [0] tiles listed, [1] overflow
+    uint32_t *fix_count;  // non-null after a correction: [0] tiles listed, [1] overflow (cleared after use)
     const uint32_t *cc_sto, *rc_sto;   // non-null: stored-side sums of the GEMM (floating point)
     uint32_t *zero_ptr;   // region every block helps to clear: the re-summing region not in use,
     size_t zero_words;    // so that the next re-sum finds it clean
@@ -236,8 +236,14 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     const unsigned nr = __syncthreads_count(frow);
     const unsigned nc = __syncthreads_count(fcol);
     if (tid == 0) {
-        if (nr) atomicAdd(a.ticket + 1, nr);
-        if (nc) atomicAdd(a.ticket + 2, nc);
+        if (nr | nc) {
+            // rare: the counts must be at the coherence point before this block's ticket is, so
+            // fetch their old values and wait for them
+            unsigned o1 = 0, o2 = 0;
+            if (nr) o1 = atomicAdd(a.ticket + 1, nr);
+            if (nc) o2 = atomicAdd(a.ticket + 2, nc);
+            asm volatile("s_waitcnt vmcnt(0)" :: "v"(o1), "v"(o2) : "memory");
+        }
         unsigned total = gridDim.x * gridDim.z;
         unsigned t = atomicAdd(a.ticket, 1u);
         is_last = (t == total - 1);
@@ -250,8 +256,9 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         a.counts[0] = r;
         a.counts[1] = c;
         if (a.fix_count) {
-            const uint32_t tiles = a.fix_count[0];
-            a.counts[2] = a.fix_count[1] ? 3u : status_of(r, c);
+            // the list is consumed: the next correction starts from an empty one
+            const uint32_t tiles = atomicExch(a.fix_count, 0u);
+            a.counts[2] = atomicExch(a.fix_count + 1, 0u) ? 3u : status_of(r, c);
             a.counts[3] = tiles > (uint32_t)MAX_FIX_TILES ? (uint32_t)MAX_FIX_TILES : tiles;
             a.counts[4] = before;
         } else {
@@ -713,23 +720,51 @@ struct LocArgs {
     uint32_t *fix_count;
 };
 
-__global__ __launch_bounds__(256) void locate_kernel(LocArgs a)
+constexpr int LOC_THREADS = 1024;
+
+// Appends the CT-tile index of every non-zero byte of flag[0..n) to list (at most MAX_LIST kept;
+// *count keeps counting).  Sixteen flags per load where the address allows: flags are almost
+// all zero, and the scan is bound by the latency of its loads.
+__device__ inline void list_flagged(const uint8_t *flag, int n, int *list, int *count, int tid)
+{
+    auto note = [&](int i) {
+        int p = atomicAdd(count, 1);
+        if (p < MAX_LIST) list[p] = i / CT;
+    };
+    const int head = min(n, (int)((16u - (unsigned)((uintptr_t)flag & 15u)) & 15u));
+    const int nchunk = (n - head) / 16;
+    const int tail0 = head + nchunk * 16;
+    if (tid < head && flag[tid]) note(tid);
+    if (tid < n - tail0 && flag[tail0 + tid]) note(tail0 + tid);
+    const i32x4 *body = reinterpret_cast<const i32x4 *>(flag + head);
+    for (int c0 = 0; c0 < nchunk; c0 += 4 * LOC_THREADS) {
+        i32x4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * LOC_THREADS + tid;
+            v[u] = i32x4{0, 0, 0, 0};
+            if (c < nchunk) v[u] = body[c];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((v[u][0] | v[u][1] | v[u][2] | v[u][3]) == 0) continue;
+            const int c = c0 + u * LOC_THREADS + tid;
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                if (((unsigned)v[u][q >> 2] >> (8 * (q & 3))) & 0xFFu) note(head + c * 16 + q);
+        }
+    }
+}
+
+__global__ __launch_bounds__(LOC_THREADS) void locate_kernel(LocArgs a)
 {
     __shared__ int rows[MAX_LIST], cols[MAX_LIST];
     __shared__ int nr, nc;
     const int bz = blockIdx.x, tid = threadIdx.x;
     if (tid == 0) { nr = 0; nc = 0; }
     __syncthreads();
-    for (int i = tid; i < a.M; i += 256)
-        if (a.row_flag[(long)bz * a.M + i]) {
-            int p = atomicAdd(&nr, 1);
-            if (p < MAX_LIST) rows[p] = i / CT;
-        }
-    for (int j = tid; j < a.N; j += 256)
-        if (a.col_flag[(long)bz * a.N + j]) {
-            int p = atomicAdd(&nc, 1);
-            if (p < MAX_LIST) cols[p] = j / CT;
-        }
+    list_flagged(a.row_flag + (long)bz * a.M, a.M, rows, &nr, tid);
+    list_flagged(a.col_flag + (long)bz * a.N, a.N, cols, &nc, tid);
     __syncthreads();
     if (tid != 0) return;
     if (nr == 0 || nc == 0) return;                     // clean, or one-sided: nothing to recompute
@@ -759,8 +794,16 @@ __global__ __launch_bounds__(256) void locate_kernel(LocArgs a)
     if (overflow) atomicExch(a.fix_count + 1, 1u);
 }
 
-// Step 2: one wave recomputes one CT x CT tile of C over the whole K, with the same MFMA
-// instruction and the same ascending-k order as the GEMM kernel.
+// Step 2: one workgroup recomputes one CT x CT tile of C over the whole K.  Its first wave issues
+// every MFMA, the same instruction in the same ascending-k order as the GEMM kernel, so a
+// floating-point tile comes back with the bits the GEMM produced.  What bounds the step is the
+// latency of the operand loads (a wave keeps 2 * FIX_UB 16-byte loads per lane in flight), so all
+// FIX_WAVES waves load, each a different run of FIX_UB k-steps, and hand the operands to the
+// first wave through LDS, in the lane layout they are consumed in.
+constexpr int FIX_WAVES = 8;                    // waves that load
+constexpr int FIX_UB = 8;                       // k-steps a wave loads per group
+constexpr size_t FIX_LDS_BYTES = (size_t)FIX_WAVES * FIX_UB * 2 * 64 * 16;
+
 struct FixArgs {
     const uint8_t *A, *B;
     uint8_t *C;
@@ -771,17 +814,20 @@ struct FixArgs {
 };
 
 template <int DT>
-__global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
+__global__ __launch_bounds__(64 * FIX_WAVES) void recompute_kernel(FixArgs a)
 {
     using T = Traits<DT>;
     typedef typename T::accv_t accv_t;
     constexpr int ES = T::ES, CE = 16 / ES;
+    constexpr int UB = FIX_UB;
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    i32x4 *stage = reinterpret_cast<i32x4 *>(lds);          // [FIX_WAVES * UB k-steps][A, B][64 lanes]
     unsigned n = a.fix_count[0];
     if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
-    if (blockIdx.x >= n) return;
+    if (blockIdx.x >= n) return;                            // the whole workgroup leaves
     const int bz = a.fix_tiles[3 * blockIdx.x], tr = a.fix_tiles[3 * blockIdx.x + 1],
               tc = a.fix_tiles[3 * blockIdx.x + 2];
-    const int lane = threadIdx.x, l32 = lane & 31, lh = lane >> 5;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
     const int row = tr * CT + l32, col = tc * CT + l32;
     const uint8_t *Ab = a.A + (long)bz * a.sA * ES, *Bb = a.B + (long)bz * a.sB * ES;
     const int K = a.K;
@@ -789,7 +835,6 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = T::zero();
     const int steps = (K + 2 * CE - 1) / (2 * CE);
-    constexpr int UB = 8;                       // k-steps whose operands are in flight together
     auto load_a = [&](int ks) __attribute__((always_inline)) -> i32x4 {
         const int kb = ks * 2 * CE + lh * CE;
         i32x4 av = {0, 0, 0, 0};
@@ -827,14 +872,36 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
         }
         return bv;
     };
-    for (int ks0 = 0; ks0 < steps; ks0 += UB) {
+    // every wave takes the same number of trips: the barriers are reached by all
+    for (int g0 = 0; g0 < steps; g0 += FIX_WAVES * UB) {
+        const int ks0 = g0 + wave * UB;
         i32x4 av[UB], bv[UB];
 #pragma unroll
         for (int u = 0; u < UB; ++u) { av[u] = load_a(ks0 + u); bv[u] = load_b(ks0 + u); }
+        __syncthreads();                                    // the first wave is done with the previous group
 #pragma unroll
-        for (int u = 0; u < UB; ++u)
-            if (ks0 + u < steps) acc = T::mfma(bv[u], av[u], acc);   // B first: lane = row of C, registers = columns
+        for (int u = 0; u < UB; ++u) {
+            stage[((wave * UB + u) * 2 + 0) * 64 + lane] = av[u];
+            stage[((wave * UB + u) * 2 + 1) * 64 + lane] = bv[u];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // whole runs of UB k-steps (a run's k-steps past the end of K hold zeros and add nothing);
+            // a run's operands are read together, ahead of its chain of dependent MFMAs
+            const int nrun = min(FIX_WAVES, (steps - g0 + UB - 1) / UB);
+            for (int w2 = 0; w2 < nrun; ++w2) {
+                i32x4 x[UB], y[UB];
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    x[u] = stage[((w2 * UB + u) * 2 + 0) * 64 + lane];
+                    y[u] = stage[((w2 * UB + u) * 2 + 1) * 64 + lane];
+                }
+#pragma unroll
+                for (int u = 0; u < UB; ++u) acc = T::mfma(y[u], x[u], acc);   // B first: lane = row of C, registers = columns
+            }
+        }
     }
+    if (wave != 0) return;
     uint8_t *Cb = a.C + (long)bz * a.sC * T::OS;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -843,16 +910,31 @@ __global__ __launch_bounds__(64) void recompute_kernel(FixArgs a)
     }
 }
 
+template <int DT>
+static hipError_t launch_recompute(const FixArgs &f, hipStream_t st)
+{
+    auto kern = recompute_kernel<DT>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)FIX_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(MAX_FIX_TILES), dim3(64 * FIX_WAVES), FIX_LDS_BYTES, st, f);
+    return hipGetLastError();
+}
+
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, bool with_sto, size_t stale_words,
+                          const Workspace &w, const Verdict &v, bool with_sto, bool clear_list, size_t stale_words,
                           uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
 {
-    hipError_t e = launch_zero(w.fix_count, 2, st);
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (clear_list && (e = launch_zero(w.fix_count, 2, st)) != hipSuccess) return e;
     LocArgs l;
     l.row_flag = v.row_flag; l.col_flag = v.col_flag; l.M = s.M; l.N = s.N;
     l.fix_tiles = w.fix_tiles; l.fix_count = w.fix_count;
-    hipLaunchKernelGGL(locate_kernel, dim3((unsigned)s.batch), dim3(256), 0, st, l);
+    hipLaunchKernelGGL(locate_kernel, dim3((unsigned)s.batch), dim3(LOC_THREADS), 0, st, l);
     if ((e = hipGetLastError()) != hipSuccess) return e;
 
     FixArgs f;
@@ -861,12 +943,12 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     f.lda = s.lda; f.ldb = s.ldb; f.ldc = s.ldc; f.sA = s.sA; f.sB = s.sB; f.sC = s.sC;
     f.fix_tiles = w.fix_tiles; f.fix_count = w.fix_count;
     switch (dt) {
-    case DT_I8:   hipLaunchKernelGGL(recompute_kernel<DT_I8>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
-    case DT_BF16: hipLaunchKernelGGL(recompute_kernel<DT_BF16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
-    case DT_F16:  hipLaunchKernelGGL(recompute_kernel<DT_F16>, dim3(MAX_FIX_TILES), dim3(64), 0, st, f); break;
+    case DT_I8:   e = launch_recompute<DT_I8>(f, st); break;
+    case DT_BF16: e = launch_recompute<DT_BF16>(f, st); break;
+    case DT_F16:  e = launch_recompute<DT_F16>(f, st); break;
     default: return hipErrorInvalidValue;
     }
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (e != hipSuccess) return e;
     // re-check: the stored C is re-summed as a whole (a streaming pass at HBM speed is cheaper
     // than strided column walks over the touched tiles) and compared with the predictions
     if (stale_words && (e = launch_zero(w.cc_vobs, stale_words, st)) != hipSuccess) return e;
