@@ -182,9 +182,12 @@ int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape
 
 /* Replay at tile granularity (Sec. III-B.3): recomputes every 32x32 tile of C that holds a
  * (flagged row, flagged column) pair from A and B (same MFMA and k order as abft_gemm, so the
- * repaired elements are bit-identical to an undisturbed run), then re-sums the stored C as
- * abft_verify does and rewrites flags and counts (counts[3] = tiles recomputed, counts[4] =
- * status before).  At most 256 tiles per call; beyond that status = ABFT_TOO_MANY and the
+ * repaired elements are bit-identical to an undisturbed run), then checks again and rewrites
+ * flags and counts (counts[3] = tiles recomputed, counts[4] = status before).  The second check:
+ * when the context holds the sums of this stored C (the last call on it was abft_verify,
+ * abft_correct or abft_correct_checksum, and C has not been written since), only the rows and the
+ * columns of the recomputed tiles are summed again; otherwise the whole stored C is, as
+ * abft_verify does.  At most 256 tiles per call; beyond that status = ABFT_TOO_MANY and the
  * caller replays the GEMM.  A and B must be unchanged since abft_gemm. */
 int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype,
                  const abft_shape *s, const abft_result *r, void *stream);

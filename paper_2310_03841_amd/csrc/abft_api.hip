@@ -391,7 +391,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         carve(ctx, dtype, sh, &w);
         const bool clear_list = ctx->list_dirty;
         ctx->list_dirty = true;
-        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, rp.stale, rp.other, rp.other_words, st));
+        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, false, rp.stale, rp.other, rp.other_words, st));
         ctx->list_dirty = false;
         end_resum(ctx, words);
         ctx->vobs_valid = true;
@@ -437,13 +437,25 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     if (rc) return rc;
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
     hipStream_t st = (hipStream_t)stream;
+    const bool clear_list = ctx->list_dirty;
+    Workspace w;
+    if (ctx->vobs_valid) {
+        // abft_verify (or an earlier correction) left the sums of this stored C: they are brought up
+        // to date in place, for the rows and columns of the recomputed tiles only
+        carve(ctx, dtype, sh, &w);
+        ctx->list_dirty = true;
+        ctx->vobs_valid = false;
+        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, true, 0, nullptr, 0, st));
+        ctx->list_dirty = false;
+        ctx->vobs_valid = true;
+        return ABFT_OK;
+    }
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
     const ResumPlan rp = begin_resum(ctx, words, st);
-    Workspace w;
     carve(ctx, dtype, sh, &w);
-    const bool clear_list = ctx->list_dirty;
     ctx->list_dirty = true;
-    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, rp.stale, rp.other, rp.other_words, st));
+    HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, false, rp.stale, rp.other,
+                           rp.other_words, st));
     ctx->list_dirty = false;
     end_resum(ctx, words);
     ctx->vobs_valid = true;

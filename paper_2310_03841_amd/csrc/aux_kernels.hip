@@ -797,10 +797,11 @@ __global__ __launch_bounds__(LOC_THREADS) void locate_kernel(LocArgs a)
 // Step 2: one workgroup recomputes one CT x CT tile of C over the whole K.  Its first wave issues
 // every MFMA, the same instruction in the same ascending-k order as the GEMM kernel, so a
 // floating-point tile comes back with the bits the GEMM produced.  What bounds the step is the
-// latency of the operand loads (a wave keeps 2 * FIX_UB 16-byte loads per lane in flight), so all
-// FIX_WAVES waves load, each a different run of FIX_UB k-steps, and hand the operands to the
-// first wave through LDS, in the lane layout they are consumed in.
-constexpr int FIX_WAVES = 8;                    // waves that load
+// latency of the operand loads (a wave keeps 2 * FIX_UB 16-byte loads per lane in flight), so
+// FIX_WAVES further waves load, each a different run of FIX_UB k-steps, and hand the operands to
+// the first wave through LDS, in the lane layout they are consumed in; while it works through one
+// group of runs the loads of the next group are in flight.
+constexpr int FIX_WAVES = 8;                    // waves that load (the workgroup has one more)
 constexpr int FIX_UB = 8;                       // k-steps a wave loads per group
 constexpr size_t FIX_LDS_BYTES = (size_t)FIX_WAVES * FIX_UB * 2 * 64 * 16;
 
@@ -811,10 +812,12 @@ struct FixArgs {
     long lda, ldb, ldc, sA, sB, sC;
     const int32_t *fix_tiles;
     const uint32_t *fix_count;
+    uint32_t *cc_vobs;      // non-null: the re-summed column sums of the tile's columns are cleared (they are
+                            // accumulated again by resum_touched_kernel)
 };
 
 template <int DT>
-__global__ __launch_bounds__(64 * FIX_WAVES) void recompute_kernel(FixArgs a)
+__global__ __launch_bounds__(64 * (FIX_WAVES + 1)) void recompute_kernel(FixArgs a)
 {
     using T = Traits<DT>;
     typedef typename T::accv_t accv_t;
@@ -831,6 +834,7 @@ __global__ __launch_bounds__(64 * FIX_WAVES) void recompute_kernel(FixArgs a)
     const int row = tr * CT + l32, col = tc * CT + l32;
     const uint8_t *Ab = a.A + (long)bz * a.sA * ES, *Bb = a.B + (long)bz * a.sB * ES;
     const int K = a.K;
+    if (a.cc_vobs && wave == 1 && lane < CT && col < a.N) a.cc_vobs[(long)bz * a.N + col] = 0u;
     accv_t acc;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = T::zero();
@@ -874,30 +878,44 @@ __global__ __launch_bounds__(64 * FIX_WAVES) void recompute_kernel(FixArgs a)
     };
     // every wave takes the same number of trips: the barriers are reached by all
     for (int g0 = 0; g0 < steps; g0 += FIX_WAVES * UB) {
-        const int ks0 = g0 + wave * UB;
+        const int lw = wave - 1;                            // loading wave 0 .. FIX_WAVES - 1
+        const int ks0 = g0 + lw * UB;
         i32x4 av[UB], bv[UB];
+        if (wave != 0) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) { av[u] = load_a(ks0 + u); bv[u] = load_b(ks0 + u); }
+            for (int u = 0; u < UB; ++u) { av[u] = load_a(ks0 + u); bv[u] = load_b(ks0 + u); }
+        }
         __syncthreads();                                    // the first wave is done with the previous group
+        if (wave != 0) {
 #pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            stage[((wave * UB + u) * 2 + 0) * 64 + lane] = av[u];
-            stage[((wave * UB + u) * 2 + 1) * 64 + lane] = bv[u];
+            for (int u = 0; u < UB; ++u) {
+                stage[((lw * UB + u) * 2 + 0) * 64 + lane] = av[u];
+                stage[((lw * UB + u) * 2 + 1) * 64 + lane] = bv[u];
+            }
         }
         __syncthreads();
         if (wave == 0) {
             // whole runs of UB k-steps (a run's k-steps past the end of K hold zeros and add nothing);
-            // a run's operands are read together, ahead of its chain of dependent MFMAs
+            // the operands of the next run are read while the chain of dependent MFMAs of this one runs
             const int nrun = min(FIX_WAVES, (steps - g0 + UB - 1) / UB);
-            for (int w2 = 0; w2 < nrun; ++w2) {
-                i32x4 x[UB], y[UB];
+            auto read_run = [&](int r, i32x4 (&x)[UB], i32x4 (&y)[UB]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int u = 0; u < UB; ++u) {
-                    x[u] = stage[((w2 * UB + u) * 2 + 0) * 64 + lane];
-                    y[u] = stage[((w2 * UB + u) * 2 + 1) * 64 + lane];
+                    x[u] = stage[((r * UB + u) * 2 + 0) * 64 + lane];
+                    y[u] = stage[((r * UB + u) * 2 + 1) * 64 + lane];
                 }
+            };
+            i32x4 x0[UB], y0[UB], x1[UB], y1[UB];
+            read_run(0, x0, y0);
+            for (int r = 0; r < nrun; r += 2) {
+                read_run(min(r + 1, FIX_WAVES - 1), x1, y1);
 #pragma unroll
-                for (int u = 0; u < UB; ++u) acc = T::mfma(y[u], x[u], acc);   // B first: lane = row of C, registers = columns
+                for (int u = 0; u < UB; ++u) acc = T::mfma(y0[u], x0[u], acc);   // B first: lane = row of C, registers = columns
+                if (r + 1 < nrun) {
+                    read_run(min(r + 2, FIX_WAVES - 1), x0, y0);
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) acc = T::mfma(y1[u], x1[u], acc);
+                }
             }
         }
     }
@@ -907,6 +925,103 @@ __global__ __launch_bounds__(64 * FIX_WAVES) void recompute_kernel(FixArgs a)
     for (int i = 0; i < 16; ++i) {
         const int gc = tc * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
         if (row < a.M && gc < a.N) T::store_c(Cb, (long)row * a.ldc + gc, acc[i]);
+    }
+}
+
+// Step 3 when the sums of the stored C are at hand (abft_verify ran on this C): only the rows and
+// the columns of the recomputed tiles changed, so only their sums are formed again.  Workgroup
+// (t, p) serves listed tile t: p < CT sums row p of the tile over all N and stores it; every p sums
+// the tile's CT columns over its share of the M rows and adds that to the column sums, which
+// recompute_kernel has cleared.  A tile row or tile column listed more than once is summed by
+// its first tile only.
+constexpr int TOUCH_PARTS = 64;
+
+struct TouchArgs {
+    const uint8_t *C;
+    long ldc, sC;
+    int M, N;
+    const int32_t *fix_tiles;
+    const uint32_t *fix_count;
+    uint32_t *cc_vobs, *rc_vobs;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void resum_touched_kernel(TouchArgs a)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int OS = T::OS, CE = 16 / OS;
+    constexpr int CPR = CT / CE;                            // 16-byte chunks across a tile
+    constexpr int RL = 256 / CPR;                           // rows a pass of the workgroup covers
+    __shared__ acc_t red[256 * CE];
+    unsigned n = a.fix_count[0];
+    if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
+    if (blockIdx.x >= n) return;
+    const int t = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
+    const int bz = a.fix_tiles[3 * t], tr = a.fix_tiles[3 * t + 1], tc = a.fix_tiles[3 * t + 2];
+    bool first_row = true, first_col = true;
+    for (int q = 0; q < t; ++q)
+        if (a.fix_tiles[3 * q] == bz) {
+            first_row = first_row && a.fix_tiles[3 * q + 1] != tr;
+            first_col = first_col && a.fix_tiles[3 * q + 2] != tc;
+        }
+    const uint8_t *Cb = a.C + (long)bz * a.sC * OS;
+    const int M = a.M, N = a.N;
+
+    const int row = tr * CT + part;
+    if (first_row && part < CT && row < M) {
+        acc_t s = T::zero();
+        const int nch = (N + CE - 1) / CE;
+        for (int c = tid; c < nch; c += 256) {
+            const i32x4 v = *reinterpret_cast<const i32x4 *>(Cb + ((long)row * a.ldc + (long)c * CE) * OS);
+            const int nvalid = N - c * CE;
+#pragma unroll
+            for (int q = 0; q < CE; ++q)
+                if (q < nvalid) s = add_t(s, out_elem<DT>(v, q));
+        }
+        s = wave_sum(s);
+        if ((tid & 63) == 0) red[tid >> 6] = s;
+        __syncthreads();
+        if (tid == 0) a.rc_vobs[(long)bz * M + row] = as_word(add_t(add_t(red[0], red[1]), add_t(red[2], red[3])));
+        __syncthreads();                                    // red is used again below
+    }
+    if (!first_col) return;
+
+    const int mc = (M + TOUCH_PARTS - 1) / TOUCH_PARTS;
+    const int rbeg = part * mc, rend = min(rbeg + mc, M);
+    const int cx = tid % CPR, ry = tid / CPR;
+    const int col0 = tc * CT + cx * CE;
+    const int nvalid = N - col0;
+    acc_t colacc[CE];
+#pragma unroll
+    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
+    for (int r0 = rbeg + ry; r0 < rend; r0 += RL * ENC_UNROLL) {
+        i32x4 v[ENC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            const int r = r0 + u * RL;
+            v[u] = i32x4{0, 0, 0, 0};
+            if (nvalid > 0 && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
+        }
+#pragma unroll
+        for (int u = 0; u < ENC_UNROLL; ++u) {
+            if (r0 + u * RL < rend) {
+#pragma unroll
+                for (int q = 0; q < CE; ++q)
+                    if (q < nvalid) colacc[q] = add_t(colacc[q], out_elem<DT>(v[u], q));
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < CE; ++q) red[ry * CT + cx * CE + q] = colacc[q];
+    __syncthreads();
+    if (tid < CT) {
+        const int col = tc * CT + tid;
+        if (col < N && rbeg < rend) {
+            acc_t s = red[tid];
+            for (int y = 1; y < RL; ++y) s = add_t(s, red[y * CT + tid]);
+            atomic_add_word(a.cc_vobs + (long)bz * N + col, s);
+        }
     }
 }
 
@@ -921,13 +1036,13 @@ static hipError_t launch_recompute(const FixArgs &f, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(MAX_FIX_TILES), dim3(64 * FIX_WAVES), FIX_LDS_BYTES, st, f);
+    hipLaunchKernelGGL(kern, dim3(MAX_FIX_TILES), dim3(64 * (FIX_WAVES + 1)), FIX_LDS_BYTES, st, f);
     return hipGetLastError();
 }
 
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
-                          const Workspace &w, const Verdict &v, bool with_sto, bool clear_list, size_t stale_words,
-                          uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
+                          const Workspace &w, const Verdict &v, bool with_sto, bool clear_list, bool targeted,
+                          size_t stale_words, uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
 {
     hipError_t e = hipSuccess;
     if (clear_list && (e = launch_zero(w.fix_count, 2, st)) != hipSuccess) return e;
@@ -942,6 +1057,7 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     f.M = s.M; f.N = s.N; f.K = s.K; f.transB = s.transB;
     f.lda = s.lda; f.ldb = s.ldb; f.ldc = s.ldc; f.sA = s.sA; f.sB = s.sB; f.sC = s.sC;
     f.fix_tiles = w.fix_tiles; f.fix_count = w.fix_count;
+    f.cc_vobs = targeted ? w.cc_vobs : nullptr;
     switch (dt) {
     case DT_I8:   e = launch_recompute<DT_I8>(f, st); break;
     case DT_BF16: e = launch_recompute<DT_BF16>(f, st); break;
@@ -949,8 +1065,21 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    // re-check: the stored C is re-summed as a whole (a streaming pass at HBM speed is cheaper
-    // than strided column walks over the touched tiles) and compared with the predictions
+    if (targeted) {
+        TouchArgs t;
+        t.C = (const uint8_t *)C; t.ldc = s.ldc; t.sC = s.sC; t.M = s.M; t.N = s.N;
+        t.fix_tiles = w.fix_tiles; t.fix_count = w.fix_count; t.cc_vobs = w.cc_vobs; t.rc_vobs = w.rc_vobs;
+        const dim3 grid(MAX_FIX_TILES, TOUCH_PARTS);
+        switch (dt) {
+        case DT_I8:   hipLaunchKernelGGL(resum_touched_kernel<DT_I8>, grid, dim3(256), 0, st, t); break;
+        case DT_BF16: hipLaunchKernelGGL(resum_touched_kernel<DT_BF16>, grid, dim3(256), 0, st, t); break;
+        default:      hipLaunchKernelGGL(resum_touched_kernel<DT_F16>, grid, dim3(256), 0, st, t); break;
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        return launch_compare(dt, s, w, v, true, with_sto, nullptr, 0, st);
+    }
+    // re-check without earlier sums of this C: the stored C is re-summed as a whole (a streaming
+    // pass at HBM speed) and compared with the predictions
     if (stale_words && (e = launch_zero(w.cc_vobs, stale_words, st)) != hipSuccess) return e;
     if ((e = launch_verify_sums(dt, C, s, w, st)) != hipSuccess) return e;
     return launch_compare(dt, s, w, v, true, with_sto, zero_ptr, zero_words, st);

@@ -608,6 +608,59 @@ def test_transformer_block_gemms_full_size_sampled(ctx_block, cfg, gi):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 203, 256, 2, True), (600, 520, 128, 1, False)])
+def test_correction_of_several_tiles_keeps_the_resummed_vectors(ctx, dtype, M, N, K, batch, trans_b):
+    """Several corrupted elements at once, some sharing a tile row or a tile column, some in the
+    ragged last tiles, some turned into Inf / NaN: after verify + correct the stored C is the clean
+    one, every flag is down, and the re-summed vectors -- brought up to date for the rows and
+    columns of the recomputed tiles only -- are the sums of the clean stored C."""
+    A, B = gen.gen_operands(dtype, M, N, K, 411, 412, trans_b=trans_b, batch=batch)
+    P = oracle_items(dtype, A, B, trans_b)
+    run = Run(ctx, dtype, A, B, trans_b)
+    run.gemm(ab.ABFT_DETECT)
+    clean = np.stack([p.C_stored for p in P])
+    if dtype == "i8":
+        assert np.array_equal(run.C(), clean)
+    C_clean = run.C().copy()
+    # integers: a different bit per element, so that two errors in one column cannot cancel mod 2^32
+    bits = [30, 29, 28, 27, 26, 25] if dtype == "i8" else [14] * 6
+    spots = [(0, 0, 0), (0, 0, 40), (0, 70, 5), (0, M - 1, N - 1), (0, M - 1, 40)]
+    tiles = 3 * 3                                           # tile rows {0, 2, last} x tile columns {0, 1, last}
+    if batch > 1:
+        spots.append((1, 33, N - 1))
+        tiles += 1
+    run.verify()
+    for (bi, i, j), bit in zip(spots, bits):
+        run.inject(bi, i, j, bit)
+    run.verify()
+    rf, cf = run.flags()
+    for (bi, i, j) in spots:
+        assert rf[bi, i] and cf[bi, j]
+    assert rf.sum() == (3 if batch == 1 else 4) and cf.sum() == (4 if batch == 1 else 5)
+    run.correct()
+    assert np.array_equal(run.C(), C_clean), "C not restored"
+    rf, cf = run.flags()
+    cnt = run.cnt()
+    assert not rf.any() and not cf.any()
+    assert cnt[0] == 0 and cnt[1] == 0 and cnt[2] == ab.ABFT_CLEAN and cnt[3] == tiles
+    cc_v, rc_v = run.ws(ab.ABFT_WS_CC_VOBS), run.ws(ab.ABFT_WS_RC_VOBS)
+    for bi in range(batch):
+        _, _, _, _, cc_obs, rc_obs = orc.check(P[bi], C_clean[bi])
+        if dtype == "i8":
+            assert np.array_equal(cc_v[bi].view(np.uint32), (np.asarray(cc_obs) & 0xFFFFFFFF).astype(np.uint32))
+            assert np.array_equal(rc_v[bi].view(np.uint32), (np.asarray(rc_obs) & 0xFFFFFFFF).astype(np.uint32))
+        else:
+            assert np.max(np.abs(cc_v[bi] - cc_obs)) <= 1e-2 * P[bi].tau
+            assert np.max(np.abs(rc_v[bi] - rc_obs)) <= 1e-2 * P[bi].tau
+    run.correct()                                           # nothing left to repair
+    cnt = run.cnt()
+    assert cnt[2] == ab.ABFT_CLEAN and cnt[3] == 0 and np.array_equal(run.C(), C_clean)
+    run.verify()                                            # the full re-sum agrees
+    rf, cf = run.flags()
+    assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+
+
 @pytest.mark.parametrize("M,N,K,batch,trans_b", [(197, 768, 768, 1, True), (130, 70, 100, 3, False),
                                                  (520, 1030, 256, 2, True)])
 def test_checksum_only_correction_int8(ctx, M, N, K, batch, trans_b):
