@@ -435,6 +435,24 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 if constexpr (T::IS_INT) csa[s2][q] = item_s16x2{0, 0};
                 else csa[s2][q] = 0.f;
             }
+        // int8 with |b| < 2^15: the thread's sixteen values of b per slab as pairs of 16-bit halves,
+        // (b[4 d], b[4 d + 2]) and (b[4 d + 1], b[4 d + 3]), the order the pairs of A's bytes come in;
+        // they are the same for every row block
+        item_s16x2 bpk[T::IS_INT ? MAXS : 1][8];
+        if constexpr (T::IS_INT) {
+            if (PROT && !loader && g.b16_ok) {
+#pragma unroll
+                for (int s2 = 0; s2 < MAXS; ++s2) {
+                    const int sc = s2 < nslab ? s2 : nslab - 1;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + sc * KE + c8 * CE + 4 * d);
+                        bpk[s2][2 * d] = item_s16x2{(short)w[0], (short)w[2]};
+                        bpk[s2][2 * d + 1] = item_s16x2{(short)w[1], (short)w[3]};
+                    }
+                }
+            }
+        }
         acc_t cs[TPW][4];
         float cs_s[STO ? TPW : 1][4];            // column sums of the stored values
 #pragma unroll
@@ -453,61 +471,81 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 // The block's share of a = e^T A (kept in registers until the item ends), of the
                 // row prediction A b and of max|A|: thread (c8, rg) reads chunk c8 of rows
                 // rg + 32 p in every slab; a row's dot product is completed over its 8 lanes.
-                acc_t dot[WM];
+                // All of the thread's chunks are requested before the first is used (a slab past
+                // the last reads the last again and is not used).
+                auto a_pass = [&](auto b16_c) __attribute__((always_inline)) {
+                    constexpr bool B16 = decltype(b16_c)::value;
+                    acc_t dot[WM];
 #pragma unroll
-                for (int p = 0; p < WM; ++p) dot[p] = T::zero();
+                    for (int p = 0; p < WM; ++p) dot[p] = T::zero();
+                    i32x4 xa[MAXS][WM];
 #pragma unroll
-                for (int s2 = 0; s2 < MAXS; ++s2) {
-                    if (s2 < nslab) {
-                        acc_t bv[CE];
+                    for (int s2 = 0; s2 < MAXS; ++s2) {
+                        const int sc = s2 < nslab ? s2 : nslab - 1;
 #pragma unroll
-                        for (int q4 = 0; q4 < CE / 4; ++q4) {
-                            const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + s2 * KE + c8 * CE + 4 * q4);
+                        for (int p = 0; p < WM; ++p)
+                            xa[s2][p] = *reinterpret_cast<const i32x4 *>(sAc + sc * BMr * SLAB_BYTES +
+                                                                         (rg + 32 * p) * SLAB_BYTES + ((c8 ^ (rg & 7)) * 16));
+                    }
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) bv[4 * q4 + e] = from_word<acc_t>((uint32_t)w[e]);
-                        }
+                    for (int s2 = 0; s2 < MAXS; ++s2) {
+                        if (s2 < nslab) {
+                            acc_t bv[CE];
+                            if constexpr (!B16) {
 #pragma unroll
-                        for (int p = 0; p < WM; ++p) {
-                            i32x4 x4 = *reinterpret_cast<const i32x4 *>(sAc + s2 * BMr * SLAB_BYTES +
-                                                                        (rg + 32 * p) * SLAB_BYTES + ((c8 ^ (rg & 7)) * 16));
-                            if (m0 + rg + 32 * p >= M) x4 = i32x4{0, 0, 0, 0};
-                            if constexpr (T::IS_INT) {
+                                for (int q4 = 0; q4 < CE / 4; ++q4) {
+                                    const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + s2 * KE + c8 * CE + 4 * q4);
 #pragma unroll
-                                for (int d = 0; d < 4; ++d) {
-                                    const int wd = x4[d];
-                                    const item_s16x2 w = item_s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
-                                    const item_s16x2 ev = (w << 8) >> 8, od = w >> 8;   // bytes 0, 2 and 1, 3, sign-extended
-                                    csa[s2][2 * d] += ev;
-                                    csa[s2][2 * d + 1] += od;
-                                    if (g.b16_ok) {
-                                        // the same pairs against pairs of b: two products per instruction
-                                        const item_s16x2 b02 = item_s16x2{(short)bv[4 * d], (short)bv[4 * d + 2]};
-                                        const item_s16x2 b13 = item_s16x2{(short)bv[4 * d + 1], (short)bv[4 * d + 3]};
-                                        dot[p] = __builtin_amdgcn_sdot2(ev, b02, (int)dot[p], false);
-                                        dot[p] = __builtin_amdgcn_sdot2(od, b13, (int)dot[p], false);
-                                    }
+                                    for (int e = 0; e < 4; ++e) bv[4 * q4 + e] = from_word<acc_t>((uint32_t)w[e]);
                                 }
                             }
-                            if (T::IS_INT && g.b16_ok) continue;
 #pragma unroll
-                            for (int q = 0; q < CE; ++q) {
-                                const acc_t x = T::elem(x4, q);
-                                if constexpr (!T::IS_INT) csa[s2][q] = csa[s2][q] + (float)x;
+                            for (int p = 0; p < WM; ++p) {
+                                i32x4 x4 = xa[s2][p];
+                                if (m0 + rg + 32 * p >= M) x4 = i32x4{0, 0, 0, 0};
                                 if constexpr (T::IS_INT) {
-                                    dot[p] = g.mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot[p])
-                                                        : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot[p]);
-                                } else {
-                                    dot[p] = __builtin_fmaf((float)x, (float)bv[q], (float)dot[p]);
-                                    amax = fmaxf(amax, fabsf((float)x));
+#pragma unroll
+                                    for (int d = 0; d < 4; ++d) {
+                                        const int wd = x4[d];
+                                        const item_s16x2 w = item_s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
+                                        const item_s16x2 ev = (w << 8) >> 8, od = w >> 8;   // bytes 0, 2 and 1, 3, sign-extended
+                                        csa[s2][2 * d] += ev;
+                                        csa[s2][2 * d + 1] += od;
+                                        if constexpr (B16) {
+                                            // the same pairs against pairs of b: two products per instruction
+                                            dot[p] = __builtin_amdgcn_sdot2(ev, bpk[s2][2 * d], (int)dot[p], false);
+                                            dot[p] = __builtin_amdgcn_sdot2(od, bpk[s2][2 * d + 1], (int)dot[p], false);
+                                        }
+                                    }
+                                }
+                                if constexpr (!B16) {
+#pragma unroll
+                                    for (int q = 0; q < CE; ++q) {
+                                        const acc_t x = T::elem(x4, q);
+                                        if constexpr (!T::IS_INT) csa[s2][q] = csa[s2][q] + (float)x;
+                                        if constexpr (T::IS_INT) {
+                                            dot[p] = g.mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot[p])
+                                                                : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot[p]);
+                                        } else {
+                                            dot[p] = __builtin_fmaf((float)x, (float)bv[q], (float)dot[p]);
+                                            amax = fmaxf(amax, fabsf((float)x));
+                                        }
+                                    }
                                 }
                             }
                         }
                     }
-                }
 #pragma unroll
-                for (int p = 0; p < WM; ++p) {
-                    const acc_t d = row8_sum(dot[p]);
-                    if (c8 == p) rcpred[m0 + rg + 32 * p] = as_word(d);
+                    for (int p = 0; p < WM; ++p) {
+                        const acc_t d = row8_sum(dot[p]);
+                        if (c8 == p) rcpred[m0 + rg + 32 * p] = as_word(d);
+                    }
+                };
+                if constexpr (T::IS_INT) {
+                    if (g.b16_ok) a_pass(std::true_type{});
+                    else a_pass(std::false_type{});
+                } else {
+                    a_pass(std::false_type{});
                 }
             }
 
