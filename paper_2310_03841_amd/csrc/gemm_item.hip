@@ -36,6 +36,13 @@ constexpr int ITEM_MAX_BLOCKS = 1024;      // workgroups; items beyond are taken
 constexpr int ITEM_GROUP = 16;             // workgroups per first-level ticket
 constexpr int ITEM_STAGE_ROW = 36;         // words per staged row of a 32 x 32 block (32 + pad)
 constexpr int ITEM_STAGE_WAVE = 32 * ITEM_STAGE_ROW * 4;
+// two 16-bit integers in one register, and the same 32 bits as a word (for moves between lanes)
+typedef short item_s16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ item_s16x2 item_pair(int w) { return item_s16x2{(short)(w & 0xFFFF), (short)(w >> 16)}; }
+__device__ __forceinline__ int item_word(item_s16x2 v)
+{
+    return (int)(((uint32_t)(uint16_t)v[1] << 16) | (uint32_t)(uint16_t)v[0]);
+}
 constexpr int ITEM_LDS_LIMIT = 160 * 1024;
 constexpr int ITEM_THREADS = 320;          // four computing waves and the loading wave
 constexpr int ITEM_MAX_STAGES = 8;
@@ -424,7 +431,6 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
         // columns per register as 16-bit halves (a thread sees at most M / 32 <= 32 rows of a
         // column: |sum| <= 4096); dword d of a chunk gives csa[2 d] = columns 4 d + {0, 2} and
         // csa[2 d + 1] = columns 4 d + {1, 3}.
-        typedef short item_s16x2 __attribute__((ext_vector_type(2)));
         typedef typename std::conditional<T::IS_INT, item_s16x2, float>::type csa_t;
         constexpr int NCSA = T::IS_INT ? CE / 2 : CE;
         csa_t csa[MAXS][NCSA];
@@ -763,28 +769,60 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     }
                 }
             }
-            // a = e^T A: over the eight row groups of the wave, then over the waves
+            // a = e^T A: over the eight row groups of the wave in registers (int8: still as pairs
+            // of 16-bit halves: 256 rows of bytes fit), then one copy per wave in the wave's
+            // staging area, which the epilogues are done with; sum_waves adds the four copies
+            uint32_t *mine = reinterpret_cast<uint32_t *>(stage);
 #pragma unroll
             for (int s2 = 0; s2 < MAXS; ++s2) {
-                if (s2 < nslab) {
+                i32x4 out[2];
 #pragma unroll
-                    for (int q = 0; q < CE; ++q) {
-                        acc_t v;
-                        if constexpr (T::IS_INT) v = (acc_t)csa[s2][2 * (q >> 2) + (q & 1)][(q >> 1) & 1];
-                        else v = (acc_t)csa[s2][q];
-                        v = add_t(v, dpp_get<0x128>(v));          // lane ^ 8
+                for (int j = 0; j < 8; ++j) {
+                    if constexpr (T::IS_INT) {
+                        int w = item_word(csa[s2][j]);
+                        w = item_word(item_pair(w) + item_pair(dpp_get<0x128>(w)));          // lane ^ 8
+                        auto p16 = __builtin_amdgcn_permlane16_swap((unsigned)w, (unsigned)w, false, false);
+                        w = item_word(item_pair((int)p16[0]) + item_pair((int)p16[1]));      // lane ^ 16
+                        auto p32 = __builtin_amdgcn_permlane32_swap((unsigned)w, (unsigned)w, false, false);
+                        w = item_word(item_pair((int)p32[0]) + item_pair((int)p32[1]));      // lane ^ 32
+                        out[j >> 2][j & 3] = w;
+                    } else {
+                        float v = csa[s2][j];
+                        v = add_t(v, dpp_get<0x128>(v));              // lane ^ 8
                         v = add_xor16(v);
                         v = add_xor32(v);
-                        if (lane < 8) {
-                            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(a_lds) + s2 * KE + c8 * CE + q, (int)v);
-                            else atomicAdd(reinterpret_cast<float *>(a_lds) + s2 * KE + c8 * CE + q, (float)v);
-                        }
+                        out[j >> 2][j & 3] = (int)__float_as_uint(v);
                     }
+                }
+                if (lane < 8 && s2 < nslab) {
+                    i32x4 *dst = reinterpret_cast<i32x4 *>(mine + (s2 * 8 + lane) * 8);
+                    dst[0] = out[0];
+                    dst[1] = out[1];
                 }
             }
             if (!T::IS_INT) {
                 const float m = wave_max(amax);
                 if (lane == 0) misc[wave] = __float_as_uint(m);
+            }
+        };
+        // a[k] from the four waves' copies (int8: column 4 d + e of a chunk sits in half (e >> 1) of
+        // word 2 d + (e & 1))
+        auto sum_waves = [&]() __attribute__((always_inline)) {
+            for (int k = tid; k < nslab * KE; k += 256) {
+                const int s2 = k / KE, c = (k % KE) / CE, q = k % CE;
+                acc_t t = T::zero();
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    const uint32_t *copy = reinterpret_cast<const uint32_t *>(sA0 + S * abuf + w2 * ITEM_STAGE_WAVE) +
+                                           (s2 * 8 + c) * 8;
+                    if constexpr (T::IS_INT) {
+                        const uint32_t wd = copy[2 * (q >> 2) + (q & 1)];
+                        t += (int)(short)(((q >> 1) & 1) ? (wd >> 16) : (wd & 0xFFFFu));
+                    } else {
+                        t += __uint_as_float(copy[q]);
+                    }
+                }
+                a_lds[k] = as_word(t);
             }
         };
         // a B from the resident B against the column sums; row sums against A b; vectors out
@@ -854,6 +892,8 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
         };
         if (PROT) {
             if (!loader) reduce_sums();
+            item_barrier();
+            if (!loader) sum_waves();
             item_barrier();
             float tol = 0.f, ma = 0.f, mb = 0.f;
             if (!T::IS_INT) {
