@@ -441,10 +441,12 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 if constexpr (T::IS_INT) csa[s2][q] = item_s16x2{0, 0};
                 else csa[s2][q] = 0.f;
             }
-        // int8 with |b| < 2^15: the thread's sixteen values of b per slab as pairs of 16-bit halves,
-        // (b[4 d], b[4 d + 2]) and (b[4 d + 1], b[4 d + 3]), the order the pairs of A's bytes come in;
-        // they are the same for every row block
+        // int8: the thread's sixteen values of b per slab as pairs of 16-bit halves, (b[4 d], b[4 d + 2])
+        // and (b[4 d + 1], b[4 d + 3]), the order the pairs of A's bytes come in; they are the same for
+        // every row block.  With |b| < 2^15 (N <= 255) that is bpk[slab].  Wider sums (|b| <= 128 N < 2^17)
+        // are split, b = 256 hi + lo with 0 <= lo < 256, for a K of one slab: bpk[0] = hi, bpk[1] = lo.
         item_s16x2 bpk[T::IS_INT ? MAXS : 1][8];
+        const bool b_split = T::IS_INT && !g.b16_ok && nslab == 1;
         if constexpr (T::IS_INT) {
             if (PROT && !loader && g.b16_ok) {
 #pragma unroll
@@ -456,6 +458,15 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                         bpk[s2][2 * d] = item_s16x2{(short)w[0], (short)w[2]};
                         bpk[s2][2 * d + 1] = item_s16x2{(short)w[1], (short)w[3]};
                     }
+                }
+            } else if (PROT && !loader && b_split) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const i32x4 w = *reinterpret_cast<const i32x4 *>(b_lds + c8 * CE + 4 * d);
+                    bpk[0][2 * d] = item_s16x2{(short)(w[0] >> 8), (short)(w[2] >> 8)};
+                    bpk[0][2 * d + 1] = item_s16x2{(short)(w[1] >> 8), (short)(w[3] >> 8)};
+                    bpk[1][2 * d] = item_s16x2{(short)(w[0] & 255), (short)(w[2] & 255)};
+                    bpk[1][2 * d + 1] = item_s16x2{(short)(w[1] & 255), (short)(w[3] & 255)};
                 }
             }
         }
@@ -479,11 +490,12 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 // rg + 32 p in every slab; a row's dot product is completed over its 8 lanes.
                 // All of the thread's chunks are requested before the first is used (a slab past
                 // the last reads the last again and is not used).
-                auto a_pass = [&](auto b16_c) __attribute__((always_inline)) {
-                    constexpr bool B16 = decltype(b16_c)::value;
-                    acc_t dot[WM];
+                auto a_pass = [&](auto mode_c) __attribute__((always_inline)) {
+                    constexpr int MODE = decltype(mode_c)::value;   // 0: b as it is, 1: 16-bit pairs of b, 2: split b
+                    constexpr bool B16 = MODE != 0;
+                    acc_t dot[WM], dot_hi[WM];
 #pragma unroll
-                    for (int p = 0; p < WM; ++p) dot[p] = T::zero();
+                    for (int p = 0; p < WM; ++p) { dot[p] = T::zero(); dot_hi[p] = T::zero(); }
                     i32x4 xa[MAXS][WM];
 #pragma unroll
                     for (int s2 = 0; s2 < MAXS; ++s2) {
@@ -517,10 +529,16 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                                         const item_s16x2 ev = (w << 8) >> 8, od = w >> 8;   // bytes 0, 2 and 1, 3, sign-extended
                                         csa[s2][2 * d] += ev;
                                         csa[s2][2 * d + 1] += od;
-                                        if constexpr (B16) {
+                                        if constexpr (MODE == 1) {
                                             // the same pairs against pairs of b: two products per instruction
                                             dot[p] = __builtin_amdgcn_sdot2(ev, bpk[s2][2 * d], (int)dot[p], false);
                                             dot[p] = __builtin_amdgcn_sdot2(od, bpk[s2][2 * d + 1], (int)dot[p], false);
+                                        }
+                                        if constexpr (MODE == 2) {
+                                            dot_hi[p] = __builtin_amdgcn_sdot2(ev, bpk[0][2 * d], (int)dot_hi[p], false);
+                                            dot_hi[p] = __builtin_amdgcn_sdot2(od, bpk[0][2 * d + 1], (int)dot_hi[p], false);
+                                            dot[p] = __builtin_amdgcn_sdot2(ev, bpk[1][2 * d], (int)dot[p], false);
+                                            dot[p] = __builtin_amdgcn_sdot2(od, bpk[1][2 * d + 1], (int)dot[p], false);
                                         }
                                     }
                                 }
@@ -543,15 +561,17 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     }
 #pragma unroll
                     for (int p = 0; p < WM; ++p) {
+                        if constexpr (MODE == 2) dot[p] = (acc_t)((uint32_t)dot_hi[p] * 256u + (uint32_t)dot[p]);
                         const acc_t d = row8_sum(dot[p]);
                         if (c8 == p) rcpred[m0 + rg + 32 * p] = as_word(d);
                     }
                 };
                 if constexpr (T::IS_INT) {
-                    if (g.b16_ok) a_pass(std::true_type{});
-                    else a_pass(std::false_type{});
+                    if (g.b16_ok) a_pass(std::integral_constant<int, 1>{});
+                    else if (b_split) a_pass(std::integral_constant<int, 2>{});
+                    else a_pass(std::integral_constant<int, 0>{});
                 } else {
-                    a_pass(std::false_type{});
+                    a_pass(std::integral_constant<int, 0>{});
                 }
             }
 
