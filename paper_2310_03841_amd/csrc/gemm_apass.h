@@ -67,25 +67,71 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
 #pragma unroll
     for (int p = 0; p < P; ++p) v[p] = *reinterpret_cast<const i32x4 *>(src + p * 32 * SLAB_BYTES);
     acc_t mine = T::zero();
+    bool done = false;
+    if constexpr (T::IS_INT) {
+        if (mul24_ok) {
+            // |b| <= 128 N < 2^23: b = 256 hi + lo with 0 <= lo < 256 and |hi| < 2^15.  The bytes of a
+            // word of A as two pairs of 16-bit integers (bytes 0, 2 and bytes 1, 3): the column sums
+            // add pair-wise (at most 8 rows per thread), the row product takes two products per
+            // instruction against the pairs of hi and of lo.
+            typedef short s16x2 __attribute__((ext_vector_type(2)));
+            s16x2 bhi[8], blo[8], csp[8];
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        i32x4 x4 = v[p];
-        if (rg + 32 * p >= rows_valid) x4 = i32x4{0, 0, 0, 0};
-        acc_t dot = T::zero();
-#pragma unroll
-        for (int q = 0; q < CE; ++q) {
-            const acc_t x = T::elem(x4, q);
-            cs[q] = add_t(cs[q], x);
-            if constexpr (T::IS_INT) {
-                dot = mul24_ok ? (acc_t)(__mul24((int)x, (int)bv[q]) + (int)dot)
-                               : (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot);
-            } else {
-                dot = __builtin_fmaf((float)x, (float)bv[q], (float)dot);
-                st.amax = fmaxf(st.amax, fabsf((float)x));
+            for (int d = 0; d < 4; ++d) {
+                const int b0 = (int)bv[4 * d], b1 = (int)bv[4 * d + 1], b2 = (int)bv[4 * d + 2], b3 = (int)bv[4 * d + 3];
+                bhi[2 * d] = s16x2{(short)(b0 >> 8), (short)(b2 >> 8)};
+                bhi[2 * d + 1] = s16x2{(short)(b1 >> 8), (short)(b3 >> 8)};
+                blo[2 * d] = s16x2{(short)(b0 & 255), (short)(b2 & 255)};
+                blo[2 * d + 1] = s16x2{(short)(b1 & 255), (short)(b3 & 255)};
             }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) csp[j] = s16x2{0, 0};
+#pragma unroll
+            for (int p = 0; p < P; ++p) {
+                i32x4 x4 = v[p];
+                if (rg + 32 * p >= rows_valid) x4 = i32x4{0, 0, 0, 0};
+                int dhi = 0, dlo = 0;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int wd = x4[d];
+                    const s16x2 w = s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
+                    const s16x2 ev = (w << 8) >> 8, od = w >> 8;       // bytes 0, 2 and 1, 3, sign-extended
+                    csp[2 * d] += ev;
+                    csp[2 * d + 1] += od;
+                    dhi = __builtin_amdgcn_sdot2(ev, bhi[2 * d], dhi, false);
+                    dhi = __builtin_amdgcn_sdot2(od, bhi[2 * d + 1], dhi, false);
+                    dlo = __builtin_amdgcn_sdot2(ev, blo[2 * d], dlo, false);
+                    dlo = __builtin_amdgcn_sdot2(od, blo[2 * d + 1], dlo, false);
+                }
+                acc_t dot = (acc_t)(int)((uint32_t)dhi * 256u + (uint32_t)dlo);
+                dot = row8_sum(dot);
+                if (c == p) mine = dot;
+            }
+#pragma unroll
+            for (int q = 0; q < CE; ++q) cs[q] = (acc_t)csp[2 * (q >> 2) + (q & 1)][(q >> 1) & 1];
+            done = true;
         }
-        dot = row8_sum(dot);
-        if (c == p) mine = dot;
+    }
+    if (!done) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            i32x4 x4 = v[p];
+            if (rg + 32 * p >= rows_valid) x4 = i32x4{0, 0, 0, 0};
+            acc_t dot = T::zero();
+#pragma unroll
+            for (int q = 0; q < CE; ++q) {
+                const acc_t x = T::elem(x4, q);
+                cs[q] = add_t(cs[q], x);
+                if constexpr (T::IS_INT) {
+                    dot = (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot);
+                } else {
+                    dot = __builtin_fmaf((float)x, (float)bv[q], (float)dot);
+                    st.amax = fmaxf(st.amax, fabsf((float)x));
+                }
+            }
+            dot = row8_sum(dot);
+            if (c == p) mine = dot;
+        }
     }
     st.rdot = add_t(st.rdot, mine);
     // Column sums: first over the eight row groups of the wave (lanes with equal c), then one
