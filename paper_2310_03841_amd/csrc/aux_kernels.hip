@@ -310,6 +310,7 @@ struct FinArgs {
     uint32_t *group_ticket;   // [FIN_MAX_BLOCKS / FIN_GROUP] first-level tickets (self-cleaning)
     int batch;
     int lpr;              // B stored N x K: lanes along one row of B (8, 16, 32 or 64)
+    int ksplit;           // 1, or 4 (deep K, lpr = 64): the four waves share four rows of B, a quarter of K each
     int col_blocks;       // units [0, col_blocks) of a batch item take columns, the rest rows
     uint32_t *zero_ptr;   // region every block helps to clear: what the previous protected GEMM of this
     size_t zero_words;    // context accumulated into, so that the next one finds it clean
@@ -333,6 +334,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     constexpr int ES = T::ES, CE = 16 / ES;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     __shared__ acc_t wred[4];
+    __shared__ acc_t kpart[4][4];
     __shared__ unsigned wcnt[4][2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int M = f.M, N = f.N, K = f.K;
@@ -368,9 +370,12 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                 const int nch = (K + CE - 1) / CE;
                 const int lpr = f.lpr, rpw = 64 / lpr;
                 const int sub = lane / lpr, lc = lane % lpr;
-                const int nb = blk * (16 * rpw) + wave * 4 * rpw + sub;     // row of pass 0; pass j: + j * rpw
+                const bool split = f.ksplit == 4;
+                // row of pass 0; pass j: + j * rpw.  Deep K: every wave takes the block's four rows
+                // and every fourth run of 64 chunks.
+                const int nb = split ? blk * 4 : blk * (16 * rpw) + wave * 4 * rpw + sub;
                 acc_t dot[4] = {T::zero(), T::zero(), T::zero(), T::zero()};
-                for (int ch = lc; ch < nch; ch += lpr) {
+                for (int ch = split ? lane + 64 * wave : lc; ch < nch; ch += split ? 256 : lpr) {
                     i32x4 v[4], aw[CE / 4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -409,12 +414,23 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) dot[j] = seg_sum(dot[j], lpr);
                 }
+                if (split) {
+                    __syncthreads();                                    // previous unit done with kpart
+                    if (lane == 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) kpart[wave][j] = dot[j];
+                    }
+                    __syncthreads();
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        dot[j] = add_t(add_t(kpart[0][j], kpart[1][j]), add_t(kpart[2][j], kpart[3][j]));
+                }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const acc_t t = dot[j];
                     const int n = nb + j * rpw;
                     bool fl = false;
-                    if (lc == 0 && n < N) {
+                    if (lc == 0 && n < N && (!split || wave == 0)) {
                         const long o = (long)bz * N + n;
                         f.cc_pred[o] = as_word(t);
                         fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
@@ -547,7 +563,9 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     const int nch = (s.K + ce - 1) / ce;
     f.lpr = nch <= 8 ? 8 : (nch <= 16 ? 16 : (nch <= 32 ? 32 : 64));
     f.batch = s.batch;
-    const int rows_per_unit = 16 * (64 / f.lpr);
+    // deep K (four or more runs of 64 chunks per row): a unit is four rows, its K shared by the waves
+    f.ksplit = (s.transB && nch >= 256) ? 4 : 1;
+    const int rows_per_unit = f.ksplit == 4 ? 4 : 16 * (64 / f.lpr);
     f.col_blocks = s.transB ? (s.N + rows_per_unit - 1) / rows_per_unit : (s.N + 32 * ce - 1) / (32 * ce);
     const int row_blocks = (s.M + 255) / 256;
     const size_t smem = s.transB ? 0 : ((size_t)(s.K + 3) / 4 * 4 + (size_t)FIN_KY * 32 * ce) * 4;
