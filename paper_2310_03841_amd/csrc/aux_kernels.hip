@@ -953,6 +953,7 @@ __global__ __launch_bounds__(64 * (FIX_WAVES + 1)) void recompute_kernel(FixArgs
 // recompute_kernel has cleared.  A tile row or tile column listed more than once is summed by
 // its first tile only.
 constexpr int TOUCH_PARTS = 64;
+constexpr int TOUCH_TILES = 8;           // workgroups per part: listed tiles served at a time
 
 struct TouchArgs {
     const uint8_t *C;
@@ -974,72 +975,75 @@ __global__ __launch_bounds__(256) void resum_touched_kernel(TouchArgs a)
     __shared__ acc_t red[256 * CE];
     unsigned n = a.fix_count[0];
     if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
-    if (blockIdx.x >= n) return;
-    const int t = blockIdx.x, part = blockIdx.y, tid = threadIdx.x;
-    const int bz = a.fix_tiles[3 * t], tr = a.fix_tiles[3 * t + 1], tc = a.fix_tiles[3 * t + 2];
-    bool first_row = true, first_col = true;
-    for (int q = 0; q < t; ++q)
-        if (a.fix_tiles[3 * q] == bz) {
-            first_row = first_row && a.fix_tiles[3 * q + 1] != tr;
-            first_col = first_col && a.fix_tiles[3 * q + 2] != tc;
-        }
-    const uint8_t *Cb = a.C + (long)bz * a.sC * OS;
-    const int M = a.M, N = a.N;
+    const int part = blockIdx.y, tid = threadIdx.x;
+    // the grid has TOUCH_TILES workgroups per part; listed tiles beyond that many take further trips
+    for (int t = blockIdx.x; t < (int)n; t += gridDim.x) {
+        const int bz = a.fix_tiles[3 * t], tr = a.fix_tiles[3 * t + 1], tc = a.fix_tiles[3 * t + 2];
+        bool first_row = true, first_col = true;
+        for (int q = 0; q < t; ++q)
+            if (a.fix_tiles[3 * q] == bz) {
+                first_row = first_row && a.fix_tiles[3 * q + 1] != tr;
+                first_col = first_col && a.fix_tiles[3 * q + 2] != tc;
+            }
+        const uint8_t *Cb = a.C + (long)bz * a.sC * OS;
+        const int M = a.M, N = a.N;
 
-    const int row = tr * CT + part;
-    if (first_row && part < CT && row < M) {
-        acc_t s = T::zero();
-        const int nch = (N + CE - 1) / CE;
-        for (int c = tid; c < nch; c += 256) {
-            const i32x4 v = *reinterpret_cast<const i32x4 *>(Cb + ((long)row * a.ldc + (long)c * CE) * OS);
-            const int nvalid = N - c * CE;
-#pragma unroll
-            for (int q = 0; q < CE; ++q)
-                if (q < nvalid) s = add_t(s, out_elem<DT>(v, q));
-        }
-        s = wave_sum(s);
-        if ((tid & 63) == 0) red[tid >> 6] = s;
-        __syncthreads();
-        if (tid == 0) a.rc_vobs[(long)bz * M + row] = as_word(add_t(add_t(red[0], red[1]), add_t(red[2], red[3])));
-        __syncthreads();                                    // red is used again below
-    }
-    if (!first_col) return;
-
-    const int mc = (M + TOUCH_PARTS - 1) / TOUCH_PARTS;
-    const int rbeg = part * mc, rend = min(rbeg + mc, M);
-    const int cx = tid % CPR, ry = tid / CPR;
-    const int col0 = tc * CT + cx * CE;
-    const int nvalid = N - col0;
-    acc_t colacc[CE];
-#pragma unroll
-    for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
-    for (int r0 = rbeg + ry; r0 < rend; r0 += RL * ENC_UNROLL) {
-        i32x4 v[ENC_UNROLL];
-#pragma unroll
-        for (int u = 0; u < ENC_UNROLL; ++u) {
-            const int r = r0 + u * RL;
-            v[u] = i32x4{0, 0, 0, 0};
-            if (nvalid > 0 && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
-        }
-#pragma unroll
-        for (int u = 0; u < ENC_UNROLL; ++u) {
-            if (r0 + u * RL < rend) {
+        const int row = tr * CT + part;
+        if (first_row && part < CT && row < M) {
+            acc_t s = T::zero();
+            const int nch = (N + CE - 1) / CE;
+            for (int c = tid; c < nch; c += 256) {
+                const i32x4 v = *reinterpret_cast<const i32x4 *>(Cb + ((long)row * a.ldc + (long)c * CE) * OS);
+                const int nvalid = N - c * CE;
 #pragma unroll
                 for (int q = 0; q < CE; ++q)
-                    if (q < nvalid) colacc[q] = add_t(colacc[q], out_elem<DT>(v[u], q));
+                    if (q < nvalid) s = add_t(s, out_elem<DT>(v, q));
+            }
+            s = wave_sum(s);
+            if ((tid & 63) == 0) red[tid >> 6] = s;
+            __syncthreads();
+            if (tid == 0) a.rc_vobs[(long)bz * M + row] = as_word(add_t(add_t(red[0], red[1]), add_t(red[2], red[3])));
+            __syncthreads();                                    // red is used again below
+        }
+        if (!first_col) continue;
+
+        const int mc = (M + TOUCH_PARTS - 1) / TOUCH_PARTS;
+        const int rbeg = part * mc, rend = min(rbeg + mc, M);
+        const int cx = tid % CPR, ry = tid / CPR;
+        const int col0 = tc * CT + cx * CE;
+        const int nvalid = N - col0;
+        acc_t colacc[CE];
+#pragma unroll
+        for (int q = 0; q < CE; ++q) colacc[q] = T::zero();
+        for (int r0 = rbeg + ry; r0 < rend; r0 += RL * ENC_UNROLL) {
+            i32x4 v[ENC_UNROLL];
+#pragma unroll
+            for (int u = 0; u < ENC_UNROLL; ++u) {
+                const int r = r0 + u * RL;
+                v[u] = i32x4{0, 0, 0, 0};
+                if (nvalid > 0 && r < rend) v[u] = *reinterpret_cast<const i32x4 *>(Cb + ((long)r * a.ldc + col0) * OS);
+            }
+#pragma unroll
+            for (int u = 0; u < ENC_UNROLL; ++u) {
+                if (r0 + u * RL < rend) {
+#pragma unroll
+                    for (int q = 0; q < CE; ++q)
+                        if (q < nvalid) colacc[q] = add_t(colacc[q], out_elem<DT>(v[u], q));
+                }
             }
         }
-    }
 #pragma unroll
-    for (int q = 0; q < CE; ++q) red[ry * CT + cx * CE + q] = colacc[q];
-    __syncthreads();
-    if (tid < CT) {
-        const int col = tc * CT + tid;
-        if (col < N && rbeg < rend) {
-            acc_t s = red[tid];
-            for (int y = 1; y < RL; ++y) s = add_t(s, red[y * CT + tid]);
-            atomic_add_word(a.cc_vobs + (long)bz * N + col, s);
+        for (int q = 0; q < CE; ++q) red[ry * CT + cx * CE + q] = colacc[q];
+        __syncthreads();
+        if (tid < CT) {
+            const int col = tc * CT + tid;
+            if (col < N && rbeg < rend) {
+                acc_t s = red[tid];
+                for (int y = 1; y < RL; ++y) s = add_t(s, red[y * CT + tid]);
+                atomic_add_word(a.cc_vobs + (long)bz * N + col, s);
+            }
         }
+        __syncthreads();                                        // red is free for the next tile
     }
 }
 
@@ -1087,7 +1091,7 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
         TouchArgs t;
         t.C = (const uint8_t *)C; t.ldc = s.ldc; t.sC = s.sC; t.M = s.M; t.N = s.N;
         t.fix_tiles = w.fix_tiles; t.fix_count = w.fix_count; t.cc_vobs = w.cc_vobs; t.rc_vobs = w.rc_vobs;
-        const dim3 grid(MAX_FIX_TILES, TOUCH_PARTS);
+        const dim3 grid(TOUCH_TILES, TOUCH_PARTS);
         switch (dt) {
         case DT_I8:   hipLaunchKernelGGL(resum_touched_kernel<DT_I8>, grid, dim3(256), 0, st, t); break;
         case DT_BF16: hipLaunchKernelGGL(resum_touched_kernel<DT_BF16>, grid, dim3(256), 0, st, t); break;
