@@ -67,7 +67,7 @@ def check_clean(run: Run, P, fused=True):
             assert np.all(np.abs(Cg - p.C_ref) <= ulp * np.abs(p.C_ref) + 2e-6 * scale + 1e-7)
             # round-to-nearest-even from an fp32 accumulator: the stored bits equal the oracle's
             # rounding of the exact product except where fp32 noise crosses a rounding boundary
-            assert np.mean(C[bi] != p.C_stored) < 5e-3
+            assert np.sum(C[bi] != p.C_stored) <= max(2, 5e-3 * C[bi].size)     # small outputs: two crossings
             tol = 1e-2 * p.tau
             K = run.K
             assert np.max(np.abs(a[bi] - p.a)) <= 1e-5 * run.M * p.max_a
