@@ -743,6 +743,8 @@ ITEM_SHAPES = [
     (60, 300, 24, 64, True),       # N <= 640: five column blocks per wave at most
     (33, 577, 64, 64, False),
     (1, 1, 1, 64, True),
+    (193, 1, 236, 66, False),      # a single column: one 32-column block, 31 of them padding
+    (1, 300, 100, 64, True),       # a single row
 ]
 
 
