@@ -176,7 +176,11 @@ int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype d
 
 /* Re-sums the stored C and compares with the predictions the last abft_gemm of this shape left
  * in the context (Sec. III-B.1: sum of layer activations vs. checksum product).  Overwrites
- * flags and counts. */
+ * flags and counts.  Floating point: the stored values are rounded, and the rounding of a row of
+ * N (a column of M) of them grows like sqrt(N) (sqrt(M)) while the default tolerance grows with K;
+ * where N or M is several times K, clean rows or columns can exceed it (the comparison inside
+ * abft_gemm, on the accumulators, is not affected).  A tolerance of the caller's in r->tau
+ * (abft_discrepancy gives the statistics to fit it to) or ABFT_STORED_SUMS is the remedy. */
 int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape *s,
                 const abft_result *r, void *stream);
 
