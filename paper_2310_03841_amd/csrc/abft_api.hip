@@ -33,6 +33,10 @@ struct abft_ctx {
     int last_hip;
     // what the context currently holds
     bool b_valid, pred_valid, sto_valid, vobs_valid;
+    bool graph_mode;        // a call of this context has been captured into a graph (sticky): see in_graph_mode
+    bool vobs_captured;     // ... and they were formed by a call enqueued under capture
+    const void *vobs_C;     // the stored C the re-summed vectors belong to (with its ldc and batch stride)
+    int64_t vobs_ldc, vobs_strideC;
     bool list_dirty;        // the tile list's counters may be non-zero (a correction failed half way)
     int b_dt, pred_dt;
     abft_shape b_shape, pred_shape;
@@ -69,6 +73,47 @@ extern "C" const char *abft_strerror(int code)
 
 extern "C" int abft_last_hip_error(const abft_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
 
+// The device pools of a context, in 32-bit words, for a context that serves max_rows / max_cols /
+// max_depth (already rounded, see abft_create) / max_batch.
+constexpr int N_POOLS = 7;
+static constexpr size_t pool_total_words(size_t R, size_t Cn, size_t D, size_t Bt)
+{
+    return 2 * (D + Bt) + Bt * BATCH_WORDS + Cn + 2 * (2 * Cn + 3 * R + D + Bt) + 2 * (R + Cn) +
+           (size_t)MAX_FIX_TILES * 3 + (8 + 64);
+}
+static void pool_words(int64_t max_rows, int64_t max_cols, int64_t max_depth, int64_t max_batch, size_t words[N_POOLS])
+{
+    const size_t D = (size_t)max_depth, R = (size_t)max_rows, Cn = (size_t)max_cols, Bt = (size_t)max_batch;
+    words[0] = 2 * (D + Bt);                       // pool_depth
+    words[1] = Bt * BATCH_WORDS;                   // pool_batch
+    words[2] = Cn;                                 // pool_cols
+    words[3] = 2 * (2 * Cn + 3 * R + D + Bt);      // pool_obs
+    words[4] = 2 * (R + Cn);                       // pool_vobs
+    words[5] = (size_t)MAX_FIX_TILES * 3;          // fix_tiles
+    words[6] = 8 + 64;                             // small
+}
+static void pool_slots(abft_ctx *c, void **slot[N_POOLS])
+{
+    slot[0] = (void **)&c->pool_depth; slot[1] = (void **)&c->pool_batch; slot[2] = (void **)&c->pool_cols;
+    slot[3] = (void **)&c->pool_obs;   slot[4] = (void **)&c->pool_vobs;  slot[5] = (void **)&c->fix_tiles;
+    slot[6] = (void **)&c->small;
+}
+// Host-side bookkeeping of a context whose pools are all zero.
+static void start_clean(abft_ctx *c)
+{
+    const size_t D = (size_t)c->cfg.max_depth, R = (size_t)c->cfg.max_rows, Cn = (size_t)c->cfg.max_cols,
+                 Bt = (size_t)c->cfg.max_batch;
+    c->region_words = 2 * Cn + 3 * R + D + Bt;
+    c->cur = 0;
+    c->dirty[0] = c->dirty[1] = 0;
+    c->vregion_words = R + Cn;
+    c->vcur = 0;
+    c->vdirty[0] = c->vdirty[1] = 0;
+    c->bslot_words = D + Bt;
+    c->bslot = 0;
+    c->bclean[0] = c->bclean[1] = true;
+}
+
 extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
 {
     if (!out || !cfg) return ABFT_EINVAL;
@@ -82,20 +127,13 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     c->arm.batch = -1;
     hipError_t e = hipSetDevice(cfg->device);
     if (e != hipSuccess) { int r = fail_hip(c, e); delete c; return r; }
-    const size_t D = (size_t)c->cfg.max_depth, R = (size_t)cfg->max_rows, Cn = (size_t)cfg->max_cols,
-                 Bt = (size_t)cfg->max_batch;
-    struct { void **p; size_t bytes; } req[] = {
-        {(void **)&c->pool_depth, 2 * (D + Bt) * 4},
-        {(void **)&c->pool_batch, Bt * BATCH_WORDS * 4},
-        {(void **)&c->pool_cols, Cn * 4},
-        {(void **)&c->pool_obs, 2 * (2 * Cn + 3 * R + D + Bt) * 4},
-        {(void **)&c->pool_vobs, 2 * (R + Cn) * 4},
-        {(void **)&c->fix_tiles, (size_t)MAX_FIX_TILES * 3 * 4},
-        {(void **)&c->small, (8 + 64) * 4},
-    };
-    for (auto &q : req) {
-        e = hipMalloc(q.p, q.bytes);
-        if (e == hipSuccess) e = hipMemset(*q.p, 0, q.bytes);
+    size_t words[N_POOLS];
+    pool_words(c->cfg.max_rows, c->cfg.max_cols, c->cfg.max_depth, c->cfg.max_batch, words);
+    void **slot[N_POOLS];
+    pool_slots(c, slot);
+    for (int i = 0; i < N_POOLS; ++i) {
+        e = hipMalloc(slot[i], words[i] * 4);
+        if (e == hipSuccess) e = hipMemset(*slot[i], 0, words[i] * 4);
         if (e != hipSuccess) {
             int r = fail_hip(c, e);
             abft_destroy(c);
@@ -104,15 +142,7 @@ extern "C" int abft_create(abft_ctx **out, const abft_config *cfg)
     }
     e = hipDeviceSynchronize();
     if (e != hipSuccess) { int r = fail_hip(c, e); abft_destroy(c); return r; }
-    c->region_words = 2 * Cn + 3 * R + D + Bt;
-    c->cur = 0;
-    c->dirty[0] = c->dirty[1] = 0;
-    c->vregion_words = R + Cn;
-    c->vcur = 0;
-    c->vdirty[0] = c->vdirty[1] = 0;
-    c->bslot_words = D + Bt;
-    c->bslot = 0;
-    c->bclean[0] = c->bclean[1] = true;
+    start_clean(c);
     *out = c;
     return ABFT_OK;
 }
@@ -134,7 +164,7 @@ extern "C" int abft_destroy(abft_ctx *c)
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // need: 1 = A, 2 = B, 4 = C
-static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need, Shape *o)
+static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need, Shape *o, bool protect = true)
 {
     if (!c || !s) return ABFT_EINVAL;
     if (dt != ABFT_I8 && dt != ABFT_BF16 && dt != ABFT_F16) return ABFT_EINVAL;
@@ -143,7 +173,7 @@ static int check_shape(const abft_ctx *c, int dt, const abft_shape *s, int need,
     if (s->transB != 0 && s->transB != 1) return ABFT_EINVAL;
     const int es = elem_size(dt), os = out_size(dt);
     if (dt == ABFT_I8 && s->K >= (1 << 17)) return ABFT_ESHAPE;       // K * 2^14 must stay below 2^31
-    if ((need & 1) && s->K > protect_max_k(dt)) return ABFT_ESHAPE;   // deeper than the protected GEMM covers
+    if (protect && (need & 1) && s->K > protect_max_k(dt)) return ABFT_ESHAPE;   // deeper than the protected GEMM covers
     if ((need & 1) && s->lda < s->K) return ABFT_ESHAPE;
     if ((need & 2) && s->ldb < (s->transB ? s->K : s->N)) return ABFT_ESHAPE;
     if ((need & 4) && s->ldc < s->N) return ABFT_ESHAPE;
@@ -205,6 +235,18 @@ static bool same_out(const abft_shape &x, const abft_shape &y)
 {
     return x.M == y.M && x.N == y.N && x.batch == y.batch;
 }
+// abft_correct recomputes tiles from A and B: the operand geometry must be the one the predictions
+// were formed with
+static bool same_problem(const abft_shape &x, const abft_shape &y)
+{
+    return same_out(x, y) && x.K == y.K && x.transB == y.transB && x.lda == y.lda && x.ldb == y.ldb &&
+           x.ldc == y.ldc &&
+           (x.batch == 1 || (x.strideA == y.strideA && x.strideB == y.strideB && x.strideC == y.strideC));
+}
+static bool same_c_layout(const abft_shape &x, const abft_shape &y)
+{
+    return same_out(x, y) && x.ldc == y.ldc && (x.batch == 1 || x.strideC == y.strideC);
+}
 
 static int check_verdict(const abft_result *r, Verdict *v)
 {
@@ -229,13 +271,33 @@ static bool capturing(hipStream_t st)
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     return hipStreamIsCapturing(st, &cs) == hipSuccess && cs == hipStreamCaptureStatusActive;
 }
+// Once a call of a context has been captured, replays run at times the host does not see, so
+// what the host knows about "which region is clean" is worth nothing any more, for captured and
+// for eager calls alike.  From then on (sticky) the context stops alternating: every call works
+// on the regions in use at that moment, clears what it accumulates into itself before it starts
+// and clears nothing else.  The context then behaves like one with a single set of regions: the
+// last call that ran, eager or replayed, is the one whose vectors it holds.
+static bool in_graph_mode(abft_ctx *ctx, hipStream_t st)
+{
+    if (!ctx->graph_mode && capturing(st)) ctx->graph_mode = true;
+    return ctx->graph_mode;
+}
 
 static ResumPlan begin_resum(abft_ctx *ctx, size_t words, hipStream_t st)
 {
+    if (in_graph_mode(ctx, st)) {
+        ResumPlan p;
+        p.stale = words > ctx->vdirty[ctx->vcur] ? words : ctx->vdirty[ctx->vcur];
+        if (p.stale > ctx->vregion_words) p.stale = ctx->vregion_words;
+        p.other = nullptr;
+        p.other_words = 0;
+        ctx->vdirty[ctx->vcur] = ctx->vregion_words;
+        return p;
+    }
     const int prev = ctx->vcur;
     ctx->vcur ^= 1;
     ResumPlan p;
-    p.stale = capturing(st) ? words : ctx->vdirty[ctx->vcur];
+    p.stale = ctx->vdirty[ctx->vcur];
     p.other = ctx->pool_vobs + (size_t)prev * ctx->vregion_words;
     p.other_words = ctx->vdirty[prev];
     // until the kernels are enqueued both count as dirty; end_resum settles it
@@ -247,15 +309,16 @@ static ResumPlan begin_resum(abft_ctx *ctx, size_t words, hipStream_t st)
 static void end_resum(abft_ctx *ctx, size_t words)
 {
     ctx->vdirty[ctx->vcur] = words;
-    ctx->vdirty[ctx->vcur ^ 1] = 0;
+    if (!ctx->graph_mode) ctx->vdirty[ctx->vcur ^ 1] = 0;
 }
 
 // A pass over B accumulates into the slot that is not in use; that slot is clean unless two
 // passes follow each other without a protected GEMM in between (whose finish kernel cleans it).
 static int begin_b_pass(abft_ctx *ctx, hipStream_t st)
 {
-    const int target = ctx->bslot ^ 1;
-    if (!ctx->bclean[target] || capturing(st))
+    const bool gm = in_graph_mode(ctx, st);
+    const int target = gm ? ctx->bslot : ctx->bslot ^ 1;
+    if (!ctx->bclean[target] || gm)
         HIP_TRY(launch_zero(ctx->pool_depth + (size_t)target * ctx->bslot_words, ctx->bslot_words, st));
     ctx->bclean[target] = false;
     ctx->bslot = target;
@@ -289,15 +352,17 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
                          const Shape &sh, Workspace *w, const Verdict &v, const InjectArm &arm, hipEvent_t *ev,
                          hipStream_t st)
 {
+    const bool gm = in_graph_mode(ctx, st);
     const int prev = ctx->cur;
-    ctx->cur ^= 1;
+    if (!gm) ctx->cur ^= 1;
     if (!cached) {
         int rc = begin_b_pass(ctx, st);
         if (rc) return rc;
     }
     carve(ctx, dtype, sh, w);
     uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
-    const size_t stale = capturing(st) ? w->zero_words : ctx->dirty[ctx->cur];
+    size_t stale = ctx->dirty[ctx->cur];
+    if (gm && stale < w->zero_words) stale = w->zero_words;
     ctx->dirty[ctx->cur] = ctx->region_words;            // until everything below is enqueued
     if (!cached) HIP_TRY(launch_encode_b(dtype, B, sh, *w, w->cc_obs, stale, st));
     else if (stale) HIP_TRY(launch_zero(w->cc_obs, stale, st));
@@ -305,16 +370,21 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
     ctx->sto_valid = false;
     HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, *w, arm, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
-    const size_t prev_dirty = ctx->dirty[prev];
-    ctx->dirty[prev] = ctx->region_words;
-    // the finish kernel also cleans the b slot that is not in use (for the next pass over B)
-    const int other = ctx->bslot ^ 1;
-    uint32_t *other_base = ctx->pool_depth + (size_t)other * ctx->bslot_words;
-    HIP_TRY(launch_finish(dtype, B, sh, *w, v, prev_base, prev_dirty, ctx->bclean[other] ? nullptr : other_base,
-                          ctx->bslot_words, st));
-    ctx->bclean[other] = true;
-    ctx->dirty[prev] = 0;
-    ctx->dirty[ctx->cur] = w->zero_words;
+    if (gm) {
+        HIP_TRY(launch_finish(dtype, B, sh, *w, v, nullptr, 0, nullptr, 0, st));
+        ctx->dirty[ctx->cur] = w->zero_words;
+    } else {
+        const size_t prev_dirty = ctx->dirty[prev];
+        ctx->dirty[prev] = ctx->region_words;
+        // the finish kernel also cleans the b slot that is not in use (for the next pass over B)
+        const int other = ctx->bslot ^ 1;
+        uint32_t *other_base = ctx->pool_depth + (size_t)other * ctx->bslot_words;
+        HIP_TRY(launch_finish(dtype, B, sh, *w, v, prev_base, prev_dirty, ctx->bclean[other] ? nullptr : other_base,
+                              ctx->bslot_words, st));
+        ctx->bclean[other] = true;
+        ctx->dirty[prev] = 0;
+        ctx->dirty[ctx->cur] = w->zero_words;
+    }
     if (ev) HIP_TRY(hipEventRecord(ev[3], st));
     return ABFT_OK;
 }
@@ -335,17 +405,38 @@ static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, bool stored, cons
     return ABFT_OK;
 }
 
+// The context now holds the row / column sums of this stored C.
+static void note_vobs(abft_ctx *ctx, const void *C, const abft_shape *s, hipStream_t st)
+{
+    ctx->vobs_valid = true;
+    ctx->vobs_captured = capturing(st);
+    ctx->vobs_C = C;
+    ctx->vobs_ldc = s->ldc;
+    ctx->vobs_strideC = s->batch > 1 ? s->strideC : 0;
+}
+// May a correction bring those sums up to date in place instead of summing the whole C again?
+// Only if they belong to this C, and, once a graph is in play, only inside the captured sequence
+// that formed them (what an eager call finds in the region may be a replay's).
+static bool vobs_usable(const abft_ctx *ctx, const void *C, const abft_shape *s, hipStream_t st)
+{
+    if (!ctx->vobs_valid || ctx->vobs_C != C || ctx->vobs_ldc != s->ldc ||
+        ctx->vobs_strideC != (s->batch > 1 ? s->strideC : 0))
+        return false;
+    if (!ctx->graph_mode) return true;
+    return ctx->vobs_captured && capturing(st);
+}
+
 extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
                          const abft_shape *s, const abft_result *r, void *stream)
 {
-    Shape sh;
-    int rc = check_shape(ctx, dtype, s, 7, &sh);
-    if (rc) return rc;
-    if (!A || !B || !C) return ABFT_EINVAL;
-    if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return ABFT_EALIGN;
     const int base = mode & ABFT_MODE_MASK;
     if (base != ABFT_OFF && base != ABFT_DETECT && base != ABFT_DETECT_CORRECT) return ABFT_EINVAL;
     if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED | ABFT_STORED_SUMS)) return ABFT_EINVAL;
+    Shape sh;
+    int rc = check_shape(ctx, dtype, s, 7, &sh, base != ABFT_OFF);
+    if (rc) return rc;
+    if (!A || !B || !C) return ABFT_EINVAL;
+    if (!aligned16(A) || !aligned16(B) || !aligned16(C)) return ABFT_EALIGN;
     hipStream_t st = (hipStream_t)stream;
     Workspace w;
     carve(ctx, dtype, sh, &w);
@@ -389,12 +480,12 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words, st);
         carve(ctx, dtype, sh, &w);
-        const bool clear_list = ctx->list_dirty;
+        const bool clear_list = ctx->list_dirty || ctx->graph_mode;
         ctx->list_dirty = true;
         HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, false, rp.stale, rp.other, rp.other_words, st));
         ctx->list_dirty = false;
         end_resum(ctx, words);
-        ctx->vobs_valid = true;
+        note_vobs(ctx, C, s, st);
     }
     return ABFT_OK;
 }
@@ -410,9 +501,10 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     Verdict v;
     rc = check_verdict(r, &v);
     if (rc) return rc;
-    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_c_layout(ctx->pred_shape, *s))) return ABFT_ESTATE;
     hipStream_t st = (hipStream_t)stream;
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
+    ctx->vobs_valid = false;
     const ResumPlan rp = begin_resum(ctx, words, st);
     Workspace w;
     carve(ctx, dtype, sh, &w);
@@ -420,7 +512,7 @@ extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const
     HIP_TRY(launch_verify_sums(dtype, C, sh, w, st));
     HIP_TRY(launch_compare(dtype, sh, w, v, false, ctx->sto_valid, rp.other, rp.other_words, st));
     end_resum(ctx, words);
-    ctx->vobs_valid = true;
+    note_vobs(ctx, C, s, st);
     return ABFT_OK;
 }
 
@@ -435,11 +527,11 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     Verdict v;
     rc = check_verdict(r, &v);
     if (rc) return rc;
-    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
+    if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_problem(ctx->pred_shape, *s))) return ABFT_ESTATE;
     hipStream_t st = (hipStream_t)stream;
-    const bool clear_list = ctx->list_dirty;
+    const bool clear_list = ctx->list_dirty || in_graph_mode(ctx, st);
     Workspace w;
-    if (ctx->vobs_valid) {
+    if (vobs_usable(ctx, C, s, st)) {
         // abft_verify (or an earlier correction) left the sums of this stored C: they are brought up
         // to date in place, for the rows and columns of the recomputed tiles only
         carve(ctx, dtype, sh, &w);
@@ -450,6 +542,7 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
         ctx->vobs_valid = true;
         return ABFT_OK;
     }
+    ctx->vobs_valid = false;
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
     const ResumPlan rp = begin_resum(ctx, words, st);
     carve(ctx, dtype, sh, &w);
@@ -458,7 +551,7 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
                            rp.other_words, st));
     ctx->list_dirty = false;
     end_resum(ctx, words);
-    ctx->vobs_valid = true;
+    note_vobs(ctx, C, s, st);
     return ABFT_OK;
 }
 
@@ -475,7 +568,7 @@ extern "C" int abft_correct_checksum(abft_ctx *ctx, void *C, abft_dtype dtype, c
     rc = check_verdict(r, &v);
     if (rc) return rc;
     if (!(ctx->pred_valid && ctx->pred_dt == (int)dtype && same_out(ctx->pred_shape, *s))) return ABFT_ESTATE;
-    if (!ctx->vobs_valid) return ABFT_ESTATE;     // needs the re-summed stored C of abft_verify
+    if (!vobs_usable(ctx, C, s, (hipStream_t)stream)) return ABFT_ESTATE;     // needs the re-summed stored C of abft_verify
     Workspace w;
     carve(ctx, dtype, sh, &w);
     HIP_TRY(launch_arith_fix(C, sh, w, v, (hipStream_t)stream));
@@ -515,6 +608,7 @@ extern "C" int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_
     if (!C) return ABFT_EINVAL;
     if (bit < 0 || bit >= 8 * out_size(dtype)) return ABFT_EINVAL;
     HIP_TRY(launch_flip(C, dtype, sh, batch_idx, row, col, bit, (hipStream_t)stream));
+    if (C == ctx->vobs_C) ctx->vobs_valid = false;     // the sums the context holds describe C before the flip
     return ABFT_OK;
 }
 

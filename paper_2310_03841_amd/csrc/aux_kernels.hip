@@ -201,7 +201,8 @@ struct CmpArgs {
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
     uint32_t *fix_count;  // non-null after a correction: [0] tiles listed, [1] overflow (cleared after use)
-    const uint32_t *cc_sto, *rc_sto;   // non-null: stored-side sums of the GEMM (floating point)
+    const int32_t *fix_tiles;          // after a correction: the tiles it recomputed
+    uint32_t *cc_sto, *rc_sto;         // non-null: stored-side sums of the GEMM (floating point)
     uint32_t *zero_ptr;   // region every block helps to clear: the re-summing region not in use,
     size_t zero_words;    // so that the next re-sum finds it clean
     int M, N, batch;
@@ -221,6 +222,22 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
     }
     const float tol = IS_INT ? 0.f : (a.tau_override > 0.f ? a.tau_override : a.tau[bz]);
     bool frow = false, fcol = false;
+    if (!IS_INT && a.fix_count && a.rc_sto && idx < M + N) {
+        // After a correction the stored-side sums of the GEMM no longer describe the rows and
+        // columns of the recomputed tiles: if the fault was already in the accumulators when the
+        // epilogue summed them, those sums contain it, and the repaired values do not.  The fresh
+        // re-sum of the repaired rows and columns takes their place.
+        unsigned n = a.fix_count[0];
+        if (n > (unsigned)MAX_FIX_TILES) n = MAX_FIX_TILES;
+        const int mine = (idx < M ? idx : idx - M) / CT, which = idx < M ? 1 : 2;
+        bool touched = false;
+        for (unsigned t = 0; t < n; ++t)
+            touched = touched || (a.fix_tiles[3 * t] == bz && a.fix_tiles[3 * t + which] == mine);
+        if (touched) {
+            if (idx < M) a.rc_sto[(long)bz * M + idx] = a.rc_obs[(long)bz * M + idx];
+            else a.cc_sto[(long)bz * N + idx - M] = a.cc_obs[(long)bz * N + idx - M];
+        }
+    }
     if (idx < M) {
         frow = mismatch<IS_INT>(a.rc_obs[(long)bz * M + idx], a.rc_pred[(long)bz * M + idx], tol);
         if (!IS_INT && a.rc_sto)
@@ -277,6 +294,7 @@ hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verd
     a.cc_sto = (with_sto && dt != DT_I8) ? w.cc_sto : nullptr;
     a.rc_sto = a.cc_sto ? w.rc_sto : nullptr;
     a.fix_count = after_fix ? w.fix_count : nullptr;
+    a.fix_tiles = w.fix_tiles;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
     a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
     a.tau = w.tau; a.tau_override = v.tau_override;

@@ -971,51 +971,112 @@ def test_item_kernel_more_items_than_workgroups(dtype, M, N, K, batch, trans_b):
 
 @pytest.mark.parametrize("dtype,M,N,K,batch,trans_b", [("i8", 197, 768, 768, 1, True), ("bf16", 600, 520, 256, 2, True),
                                                        ("bf16", 100, 130, 72, 65, True), ("i8", 70, 50, 40, 64, False)])
-def test_calls_can_be_captured_in_a_graph(ctx_items, dtype, M, N, K, batch, trans_b):
+def test_calls_can_be_captured_in_a_graph(dtype, M, N, K, batch, trans_b):
     """The hot calls only enqueue kernels (no allocation, no copy, no synchronisation, no memset
     node): a protected GEMM followed by a verify is captured once and replayed several times, with
-    eager work in between, and every replay must give the eager result -- also with a fault
-    armed by the host between replays showing up in exactly that replay's flags."""
-    ctx = ctx_items
-    A, B = gen.gen_operands(dtype, M, N, K, 95, 96, trans_b=trans_b, batch=batch, b_kind="act" if batch > 1 else "weight")
-    run = Run(ctx, dtype, A, B, trans_b)
-    res = run.result()
-    run.gemm(ab.ABFT_DETECT)                     # warm-up: kernel attributes are set on first use
-    run.verify()
-    C_eager = run.dC.clone()
-    vec_eager = [run.ws(w).copy() for w in (ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED, ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS)]
-    assert run.cnt()[2] == ab.ABFT_CLEAN
-    graph = torch.cuda.CUDAGraph()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        with torch.cuda.graph(graph, stream=side):
-            rc1 = ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, run.shape, res)
-            rc2 = ab.abft_verify(ctx, run.dC, run.code, run.shape, res)
-    assert rc1 == ab.ABFT_OK and rc2 == ab.ABFT_OK
-    torch.cuda.current_stream().wait_stream(side)
-    for rep in range(4):
-        run.dC.fill_(0)
-        run.counts.fill_(99)
-        run.row_flag.fill_(7)
-        run.col_flag.fill_(7)
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(run.dC[:, :, :N], C_eager[:, :, :N]), rep
-        rf, cf = run.flags()
-        assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN, rep
-        for w, want in zip((ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED, ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS), vec_eager):
-            got = run.ws(w)
-            if dtype == "i8":
-                assert np.array_equal(got, want), (rep, w)
-            else:       # fp32 atomics: the order of the additions is not fixed
-                assert np.allclose(got, want, rtol=0, atol=1e-3 * max(1.0, float(np.max(np.abs(want))))), (rep, w)
-        # eager work between the replays, on the same context
-        run.inject(0, 1, 2, 5 if dtype == "i8" else 14)
+    eager calls on the same context in between -- a verify of a flipped C, which must flag exactly
+    the flipped element, and a protected GEMM with nothing cached, which must give the eager
+    vectors -- and every replay must give the eager result again."""
+    ctx = ab.abft_create(max_rows=70 * 256, max_cols=70 * 256, max_depth=70 * 128, max_batch=70)
+    try:
+        A, B = gen.gen_operands(dtype, M, N, K, 95, 96, trans_b=trans_b, batch=batch, b_kind="act" if batch > 1 else "weight")
+        run = Run(ctx, dtype, A, B, trans_b)
+        res = run.result()
+        WS = (ab.ABFT_WS_B_SUM, ab.ABFT_WS_A_SUM, ab.ABFT_WS_CC_PRED, ab.ABFT_WS_RC_PRED, ab.ABFT_WS_CC_OBS, ab.ABFT_WS_RC_OBS)
+        run.gemm(ab.ABFT_DETECT)                     # warm-up: kernel attributes are set on first use
         run.verify()
-        assert run.cnt()[2] == ab.ABFT_LOCALISED
-    del graph
+        C_eager = run.dC.clone()
+        C_host = run.C().copy()
+        vec_eager = [run.ws(w).copy() for w in WS]
+        assert run.cnt()[2] == ab.ABFT_CLEAN
+
+        def same_vectors(tag):
+            for w, want in zip(WS, vec_eager):
+                got = run.ws(w)
+                if dtype == "i8":
+                    assert np.array_equal(got, want), (tag, w)
+                else:       # fp32 atomics: the order of the additions is not fixed
+                    assert np.allclose(got, want, rtol=0, atol=1e-3 * max(1.0, float(np.max(np.abs(want))))), (tag, w)
+
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                rc1 = ab.abft_gemm(ctx, run.dA, run.dB, run.dC, run.code, ab.ABFT_DETECT, run.shape, res)
+                rc2 = ab.abft_verify(ctx, run.dC, run.code, run.shape, res)
+        assert rc1 == ab.ABFT_OK and rc2 == ab.ABFT_OK
+        torch.cuda.current_stream().wait_stream(side)
+        bit = 5 if dtype == "i8" else 14
+        for rep in range(4):
+            run.dC.fill_(0)
+            run.counts.fill_(99)
+            run.row_flag.fill_(7)
+            run.col_flag.fill_(7)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(run.dC[:, :, :N], C_eager[:, :, :N]), rep
+            rf, cf = run.flags()
+            assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN, rep
+            same_vectors(("replay", rep))
+            # eager calls between the replays, on the same context
+            bi = rep % batch
+            fi, fj = 1, 2
+            if dtype != "i8":                        # an element below 2: setting bit 14 makes it huge
+                small = np.argwhere(np.abs(orc.decode(C_host[bi], dtype)) < 1.0)
+                fi, fj = int(small[rep][0]), int(small[rep][1])
+            run.inject(bi, fi, fj, bit)
+            run.verify()
+            rf, cf = run.flags()
+            cnt = run.cnt()
+            assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, fi] and cf[bi, fj], rep
+            assert cnt[0] == 1 and cnt[1] == 1 and cnt[2] == ab.ABFT_LOCALISED, rep
+            if rep % 2:
+                run.correct()
+                assert run.cnt()[2] == ab.ABFT_CLEAN and torch.equal(run.dC[:, :, :N], C_eager[:, :, :N]), rep
+            run.dC.fill_(0)
+            run.gemm(ab.ABFT_DETECT)                 # nothing cached: pass over B, GEMM, finish
+            assert torch.equal(run.dC[:, :, :N], C_eager[:, :, :N]), rep
+            rf, cf = run.flags()
+            assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN, rep
+            same_vectors(("eager", rep))
+        del graph
+    finally:
+        ab.abft_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,M,N,K", [("bf16", 600, 520, 256), ("f16", 197, 768, 768)])
+def test_fault_before_the_stored_sums_is_corrected_to_clean(ctx, dtype, M, N, K):
+    """A fault that is in the accumulators when the epilogue sums the values it stores is part of
+    those sums.  After abft_correct has recomputed the tile, the sums of its rows and columns are
+    the fresh ones: the call ends CLEAN, and so does a later abft_verify."""
+    A, B = gen.gen_operands(dtype, M, N, K, 61, 62, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS)
+    C_clean = run.C().copy()
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    for (i, j, bit) in [(5, 7, 30), (M - 1, N - 1, 30), (300, 33, 30)]:     # |C| < 2: bit 30 set makes it huge
+        i = min(i, M - 1)
+        run.inject(0, i, j, bit, ab.ABFT_INJECT_ACCUMULATOR)
+        run.gemm(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS)
+        rf, cf = run.flags()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]
+        run.correct()
+        cnt = run.cnt()
+        assert cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+        assert np.array_equal(run.C(), C_clean)
+        run.verify()
+        rf, cf = run.flags()
+        assert not rf.any() and not cf.any() and run.cnt()[2] == ab.ABFT_CLEAN
+        # the tight storage check is still armed: a flip far below tau is seen
+        jm = int(np.argmax(np.abs(orc.decode(C_clean[0, 2], dtype))))     # |delta| = |C| / 16: between tau / 100 and tau
+        run.inject(0, 2, jm, 3 if dtype == "bf16" else 6)
+        run.verify()
+        rf, cf = run.flags()
+        assert rf[0, 2] and cf[0, jm] and rf.sum() == 1 and cf.sum() == 1
+        run.correct()
+        assert run.cnt()[2] == ab.ABFT_CLEAN and np.array_equal(run.C(), C_clean)
 
 
 def _random_shapes():
