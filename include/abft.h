@@ -174,6 +174,26 @@ int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_sha
 int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
               const abft_shape *s, const abft_result *r, void *stream);
 
+/* abft_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments (without a context), same
+ * kernels, same results as abft_gemm; the workspace (checksum vectors, partial sums, tickets) is
+ * a fixed array of about 3 MB inside the library's device image instead of the pools of a
+ * context, so the call allocates nothing, on the device or through any library.  Each GPU holds
+ * its own copy of that array from the moment the library is loaded until the process ends; the
+ * call uses the copy of the current device.  Limits (ABFT_EWORKSPACE beyond them):
+ * batch * M <= ABFT_STATIC_MAX_ROWS, batch * N <= ABFT_STATIC_MAX_COLS,
+ * batch * (K rounded up to 128) <= ABFT_STATIC_MAX_DEPTH, batch <= ABFT_STATIC_MAX_BATCH.
+ * All calls on one GPU share the array and the state in it (the cached encoding of B, the
+ * predictions): calls that overlap in time on one GPU, from different streams or threads, race.
+ * Use abft_create contexts where that is needed.  abft_verify / abft_correct have no such
+ * variant: use ABFT_DETECT_CORRECT here, or a context. */
+#define ABFT_STATIC_MAX_ROWS  65536
+#define ABFT_STATIC_MAX_COLS  16384
+#define ABFT_STATIC_MAX_DEPTH 16384
+#define ABFT_STATIC_MAX_BATCH 64
+int abft_gemm_static(const void *A, const void *B, void *C, abft_dtype dtype, int mode,
+                     const abft_shape *s, const abft_result *r, void *stream);
+
 /* Re-sums the stored C and compares with the predictions the last abft_gemm of this shape left
  * in the context (Sec. III-B.1: sum of layer activations vs. checksum product).  Overwrites
  * flags and counts.  Floating point: the stored values are rounded, and the rounding of a row of

@@ -21,7 +21,7 @@ __all__ = [
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
     "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS", "ABFT_WS_CC_STO", "ABFT_WS_RC_STO",
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
-    "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_verify", "abft_correct",
+    "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_gemm_static", "abft_verify", "abft_correct",
     "abft_correct_checksum", "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
     "abft_version", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
@@ -72,6 +72,9 @@ _SIGS = {
     "abft_gemm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                  ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
                                  ctypes.POINTER(abft_result), ctypes.c_void_p]),
+    "abft_gemm_static": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
+                                        ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_verify": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                    ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_correct": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -193,6 +196,13 @@ def abft_gemm(ctx, A, B, C, dtype: int, mode: int, shape: abft_shape, result: ab
     r = ctypes.byref(result) if result is not None else None
     return int(lib().abft_gemm(ctx, _ptr(A), _ptr(B), _ptr(C), dtype, mode, ctypes.byref(shape), r,
                                _stream(stream)))
+
+
+def abft_gemm_static(A, B, C, dtype: int, mode: int, shape: abft_shape, result: abft_result | None = None,
+                     stream=None) -> int:
+    r = ctypes.byref(result) if result is not None else None
+    return int(lib().abft_gemm_static(_ptr(A), _ptr(B), _ptr(C), dtype, mode, ctypes.byref(shape), r,
+                                      _stream(stream)))
 
 
 def abft_verify(ctx, C, dtype: int, shape: abft_shape, result: abft_result, stream=None) -> int:

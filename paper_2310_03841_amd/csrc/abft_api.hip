@@ -1,6 +1,7 @@
 // C-ABI of libabft: context, argument validation, workspace carving, launch order.
 // Every hot call only enqueues kernels on the caller's stream.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -33,6 +34,7 @@ struct abft_ctx {
     int last_hip;
     // what the context currently holds
     bool b_valid, pred_valid, sto_valid, vobs_valid;
+    bool is_static;         // the context of abft_gemm_static: its pools are not allocations
     bool graph_mode;        // a call of this context has been captured into a graph (sticky): see in_graph_mode
     bool vobs_captured;     // ... and they were formed by a call enqueued under capture
     const void *vobs_C;     // the stored C the re-summed vectors belong to (with its ldc and batch stride)
@@ -151,7 +153,7 @@ static void prof_free(abft_ctx *c);
 
 extern "C" int abft_destroy(abft_ctx *c)
 {
-    if (!c) return ABFT_EINVAL;
+    if (!c || c->is_static) return ABFT_EINVAL;
     prof_free(c);
     void *ptrs[] = {c->pool_depth, c->pool_batch, c->pool_cols, c->pool_obs, c->pool_vobs, c->fix_tiles, c->small};
     for (void *p : ptrs)
@@ -488,6 +490,68 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
         note_vobs(ctx, C, s, st);
     }
     return ABFT_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// abft_gemm for callers that cannot allocate device memory (code under graph capture, serving
+// loops, harnesses that forbid it): the workspace is a fixed array in the library's device image
+// instead of the pools abft_create allocates.  Every GPU holds its own copy of the array, at its
+// own address, from the moment the library is loaded until the process ends.
+constexpr int64_t STATIC_MAX_ROWS = ABFT_STATIC_MAX_ROWS, STATIC_MAX_COLS = ABFT_STATIC_MAX_COLS,
+                  STATIC_MAX_DEPTH = ABFT_STATIC_MAX_DEPTH, STATIC_MAX_BATCH = ABFT_STATIC_MAX_BATCH;
+constexpr int64_t STATIC_DEPTH_WORDS = STATIC_MAX_DEPTH + (int64_t)SLAB_BYTES * STATIC_MAX_BATCH;   // as abft_create rounds it
+// every pool starts on a 256-byte boundary
+constexpr size_t STATIC_SCRATCH_WORDS =
+    pool_total_words(STATIC_MAX_ROWS, STATIC_MAX_COLS, STATIC_DEPTH_WORDS, STATIC_MAX_BATCH) + N_POOLS * 64;
+static __device__ __align__(256) uint32_t scratch[STATIC_SCRATCH_WORDS];
+
+constexpr int STATIC_MAX_DEVICES = 32;
+static abft_ctx g_static_ctx[STATIC_MAX_DEVICES];     // static storage: zero-initialised
+static bool g_static_ready[STATIC_MAX_DEVICES];
+static std::mutex g_static_lock;
+
+extern "C" int abft_gemm_static(const void *A, const void *B, void *C, abft_dtype dtype, int mode,
+                                const abft_shape *s, const abft_result *r, void *stream)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return ABFT_EHIP;
+    abft_ctx *ctx = &g_static_ctx[dev];
+    {
+        std::lock_guard<std::mutex> hold(g_static_lock);
+        if (!g_static_ready[dev]) {
+            // `scratch` in host code is a stand-in for the symbol, not a device address: ask the
+            // runtime where this device's copy of the array lives, once, and use that pointer.
+            uint32_t *base = nullptr;
+            hipError_t e = hipGetSymbolAddress((void **)&base, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !base) { ctx->last_hip = (int)e; return ABFT_EHIP; }
+            memset(ctx, 0, sizeof(*ctx));
+            ctx->is_static = true;
+            ctx->cfg.max_rows = STATIC_MAX_ROWS;
+            ctx->cfg.max_cols = STATIC_MAX_COLS;
+            ctx->cfg.max_depth = STATIC_DEPTH_WORDS;
+            ctx->cfg.max_batch = STATIC_MAX_BATCH;
+            ctx->cfg.device = dev;
+            ctx->arm.batch = -1;
+            size_t words[N_POOLS];
+            pool_words(STATIC_MAX_ROWS, STATIC_MAX_COLS, STATIC_DEPTH_WORDS, STATIC_MAX_BATCH, words);
+            void **slot[N_POOLS];
+            pool_slots(ctx, slot);
+            size_t off = 0;
+            for (int i = 0; i < N_POOLS; ++i) {
+                *slot[i] = base + off;
+                off += (words[i] + 63) / 64 * 64;
+            }
+            if (off > STATIC_SCRATCH_WORDS) return ABFT_EWORKSPACE;
+            // The array is zero when the library is loaded; whatever an earlier user of this process
+            // left in it is cleared here, by a kernel on the caller's stream (no memset node: the
+            // call may be under capture).
+            e = launch_zero(base, STATIC_SCRATCH_WORDS, (hipStream_t)stream);
+            if (e != hipSuccess) { ctx->last_hip = (int)e; return ABFT_EHIP; }
+            start_clean(ctx);
+            g_static_ready[dev] = true;
+        }
+    }
+    return abft_gemm(ctx, A, B, C, dtype, mode, s, r, stream);
 }
 
 extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape *s,
