@@ -563,6 +563,175 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     }
 }
 
+// The same step for a B stored N x K (a Linear layer's weight: the common case), arranged so that
+// a block's critical path is one round of loads, one reduction and one ticket: the kernel is bound
+// by latency, not by the 2 K N bytes it reads, so everything a block needs is requested before
+// anything is used.  A unit is (batch item, block of rows of B): each wave takes FN_RW rows of B
+// with its lanes along K (deep K: the four waves share FN_RW rows, a quarter of K each), and the
+// unit also compares its share of the M rows.  One ticket per block; the last block writes counts.
+constexpr int FN_RW = 8;
+
+template <int DT>
+__global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
+{
+    using T = Traits<DT>;
+    typedef typename T::acc_t acc_t;
+    constexpr int ES = T::ES, CE = 16 / ES;
+    __shared__ acc_t wred[4];
+    __shared__ acc_t kpart[4][FN_RW];
+    __shared__ unsigned wcnt[4][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int M = f.M, N = f.N, K = f.K;
+    {
+        const size_t nb = gridDim.x;
+        for (size_t i = (size_t)blockIdx.x * 256 + tid; i < f.zero_words; i += nb * 256) f.zero_ptr[i] = 0u;
+        for (size_t i = (size_t)blockIdx.x * 256 + tid; i < f.zero2_words; i += nb * 256) f.zero2_ptr[i] = 0u;
+    }
+    const int nch = (K + CE - 1) / CE;
+    const bool split = f.ksplit == 4;
+    const int rpb = split ? FN_RW : 4 * FN_RW;                  // rows of B per unit
+    const int units = f.col_blocks * f.batch;
+    const int rshare = (M + f.col_blocks - 1) / f.col_blocks;   // rows of C a unit compares
+    const bool vec_a = (K & 3) == 0;                            // 16-byte loads of a are aligned
+    unsigned nr_w = 0, nc_w = 0;
+
+    for (int u = blockIdx.x; u < units; u += gridDim.x) {
+        const int bz = u / f.col_blocks, cb = u - bz * f.col_blocks;
+        const uint8_t *Bb = f.B + (long)bz * f.sB * ES;
+        const uint32_t *asum = f.a_sum + (long)bz * K;
+        // ---- everything the unit will compare against, requested first
+        const int nrow0 = cb * rpb + (split ? 0 : wave * FN_RW);
+        uint32_t my_obs = 0;
+        if (lane < FN_RW && nrow0 + lane < N) my_obs = f.cc_obs[(long)bz * N + nrow0 + lane];
+        const int rbeg = cb * rshare, rend = min(rbeg + rshare, M);
+        uint32_t ro = 0, rp = 0;
+        if (rbeg + tid < rend) { ro = f.rc_obs[(long)bz * M + rbeg + tid]; rp = f.rc_pred[(long)bz * M + rbeg + tid]; }
+        float tol = 0.f;
+        if (!T::IS_INT) {
+            const float ma = __uint_as_float(f.a_max[bz]), mb = __uint_as_float(f.b_max[bz]);
+            tol = f.tau_override > 0.f ? f.tau_override : (1e-3f * (float)K) * ma * mb;
+            if (cb == 0 && tid == 0) {
+                f.maxabs[(long)bz * 2] = ma;
+                f.maxabs[(long)bz * 2 + 1] = mb;
+                f.tau[bz] = tol;
+            }
+        }
+        // ---- a B over this wave's rows: two chunks per lane and trip, all loads of a trip in flight
+        acc_t dot[FN_RW];
+#pragma unroll
+        for (int j = 0; j < FN_RW; ++j) dot[j] = T::zero();
+        const int cstep = split ? 512 : 128;
+        for (int ch0 = split ? wave * 128 : 0; ch0 < nch; ch0 += cstep) {
+            i32x4 v[FN_RW][2], aw[2][CE / 4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int ch = ch0 + 64 * h + lane;
+                const bool in = ch < nch && (!split || ch < ch0 + 128);
+#pragma unroll
+                for (int j = 0; j < FN_RW; ++j) {
+                    v[j][h] = i32x4{0, 0, 0, 0};
+                    if (in && nrow0 + j < N) v[j][h] = *reinterpret_cast<const i32x4 *>(Bb + ((long)(nrow0 + j) * f.ldb + (long)ch * CE) * ES);
+                }
+                const int left = K - ch * CE;
+#pragma unroll
+                for (int q4 = 0; q4 < CE / 4; ++q4) {
+                    aw[h][q4] = i32x4{0, 0, 0, 0};
+                    if (in) {
+                        const uint32_t *ap = asum + ch * CE + 4 * q4;
+                        if (vec_a && left >= CE) aw[h][q4] = *reinterpret_cast<const i32x4 *>(ap);
+                        else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) aw[h][q4][e] = (4 * q4 + e < left) ? (int)ap[e] : 0;
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int left = K - (ch0 + 64 * h + lane) * CE;
+#pragma unroll
+                for (int j = 0; j < FN_RW; ++j) {
+                    i32x4 w = v[j][h];
+                    if (left < CE) w = mask_chunk(w, left > 0 ? left * ES : 0);
+#pragma unroll
+                    for (int q = 0; q < CE; ++q)
+                        dot[j] = add_t(dot[j], mul_t(T::elem(w, q), from_word<acc_t>((uint32_t)aw[h][q >> 2][q & 3])));
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < FN_RW; ++j) dot[j] = wave_sum(dot[j]);
+        if (split) {
+            __syncthreads();                                    // previous unit done with kpart
+            if (lane == 0) {
+#pragma unroll
+                for (int j = 0; j < FN_RW; ++j) kpart[wave][j] = dot[j];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < FN_RW; ++j)
+                dot[j] = add_t(add_t(kpart[0][j], kpart[1][j]), add_t(kpart[2][j], kpart[3][j]));
+        }
+        {
+            acc_t mine = dot[0];
+#pragma unroll
+            for (int j = 1; j < FN_RW; ++j) mine = lane == j ? dot[j] : mine;
+            bool fl = false;
+            if (lane < FN_RW && nrow0 + lane < N && (!split || wave == 0)) {
+                const long o = (long)bz * N + nrow0 + lane;
+                f.cc_pred[o] = as_word(mine);
+                fl = mismatch<T::IS_INT>(my_obs, as_word(mine), tol);
+                f.col_flag[o] = fl ? 1 : 0;
+            }
+            nc_w += __popcll(__ballot(fl));
+        }
+        // ---- this unit's share of the rows
+        for (int r = rbeg + tid; r - tid < rend; r += 256) {
+            bool fl = false;
+            if (r < rend) {
+                const long o = (long)bz * M + r;
+                if (r != rbeg + tid) { ro = f.rc_obs[o]; rp = f.rc_pred[o]; }
+                fl = mismatch<T::IS_INT>(ro, rp, tol);
+                f.row_flag[o] = fl ? 1 : 0;
+            }
+            nr_w += __popcll(__ballot(fl));
+        }
+        if (cb == 0) {
+            // scalar a . b (the single-number check value of Sec. III-B.1)
+            acc_t sv = T::zero();
+            for (int k = tid; k < K; k += 256)
+                sv = add_t(sv, mul_t(from_word<acc_t>(asum[k]), from_word<acc_t>(f.b_sum[(long)bz * K + k])));
+            sv = wave_sum(sv);
+            __syncthreads();                                    // wred free again
+            if (lane == 0) wred[wave] = sv;
+            __syncthreads();
+            if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
+        }
+    }
+    if (lane == 0) { wcnt[wave][0] = nr_w; wcnt[wave][1] = nc_w; }
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned nr = wcnt[0][0] + wcnt[1][0] + wcnt[2][0] + wcnt[3][0];
+        const unsigned nc = wcnt[0][1] + wcnt[1][1] + wcnt[2][1] + wcnt[3][1];
+        if (nr | nc) {
+            // rare: the counts must be at the coherence point before this block's ticket is
+            unsigned o1 = 0, o2 = 0;
+            if (nr) o1 = atomicAdd(f.ticket + 1, nr);
+            if (nc) o2 = atomicAdd(f.ticket + 2, nc);
+            asm volatile("s_waitcnt vmcnt(0)" :: "v"(o1), "v"(o2) : "memory");
+        }
+        if (atomicAdd(f.ticket, 1u) == gridDim.x - 1) {
+            const uint32_t r = atomicExch(f.ticket + 1, 0u), c = atomicExch(f.ticket + 2, 0u);
+            atomicExch(f.ticket, 0u);
+            f.counts[0] = r;
+            f.counts[1] = c;
+            f.counts[2] = status_of(r, c);
+            f.counts[3] = 0u;
+            f.counts[4] = status_of(r, c);
+        }
+    }
+}
+
 hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace &w, const Verdict &v,
                          uint32_t *zero_ptr, size_t zero_words, uint32_t *zero2_ptr, size_t zero2_words,
                          hipStream_t st)
@@ -579,14 +748,29 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     f.group_ticket = w.cmp_ticket + 4;
     const int ce = 16 / elem_size(dt);
     const int nch = (s.K + ce - 1) / ce;
-    f.lpr = nch <= 8 ? 8 : (nch <= 16 ? 16 : (nch <= 32 ? 32 : 64));
     f.batch = s.batch;
-    // deep K (four or more runs of 64 chunks per row): a unit is four rows, its K shared by the waves
-    f.ksplit = (s.transB && nch >= 256) ? 4 : 1;
-    const int rows_per_unit = f.ksplit == 4 ? 4 : 16 * (64 / f.lpr);
-    f.col_blocks = s.transB ? (s.N + rows_per_unit - 1) / rows_per_unit : (s.N + 32 * ce - 1) / (32 * ce);
+    if (s.transB) {
+        // deep K (more than one trip of 128 chunks per row): the waves of a block share its rows
+        f.ksplit = nch > 128 ? 4 : 1;
+        f.lpr = 64;
+        const int rpb = f.ksplit == 4 ? FN_RW : 4 * FN_RW;
+        f.col_blocks = (s.N + rpb - 1) / rpb;
+        const long units = (long)f.col_blocks * s.batch;
+        if (units > 0x7FFFFFFFL) return hipErrorInvalidValue;
+        dim3 grid((unsigned)(units < 512 ? units : 512), 1, 1);
+        switch (dt) {
+        case DT_I8:   hipLaunchKernelGGL(finish_nk_kernel<DT_I8>, grid, dim3(256), 0, st, f); break;
+        case DT_BF16: hipLaunchKernelGGL(finish_nk_kernel<DT_BF16>, grid, dim3(256), 0, st, f); break;
+        case DT_F16:  hipLaunchKernelGGL(finish_nk_kernel<DT_F16>, grid, dim3(256), 0, st, f); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
+    f.lpr = nch <= 8 ? 8 : (nch <= 16 ? 16 : (nch <= 32 ? 32 : 64));
+    f.ksplit = 1;
+    f.col_blocks = (s.N + 32 * ce - 1) / (32 * ce);
     const int row_blocks = (s.M + 255) / 256;
-    const size_t smem = s.transB ? 0 : ((size_t)(s.K + 3) / 4 * 4 + (size_t)FIN_KY * 32 * ce) * 4;
+    const size_t smem = ((size_t)(s.K + 3) / 4 * 4 + (size_t)FIN_KY * 32 * ce) * 4;
     const long units = (long)(f.col_blocks + row_blocks) * s.batch;
     if (units > 0x7FFFFFFFL) return hipErrorInvalidValue;
     dim3 grid((unsigned)(units < FIN_MAX_BLOCKS ? units : FIN_MAX_BLOCKS), 1, 1);
