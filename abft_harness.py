@@ -1,5 +1,7 @@
-"""Plumbing for the GPU parity tests: upload operands, run the library through its C ABI
-binding, read results and workspace vectors back as numpy arrays."""
+"""Plumbing shared by the GPU parity tests, bench.py and the smoke run: upload operands, call the
+library through its C-ABI binding, read results and workspace vectors back as numpy arrays.
+No arithmetic of the method lives here, and nothing here is called inside a timed region (the
+methods of Run synchronise)."""
 from __future__ import annotations
 
 import numpy as np

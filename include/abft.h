@@ -264,6 +264,14 @@ int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *til
 int abft_profile_begin(abft_ctx *ctx, int max_calls);
 int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls);
 
+/* Report helper (not a hot call: allocates, creates events, waits): runs, on the current device
+ * and its default stream, a kernel that issues nothing but the matrix instructions of `dtype` in
+ * the GEMM kernel's register shape (one wave per SIMD, sixteen 32 x 32 accumulators) for about
+ * `seconds` (at most 2), and returns the rate it sustained in 1e12 operations per second and the
+ * shader clock it ran at.  A GEMM kernel's rate divided by this says how well its loop feeds the
+ * matrix pipe, apart from the clock the chip grants under that load. */
+int abft_mfma_peak(abft_dtype dtype, double seconds, double *tera_ops, double *clock_mhz);
+
 const char *abft_strerror(int code);
 /* hipError_t value of the last failing HIP call on this context (0 if none). */
 int abft_last_hip_error(const abft_ctx *ctx);

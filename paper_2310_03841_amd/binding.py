@@ -23,7 +23,7 @@ __all__ = [
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
     "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_gemm_static", "abft_verify", "abft_correct",
     "abft_correct_checksum", "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
-    "abft_version", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
+    "abft_version", "abft_mfma_peak", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
 
 ABFT_I8, ABFT_BF16, ABFT_F16 = 0, 1, 2
@@ -95,6 +95,8 @@ _SIGS = {
     "abft_profile_begin": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "abft_profile_end": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_double),
                                         ctypes.POINTER(ctypes.c_int)]),
+    "abft_mfma_peak": (ctypes.c_int, [ctypes.c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.POINTER(ctypes.c_double)]),
     "abft_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "abft_last_hip_error": (ctypes.c_int, [ctypes.c_void_p]),
     "abft_version": (ctypes.c_int, []),
@@ -252,6 +254,15 @@ def abft_profile_end(ctx):
     if rc != ABFT_OK:
         raise AbftError(rc, "abft_profile_end")
     return [float(x) for x in ms], n.value
+
+
+def abft_mfma_peak(dtype: int, seconds: float = 0.1):
+    """(1e12 operations per second of a matrix-instruction-only kernel, shader clock in MHz)."""
+    t, c = ctypes.c_double(), ctypes.c_double()
+    rc = lib().abft_mfma_peak(dtype, float(seconds), ctypes.byref(t), ctypes.byref(c))
+    if rc != ABFT_OK:
+        raise AbftError(rc, "abft_mfma_peak")
+    return t.value, c.value
 
 
 def abft_tile_shape(dtype: int, shape: abft_shape):

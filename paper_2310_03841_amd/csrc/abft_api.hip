@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <mutex>
 #include <new>
+#include <vector>
 #include <string.h>
 
 #include "../../include/abft.h"
@@ -756,6 +757,51 @@ extern "C" int abft_profile_end(abft_ctx *ctx, double ms[4], int *calls)
     *calls = n;
     prof_free(ctx);
     return ABFT_OK;
+}
+
+extern "C" int abft_mfma_peak(abft_dtype dtype, double seconds, double *tera_ops, double *clock_mhz)
+{
+    if (!tera_ops || !clock_mhz || !(seconds > 0.0) || seconds > 2.0) return ABFT_EINVAL;
+    if (dtype != ABFT_I8 && dtype != ABFT_BF16 && dtype != ABFT_F16) return ABFT_EINVAL;
+    hipError_t e = hipSuccess;
+    const int cus = device_cu_count(&e);
+    if (e != hipSuccess || cus <= 0) return ABFT_EHIP;
+    unsigned long long *clk = nullptr;
+    uint32_t *sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = ABFT_EHIP;
+    std::vector<unsigned long long> h((size_t)2 * cus);
+    const double ops_per_iter = (double)cus * 4 * 16 * 2.0 * 32 * 32 * (dtype == ABFT_I8 ? 32 : 16);
+    float ms = 0.f;
+    int iters = 2000;
+    if (hipMalloc(&clk, sizeof(unsigned long long) * 2 * cus) != hipSuccess) goto out;
+    if (hipMalloc(&sink, 256 * 4) != hipSuccess) goto out;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto out;
+    // a short run sizes the long one; only the long one is reported
+    for (int pass = 0; pass < 2; ++pass) {
+        if (hipEventRecord(e0, nullptr) != hipSuccess) goto out;
+        if (launch_mfma_peak(dtype, cus, iters, clk, sink, nullptr) != hipSuccess) goto out;
+        if (hipEventRecord(e1, nullptr) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) goto out;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess || !(ms > 0.f)) goto out;
+        if (pass == 0) {
+            double want = iters * (seconds * 1e3 / ms);
+            iters = want > 5e7 ? 50000000 : (want < 2000 ? 2000 : (int)want);
+        }
+    }
+    if (hipMemcpy(h.data(), clk, sizeof(unsigned long long) * 2 * cus, hipMemcpyDeviceToHost) != hipSuccess) goto out;
+    {
+        double cyc = 0, wall = 0;
+        for (int i = 0; i < cus; ++i) { cyc += (double)h[2 * i]; wall += (double)h[2 * i + 1]; }
+        *tera_ops = ops_per_iter * iters / (ms * 1e-3) / 1e12;
+        *clock_mhz = wall > 0 ? cyc / wall * 100.0 : 0.0;      // the constant counter runs at 100 MHz
+    }
+    rc = ABFT_OK;
+out:
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (clk) (void)hipFree(clk);
+    if (sink) (void)hipFree(sink);
+    return rc;
 }
 
 extern "C" int abft_tile_shape(abft_dtype dtype, const abft_shape *s, int *tile_m, int *tile_n)

@@ -66,6 +66,12 @@ struct Verdict {                    // caller buffers
     float tau_override;
 };
 
+// Raises the dynamic-LDS limit of a kernel, once per (kernel, device); contexts may be driven
+// from several host threads, so the bookkeeping is behind a mutex.
+hipError_t ensure_max_lds(const void *kernel, int bytes);
+// Compute units of the current device (cached per device, thread-safe); 0 on error.
+int device_cu_count(hipError_t *err);
+
 // ---- launchers (each enqueues on `st`, returns the hipError_t of the launch) ----
 hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st);
 // zero_ptr / zero_words: a region every block of the pass helps to clear (may be null / 0)
@@ -110,5 +116,8 @@ hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, bool stored_sum
                             const Shape &s, const Workspace &w, const Verdict *v, const InjectArm &arm,
                             hipStream_t st);
 void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn);
+// report helper: `blocks` workgroups of four waves issue iters x 16 matrix instructions each;
+// clk[2 b], clk[2 b + 1] = shader-clock and 100 MHz ticks workgroup b spent in its loop
+hipError_t launch_mfma_peak(int dt, int blocks, int iters, unsigned long long *clk, uint32_t *sink, hipStream_t st);
 
 }  // namespace abft

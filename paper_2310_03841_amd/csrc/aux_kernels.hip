@@ -7,9 +7,49 @@
 // for integers and a tolerance for floating point follow item (2) there; the
 // tile recompute is the replay correction of Sec. III-B.3 at tile granularity;
 // the flip is the fault model of Sec. II-A / III-A.
+#include <mutex>
+
 #include "abft_device.h"
 
 namespace abft {
+
+// ======================================================================== per-device launch state
+static std::mutex g_launch_lock;
+
+hipError_t ensure_max_lds(const void *kernel, int bytes)
+{
+    struct Done { const void *kernel; int device; };
+    static Done done[512];
+    static int n_done = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> hold(g_launch_lock);
+    for (int i = 0; i < n_done; ++i)
+        if (done[i].kernel == kernel && done[i].device == dev) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    if (n_done < 512) done[n_done++] = Done{kernel, dev};
+    return hipSuccess;
+}
+
+int device_cu_count(hipError_t *err)
+{
+    static int cus[64];
+    int dev = 0, n = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= 64)) e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> hold(g_launch_lock);
+        if (cus[dev] == 0) {
+            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) cus[dev] = n > 0 ? n : 256;
+        }
+        n = cus[dev];
+    }
+    if (err) *err = e;
+    return e == hipSuccess ? n : 0;
+}
 
 // ======================================================================== zero
 __global__ void zero_kernel(uint32_t *p, size_t n)
@@ -1253,13 +1293,8 @@ template <int DT>
 static hipError_t launch_recompute(const FixArgs &f, hipStream_t st)
 {
     auto kern = recompute_kernel<DT>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)FIX_LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    hipError_t e = ensure_max_lds(reinterpret_cast<const void *>(kern), (int)FIX_LDS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(MAX_FIX_TILES), dim3(64 * (FIX_WAVES + 1)), FIX_LDS_BYTES, st, f);
     return hipGetLastError();
 }
@@ -1396,6 +1431,69 @@ hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row
 {
     long idx = batch_idx * s.sC + row * s.ldc + col;
     hipLaunchKernelGGL(flip_kernel, dim3(1), dim3(64), 0, st, (uint8_t *)C, idx, out_size(dt), bit);
+    return hipGetLastError();
+}
+
+// ====================================================================== report: matrix-pipe ceiling
+// Nothing but matrix instructions, in the GEMM kernel's own shape: one wave per SIMD, sixteen
+// independent 32 x 32 accumulators (all 256 accumulator registers), operands held in registers.
+// What it reaches is the ceiling of the matrix pipe at the clock the chip sustains under that
+// load; the fraction of it a GEMM kernel reaches says how well its loop feeds the pipe, apart
+// from the clock.  Every wave also reads the shader clock counter and the constant 100 MHz
+// counter around its loop, which gives the clock it ran at.
+template <int DT>
+__global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, unsigned long long *clk, uint32_t *sink)
+{
+    using T = Traits<DT>;
+    typedef typename T::accv_t accv_t;
+    // Operands with the bit activity of real data: random signs and mantissas, magnitudes in
+    // [1/128, 1), four different register sets taken in turn.  (With operands that never change
+    // the matrix pipe toggles few bits, draws little power and keeps a clock no GEMM on real data
+    // is granted.)
+    uint32_t h = (uint32_t)(blockIdx.x * 256 + threadIdx.x) * 2654435761u + 12345u;
+    auto next = [&]() __attribute__((always_inline)) -> int {
+        h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+        uint32_t w = h;
+        if (DT == DT_BF16) w = (w & 0x807F807Fu) | 0x3C003C00u | ((w >> 3) & 0x03800380u);
+        if (DT == DT_F16) w = (w & 0x83FF83FFu) | 0x20002000u | ((w >> 3) & 0x1C001C00u);
+        return (int)w;
+    };
+    i32x4 a[4], b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        a[q] = i32x4{next(), next(), next(), next()};
+        b[q] = i32x4{next(), next(), next(), next()};
+    }
+    accv_t acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = T::zero();
+    const unsigned long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = T::mfma(b[j & 3], a[(j >> 2) & 3], acc[j]);
+    }
+    const unsigned long long c1 = clock64(), w1 = wall_clock64();
+    // keep the accumulators alive
+    typename T::acc_t t = T::zero();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) t = add_t(t, acc[j][j]);
+    if (as_word(t) == 0x7FC12345u) sink[threadIdx.x] = as_word(t);
+    if (threadIdx.x == 0) {
+        clk[2 * blockIdx.x] = c1 - c0;
+        clk[2 * blockIdx.x + 1] = w1 - w0;
+    }
+}
+
+hipError_t launch_mfma_peak(int dt, int blocks, int iters, unsigned long long *clk, uint32_t *sink, hipStream_t st)
+{
+    switch (dt) {
+    case DT_I8:   hipLaunchKernelGGL(mfma_peak_kernel<DT_I8>, dim3(blocks), dim3(256), 0, st, iters, clk, sink); break;
+    case DT_BF16: hipLaunchKernelGGL(mfma_peak_kernel<DT_BF16>, dim3(blocks), dim3(256), 0, st, iters, clk, sink); break;
+    case DT_F16:  hipLaunchKernelGGL(mfma_peak_kernel<DT_F16>, dim3(blocks), dim3(256), 0, st, iters, clk, sink); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -264,8 +264,6 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
 }
 
 // ------------------------------------------------------------------------------------------
-static int g_num_cu = 0;
-
 // How many tile rows get 256-row tiles (the rest of M gets 128-row tiles).  Workgroups are
 // dispatched in index order to whichever CU is free, one per CU; a 128 x 256 tile takes about
 // 0.62 of the time of a 256 x 256 tile (measured), not half: its main loop waits on the same
@@ -326,22 +324,12 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
     constexpr int smem_main = 2 * (256 + 256) * SLAB_BYTES;
     constexpr int smem_max = 160 * 1024;
     auto kern = gemm_fast_kernel<DT, PROT>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
-    if (g_num_cu == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        g_num_cu = n > 0 ? n : 256;
-    }
+    hipError_t e = ensure_max_lds(reinterpret_cast<const void *>(kern), smem_max);
+    if (e != hipSuccess) return e;
+    const int num_cu = device_cu_count(&e);
+    if (e != hipSuccess) return e;
     g.tiles_n = (g.N + 255) / 256;
-    const int big_rows = choose_big_rows(g.M, g.tiles_n, batch, g_num_cu);
+    const int big_rows = choose_big_rows(g.M, g.tiles_n, batch, num_cu);
     g.tiles_m_big = big_rows;
     g.n_big = big_rows * g.tiles_n;
     const int rest = g.M - big_rows * 256;

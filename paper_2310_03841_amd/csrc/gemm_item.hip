@@ -1002,13 +1002,8 @@ template <int DT, int WM, int TPW, bool PROT, bool TRANSB, bool RES, bool STO>
 static hipError_t launch_item_sto(const ItemArgs &g, size_t smem, hipStream_t st)
 {
     auto kern = gemm_item_kernel<DT, WM, TPW, PROT, TRANSB, RES, STO>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, ITEM_LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    hipError_t e = ensure_max_lds(reinterpret_cast<const void *>(kern), ITEM_LDS_LIMIT);
+    if (e != hipSuccess) return e;
     const unsigned blocks = (unsigned)(g.batch < ITEM_MAX_BLOCKS ? g.batch : ITEM_MAX_BLOCKS);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(RES ? 256 : ITEM_THREADS), smem, st, g);
     return hipGetLastError();

@@ -244,12 +244,9 @@ static hipError_t launch_one(const GemmArgs &g, int batch, hipStream_t st)
     constexpr int smem_main = 2 * (BM + BN) * SLAB_BYTES;
     constexpr int smem_max = smem_main + (PROT ? (4096 + SLAB_BYTES) * 8 : 0);
     auto kern = gemm_kernel<DT, BM, BN, PROT, TRANSB>;
-    static bool attr_done = false;
-    if (!attr_done && smem_max > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
+    if (smem_max > 48 * 1024) {
+        hipError_t e = ensure_max_lds(reinterpret_cast<const void *>(kern), smem_max);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     size_t smem = smem_main;
     if (PROT) {

@@ -12,7 +12,7 @@ import torch
 import abft_inputs as gen
 import oracle as orc
 import paper_2310_03841_amd as ab
-from gpu_util import Run
+from abft_harness import Run
 
 pytestmark = pytest.mark.gpu
 
@@ -371,7 +371,7 @@ def test_corrupted_checksum_is_one_sided(ctx):
     run = Run(ctx, "i8", A, B, True)
     run.gemm(ab.ABFT_DETECT)
     ptr, n = ab.abft_workspace(ctx, ab.ABFT_WS_RC_PRED, run.shape)
-    from gpu_util import _DevView
+    from abft_harness import _DevView
     t = torch.as_tensor(_DevView(ptr, n, "<i4"), device="cuda")
     t[10] += 1
     torch.cuda.synchronize()
@@ -443,15 +443,13 @@ def test_argument_errors(ctx):
     assert run.cnt()[2] == ab.ABFT_CLEAN
 
 
-def test_full_size_bench_workload_sampled(ctx_big):
-    """The benchmark workload at full size (ViT-B fc1, batch 64, bf16), in the launch configuration
-    bench.py times.  The oracle recomputes a seeded sample of full rows of C one by one, all four
-    checksum vectors exactly (O(MK + KN + K(M+N)) work), and the flags must be clean."""
-    dtype = "bf16"
-    g = gen.CONFIGS[1]["gemms"][0]
-    M, N, K = g["M"], g["N"], g["K"]
-    A, B = gen.gen_operands(dtype, M, N, K, gen.seed_for(1, 0), gen.seed_for(1, 1), trans_b=True)
-    run = Run(ctx_big, dtype, A, B, True)
+def _full_size_fp(ctx, dtype, M, N, K, seed_a, seed_b, sample_seed, edge_rows):
+    """A floating-point GEMM at full size, in the launch configuration bench.py times: every element
+    of C, all checksum vectors (the oracle computes all of it in a few seconds), clean flags; then
+    seeded stored-C flips far above the tolerance are localised and repaired bit for bit, and with
+    the stored-side sums also a mantissa flip far below it."""
+    A, B = gen.gen_operands(dtype, M, N, K, seed_a, seed_b, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
     run.gemm(ab.ABFT_DETECT)
     rf, cf = run.flags()
     cnt = run.cnt()
@@ -471,30 +469,65 @@ def test_full_size_bench_workload_sampled(ctx_big):
     assert np.max(np.abs(run.ws(ab.ABFT_WS_CC_OBS)[0] - cc)) <= tol * np.sqrt(M)
     assert np.max(np.abs(run.ws(ab.ABFT_WS_RC_OBS)[0] - rc)) <= tol * np.sqrt(N)
     assert abs(run.ws(ab.ABFT_WS_S_PRED)[0, 0] - s) <= 1e-4 * K * M * N * ma * mb
-    # sampled rows: every tile row region incl. the 128-row tiles at the bottom and the last row
-    rng = np.random.default_rng(gen.seed_for(1, 7))
-    rows = np.unique(np.concatenate([rng.integers(0, M, 24), [0, 255, 256, 10751, 10752, 10880, M - 1]]))
+    # the whole of C, element by element
     C = run.C()[0]
-    ref = orc.gemm(np.ascontiguousarray(Ad[rows]), Bd, True)
-    got = orc.decode(C[rows], dtype)
+    ref = orc.gemm(Ad, Bd, True)
+    got = orc.decode(C, dtype)
     scale = np.max(np.abs(ref))
-    assert np.max(np.abs(got - ref)) <= 1e-2 * scale
-    assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 2e-6 * scale + 1e-7)
-    assert np.mean(C[rows] != orc.store(ref, dtype)) < 5e-3
-    # a stored flip at full size: verify localises it, correct restores the bits
+    ulp = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11
+    err = np.abs(got - ref)
+    assert np.max(err) <= 1e-2 * scale
+    assert np.all(err <= ulp * np.abs(ref) + 2e-6 * scale + 1e-7)
+    assert np.mean(C != orc.store(ref, dtype)) < 5e-3       # fp32 noise across a rounding boundary
+    del err, got
+    # stored flips at full size: an exponent flip of a small element is far above tau
     C_before = run.dC.clone()
-    i, j, bit = 11000, 2999, 14
+    rng = np.random.default_rng(sample_seed)
+    top = 14                                                 # bf16 and fp16: the top exponent bit
+    ok = (np.abs(ref) > 0.05) & (np.abs(ref) < 0.5)         # setting bit 14 multiplies these by 2^16 or more
+    cand = np.argwhere(ok)
+    picks = [tuple(cand[k]) for k in rng.integers(0, len(cand), 4)] + \
+            [(r, int(np.flatnonzero(ok[r])[-1])) for r in edge_rows]
+    for (i, j) in picks:
+        i, j = int(i), int(j)
+        run.inject(0, i, j, top)
+        run.verify()
+        rf, cf = run.flags()
+        assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j] and run.cnt()[2] == ab.ABFT_LOCALISED
+        run.correct()
+        assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
+    # with the stored-side sums a mantissa flip below tau is seen as well
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS)
+    assert run.cnt()[2] == ab.ABFT_CLEAN and torch.equal(run.dC, C_before)
+    i = int(rng.integers(0, M))
+    j = int(np.argmax(np.abs(ref[i])))
+    bit = 3 if dtype == "bf16" else 6                        # |delta| = |C| / 16
+    assert tau / 100 < abs(ref[i, j]) / 16 < tau / 2
     run.inject(0, i, j, bit)
     run.verify()
     rf, cf = run.flags()
-    assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j] and run.cnt()[2] == ab.ABFT_LOCALISED
+    assert rf.sum() == 1 and cf.sum() == 1 and rf[0, i] and cf[0, j]
     run.correct()
-    assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
+    assert torch.equal(run.dC, C_before) and run.cnt()[2] == ab.ABFT_CLEAN
 
 
-def test_full_size_int8_fc2_sampled(ctx_big):
-    """ViT-B fc2 at batch 32 in int8 (the injection-campaign GEMM): exact checksums in Z/2^32 at
-    full size, sampled rows bit-exact, a handful of seeded flips detected, localised, repaired."""
+def test_full_size_bench_workload(ctx_big):
+    """The benchmark workload (ViT-B fc1, batch 64, bf16: 12608 x 3072 x 768)."""
+    g = gen.CONFIGS[1]["gemms"][0]
+    _full_size_fp(ctx_big, "bf16", g["M"], g["N"], g["K"], gen.seed_for(1, 0), gen.seed_for(1, 1), gen.seed_for(1, 7),
+                  [0, 255, 256, 10751, 10752, 10880, g["M"] - 1])
+
+
+def test_full_size_fp16_fc2(ctx_big):
+    """The fp16 leg of the injection campaign (ViT-B fc2 at batch 32: 6304 x 768 x 3072)."""
+    g = gen.CONFIGS[4]["gemms"][0]
+    _full_size_fp(ctx_big, "f16", g["M"], g["N"], g["K"], gen.seed_for(4, 2), gen.seed_for(4, 3), gen.seed_for(4, 8),
+                  [0, 127, 128, 6143, 6144, g["M"] - 1])
+
+
+def test_full_size_int8_fc2(ctx_big):
+    """ViT-B fc2 at batch 32 in int8 (the injection-campaign GEMM): every element of C bit-exact,
+    exact checksums in Z/2^32 at full size, seeded flips detected, localised, repaired."""
     g = gen.CONFIGS[4]["gemms"][0]
     M, N, K = g["M"], g["N"], g["K"]
     A, B = gen.gen_operands("i8", M, N, K, gen.seed_for(4, 0), gen.seed_for(4, 1), trans_b=True)
@@ -508,11 +541,9 @@ def test_full_size_int8_fc2_sampled(ctx_big):
                         (ab.ABFT_WS_RC_PRED, rc), (ab.ABFT_WS_CC_OBS, cc), (ab.ABFT_WS_RC_OBS, rc)):
         assert np.array_equal(run.ws(which)[0].view(np.uint32), ring(want)), which
     assert run.ws(ab.ABFT_WS_S_PRED)[0, 0].view(np.uint32) == ring(s)
-    rng = np.random.default_rng(gen.seed_for(4, 7))
-    rows = np.unique(np.concatenate([rng.integers(0, M, 16), [0, 6143, 6144, M - 1]]))
-    ref = orc.gemm(np.ascontiguousarray(A[0][rows]), B[0], True)
+    ref = orc.gemm(A[0], B[0], True)
     C = run.C()[0]
-    assert np.array_equal(C[rows], ref.astype(np.int32))
+    assert np.array_equal(C, ref.astype(np.int32))
     C_before = run.dC.clone()
     for (_, i, j, bit) in gen.gen_flips(12, M, N, "i8", gen.seed_for(4, 9)):
         i, j, bit = int(i), int(j), int(bit)
@@ -869,7 +900,7 @@ def test_leading_dimensions_and_batch_strides(ctx_items, dtype, M, N, K, batch, 
         assert np.all(Ch[:, M:, :] == 0x1234) and np.all(Ch[:, :, N:] == 0x1234), "wrote outside C"
     c = cnt.cpu().numpy()
     assert not rf.cpu().numpy().any() and not cf.cpu().numpy().any() and c[0] == 0 and c[1] == 0 and c[2] == ab.ABFT_CLEAN
-    from gpu_util import read_ws
+    from abft_harness import read_ws
     kind = "i" if dtype == "i8" else "f"
     ccp = read_ws(ctx, ab.ABFT_WS_CC_PRED, shape, kind).reshape(batch, -1)
     rcp = read_ws(ctx, ab.ABFT_WS_RC_PRED, shape, kind).reshape(batch, -1)

@@ -7,7 +7,7 @@ import torch
 
 import abft_inputs as gen
 import paper_2310_03841_amd as ab
-from gpu_util import Run
+from abft_harness import Run
 
 pytestmark = pytest.mark.gpu
 
