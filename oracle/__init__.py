@@ -22,6 +22,10 @@ Steps, in the order of the paper's checksum description (Sec. III-B.1,
   localise        flagged rows x flagged columns
   correct         flagged elements take the recomputed value (replay,
                   Sec. III-B.3, at element granularity)
+  with_bias       the layer bias added to every output row and its share in
+                  every checksum (Sec. III-B.1 "Checksums")
+  calibrated_*    thresholds read off pooled fault-free discrepancies at a
+                  confidence level (Sec. III-B.1 "Eps Generation")
 
 Readings of the paper where it is silent (kept in one place):
   * integer checksums live in the ring Z/2^32 (Sec. III-B.1 item (1) names the
@@ -143,11 +147,17 @@ def decode_stored(X: np.ndarray, dtype: str) -> np.ndarray:
 
 
 def flip(X: np.ndarray, row: int, col: int, bit: int) -> np.ndarray:
-    """Copy of the stored matrix X (int32 or uint16 bits) with one bit of one element inverted."""
+    """Copy of the stored matrix X with one bit of one element inverted (the single-bit-flip fault
+    model of Sec. II-A / III-A).  X is an output (int32 or uint16 bits) or an operand (int8 or
+    uint16 bits: flips in inputs and weights are the other injection sites the paper names)."""
     Y = np.array(X, copy=True)
     if Y.dtype == np.int32:
         u = Y.view(np.uint32)
         u[row, col] ^= np.uint32(1 << bit)
+    elif Y.dtype == np.int8:
+        assert 0 <= bit < 8
+        u = Y.view(np.uint8)
+        u[row, col] ^= np.uint8(1 << bit)
     else:
         assert Y.dtype == np.uint16 and 0 <= bit < 16
         Y[row, col] ^= np.uint16(1 << bit)
@@ -319,20 +329,39 @@ class Protected:
     extra: dict = field(default_factory=dict)
 
 
-def protected_gemm(A_bits: np.ndarray, B_bits: np.ndarray, dtype: str, trans_b: bool) -> Protected:
-    """Run decode, gemm, encode, predict on one (un-batched) pair of stored operands."""
+def with_bias(C_ref, cc_pred, rc_pred, s_pred, bias):
+    """A layer with a bias: every row of the output has the bias vector added, so the checksum
+    product is adjusted by the bias (Sec. III-B.1 "Checksums": the product of the two input-side
+    checksums, adjusted by the layer bias, is what the sum of the activations is compared with).
+    Summed over the M rows a column gains M bias[j]; summed over the columns a row gains
+    sum_j bias[j]; the scalar gains M sum_j bias[j].  bias: int64 (integer path) or fp64, length N."""
+    M = C_ref.shape[0]
+    bias = np.asarray(bias, dtype=C_ref.dtype)
+    assert bias.shape == (C_ref.shape[1],)
+    sb = bias.sum()
+    return C_ref + bias[None, :], cc_pred + M * bias, rc_pred + sb, s_pred + M * sb
+
+
+def protected_gemm(A_bits: np.ndarray, B_bits: np.ndarray, dtype: str, trans_b: bool, bias=None) -> Protected:
+    """Run decode, gemm, encode, predict on one (un-batched) pair of stored operands.
+    bias: optional length-N vector (int32 values for the integer path, fp32 otherwise) added to
+    every row of the product before it is stored."""
     if dtype == "i8":
         A = np.ascontiguousarray(A_bits, dtype=np.int8)
         Bm = np.ascontiguousarray(B_bits, dtype=np.int8)
         C_ref = gemm(A, Bm, trans_b)
         a, b = encode(A, Bm, trans_b)
         cc, rc, s = predict(A, Bm, a, b, trans_b)
+        if bias is not None:
+            C_ref, cc, rc, s = with_bias(C_ref, cc, rc, s, np.asarray(bias).astype(np.int64))
         return Protected(dtype, C_ref, store(C_ref, dtype), a, b, cc, rc, s)
     A = decode(A_bits, dtype)
     Bm = decode(B_bits, dtype)
     C_ref = gemm(A, Bm, trans_b)
     a, b = encode(A, Bm, trans_b)
     cc, rc, s = predict(A, Bm, a, b, trans_b)
+    if bias is not None:
+        C_ref, cc, rc, s = with_bias(C_ref, cc, rc, s, np.asarray(bias, dtype=np.float32).astype(np.float64))
     K = A.shape[1]
     ma, mb = float(np.max(np.abs(A))), float(np.max(np.abs(Bm)))
     return Protected(dtype, C_ref, store(C_ref, dtype), a, b, cc, rc, s,
@@ -387,6 +416,24 @@ def discrepancy_stats(P: Protected, X_stored: np.ndarray):
         d = np.asarray(obs, dtype=np.float64) - np.asarray(pred, dtype=np.float64)
         out[name] = (float(d.sum()), float((d * d).sum()), float(np.max(np.abs(d))), int(d.size))
     return out
+
+
+def confidence_z(confidence: float) -> float:
+    """Half-width, in standard deviations, of the central interval of a normal distribution that
+    holds `confidence` of its mass (0.999 -> 3.2905, 0.9999 -> 3.8906): the confidence levels at
+    which the paper reads its thresholds off the fitted discrepancy distribution (Sec. III-B.1
+    "Eps Generation", Sec. IV-C)."""
+    from statistics import NormalDist
+    assert 0.0 < confidence < 1.0
+    return NormalDist().inv_cdf(0.5 + 0.5 * confidence)
+
+
+def calibrated_thresholds(row_stats, col_stats, confidence: float):
+    """Eps generation over pooled fault-free runs, one threshold for the row check and one for the
+    column check: each is |mean| + z(confidence) * std of the discrepancies of its side, pooled
+    over every (sum, sumsq, maxabs, count) tuple given for that side.  Returns (tau_rows, tau_cols)."""
+    z = confidence_z(confidence)
+    return calibrated_tau(row_stats, z), calibrated_tau(col_stats, z)
 
 
 def calibrated_tau(stats, z: float) -> float:

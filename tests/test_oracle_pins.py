@@ -424,3 +424,101 @@ def test_weight_fault_after_encoding_shows_on_the_row_side_only():
     assert np.array_equal(rf, A[:, k] != 0) and not cf.any()
     E, status = orc.localise(rf, cf)
     assert E == [] and status == orc.CHECKSUM_SUSPECT
+
+
+# ------------------------------------------------------------------ bias, operand flips, confidence levels
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_bias_moves_every_checksum_by_its_closed_form(dtype):
+    """Sec. III-B.1 "Checksums": the checked product is adjusted by the layer bias.  Closed forms:
+    a constant bias c moves every element by c, every column sum by M c, every row sum by N c
+    and the scalar by M N c; a general bias moves column j by M bias[j] and every row by
+    sum(bias); with A = 0 the output is the bias in every row; and the identity observed ==
+    predicted still holds (exactly for integers)."""
+    M, N, K = 9, 14, 24
+    A, B = gen.gen_operands(dtype, M, N, K, 71, 72, trans_b=True)
+    P0 = orc.protected_gemm(A[0], B[0], dtype, True)
+    c = 3
+    Pc = orc.protected_gemm(A[0], B[0], dtype, True, bias=np.full(N, c))
+    assert np.array_equal(Pc.C_ref, P0.C_ref + c)
+    assert np.allclose(Pc.cc_pred, P0.cc_pred + M * c, rtol=0, atol=1e-9)
+    assert np.allclose(Pc.rc_pred, P0.rc_pred + N * c, rtol=0, atol=1e-9)
+    assert abs(Pc.s_pred - (P0.s_pred + M * N * c)) <= 1e-9
+    rng = np.random.default_rng(5)
+    bias = rng.integers(-1000, 1000, N) if dtype == "i8" else rng.standard_normal(N).astype(np.float32)
+    Pb = orc.protected_gemm(A[0], B[0], dtype, True, bias=bias)
+    bw = np.asarray(bias, dtype=np.int64 if dtype == "i8" else np.float64)
+    for j in range(N):
+        assert np.allclose(Pb.C_ref[:, j], P0.C_ref[:, j] + bw[j], rtol=0, atol=1e-12)
+    # library cross-check of the adjusted checksums and the identity on the product itself
+    assert np.allclose(Pb.cc_pred, Pb.C_ref.sum(axis=0), rtol=1e-12, atol=1e-9)
+    assert np.allclose(Pb.rc_pred, Pb.C_ref.sum(axis=1), rtol=1e-12, atol=1e-9)
+    cc_obs, rc_obs, s_obs = orc.observe(Pb.C_ref)
+    if dtype == "i8":
+        assert np.array_equal(cc_obs, Pb.cc_pred) and np.array_equal(rc_obs, Pb.rc_pred) and s_obs == Pb.s_pred
+        rf, cf, E, status, _, _ = orc.check(Pb, Pb.C_stored)
+        assert status == orc.CLEAN and not rf.any() and not cf.any()
+    # A = 0: the output is the bias, row by row
+    Z = np.zeros_like(A[0])
+    Pz = orc.protected_gemm(Z, B[0], dtype, True, bias=bias)
+    assert np.array_equal(Pz.C_ref, np.tile(bw, (M, 1)))
+    # a dropped bias term would be caught: the adjusted prediction differs from the plain one
+    assert not np.allclose(Pb.rc_pred, P0.rc_pred) and not np.allclose(Pb.cc_pred, P0.cc_pred)
+
+
+def test_operand_flips_move_one_row_or_one_column_of_the_product():
+    """Flips in inputs and weights (the other injection sites of Sec. II-A / III-A).  Linearity:
+    a flip of A[i,k] by delta moves row i of C by delta B[k,:] and nothing else; a flip of the
+    stored weight W[n,k] by delta moves column n of C by delta A[:,k].  Against checksums taken
+    before the flip: an A flip shows in the column check wherever delta B[k,j] != 0 and in row i
+    iff delta b[k] != 0; a weight flip shows in the row check wherever delta A[i,k] != 0 and in
+    column n iff delta a[k] != 0."""
+    M, N, K = 7, 9, 16
+    A, B = gen.gen_operands("i8", M, N, K, 81, 82, trans_b=True)
+    A, B = A[0], B[0]
+    P = orc.protected_gemm(A, B, "i8", True)
+    rng = np.random.default_rng(9)
+    for _ in range(20):
+        i, k, n, bit = int(rng.integers(M)), int(rng.integers(K)), int(rng.integers(N)), int(rng.integers(8))
+        A2 = orc.flip(A, i, k, bit)
+        dA = int(A2[i, k]) - int(A[i, k])
+        assert dA in (1 << bit, -(1 << bit)) or (bit == 7 and abs(dA) == 128)
+        C2 = orc.gemm(A2, B, True)
+        want = P.C_ref.copy()
+        want[i, :] += dA * B[:, k].astype(np.int64)
+        assert np.array_equal(C2, want)
+        rf, cf, E, status, _, _ = orc.check(P, orc.store(C2, "i8"))
+        assert np.array_equal(cf, dA * B[:, k].astype(np.int64) != 0)
+        assert not rf.any() or rf[i]
+        assert rf.sum() == (1 if dA * int(P.b[k]) != 0 else 0)
+        B2 = orc.flip(B, n, k, bit)
+        dB = int(B2[n, k]) - int(B[n, k])
+        C3 = orc.gemm(A, B2, True)
+        want = P.C_ref.copy()
+        want[:, n] += dB * A[:, k].astype(np.int64)
+        assert np.array_equal(C3, want)
+        rf, cf, E, status, _, _ = orc.check(P, orc.store(C3, "i8"))
+        assert np.array_equal(rf, dB * A[:, k].astype(np.int64) != 0)
+        assert cf.sum() == (1 if dB * int(P.a[k]) != 0 else 0) and (not cf.any() or cf[n])
+    # 16-bit operands: the flipped pattern decodes to the hand value
+    X = np.array([[0x3FC0]], dtype=np.uint16)                    # bf16 1.5
+    assert np.isnan(orc.decode(orc.flip(X, 0, 0, 14), "bf16")[0, 0])     # exponent all ones, mantissa not zero
+    assert orc.decode(orc.flip(X, 0, 0, 7), "bf16")[0, 0] == 0.75
+    assert orc.decode(orc.flip(X, 0, 0, 6), "bf16")[0, 0] == 1.0
+
+
+def test_confidence_levels_and_separate_thresholds():
+    """Eps generation at the paper's confidence levels: textbook normal quantiles (two-sided
+    99.9 % -> 3.2905, 99.99 % -> 3.8906, 95 % -> 1.9600), and row / column thresholds fitted
+    separately from pooled statistics in closed form."""
+    assert orc.confidence_z(0.95) == pytest.approx(1.959964, abs=1e-5)
+    assert orc.confidence_z(0.999) == pytest.approx(3.290527, abs=1e-5)
+    assert orc.confidence_z(0.9999) == pytest.approx(3.890592, abs=1e-5)
+    # rows: discrepancies {+1, -1} x 50 over two runs -> mean 0, std 1; columns: all equal 2 -> std 0
+    rows = [(0.0, 50.0, 1.0, 50), (0.0, 50.0, 1.0, 50)]
+    cols = [(40.0, 80.0, 2.0, 20)]
+    tr, tc = orc.calibrated_thresholds(rows, cols, 0.999)
+    assert tr == pytest.approx(3.290527, abs=1e-5)
+    assert tc == pytest.approx(2.0, abs=1e-12)
+    # pooling is over counts, not over runs: a run with ten times the entries weighs ten times
+    rows2 = [(0.0, 0.0, 0.0, 900), (0.0, 100.0, 1.0, 100)]
+    assert orc.calibrated_tau(rows2, 1.0) == pytest.approx(np.sqrt(0.1), rel=1e-12)
