@@ -81,6 +81,20 @@ class Run:
         assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
         torch.cuda.synchronize()
 
+    def gemm_bias(self, bias, mode=ab.ABFT_DETECT):
+        """bias: device tensor of N float32 (bf16 / f16) or int32 (i8) values"""
+        rc = ab.abft_gemm_bias(self.ctx, self.dA, self.dB, bias, self.dC, self.code, mode, self.shape,
+                               None if (mode & 0xF) == ab.ABFT_OFF else self.result())
+        assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+        torch.cuda.synchronize()
+
+    def inject_operand(self, which, b, row, col, bit):
+        """which: 'A' or 'B'; (row, col) index the operand array as stored"""
+        where, ptr = (ab.ABFT_INJECT_OPERAND_A, self.dA) if which == "A" else (ab.ABFT_INJECT_OPERAND_B, self.dB)
+        rc = ab.abft_inject(self.ctx, ptr, self.code, self.shape, b, row, col, bit, where)
+        assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+        torch.cuda.synchronize()
+
     def verify(self):
         rc = ab.abft_verify(self.ctx, self.dC, self.code, self.shape, self.result())
         assert rc == ab.ABFT_OK, ab.abft_strerror(rc)

@@ -148,7 +148,7 @@ typedef enum {
 } abft_ws_id;
 
 /* where a flip lands */
-enum { ABFT_INJECT_STORED_C = 0, ABFT_INJECT_ACCUMULATOR = 1 };
+enum { ABFT_INJECT_STORED_C = 0, ABFT_INJECT_ACCUMULATOR = 1, ABFT_INJECT_OPERAND_A = 2, ABFT_INJECT_OPERAND_B = 3 };
 
 /* Allocates the context and its device workspace on cfg->device (the only call that allocates). */
 int abft_create(abft_ctx **out, const abft_config *cfg);
@@ -173,6 +173,17 @@ int abft_encode_b(abft_ctx *ctx, const void *B, abft_dtype dtype, const abft_sha
  * mode ABFT_OFF ignores `r` (may be NULL).  Flags and counts are overwritten. */
 int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
               const abft_shape *s, const abft_result *r, void *stream);
+
+/* The protected GEMM of a layer with a bias: C = A B + bias, the bias vector (DEVICE, N entries:
+ * float for ABFT_BF16 / ABFT_F16, int32 for ABFT_I8; shared by all batch items) added to every row
+ * of the product before rounding.  The checked quantity is adjusted accordingly (Sec. III-B.1
+ * "Checksums": the product of the input-side checksums is adjusted by the layer bias): the column
+ * prediction gains M bias[j], the row prediction sum_j bias[j], the scalar M sum_j bias[j]; the
+ * observed sums are taken from the biased values.  Everything else as abft_gemm (batches of small
+ * problems take the tiled kernels here).  abft_verify / abft_correct after this call use the same
+ * bias: the vector must stay valid and unchanged until they have run. */
+int abft_gemm_bias(abft_ctx *ctx, const void *A, const void *B, const void *bias, void *C,
+                   abft_dtype dtype, int mode, const abft_shape *s, const abft_result *r, void *stream);
 
 /* abft_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments (without a context), same
@@ -245,7 +256,13 @@ int abft_discrepancy(abft_ctx *ctx, abft_dtype dtype, const abft_shape *s, int s
 /* Test hook for the single-bit-flip fault model.  ABFT_INJECT_STORED_C inverts bit `bit`
  * (0..31 for int32 C, 0..15 for bf16/f16 C) of C[batch_idx][row][col] on the stream.
  * ABFT_INJECT_ACCUMULATOR arms a one-shot flip of bit 0..31 of the int32/fp32 accumulator of
- * that element, applied inside the next abft_gemm before its epilogue (C may be NULL). */
+ * that element, applied inside the next abft_gemm before its epilogue (C may be NULL).
+ * ABFT_INJECT_OPERAND_A / _B (the input and weight sites of the same fault model): `C` is the
+ * operand's device pointer; (row, col) index the array as stored (A: M x K; B: N x K with
+ * transB, else K x N); bit 0..7 for ABFT_I8, 0..15 otherwise.  What the checks see of such a flip
+ * depends on when the checksums were taken: a flip before abft_gemm is part of the operands the
+ * call encodes (consistent, hence silent); a weight flipped after abft_encode_b and used with
+ * ABFT_B_CHECKSUM_CACHED shows as row flags in every row i with A[i,k] != 0. */
 int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_shape *s, int64_t batch_idx,
                 int64_t row, int64_t col, int bit, int where, void *stream);
 

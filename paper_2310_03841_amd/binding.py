@@ -17,11 +17,11 @@ __all__ = [
     "ABFT_I8", "ABFT_BF16", "ABFT_F16", "ABFT_OFF", "ABFT_DETECT", "ABFT_DETECT_CORRECT",
     "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
     "ABFT_EHIP", "ABFT_ESTATE", "ABFT_CLEAN", "ABFT_LOCALISED", "ABFT_CHECKSUM_SUSPECT", "ABFT_TOO_MANY",
-    "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR",
+    "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR", "ABFT_INJECT_OPERAND_A", "ABFT_INJECT_OPERAND_B",
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
     "ABFT_WS_RC_OBS", "ABFT_WS_CC_VOBS", "ABFT_WS_RC_VOBS", "ABFT_WS_TAU", "ABFT_WS_S_PRED", "ABFT_WS_MAXABS", "ABFT_WS_CC_STO", "ABFT_WS_RC_STO",
     "abft_shape", "abft_config", "abft_result", "AbftError", "lib", "lib_path", "exported_symbols",
-    "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_gemm_static", "abft_verify", "abft_correct",
+    "abft_create", "abft_destroy", "abft_encode_b", "abft_gemm", "abft_gemm_bias", "abft_gemm_static", "abft_verify", "abft_correct",
     "abft_correct_checksum", "abft_inject", "abft_discrepancy", "abft_workspace", "abft_tile_shape", "abft_strerror", "abft_last_hip_error",
     "abft_version", "abft_mfma_peak", "abft_profile_begin", "abft_profile_end", "make_shape", "make_result", "DTYPE_CODE",
 ]
@@ -34,7 +34,7 @@ ABFT_STORED_SUMS = 0x20
 ABFT_DISC_FUSED, ABFT_DISC_STORED = 0, 1
 ABFT_OK, ABFT_EINVAL, ABFT_EALIGN, ABFT_ESHAPE, ABFT_EWORKSPACE, ABFT_EHIP, ABFT_ESTATE = 0, -1, -2, -3, -4, -5, -6
 ABFT_CLEAN, ABFT_LOCALISED, ABFT_CHECKSUM_SUSPECT, ABFT_TOO_MANY = 0, 1, 2, 3
-ABFT_INJECT_STORED_C, ABFT_INJECT_ACCUMULATOR = 0, 1
+ABFT_INJECT_STORED_C, ABFT_INJECT_ACCUMULATOR, ABFT_INJECT_OPERAND_A, ABFT_INJECT_OPERAND_B = 0, 1, 2, 3
 (ABFT_WS_A_SUM, ABFT_WS_B_SUM, ABFT_WS_CC_PRED, ABFT_WS_RC_PRED, ABFT_WS_CC_OBS, ABFT_WS_RC_OBS,
  ABFT_WS_CC_VOBS, ABFT_WS_RC_VOBS, ABFT_WS_TAU, ABFT_WS_S_PRED, ABFT_WS_MAXABS,
  ABFT_WS_CC_STO, ABFT_WS_RC_STO) = range(13)
@@ -72,6 +72,9 @@ _SIGS = {
     "abft_gemm": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                  ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
                                  ctypes.POINTER(abft_result), ctypes.c_void_p]),
+    "abft_gemm_bias": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
+                                      ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_gemm_static": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
                                         ctypes.POINTER(abft_result), ctypes.c_void_p]),
@@ -198,6 +201,13 @@ def abft_gemm(ctx, A, B, C, dtype: int, mode: int, shape: abft_shape, result: ab
     r = ctypes.byref(result) if result is not None else None
     return int(lib().abft_gemm(ctx, _ptr(A), _ptr(B), _ptr(C), dtype, mode, ctypes.byref(shape), r,
                                _stream(stream)))
+
+
+def abft_gemm_bias(ctx, A, B, bias, C, dtype: int, mode: int, shape: abft_shape, result: abft_result | None = None,
+                   stream=None) -> int:
+    r = ctypes.byref(result) if result is not None else None
+    return int(lib().abft_gemm_bias(ctx, _ptr(A), _ptr(B), _ptr(bias), _ptr(C), dtype, mode, ctypes.byref(shape), r,
+                                    _stream(stream)))
 
 
 def abft_gemm_static(A, B, C, dtype: int, mode: int, shape: abft_shape, result: abft_result | None = None,

@@ -42,6 +42,7 @@ struct abft_ctx {
     int64_t vobs_ldc, vobs_strideC;
     bool list_dirty;        // the tile list's counters may be non-zero (a correction failed half way)
     int b_dt, pred_dt;
+    const void *pred_bias;  // layer bias of the GEMM the predictions belong to (abft_correct adds it to recomputed tiles)
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
     hipEvent_t *prof_ev;    // 4 events per recorded call
@@ -226,6 +227,7 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->fix_tiles = c->fix_tiles;
     w->fix_count = c->small;
     w->cmp_ticket = c->small + 4;
+    w->bias = nullptr;
     (void)dt;
 }
 
@@ -362,7 +364,9 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
         int rc = begin_b_pass(ctx, st);
         if (rc) return rc;
     }
+    const uint32_t *bias = w->bias;
     carve(ctx, dtype, sh, w);
+    w->bias = bias;
     uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
     size_t stale = ctx->dirty[ctx->cur];
     if (gm && stale < w->zero_words) stale = w->zero_words;
@@ -429,8 +433,25 @@ static bool vobs_usable(const abft_ctx *ctx, const void *C, const abft_shape *s,
     return ctx->vobs_captured && capturing(st);
 }
 
+static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bias, void *C, abft_dtype dtype, int mode,
+                     const abft_shape *s, const abft_result *r, void *stream);
+
 extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, abft_dtype dtype, int mode,
                          const abft_shape *s, const abft_result *r, void *stream)
+{
+    return gemm_impl(ctx, A, B, nullptr, C, dtype, mode, s, r, stream);
+}
+
+extern "C" int abft_gemm_bias(abft_ctx *ctx, const void *A, const void *B, const void *bias, void *C,
+                              abft_dtype dtype, int mode, const abft_shape *s, const abft_result *r, void *stream)
+{
+    if (!bias) return ABFT_EINVAL;
+    if (((uintptr_t)bias & 3u) != 0) return ABFT_EALIGN;
+    return gemm_impl(ctx, A, B, bias, C, dtype, mode, s, r, stream);
+}
+
+static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bias, void *C, abft_dtype dtype, int mode,
+                     const abft_shape *s, const abft_result *r, void *stream)
 {
     const int base = mode & ABFT_MODE_MASK;
     if (base != ABFT_OFF && base != ABFT_DETECT && base != ABFT_DETECT_CORRECT) return ABFT_EINVAL;
@@ -443,6 +464,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     hipStream_t st = (hipStream_t)stream;
     Workspace w;
     carve(ctx, dtype, sh, &w);
+    w.bias = (const uint32_t *)bias;
     InjectArm arm = ctx->arm;
     if (arm.batch >= 0 && (arm.batch >= sh.batch || arm.row >= sh.M || arm.col >= sh.N)) return ABFT_EINVAL;
 
@@ -466,7 +488,7 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     const bool stored = (mode & ABFT_STORED_SUMS) != 0;
-    const bool item = gemm_item_eligible(dtype, sh, stored);
+    const bool item = !bias && gemm_item_eligible(dtype, sh, stored);
     rc = item ? enqueue_item(ctx, dtype, cached, stored, A, B, C, sh, w, v, arm, ev, st)
               : enqueue_tiled(ctx, dtype, cached, stored, A, B, C, sh, &w, v, arm, ev, st);
     if (rc) return rc;
@@ -477,12 +499,14 @@ extern "C" int abft_gemm(abft_ctx *ctx, const void *A, const void *B, void *C, a
     ctx->pred_valid = true;
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
+    ctx->pred_bias = bias;
     // a correction inside this call replaces values the stored-side sums already contain
     ctx->sto_valid = stored && base == ABFT_DETECT;
     if (base == ABFT_DETECT_CORRECT) {
         const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
         const ResumPlan rp = begin_resum(ctx, words, st);
         carve(ctx, dtype, sh, &w);
+        w.bias = (const uint32_t *)bias;
         const bool clear_list = ctx->list_dirty || ctx->graph_mode;
         ctx->list_dirty = true;
         HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, false, rp.stale, rp.other, rp.other_words, st));
@@ -600,6 +624,7 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
         // abft_verify (or an earlier correction) left the sums of this stored C: they are brought up
         // to date in place, for the rows and columns of the recomputed tiles only
         carve(ctx, dtype, sh, &w);
+        w.bias = (const uint32_t *)ctx->pred_bias;
         ctx->list_dirty = true;
         ctx->vobs_valid = false;
         HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, true, 0, nullptr, 0, st));
@@ -611,6 +636,7 @@ extern "C" int abft_correct(abft_ctx *ctx, const void *A, const void *B, void *C
     const size_t words = (size_t)sh.batch * ((size_t)sh.M + sh.N);
     const ResumPlan rp = begin_resum(ctx, words, st);
     carve(ctx, dtype, sh, &w);
+    w.bias = (const uint32_t *)ctx->pred_bias;
     ctx->list_dirty = true;
     HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, ctx->sto_valid, clear_list, false, rp.stale, rp.other,
                            rp.other_words, st));
@@ -660,6 +686,19 @@ extern "C" int abft_inject(abft_ctx *ctx, void *C, abft_dtype dtype, const abft_
                            int64_t row, int64_t col, int bit, int where, void *stream)
 {
     Shape sh;
+    if (where == ABFT_INJECT_OPERAND_A || where == ABFT_INJECT_OPERAND_B) {
+        // a bit of an element of the stored operand array: A is M x K; B is N x K or K x N as stored
+        const bool isA = where == ABFT_INJECT_OPERAND_A;
+        int rc = check_shape(ctx, dtype, s, isA ? 1 : 2, &sh, false);
+        if (rc) return rc;
+        if (!C) return ABFT_EINVAL;
+        const int64_t rows = isA ? sh.M : (sh.transB ? sh.N : sh.K), cols = isA ? sh.K : (sh.transB ? sh.K : sh.N);
+        if (batch_idx < 0 || batch_idx >= sh.batch || row < 0 || row >= rows || col < 0 || col >= cols) return ABFT_EINVAL;
+        if (bit < 0 || bit >= 8 * elem_size(dtype)) return ABFT_EINVAL;
+        const long idx = batch_idx * (isA ? sh.sA : sh.sB) + row * (isA ? sh.lda : sh.ldb) + col;
+        HIP_TRY(launch_flip_at(C, idx, elem_size(dtype), bit, (hipStream_t)stream));
+        return ABFT_OK;
+    }
     int rc = check_shape(ctx, dtype, s, where == ABFT_INJECT_STORED_C ? 4 : 0, &sh);
     if (rc) return rc;
     if (batch_idx < 0 || batch_idx >= sh.batch || row < 0 || row >= sh.M || col < 0 || col >= sh.N)

@@ -50,6 +50,9 @@ struct Workspace {
     int32_t  *fix_tiles;            // [MAX_FIX_TILES][3] (batch, tile row, tile col)
     uint32_t *fix_count;            // [4]: 0 tiles, 1 overflow flag, 2 ticket, 3 spare
     uint32_t *cmp_ticket;           // [4] ticket and counts, then [64] first-level tickets of the finish kernel
+    // not workspace, but travels with it: the layer bias of the current call (device, [N], float or
+    // int32 words; null = none).  Added to every row of the product before rounding and sums.
+    const uint32_t *bias;
 };
 
 struct Shape {
@@ -109,6 +112,8 @@ hipError_t launch_arith_fix(void *C, const Shape &s, const Workspace &w, const V
 hipError_t launch_discrepancy(const Shape &s, const Workspace &w, bool stored, float *out, hipStream_t st);
 hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,
                        hipStream_t st);
+// inverts one bit of the elem_bytes-wide element at element index idx of `base`
+hipError_t launch_flip_at(void *base, long idx, int elem_bytes, int bit, hipStream_t st);
 // Batches of small problems (attention heads): one workgroup per batch item, all checksums and
 // the comparison inside the GEMM kernel (gemm_item.hip).  v may be null when protect is false.
 bool gemm_item_eligible(int dt, const Shape &s, bool stored_sums);

@@ -358,7 +358,9 @@ struct FinArgs {
     long ldb, sB;
     int transB;
     int M, N, K;
-    const uint32_t *a_sum, *b_sum, *rc_pred, *cc_obs, *rc_obs, *a_max;
+    const uint32_t *a_sum, *b_sum, *cc_obs, *rc_obs, *a_max;
+    uint32_t *rc_pred;    // A b from the GEMM; with a bias the finish kernel adds sum(bias) in place
+    const uint32_t *bias; // layer bias [N] or null: cc_pred gains M bias[n], rc_pred sum(bias), a.b M sum(bias)
     uint32_t *cc_pred, *s_pred;
     float *maxabs, *tau;
     float tau_override;
@@ -376,6 +378,19 @@ struct FinArgs {
     uint32_t *zero2_ptr;  // second region to clear: the b slot the next pass over B will accumulate into
     size_t zero2_words;
 };
+
+// Sum of the layer bias over its N entries, by the whole block (every thread gets the total).
+template <typename acc_t>
+__device__ __forceinline__ acc_t block_bias_sum(const uint32_t *bias, int N, acc_t *red4)
+{
+    acc_t v = acc_t(0);
+    for (int n = threadIdx.x; n < N; n += 256) v = add_t(v, from_word<acc_t>(bias[n]));
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return add_t(add_t(red4[0], red4[1]), add_t(red4[2], red4[3]));
+}
 
 constexpr int FIN_KY = 8;          // k lanes of a column block over a B stored K x N
 constexpr int FIN_MAX_BLOCKS = 1024;
@@ -405,6 +420,8 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
     const int upi = f.col_blocks + row_blocks;                 // units per batch item
     const int units = upi * f.batch;                           // fits: checked by the launcher
     unsigned nr_w = 0, nc_w = 0;                               // flagged rows / columns seen by this wave
+    acc_t sb = T::zero();                                      // sum of the bias
+    if (f.bias) sb = block_bias_sum<acc_t>(f.bias, N, wred);
 
     for (int u = blockIdx.x; u < units; u += gridDim.x) {
         const int bz = u / upi, blk = u - bz * upi;
@@ -485,11 +502,12 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                 }
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const acc_t t = dot[j];
+                    acc_t t = dot[j];
                     const int n = nb + j * rpw;
                     bool fl = false;
                     if (lc == 0 && n < N && (!split || wave == 0)) {
                         const long o = (long)bz * N + n;
+                        if (f.bias) t = add_t(t, mul_t((acc_t)M, from_word<acc_t>(f.bias[n])));
                         f.cc_pred[o] = as_word(t);
                         fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
                         f.col_flag[o] = fl ? 1 : 0;
@@ -538,6 +556,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                         acc_t t = red[c];
 #pragma unroll
                         for (int y = 1; y < FIN_KY; ++y) t = add_t(t, red[y * 32 * CE + c]);
+                        if (f.bias) t = add_t(t, mul_t((acc_t)M, from_word<acc_t>(f.bias[n])));
                         const long o = (long)bz * N + n;
                         f.cc_pred[o] = as_word(t);
                         fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
@@ -551,7 +570,9 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
             bool fl = false;
             if (r < M) {
                 const long o = (long)bz * M + r;
-                fl = mismatch<T::IS_INT>(f.rc_obs[o], f.rc_pred[o], tol);
+                uint32_t rpw = f.rc_pred[o];
+                if (f.bias) { rpw = as_word(add_t(from_word<acc_t>(rpw), sb)); f.rc_pred[o] = rpw; }
+                fl = mismatch<T::IS_INT>(f.rc_obs[o], rpw, tol);
                 f.row_flag[o] = fl ? 1 : 0;
             }
             nr_w += __popcll(__ballot(fl));
@@ -564,7 +585,8 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                 __syncthreads();                                        // wred free again
                 if (lane == 0) wred[wave] = v;
                 __syncthreads();
-                if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
+                if (tid == 0)
+                    f.s_pred[bz] = as_word(add_t(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])), mul_t((acc_t)M, sb)));
             }
         }
     }
@@ -632,8 +654,10 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
     const int rpb = split ? FN_RW : 4 * FN_RW;                  // rows of B per unit
     const int units = f.col_blocks * f.batch;
     const int rshare = (M + f.col_blocks - 1) / f.col_blocks;   // rows of C a unit compares
-    const bool vec_a = (K & 3) == 0;                            // 16-byte loads of a are aligned
+    const bool vec_a = (K & 3) == 0 && ((uintptr_t)f.a_sum & 15u) == 0;     // 16-byte loads of a are aligned
     unsigned nr_w = 0, nc_w = 0;
+    acc_t sb = T::zero();                                       // sum of the bias
+    if (f.bias) sb = block_bias_sum<acc_t>(f.bias, N, wred);
 
     for (int u = blockIdx.x; u < units; u += gridDim.x) {
         const int bz = u / f.col_blocks, cb = u - bz * f.col_blocks;
@@ -642,7 +666,11 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
         // ---- everything the unit will compare against, requested first
         const int nrow0 = cb * rpb + (split ? 0 : wave * FN_RW);
         uint32_t my_obs = 0;
-        if (lane < FN_RW && nrow0 + lane < N) my_obs = f.cc_obs[(long)bz * N + nrow0 + lane];
+        acc_t my_bias = T::zero();
+        if (lane < FN_RW && nrow0 + lane < N) {
+            my_obs = f.cc_obs[(long)bz * N + nrow0 + lane];
+            if (f.bias) my_bias = mul_t((acc_t)M, from_word<acc_t>(f.bias[nrow0 + lane]));
+        }
         const int rbeg = cb * rshare, rend = min(rbeg + rshare, M);
         uint32_t ro = 0, rp = 0;
         if (rbeg + tid < rend) { ro = f.rc_obs[(long)bz * M + rbeg + tid]; rp = f.rc_pred[(long)bz * M + rbeg + tid]; }
@@ -716,6 +744,7 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
             acc_t mine = dot[0];
 #pragma unroll
             for (int j = 1; j < FN_RW; ++j) mine = lane == j ? dot[j] : mine;
+            mine = add_t(mine, my_bias);
             bool fl = false;
             if (lane < FN_RW && nrow0 + lane < N && (!split || wave == 0)) {
                 const long o = (long)bz * N + nrow0 + lane;
@@ -731,6 +760,7 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
             if (r < rend) {
                 const long o = (long)bz * M + r;
                 if (r != rbeg + tid) { ro = f.rc_obs[o]; rp = f.rc_pred[o]; }
+                if (f.bias) { rp = as_word(add_t(from_word<acc_t>(rp), sb)); f.rc_pred[o] = rp; }
                 fl = mismatch<T::IS_INT>(ro, rp, tol);
                 f.row_flag[o] = fl ? 1 : 0;
             }
@@ -745,7 +775,8 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
             __syncthreads();                                    // wred free again
             if (lane == 0) wred[wave] = sv;
             __syncthreads();
-            if (tid == 0) f.s_pred[bz] = as_word(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])));
+            if (tid == 0)
+                f.s_pred[bz] = as_word(add_t(add_t(add_t(wred[0], wred[1]), add_t(wred[2], wred[3])), mul_t((acc_t)M, sb)));
         }
     }
     if (lane == 0) { wcnt[wave][0] = nr_w; wcnt[wave][1] = nc_w; }
@@ -782,6 +813,7 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     f.B = (const uint8_t *)B; f.ldb = s.ldb; f.sB = s.sB; f.transB = s.transB;
     f.M = s.M; f.N = s.N; f.K = s.K;
     f.a_sum = w.a_sum; f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;
+    f.bias = w.bias;
     f.a_max = w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
     f.tau_override = v.tau_override;
     f.row_flag = v.row_flag; f.col_flag = v.col_flag; f.counts = v.counts; f.ticket = w.cmp_ticket;
@@ -1074,6 +1106,7 @@ struct FixArgs {
     const uint32_t *fix_count;
     uint32_t *cc_vobs;      // non-null: the re-summed column sums of the tile's columns are cleared (they are
                             // accumulated again by resum_touched_kernel)
+    const uint32_t *bias;   // layer bias [N] or null
 };
 
 template <int DT>
@@ -1184,7 +1217,11 @@ __global__ __launch_bounds__(64 * (FIX_WAVES + 1)) void recompute_kernel(FixArgs
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int gc = tc * CT + 8 * (i >> 2) + 4 * lh + (i & 3);
-        if (row < a.M && gc < a.N) T::store_c(Cb, (long)row * a.ldc + gc, acc[i]);
+        if (row < a.M && gc < a.N) {
+            typename T::acc_t v = acc[i];
+            if (a.bias) v = add_t(v, from_word<typename T::acc_t>(a.bias[gc]));
+            T::store_c(Cb, (long)row * a.ldc + gc, v);
+        }
     }
 }
 
@@ -1317,6 +1354,7 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     f.lda = s.lda; f.ldb = s.ldb; f.ldc = s.ldc; f.sA = s.sA; f.sB = s.sB; f.sC = s.sC;
     f.fix_tiles = w.fix_tiles; f.fix_count = w.fix_count;
     f.cc_vobs = targeted ? w.cc_vobs : nullptr;
+    f.bias = w.bias;
     switch (dt) {
     case DT_I8:   e = launch_recompute<DT_I8>(f, st); break;
     case DT_BF16: e = launch_recompute<DT_BF16>(f, st); break;
@@ -1420,10 +1458,18 @@ __global__ void flip_kernel(uint8_t *C, long idx, int os, int bit)
     if (os == 4) {
         uint32_t *p = reinterpret_cast<uint32_t *>(C) + idx;
         *p ^= (1u << bit);
+    } else if (os == 1) {
+        C[idx] = (uint8_t)(C[idx] ^ (uint8_t)(1u << bit));
     } else {
         uint16_t *p = reinterpret_cast<uint16_t *>(C) + idx;
         *p = (uint16_t)(*p ^ (uint16_t)(1u << bit));
     }
+}
+
+hipError_t launch_flip_at(void *base, long idx, int elem_bytes, int bit, hipStream_t st)
+{
+    hipLaunchKernelGGL(flip_kernel, dim3(1), dim3(64), 0, st, (uint8_t *)base, idx, elem_bytes, bit);
+    return hipGetLastError();
 }
 
 hipError_t launch_flip(void *C, int dt, const Shape &s, long batch_idx, long row, long col, int bit,

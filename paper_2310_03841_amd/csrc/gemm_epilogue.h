@@ -125,6 +125,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     acc_t *rp = cs_part + 2 * BN;                                          // [BM] row dots of the A pass
     float *amax4 = reinterpret_cast<float *>(rp + BM);                     // [4]
     uint8_t *Cb = g.C + (long)bz * g.sC * OS;
+    // layer bias of this tile's columns, staged once (zero beyond N); added to every accumulator
+    // value on its way out, before the sums and before rounding
+    const bool has_bias = g.bias != nullptr;
+    acc_t *bias_lds = reinterpret_cast<acc_t *>(amax4 + 4);                // [BN]
+    if (has_bias) {
+        for (int t = tid; t < BN; t += 256) bias_lds[t] = n0 + t < N ? from_word<acc_t>(g.bias[n0 + t]) : T::zero();
+        __syncthreads();
+    }
     const bool inj_here = g.inj_b == bz && g.inj_row >= m0 && g.inj_row < m0 + BM &&
                           g.inj_col >= n0 && g.inj_col < n0 + BN;
     const int wr0 = m0 + wm * TM, wc0 = n0 + wn * TN;                      // first row / column of the wave tile
@@ -170,8 +178,13 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 constexpr int ni = decltype(ni_c)::value;
                 static_for<0, 4>([&](auto q_c) {
                     constexpr int q = decltype(q_c)::value;
-                    const acc_t v0 = acc_read(acc[mi][ni][4 * q]), v1 = acc_read(acc[mi][ni][4 * q + 1]),
-                                v2 = acc_read(acc[mi][ni][4 * q + 2]), v3 = acc_read(acc[mi][ni][4 * q + 3]);
+                    acc_t v0 = acc_read(acc[mi][ni][4 * q]), v1 = acc_read(acc[mi][ni][4 * q + 1]),
+                          v2 = acc_read(acc[mi][ni][4 * q + 2]), v3 = acc_read(acc[mi][ni][4 * q + 3]);
+                    if (has_bias) {
+                        const i32x4 bb = *reinterpret_cast<const i32x4 *>(bias_lds + wn * TN + ni * 32 + 8 * q + 4 * lh);
+                        v0 = add_t(v0, from_word<acc_t>((uint32_t)bb[0])); v1 = add_t(v1, from_word<acc_t>((uint32_t)bb[1]));
+                        v2 = add_t(v2, from_word<acc_t>((uint32_t)bb[2])); v3 = add_t(v3, from_word<acc_t>((uint32_t)bb[3]));
+                    }
                     if (PROT) {
                         cp[PROT ? ni : 0][4 * q] = add_t(cp[PROT ? ni : 0][4 * q], v0);
                         cp[PROT ? ni : 0][4 * q + 1] = add_t(cp[PROT ? ni : 0][4 * q + 1], v1);
@@ -237,7 +250,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 for (int j = 0; j < CPL; ++j) {
                     const int col = CPL * lane + j, gc = wc0 + col;
                     if (gc < N) {
-                        const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + col * 4));
+                        acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + r * SROW + col * 4));
+                        if (has_bias) v = add_t(v, bias_lds[wn * TN + col]);
                         T::store_c(Cb, (long)(br + r) * g.ldc + gc, v);
                         if (PROT) colacc[j] = add_t(colacc[j], v);
                         if constexpr (PROT && !T::IS_INT) {
@@ -257,7 +271,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                 for (int c = 0; c < HC; ++c) {
                     const int col = lh * HC + ((c + l32) & (HC - 1));
                     if (col < ncol) {
-                        const acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + l32 * SROW + col * 4));
+                        acc_t v = from_word<acc_t>(*reinterpret_cast<const uint32_t *>(wbuf + l32 * SROW + col * 4));
+                        if (has_bias) v = add_t(v, bias_lds[wn * TN + col]);
                         rs = add_t(rs, v);
                         if constexpr (!T::IS_INT) {
                             if (sto) rs_s += stored_value<DT>((float)v);
@@ -323,8 +338,14 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
                             constexpr int ni = decltype(ni_c)::value;
                             static_for<0, 8>([&](auto h_c) {
                                 constexpr int h = decltype(h_c)::value;
-                                const uint32_t w = pack2<DT>((float)acc_read(acc[mi][ni][2 * h]),
-                                                             (float)acc_read(acc[mi][ni][2 * h + 1]));
+                                float x0 = (float)acc_read(acc[mi][ni][2 * h]), x1 = (float)acc_read(acc[mi][ni][2 * h + 1]);
+                                if (has_bias) {
+                                    // register i of a block is column 8 (i >> 2) + 4 lh + (i & 3)
+                                    const int cb0 = wn * TN + ni * 32 + 8 * ((2 * h) >> 2) + 4 * lh + ((2 * h) & 3);
+                                    x0 += (float)bias_lds[cb0];
+                                    x1 += (float)bias_lds[cb0 + 1];
+                                }
+                                const uint32_t w = pack2<DT>(x0, x1);
                                 float s0, s1;
                                 if constexpr (DT == DT_BF16) {
                                     s0 = __uint_as_float(w << 16);

@@ -288,7 +288,7 @@ void gemm_tile_shape(int dt, const Shape &s, int *tm, int *tn)
 hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, const void *B, void *C,
                        const Shape &s, const Workspace &w, const InjectArm &arm, hipStream_t st)
 {
-    if (!protect && gemm_item_eligible(dt, s, false))
+    if (!protect && !w.bias && gemm_item_eligible(dt, s, false))
         return launch_gemm_item(dt, false, false, false, A, B, C, s, w, nullptr, arm, st);
     GemmArgs g;
     g.A = (const uint8_t *)A;
@@ -300,6 +300,7 @@ hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, co
     g.inj_b = arm.batch; g.inj_row = arm.row; g.inj_col = arm.col; g.inj_bit = arm.bit;
     g.cc_obs = w.cc_obs; g.rc_obs = w.rc_obs; g.rc_pred = w.rc_pred;
     g.a_sum = w.a_sum; g.a_max = w.a_max; g.b_sum = w.b_sum;
+    g.bias = w.bias;
     g.cc_sto = (protect && stored_sums && dt != DT_I8) ? w.cc_sto : nullptr;
     g.rc_sto = g.cc_sto ? w.rc_sto : nullptr;
     g.mul24_ok = s.N < 65536 ? 1 : 0;            // |b| <= 128 N

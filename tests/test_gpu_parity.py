@@ -964,6 +964,107 @@ def test_faults_in_the_operands(ctx, M, N, K):
     assert np.array_equal(run.C()[0], orc.gemm(A2[0], B2[0], True).astype(np.int32))
 
 
+@pytest.mark.parametrize("dtype", ["i8", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K,batch,trans_b", [(777, 600, 192, 1, True), (300, 200, 264, 2, True), (150, 200, 136, 2, False),
+                                                 (197, 64, 197, 3, False), (100, 130, 72, 65, True), (520, 1030, 256, 1, True)])
+def test_gemm_with_layer_bias(ctx_items, dtype, M, N, K, batch, trans_b):
+    """C = A B + bias (Sec. III-B.1 "Checksums": the checked product is adjusted by the layer
+    bias): C, both predictions, both observed sums, the scalar, clean flags, the unprotected mode,
+    and a stored flip localised and repaired by a tile recompute that adds the bias again -- on the
+    256-wide tiles, the general kernel, both layouts of B, batches, and a batch the bias-free call
+    would hand to the one-workgroup-per-item kernel."""
+    ctx = ctx_items
+    A, B = gen.gen_operands(dtype, M, N, K, 301 + M, 302 + N, trans_b=trans_b, batch=batch,
+                            b_kind="weight" if batch == 1 else "act")
+    rng = np.random.default_rng(77 + N)
+    if dtype == "i8":
+        bias = rng.integers(-100000, 100000, N).astype(np.int32)
+        d_bias = torch.from_numpy(bias).to("cuda")
+    else:
+        # of the size of the product's entries: the tolerance 1e-3 K max|A| max|B| knows nothing of
+        # the bias, and the rounding of a stored row grows with the magnitude of its entries
+        bias = (0.1 * rng.standard_normal(N)).astype(np.float32)
+        d_bias = torch.from_numpy(bias).to("cuda")
+    P = [orc.protected_gemm(A[b], B[b], dtype, trans_b, bias=bias) for b in range(batch)]
+    run = Run(ctx, dtype, A, B, trans_b)
+    run.gemm_bias(d_bias, ab.ABFT_DETECT)
+    check_clean(run, P)
+    C_prot = run.C().copy()
+    run.dC.fill_(0)
+    run.gemm_bias(d_bias, ab.ABFT_OFF)
+    assert np.array_equal(run.C(), C_prot)
+    # the plain call on the same operands is the product without the bias
+    run.gemm(ab.ABFT_DETECT)
+    check_clean(run, oracle_items(dtype, A, B, trans_b))
+    # stored flip: verify against the biased predictions, repair by recompute
+    run.gemm_bias(d_bias, ab.ABFT_DETECT | (ab.ABFT_STORED_SUMS if dtype != "i8" else 0))
+    assert np.array_equal(run.C(), C_prot)
+    run.verify()
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    bi, i = batch - 1, M // 2
+    mag = np.abs(P[bi].C_ref[i])
+    mid = np.flatnonzero((mag > 0.05) & (mag < 0.5))         # top exponent bit clear: setting it multiplies by 2^16 or more
+    j = int(mid[0]) if mid.size else int(np.argmin(mag))
+    run.inject(bi, i, j, 30 if dtype == "i8" else 14)
+    run.verify()
+    rf, cf = run.flags()
+    assert rf.sum() == 1 and cf.sum() == 1 and rf[bi, i] and cf[bi, j]
+    run.correct()
+    assert np.array_equal(run.C(), C_prot) and run.cnt()[2] == ab.ABFT_CLEAN and run.cnt()[3] == 1
+    # DETECT_CORRECT with a fault in the accumulators
+    acc0 = np.abs(P[0].C_ref - np.asarray(bias, dtype=P[0].C_ref.dtype)[None, :])      # the accumulator: the product alone
+    ai, aj = (M - 1, N - 1) if dtype == "i8" else tuple(int(x) for x in np.argwhere(acc0 < 1.0)[-1])
+    run.inject(0, ai, aj, 30, ab.ABFT_INJECT_ACCUMULATOR)    # |acc| < 2: bit 30 set makes it huge
+    run.gemm_bias(d_bias, ab.ABFT_DETECT_CORRECT)
+    cnt = run.cnt()
+    assert cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+    assert np.array_equal(run.C(), C_prot)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_operand_injection_sites(ctx, dtype):
+    """Flips in inputs and weights (Sec. II-A / III-A) through abft_inject: the bit lands where the
+    oracle's flip puts it; a weight flipped after its offline encoding shows as row flags in
+    exactly the rows the oracle names and in no column (the column prediction reads the weight as
+    it is); a flip before the call is part of the operands the call encodes: clean, and C is the
+    product of the flipped operands."""
+    M, N, K = 197, 264, 128
+    A, B = gen.gen_operands(dtype, M, N, K, 401, 402, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
+    assert ab.abft_encode_b(ctx, run.dB, run.code, run.shape) == ab.ABFT_OK
+    P = orc.protected_gemm(A[0], B[0], dtype, True)
+    n, k, bit = 33, 77, 6 if dtype == "i8" else 13
+    run.inject_operand("B", 0, n, k, bit)
+    B2 = orc.flip(B[0], n, k, bit)
+    assert np.array_equal(run.dB.cpu().numpy()[0, :, :K].view(B2.dtype), B2)
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED)
+    rf, cf = run.flags()
+    P2 = orc.protected_gemm(A[0], B2, dtype, True)
+    orf, ocf, _, status, _, _ = orc.check(P, P2.C_stored if dtype == "i8" else orc.store(P2.C_ref, dtype))
+    if dtype == "i8":
+        assert np.array_equal(rf[0], orf) and not cf.any() and run.cnt()[2] == ab.ABFT_CHECKSUM_SUSPECT
+        assert np.array_equal(run.C()[0], P2.C_stored)
+    else:
+        d = np.abs((orc.decode(B2, dtype)[n, k] - orc.decode(B[0], dtype)[n, k]) * orc.decode(A[0], dtype)[:, k])
+        sure = d > 2 * P.tau
+        quiet = d < P.tau / 2
+        assert rf[0][sure].all() and not rf[0][quiet].any() and not cf.any()
+    # an input flipped before the call: consistent, hence silent
+    i, ka = 100, 5
+    run.inject_operand("A", 0, i, ka, bit)
+    A2 = orc.flip(A[0], i, ka, bit)
+    assert np.array_equal(run.dA.cpu().numpy()[0, :, :K].view(A2.dtype), A2)
+    run.gemm(ab.ABFT_DETECT)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    check_clean(run, [orc.protected_gemm(A2, B2, dtype, True)])
+    # argument checks
+    s = run.shape
+    assert ab.abft_inject(ctx, run.dA, run.code, s, 0, M, 0, 0, ab.ABFT_INJECT_OPERAND_A) == ab.ABFT_EINVAL
+    assert ab.abft_inject(ctx, run.dA, run.code, s, 0, 0, K, 0, ab.ABFT_INJECT_OPERAND_A) == ab.ABFT_EINVAL
+    assert ab.abft_inject(ctx, run.dB, run.code, s, 0, N, 0, 0, ab.ABFT_INJECT_OPERAND_B) == ab.ABFT_EINVAL
+    assert ab.abft_inject(ctx, run.dB, run.code, s, 0, 0, 0, 8 if dtype == "i8" else 16, ab.ABFT_INJECT_OPERAND_B) == ab.ABFT_EINVAL
+
+
 @pytest.mark.parametrize("dtype", ["i8", "bf16"])
 @pytest.mark.parametrize("M,N,K,batch,trans_b", [(40, 50, 64, 1100, True), (70, 40, 100, 1030, False),
                                                  (36, 300, 128, 1040, True)])
