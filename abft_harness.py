@@ -71,9 +71,10 @@ class Run:
         self.col_flag = torch.full((self.batch * self.N,), 7, dtype=torch.uint8, device="cuda")
         self.counts = torch.full((8,), 99, dtype=torch.int32, device="cuda")
         self.tau = 0.0
+        self.tau_cols = 0.0
 
     def result(self):
-        return ab.make_result(self.row_flag, self.col_flag, self.counts, self.tau)
+        return ab.make_result(self.row_flag, self.col_flag, self.counts, self.tau, self.tau_cols)
 
     def gemm(self, mode=ab.ABFT_DETECT):
         rc = ab.abft_gemm(self.ctx, self.dA, self.dB, self.dC, self.code, mode, self.shape,

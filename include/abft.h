@@ -128,6 +128,9 @@ typedef struct {
                                   4 = status before that correction, 5..7 reserved */
     float     tau;        /* floating point only: > 0 overrides the tolerance
                              1e-3 * K * max|A| * max|B| (per batch item); 0 = use that default */
+    float     tau_cols;   /* floating point only: > 0 is the tolerance of the column check alone (the
+                             row check keeps tau or the default): thresholds calibrated separately
+                             for the two checks (Sec. III-B.1 "Eps Generation"); 0 = same as rows */
 } abft_result;
 
 /* Workspace vectors that tests and reports may read back (device pointers into the context). */

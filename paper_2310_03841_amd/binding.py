@@ -55,7 +55,7 @@ class abft_config(ctypes.Structure):
 
 class abft_result(ctypes.Structure):
     _fields_ = [("row_flag", ctypes.c_void_p), ("col_flag", ctypes.c_void_p), ("counts", ctypes.c_void_p),
-                ("tau", ctypes.c_float)]
+                ("tau", ctypes.c_float), ("tau_cols", ctypes.c_float)]
 
 
 class AbftError(RuntimeError):
@@ -163,8 +163,8 @@ def make_shape(M, N, K, batch=1, lda=None, ldb=None, ldc=None, strideA=None, str
     return abft_shape(M, N, K, batch, lda, ldb, ldc, strideA, strideB, strideC, 1 if transB else 0, 0)
 
 
-def make_result(row_flag, col_flag, counts, tau: float = 0.0) -> abft_result:
-    return abft_result(_ptr(row_flag), _ptr(col_flag), _ptr(counts), float(tau))
+def make_result(row_flag, col_flag, counts, tau: float = 0.0, tau_cols: float = 0.0) -> abft_result:
+    return abft_result(_ptr(row_flag), _ptr(col_flag), _ptr(counts), float(tau), float(tau_cols))
 
 
 def abft_strerror(code: int) -> str:

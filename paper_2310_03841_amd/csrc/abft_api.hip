@@ -256,8 +256,9 @@ static bool same_c_layout(const abft_shape &x, const abft_shape &y)
 static int check_verdict(const abft_result *r, Verdict *v)
 {
     if (!r || !r->row_flag || !r->col_flag || !r->counts) return ABFT_EINVAL;
-    if (!(r->tau >= 0.f)) return ABFT_EINVAL;
+    if (!(r->tau >= 0.f) || !(r->tau_cols >= 0.f)) return ABFT_EINVAL;
     v->row_flag = r->row_flag; v->col_flag = r->col_flag; v->counts = r->counts; v->tau_override = r->tau;
+    v->tau_override_cols = r->tau_cols;
     return ABFT_OK;
 }
 

@@ -66,7 +66,8 @@ struct InjectArm { int batch, row, col, bit; };   // batch < 0: not armed
 struct Verdict {                    // caller buffers
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
-    float tau_override;
+    float tau_override;             // > 0: tolerance of both checks instead of 1e-3 K max|A| max|B|
+    float tau_override_cols;        // > 0: tolerance of the column check (the row check keeps the other)
 };
 
 // Raises the dynamic-LDS limit of a kernel, once per (kernel, device); contexts may be driven

@@ -237,6 +237,7 @@ struct CmpArgs {
     const uint32_t *cc_obs, *rc_obs;
     const float *tau;
     float tau_override;   // > 0: use this tolerance instead of tau[]
+    float tau_override_cols;   // > 0: tolerance of the column check
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
@@ -261,6 +262,7 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         for (size_t i = bid * 256 + tid; i < a.zero_words; i += nb * 256) a.zero_ptr[i] = 0u;
     }
     const float tol = IS_INT ? 0.f : (a.tau_override > 0.f ? a.tau_override : a.tau[bz]);
+    const float tol_c = (!IS_INT && a.tau_override_cols > 0.f) ? a.tau_override_cols : tol;
     bool frow = false, fcol = false;
     if (!IS_INT && a.fix_count && a.rc_sto && idx < M + N) {
         // After a correction the stored-side sums of the GEMM no longer describe the rows and
@@ -285,9 +287,9 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         a.row_flag[(long)bz * M + idx] = frow ? 1 : 0;
     } else if (idx < M + N) {
         const int j = idx - M;
-        fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], a.cc_pred[(long)bz * N + j], tol);
+        fcol = mismatch<IS_INT>(a.cc_obs[(long)bz * N + j], a.cc_pred[(long)bz * N + j], tol_c);
         if (!IS_INT && a.cc_sto)
-            fcol = fcol || mismatch<false>(a.cc_obs[(long)bz * N + j], a.cc_sto[(long)bz * N + j], STO_TOL_FACTOR * tol);
+            fcol = fcol || mismatch<false>(a.cc_obs[(long)bz * N + j], a.cc_sto[(long)bz * N + j], STO_TOL_FACTOR * tol_c);
         a.col_flag[(long)bz * N + j] = fcol ? 1 : 0;
     }
     const unsigned nr = __syncthreads_count(frow);
@@ -337,7 +339,7 @@ hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verd
     a.fix_tiles = w.fix_tiles;
     a.cc_pred = w.cc_pred; a.rc_pred = w.rc_pred;
     a.cc_obs = w.cc_vobs; a.rc_obs = w.rc_vobs;
-    a.tau = w.tau; a.tau_override = v.tau_override;
+    a.tau = w.tau; a.tau_override = v.tau_override; a.tau_override_cols = v.tau_override_cols;
     a.row_flag = v.row_flag; a.col_flag = v.col_flag; a.counts = v.counts;
     a.ticket = w.cmp_ticket;
     a.M = s.M; a.N = s.N; a.batch = s.batch;
@@ -363,7 +365,7 @@ struct FinArgs {
     const uint32_t *bias; // layer bias [N] or null: cc_pred gains M bias[n], rc_pred sum(bias), a.b M sum(bias)
     uint32_t *cc_pred, *s_pred;
     float *maxabs, *tau;
-    float tau_override;
+    float tau_override, tau_override_cols;
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;     // [3]: ticket, flagged rows, flagged cols (self-cleaning)
@@ -509,7 +511,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                         const long o = (long)bz * N + n;
                         if (f.bias) t = add_t(t, mul_t((acc_t)M, from_word<acc_t>(f.bias[n])));
                         f.cc_pred[o] = as_word(t);
-                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), f.tau_override_cols > 0.f ? f.tau_override_cols : tol);
                         f.col_flag[o] = fl ? 1 : 0;
                     }
                     nc_w += __popcll(__ballot(fl));
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(256) void finish_kernel(FinArgs f)
                         if (f.bias) t = add_t(t, mul_t((acc_t)M, from_word<acc_t>(f.bias[n])));
                         const long o = (long)bz * N + n;
                         f.cc_pred[o] = as_word(t);
-                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), tol);
+                        fl = mismatch<T::IS_INT>(f.cc_obs[o], as_word(t), f.tau_override_cols > 0.f ? f.tau_override_cols : tol);
                         f.col_flag[o] = fl ? 1 : 0;
                     }
                     nc_w += __popcll(__ballot(fl));
@@ -749,7 +751,7 @@ __global__ __launch_bounds__(256) void finish_nk_kernel(FinArgs f)
             if (lane < FN_RW && nrow0 + lane < N && (!split || wave == 0)) {
                 const long o = (long)bz * N + nrow0 + lane;
                 f.cc_pred[o] = as_word(mine);
-                fl = mismatch<T::IS_INT>(my_obs, as_word(mine), tol);
+                fl = mismatch<T::IS_INT>(my_obs, as_word(mine), f.tau_override_cols > 0.f ? f.tau_override_cols : tol);
                 f.col_flag[o] = fl ? 1 : 0;
             }
             nc_w += __popcll(__ballot(fl));
@@ -815,7 +817,7 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     f.a_sum = w.a_sum; f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;
     f.bias = w.bias;
     f.a_max = w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
-    f.tau_override = v.tau_override;
+    f.tau_override = v.tau_override; f.tau_override_cols = v.tau_override_cols;
     f.row_flag = v.row_flag; f.col_flag = v.col_flag; f.counts = v.counts; f.ticket = w.cmp_ticket;
     f.group_ticket = w.cmp_ticket + 4;
     const int ce = 16 / elem_size(dt);

@@ -96,7 +96,7 @@ struct ItemArgs {
     uint32_t *cc_obs, *rc_obs, *rc_pred, *a_sum, *a_max, *b_sum, *b_max, *cc_pred, *s_pred;
     uint32_t *cc_sto, *rc_sto;                    // sums of C as stored (after rounding), on request (floating point)
     float *maxabs, *tau;
-    float tau_override;
+    float tau_override, tau_override_cols;
     uint8_t *row_flag, *col_flag;
     uint32_t *counts;
     uint32_t *ticket;                             // [3]: ticket, flagged rows, flagged cols (self-cleaning)
@@ -881,7 +881,7 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     g.cc_pred[o] = as_word(dot);
                     g.cc_obs[o] = obs;
                     if (STO) g.cc_sto[o] = ccsto[n];
-                    fl = mismatch<T::IS_INT>(obs, as_word(dot), tol);
+                    fl = mismatch<T::IS_INT>(obs, as_word(dot), g.tau_override_cols > 0.f ? g.tau_override_cols : tol);
                     g.col_flag[o] = fl ? 1 : 0;
                 }
                 nc_w += __popcll(__ballot(fl));
@@ -1074,6 +1074,7 @@ hipError_t launch_gemm_item(int dt, bool protect, bool cached_b, bool stored_sum
     g.cc_sto = sto ? w.cc_sto : nullptr; g.rc_sto = sto ? w.rc_sto : nullptr;
     g.maxabs = w.maxabs; g.tau = w.tau;
     g.tau_override = v ? v->tau_override : 0.f;
+    g.tau_override_cols = v ? v->tau_override_cols : 0.f;
     g.row_flag = v ? v->row_flag : nullptr; g.col_flag = v ? v->col_flag : nullptr;
     g.counts = v ? v->counts : nullptr;
     g.ticket = w.cmp_ticket; g.group_ticket = w.cmp_ticket + 4;

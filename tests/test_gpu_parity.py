@@ -325,6 +325,73 @@ def test_discrepancy_statistics(ctx, dtype, M, N, K, batch, trans_b):
     assert ab.abft_discrepancy(ctx, ab.ABFT_I8, i8, ab.ABFT_DISC_FUSED, stats) == ab.ABFT_EINVAL
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_thresholds_calibrated_over_pooled_clean_runs(ctx, dtype):
+    """Eps generation as the paper states it (Sec. III-B.1 "Eps Generation", Sec. IV-C): the
+    discrepancies of fault-free seeded runs of one layer shape are pooled, rows and columns are
+    fitted separately, and the thresholds are read off at a confidence level.  Pooled device
+    statistics against the oracle's; then the two thresholds go into the checks: flips between the
+    calibrated and the analytic tolerance are seen only under the calibrated ones, the row check
+    and the column check each obey their own threshold, and clean outputs stay (nearly) clean."""
+    M, N, K, runs = 300, 1030, 256, 12
+    _, B = gen.gen_operands(dtype, M, N, K, 501, 502, trans_b=True)
+    stats = torch.zeros((1, 8), dtype=torch.float32, device="cuda")
+    rows_g, cols_g, rows_o, cols_o = [], [], [], []
+    last = None
+    for r in range(runs):
+        A, _ = gen.gen_operands(dtype, M, N, K, 600 + r, 502, trans_b=True)
+        run = Run(ctx, dtype, A, B, True)
+        run.gemm(ab.ABFT_DETECT)
+        run.verify()
+        assert ab.abft_discrepancy(ctx, run.code, run.shape, ab.ABFT_DISC_STORED, stats) == ab.ABFT_OK
+        torch.cuda.synchronize()
+        g = stats.cpu().numpy().astype(np.float64)[0]
+        rows_g.append(tuple(g[0:4]))
+        cols_g.append(tuple(g[4:8]))
+        P = orc.protected_gemm(A[0], B[0], dtype, True)
+        want = orc.discrepancy_stats(P, P.C_stored)
+        rows_o.append(want["rows"])
+        cols_o.append(want["cols"])
+        last = (run, P)
+    for conf in (0.999, 0.9999):
+        tr_g, tc_g = orc.calibrated_thresholds(rows_g, cols_g, conf)
+        tr_o, tc_o = orc.calibrated_thresholds(rows_o, cols_o, conf)
+        assert tr_g == pytest.approx(tr_o, rel=0.1) and tc_g == pytest.approx(tc_o, rel=0.1)
+    run, P = last
+    tr, tc = orc.calibrated_thresholds(rows_g, cols_g, 0.9999)
+    assert tc < tr < P.tau                      # rows sum 1030 rounded values, columns 300: sqrt(N) against sqrt(M)
+    # clean output under the calibrated thresholds: at 99.99 % at most a few of the 1330 checks flag
+    run.tau, run.tau_cols = float(tr), float(tc)
+    run.verify()
+    assert run.cnt()[0] + run.cnt()[1] <= 2
+    C_clean = run.dC.clone()
+    Cd = orc.decode(P.C_stored, dtype)
+    # a flip with tc < |delta| < tr is seen by the column check only; one above tr by both; both
+    # are invisible to the analytic tolerance
+    def flip_with_delta(lo, hi):
+        for bit in range(9, 3, -1) if dtype == "f16" else range(6, 0, -1):
+            for (i, j) in [(7, 11), (150, 500), (299, 1029), (33, 64), (200, 900)]:
+                d = abs(orc.decode(orc.flip(P.C_stored, i, j, bit), dtype)[i, j] - Cd[i, j])
+                if lo < d < hi:
+                    return i, j, bit
+        return None
+    for lo, hi, want_row in ((1.5 * tc, tr / 1.5, False), (1.5 * tr, P.tau / 1.5, True)):
+        pick = flip_with_delta(lo, hi)
+        if pick is None:
+            continue
+        i, j, bit = pick
+        run.tau, run.tau_cols = 0.0, 0.0
+        run.inject(0, i, j, bit)
+        run.verify()
+        assert run.cnt()[2] == ab.ABFT_CLEAN                       # below the analytic tolerance
+        run.tau, run.tau_cols = float(tr), float(tc)
+        run.verify()
+        rf, cf = run.flags()
+        assert cf[0, j] and bool(rf[0, i]) == want_row
+        run.dC.copy_(C_clean)
+    run.tau, run.tau_cols = 0.0, 0.0
+
+
 def _with_ld(C, run):
     full = np.zeros((run.batch, run.M, run.ldc), dtype=np.int32 if run.dtype == "i8" else np.int16)
     full[:, :, :run.N] = C.view(full.dtype)
