@@ -75,7 +75,10 @@ hipError_t launch_zero(uint32_t *p, size_t nwords, hipStream_t st)
 // that reads A is done by the GEMM kernel on the slabs it holds in LDS (gemm_apass.h); what is
 // left here is the pass over B, which must be complete before that (A b needs all of b).  For a
 // weight it is done once, offline (remark (2) of the same paragraph).
-constexpr int ENC_UNROLL = 8;     // independent 16-byte loads in flight per thread (B pass)
+#ifndef ENC_UNROLL_N
+#define ENC_UNROLL_N 8
+#endif
+constexpr int ENC_UNROLL = ENC_UNROLL_N;     // independent 16-byte loads in flight per thread (B pass)
 #ifndef ENC_BATCHES
 #define ENC_BATCHES 2
 #endif

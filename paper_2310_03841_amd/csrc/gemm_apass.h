@@ -24,6 +24,23 @@ template <typename T> __device__ __forceinline__ T row8_sum(T v)
     return v;
 }
 
+// LDS atomic add on a 32-bit checksum word, written as the instruction itself.  Through the
+// compiler's atomicAdd every one of these is preceded by a wait for ALL outstanding memory
+// operations of the wave: the operand loads of the next slab go straight into LDS
+// (global_load_lds) and the compiler, which cannot tell their target from this word, orders the
+// atomic behind them -- the pass then stalls for a full load latency in every slab it reduces.
+// The words added to here are never a target of those loads.
+__device__ __forceinline__ void lds_add_word(uint32_t *p, float v)
+{
+    const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)p;
+    asm volatile("ds_add_f32 %0, %1" :: "v"(a), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_add_word(uint32_t *p, int v)
+{
+    const uint32_t a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t *)p;
+    asm volatile("ds_add_u32 %0, %1" :: "v"(a), "v"(v) : "memory");
+}
+
 // Per-thread state of the A pass that lives across the slabs of one tile.
 template <int DT> struct APassState {
     typename Traits<DT>::acc_t rdot;   // dot of row (t >> 3) + 32 (t & 7) with b, over the owned slabs
@@ -147,10 +164,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
     }
     if ((tid & 63) < 8) {
 #pragma unroll
-        for (int q = 0; q < CE; ++q) {
-            if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(col_lds) + c * CE + q, (int)cs[q]);
-            else atomicAdd(reinterpret_cast<float *>(col_lds) + c * CE + q, (float)cs[q]);
-        }
+        for (int q = 0; q < CE; ++q) lds_add_word(col_lds + c * CE + q, cs[q]);
     }
 }
 

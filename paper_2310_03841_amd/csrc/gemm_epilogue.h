@@ -94,12 +94,12 @@ template <int DT> __device__ __forceinline__ float stored_value(float v)
 template <int DT> struct EpiProt {
     APassState<DT> st;        // row dots and max|A| of the owned slabs
     const uint32_t *col_lds;  // column sums of the owned slabs, KE words each (LDS)
-    int owned;                // number of owned slabs: slab j is slab tn + j * tiles_n of K
-    int tn, tiles_n;
+    int owned;                // number of owned slabs reduced: the j-th is slab slab0 + j * slab_step of K
+    int slab0, slab_step;
 };
 
-template <int DT, int BM, int BN, bool PROT>
-__device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
+template <int DT, int BM, int BN, bool PROT, bool BIAS>
+__device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                                               typename Traits<DT>::accv_t (&acc)[BM / 64][BN / 64],
                                               uint8_t *smem, int m0, int n0, int bz, const EpiProt<DT> &ep)
 {
@@ -127,7 +127,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
     uint8_t *Cb = g.C + (long)bz * g.sC * OS;
     // layer bias of this tile's columns, staged once (zero beyond N); added to every accumulator
     // value on its way out, before the sums and before rounding
-    const bool has_bias = g.bias != nullptr;
+    constexpr bool has_bias = BIAS;
     acc_t *bias_lds = reinterpret_cast<acc_t *>(amax4 + 4);                // [BN]
     if (has_bias) {
         for (int t = tid; t < BN; t += 256) bias_lds[t] = n0 + t < N ? from_word<acc_t>(g.bias[n0 + t]) : T::zero();
@@ -423,7 +423,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
         }
         // column sums of A over this tile's rows, for the slabs this workgroup reduced
         for (int t = tid; t < ep.owned * KE; t += 256) {
-            const int k = ((t / KE) * ep.tiles_n + ep.tn) * KE + (t % KE);
+            const int k = (ep.slab0 + (t / KE) * ep.slab_step) * KE + (t % KE);
             if (k < g.K) atomic_add_word(g.a_sum + (long)bz * g.K + k, from_word<acc_t>(ep.col_lds[t]));
         }
         if (!T::IS_INT && tid == 0) {
@@ -431,6 +431,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
             if (m > 0.f) atomicMax(g.a_max + bz, __float_as_uint(m));
         }
     }
+}
+
+// With and without a layer bias: two copies of the epilogue behind one uniform branch (a test per
+// group of four values inside one copy costs a branch per group).
+template <int DT, int BM, int BN, bool PROT>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &g,
+                                              typename Traits<DT>::accv_t (&acc)[BM / 64][BN / 64],
+                                              uint8_t *smem, int m0, int n0, int bz, const EpiProt<DT> &ep)
+{
+    if (g.bias != nullptr) gemm_epilogue_impl<DT, BM, BN, PROT, true>(g, acc, smem, m0, n0, bz, ep);
+    else gemm_epilogue_impl<DT, BM, BN, PROT, false>(g, acc, smem, m0, n0, bz, ep);
 }
 
 }  // namespace abft

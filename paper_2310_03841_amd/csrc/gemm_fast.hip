@@ -170,7 +170,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     uint32_t *col_lds = reinterpret_cast<uint32_t *>(smem + AUX_OFF);
     EpiProt<DT> ep;
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
-    ep.col_lds = col_lds; ep.tn = tn; ep.tiles_n = g.tiles_n; ep.owned = 0;
+    ep.col_lds = col_lds; ep.slab0 = tn; ep.slab_step = g.tiles_n; ep.owned = 0;
     {
         const int nslab = K / KE;                      // at least 3 (gemm_fast_eligible)
         int next_own = tn;

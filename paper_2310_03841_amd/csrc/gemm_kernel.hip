@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     uint32_t *col_lds = reinterpret_cast<uint32_t *>(smem + 2 * BUF);
     EpiProt<DT> ep;
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
-    ep.col_lds = col_lds; ep.tn = tn_idx; ep.tiles_n = g.tiles_n; ep.owned = 0;
+    ep.col_lds = col_lds; ep.slab0 = tn_idx; ep.slab_step = g.tiles_n; ep.owned = 0;
     int next_own = tn_idx;
     const int owned = (PROT && tn_idx < nslab) ? (nslab - tn_idx + g.tiles_n - 1) / g.tiles_n : 0;
     uint32_t *b_lds = col_lds + owned * KE;
