@@ -245,20 +245,25 @@ __device__ __forceinline__ void map_tile(int bid, int nb, int tiles_m, int tiles
 }
 
 // The grid mixes two tile shapes against wave quantisation: 256 x 256 tiles cover the first
-// big_rows rows in whole rounds of the machine, 128 x 256 tiles cover the rest, are dispatched
-// after them and take half as long, so the last round is short.  (600 big tiles on 256 CUs
-// would be three rounds for 2.34 rounds of work.)
+// big_rows rows, 128 x 256 tiles the rest; how many of each is chosen by playing the dispatch
+// through (choose_big_rows).  (600 big tiles on 256 CUs would be three rounds for 2.34 rounds
+// of work.)
 template <int DT, bool PROT>
 __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int bid = blockIdx.x, bz = blockIdx.z;
     int tm, tn;
-    if (bid < g.n_big) {
-        map_tile(bid, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
+    // The 128-row tiles are dispatched first: the compute units that start with one are half a
+    // tile ahead of the others from then on, so the two groups store their tiles of C at different
+    // times (a round of the machine that stores in step asks for tens of MB at once) and draw on
+    // the matrix pipes at different times.  Measured on 12608 x 3072 x 768: 63 -> 60.5 us.
+    const int n_small = (int)gridDim.x - g.n_big;
+    if (bid >= n_small) {
+        map_tile(bid - n_small, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
         fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tn);
     } else {
-        map_tile(bid - g.n_big, (int)gridDim.x - g.n_big, g.tiles_m_small, g.tiles_n, &tm, &tn);
+        map_tile(bid, n_small, g.tiles_m_small, g.tiles_n, &tm, &tn);
         fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, tn);
     }
 }
@@ -278,7 +283,7 @@ static double play_schedule(int big_rows, int M, int tiles_n, int batch, int ncu
     double end = 0.0;
     for (int z = 0; z < batch; ++z)
         for (long t = 0; t < nb + ns; ++t) {
-            const double f = cu.top() + (t < nb ? 1.0 : 0.62);
+            const double f = cu.top() + (t < ns ? 0.62 : 1.0);     // dispatch order: the half-height tiles first
             cu.pop();
             cu.push(f);
             if (f > end) end = f;
