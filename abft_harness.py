@@ -129,7 +129,7 @@ class Run:
 
     def ws(self, which):
         kind = "i" if self.dtype == "i8" else "f"
-        if which in (ab.ABFT_WS_TAU, ab.ABFT_WS_MAXABS):
+        if which in (ab.ABFT_WS_TAU, ab.ABFT_WS_MAXABS, ab.ABFT_WS_C_MAX):
             kind = "f"
         v = read_ws(self.ctx, which, self.shape, kind)
         return v.reshape(self.batch, -1)

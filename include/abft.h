@@ -77,9 +77,15 @@ enum {
                                    flip in stored C shows far below tau).  Ignored for ABFT_I8, where
                                    the stored values are the accumulators, and not kept with
                                    ABFT_DETECT_CORRECT (a correction replaces summed values). */
-    ABFT_B_CHECKSUM_CACHED = 0x10 /* reuse the encoding of B left in the context by abft_encode_b
+    ABFT_B_CHECKSUM_CACHED = 0x10, /* reuse the encoding of B left in the context by abft_encode_b
                                      (or by the previous abft_gemm with the same B and shape):
                                      the paper's offline weight checksum */
+    ABFT_A_CHECKSUM_GIVEN = 0x40   /* a = e^T A (and max|A|) come from the caller (abft_supply_a): the
+                                      checksum generated while A was produced (Sec. V "Optimizations"
+                                      (2)), e.g. the stored-side column sums ABFT_WS_CC_STO of the
+                                      protected GEMM whose output this A is.  The call then forms only
+                                      the row prediction from A, and a corruption of A between its
+                                      producer and this call shows in the column check */
 };
 
 enum {
@@ -147,7 +153,9 @@ typedef enum {
     ABFT_WS_S_PRED  = 9,  /* scalar a.b [batch] (the paper's own scalar check value) */
     ABFT_WS_MAXABS  = 10, /* max|A|, max|B| [batch][2] float (floating point only) */
     ABFT_WS_CC_STO  = 11, /* e^T C of the values as stored, from the GEMM epilogue (ABFT_STORED_SUMS) [batch][N] */
-    ABFT_WS_RC_STO  = 12  /* C e   of the values as stored [batch][M] */
+    ABFT_WS_RC_STO  = 12, /* C e   of the values as stored [batch][M] */
+    ABFT_WS_C_MAX   = 13  /* max|C as stored| [batch] float, formed with the stored-side sums (what a
+                             consumer of this C needs as its max|A|) */
 } abft_ws_id;
 
 /* where a flip lands */
@@ -207,6 +215,17 @@ int abft_gemm_bias(abft_ctx *ctx, const void *A, const void *B, const void *bias
 #define ABFT_STATIC_MAX_BATCH 64
 int abft_gemm_static(const void *A, const void *B, void *C, abft_dtype dtype, int mode,
                      const abft_shape *s, const abft_result *r, void *stream);
+
+/* Producer-side input checksum for the next abft_gemm / abft_gemm_bias on this context called with
+ * ABFT_A_CHECKSUM_GIVEN (Sec. V "Optimizations" (2): the checksum is generated while the tensor is
+ * produced, so the consumer does not form it again).  a: DEVICE, [batch][K] words (float for
+ * ABFT_BF16 / ABFT_F16, int32 in Z/2^32 for ABFT_I8), the column sums of the consumer's A;
+ * amax: DEVICE, [batch] float, max|A| (may be NULL: then the call must bring its tolerance in
+ * abft_result.tau; ignored for ABFT_I8).  Both must stay valid until that call's kernels have run;
+ * the pointers are consumed by that call.  Where A is the stored output of a protected GEMM run
+ * with ABFT_STORED_SUMS on the same shape family (consumer M, K = producer M, N), a and amax are
+ * that call's ABFT_WS_CC_STO and ABFT_WS_C_MAX.  ABFT_WS_A_SUM is not filled by such a call. */
+int abft_supply_a(abft_ctx *ctx, const void *a, const void *amax);
 
 /* Re-sums the stored C and compares with the predictions the last abft_gemm of this shape left
  * in the context (Sec. III-B.1: sum of layer activations vs. checksum product).  Overwrites

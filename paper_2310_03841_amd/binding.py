@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libabft.so")
 
 __all__ = [
     "ABFT_I8", "ABFT_BF16", "ABFT_F16", "ABFT_OFF", "ABFT_DETECT", "ABFT_DETECT_CORRECT",
-    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
+    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_A_CHECKSUM_GIVEN", "ABFT_WS_C_MAX", "abft_supply_a", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
     "ABFT_EHIP", "ABFT_ESTATE", "ABFT_CLEAN", "ABFT_LOCALISED", "ABFT_CHECKSUM_SUSPECT", "ABFT_TOO_MANY",
     "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR", "ABFT_INJECT_OPERAND_A", "ABFT_INJECT_OPERAND_B",
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
@@ -31,6 +31,8 @@ DTYPE_CODE = {"i8": ABFT_I8, "bf16": ABFT_BF16, "f16": ABFT_F16}
 ABFT_OFF, ABFT_DETECT, ABFT_DETECT_CORRECT = 0, 1, 2
 ABFT_B_CHECKSUM_CACHED = 0x10
 ABFT_STORED_SUMS = 0x20
+ABFT_A_CHECKSUM_GIVEN = 0x40
+ABFT_WS_C_MAX = 13
 ABFT_DISC_FUSED, ABFT_DISC_STORED = 0, 1
 ABFT_OK, ABFT_EINVAL, ABFT_EALIGN, ABFT_ESHAPE, ABFT_EWORKSPACE, ABFT_EHIP, ABFT_ESTATE = 0, -1, -2, -3, -4, -5, -6
 ABFT_CLEAN, ABFT_LOCALISED, ABFT_CHECKSUM_SUSPECT, ABFT_TOO_MANY = 0, 1, 2, 3
@@ -78,6 +80,7 @@ _SIGS = {
     "abft_gemm_static": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
                                         ctypes.POINTER(abft_result), ctypes.c_void_p]),
+    "abft_supply_a": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
     "abft_verify": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                    ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_correct": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -215,6 +218,10 @@ def abft_gemm_static(A, B, C, dtype: int, mode: int, shape: abft_shape, result: 
     r = ctypes.byref(result) if result is not None else None
     return int(lib().abft_gemm_static(_ptr(A), _ptr(B), _ptr(C), dtype, mode, ctypes.byref(shape), r,
                                       _stream(stream)))
+
+
+def abft_supply_a(ctx, a, amax=None) -> int:
+    return int(lib().abft_supply_a(ctx, _ptr(a), _ptr(amax)))
 
 
 def abft_verify(ctx, C, dtype: int, shape: abft_shape, result: abft_result, stream=None) -> int:

@@ -42,6 +42,7 @@ struct abft_ctx {
     int64_t vobs_ldc, vobs_strideC;
     bool list_dirty;        // the tile list's counters may be non-zero (a correction failed half way)
     int b_dt, pred_dt;
+    const void *given_a, *given_amax;   // abft_supply_a: a = e^T A and max|A| for the next call with ABFT_A_CHECKSUM_GIVEN
     const void *pred_bias;  // layer bias of the GEMM the predictions belong to (abft_correct adds it to recomputed tiles)
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
@@ -82,7 +83,7 @@ extern "C" int abft_last_hip_error(const abft_ctx *ctx) { return ctx ? ctx->last
 constexpr int N_POOLS = 7;
 static constexpr size_t pool_total_words(size_t R, size_t Cn, size_t D, size_t Bt)
 {
-    return 2 * (D + Bt) + Bt * BATCH_WORDS + Cn + 2 * (2 * Cn + 3 * R + D + Bt) + 2 * (R + Cn) +
+    return 2 * (D + Bt) + Bt * BATCH_WORDS + Cn + 2 * (2 * Cn + 3 * R + D + 2 * Bt) + 2 * (R + Cn) +
            (size_t)MAX_FIX_TILES * 3 + (8 + 64);
 }
 static void pool_words(int64_t max_rows, int64_t max_cols, int64_t max_depth, int64_t max_batch, size_t words[N_POOLS])
@@ -91,7 +92,7 @@ static void pool_words(int64_t max_rows, int64_t max_cols, int64_t max_depth, in
     words[0] = 2 * (D + Bt);                       // pool_depth
     words[1] = Bt * BATCH_WORDS;                   // pool_batch
     words[2] = Cn;                                 // pool_cols
-    words[3] = 2 * (2 * Cn + 3 * R + D + Bt);      // pool_obs
+    words[3] = 2 * (2 * Cn + 3 * R + D + 2 * Bt);  // pool_obs
     words[4] = 2 * (R + Cn);                       // pool_vobs
     words[5] = (size_t)MAX_FIX_TILES * 3;          // fix_tiles
     words[6] = 8 + 64;                             // small
@@ -107,7 +108,7 @@ static void start_clean(abft_ctx *c)
 {
     const size_t D = (size_t)c->cfg.max_depth, R = (size_t)c->cfg.max_rows, Cn = (size_t)c->cfg.max_cols,
                  Bt = (size_t)c->cfg.max_batch;
-    c->region_words = 2 * Cn + 3 * R + D + Bt;
+    c->region_words = 2 * Cn + 3 * R + D + 2 * Bt;
     c->cur = 0;
     c->dirty[0] = c->dirty[1] = 0;
     c->vregion_words = R + Cn;
@@ -221,13 +222,15 @@ static void carve(const abft_ctx *c, int dt, const Shape &s, Workspace *w)
     w->a_max = w->a_sum + bK;
     w->cc_sto = w->a_max + s.batch;
     w->rc_sto = w->cc_sto + bN;
-    w->zero_words = 2 * bN + 3 * bM + bK + (size_t)s.batch;
+    w->c_max = w->rc_sto + bM;
+    w->zero_words = 2 * bN + 3 * bM + bK + 2 * (size_t)s.batch;
     w->cc_vobs = c->pool_vobs + (size_t)c->vcur * c->vregion_words;
     w->rc_vobs = w->cc_vobs + bN;
     w->fix_tiles = c->fix_tiles;
     w->fix_count = c->small;
     w->cmp_ticket = c->small + 4;
     w->bias = nullptr;
+    w->a_given = w->amax_given = nullptr;
     (void)dt;
 }
 
@@ -365,9 +368,9 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
         int rc = begin_b_pass(ctx, st);
         if (rc) return rc;
     }
-    const uint32_t *bias = w->bias;
+    const uint32_t *bias = w->bias, *a_given = w->a_given, *amax_given = w->amax_given;
     carve(ctx, dtype, sh, w);
-    w->bias = bias;
+    w->bias = bias; w->a_given = a_given; w->amax_given = amax_given;
     uint32_t *prev_base = ctx->pool_obs + (size_t)prev * ctx->region_words;
     size_t stale = ctx->dirty[ctx->cur];
     if (gm && stale < w->zero_words) stale = w->zero_words;
@@ -456,7 +459,7 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
 {
     const int base = mode & ABFT_MODE_MASK;
     if (base != ABFT_OFF && base != ABFT_DETECT && base != ABFT_DETECT_CORRECT) return ABFT_EINVAL;
-    if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED | ABFT_STORED_SUMS)) return ABFT_EINVAL;
+    if (mode & ~(ABFT_MODE_MASK | ABFT_B_CHECKSUM_CACHED | ABFT_STORED_SUMS | ABFT_A_CHECKSUM_GIVEN)) return ABFT_EINVAL;
     Shape sh;
     int rc = check_shape(ctx, dtype, s, 7, &sh, base != ABFT_OFF);
     if (rc) return rc;
@@ -466,6 +469,14 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
     Workspace w;
     carve(ctx, dtype, sh, &w);
     w.bias = (const uint32_t *)bias;
+    const bool given = base != ABFT_OFF && (mode & ABFT_A_CHECKSUM_GIVEN) != 0;
+    if (given) {
+        if (!ctx->given_a) return ABFT_ESTATE;                       // abft_supply_a first
+        // without max|A| there is no default tolerance: the caller must bring one
+        if (dtype != ABFT_I8 && !ctx->given_amax && !(r && r->tau > 0.f)) return ABFT_EINVAL;
+        w.a_given = (const uint32_t *)ctx->given_a;
+        w.amax_given = (const uint32_t *)ctx->given_amax;
+    }
     InjectArm arm = ctx->arm;
     if (arm.batch >= 0 && (arm.batch >= sh.batch || arm.row >= sh.M || arm.col >= sh.N)) return ABFT_EINVAL;
 
@@ -489,7 +500,7 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
     hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
     if (ev) HIP_TRY(hipEventRecord(ev[0], st));
     const bool stored = (mode & ABFT_STORED_SUMS) != 0;
-    const bool item = !bias && gemm_item_eligible(dtype, sh, stored);
+    const bool item = !bias && !given && gemm_item_eligible(dtype, sh, stored);
     rc = item ? enqueue_item(ctx, dtype, cached, stored, A, B, C, sh, w, v, arm, ev, st)
               : enqueue_tiled(ctx, dtype, cached, stored, A, B, C, sh, &w, v, arm, ev, st);
     if (rc) return rc;
@@ -501,6 +512,7 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
     ctx->pred_dt = dtype;
     ctx->pred_shape = *s;
     ctx->pred_bias = bias;
+    if (given) ctx->given_a = ctx->given_amax = nullptr;              // consumed
     // a correction inside this call replaces values the stored-side sums already contain
     ctx->sto_valid = stored && base == ABFT_DETECT;
     if (base == ABFT_DETECT_CORRECT) {
@@ -578,6 +590,15 @@ extern "C" int abft_gemm_static(const void *A, const void *B, void *C, abft_dtyp
         }
     }
     return abft_gemm(ctx, A, B, C, dtype, mode, s, r, stream);
+}
+
+extern "C" int abft_supply_a(abft_ctx *ctx, const void *a, const void *amax)
+{
+    if (!ctx || !a) return ABFT_EINVAL;
+    if (((uintptr_t)a & 3u) || ((uintptr_t)amax & 3u)) return ABFT_EALIGN;
+    ctx->given_a = a;
+    ctx->given_amax = amax;
+    return ABFT_OK;
 }
 
 extern "C" int abft_verify(abft_ctx *ctx, const void *C, abft_dtype dtype, const abft_shape *s,
@@ -742,6 +763,7 @@ extern "C" int abft_workspace(abft_ctx *ctx, int which, const abft_shape *s, voi
     case ABFT_WS_MAXABS:  *ptr = w.maxabs;  *count = 2 * b; break;
     case ABFT_WS_CC_STO:  *ptr = w.cc_sto;  *count = b * sh.N; break;
     case ABFT_WS_RC_STO:  *ptr = w.rc_sto;  *count = b * sh.M; break;
+    case ABFT_WS_C_MAX:   *ptr = w.c_max;   *count = b; break;
     default: return ABFT_EINVAL;
     }
     return ABFT_OK;

@@ -38,12 +38,13 @@ struct Workspace {
     uint32_t *s_pred;               // [batch]
     // one region that must be zero before the protected GEMM, filled by its atomics:
     //   cc_obs [batch][N] | rc_obs [batch][M] | rc_pred [batch][M] | a_sum [batch][K] | a_max [batch]
-    //   | cc_sto [batch][N] | rc_sto [batch][M]
+    //   | cc_sto [batch][N] | rc_sto [batch][M] | c_max [batch]
     uint32_t *cc_obs, *rc_obs;      // observed sums of C (epilogue)
     uint32_t *rc_pred;              // A (B e), from the operand slabs of A in LDS
     uint32_t *a_sum;                // a = e^T A, from the same slabs
     uint32_t *a_max;                // max|A| (float bits)
     uint32_t *cc_sto, *rc_sto;      // sums of C as stored (floating point, on request)
+    uint32_t *c_max;                // max|C as stored| (float bits) [batch], formed with them
     size_t zero_words;              // words from cc_obs on
     uint32_t *cc_vobs, *rc_vobs;    // re-summed from stored C
     // correction
@@ -53,6 +54,9 @@ struct Workspace {
     // not workspace, but travels with it: the layer bias of the current call (device, [N], float or
     // int32 words; null = none).  Added to every row of the product before rounding and sums.
     const uint32_t *bias;
+    // likewise: a = e^T A [batch][K] and max|A| [batch] (float bits; may be null) supplied by the
+    // caller for this call (null = formed by the GEMM from the slabs of A it holds)
+    const uint32_t *a_given, *amax_given;
 };
 
 struct Shape {

@@ -817,9 +817,10 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
     f.zero_ptr = zero_ptr; f.zero_words = zero_ptr ? zero_words : 0;
     f.B = (const uint8_t *)B; f.ldb = s.ldb; f.sB = s.sB; f.transB = s.transB;
     f.M = s.M; f.N = s.N; f.K = s.K;
-    f.a_sum = w.a_sum; f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;
+    f.a_sum = w.a_given ? w.a_given : w.a_sum;
+    f.b_sum = w.b_sum; f.rc_pred = w.rc_pred; f.cc_obs = w.cc_obs; f.rc_obs = w.rc_obs;
     f.bias = w.bias;
-    f.a_max = w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
+    f.a_max = (w.a_given && w.amax_given) ? w.amax_given : w.a_max; f.cc_pred = w.cc_pred; f.s_pred = w.s_pred; f.maxabs = w.maxabs; f.tau = w.tau;
     f.tau_override = v.tau_override; f.tau_override_cols = v.tau_override_cols;
     f.row_flag = v.row_flag; f.col_flag = v.col_flag; f.counts = v.counts; f.ticket = w.cmp_ticket;
     f.group_ticket = w.cmp_ticket + 4;

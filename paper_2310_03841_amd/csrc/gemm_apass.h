@@ -59,7 +59,9 @@ __host__ __device__ inline size_t apass_lds_bytes(int dt, int nslab, int tiles_n
 // that belong to the slab (LDS).  rows_valid: rows of the tile inside M (rows beyond may hold
 // anything, finite or not: they are ignored).  col_lds: KE words of this slab's column sums
 // (LDS atomics: the four waves add to the same words).
-template <int DT, int BM>
+// GIVEN: the caller supplied a = e^T A and max|A| (a checksum carried over from the kernel that
+// produced A): only the row dots are formed.
+template <int DT, int BM, bool GIVEN = false>
 __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds, int rows_valid,
                                        uint32_t *col_lds, APassState<DT> &st, bool mul24_ok)
 {
@@ -113,8 +115,10 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
                     const int wd = x4[d];
                     const s16x2 w = s16x2{(short)(wd & 0xFFFF), (short)(wd >> 16)};
                     const s16x2 ev = (w << 8) >> 8, od = w >> 8;       // bytes 0, 2 and 1, 3, sign-extended
-                    csp[2 * d] += ev;
-                    csp[2 * d + 1] += od;
+                    if (!GIVEN) {
+                        csp[2 * d] += ev;
+                        csp[2 * d + 1] += od;
+                    }
                     dhi = __builtin_amdgcn_sdot2(ev, bhi[2 * d], dhi, false);
                     dhi = __builtin_amdgcn_sdot2(od, bhi[2 * d + 1], dhi, false);
                     dlo = __builtin_amdgcn_sdot2(ev, blo[2 * d], dlo, false);
@@ -138,12 +142,12 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
 #pragma unroll
             for (int q = 0; q < CE; ++q) {
                 const acc_t x = T::elem(x4, q);
-                cs[q] = add_t(cs[q], x);
+                if (!GIVEN) cs[q] = add_t(cs[q], x);
                 if constexpr (T::IS_INT) {
                     dot = (acc_t)((uint32_t)x * (uint32_t)bv[q] + (uint32_t)dot);
                 } else {
                     dot = __builtin_fmaf((float)x, (float)bv[q], (float)dot);
-                    st.amax = fmaxf(st.amax, fabsf((float)x));
+                    if (!GIVEN) st.amax = fmaxf(st.amax, fabsf((float)x));
                 }
             }
             dot = row8_sum(dot);
@@ -151,6 +155,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
         }
     }
     st.rdot = add_t(st.rdot, mine);
+    if constexpr (GIVEN) return;
     // Column sums: first over the eight row groups of the wave (lanes with equal c), then one
     // LDS atomic per column and wave.  (LDS atomics in which several lanes of one instruction
     // hit the same word are served one lane at a time.)

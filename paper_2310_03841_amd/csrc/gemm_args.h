@@ -18,6 +18,9 @@ struct GemmArgs {
     uint32_t *a_sum;                              // e^T A                      [batch][K]
     uint32_t *a_max;                              // max|A| as float bits       [batch]
     uint32_t *cc_sto, *rc_sto;                    // sums of C as stored (after rounding), or null
+    uint32_t *c_max;                              // max|C as stored| as float bits [batch] (with cc_sto)
+    int a_given;                                  // a = e^T A and max|A| come from the caller: the pass over A's
+                                                  // slabs forms the row dots only, nothing is added to a_sum / a_max
     const uint32_t *bias;                         // layer bias [N] (float / int32 words) or null
     const uint32_t *b_sum;                        // B e, complete before the launch [batch][K]
     int mul24_ok;                                 // int8: |b| < 2^23, 24-bit multiplies are exact

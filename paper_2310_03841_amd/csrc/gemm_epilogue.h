@@ -153,6 +153,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
     // pass over the accumulators further down
     const bool sto = PROT && !T::IS_INT && g.cc_sto != nullptr;
     float colacc_s[CPL], rowsto[MI];
+    float cmax_s = 0.f;                 // max|value as stored| seen by this lane (with the stored-side sums)
 #pragma unroll
     for (int j = 0; j < CPL; ++j) colacc_s[j] = 0.f;
 #pragma unroll
@@ -255,7 +256,11 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                         T::store_c(Cb, (long)(br + r) * g.ldc + gc, v);
                         if (PROT) colacc[j] = add_t(colacc[j], v);
                         if constexpr (PROT && !T::IS_INT) {
-                            if (sto) colacc_s[j] += stored_value<DT>((float)v);
+                            if (sto) {
+                                const float sv = stored_value<DT>((float)v);
+                                colacc_s[j] += sv;
+                                cmax_s = fmaxf(cmax_s, fabsf(sv));
+                            }
                         }
                     }
                 }
@@ -357,6 +362,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                                 cp[PROT ? ni : 0][2 * h] = add_t(cp[PROT ? ni : 0][2 * h], (acc_t)s0);
                                 cp[PROT ? ni : 0][2 * h + 1] = add_t(cp[PROT ? ni : 0][2 * h + 1], (acc_t)s1);
                                 rsum += s0 + s1;
+                                cmax_s = fmaxf(cmax_s, fmaxf(fabsf(s0), fabsf(s1)));
                             });
                             __builtin_amdgcn_sched_barrier(0);
                         });
@@ -393,6 +399,9 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                     const int gc = wc0 + CPL * lane + j;
                     if (gc < N) unsafeAtomicAdd(reinterpret_cast<float *>(g.cc_sto) + (long)bz * N + gc, colacc_s[j]);
                 }
+                // the largest stored magnitude: what a consumer of this C needs as its max|A|
+                cmax_s = wave_max(cmax_s);
+                if (lane == 0 && cmax_s > 0.f && cmax_s == cmax_s) atomicMax(g.c_max + bz, __float_as_uint(cmax_s));
             }
         }
         // ---- what the pass over A's slabs left in registers
@@ -422,11 +431,11 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
             }
         }
         // column sums of A over this tile's rows, for the slabs this workgroup reduced
-        for (int t = tid; t < ep.owned * KE; t += 256) {
+        for (int t = tid; t < ep.owned * KE && !g.a_given; t += 256) {
             const int k = (ep.slab0 + (t / KE) * ep.slab_step) * KE + (t % KE);
             if (k < g.K) atomic_add_word(g.a_sum + (long)bz * g.K + k, from_word<acc_t>(ep.col_lds[t]));
         }
-        if (!T::IS_INT && tid == 0) {
+        if (!T::IS_INT && tid == 0 && !g.a_given) {
             const float m = fmaxf(fmaxf(amax4[0], amax4[1]), fmaxf(amax4[2], amax4[3]));
             if (m > 0.f) atomicMax(g.a_max + bz, __float_as_uint(m));
         }

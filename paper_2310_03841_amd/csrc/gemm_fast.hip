@@ -200,8 +200,12 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
             constexpr bool LOADS = decltype(loads_c)::value;
             const int buf = s & 1;
             if (PROT && s == next_own) {
-                a_pass<DT, BM>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
-                               g.mul24_ok != 0);
+                if (g.a_given)
+                    a_pass<DT, BM, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                                         g.mul24_ok != 0);
+                else
+                    a_pass<DT, BM>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                                   g.mul24_ok != 0);
                 next_own += g.tiles_n;
                 ep.owned += 1;
             }

@@ -213,8 +213,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     // flight in the other set).
     auto one_slab = [&](int s, SlabRegs &Rnext, SlabRegs & /*Rafter*/) __attribute__((always_inline)) {
         if (PROT && s == next_own) {
-            a_pass<DT, BM>(smem + (s & 1) * BUF, b_lds + ep.owned * KE, BM, col_lds + ep.owned * KE, ep.st,
-                           g.mul24_ok != 0);
+            if (g.a_given)
+                a_pass<DT, BM, true>(smem + (s & 1) * BUF, b_lds + ep.owned * KE, BM, col_lds + ep.owned * KE, ep.st,
+                                     g.mul24_ok != 0);
+            else
+                a_pass<DT, BM>(smem + (s & 1) * BUF, b_lds + ep.owned * KE, BM, col_lds + ep.owned * KE, ep.st,
+                               g.mul24_ok != 0);
             next_own += g.tiles_n;
             ep.owned += 1;
         }
@@ -303,6 +307,8 @@ hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, co
     g.bias = w.bias;
     g.cc_sto = (protect && stored_sums && dt != DT_I8) ? w.cc_sto : nullptr;
     g.rc_sto = g.cc_sto ? w.rc_sto : nullptr;
+    g.c_max = g.cc_sto ? w.c_max : nullptr;
+    g.a_given = (protect && w.a_given) ? 1 : 0;
     g.mul24_ok = s.N < 65536 ? 1 : 0;            // |b| <= 128 N
     g.tiles_m = g.tiles_n = g.n_big = g.tiles_m_big = g.tiles_m_small = 0;
     const bool tb = s.transB != 0;

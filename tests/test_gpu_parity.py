@@ -1088,6 +1088,95 @@ def test_gemm_with_layer_bias(ctx_items, dtype, M, N, K, batch, trans_b):
     assert np.array_equal(run.C(), C_prot)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N1,N2,K1", [(600, 512, 520, 256), (197, 768, 264, 128)])
+def test_input_checksum_carried_over_from_the_producer(ctx, dtype, M, N1, N2, K1):
+    """Sec. V "Optimizations" (2): the checksum of a tensor is generated while it is produced.
+    Producer C1 = A1 W1^T with the stored-side sums; consumer C2 = C1 W2^T takes e^T C1 and
+    max|C1| from the producer (abft_supply_a + ABFT_A_CHECKSUM_GIVEN) instead of forming them.
+    Clean: the consumer's vectors match the oracle's for the stored C1.  A bit of C1 flipped between
+    the two calls is outside the consumer's own view of its input (its row prediction is formed from
+    the flipped tensor) but disagrees with the carried checksum: the column check flags exactly the
+    columns the oracle names, the row check stays silent."""
+    A1, W1 = gen.gen_operands(dtype, M, N1, K1, 701, 702, trans_b=True)
+    _, W2 = gen.gen_operands(dtype, M, N2, N1, 703, 704, trans_b=True)
+    prod = Run(ctx, dtype, A1, W1, True)
+    prod.gemm(ab.ABFT_DETECT | ab.ABFT_STORED_SUMS)
+    assert prod.cnt()[2] == ab.ABFT_CLEAN
+    C1 = prod.C()                                               # (1, M, N1) bits as stored
+    a_ptr, na = ab.abft_workspace(ctx, ab.ABFT_WS_CC_STO, prod.shape)
+    m_ptr, _ = ab.abft_workspace(ctx, ab.ABFT_WS_C_MAX, prod.shape)
+    assert na == N1
+    # the producer's side of the hand-over against the oracle: column sums and max of the stored C1
+    C1d = orc.decode(C1[0], dtype)
+    assert np.max(np.abs(prod.ws(ab.ABFT_WS_CC_STO)[0] - C1d.sum(axis=0))) <= 1e-5 * M * np.max(np.abs(C1d))
+    assert prod.ws(ab.ABFT_WS_C_MAX)[0, 0] == np.float32(np.max(np.abs(C1d)))
+    # keep the carried vectors: the consumer's call reuses the context's regions
+    from abft_harness import _DevView
+    a_dev = torch.as_tensor(_DevView(a_ptr, N1, "<u4"), device="cuda").clone()
+    m_dev = torch.as_tensor(_DevView(m_ptr, 1, "<u4"), device="cuda").clone()
+    cons = Run(ctx, dtype, C1, W2, True)
+    P2 = orc.protected_gemm(C1[0], W2[0], dtype, True)
+
+    def consumer():
+        assert ab.abft_supply_a(ctx, a_dev, m_dev) == ab.ABFT_OK
+        cons.gemm(ab.ABFT_DETECT | ab.ABFT_A_CHECKSUM_GIVEN)
+    consumer()
+    rf, cf = cons.flags()
+    assert not rf.any() and not cf.any() and cons.cnt()[2] == ab.ABFT_CLEAN
+    tol = 1e-2 * P2.tau
+    assert cons.ws(ab.ABFT_WS_TAU)[0, 0] == pytest.approx(P2.tau, rel=1e-5)
+    assert np.max(np.abs(cons.ws(ab.ABFT_WS_CC_PRED)[0] - P2.cc_pred)) <= tol * np.sqrt(M)
+    assert np.max(np.abs(cons.ws(ab.ABFT_WS_RC_PRED)[0] - P2.rc_pred)) <= tol * np.sqrt(N2)
+    cc0, rc0, _ = orc.observe(P2.C_ref)
+    assert np.max(np.abs(cons.ws(ab.ABFT_WS_CC_OBS)[0] - cc0)) <= tol * np.sqrt(M)
+    assert np.max(np.abs(cons.ws(ab.ABFT_WS_RC_OBS)[0] - rc0)) <= tol * np.sqrt(N2)
+    assert np.max(np.abs(orc.decode(cons.C()[0], dtype) - P2.C_ref)) <= 1e-2 * np.max(np.abs(P2.C_ref))
+    # the mode bit without a supplied vector is refused (the pointers are consumed by the call)
+    assert ab.abft_gemm(ctx, cons.dA, cons.dB, cons.dC, cons.code, ab.ABFT_DETECT | ab.ABFT_A_CHECKSUM_GIVEN,
+                        cons.shape, cons.result()) == ab.ABFT_ESTATE
+    # a flip of C1 between producer and consumer
+    i, k, bit = M // 3, N1 // 5, 14
+    small = np.flatnonzero(np.abs(C1d[i]) < 1.0)
+    k = int(small[len(small) // 2])                            # below 2: bit 14 set makes it huge
+    cons.inject_operand("A", 0, i, k, bit)
+    consumer()
+    rf, cf = cons.flags()
+    A2f = orc.flip(C1[0], i, k, bit)
+    with np.errstate(all="ignore"):
+        delta = orc.decode(A2f, dtype)[i, k] - C1d[i, k]
+        shift = np.abs(delta * orc.decode(W2[0], dtype)[:, k])                 # what column j of C2 moved by
+    sure, quiet = ~(shift <= 2 * P2.tau), shift < P2.tau / 2
+    assert cf[0][sure].all() and not cf[0][quiet].any() and sure.any()
+    assert not rf.any() and cons.cnt()[2] == ab.ABFT_CHECKSUM_SUSPECT
+
+
+def test_input_checksum_given_int8(ctx):
+    """The same mode on the integer path: the caller's a = e^T A (here the oracle's, in Z/2^32);
+    an input flipped after its checksum was taken flags exactly the columns j with B[k,j] != 0."""
+    M, N, K = 300, 264, 256
+    A, B = gen.gen_operands("i8", M, N, K, 711, 712, trans_b=True)
+    P = orc.protected_gemm(A[0], B[0], "i8", True)
+    a_dev = torch.from_numpy(ring(P.a).view(np.int32)).to("cuda")
+    run = Run(ctx, "i8", A, B, True)
+    assert ab.abft_supply_a(ctx, a_dev, None) == ab.ABFT_OK
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_A_CHECKSUM_GIVEN)
+    assert run.cnt()[2] == ab.ABFT_CLEAN
+    assert np.array_equal(run.C()[0], P.C_stored)
+    assert np.array_equal(run.ws(ab.ABFT_WS_CC_PRED)[0].view(np.uint32), ring(P.cc_pred))
+    assert np.array_equal(run.ws(ab.ABFT_WS_RC_PRED)[0].view(np.uint32), ring(P.rc_pred))
+    i, k, bit = 123, 45, 6
+    run.inject_operand("A", 0, i, k, bit)
+    assert ab.abft_supply_a(ctx, a_dev, None) == ab.ABFT_OK
+    run.gemm(ab.ABFT_DETECT | ab.ABFT_A_CHECKSUM_GIVEN)
+    rf, cf = run.flags()
+    A2 = orc.flip(A[0], i, k, bit)
+    P2 = orc.protected_gemm(A2, B[0], "i8", True)
+    _, ocf, _, _, _, _ = orc.check(P, P2.C_stored)             # the old checksums against the new product
+    assert np.array_equal(cf[0], ocf) and not rf.any() and run.cnt()[2] == ab.ABFT_CHECKSUM_SUSPECT
+    assert np.array_equal(run.C()[0], P2.C_stored)
+
+
 @pytest.mark.parametrize("dtype", ["i8", "bf16"])
 def test_operand_injection_sites(ctx, dtype):
     """Flips in inputs and weights (Sec. II-A / III-A) through abft_inject: the bit lands where the
