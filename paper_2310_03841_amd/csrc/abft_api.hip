@@ -522,10 +522,13 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
         w.bias = (const uint32_t *)bias;
         const bool clear_list = ctx->list_dirty || ctx->graph_mode;
         ctx->list_dirty = true;
-        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, false, rp.stale, rp.other, rp.other_words, st));
+        // a clean call (the common case) must not pay for a pass over the whole stored C: the
+        // re-sum and the compare behind the recompute do nothing when no tile was listed
+        HIP_TRY(launch_correct(dtype, A, B, C, sh, w, v, false, clear_list, false, rp.stale, rp.other, rp.other_words, st,
+                               true));
         ctx->list_dirty = false;
         end_resum(ctx, words);
-        note_vobs(ctx, C, s, st);
+        ctx->vobs_valid = false;                 // whether the sums were formed is known on the device only
     }
     return ABFT_OK;
 }

@@ -99,18 +99,23 @@ hipError_t launch_finish(int dt, const void *B, const Shape &s, const Workspace 
 // with_sto: a row / column also flags when the re-summed stored C differs from the stored-side
 // sums of the GEMM by more than STO_TOL_FACTOR * tau
 // zero_ptr / zero_words: a region every block of the kernel helps to clear (may be null / 0)
+// gated: the kernel does nothing when the tile list of the correction before it is empty
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
-hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st);
+                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st, bool gated = false);
+hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st,
+                              bool gated = false);
 // stale_words: leading words of the re-summing region in use that must be cleared first;
 // zero_ptr / zero_words: the other re-summing region, cleared by the final compare
 // targeted: the re-summing region in use holds the sums of this C as it was before the call; only
 // the rows and columns of the recomputed tiles are summed again, in place (stale_words, zero_ptr unused)
+// skip_if_clean: when no tile was listed (the check before found nothing to recompute) the re-sum
+// of stored C and the final compare do nothing: flags and counts stay as that check wrote them
 // clear_list: the tile list's counters may be non-zero (the final compare of a correction leaves
 // them at zero, so only after a call that failed half way)
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
                           const Workspace &w, const Verdict &v, bool with_sto, bool clear_list, bool targeted,
-                          size_t stale_words, uint32_t *zero_ptr, size_t zero_words, hipStream_t st);
+                          size_t stale_words, uint32_t *zero_ptr, size_t zero_words, hipStream_t st,
+                          bool skip_if_clean = false);
 // integers: repairs a single flagged element per batch item from the checksums alone
 hipError_t launch_arith_fix(void *C, const Shape &s, const Workspace &w, const Verdict &v, hipStream_t st);
 // stored: the sums of the last re-sum of stored C instead of the epilogue's

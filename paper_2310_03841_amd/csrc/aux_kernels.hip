@@ -250,6 +250,8 @@ struct CmpArgs {
     uint32_t *zero_ptr;   // region every block helps to clear: the re-summing region not in use,
     size_t zero_words;    // so that the next re-sum finds it clean
     int M, N, batch;
+    const uint32_t *gate; // non-null: if *gate == 0 (no tile was listed for recomputation) the kernel
+                          // leaves flags and counts as the check before it wrote them
 };
 
 template <bool IS_INT>
@@ -264,6 +266,7 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
         const size_t bid = blockIdx.x + (size_t)gridDim.x * blockIdx.z;
         for (size_t i = bid * 256 + tid; i < a.zero_words; i += nb * 256) a.zero_ptr[i] = 0u;
     }
+    if (a.gate && *a.gate == 0u) return;           // uniform over the grid: nobody touches the ticket
     const float tol = IS_INT ? 0.f : (a.tau_override > 0.f ? a.tau_override : a.tau[bz]);
     const float tol_c = (!IS_INT && a.tau_override_cols > 0.f) ? a.tau_override_cols : tol;
     bool frow = false, fcol = false;
@@ -332,9 +335,10 @@ __global__ __launch_bounds__(256) void compare_kernel(CmpArgs a)
 }
 
 hipError_t launch_compare(int dt, const Shape &s, const Workspace &w, const Verdict &v, bool after_fix,
-                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
+                          bool with_sto, uint32_t *zero_ptr, size_t zero_words, hipStream_t st, bool gated)
 {
     CmpArgs a;
+    a.gate = gated ? w.fix_count : nullptr;
     a.zero_ptr = zero_ptr; a.zero_words = zero_ptr ? zero_words : 0;
     a.cc_sto = (with_sto && dt != DT_I8) ? w.cc_sto : nullptr;
     a.rc_sto = a.cc_sto ? w.rc_sto : nullptr;
@@ -921,6 +925,7 @@ struct VerArgs {
     int M, N;
     int cw_log2, rpb, nwin, nrb;
     uint32_t *cc_vobs, *rc_vobs;
+    const uint32_t *gate; // non-null: nothing to do if *gate == 0 (no tile was recomputed: C is as it was checked)
 };
 
 // value q of a 16-byte chunk of stored C
@@ -941,6 +946,7 @@ __global__ __launch_bounds__(256) void verify_kernel(VerArgs a)
     constexpr int OS = T::OS, CE = 16 / OS;
     __shared__ acc_t red[256 * CE];
     const int tid = threadIdx.x, bz = blockIdx.z;
+    if (a.gate && *a.gate == 0u) return;
     const int win = blockIdx.x % a.nwin, rb = blockIdx.x / a.nwin;
     const int CW = 1 << a.cw_log2, RL = 256 >> a.cw_log2;
     const int cx = tid & (CW - 1), ry = tid >> a.cw_log2;
@@ -992,9 +998,10 @@ __global__ __launch_bounds__(256) void verify_kernel(VerArgs a)
     }
 }
 
-hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st)
+hipError_t launch_verify_sums(int dt, const void *C, const Shape &s, const Workspace &w, hipStream_t st, bool gated)
 {
     VerArgs a;
+    a.gate = gated ? w.fix_count : nullptr;
     a.C = (const uint8_t *)C; a.ldc = s.ldc; a.sC = s.sC; a.M = s.M; a.N = s.N;
     a.cc_vobs = w.cc_vobs; a.rc_vobs = w.rc_vobs;
     EncPlan plan = plan_window(s.M, s.N, 16 / out_size(dt));
@@ -1344,7 +1351,7 @@ static hipError_t launch_recompute(const FixArgs &f, hipStream_t st)
 
 hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const Shape &s,
                           const Workspace &w, const Verdict &v, bool with_sto, bool clear_list, bool targeted,
-                          size_t stale_words, uint32_t *zero_ptr, size_t zero_words, hipStream_t st)
+                          size_t stale_words, uint32_t *zero_ptr, size_t zero_words, hipStream_t st, bool skip_if_clean)
 {
     hipError_t e = hipSuccess;
     if (clear_list && (e = launch_zero(w.fix_count, 2, st)) != hipSuccess) return e;
@@ -1384,8 +1391,8 @@ hipError_t launch_correct(int dt, const void *A, const void *B, void *C, const S
     // re-check without earlier sums of this C: the stored C is re-summed as a whole (a streaming
     // pass at HBM speed) and compared with the predictions
     if (stale_words && (e = launch_zero(w.cc_vobs, stale_words, st)) != hipSuccess) return e;
-    if ((e = launch_verify_sums(dt, C, s, w, st)) != hipSuccess) return e;
-    return launch_compare(dt, s, w, v, true, with_sto, zero_ptr, zero_words, st);
+    if ((e = launch_verify_sums(dt, C, s, w, st, skip_if_clean)) != hipSuccess) return e;
+    return launch_compare(dt, s, w, v, true, with_sto, zero_ptr, zero_words, st, skip_if_clean);
 }
 
 // ====================================================================== checksum-only correction
