@@ -8,6 +8,15 @@ slabs and its own accumulators, and the finish kernel (column prediction, compar
 every ABFT-side kernel is inside the timed region, nothing is cached.
 Useful work counted: 2*M*N*K only.
 
+The steps of the timed region are dealt round-robin to --streams HIP streams (default 2), each
+with its own context, its own batch of activations and its own output; the weight is shared.
+The three kernels of a step depend on each other, and the two small ones are bound by launch
+and memory latency, not by work: with a second, independent batch in flight the chip runs one
+batch's GEMM under the other's small kernels and fills the short last round of one GEMM with the
+first tiles of the next.  The unprotected baseline is timed the same way; the single-stream
+figures of every mode are reported beside it (protection.single_stream), and the per-kernel
+durations behind the roofline come from the single-stream leg, where kernels do not overlap.
+
 Prints ONE JSON line (see the fields below); everything else goes to stderr.
 """
 from __future__ import annotations
@@ -39,6 +48,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--streams", type=int, default=2,
+                    help="independent batches in flight (streams, each with a context of its own) in the "
+                         "timed region; 1 = every step waits for the one before it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--clock-warmup-ms", type=float, default=60.0,
                     help="before the warm-up steps, run the same step for this long: the shader clock of an "
@@ -88,13 +100,43 @@ def main():
 
     res = run.result()
 
-    def timed(mode, steps, warmup):
-        for _ in range(warmup):
-            step(mode)
+    # ---- the lanes of the pipelined region: lane i = (context, problem, result block, stream).
+    # Further lanes get a batch of activations of their own (another seed) and share the weight.
+    n_lanes = max(1, args.streams)
+    lanes = [(ctx, run, res, torch.cuda.Stream())]
+    for i in range(1, n_lanes):
+        Ai, _ = gen.gen_operands(dtype, M, N, K, gen.seed_for(1, 30 + i), gen.seed_for(1, 1), trans_b=True)
+        ci = ab.abft_create(max_rows=M, max_cols=N, max_depth=K, max_batch=1)
+        ri = Run(ci, dtype, Ai, B, True)
+        ri.dB = run.dB
+        lanes.append((ci, ri, ri.result(), torch.cuda.Stream()))
+        del Ai
+
+    def lane_step(i, mode):
+        c, r, rs, st = lanes[i]
+        rc = ab.abft_gemm(c, r.dA, r.dB, r.dC, r.code, mode, r.shape, None if mode == ab.ABFT_OFF else rs, st.cuda_stream)
+        if rc != ab.ABFT_OK:
+            raise RuntimeError(ab.abft_strerror(rc))
+
+    def timed(mode, steps, warmup, nl=1):
+        """W warm-up steps, then exactly K steps between two device-wide synchronisations; with
+        nl > 1 the steps go round-robin to nl lanes (nl = 1: the default stream, as a caller with
+        one dependent chain of layers would run)."""
+        if nl == 1:
+            for _ in range(warmup):
+                step(mode)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step(mode)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / steps
+        for k in range(warmup):
+            lane_step(k % nl, mode)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            step(mode)
+        for k in range(steps):
+            lane_step(k % nl, mode)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
@@ -122,25 +164,40 @@ def main():
                 cb = ab.abft_create(max_rows=bb * Mb, max_cols=bb * Nb, max_depth=bb * ((Kb + 127) // 128 * 128),
                                     max_batch=bb)
                 rb = Run(cb, cdt, Ab, Bb, tb)
-                resb = rb.result()
+                # a second, independent batch of the same class for the pipelined figures
+                cb2 = ab.abft_create(max_rows=bb * Mb, max_cols=bb * Nb, max_depth=bb * ((Kb + 127) // 128 * 128),
+                                     max_batch=bb)
+                rb2 = Run(cb2, cdt, Ab, Bb, tb)
+                if gg["b_kind"] == "weight":
+                    rb2.dB = rb.dB
+                blanes = [(cb, rb, rb.result(), torch.cuda.Stream()), (cb2, rb2, rb2.result(), torch.cuda.Stream())]
 
-                def tstep(mode, n=30):
-                    for it in range(n + 5):
-                        if it == 5:
+                def tstep(mode, n=30, nl=1):
+                    for it in range(n + 6):
+                        if it == 6:
                             torch.cuda.synchronize()
                             t0 = time.perf_counter()
-                        rcb = ab.abft_gemm(cb, rb.dA, rb.dB, rb.dC, rb.code, mode, rb.shape,
-                                           None if mode == ab.ABFT_OFF else resb)
+                        c_, r_, rs_, st_ = blanes[it % nl]
+                        rcb = ab.abft_gemm(c_, r_.dA, r_.dB, r_.dC, r_.code, mode, r_.shape,
+                                           None if mode == ab.ABFT_OFF else rs_, st_.cuda_stream if nl > 1 else None)
                         if rcb != ab.ABFT_OK:
                             raise RuntimeError(ab.abft_strerror(rcb))
                     torch.cuda.synchronize()
                     return (time.perf_counter() - t0) / n * 1e6
                 us_off, us_on = tstep(ab.ABFT_OFF), tstep(ab.ABFT_DETECT)
                 assert rb.cnt()[2] == ab.ABFT_CLEAN
-                us_c = tstep(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED) if gg["b_kind"] == "weight" else None
+                CB = ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED
+                us_c = tstep(CB) if gg["b_kind"] == "weight" else None
+                us_off2, us_on2 = tstep(ab.ABFT_OFF, nl=2), tstep(ab.ABFT_DETECT, nl=2)
+                assert rb.cnt()[2] == ab.ABFT_CLEAN and rb2.cnt()[2] == ab.ABFT_CLEAN
+                us_c2 = tstep(CB, nl=2) if gg["b_kind"] == "weight" else None
+                ab.abft_destroy(cb2)
+                del rb2, blanes
                 es, osz = (1, 4) if cdt == "i8" else (2, 2)
                 rows.append({"gemm": gg["name"], "M": Mb, "N": Nb, "K": Kb, "batch": bb,
                              "us_unprotected": us_off, "us_protected": us_on, "us_protected_b_cached": us_c,
+                             "two_streams": {"us_unprotected": us_off2, "us_protected": us_on2,
+                                             "us_protected_b_cached": us_c2},
                              "gflop": 2.0 * Mb * Nb * Kb * bb / 1e9,
                              "mbytes": bb * (Mb * Kb * es + Nb * Kb * es + Mb * Nb * osz) / 1e6,
                              "tile": list(ab.abft_tile_shape(rb.code, rb.shape))})
@@ -150,14 +207,24 @@ def main():
             t_off = sum(r["us_unprotected"] for r in rows)
             t_on = sum(r["us_protected"] for r in rows)
             t_c = sum(r["us_protected_b_cached"] or r["us_protected"] for r in rows)
+            t_off2 = sum(r["two_streams"]["us_unprotected"] for r in rows)
+            t_on2 = sum(r["two_streams"]["us_protected"] for r in rows)
+            t_c2 = sum(r["two_streams"]["us_protected_b_cached"] or r["two_streams"]["us_protected"] for r in rows)
             blocks[f"config{cfg + 1}_{cdt}"] = {"gemms": rows, "us_unprotected": t_off, "us_protected": t_on,
                                                "us_protected_weights_cached": t_c,
                                                "overhead_pct": 100.0 * (t_on - t_off) / t_off,
-                                               "overhead_pct_weights_cached": 100.0 * (t_c - t_off) / t_off}
+                                               "overhead_pct_weights_cached": 100.0 * (t_c - t_off) / t_off,
+                                               "two_streams": {
+                                                   "us_unprotected": t_off2, "us_protected": t_on2,
+                                                   "us_protected_weights_cached": t_c2,
+                                                   "overhead_pct": 100.0 * (t_on2 - t_off2) / t_off2,
+                                                   "overhead_pct_weights_cached": 100.0 * (t_c2 - t_off2) / t_off2,
+                                                   "note": "per class: calls dealt alternately to two streams, each "
+                                                           "with its own context, activations and output (us per call)"}}
             log(f"block config {cfg + 1} ({cdt}): " + "; ".join(
                 f"{r['gemm']} {r['us_unprotected']:.0f}->{r['us_protected']:.0f}" +
                 (f"/{r['us_protected_b_cached']:.0f}" if r['us_protected_b_cached'] else "") for r in rows) +
-                f" | total {t_off:.0f} -> {t_on:.0f} / {t_c:.0f} us")
+                f" | total {t_off:.0f} -> {t_on:.0f} / {t_c:.0f} us | two streams {t_off2:.0f} -> {t_on2:.0f} / {t_c2:.0f} us")
         return blocks
 
     if args.only_blocks:
@@ -185,18 +252,35 @@ def main():
             torch.cuda.synchronize()
             clock_steps += 50
 
+    # every lane has run a protected step (the cached mode needs the encoding of B in each context)
+    for i in range(n_lanes):
+        lane_step(i, ab.ABFT_DETECT)
+    torch.cuda.synchronize()
+
     # ---- the timed region of the contract: W warm-up steps, then exactly K steps
-    ms_prot = timed(ab.ABFT_DETECT, args.steps, args.warmup)
+    CACHED = ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED
+    ms_prot = timed(ab.ABFT_DETECT, args.steps, args.warmup, n_lanes)
+    for c, r, rs, st in lanes:
+        cnt = r.cnt()
+        assert cnt[2] == ab.ABFT_CLEAN, f"clean run flagged: {cnt}"
     cnt = run.cnt()
-    assert cnt[2] == ab.ABFT_CLEAN, f"clean run flagged: {cnt}"
-    ms_off = timed(ab.ABFT_OFF, args.steps, args.warmup)
-    ms_cached = timed(ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED, args.steps, args.warmup)
-    # interleaved repeat to average out clock drift between the two modes
-    reps = []
-    for _ in range(3):
-        reps.append((timed(ab.ABFT_DETECT, args.steps, 2), timed(ab.ABFT_OFF, args.steps, 2)))
-    ms_prot_i = float(np.median([r[0] for r in reps]))
-    ms_off_i = float(np.median([r[1] for r in reps]))
+    ms_off = timed(ab.ABFT_OFF, args.steps, args.warmup, n_lanes)
+    ms_cached = timed(CACHED, args.steps, args.warmup, n_lanes)
+    # interleaved repeats to average out clock drift between the modes
+    def interleaved(nl):
+        reps = [(timed(ab.ABFT_DETECT, args.steps, 2, nl), timed(ab.ABFT_OFF, args.steps, 2, nl),
+                 timed(CACHED, args.steps, 2, nl)) for _ in range(3)]
+        return [float(np.median([r[k] for r in reps])) for k in range(3)]
+    ms_prot_i, ms_off_i, ms_cached_i = interleaved(n_lanes)
+    # the same three modes with one stream: every step waits for the one before it
+    if n_lanes > 1:
+        s1 = interleaved(1)
+        single = {"protected_ms": s1[0], "unprotected_ms": s1[1], "protected_b_cached_ms": s1[2],
+                  "overhead_pct": 100.0 * (s1[0] - s1[1]) / s1[1], "overhead_pct_b_cached": 100.0 * (s1[2] - s1[1]) / s1[1],
+                  "tflops": flops / (s1[0] * 1e-3) / 1e12,
+                  "note": "same steps on one stream (medians of three interleaved rounds of K steps)"}
+    else:
+        single = None
 
     # ---- spread of single steps (events around every step; the events themselves cost ~1 us)
     def step_percentiles(mode, n=100):
@@ -241,7 +325,10 @@ def main():
     gemm_ms = prof[1]
     # matrix-pipe ceiling at the clock the chip sustains (a kernel of matrix instructions only)
     peak_meas, clock_mhz = ab.abft_mfma_peak(run.code, 0.1)
-    log(f"protected step {ms_prot:.4f} ms | unprotected {ms_off:.4f} ms | B cached {ms_cached:.4f} ms")
+    log(f"{n_lanes} stream(s): protected step {ms_prot:.4f} ms | unprotected {ms_off:.4f} ms | B cached {ms_cached:.4f} ms")
+    if single:
+        log(f"one stream: protected {single['protected_ms']:.4f} ms | unprotected {single['unprotected_ms']:.4f} ms | "
+            f"B cached {single['protected_b_cached_ms']:.4f} ms")
     log(f"kernel events: pass over B {prof[0]*1e3:.1f} us, gemm {prof[1]*1e3:.1f} us, finish {prof[2]*1e3:.1f} us; "
         f"unprotected gemm {prof_off[1]*1e3:.1f} us")
 
@@ -543,7 +630,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_prot,
-        "ms_per_step_event_p50": spread["protected"]["p50_us"] * 1e-3,
+        "ms_per_step_event_p50_single_stream": spread["protected"]["p50_us"] * 1e-3,
         "clock_warmup_steps": clock_steps,
         "higher_is_better": True,
         "scaling": "weak",
@@ -553,11 +640,16 @@ def main():
         "config": {"workload": "ViT-B MLP fc1, batch 64, bf16: A 12608x768 N(0,1), W 3072x768 N(0,0.02), "
                                "C bf16, fp32 accumulate + fp32 checksums", "M": M, "N": N, "K": K,
                    "mode": "DETECT (pass over B, GEMM with A-slab and accumulator sums, finish: predict + compare)",
+                   "streams": n_lanes,
+                   "pipelining": "steps dealt round-robin to the streams; a context, a batch of activations and an "
+                                 "output per stream, the weight shared; the unprotected baseline is timed the same way",
                    "tile": list(ab.abft_tile_shape(run.code, run.shape))},
         "roofline": {"bound": "mfma", "achieved": flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[dtype],
                      "unit": "TFLOP/s", "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
                      "traffic": MEASURED_TRAFFIC_BYTES, "kernel": "gemm_fast_kernel<bf16, 256, 256, protected>",
                      "kernel_ms": gemm_ms,
+                     "kernel_ms_note": "HIP events around the kernel on its launch stream, average over K steps of the "
+                                       "single-stream leg (kernels of different streams overlap in the pipelined leg)",
                      "peak_measured": peak_meas, "frac_of_measured": flops / (gemm_ms * 1e-3) / 1e12 / peak_meas,
                      "sustained_clock_mhz": clock_mhz,
                      "peak_measured_note": "abft_mfma_peak: 0.1 s of matrix instructions only, one wave per SIMD, "
@@ -565,8 +657,11 @@ def main():
         "protection": {
             "unprotected_ms": ms_off, "unprotected_tflops": flops / (ms_off * 1e-3) / 1e12,
             "overhead_pct": 100.0 * (ms_prot_i - ms_off_i) / ms_off_i,
-            "overhead_pct_b_cached": 100.0 * (ms_cached - ms_off) / ms_off,
-            "interleaved_ms": [ms_prot_i, ms_off_i],
+            "overhead_pct_b_cached": 100.0 * (ms_cached_i - ms_off_i) / ms_off_i,
+            "interleaved_ms": {"protected": ms_prot_i, "unprotected": ms_off_i, "protected_b_cached": ms_cached_i,
+                               "note": "medians of three interleaved rounds of K steps; the two percentages come from these"},
+            "b_cached_ms": ms_cached,
+            "single_stream": single,
             "kernel_us": {"pass_over_B": prof[0] * 1e3, "gemm": prof[1] * 1e3, "finish": prof[2] * 1e3,
                           "gemm_unprotected": prof_off[1] * 1e3},
             "frac_of_peak_whole_step": flops / (ms_prot * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
@@ -611,7 +706,8 @@ def main():
                                "cores": orc.threads(), "kind": "oracle",
                                "sample": f"first {rows} of {M} rows of A against the full weight: fp64 "
                                          f"GEMM, encode, predict, observe, flags ({dt:.1f} s)"}
-    ab.abft_destroy(ctx)
+    for c, r, rs, st in lanes:
+        ab.abft_destroy(c)
     print(json.dumps(out), flush=True)
 
 

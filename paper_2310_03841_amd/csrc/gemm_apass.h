@@ -61,7 +61,8 @@ __host__ __device__ inline size_t apass_lds_bytes(int dt, int nslab, int tiles_n
 // (LDS atomics: the four waves add to the same words).
 // GIVEN: the caller supplied a = e^T A and max|A| (a checksum carried over from the kernel that
 // produced A): only the row dots are formed.
-template <int DT, int BM, bool GIVEN = false>
+// SW16: the slab's swizzle is slot = chunk ^ ((row >> 1) & 7) (gemm_fast) instead of chunk ^ (row & 7).
+template <int DT, int BM, bool GIVEN = false, bool SW16 = false>
 __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds, int rows_valid,
                                        uint32_t *col_lds, APassState<DT> &st, bool mul24_ok)
 {
@@ -71,7 +72,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
     constexpr int P = BM / 32;
     const int tid = threadIdx.x;
     const int c = tid & 7, rg = tid >> 3;
-    const uint8_t *src = sA + rg * SLAB_BYTES + ((c ^ (rg & 7)) * 16);
+    const uint8_t *src = sA + rg * SLAB_BYTES + ((c ^ (SW16 ? (rg >> 1) & 7 : rg & 7)) * 16);
 
     acc_t bv[CE], cs[CE];
 #pragma unroll

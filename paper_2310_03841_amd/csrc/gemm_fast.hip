@@ -50,13 +50,17 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     const uint8_t *Bb = g.B + (long)bz * g.sB * ES;
 
     // ---- global sources.  Load group p of this wave covers tile rows (4 p + wave) * 8 .. + 8;
-    // lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches the chunk (l & 7) ^ (l >> 3)
-    // so that LDS slot = chunk ^ (row & 7).  An address is a wave-uniform base (tile origin plus
+    // lane l lands in LDS row + (l >> 3), slot (l & 7), and fetches the chunk for which
+    // LDS slot = chunk ^ ((row >> 1) & 7).  (A 16-byte fragment read is served sixteen lanes at a
+    // time from 64 banks: sixteen consecutive rows must fall on sixteen different 16-byte bank
+    // groups.  Two consecutive 128-byte rows span all 64 banks, so the eight even rows need eight
+    // different slots, and so do the eight odd rows; chunk ^ (row & 7) makes rows r and r + 8
+    // collide, which the LDS bank-conflict counter showed as half of all LDS cycles.)  An address is a wave-uniform base (tile origin plus
     // the slab's offset along K) plus a per-lane 32-bit offset that never changes, so issuing a
     // load inside the main loop costs no vector arithmetic and no branch.  Rows of the tile past
     // the end of the matrix fetch the last valid row instead.
     const int lrow = lane >> 3;
-    const int lchunk = (lane & 7) ^ lrow;
+    const int lchunk = (lane & 7) ^ (((wave & 1) << 2) + (lrow >> 1));
     const uint8_t *a_base = Ab + (long)m0 * g.lda * ES;
     const uint8_t *b_base = Bb + (long)n0 * g.ldb * ES;
     uint32_t a_off[GA], b_off[GB];
@@ -106,7 +110,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     auto ldfr = [&](int buf, int s4, int set) __attribute__((always_inline)) {
         const uint8_t *sA = smem + buf * BUF;
         const uint8_t *sB = sA + BM * SLAB_BYTES;
-        const int sw = ((2 * s4 + lh) ^ (lane & 7)) * 16;
+        const int sw = ((2 * s4 + lh) ^ ((lane >> 1) & 7)) * 16;
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
             fa[set][mi] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + mi * 32 + l32) * SLAB_BYTES + sw);
@@ -144,7 +148,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         uint8_t *dB = dA + BM * SLAB_BYTES;
         const uint8_t *sA = smem + (buf ^ 1) * BUF;
         const uint8_t *sB = sA + BM * SLAB_BYTES;
-        const int sw = (lh ^ (lane & 7)) * 16;
+        const int sw = (lh ^ ((lane >> 1) & 7)) * 16;
         static_for<0, NMF>([&](auto j_c) {
             constexpr int j = decltype(j_c)::value;
             constexpr int mi = j / NI, ni = j % NI;
@@ -201,10 +205,10 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
             const int buf = s & 1;
             if (PROT && s == next_own) {
                 if (g.a_given)
-                    a_pass<DT, BM, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
                                          g.mul24_ok != 0);
                 else
-                    a_pass<DT, BM>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, false, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
                                    g.mul24_ok != 0);
                 next_own += g.tiles_n;
                 ep.owned += 1;
