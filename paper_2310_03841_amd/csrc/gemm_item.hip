@@ -735,14 +735,13 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                 for (int p = 0; p < 4; ++p) {
                     // the waves that share these rows add their parts (distinct words per lane)
                     const acc_t r = row8_sum(rsum[p]);
-                    if ((lane & 7) == 0 && mact) {
-                        uint32_t *dst = rcobs + m0 + wm * 32 + 8 * p + (lane >> 3);
-                        if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)r);
-                        else atomicAdd(reinterpret_cast<float *>(dst), (float)r);
-                    }
+                    // (the add as the instruction itself: through atomicAdd the compiler, which
+                    // cannot tell these words from the targets of the direct-to-LDS loads, makes the
+                    // wave wait for every store of C it has in flight before each add)
+                    if ((lane & 7) == 0 && mact) lds_add_word(rcobs + m0 + wm * 32 + 8 * p + (lane >> 3), r);
                     if constexpr (STO) {
                         const float rs = row8_sum(rsum_s[p]);
-                        if ((lane & 7) == 0 && mact) atomicAdd(reinterpret_cast<float *>(rcsto) + m0 + wm * 32 + 8 * p + (lane >> 3), rs);
+                        if ((lane & 7) == 0 && mact) lds_add_word(rcsto + m0 + wm * 32 + 8 * p + (lane >> 3), rs);
                     }
                 }
             }
@@ -777,15 +776,14 @@ __global__ __launch_bounds__(RES ? 256 : ITEM_THREADS) void gemm_item_kernel(Ite
                     if (lane < 8 && nb < NB) {
                         uint32_t *dst = ccobs + nb * 32 + 4 * lane + e;
                         if (WM == 1) *dst = as_word(v);
-                        else if constexpr (T::IS_INT) atomicAdd(reinterpret_cast<int *>(dst), (int)v);
-                        else atomicAdd(reinterpret_cast<float *>(dst), (float)v);
+                        else lds_add_word(dst, v);
                     }
                     if constexpr (STO) {
                         float vs = cs_s[t][e];
                         vs = add_t(vs, dpp_get<0x128>(vs));       // lane ^ 8
                         vs = add_xor16(vs);
                         vs = add_xor32(vs);
-                        if (lane < 8 && nb < NB) atomicAdd(reinterpret_cast<float *>(ccsto) + nb * 32 + 4 * lane + e, vs);
+                        if (lane < 8 && nb < NB) lds_add_word(ccsto + nb * 32 + 4 * lane + e, vs);
                     }
                 }
             }
