@@ -112,8 +112,21 @@ def main():
         lanes.append((ci, ri, ri.result(), torch.cuda.Stream()))
         del Ai
 
-    def lane_step(i, mode):
+    # Every context records an event behind each of its GEMM kernels; after a synchronisation the
+    # first call of lane i waits for the first GEMM of lane i - 1, so that the lanes' GEMMs do not
+    # start together (they would share the chip, end together and leave it idle during both
+    # finish kernels; from an offset start the lanes stay apart by themselves).
+    lane_events = []
+    for c, r, rs, st in lanes:
+        ev = torch.cuda.Event()
+        ev.record(st)
+        assert ab.abft_gemm_done_event(c, ev.cuda_event) == ab.ABFT_OK
+        lane_events.append(ev)
+
+    def lane_step(i, mode, first=False):
         c, r, rs, st = lanes[i]
+        if first and i > 0:
+            st.wait_event(lane_events[i - 1])
         rc = ab.abft_gemm(c, r.dA, r.dB, r.dC, r.code, mode, r.shape, None if mode == ab.ABFT_OFF else rs, st.cuda_stream)
         if rc != ab.ABFT_OK:
             raise RuntimeError(ab.abft_strerror(rc))
@@ -132,11 +145,11 @@ def main():
             torch.cuda.synchronize()
             return (time.perf_counter() - t0) * 1e3 / steps
         for k in range(warmup):
-            lane_step(k % nl, mode)
+            lane_step(k % nl, mode, first=k < nl)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(steps):
-            lane_step(k % nl, mode)
+            lane_step(k % nl, mode, first=k < nl)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
@@ -171,6 +184,9 @@ def main():
                 if gg["b_kind"] == "weight":
                     rb2.dB = rb.dB
                 blanes = [(cb, rb, rb.result(), torch.cuda.Stream()), (cb2, rb2, rb2.result(), torch.cuda.Stream())]
+                bev = torch.cuda.Event()
+                bev.record(blanes[0][3])
+                assert ab.abft_gemm_done_event(cb, bev.cuda_event) == ab.ABFT_OK
 
                 def tstep(mode, n=30, nl=1):
                     for it in range(n + 6):
@@ -178,6 +194,8 @@ def main():
                             torch.cuda.synchronize()
                             t0 = time.perf_counter()
                         c_, r_, rs_, st_ = blanes[it % nl]
+                        if nl > 1 and it in (1, 7):              # second lane's first call after a synchronisation
+                            st_.wait_event(bev)
                         rcb = ab.abft_gemm(c_, r_.dA, r_.dB, r_.dC, r_.code, mode, r_.shape,
                                            None if mode == ab.ABFT_OFF else rs_, st_.cuda_stream if nl > 1 else None)
                         if rcb != ab.ABFT_OK:
@@ -642,7 +660,9 @@ def main():
                    "mode": "DETECT (pass over B, GEMM with A-slab and accumulator sums, finish: predict + compare)",
                    "streams": n_lanes,
                    "pipelining": "steps dealt round-robin to the streams; a context, a batch of activations and an "
-                                 "output per stream, the weight shared; the unprotected baseline is timed the same way",
+                                 "output per stream, the weight shared; after each synchronisation the second stream's "
+                                 "first call waits for the first stream's first GEMM kernel (abft_gemm_done_event); the "
+                                 "unprotected baseline is timed the same way",
                    "tile": list(ab.abft_tile_shape(run.code, run.shape))},
         "roofline": {"bound": "mfma", "achieved": flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[dtype],
                      "unit": "TFLOP/s", "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],

@@ -227,6 +227,21 @@ int abft_gemm_static(const void *A, const void *B, void *C, abft_dtype dtype, in
  * that call's ABFT_WS_CC_STO and ABFT_WS_C_MAX.  ABFT_WS_A_SUM is not filled by such a call. */
 int abft_supply_a(abft_ctx *ctx, const void *a, const void *amax);
 
+/* Pipelining several independent GEMMs (Sec. IV-C: the check must stay a small fraction of the
+ * layer's time).  A protected call is a chain of dependent kernels of which only the GEMM fills
+ * the chip; the pass over B and the finish kernel are bound by latency.  Two streams, each with a
+ * context of its own, hide them: while one stream's GEMM runs, the other stream's small kernels
+ * run beside it.  For that the two GEMMs must not start together (they would share the chip, end
+ * together and leave it idle during both finish kernels, and that state persists).  `event` is a
+ * caller-owned hipEvent_t that every following abft_gemm / abft_gemm_bias of this context (any
+ * mode, also ABFT_OFF) records on its stream right behind its GEMM kernel, before the finish
+ * kernel; the caller lets the other stream wait for it (hipStreamWaitEvent) before that stream's
+ * first call, after which the streams stay half a step apart by themselves.  NULL stops the
+ * recording.  Nothing is recorded while a call is being captured into a graph, nor by protected
+ * calls of a context once one of its calls has been captured.  The event must stay
+ * valid until it is replaced or the context destroyed; the library never waits on it. */
+int abft_gemm_done_event(abft_ctx *ctx, void *event);
+
 /* Re-sums the stored C and compares with the predictions the last abft_gemm of this shape left
  * in the context (Sec. III-B.1: sum of layer activations vs. checksum product).  Overwrites
  * flags and counts.  Floating point: the stored values are rounded, and the rounding of a row of

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libabft.so")
 
 __all__ = [
     "ABFT_I8", "ABFT_BF16", "ABFT_F16", "ABFT_OFF", "ABFT_DETECT", "ABFT_DETECT_CORRECT",
-    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_A_CHECKSUM_GIVEN", "ABFT_WS_C_MAX", "abft_supply_a", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
+    "ABFT_B_CHECKSUM_CACHED", "ABFT_STORED_SUMS", "ABFT_A_CHECKSUM_GIVEN", "ABFT_WS_C_MAX", "abft_supply_a", "abft_gemm_done_event", "ABFT_DISC_FUSED", "ABFT_DISC_STORED", "ABFT_OK", "ABFT_EINVAL", "ABFT_EALIGN", "ABFT_ESHAPE", "ABFT_EWORKSPACE",
     "ABFT_EHIP", "ABFT_ESTATE", "ABFT_CLEAN", "ABFT_LOCALISED", "ABFT_CHECKSUM_SUSPECT", "ABFT_TOO_MANY",
     "ABFT_INJECT_STORED_C", "ABFT_INJECT_ACCUMULATOR", "ABFT_INJECT_OPERAND_A", "ABFT_INJECT_OPERAND_B",
     "ABFT_WS_A_SUM", "ABFT_WS_B_SUM", "ABFT_WS_CC_PRED", "ABFT_WS_RC_PRED", "ABFT_WS_CC_OBS",
@@ -81,6 +81,7 @@ _SIGS = {
                                         ctypes.c_int, ctypes.c_int, ctypes.POINTER(abft_shape),
                                         ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_supply_a": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]),
+    "abft_gemm_done_event": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p]),
     "abft_verify": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(abft_shape),
                                    ctypes.POINTER(abft_result), ctypes.c_void_p]),
     "abft_correct": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -218,6 +219,11 @@ def abft_gemm_static(A, B, C, dtype: int, mode: int, shape: abft_shape, result: 
     r = ctypes.byref(result) if result is not None else None
     return int(lib().abft_gemm_static(_ptr(A), _ptr(B), _ptr(C), dtype, mode, ctypes.byref(shape), r,
                                       _stream(stream)))
+
+
+def abft_gemm_done_event(ctx, event) -> int:
+    """event: a hipEvent_t handle as an integer (torch.cuda.Event(...).cuda_event after its first record), or None"""
+    return int(lib().abft_gemm_done_event(ctx, ctypes.c_void_p(int(event)) if event else None))
 
 
 def abft_supply_a(ctx, a, amax=None) -> int:

@@ -43,6 +43,7 @@ struct abft_ctx {
     bool list_dirty;        // the tile list's counters may be non-zero (a correction failed half way)
     int b_dt, pred_dt;
     const void *given_a, *given_amax;   // abft_supply_a: a = e^T A and max|A| for the next call with ABFT_A_CHECKSUM_GIVEN
+    hipEvent_t done_event;              // abft_gemm_done_event: recorded behind every GEMM kernel (null: none)
     const void *pred_bias;  // layer bias of the GEMM the predictions belong to (abft_correct adds it to recomputed tiles)
     abft_shape b_shape, pred_shape;
     // optional kernel timing (abft_profile_begin / _end)
@@ -380,6 +381,7 @@ static int enqueue_tiled(abft_ctx *ctx, int dtype, bool cached, bool stored, con
     if (ev) HIP_TRY(hipEventRecord(ev[1], st));
     ctx->sto_valid = false;
     HIP_TRY(launch_gemm(dtype, true, stored, A, B, C, sh, *w, arm, st));
+    if (ctx->done_event && !gm) HIP_TRY(hipEventRecord(ctx->done_event, st));
     if (ev) HIP_TRY(hipEventRecord(ev[2], st));
     if (gm) {
         HIP_TRY(launch_finish(dtype, B, sh, *w, v, nullptr, 0, nullptr, 0, st));
@@ -412,6 +414,7 @@ static int enqueue_item(abft_ctx *ctx, int dtype, bool cached, bool stored, cons
     if (ctx->dirty[ctx->cur] < w.zero_words) ctx->dirty[ctx->cur] = w.zero_words;
     ctx->sto_valid = false;
     HIP_TRY(launch_gemm_item(dtype, true, cached, stored, A, B, C, sh, w, &v, arm, st));
+    if (ctx->done_event && !in_graph_mode(ctx, st)) HIP_TRY(hipEventRecord(ctx->done_event, st));
     if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); }
     return ABFT_OK;
 }
@@ -485,6 +488,7 @@ static int gemm_impl(abft_ctx *ctx, const void *A, const void *B, const void *bi
         hipEvent_t *ev = (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) ? ctx->prof_ev + 4 * ctx->prof_n : nullptr;
         if (ev) { HIP_TRY(hipEventRecord(ev[0], st)); HIP_TRY(hipEventRecord(ev[1], st)); }
         HIP_TRY(launch_gemm(dtype, false, false, A, B, C, sh, w, arm, st));
+        if (ctx->done_event && !capturing(st)) HIP_TRY(hipEventRecord(ctx->done_event, st));
         if (ev) { HIP_TRY(hipEventRecord(ev[2], st)); HIP_TRY(hipEventRecord(ev[3], st)); ctx->prof_n++; }
         return ABFT_OK;
     }
@@ -593,6 +597,13 @@ extern "C" int abft_gemm_static(const void *A, const void *B, void *C, abft_dtyp
         }
     }
     return abft_gemm(ctx, A, B, C, dtype, mode, s, r, stream);
+}
+
+extern "C" int abft_gemm_done_event(abft_ctx *ctx, void *event)
+{
+    if (!ctx) return ABFT_EINVAL;
+    ctx->done_event = (hipEvent_t)event;
+    return ABFT_OK;
 }
 
 extern "C" int abft_supply_a(abft_ctx *ctx, const void *a, const void *amax)

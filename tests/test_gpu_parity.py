@@ -1424,3 +1424,83 @@ def test_two_contexts_on_two_streams():
     finally:
         ab.abft_destroy(c1)
         ab.abft_destroy(c2)
+
+
+def test_two_streams_half_a_step_apart():
+    """Two independent batches of one Linear layer, each with a context and a stream of its own,
+    the weight shared: every context records an event behind its GEMM kernel
+    (abft_gemm_done_event) and the second stream's first call waits for the first stream's GEMM.
+    Results must be those of each batch's own problem, in every mode, and the events must have
+    been recorded."""
+    M, N, K = 1100, 768, 256
+    ctxs = [ab.abft_create(max_rows=M, max_cols=N, max_depth=K, max_batch=1) for _ in range(2)]
+    try:
+        A0, B = gen.gen_operands("bf16", M, N, K, 301, 302, trans_b=True)
+        A1, _ = gen.gen_operands("bf16", M, N, K, 303, 302, trans_b=True)
+        runs = [Run(ctxs[0], "bf16", A0, B, True), Run(ctxs[1], "bf16", A1, B, True)]
+        runs[1].dB = runs[0].dB                                  # one weight tensor for both
+        Ps = [oracle_items("bf16", A0, B, True), oracle_items("bf16", A1, B, True)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        events = []
+        for c, st in zip(ctxs, streams):
+            ev = torch.cuda.Event()
+            ev.record(st)
+            assert ab.abft_gemm_done_event(c, ev.cuda_event) == ab.ABFT_OK
+            events.append(ev)
+        torch.cuda.synchronize()
+        for mode in (ab.ABFT_DETECT, ab.ABFT_DETECT | ab.ABFT_B_CHECKSUM_CACHED, ab.ABFT_OFF, ab.ABFT_DETECT):
+            print(f"two streams mode={mode}", flush=True)
+            for k in range(6):
+                i = k & 1
+                r = runs[i]
+                if k == 1:
+                    streams[1].wait_event(events[0])
+                rc = ab.abft_gemm(ctxs[i], r.dA, r.dB, r.dC, r.code, mode, r.shape,
+                                  None if mode == ab.ABFT_OFF else r.result(), streams[i].cuda_stream)
+                assert rc == ab.ABFT_OK, ab.abft_strerror(rc)
+            torch.cuda.synchronize()
+            assert events[0].query() and events[1].query()
+            if mode != ab.ABFT_OFF:
+                check_clean(runs[0], Ps[0])
+                check_clean(runs[1], Ps[1])
+        assert ab.abft_gemm_done_event(ctxs[0], None) == ab.ABFT_OK
+        runs[0].gemm(ab.ABFT_DETECT)
+        check_clean(runs[0], Ps[0])
+    finally:
+        for c in ctxs:
+            ab.abft_destroy(c)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "bf16"])
+def test_detect_correct_on_clean_input_leaves_the_fused_verdict(ctx, dtype):
+    """A clean DETECT_CORRECT call recomputes nothing and does not re-sum the stored C: flags,
+    counts and C are those of a DETECT call; a stored flip afterwards is still found and repaired
+    (the correction then sums the stored C itself)."""
+    M, N, K = 700, 520, 192
+    A, B = gen.gen_operands(dtype, M, N, K, 311, 312, trans_b=True)
+    run = Run(ctx, dtype, A, B, True)
+    P = oracle_items(dtype, A, B, True)
+    run.gemm(ab.ABFT_DETECT)
+    C_clean = run.C().copy()
+    for rep in range(3):
+        run.gemm(ab.ABFT_DETECT_CORRECT)
+        cnt = run.cnt()
+        rf, cf = run.flags()
+        assert not rf.any() and not cf.any()
+        assert cnt[0] == 0 and cnt[1] == 0 and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 0 and cnt[4] == ab.ABFT_CLEAN
+        assert np.array_equal(run.C(), C_clean)
+    check_clean(run, P)
+    run.inject(0, 321, 123, 30 if dtype == "i8" else 14)
+    run.verify()
+    rf, cf = run.flags()
+    assert rf[0, 321] and cf[0, 123]
+    run.correct()
+    assert np.array_equal(run.C(), C_clean) and run.cnt()[2] == ab.ABFT_CLEAN
+    # and a fault inside a DETECT_CORRECT call is repaired by that call, clean calls before and after
+    run.inject(0, 5, 7, 30, ab.ABFT_INJECT_ACCUMULATOR)
+    run.gemm(ab.ABFT_DETECT_CORRECT)
+    cnt = run.cnt()
+    assert np.array_equal(run.C(), C_clean) and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 1 and cnt[4] == ab.ABFT_LOCALISED
+    run.gemm(ab.ABFT_DETECT_CORRECT)
+    cnt = run.cnt()
+    assert np.array_equal(run.C(), C_clean) and cnt[2] == ab.ABFT_CLEAN and cnt[3] == 0
