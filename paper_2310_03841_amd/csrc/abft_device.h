@@ -12,6 +12,17 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
+// The thread's index inside its workgroup, as a value the optimiser cannot move or merge.  Code
+// that runs once per tile inside a loop over tiles derives dozens of per-lane addresses from
+// it; taken from the plain built-in they are all computed once before the loop and held in
+// registers across it (40 more vector registers in the fast GEMM kernel).
+__device__ __forceinline__ int tile_thread_index()
+{
+    int t = (int)threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 // ---------------------------------------------------------------- conversions
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 

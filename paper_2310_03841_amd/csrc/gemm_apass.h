@@ -62,7 +62,9 @@ __host__ __device__ inline size_t apass_lds_bytes(int dt, int nslab, int tiles_n
 // GIVEN: the caller supplied a = e^T A and max|A| (a checksum carried over from the kernel that
 // produced A): only the row dots are formed.
 // SW16: the slab's swizzle is slot = chunk ^ ((row >> 1) & 7) (gemm_fast) instead of chunk ^ (row & 7).
-template <int DT, int BM, bool GIVEN = false, bool SW16 = false>
+// SPLIT_ONLY: int8 with |b| < 2^23 guaranteed by the caller (mul24_ok is not consulted): the
+// element-wise integer form is left out, which is what keeps the fast kernel's registers free of spills.
+template <int DT, int BM, bool GIVEN = false, bool SW16 = false, bool SPLIT_ONLY = false>
 __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds, int rows_valid,
                                        uint32_t *col_lds, APassState<DT> &st, bool mul24_ok)
 {
@@ -70,7 +72,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
     typedef typename T::acc_t acc_t;
     constexpr int CE = 16 / T::ES;
     constexpr int P = BM / 32;
-    const int tid = threadIdx.x;
+    const int tid = tile_thread_index();
     const int c = tid & 7, rg = tid >> 3;
     const uint8_t *src = sA + rg * SLAB_BYTES + ((c ^ (SW16 ? (rg >> 1) & 7 : rg & 7)) * 16);
 
@@ -89,7 +91,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
     acc_t mine = T::zero();
     bool done = false;
     if constexpr (T::IS_INT) {
-        if (mul24_ok) {
+        if (mul24_ok || SPLIT_ONLY) {
             // |b| <= 128 N < 2^23: b = 256 hi + lo with 0 <= lo < 256 and |hi| < 2^15.  The bytes of a
             // word of A as two pairs of 16-bit integers (bytes 0, 2 and bytes 1, 3): the column sums
             // add pair-wise (at most 8 rows per thread), the row product takes two products per
@@ -134,7 +136,7 @@ __device__ __forceinline__ void a_pass(const uint8_t *sA, const uint32_t *b_lds,
             done = true;
         }
     }
-    if (!done) {
+    if (!(T::IS_INT && SPLIT_ONLY) && !done) {
 #pragma unroll
         for (int p = 0; p < P; ++p) {
             i32x4 x4 = v[p];

@@ -10,7 +10,8 @@ struct GemmArgs {
     int M, N, K;
     long lda, ldb, ldc, sA, sB, sC;               // elements
     int tiles_m, tiles_n;
-    int n_big, tiles_m_big, tiles_m_small;        // fast path: 256-row tiles first, then 128-row tiles
+    int n_big, tiles_m_big, tiles_m_small;        // fast path: 256-row tiles and 128-row tiles
+    int n_small, batch;                           // fast path: 128-row tiles per batch item; batch items
     int inj_b, inj_row, inj_col, inj_bit;         // armed accumulator flip (inj_b < 0: none)
     // protected launches: all of these are accumulated with atomics and start at zero
     uint32_t *cc_obs, *rc_obs;                    // observed sums of C        [batch][N], [batch][M]

@@ -113,7 +113,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
     constexpr int WAVE_BYTES = epi_wave_bytes(TN);
     constexpr int CROW = TN * OS + 16;              // staged C row (bytes), padded
     constexpr int SROW = TN * 4 + 16;               // staged 32-bit row (bytes), padded
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = tile_thread_index(), lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;

@@ -40,7 +40,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     constexpr int GA = BM / 32, GB = BN / 32;     // 8-row load groups per wave per slab
     constexpr int BUF = (BM + BN) * SLAB_BYTES;
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = tile_thread_index(), lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform by construction
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -205,10 +205,10 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
             const int buf = s & 1;
             if (PROT && s == next_own) {
                 if (g.a_given)
-                    a_pass<DT, BM, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, true, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
                                          g.mul24_ok != 0);
                 else
-                    a_pass<DT, BM, false, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, false, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
                                    g.mul24_ok != 0);
                 next_own += g.tiles_n;
                 ep.owned += 1;
@@ -260,19 +260,25 @@ template <int DT, bool PROT>
 __global__ __launch_bounds__(256) void gemm_fast_kernel(GemmArgs g)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int bid = blockIdx.x, bz = blockIdx.z;
-    int tm, tn;
-    // The 128-row tiles are dispatched first: the compute units that start with one are half a
+    // Persistent workgroups: one per compute unit, each walks the tile list with the grid's stride.
+    // The 128-row tiles come first in the list: the compute units that start with one are half a
     // tile ahead of the others from then on, so the two groups store their tiles of C at different
     // times (a round of the machine that stores in step asks for tens of MB at once) and draw on
     // the matrix pipes at different times.  Measured on 12608 x 3072 x 768: 63 -> 60.5 us.
-    const int n_small = (int)gridDim.x - g.n_big;
-    if (bid >= n_small) {
-        map_tile(bid - n_small, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tn);
-    } else {
-        map_tile(bid, n_small, g.tiles_m_small, g.tiles_n, &tm, &tn);
-        fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, tn);
+    const int per_item = g.n_small + g.n_big;
+    const int total = per_item * g.batch;
+    for (int t = blockIdx.x; t < total; t += gridDim.x) {
+        const int bz = t / per_item, bid = t - bz * per_item;
+        int tm, tn;
+        if (bid >= g.n_small) {
+            map_tile(bid - g.n_small, g.n_big, g.tiles_m_big, g.tiles_n, &tm, &tn);
+            fast_tile<DT, 256, 256, PROT>(g, smem, tm * 256, tn * 256, bz, tn);
+        } else {
+            map_tile(bid, g.n_small, g.tiles_m_small, g.tiles_n, &tm, &tn);
+            fast_tile<DT, 128, 256, PROT>(g, smem, g.tiles_m_big * 256 + tm * 128, tn * 256, bz, tn);
+        }
+        // the epilogue's last reads of LDS precede the next tile's first writes
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     }
 }
 
@@ -348,7 +354,11 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
     const int rest = g.M - big_rows * 256;
     g.tiles_m_small = rest > 0 ? (rest + 127) / 128 : 0;
     g.tiles_m = g.tiles_m_big + g.tiles_m_small;
-    dim3 grid((unsigned)(g.n_big + g.tiles_m_small * g.tiles_n), 1, (unsigned)batch);
+    g.n_small = g.tiles_m_small * g.tiles_n;
+    g.batch = batch;
+    const long total = (long)(g.n_big + g.n_small) * batch;
+    if (total > 0x7FFFFFFFL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(total < num_cu ? total : num_cu), 1, 1);
     size_t smem = smem_main;
     if (PROT) {
         const int ke = SLAB_BYTES / Traits<DT>::ES;
@@ -364,7 +374,8 @@ bool gemm_fast_eligible(int dt, int M, int N, int K, bool transB, long lda, long
     const int ke = SLAB_BYTES / elem_size(dt);
     // whole slabs, at least three of them (the main loop is peeled), and 32-bit row offsets
     // inside a tile
-    return transB && (K % ke) == 0 && K >= 3 * ke && M >= 512 && N >= 512 &&
+    // (int8: N < 65536 keeps |b| <= 128 N below 2^23, which the pass over A's slabs relies on here)
+    return transB && (K % ke) == 0 && K >= 3 * ke && M >= 512 && N >= 512 && (dt != DT_I8 || N < 65536) &&
            lda * elem_size(dt) < (1L << 23) && ldb * elem_size(dt) < (1L << 23);
 }
 

@@ -311,6 +311,7 @@ hipError_t launch_gemm(int dt, bool protect, bool stored_sums, const void *A, co
     g.a_given = (protect && w.a_given) ? 1 : 0;
     g.mul24_ok = s.N < 65536 ? 1 : 0;            // |b| <= 128 N
     g.tiles_m = g.tiles_n = g.n_big = g.tiles_m_big = g.tiles_m_small = 0;
+    g.n_small = 0; g.batch = s.batch;
     const bool tb = s.transB != 0;
     if (gemm_fast_eligible(dt, s.M, s.N, s.K, tb, s.lda, s.ldb)) return launch_gemm_fast(dt, protect, g, s.batch, st);
     switch (dt) {
