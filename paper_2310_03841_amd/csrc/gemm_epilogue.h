@@ -96,6 +96,8 @@ template <int DT> struct EpiProt {
     const uint32_t *col_lds;  // column sums of the owned slabs, KE words each (LDS)
     int owned;                // number of owned slabs reduced: the j-th is slab slab0 + j * slab_step of K
     int slab0, slab_step;
+    int col_copies;           // 1, or 4: one set of column sums per wave, col_stride words apart, to be added up
+    int col_stride;
 };
 
 template <int DT, int BM, int BN, bool PROT, bool BIAS>
@@ -433,7 +435,11 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
         // column sums of A over this tile's rows, for the slabs this workgroup reduced
         for (int t = tid; t < ep.owned * KE && !g.a_given; t += 256) {
             const int k = (ep.slab0 + (t / KE) * ep.slab_step) * KE + (t % KE);
-            if (k < g.K) atomic_add_word(g.a_sum + (long)bz * g.K + k, from_word<acc_t>(ep.col_lds[t]));
+            if (k < g.K) {
+                acc_t v = from_word<acc_t>(ep.col_lds[t]);
+                for (int w = 1; w < ep.col_copies; ++w) v = add_t(v, from_word<acc_t>(ep.col_lds[w * ep.col_stride + t]));
+                atomic_add_word(g.a_sum + (long)bz * g.K + k, v);
+            }
         }
         if (!T::IS_INT && tid == 0 && !g.a_given) {
             const float m = fmaxf(fmaxf(amax4[0], amax4[1]), fmaxf(amax4[2], amax4[3]));

@@ -175,21 +175,24 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
     EpiProt<DT> ep;
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
     ep.col_lds = col_lds; ep.slab0 = tn; ep.slab_step = g.tiles_n; ep.owned = 0;
+    ep.col_copies = 4; ep.col_stride = 0;
     {
         const int nslab = K / KE;                      // at least 3 (gemm_fast_eligible)
         int next_own = tn;
         const int owned = (PROT && tn < nslab) ? (nslab - tn + g.tiles_n - 1) / g.tiles_n : 0;
-        uint32_t *b_lds = col_lds + owned * KE;
+        // column sums: one set of owned * KE words per wave (plain stores, added up by the epilogue)
+        ep.col_stride = owned * KE;
+        uint32_t *col_mine = col_lds + wave * owned * KE;
+        uint32_t *b_lds = col_lds + 4 * owned * KE;
         if (PROT) {
-            // the values of b the owned slabs need, straight into LDS (one slab per wave and turn),
-            // and zeros for the column sums; both are in place behind the first barrier
+            // the values of b the owned slabs need, straight into LDS (one slab per wave and turn):
+            // in place behind the first barrier
             for (int j = wave; j < owned; j += 4) {
                 const uint32_t *src = g.b_sum + (long)bz * K + (long)(tn + j * g.tiles_n) * KE + lane;
 #pragma unroll
                 for (int h = 0; h < KE / 64; ++h)
                     __builtin_amdgcn_global_load_lds((gas_ptr)(src + 64 * h), (las_ptr)(b_lds + j * KE + 64 * h), 4, 0, 0);
             }
-            for (int t = tid; t < owned * KE; t += 256) col_lds[t] = 0u;
         }
         issue_loads(0, 0);
         issue_loads(1, 1);
@@ -200,15 +203,17 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
         else if constexpr (GA + GB == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         else __syncthreads();
         ldfr(0, 0, 0);
-        auto slab = [&](auto first_c, auto loads_c, int s) __attribute__((always_inline)) {
+        // own_c: whether the slab can be one that this workgroup reduces (the first slab and the last
+        // two: the pass then runs ahead of the slab's MFMAs; the middle slabs have own_slab below)
+        auto slab = [&](auto first_c, auto loads_c, auto own_c, int s) __attribute__((always_inline)) {
             constexpr bool LOADS = decltype(loads_c)::value;
             const int buf = s & 1;
-            if (PROT && s == next_own) {
+            if (PROT && decltype(own_c)::value && s == next_own) {
                 if (g.a_given)
-                    a_pass<DT, BM, true, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, true, true, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_mine + ep.owned * KE, ep.st,
                                          g.mul24_ok != 0);
                 else
-                    a_pass<DT, BM, false, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_lds + ep.owned * KE, ep.st,
+                    a_pass<DT, BM, false, true, true, true>(smem + buf * BUF, b_lds + ep.owned * KE, a_rows, col_mine + ep.owned * KE, ep.st,
                                    g.mul24_ok != 0);
                 next_own += g.tiles_n;
                 ep.owned += 1;
@@ -228,9 +233,79 @@ __device__ __forceinline__ void fast_tile(const GemmArgs &g, uint8_t *smem, int 
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        slab(std::true_type{}, std::true_type{}, 0);
-        for (int s = 1; s < nslab - 2; ++s) slab(std::false_type{}, std::true_type{}, s);
-        for (int s = nslab - 2; s < nslab; ++s) slab(std::false_type{}, std::false_type{}, s);
+        // A middle slab that this workgroup reduces: the same MFMAs, fragment reads and loads as any
+        // other slab, in explicit program order (one group per MFMA, fenced), with one piece of the
+        // pass over the slab (gemm_apass.h) behind every MFMA.  The pieces start half a step late, so
+        // that the chunks begin() requested have arrived.  Straight-line code of its own: a branch
+        // around the pass inside the common slab code keeps it apart from the MFMAs, and the pass
+        // then runs while the matrix pipe waits.
+        // (With a checksum of A supplied by the caller the column sums and the maximum are formed all
+        // the same, under the MFMAs, and not handed on: a second copy of the slab would have to sit
+        // behind a branch.)
+        auto own_slab = [&](int s) __attribute__((always_inline)) {
+            constexpr bool GIVEN = false;
+            constexpr int NMF = MI * NI, NLD = GA + GB, LAG = NMF / 2;
+            const int buf = s & 1;
+            APassSteps<DT, BM, GIVEN> ap;
+            __builtin_amdgcn_sched_barrier(0);
+            ap.begin(smem + buf * BUF, b_lds + ep.owned * KE, a_rows);
+            const uint8_t *ak = a_base + (long)(s + 2) * SLAB_BYTES;
+            const uint8_t *bk = b_base + (long)(s + 2) * SLAB_BYTES;
+            uint8_t *dA = smem + buf * BUF;
+            uint8_t *dB = dA + BM * SLAB_BYTES;
+            static_for<0, 4>([&](auto t_c) {
+                constexpr int t = decltype(t_c)::value;
+                constexpr int set = t & 1, nset = set ^ 1;
+                // fragments of the next step: step t + 1 of this slab, or step 0 of the next slab
+                const uint8_t *sA = smem + (t < 3 ? buf : buf ^ 1) * BUF;
+                const uint8_t *sB = sA + BM * SLAB_BYTES;
+                const int sw = ((2 * ((t + 1) & 3) + lh) ^ ((lane >> 1) & 7)) * 16;
+                static_for<0, NMF>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    constexpr int mi = j / NI, ni = j % NI;
+                    acc[mi][ni] = T::mfma(fb[set][ni], fa[set][mi], acc[mi][ni]);
+                    if constexpr (j < MI)
+                        fa[nset][j] = *reinterpret_cast<const i32x4 *>(sA + (wm * TM + j * 32 + l32) * SLAB_BYTES + sw);
+                    else if constexpr (j < MI + NI)
+                        fb[nset][j - MI] = *reinterpret_cast<const i32x4 *>(sB + (wn * TN + (j - MI) * 32 + l32) * SLAB_BYTES + sw);
+                    if constexpr (t == 3) {
+                        constexpr int l0 = j * NLD / NMF, l1 = (j + 1) * NLD / NMF;
+                        static_for<l0, l1>([&](auto l_c) {
+                            constexpr int l = decltype(l_c)::value;
+                            if constexpr (l < GA)
+                                __builtin_amdgcn_global_load_lds((gas_ptr)(ak + a_off[l]), (las_ptr)(dA + (4 * l + wave) * 8 * SLAB_BYTES), 16, 0, 0);
+                            else
+                                __builtin_amdgcn_global_load_lds((gas_ptr)(bk + b_off[l - GA]), (las_ptr)(dB + (4 * (l - GA) + wave) * 8 * SLAB_BYTES), 16, 0, 0);
+                        });
+                    }
+                    ap.template piece<t * NMF + j - LAG>();
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                if constexpr (t == 2) __syncthreads();
+            });
+            static_for<4 * NMF - LAG, 4 * NMF>([&](auto k_c) { ap.template piece<decltype(k_c)::value>(); });
+            ap.end(col_mine + ep.owned * KE, ep.st);
+            __builtin_amdgcn_sched_barrier(0);
+            next_own += g.tiles_n;
+            ep.owned += 1;
+        };
+        typedef std::false_type never_own;
+        typedef std::true_type maybe_own;
+        slab(std::true_type{}, std::true_type{}, maybe_own{}, 0);
+        // the middle slabs: runs of slabs that are not this workgroup's, each followed by one that is
+        int s = 1;
+        const int mid_end = nslab - 2;
+        // (loops and straight-line code only: an if / else with MFMAs in both arms would move the
+        // accumulators out of the accumulation registers)
+        if constexpr (PROT) {
+            while (next_own < mid_end) {                   // next_own >= s here
+                for (; s < next_own; ++s) slab(std::false_type{}, std::true_type{}, never_own{}, s);
+                own_slab(s);
+                ++s;
+            }
+        }
+        for (; s < mid_end; ++s) slab(std::false_type{}, std::true_type{}, never_own{}, s);
+        for (; s < nslab; ++s) slab(std::false_type{}, std::false_type{}, maybe_own{}, s);
     }
     __syncthreads();
     gemm_epilogue<DT, BM, BN, PROT>(g, acc, smem, m0, n0, bz, ep);
@@ -362,7 +437,7 @@ static hipError_t launch_fast_one(GemmArgs &g, int batch, hipStream_t st)
     size_t smem = smem_main;
     if (PROT) {
         const int ke = SLAB_BYTES / Traits<DT>::ES;
-        smem += apass_lds_bytes(DT, g.K / ke, g.tiles_n);
+        smem += apass_lds_bytes_per_wave(DT, g.K / ke, g.tiles_n);
         if (smem > (size_t)smem_max) return hipErrorInvalidValue;
     }
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, g);
@@ -376,7 +451,10 @@ bool gemm_fast_eligible(int dt, int M, int N, int K, bool transB, long lda, long
     // inside a tile
     // (int8: N < 65536 keeps |b| <= 128 N below 2^23, which the pass over A's slabs relies on here)
     return transB && (K % ke) == 0 && K >= 3 * ke && M >= 512 && N >= 512 && (dt != DT_I8 || N < 65536) &&
-           lda * elem_size(dt) < (1L << 23) && ldb * elem_size(dt) < (1L << 23);
+           lda * elem_size(dt) < (1L << 23) && ldb * elem_size(dt) < (1L << 23) &&
+           // what the pass over A's slabs keeps per tile fits behind the operand buffers (protected or
+           // not: the tile shape of a problem does not depend on the mode)
+           2 * (256 + 256) * SLAB_BYTES + apass_lds_bytes_per_wave(dt, K / ke, (N + 255) / 256) <= 160 * 1024;
 }
 
 void gemm_fast_tile(int *tm, int *tn) { *tm = 256; *tn = 256; }

@@ -194,6 +194,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
     EpiProt<DT> ep;
     ep.st.rdot = T::zero(); ep.st.amax = 0.f;
     ep.col_lds = col_lds; ep.slab0 = tn_idx; ep.slab_step = g.tiles_n; ep.owned = 0;
+    ep.col_copies = 1; ep.col_stride = 0;
     int next_own = tn_idx;
     const int owned = (PROT && tn_idx < nslab) ? (nslab - tn_idx + g.tiles_n - 1) / g.tiles_n : 0;
     uint32_t *b_lds = col_lds + owned * KE;
