@@ -406,8 +406,9 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                 if (lane == 0 && cmax_s > 0.f && cmax_s == cmax_s) atomicMax(g.c_max + bz, __float_as_uint(cmax_s));
             }
         }
-        // ---- what the pass over A's slabs left in registers
-        {
+        // ---- what the pass over A's slabs left in registers (nothing in a tile that reduced no slab:
+        // where K has fewer slabs than the tile row has tiles, that is most tiles)
+        if (ep.owned > 0) {
             constexpr int P = BM / 32;
             const int c = tid & 7, rg = tid >> 3;
             if (c < P) rp[rg + 32 * c] = ep.st.rdot;
@@ -424,7 +425,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                 const int gr = m0 + t;
                 if (gr < M) {
                     atomic_add_word(g.rc_obs + (long)bz * M + gr, add_t(rs_part[t], rs_part[BM + t]));
-                    atomic_add_word(g.rc_pred + (long)bz * M + gr, rp[t]);
+                    if (ep.owned > 0) atomic_add_word(g.rc_pred + (long)bz * M + gr, rp[t]);
                 }
             } else {
                 const int gc = n0 + (t - BM);
@@ -441,7 +442,7 @@ __device__ __forceinline__ void gemm_epilogue_impl(const GemmArgs &g,
                 atomic_add_word(g.a_sum + (long)bz * g.K + k, v);
             }
         }
-        if (!T::IS_INT && tid == 0 && !g.a_given) {
+        if (!T::IS_INT && tid == 0 && !g.a_given && ep.owned > 0) {
             const float m = fmaxf(fmaxf(amax4[0], amax4[1]), fmaxf(amax4[2], amax4[3]));
             if (m > 0.f) atomicMax(g.a_max + bz, __float_as_uint(m));
         }
