@@ -98,6 +98,8 @@ SHAPES = [
     (520, 1030, 256, 2, True),     # 256x256-tile path for all types, ragged both ways, batched
     (512, 512, 128, 1, True),      # tile-exact on the 256x256 path
     (520, 600, 4096, 1, True),     # deepest K of a protected GEMM: 16 / 32 slabs per workgroup to reduce
+    (600, 512, 640, 1, True),      # two tile columns: a workgroup reduces every other slab of its tile row
+    (520, 1300, 1152, 1, True),    # six tile columns, a ragged last one: owned slabs three (int8: one or two) apart
     (140, 90, 4096, 1, False),     # the same on the general kernel
 ]
 
