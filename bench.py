@@ -8,14 +8,16 @@ slabs and its own accumulators, and the finish kernel (column prediction, compar
 every ABFT-side kernel is inside the timed region, nothing is cached.
 Useful work counted: 2*M*N*K only.
 
-The steps of the timed region are dealt round-robin to --streams HIP streams (default 2), each
+The steps of the timed region are dealt round-robin to --streams HIP streams (default 3), each
 with its own context, its own batch of activations and its own output; the weight is shared.
 The three kernels of a step depend on each other, and the two small ones are bound by launch
-and memory latency, not by work: with a second, independent batch in flight the chip runs one
-batch's GEMM under the other's small kernels and fills the short last round of one GEMM with the
-first tiles of the next.  The unprotected baseline is timed the same way; the single-stream
-figures of every mode are reported beside it (protection.single_stream), and the per-kernel
-durations behind the roofline come from the single-stream leg, where kernels do not overlap.
+and memory latency, not by work: with further independent batches in flight the chip runs one
+batch's GEMM under the others' small kernels and fills the short last round of one GEMM with the
+first tiles of the next.  The unprotected baseline is timed the same way with one, two, ...
+streams, and the fastest of them counts (the unprotected kernel is fastest with two); the
+single-stream figures of every mode are reported beside it (protection.single_stream), and the
+per-kernel durations behind the roofline come from the single-stream leg, where kernels do not
+overlap.
 
 Prints ONE JSON line (see the fields below); everything else goes to stderr.
 """
@@ -48,7 +50,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=3,
                     help="independent batches in flight (streams, each with a context of its own) in the "
                          "timed region; 1 = every step waits for the one before it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -282,17 +284,27 @@ def main():
         cnt = r.cnt()
         assert cnt[2] == ab.ABFT_CLEAN, f"clean run flagged: {cnt}"
     cnt = run.cnt()
-    ms_off = timed(ab.ABFT_OFF, args.steps, args.warmup, n_lanes)
+    # The unprotected kernel is timed with every number of streams up to the one in use and the
+    # fastest of them is the baseline: more GEMMs in flight than two make the unprotected kernel
+    # slower (its workgroups share the caches with more neighbours), and the overhead must not
+    # profit from that.
+    off_lanes = list(range(1, n_lanes + 1))
+    ms_off_by_lanes = {k: timed(ab.ABFT_OFF, args.steps, args.warmup, k) for k in off_lanes}
+    ms_off = min(ms_off_by_lanes.values())
     ms_cached = timed(CACHED, args.steps, args.warmup, n_lanes)
     # interleaved repeats to average out clock drift between the modes
-    def interleaved(nl):
-        reps = [(timed(ab.ABFT_DETECT, args.steps, 2, nl), timed(ab.ABFT_OFF, args.steps, 2, nl),
+    def interleaved(nl, off_nl):
+        reps = [(timed(ab.ABFT_DETECT, args.steps, 2, nl), [timed(ab.ABFT_OFF, args.steps, 2, k) for k in off_nl],
                  timed(CACHED, args.steps, 2, nl)) for _ in range(3)]
-        return [float(np.median([r[k] for r in reps])) for k in range(3)]
-    ms_prot_i, ms_off_i, ms_cached_i = interleaved(n_lanes)
+        off = [float(np.median([r[1][j] for r in reps])) for j in range(len(off_nl))]
+        return float(np.median([r[0] for r in reps])), off, float(np.median([r[2] for r in reps]))
+    ms_prot_i, off_i, ms_cached_i = interleaved(n_lanes, off_lanes)
+    ms_off_i = min(off_i)
+    off_streams_i = off_lanes[off_i.index(ms_off_i)]
     # the same three modes with one stream: every step waits for the one before it
     if n_lanes > 1:
-        s1 = interleaved(1)
+        s1p, s1o, s1c = interleaved(1, [1])
+        s1 = (s1p, s1o[0], s1c)
         single = {"protected_ms": s1[0], "unprotected_ms": s1[1], "protected_b_cached_ms": s1[2],
                   "overhead_pct": 100.0 * (s1[0] - s1[1]) / s1[1], "overhead_pct_b_cached": 100.0 * (s1[2] - s1[1]) / s1[1],
                   "tflops": flops / (s1[0] * 1e-3) / 1e12,
@@ -660,9 +672,9 @@ def main():
                    "mode": "DETECT (pass over B, GEMM with A-slab and accumulator sums, finish: predict + compare)",
                    "streams": n_lanes,
                    "pipelining": "steps dealt round-robin to the streams; a context, a batch of activations and an "
-                                 "output per stream, the weight shared; after each synchronisation the second stream's "
-                                 "first call waits for the first stream's first GEMM kernel (abft_gemm_done_event); the "
-                                 "unprotected baseline is timed the same way",
+                                 "output per stream, the weight shared; after each synchronisation every further stream's "
+                                 "first call waits for the first GEMM kernel of the stream before it (abft_gemm_done_event); "
+                                 "the unprotected baseline is timed the same way with 1..streams streams and the fastest counts",
                    "tile": list(ab.abft_tile_shape(run.code, run.shape))},
         "roofline": {"bound": "mfma", "achieved": flops / (gemm_ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS[dtype],
                      "unit": "TFLOP/s", "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
@@ -679,7 +691,12 @@ def main():
             "overhead_pct": 100.0 * (ms_prot_i - ms_off_i) / ms_off_i,
             "overhead_pct_b_cached": 100.0 * (ms_cached_i - ms_off_i) / ms_off_i,
             "interleaved_ms": {"protected": ms_prot_i, "unprotected": ms_off_i, "protected_b_cached": ms_cached_i,
-                               "note": "medians of three interleaved rounds of K steps; the two percentages come from these"},
+                               "unprotected_by_streams": {str(k): v for k, v in zip(off_lanes, off_i)},
+                               "unprotected_streams": off_streams_i,
+                               "note": "medians of three interleaved rounds of K steps; the two percentages come from "
+                                       "these; the unprotected figure is that of the number of streams (1..streams) at "
+                                       "which the unprotected kernel is fastest"},
+            "unprotected_ms_by_streams": {str(k): v for k, v in ms_off_by_lanes.items()},
             "b_cached_ms": ms_cached,
             "single_stream": single,
             "kernel_us": {"pass_over_B": prof[0] * 1e3, "gemm": prof[1] * 1e3, "finish": prof[2] * 1e3,

@@ -229,9 +229,9 @@ int abft_supply_a(abft_ctx *ctx, const void *a, const void *amax);
 
 /* Pipelining several independent GEMMs (Sec. IV-C: the check must stay a small fraction of the
  * layer's time).  A protected call is a chain of dependent kernels of which only the GEMM fills
- * the chip; the pass over B and the finish kernel are bound by latency.  Two streams, each with a
- * context of its own, hide them: while one stream's GEMM runs, the other stream's small kernels
- * run beside it.  For that the two GEMMs must not start together (they would share the chip, end
+ * the chip; the pass over B and the finish kernel are bound by latency.  Two or three streams,
+ * each with a context of its own, hide them: while one stream's GEMM runs, the other streams' small
+ * kernels run beside it.  For that the GEMMs must not start together (they would share the chip, end
  * together and leave it idle during both finish kernels, and that state persists).  `event` is a
  * caller-owned hipEvent_t that every following abft_gemm / abft_gemm_bias of this context (any
  * mode, also ABFT_OFF) records on its stream right behind its GEMM kernel, before the finish
