@@ -293,9 +293,13 @@ def main():
     ms_off = min(ms_off_by_lanes.values())
     ms_cached = timed(CACHED, args.steps, args.warmup, n_lanes)
     # interleaved repeats to average out clock drift between the modes
+    # (at least 200 steps per leg: a leg starts and ends with a synchronisation, and filling and
+    # draining three lanes of three dependent kernels each is 2-3 % of a leg of 20 steps)
+    steps_i = max(args.steps, 200)
+
     def interleaved(nl, off_nl):
-        reps = [(timed(ab.ABFT_DETECT, args.steps, 2, nl), [timed(ab.ABFT_OFF, args.steps, 2, k) for k in off_nl],
-                 timed(CACHED, args.steps, 2, nl)) for _ in range(3)]
+        reps = [(timed(ab.ABFT_DETECT, steps_i, 5, nl), [timed(ab.ABFT_OFF, steps_i, 5, k) for k in off_nl],
+                 timed(CACHED, steps_i, 5, nl)) for _ in range(3)]
         off = [float(np.median([r[1][j] for r in reps])) for j in range(len(off_nl))]
         return float(np.median([r[0] for r in reps])), off, float(np.median([r[2] for r in reps]))
     ms_prot_i, off_i, ms_cached_i = interleaved(n_lanes, off_lanes)
@@ -308,7 +312,7 @@ def main():
         single = {"protected_ms": s1[0], "unprotected_ms": s1[1], "protected_b_cached_ms": s1[2],
                   "overhead_pct": 100.0 * (s1[0] - s1[1]) / s1[1], "overhead_pct_b_cached": 100.0 * (s1[2] - s1[1]) / s1[1],
                   "tflops": flops / (s1[0] * 1e-3) / 1e12,
-                  "note": "same steps on one stream (medians of three interleaved rounds of K steps)"}
+                  "note": "same steps on one stream (medians of three interleaved rounds of max(K, 200) steps)"}
     else:
         single = None
 
@@ -693,7 +697,8 @@ def main():
             "interleaved_ms": {"protected": ms_prot_i, "unprotected": ms_off_i, "protected_b_cached": ms_cached_i,
                                "unprotected_by_streams": {str(k): v for k, v in zip(off_lanes, off_i)},
                                "unprotected_streams": off_streams_i,
-                               "note": "medians of three interleaved rounds of K steps; the two percentages come from "
+                               "steps_per_leg": steps_i,
+                               "note": "medians of three interleaved rounds of max(K, 200) steps; the two percentages come from "
                                        "these; the unprotected figure is that of the number of streams (1..streams) at "
                                        "which the unprotected kernel is fastest"},
             "unprotected_ms_by_streams": {str(k): v for k, v in ms_off_by_lanes.items()},
