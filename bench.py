@@ -38,7 +38,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per GEMM-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # same counters on a plain copy kernel (see profiles/); None until measured for this kernel version.
-MEASURED_TRAFFIC_BYTES = int((59832.3 / 0.5 + 77834.7) * 1024)   # profiles/gemm_fast_bf16_fc1_b64_hbm_traffic.txt
+MEASURED_TRAFFIC_BYTES = int((59654.2 / 0.5 + 77839.6) * 1024)   # profiles/gemm_fast_bf16_fc1_b64_hbm_traffic.txt
 
 
 def log(*a):
