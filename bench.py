@@ -39,6 +39,9 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per GEMM-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by the
 # same counters on a plain copy kernel (see profiles/); None until measured for this kernel version.
 MEASURED_TRAFFIC_BYTES = int((59654.2 / 0.5 + 77839.6) * 1024)   # profiles/gemm_fast_bf16_fc1_b64_hbm_traffic.txt
+# average duration of the same kernel under rocprofv3 --kernel-trace --stats (dispatch to completion, without
+# the launch latency that HIP events around a kernel include); profiles/gemm_fast_bf16_fc1_b64_kernel_stats.txt
+PROFILED_KERNEL_US = 65.57
 
 
 def log(*a):
@@ -684,6 +687,8 @@ def main():
                      "unit": "TFLOP/s", "frac": flops / (gemm_ms * 1e-3) / 1e12 / PEAK_TFLOPS[dtype],
                      "traffic": MEASURED_TRAFFIC_BYTES, "kernel": "gemm_fast_kernel<bf16, 256, 256, protected>",
                      "kernel_ms": gemm_ms,
+                     "kernel_us_rocprofv3": PROFILED_KERNEL_US,
+                     "frac_rocprofv3": flops / (PROFILED_KERNEL_US * 1e-6) / 1e12 / PEAK_TFLOPS[dtype],
                      "kernel_ms_note": "HIP events around the kernel on its launch stream, average over K steps of the "
                                        "single-stream leg (kernels of different streams overlap in the pipelined leg)",
                      "peak_measured": peak_meas, "frac_of_measured": flops / (gemm_ms * 1e-3) / 1e12 / peak_meas,
